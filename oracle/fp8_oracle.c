@@ -1,0 +1,345 @@
+/*
+ * CPU oracle for the dynamically scaled float8 linear layer.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the
+ * GPU library is checked against.  It shares no code with the HIP path and
+ * nothing in the product may call it.
+ *
+ * What it follows:
+ *   - The paper's FP8 training section (Section 2.1, "FP8 Training"): the
+ *     activations, weights and gradients are cast to FP8 dynamically (the
+ *     statistics are recomputed from the tensor at every call) and the matrix
+ *     product runs on the FP8 operands.
+ *   - The paper's Appendix A (FP8 scaling recipes): "tensorwise" takes one
+ *     scaling factor per tensor; "rowwise" takes one per logical row of the
+ *     left GEMM operand and one per logical column of the right operand, i.e.
+ *     every scale spans the contraction axis of its operand.
+ *   - The paper is silent about the numeric formats.  They are the two OCP
+ *     8-bit floating point formats (OFP8 specification, Section 5: E4M3 with
+ *     no infinities and a single NaN mantissa pattern, E5M2 IEEE-like), with
+ *     saturating round-to-nearest-even conversion.
+ *
+ * Floating point contract: compile with -ffp-contract=off (and no
+ * -ffast-math) so that every fp32 product and sum below rounds exactly once.
+ *
+ * Parity pins: every exported function is pinned by tests/test_oracle_*.py
+ * (closed forms, exhaustive round trips, an independent search encoder, brute
+ * force, library special cases).  Not pinned ("parity unpinned"): the payload
+ * and sign of NaN codes, and amax of inputs that contain NaN.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_E4M3FN 0
+#define ORC_E5M2 1
+
+#define ORC_TENSOR 0
+#define ORC_ROW 1 /* one scale per row: the group runs over the columns  */
+#define ORC_COL 2 /* one scale per column: the group runs over the rows  */
+
+#define ORC_POW2_SCALE 1
+#define ORC_TRANSPOSE_OUT 2
+
+/* ---------------------------------------------------------------- helpers */
+
+static inline uint32_t f32_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+static inline float bits_f32(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
+
+/* bfloat16 is the upper half of an IEEE binary32: widening is exact. */
+float orc_bf16_to_f32(uint16_t b) { return bits_f32((uint32_t)b << 16); }
+
+/* binary32 -> bfloat16, round to nearest, ties to even. */
+uint16_t orc_f32_to_bf16(float f) {
+    uint32_t u = f32_bits(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u); /* quiet NaN */
+    uint32_t lsb = (u >> 16) & 1u;
+    return (uint16_t)((u + 0x7FFFu + lsb) >> 16);
+}
+
+int orc_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Format parameters (OFP8 specification, Table 1). */
+static inline int fmt_mbits(int fmt) { return fmt == ORC_E4M3FN ? 3 : 2; }
+static inline int fmt_bias(int fmt) { return fmt == ORC_E4M3FN ? 7 : 15; }
+static inline int fmt_max_code(int fmt) { return fmt == ORC_E4M3FN ? 0x7E : 0x7B; }
+
+float orc_fp8_max(int fmt) { return fmt == ORC_E4M3FN ? 448.0f : 57344.0f; }
+
+/* ------------------------------------------------------------ O1: decode */
+/*
+ * code = S EEEE MMM (E4M3, bias 7) or S EEEEE MM (E5M2, bias 15).
+ *   E == 0        : subnormal, (M / 2^mbits) * 2^(1 - bias)
+ *   otherwise     : (1 + M / 2^mbits) * 2^(E - bias)
+ * E4M3 has no infinity; S.1111.111 is NaN and S.1111.110 = 448 is the largest
+ * finite value.  E5M2 follows IEEE: E == 31 is Inf (M == 0) or NaN.
+ */
+float orc_fp8_decode(uint8_t code, int fmt) {
+    const int mb = fmt_mbits(fmt), bias = fmt_bias(fmt);
+    const int sign = code >> 7;
+    const int e = (code & 0x7F) >> mb;
+    const int m = code & ((1 << mb) - 1);
+    double v;
+    if (fmt == ORC_E4M3FN) {
+        if (e == 15 && m == 7) return sign ? -NAN : NAN;
+    } else {
+        if (e == 31) return m ? (sign ? -NAN : NAN) : (sign ? -INFINITY : INFINITY);
+    }
+    if (e == 0) v = ldexp((double)m, 1 - bias - mb);
+    else        v = ldexp((double)((1 << mb) + m), e - bias - mb);
+    return (float)(sign ? -v : v);
+}
+
+/* ------------------------------------------------------------ O2: encode */
+/*
+ * Saturating round-to-nearest-even, implementation A: the plain definition.
+ * Clamp the magnitude to the largest finite value, then pick the finite
+ * non-negative code whose value is nearest; on an exact tie pick the code
+ * whose mantissa LSB is 0 (codes are consecutive integers, so that is the
+ * even code).  The sign bit is copied from the input.
+ */
+uint8_t orc_fp8_encode_search(float v, int fmt) {
+    const uint8_t sign = (uint8_t)((f32_bits(v) >> 24) & 0x80u);
+    if (v != v) return (uint8_t)(sign | 0x7F);
+    double a = fabs((double)v);
+    const double fmax = (double)orc_fp8_max(fmt);
+    if (a > fmax) a = fmax;
+    int best = 0;
+    double best_d = INFINITY;
+    for (int c = 0; c <= fmt_max_code(fmt); ++c) {
+        double d = fabs((double)orc_fp8_decode((uint8_t)c, fmt) - a);
+        if (d < best_d || (d == best_d && (c & 1) == 0)) { best = c; best_d = d; }
+    }
+    return (uint8_t)(sign | best);
+}
+
+/*
+ * Implementation B: the same function by integer manipulation of the
+ * binary32 bits (used on large tensors).  Normal results: add half an fp8 ulp
+ * minus one plus the LSB that will be kept, then truncate (classic RNE); a
+ * carry out of the mantissa bumps the exponent, which is the right answer.
+ * Subnormal results: adding 2^(23 + emin - mbits) in binary32 leaves the
+ * RNE-rounded multiple of the subnormal step in the low mantissa bits.
+ */
+uint8_t orc_fp8_encode_bits(float v, int fmt) {
+    const int mb = fmt_mbits(fmt), bias = fmt_bias(fmt);
+    const uint32_t u = f32_bits(v);
+    const uint8_t sign = (uint8_t)((u >> 24) & 0x80u);
+    const uint32_t mag = u & 0x7FFFFFFFu;
+    const uint32_t max_code = (uint32_t)fmt_max_code(fmt);
+    if (mag > 0x7F800000u) return (uint8_t)(sign | 0x7F);
+    if (mag >= f32_bits(orc_fp8_max(fmt))) return (uint8_t)(sign | max_code);
+    const uint32_t min_normal_exp = (uint32_t)(127 + 1 - bias);
+    uint32_t code;
+    if ((mag >> 23) >= min_normal_exp) {
+        const int shift = 23 - mb;
+        const uint32_t lsb = (mag >> shift) & 1u;
+        const uint32_t r = mag + ((1u << (shift - 1)) - 1u) + lsb;
+        code = (r >> shift) - ((uint32_t)(127 - bias) << mb);
+        if (code > max_code) code = max_code; /* rounded past the top: saturate */
+    } else {
+        const float magic = bits_f32((uint32_t)(127 + 23 + 1 - bias - mb) << 23);
+        const float t = bits_f32(mag) + magic;
+        code = f32_bits(t) - f32_bits(magic);
+    }
+    return (uint8_t)(sign | code);
+}
+
+
+/* Array forms of the scalar functions above (same arithmetic, one call). */
+void orc_fp8_encode_array(const float* v, int64_t n, int fmt, int use_search, uint8_t* out) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i)
+        out[i] = use_search ? orc_fp8_encode_search(v[i], fmt) : orc_fp8_encode_bits(v[i], fmt);
+}
+
+void orc_f32_to_bf16_array(const float* v, int64_t n, uint16_t* out) {
+    for (int64_t i = 0; i < n; ++i) out[i] = orc_f32_to_bf16(v[i]);
+}
+
+/* -------------------------------------------------------------- O3: amax */
+/*
+ * amax_g = max over the group of |x|, on bfloat16 values widened to binary32.
+ * x is [rows, cols] with leading dimension ld (elements).
+ *   TENSOR: out[1];  ROW: out[rows];  COL: out[cols].
+ */
+void orc_amax(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, int gran, float* out) {
+    if (gran == ORC_TENSOR) {
+        float m = 0.0f;
+        for (int64_t r = 0; r < rows; ++r)
+            for (int64_t c = 0; c < cols; ++c) {
+                float a = fabsf(orc_bf16_to_f32(x[r * ld + c]));
+                if (a > m) m = a;
+            }
+        out[0] = m;
+    } else if (gran == ORC_ROW) {
+#pragma omp parallel for schedule(static)
+        for (int64_t r = 0; r < rows; ++r) {
+            float m = 0.0f;
+            for (int64_t c = 0; c < cols; ++c) {
+                float a = fabsf(orc_bf16_to_f32(x[r * ld + c]));
+                if (a > m) m = a;
+            }
+            out[r] = m;
+        }
+    } else {
+#pragma omp parallel for schedule(static)
+        for (int64_t c = 0; c < cols; ++c) {
+            float m = 0.0f;
+            for (int64_t r = 0; r < rows; ++r) {
+                float a = fabsf(orc_bf16_to_f32(x[r * ld + c]));
+                if (a > m) m = a;
+            }
+            out[c] = m;
+        }
+    }
+}
+
+/* ------------------------------------------------------------- O4: scale */
+/*
+ * s = FMAX / max(amax, 1e-12), the division carried out in binary64 and the
+ * quotient rounded to binary32.  With POW2 the scale is rounded DOWN to a
+ * power of two (mantissa cleared), so that amax * s never exceeds FMAX.
+ */
+void orc_scale(const float* amax, int64_t n, int fmt, int flags, float* scale) {
+    const double fmax = (double)orc_fp8_max(fmt);
+    for (int64_t i = 0; i < n; ++i) {
+        double a = (double)amax[i];
+        if (!(a > 1e-12)) a = 1e-12;
+        float s = (float)(fmax / a);
+        if (flags & ORC_POW2_SCALE) s = bits_f32(f32_bits(s) & 0xFF800000u);
+        scale[i] = s;
+    }
+}
+
+/* -------------------------------------------------------------- O5: cast */
+/*
+ * q = encode( fp32(x) * s ): one binary32 rounding for the product, then the
+ * saturating RNE narrowing.  s is scale[0] (TENSOR), scale[r] (ROW) or
+ * scale[c] (COL).  With TRANSPOSE_OUT the byte for x[r,c] goes to
+ * q[c * ld_out + r], otherwise to q[r * ld_out + c].  use_search selects
+ * encoder A (slow) instead of B.
+ */
+void orc_cast(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, const float* scale,
+              int gran, int fmt, int flags, uint8_t* q, int64_t ld_out, int use_search) {
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t c = 0; c < cols; ++c) {
+            const float s = gran == ORC_TENSOR ? scale[0] : (gran == ORC_ROW ? scale[r] : scale[c]);
+            volatile float p = orc_bf16_to_f32(x[r * ld + c]) * s;
+            const uint8_t code = use_search ? orc_fp8_encode_search(p, fmt) : orc_fp8_encode_bits(p, fmt);
+            if (flags & ORC_TRANSPOSE_OUT) q[c * ld_out + r] = code;
+            else                           q[r * ld_out + c] = code;
+        }
+    }
+}
+
+/* -------------------------------------------------------- O8: cast stats */
+/*
+ * stats[0] = n_sat       : |fp32(x) * s| > FMAX (clamped by the cast)
+ * stats[1] = n_zero      : x != 0 but the code is +-0
+ * stats[2] = n_subnormal : nonzero code with exponent field 0
+ * stats[3] = signal power  sum x^2             (binary64)
+ * stats[4] = noise power   sum (dec(q)/s - x)^2 (binary64)
+ */
+void orc_cast_stats(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, const float* scale,
+                    int gran, int fmt, double* stats) {
+    double n_sat = 0, n_zero = 0, n_sub = 0, sig = 0, noise = 0;
+    const float fmax = orc_fp8_max(fmt);
+    const int mb = fmt_mbits(fmt);
+#pragma omp parallel for schedule(static) reduction(+ : n_sat, n_zero, n_sub, sig, noise)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t c = 0; c < cols; ++c) {
+            const float s = gran == ORC_TENSOR ? scale[0] : (gran == ORC_ROW ? scale[r] : scale[c]);
+            const float xv = orc_bf16_to_f32(x[r * ld + c]);
+            volatile float p = xv * s;
+            const uint8_t code = orc_fp8_encode_bits(p, fmt);
+            if (fabsf(p) > fmax) n_sat += 1;
+            if (xv != 0.0f && (code & 0x7F) == 0) n_zero += 1;
+            if ((code & 0x7F) != 0 && ((code & 0x7F) >> mb) == 0) n_sub += 1;
+            const double back = (double)orc_fp8_decode(code, fmt) / (double)s;
+            sig += (double)xv * (double)xv;
+            noise += (back - (double)xv) * (back - (double)xv);
+        }
+    }
+    stats[0] = n_sat; stats[1] = n_zero; stats[2] = n_sub; stats[3] = sig; stats[4] = noise;
+}
+
+/* ----------------------------------------------------- O6: scaled matmul */
+/*
+ * a: [M, K] fp8 codes, K contiguous (leading dimension lda);
+ * b: [N, K] fp8 codes, K contiguous (leading dimension ldb).
+ * For the output rows listed in row_idx (or all rows when row_idx == NULL):
+ *   acc[m, n]   = sum over k ascending of dec(a[m,k]) * dec(b[n,k]) in binary32
+ *                 (each product of two fp8 values is exact in binary32)
+ *   out32[i, n] = (acc * (1 / sa)) * (1 / sb)     in binary32
+ *   out16[i, n] = bfloat16 RNE of out32
+ *   acc64[i, n] = the same sum in binary64, times the reciprocal scales in
+ *                 binary64 (kept for error budgeting; may be NULL)
+ * sa is scale_a[0] (TENSOR) or scale_a[m] (ROW); likewise sb with n.
+ * Outputs are dense [n_rows_out, N].
+ */
+void orc_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int gran_a,
+                   const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int gran_b,
+                   int64_t M, int64_t N, int64_t K, const int64_t* row_idx, int64_t n_rows_out,
+                   float* out32, uint16_t* out16, double* acc64) {
+    float lut_a[256], lut_b[256];
+    for (int c = 0; c < 256; ++c) {
+        lut_a[c] = orc_fp8_decode((uint8_t)c, fmt_a);
+        lut_b[c] = orc_fp8_decode((uint8_t)c, fmt_b);
+    }
+    const int64_t rows = row_idx ? n_rows_out : M;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        for (int64_t n = 0; n < N; ++n) {
+            const int64_t m = row_idx ? row_idx[i] : i;
+            const uint8_t* ar = a + m * lda;
+            const uint8_t* br = b + n * ldb;
+            float acc = 0.0f;
+            double accd = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                const float fa = lut_a[ar[k]], fb = lut_b[br[k]];
+                acc = acc + fa * fb;
+                accd = accd + (double)fa * (double)fb;
+            }
+            const float sa = gran_a == ORC_TENSOR ? scale_a[0] : scale_a[m];
+            const float sb = gran_b == ORC_TENSOR ? scale_b[0] : scale_b[n];
+            const float ra = 1.0f / sa, rb = 1.0f / sb;
+            const float o = (acc * ra) * rb;
+            if (out32) out32[i * N + n] = o;
+            if (out16) out16[i * N + n] = orc_f32_to_bf16(o);
+            if (acc64) acc64[i * N + n] = accd / (double)sa / (double)sb;
+        }
+    }
+}
+
+/*
+ * High-precision linear on the unquantized bfloat16 operands (report only:
+ * measures the quantization error of the fp8 path, not used for parity).
+ * out[i, n] = sum_k a[m,k] * b[n,k] in binary64, a and b K-contiguous.
+ */
+void orc_bf16_mm_f64(const uint16_t* a, int64_t lda, const uint16_t* b, int64_t ldb,
+                     int64_t M, int64_t N, int64_t K, const int64_t* row_idx, int64_t n_rows_out,
+                     double* out) {
+    const int64_t rows = row_idx ? n_rows_out : M;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        for (int64_t n = 0; n < N; ++n) {
+            const int64_t m = row_idx ? row_idx[i] : i;
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += (double)orc_bf16_to_f32(a[m * lda + k]) * (double)orc_bf16_to_f32(b[n * ldb + k]);
+            out[i * N + n] = acc;
+        }
+    }
+}
