@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the dynamically scaled float8 linear layer on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+fp8_linear_fwd (quantize X, W; Y = X W^T) followed by fp8_linear_bwd
+(re-quantize dY, W, X along the contraction axes; dX = dY W, dW = dY^T X), all
+inputs resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is the step's throughput in TFLOP/s (6 M N K
+flop per step, quantization time included).  `roofline` describes the dominant
+kernel (the forward scaled GEMM) from HIP-event timing of that kernel alone;
+`kernels` lists every kernel of the path with its own roofline figure;
+`cpu_baseline` is the CPU oracle timed on a bounded sample of the workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+FP8_PEAK_TFLOPS = 5000.0    # MI355X dense FP8 MFMA
+BF16_PEAK_TFLOPS = 2500.0
+
+
+def _event_time_ms(fn, iters: int, warmup: int, torch) -> float:
+    """Average duration of fn() in ms from HIP events on the current stream
+    (the stream the library launches on)."""
+    for _ in range(warmup):
+        fn()
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(iters):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-legs", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=192)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2507_16099_amd as fp8
+    import synthetic_inputs as si
+
+    if not os.path.exists(fp8.library_path()):
+        from paper_2507_16099_amd import build as _b
+        _b.build()
+    fp8.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    wl = si.WORKLOADS[args.workload or si.BENCH_WORKLOAD]
+    M, K, N = wl.M, wl.K, wl.N
+    rowwise = wl.recipe == si.ROWWISE
+    recipe = fp8.Recipe(gran=fp8.FP8_ROW if rowwise else fp8.FP8_TENSOR,
+                        flags=fp8.FP8_POW2_SCALE if wl.pow2 else 0)
+
+    # synthetic inputs of the workload's distributions, generated on the device
+    g = torch.Generator(device=dev)
+    g.manual_seed(wl.seed)
+
+    def normal(shape, std):
+        return (torch.randn(shape, generator=g, device=dev, dtype=torch.float32) * std).to(torch.bfloat16)
+
+    def draw(dist, shape):
+        if dist[0] == "normal":
+            return normal(shape, dist[1])
+        # Student-t with hot columns
+        z = torch.randn(shape, generator=g, device=dev)
+        chi = torch.distributions.Chi2(torch.tensor(float(dist[1]), device=dev)).sample(shape)
+        v = z / torch.sqrt(chi / dist[1])
+        ncol = int(round(dist[2] * shape[1]))
+        if ncol:
+            cols = torch.randperm(shape[1], generator=g, device=dev)[:ncol]
+            v[:, cols] *= dist[3]
+        return v.to(torch.bfloat16)
+
+    x = draw(wl.x_dist, (M, K))
+    w = draw(wl.w_dist, (N, K))
+    dy = draw(wl.dy_dist, (M, N))
+    y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    dx = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+    dw = torch.empty((N, K), dtype=torch.bfloat16, device=dev)
+    ws_f = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, recipe, False), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, recipe, True), dtype=torch.uint8, device=dev)
+
+    def step():
+        fp8.fp8_linear_fwd(x, w, recipe, y=y, workspace=ws_f)
+        if wl.backward:
+            fp8.fp8_linear_bwd(dy, x, w, recipe, dx=dx, dw=dw, workspace=ws_b)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    n_gemm = 3 if wl.backward else 1
+    flop_step = n_gemm * 2.0 * M * N * K
+    value = flop_step / (ms_per_step * 1e-3) / 1e12
+
+    result = {
+        "metric": "fp8 scaled-GEMM TFLOP/s + cast GB/s; fp8 linear fwd+bwd vs bf16, 1 GPU",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "fp8_e4m3fn/e5m2 x fp32-accumulate -> bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "M": M, "K": K, "N": N, "recipe": wl.recipe, "pow2_scales": wl.pow2,
+                   "pass": "fwd+bwd" if wl.backward else "fwd", "flop_per_step": flop_step},
+    }
+
+    # ------------------------------------------------ per-kernel legs
+    if not args.no_kernel_legs:
+        it, wu = max(5, args.steps), 3
+        kernels = {}
+        gran = fp8.FP8_ROW if rowwise else fp8.FP8_TENSOR
+        fl = recipe.flags
+        T = fp8.FP8_TRANSPOSE_OUT
+        E4, E5 = fp8.FP8_E4M3FN, fp8.FP8_E5M2
+
+        # operands for the GEMM legs (the same calls the linear makes)
+        xq, sx = fp8.fp8_quantize(x, gran, E4, fl)
+        wq, sw = fp8.fp8_quantize(w, gran, E4, fl)
+
+        def gemm_leg(name, a, fa, sa, b, fb, sb, out):
+            m, k = a.shape
+            n = b.shape[0]
+            ms = _event_time_ms(lambda: fp8.fp8_scaled_mm(a, fa, sa, gran, b, fb, sb, gran, 0, out=out), it, wu, torch)
+            tf = 2.0 * m * n * k / (ms * 1e-3) / 1e12
+            kernels[name] = {"ms": round(ms, 4), "TFLOP/s": round(tf, 1), "frac_of_fp8_peak": round(tf / FP8_PEAK_TFLOPS, 4)}
+            return ms, tf
+
+        def cast_leg(name, fn, elems, bytes_per_elem):
+            ms = _event_time_ms(fn, it, wu, torch)
+            gbs = elems * bytes_per_elem / (ms * 1e-3) / 1e9
+            kernels[name] = {"ms": round(ms, 4), "GB/s": round(gbs, 1), "bytes_per_elem": bytes_per_elem,
+                             "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+
+        fwd_ms, fwd_tf = gemm_leg("gemm_fwd", xq, E4, sx, wq, E4, sw, y)
+        if rowwise:
+            cast_leg("quant_x_row", lambda: fp8.fp8_quantize(x, gran, E4, fl, out=xq, scale_out=sx), M * K, 3)
+            cast_leg("quant_w_row", lambda: fp8.fp8_quantize(w, gran, E4, fl, out=wq, scale_out=sw), N * K, 3)
+        else:
+            cast_leg("quant_x_tensor", lambda: fp8.fp8_quantize(x, gran, E4, fl, out=xq, scale_out=sx), M * K, 5)
+            cast_leg("quant_w_tensor", lambda: fp8.fp8_quantize(w, gran, E4, fl, out=wq, scale_out=sw), N * K, 5)
+        cast_leg("amax_x_tensor", lambda: fp8.fp8_amax(x, fp8.FP8_TENSOR), M * K, 2)
+        cast_leg("cast_x_given_scale", lambda: fp8.fp8_cast(x, sx, gran, E4, 0, out=xq), M * K, 3)
+        if wl.backward:
+            cgran = fp8.FP8_COL if rowwise else fp8.FP8_TENSOR
+            gq, sg = fp8.fp8_quantize(dy, gran, E5, fl)
+            wt, swt = fp8.fp8_quantize(w, cgran, E4, fl | T)
+            gemm_leg("gemm_dx", gq, E5, sg, wt, E4, swt, dx)
+            cast_leg("quant_dy_row" if rowwise else "quant_dy_tensor",
+                     lambda: fp8.fp8_quantize(dy, gran, E5, fl, out=gq, scale_out=sg), M * N, 3 if rowwise else 5)
+            cast_leg("quant_w_col_t", lambda: fp8.fp8_quantize(w, cgran, E4, fl | T, out=wt, scale_out=swt), N * K, 5)
+            del gq, wt
+            gqt, sgt = fp8.fp8_quantize(dy, cgran, E5, fl | T)
+            xt, sxt = fp8.fp8_quantize(x, cgran, E4, fl | T)
+            gemm_leg("gemm_dw", gqt, E5, sgt, xt, E4, sxt, dw)
+            cast_leg("quant_dy_col_t", lambda: fp8.fp8_quantize(dy, cgran, E5, fl | T, out=gqt, scale_out=sgt), M * N, 5)
+            cast_leg("quant_x_col_t", lambda: fp8.fp8_quantize(x, cgran, E4, fl | T, out=xt, scale_out=sxt), M * K, 5)
+            del gqt, xt
+        # bf16 comparator: the same three products by the vendor BLAS through torch
+        def bf16_step():
+            torch.matmul(x, w.t(), out=y)
+            if wl.backward:
+                torch.matmul(dy, w, out=dx)
+                torch.matmul(dy.t(), x, out=dw)
+        bf_ms = _event_time_ms(bf16_step, max(3, args.steps // 2), 2, torch)
+        fp8_ms = _event_time_ms(step, max(3, args.steps // 2), 2, torch)
+        result["kernels"] = kernels
+        result["vs_bf16"] = {"bf16_ms_per_step": round(bf_ms, 4), "fp8_ms_per_step": round(fp8_ms, 4),
+                             "speedup": round(bf_ms / fp8_ms, 3),
+                             "bf16_TFLOP/s": round(flop_step / (bf_ms * 1e-3) / 1e12, 1),
+                             "comparator": "torch.matmul bf16 (vendor BLAS), benchmark only"}
+        result["roofline"] = {"kernel": "gemm_fp8_tn_kernel (forward GEMM)", "bound": "mfma",
+                              "achieved": round(fwd_tf, 1), "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
+                              "frac": round(fwd_tf / FP8_PEAK_TFLOPS, 4), "traffic": None,
+                              "flop_per_launch": 2.0 * M * N * K, "avg_launch_ms": round(fwd_ms, 4)}
+
+    # ------------------------------------------------ CPU oracle baseline
+    if not args.no_cpu_baseline:
+        from oracle import fp8_oracle as orc
+        ms_rows = min(M, args.cpu_sample_rows)
+        sub = si.scaled_down(wl, ms_rows, K, N)
+        hx, hw, hdy = sub.x(), sub.w(), sub.dy()
+        orec = orc.Recipe(gran=orc.ROW if rowwise else orc.TENSOR, pow2=wl.pow2)
+        orc.lib()
+        c0 = time.perf_counter()
+        orc.linear_fwd(hx, hw, orec)
+        if wl.backward:
+            orc.linear_bwd_dx(hdy, hw, orec)
+            orc.linear_bwd_dw(hdy, hx, orec)
+        c1 = time.perf_counter()
+        cflop = n_gemm * 2.0 * ms_rows * N * K
+        result["cpu_baseline"] = {"value": round(cflop / (c1 - c0) / 1e12, 6), "unit": "TFLOP/s",
+                                  "cores": orc.num_threads(), "kind": "oracle",
+                                  "sample": f"same workload with M reduced to {ms_rows} tokens (full K, N): "
+                                            f"quantize + {n_gemm} GEMMs, {c1 - c0:.1f} s of CPU time"}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,171 @@
+/*
+ * fp8mi355 - dynamically scaled float8 linear layer for AMD Instinct MI355X
+ * (gfx950 / CDNA4).  C ABI of libfp8mi355.so.
+ *
+ * The library implements the hot path of the FP8 training flow described in
+ * the TorchAO paper (arXiv 2507.16099), Section 2.1 "FP8 Training" and
+ * Appendix A "FP8 Scaling Recipes": activations, weights and gradients are
+ * cast to FP8 dynamically (amax -> scale -> saturating round-to-nearest-even
+ * cast) and the matrix products run on FP8 matrix cores with fp32
+ * accumulation, for the forward product Y = X W^T and the two backward
+ * products dX = dY W and dW = dY^T X.
+ *
+ * Conventions common to every call
+ * --------------------------------
+ *  - All data pointers are DEVICE pointers (HBM of the current HIP device),
+ *    16-byte aligned.  bfloat16 tensors are passed as const void*, fp8
+ *    tensors as uint8_t* (one code per byte), scales and amax as float*.
+ *  - Matrices are row-major; `ld*` arguments are leading dimensions in
+ *    ELEMENTS and must be >= the number of columns and a multiple of 8 for
+ *    bfloat16 inputs / 16 for fp8 tensors (keeps every row 16-byte aligned).
+ *  - A "scale" s is the quantization multiplier: q = cast(x * s).  The GEMM
+ *    dequantizes with 1/s.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Every call only enqueues work on that stream and returns; nothing
+ *    synchronizes with the host.
+ *  - Ownership: the caller owns every buffer, including the workspace.  The
+ *    library allocates no device memory and keeps no state between calls.
+ *  - Errors: arguments are validated on the host BEFORE anything is launched.
+ *    A negative fp8_status is returned and fp8_last_error() describes it;
+ *    nothing is thrown across the boundary and the process is never aborted.
+ *    Inputs are expected to be finite; NaN maps to a NaN code, +-Inf saturates
+ *    in fp8_cast, and amax of non-finite input is unspecified.
+ *  - Empty problems (a dimension equal to 0) are accepted and do nothing.
+ */
+#ifndef FP8MI355_H
+#define FP8MI355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* FP8 formats (OCP OFP8): E4M3 "fn" (bias 7, max 448, no Inf) for activations
+ * and weights, E5M2 (bias 15, max 57344) for gradients. */
+enum fp8_format { FP8_E4M3FN = 0, FP8_E5M2 = 1 };
+
+/* Scaling granularity (Appendix A).  TENSOR: one scale for the whole matrix.
+ * ROW: one scale per row (the group runs over the columns).  COL: one scale
+ * per column (the group runs over the rows). */
+enum fp8_gran { FP8_TENSOR = 0, FP8_ROW = 1, FP8_COL = 2 };
+
+enum fp8_flags {
+    FP8_POW2_SCALE    = 1, /* round the scale down to a power of two            */
+    FP8_TRANSPOSE_OUT = 2, /* fp8_cast / fp8_quantize write q[c, r] not q[r, c] */
+    FP8_OUT_FP32      = 4  /* fp8_scaled_mm writes fp32 instead of bfloat16     */
+};
+
+enum fp8_status {
+    FP8_OK = 0,
+    FP8_ERR_NULL = -1,      /* a required pointer is NULL                       */
+    FP8_ERR_SHAPE = -2,     /* negative dimension, ld too small, K not % 16     */
+    FP8_ERR_ENUM = -3,      /* unknown format / granularity / flag              */
+    FP8_ERR_ALIGN = -4,     /* pointer or leading dimension not aligned         */
+    FP8_ERR_WORKSPACE = -5, /* workspace smaller than fp8_linear_workspace_bytes */
+    FP8_ERR_HIP = -6        /* a kernel launch failed (hipGetLastError)         */
+};
+
+/* Description of the last error on the calling thread ("" if none).  The
+ * returned pointer refers to thread-local static storage. */
+const char* fp8_last_error(void);
+
+/* Library version string, static storage. */
+const char* fp8_version(void);
+
+/*
+ * amax (Section 2.1: the cast is dynamic, so the statistic is recomputed from
+ * the tensor on every call; Appendix A fixes the group).
+ *   x        [rows, cols] bfloat16, leading dimension ld.
+ *   gran     FP8_TENSOR -> amax_out[1]; FP8_ROW -> amax_out[rows];
+ *            FP8_COL -> amax_out[cols].
+ *   amax_out max over the group of |x| as fp32 (exact: a bfloat16 magnitude).
+ */
+int fp8_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran,
+             float* amax_out, void* stream);
+
+/*
+ * scale (Appendix A: "a single scaling factor for each tensor" / per row).
+ *   scale_out[i] = fp32( FMAX(format) / max(amax[i], 1e-12) ), the quotient
+ *   correctly rounded; with FP8_POW2_SCALE it is then rounded down to 2^k.
+ *   amax and scale_out have n entries and may alias.
+ */
+int fp8_scale(const float* amax, int64_t n, int format, int flags, float* scale_out, void* stream);
+
+/*
+ * cast (Section 2.1: cast to FP8) with given scales.
+ *   q = fp8( clamp( fp32(x) * s, +-FMAX ) ), round to nearest even, saturating;
+ *   s = scale[0] (TENSOR), scale[r] (ROW) or scale[c] (COL).
+ *   q_out is [rows, cols] (leading dimension ld_out) or, with
+ *   FP8_TRANSPOSE_OUT, [cols, rows].
+ */
+int fp8_cast(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int gran,
+             int format, int flags, uint8_t* q_out, int64_t ld_out, void* stream);
+
+/*
+ * fused amax -> scale -> cast of one operand (the "dynamic quantization" of
+ * Section 2.1 as one call).  Writes the codes to q_out (layout as fp8_cast)
+ * and the scales to scale_out ([1] | [rows] | [cols]).
+ *   ROW without transpose is a single pass over HBM (the row stays in
+ *   registers between the reduction and the cast); TENSOR and COL read the
+ *   input twice.  flags: FP8_POW2_SCALE, FP8_TRANSPOSE_OUT.
+ */
+int fp8_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran, int format,
+                 int flags, uint8_t* q_out, int64_t ld_out, float* scale_out, void* stream);
+
+/*
+ * scaled GEMM on FP8 matrix cores (Section 2.1: "specialized GEMM kernels").
+ *   out[m, n] = ( sum_k dec(a[m, k]) * dec(b[n, k]) ) / (sa * sb)
+ *   a [M, K] and b [N, K] are fp8 codes with the contraction axis contiguous
+ *   (leading dimensions lda, ldb); fmt_a / fmt_b select E4M3FN or E5M2 per
+ *   operand.  sa = scale_a[0] (gran_a == FP8_TENSOR) or scale_a[m] (FP8_ROW);
+ *   sb likewise with n.  Accumulation is fp32; out is [M, N] bfloat16
+ *   (round to nearest even) or fp32 with FP8_OUT_FP32, leading dimension
+ *   ld_out.  K must be a multiple of 16; M and N are arbitrary.
+ */
+int fp8_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int gran_a,
+                  const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int gran_b,
+                  int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int flags,
+                  void* stream);
+
+/* Recipe of a linear layer (Appendix A): gran is FP8_TENSOR ("tensorwise") or
+ * FP8_ROW ("rowwise": every operand scaled along the contraction axis of the
+ * GEMM it feeds).  flags: FP8_POW2_SCALE. */
+typedef struct fp8_recipe {
+    int gran;
+    int fmt_x;  /* format of activations, normally FP8_E4M3FN */
+    int fmt_w;  /* format of weights,     normally FP8_E4M3FN */
+    int fmt_dy; /* format of gradients,   normally FP8_E5M2   */
+    int flags;
+} fp8_recipe;
+
+/* Bytes of workspace fp8_linear_fwd (bwd == 0) or fp8_linear_bwd (bwd != 0)
+ * needs for X [M,K], W [N,K], dY [M,N].  Returns 0 on invalid arguments. */
+size_t fp8_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, const fp8_recipe* recipe, int bwd);
+
+/*
+ * forward of the float8 linear: Y[M,N] = X[M,K] W[N,K]^T.
+ * X and W (bfloat16, dense row-major) are quantized along K, then multiplied.
+ * y is bfloat16 [M,N] dense.  workspace holds the fp8 copies and scales.
+ */
+int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N,
+                   const fp8_recipe* recipe, void* y, void* workspace, size_t workspace_bytes,
+                   void* stream);
+
+/*
+ * backward of the float8 linear: dX[M,K] = dY[M,N] W[N,K] and
+ * dW[N,K] = dY[M,N]^T X[M,K].  For dX, dY is quantized per row and W per
+ * column (along N); for dW, dY and X are quantized per column (along M); the
+ * per-column operands are written transposed so that every GEMM contracts
+ * over a contiguous axis.  Tensorwise: one scale per tensor, only the layouts
+ * change.  dx and dw are bfloat16, dense; either may be NULL to skip it.
+ */
+int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int64_t K, int64_t N,
+                   const fp8_recipe* recipe, void* dx, void* dw, void* workspace,
+                   size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FP8MI355_H */

@@ -1,0 +1,321 @@
+// C ABI of libfp8mi355.so: argument validation, workspace planning and the
+// composition of the linear forward / backward out of the kernels.
+// Every entry point validates on the host, then only enqueues work.
+#include "../../include/fp8mi355.h"
+#include "launchers.hpp"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+    return fail(FP8_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+bool fmt_ok(int f) { return f == FP8_E4M3FN || f == FP8_E5M2; }
+bool gran_ok(int g) { return g == FP8_TENSOR || g == FP8_ROW || g == FP8_COL; }
+constexpr int64_t kMaxDim = 0x7FFFFFFF;
+
+#define FP8_TRY(expr)                               \
+    do {                                            \
+        hipError_t e__ = (expr);                    \
+        if (e__ != hipSuccess) return hip_fail(e__, #expr); \
+    } while (0)
+
+// common checks of a bfloat16 input matrix
+int check_bf16(const char* fn, const void* x, int64_t rows, int64_t cols, int64_t ld) {
+    if (rows < 0 || cols < 0 || rows > kMaxDim || cols > kMaxDim)
+        return fail(FP8_ERR_SHAPE, "%s: rows=%lld cols=%lld out of range", fn, (long long)rows, (long long)cols);
+    if (ld < cols) return fail(FP8_ERR_SHAPE, "%s: ld=%lld < cols=%lld", fn, (long long)ld, (long long)cols);
+    if (rows > 0 && cols > 0) {
+        if (!x) return fail(FP8_ERR_NULL, "%s: input pointer is NULL", fn);
+        if (!aligned(x, 16)) return fail(FP8_ERR_ALIGN, "%s: input pointer not 16-byte aligned", fn);
+        if (ld % 8 != 0) return fail(FP8_ERR_ALIGN, "%s: ld=%lld not a multiple of 8", fn, (long long)ld);
+    }
+    return FP8_OK;
+}
+
+int64_t n_groups(int gran, int64_t rows, int64_t cols) {
+    return gran == FP8_TENSOR ? 1 : (gran == FP8_ROW ? rows : cols);
+}
+
+// amax -> scale -> cast of one operand; amax_tmp has n_groups floats
+int quantize_impl(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran, int format, int flags,
+                  uint8_t* q, int64_t ld_out, uint8_t* q_plain, int64_t ld_plain, float* scale_out,
+                  hipStream_t st) {
+    const int transpose = (flags & FP8_TRANSPOSE_OUT) ? 1 : 0;
+    const int pow2 = flags & FP8_POW2_SCALE;
+    if (gran == FP8_ROW && !transpose) {
+        hipError_t e = fp8k::launch_quant_row(x, rows, cols, ld, format, pow2, q, ld_out, scale_out, st);
+        if (e == hipSuccess) return FP8_OK;
+        if (e != hipErrorNotSupported) return hip_fail(e, "quant_row");
+    }
+    // scale_out doubles as the amax buffer: fp8_scale may run in place
+    FP8_TRY(fp8k::launch_amax(x, rows, cols, ld, gran, scale_out, st));
+    FP8_TRY(fp8k::launch_scale(scale_out, n_groups(gran, rows, cols), format, pow2, scale_out, st));
+    FP8_TRY(fp8k::launch_cast(x, rows, cols, ld, scale_out, gran, format, transpose, q, ld_out, q_plain, ld_plain, st));
+    return FP8_OK;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct FwdPlan {
+    size_t xq, wq, sx, sw, total;
+};
+struct BwdPlan {
+    size_t gq, gqt, wt, xt, sg, sgt, swt, sxt, total;
+};
+
+FwdPlan plan_fwd(int64_t M, int64_t K, int64_t N, int gran) {
+    FwdPlan p{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    p.xq = take((size_t)M * K);
+    p.wq = take((size_t)N * K);
+    p.sx = take(sizeof(float) * (gran == FP8_ROW ? (size_t)M : 1));
+    p.sw = take(sizeof(float) * (gran == FP8_ROW ? (size_t)N : 1));
+    p.total = o;
+    return p;
+}
+
+BwdPlan plan_bwd(int64_t M, int64_t K, int64_t N, int gran) {
+    BwdPlan p{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    const bool row = gran == FP8_ROW;
+    p.gq = take((size_t)M * N);   // dY codes, [M, N]
+    p.gqt = take((size_t)M * N);  // dY codes, [N, M]
+    p.wt = take((size_t)K * N);   // W codes,  [K, N]
+    p.xt = take((size_t)K * M);   // X codes,  [K, M]
+    p.sg = take(sizeof(float) * (row ? (size_t)M : 1));
+    p.sgt = take(sizeof(float) * (row ? (size_t)N : 1));
+    p.swt = take(sizeof(float) * (row ? (size_t)K : 1));
+    p.sxt = take(sizeof(float) * (row ? (size_t)K : 1));
+    p.total = o;
+    return p;
+}
+
+int check_recipe(const char* fn, const fp8_recipe* r) {
+    if (!r) return fail(FP8_ERR_NULL, "%s: recipe is NULL", fn);
+    if (r->gran != FP8_TENSOR && r->gran != FP8_ROW)
+        return fail(FP8_ERR_ENUM, "%s: recipe.gran=%d must be FP8_TENSOR or FP8_ROW", fn, r->gran);
+    if (!fmt_ok(r->fmt_x) || !fmt_ok(r->fmt_w) || !fmt_ok(r->fmt_dy))
+        return fail(FP8_ERR_ENUM, "%s: unknown fp8 format in recipe", fn);
+    if (r->flags & ~FP8_POW2_SCALE) return fail(FP8_ERR_ENUM, "%s: recipe.flags=%d has unknown bits", fn, r->flags);
+    return FP8_OK;
+}
+
+int check_linear_dims(const char* fn, int64_t M, int64_t K, int64_t N, bool bwd) {
+    if (M < 0 || K < 0 || N < 0 || M > kMaxDim || K > kMaxDim || N > kMaxDim)
+        return fail(FP8_ERR_SHAPE, "%s: M=%lld K=%lld N=%lld out of range", fn, (long long)M, (long long)K, (long long)N);
+    if (K % 16 != 0) return fail(FP8_ERR_SHAPE, "%s: K=%lld must be a multiple of 16", fn, (long long)K);
+    if (N % 8 != 0) return fail(FP8_ERR_SHAPE, "%s: N=%lld must be a multiple of 8 (dense bfloat16 rows)", fn, (long long)N);
+    if (bwd && (M % 16 != 0 || N % 16 != 0))
+        return fail(FP8_ERR_SHAPE, "%s: backward contracts over M and N: M=%lld, N=%lld must be multiples of 16", fn,
+                    (long long)M, (long long)N);
+    return FP8_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* fp8_last_error(void) { return g_err; }
+
+const char* fp8_version(void) { return "fp8mi355 0.1 (gfx950)"; }
+
+int fp8_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran, float* amax_out, void* stream) {
+    g_err[0] = 0;
+    if (!gran_ok(gran)) return fail(FP8_ERR_ENUM, "fp8_amax: unknown granularity %d", gran);
+    if (int rc = check_bf16("fp8_amax", x, rows, cols, ld)) return rc;
+    if (n_groups(gran, rows, cols) > 0 && !amax_out) return fail(FP8_ERR_NULL, "fp8_amax: amax_out is NULL");
+    if (!aligned(amax_out, 4)) return fail(FP8_ERR_ALIGN, "fp8_amax: amax_out not 4-byte aligned");
+    FP8_TRY(fp8k::launch_amax(x, rows, cols, ld, gran, amax_out, static_cast<hipStream_t>(stream)));
+    return FP8_OK;
+}
+
+int fp8_scale(const float* amax, int64_t n, int format, int flags, float* scale_out, void* stream) {
+    g_err[0] = 0;
+    if (!fmt_ok(format)) return fail(FP8_ERR_ENUM, "fp8_scale: unknown format %d", format);
+    if (flags & ~FP8_POW2_SCALE) return fail(FP8_ERR_ENUM, "fp8_scale: flags=%d has unknown bits", flags);
+    if (n < 0) return fail(FP8_ERR_SHAPE, "fp8_scale: n=%lld is negative", (long long)n);
+    if (n > 0 && (!amax || !scale_out)) return fail(FP8_ERR_NULL, "fp8_scale: NULL pointer");
+    if (!aligned(amax, 4) || !aligned(scale_out, 4)) return fail(FP8_ERR_ALIGN, "fp8_scale: pointer not 4-byte aligned");
+    FP8_TRY(fp8k::launch_scale(amax, n, format, flags, scale_out, static_cast<hipStream_t>(stream)));
+    return FP8_OK;
+}
+
+static int check_q_out(const char* fn, const uint8_t* q, int64_t rows, int64_t cols, int64_t ld_out, int transpose) {
+    const int64_t out_cols = transpose ? rows : cols;
+    if (ld_out < out_cols) return fail(FP8_ERR_SHAPE, "%s: ld_out=%lld < %lld", fn, (long long)ld_out, (long long)out_cols);
+    if (rows > 0 && cols > 0) {
+        if (!q) return fail(FP8_ERR_NULL, "%s: q_out is NULL", fn);
+        if (!aligned(q, 16)) return fail(FP8_ERR_ALIGN, "%s: q_out not 16-byte aligned", fn);
+        if (ld_out % 16 != 0) return fail(FP8_ERR_ALIGN, "%s: ld_out=%lld not a multiple of 16", fn, (long long)ld_out);
+        if (transpose && (rows + 127) / 128 > 65535) return fail(FP8_ERR_SHAPE, "%s: too many rows for a transposed cast", fn);
+    }
+    return FP8_OK;
+}
+
+int fp8_cast(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int gran, int format,
+             int flags, uint8_t* q_out, int64_t ld_out, void* stream) {
+    g_err[0] = 0;
+    if (!gran_ok(gran)) return fail(FP8_ERR_ENUM, "fp8_cast: unknown granularity %d", gran);
+    if (!fmt_ok(format)) return fail(FP8_ERR_ENUM, "fp8_cast: unknown format %d", format);
+    if (flags & ~FP8_TRANSPOSE_OUT) return fail(FP8_ERR_ENUM, "fp8_cast: flags=%d has unknown bits", flags);
+    if (int rc = check_bf16("fp8_cast", x, rows, cols, ld)) return rc;
+    const int transpose = (flags & FP8_TRANSPOSE_OUT) ? 1 : 0;
+    if (int rc = check_q_out("fp8_cast", q_out, rows, cols, ld_out, transpose)) return rc;
+    if (rows > 0 && cols > 0 && !scale) return fail(FP8_ERR_NULL, "fp8_cast: scale is NULL");
+    if (!aligned(scale, 4)) return fail(FP8_ERR_ALIGN, "fp8_cast: scale not 4-byte aligned");
+    FP8_TRY(fp8k::launch_cast(x, rows, cols, ld, scale, gran, format, transpose, q_out, ld_out, nullptr, 0,
+                              static_cast<hipStream_t>(stream)));
+    return FP8_OK;
+}
+
+int fp8_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran, int format, int flags,
+                 uint8_t* q_out, int64_t ld_out, float* scale_out, void* stream) {
+    g_err[0] = 0;
+    if (!gran_ok(gran)) return fail(FP8_ERR_ENUM, "fp8_quantize: unknown granularity %d", gran);
+    if (!fmt_ok(format)) return fail(FP8_ERR_ENUM, "fp8_quantize: unknown format %d", format);
+    if (flags & ~(FP8_TRANSPOSE_OUT | FP8_POW2_SCALE)) return fail(FP8_ERR_ENUM, "fp8_quantize: flags=%d has unknown bits", flags);
+    if (int rc = check_bf16("fp8_quantize", x, rows, cols, ld)) return rc;
+    const int transpose = (flags & FP8_TRANSPOSE_OUT) ? 1 : 0;
+    if (int rc = check_q_out("fp8_quantize", q_out, rows, cols, ld_out, transpose)) return rc;
+    if (n_groups(gran, rows, cols) > 0 && !scale_out) return fail(FP8_ERR_NULL, "fp8_quantize: scale_out is NULL");
+    if (!aligned(scale_out, 4)) return fail(FP8_ERR_ALIGN, "fp8_quantize: scale_out not 4-byte aligned");
+    return quantize_impl(x, rows, cols, ld, gran, format, flags, q_out, ld_out, nullptr, 0, scale_out,
+                         static_cast<hipStream_t>(stream));
+}
+
+int fp8_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int gran_a, const uint8_t* b,
+                  int64_t ldb, int fmt_b, const float* scale_b, int gran_b, int64_t M, int64_t N, int64_t K,
+                  void* out, int64_t ld_out, int flags, void* stream) {
+    g_err[0] = 0;
+    if (!fmt_ok(fmt_a) || !fmt_ok(fmt_b)) return fail(FP8_ERR_ENUM, "fp8_scaled_mm: unknown format");
+    if ((gran_a != FP8_TENSOR && gran_a != FP8_ROW) || (gran_b != FP8_TENSOR && gran_b != FP8_ROW))
+        return fail(FP8_ERR_ENUM, "fp8_scaled_mm: granularity must be FP8_TENSOR or FP8_ROW");
+    if (flags & ~FP8_OUT_FP32) return fail(FP8_ERR_ENUM, "fp8_scaled_mm: flags=%d has unknown bits", flags);
+    if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim)
+        return fail(FP8_ERR_SHAPE, "fp8_scaled_mm: M=%lld N=%lld K=%lld out of range", (long long)M, (long long)N, (long long)K);
+    if (K % 16 != 0) return fail(FP8_ERR_SHAPE, "fp8_scaled_mm: K=%lld must be a multiple of 16", (long long)K);
+    if (lda < K || ldb < K || ld_out < N) return fail(FP8_ERR_SHAPE, "fp8_scaled_mm: leading dimension too small");
+    if (M > 0 && N > 0) {
+        if (!out || !scale_a || !scale_b || (K > 0 && (!a || !b))) return fail(FP8_ERR_NULL, "fp8_scaled_mm: NULL pointer");
+        if (!aligned(a, 16) || !aligned(b, 16) || !aligned(out, 16))
+            return fail(FP8_ERR_ALIGN, "fp8_scaled_mm: a, b and out must be 16-byte aligned");
+        if (lda % 16 != 0 || ldb % 16 != 0) return fail(FP8_ERR_ALIGN, "fp8_scaled_mm: lda and ldb must be multiples of 16");
+        const int64_t out_align = (flags & FP8_OUT_FP32) ? 4 : 8;
+        if (ld_out % out_align != 0)
+            return fail(FP8_ERR_ALIGN, "fp8_scaled_mm: ld_out=%lld must be a multiple of %lld", (long long)ld_out, (long long)out_align);
+        if (!aligned(scale_a, 4) || !aligned(scale_b, 4)) return fail(FP8_ERR_ALIGN, "fp8_scaled_mm: scales not 4-byte aligned");
+    }
+    FP8_TRY(fp8k::launch_gemm_fp8(a, lda, fmt_a, scale_a, gran_a == FP8_ROW, b, ldb, fmt_b, scale_b, gran_b == FP8_ROW,
+                                  M, N, K, out, ld_out, (flags & FP8_OUT_FP32) ? 1 : 0, static_cast<hipStream_t>(stream)));
+    return FP8_OK;
+}
+
+size_t fp8_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, const fp8_recipe* recipe, int bwd) {
+    g_err[0] = 0;
+    if (check_recipe("fp8_linear_workspace_bytes", recipe)) return 0;
+    if (check_linear_dims("fp8_linear_workspace_bytes", M, K, N, bwd != 0)) return 0;
+    const size_t t = bwd ? plan_bwd(M, K, N, recipe->gran).total : plan_fwd(M, K, N, recipe->gran).total;
+    return t ? t : 256;
+}
+
+int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N, const fp8_recipe* recipe, void* y,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+    g_err[0] = 0;
+    if (int rc = check_recipe("fp8_linear_fwd", recipe)) return rc;
+    if (int rc = check_linear_dims("fp8_linear_fwd", M, K, N, false)) return rc;
+    if (int rc = check_bf16("fp8_linear_fwd(x)", x, M, K, K)) return rc;
+    if (int rc = check_bf16("fp8_linear_fwd(w)", w, N, K, K)) return rc;
+    if (M == 0 || N == 0) return FP8_OK;
+    if (!y || !workspace) return fail(FP8_ERR_NULL, "fp8_linear_fwd: y or workspace is NULL");
+    if (!aligned(y, 16) || !aligned(workspace, 256)) return fail(FP8_ERR_ALIGN, "fp8_linear_fwd: y (16) / workspace (256) misaligned");
+    const FwdPlan p = plan_fwd(M, K, N, recipe->gran);
+    if (workspace_bytes < p.total)
+        return fail(FP8_ERR_WORKSPACE, "fp8_linear_fwd: workspace %zu < %zu bytes", workspace_bytes, p.total);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    uint8_t *xq = ws + p.xq, *wq = ws + p.wq;
+    float *sx = reinterpret_cast<float*>(ws + p.sx), *sw = reinterpret_cast<float*>(ws + p.sw);
+    const int g = recipe->gran, fl = recipe->flags & FP8_POW2_SCALE;
+    if (int rc = quantize_impl(x, M, K, K, g, recipe->fmt_x, fl, xq, K, nullptr, 0, sx, st)) return rc;
+    if (int rc = quantize_impl(w, N, K, K, g, recipe->fmt_w, fl, wq, K, nullptr, 0, sw, st)) return rc;
+    FP8_TRY(fp8k::launch_gemm_fp8(xq, K, recipe->fmt_x, sx, g == FP8_ROW, wq, K, recipe->fmt_w, sw, g == FP8_ROW, M, N, K,
+                                  y, N, 0, st));
+    return FP8_OK;
+}
+
+int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int64_t K, int64_t N,
+                   const fp8_recipe* recipe, void* dx, void* dw, void* workspace, size_t workspace_bytes,
+                   void* stream) {
+    g_err[0] = 0;
+    if (int rc = check_recipe("fp8_linear_bwd", recipe)) return rc;
+    if (int rc = check_linear_dims("fp8_linear_bwd", M, K, N, true)) return rc;
+    if (int rc = check_bf16("fp8_linear_bwd(dy)", dy, M, N, N)) return rc;
+    if (dw) if (int rc = check_bf16("fp8_linear_bwd(x)", x, M, K, K)) return rc;
+    if (dx) if (int rc = check_bf16("fp8_linear_bwd(w)", w, N, K, K)) return rc;
+    if (M == 0 || N == 0 || K == 0 || (!dx && !dw)) return FP8_OK;
+    if (!workspace) return fail(FP8_ERR_NULL, "fp8_linear_bwd: workspace is NULL");
+    if (!aligned(dx, 16) || !aligned(dw, 16) || !aligned(workspace, 256))
+        return fail(FP8_ERR_ALIGN, "fp8_linear_bwd: dx, dw (16) / workspace (256) misaligned");
+    if ((M + 127) / 128 > 65535 || (N + 127) / 128 > 65535) return fail(FP8_ERR_SHAPE, "fp8_linear_bwd: M or N too large");
+    const BwdPlan p = plan_bwd(M, K, N, recipe->gran);
+    if (workspace_bytes < p.total)
+        return fail(FP8_ERR_WORKSPACE, "fp8_linear_bwd: workspace %zu < %zu bytes", workspace_bytes, p.total);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    uint8_t *gq = ws + p.gq, *gqt = ws + p.gqt, *wt = ws + p.wt, *xt = ws + p.xt;
+    float *sg = reinterpret_cast<float*>(ws + p.sg), *sgt = reinterpret_cast<float*>(ws + p.sgt);
+    float *swt = reinterpret_cast<float*>(ws + p.swt), *sxt = reinterpret_cast<float*>(ws + p.sxt);
+    const int fl = recipe->flags & FP8_POW2_SCALE;
+    const int T = FP8_TRANSPOSE_OUT;
+
+    if (recipe->gran == FP8_TENSOR) {
+        // one scale per tensor; dY is converted once into both layouts
+        uint8_t* plain = dx ? gq : nullptr;
+        if (dw) {
+            if (int rc = quantize_impl(dy, M, N, N, FP8_TENSOR, recipe->fmt_dy, fl | T, gqt, M, plain, N, sg, st)) return rc;
+        } else {
+            if (int rc = quantize_impl(dy, M, N, N, FP8_TENSOR, recipe->fmt_dy, fl, gq, N, nullptr, 0, sg, st)) return rc;
+        }
+        if (dx) {
+            if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st)) return rc;
+            FP8_TRY(fp8k::launch_gemm_fp8(gq, N, recipe->fmt_dy, sg, 0, wt, N, recipe->fmt_w, swt, 0, M, K, N, dx, K, 0, st));
+        }
+        if (dw) {
+            if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st)) return rc;
+            FP8_TRY(fp8k::launch_gemm_fp8(gqt, M, recipe->fmt_dy, sg, 0, xt, M, recipe->fmt_x, sxt, 0, N, K, M, dw, K, 0, st));
+        }
+        return FP8_OK;
+    }
+    // rowwise: every operand re-quantized along the contraction axis of its GEMM
+    if (dx) {  // dX = dY W, contraction over N
+        if (int rc = quantize_impl(dy, M, N, N, FP8_ROW, recipe->fmt_dy, fl, gq, N, nullptr, 0, sg, st)) return rc;
+        if (int rc = quantize_impl(w, N, K, K, FP8_COL, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st)) return rc;
+        FP8_TRY(fp8k::launch_gemm_fp8(gq, N, recipe->fmt_dy, sg, 1, wt, N, recipe->fmt_w, swt, 1, M, K, N, dx, K, 0, st));
+    }
+    if (dw) {  // dW = dY^T X, contraction over M
+        if (int rc = quantize_impl(dy, M, N, N, FP8_COL, recipe->fmt_dy, fl | T, gqt, M, nullptr, 0, sgt, st)) return rc;
+        if (int rc = quantize_impl(x, M, K, K, FP8_COL, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st)) return rc;
+        FP8_TRY(fp8k::launch_gemm_fp8(gqt, M, recipe->fmt_dy, sgt, 1, xt, M, recipe->fmt_x, sxt, 1, N, K, M, dw, K, 0, st));
+    }
+    return FP8_OK;
+}
+
+}  // extern "C"

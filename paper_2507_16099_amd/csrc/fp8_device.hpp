@@ -1,0 +1,123 @@
+// Device-side helpers shared by the quantization kernels (gfx950 only).
+//
+// Numerics (paper Section 2.1: dynamic cast to FP8; the formats are the OCP
+// OFP8 E4M3 "fn" and E5M2 encodings, which is what the gfx950 conversion and
+// matrix instructions implement):
+//   amax    - compared on the 15 magnitude bits of bfloat16 as unsigned
+//             integers (same order as the absolute values, exact);
+//   scale   - FMAX / max(amax, 1e-12) in binary64, rounded once to binary32,
+//             optionally truncated to a power of two;
+//   cast    - binary32 product x*s (one rounding), clamp to +-FMAX, then the
+//             hardware round-to-nearest-even conversion v_cvt_pk_{fp8,bf8}_f32.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fp8k {
+
+constexpr int FMT_E4M3FN = 0;
+constexpr int FMT_E5M2 = 1;
+constexpr int GRAN_TENSOR = 0;
+constexpr int GRAN_ROW = 1;
+constexpr int GRAN_COL = 2;
+constexpr int FLAG_POW2 = 1;
+
+typedef unsigned short u16x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float fmt_max(int fmt) { return fmt == FMT_E4M3FN ? 448.0f : 57344.0f; }
+
+// two bfloat16 packed in a dword -> two binary32 (exact widening)
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// running maximum of the magnitude bits of packed bfloat16 pairs
+__device__ __forceinline__ uint32_t pk_absmax(uint32_t acc, uint32_t w) {
+    w &= 0x7FFF7FFFu;
+    u16x2_t a, b;
+    __builtin_memcpy(&a, &acc, 4);
+    __builtin_memcpy(&b, &w, 4);
+    a = __builtin_elementwise_max(a, b);
+    __builtin_memcpy(&acc, &a, 4);
+    return acc;
+}
+__device__ __forceinline__ uint32_t pk_absmax4(uint32_t acc, const uint4& v) {
+    acc = pk_absmax(acc, v.x);
+    acc = pk_absmax(acc, v.y);
+    acc = pk_absmax(acc, v.z);
+    return pk_absmax(acc, v.w);
+}
+// fold the two 16-bit halves: result is the 15-bit magnitude of the maximum
+__device__ __forceinline__ uint32_t pk_fold(uint32_t acc) {
+    const uint32_t lo = acc & 0xFFFFu, hi = acc >> 16;
+    return lo > hi ? lo : hi;
+}
+__device__ __forceinline__ float mag_to_float(uint32_t mag15) { return __uint_as_float(mag15 << 16); }
+
+// maximum over the lanes of a (sub)wavefront of WIDTH lanes (power of two <= 64)
+template <int WIDTH>
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+    for (int off = WIDTH / 2; off > 0; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)v, off, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// scale from amax: binary64 quotient rounded once to binary32
+__device__ __forceinline__ float scale_from_amax(float amax, int fmt, int flags) {
+    double a = (double)amax;
+    if (!(a > 1e-12)) a = 1e-12;
+    float s = (float)((double)fmt_max(fmt) / a);
+    if (flags & FLAG_POW2) s = __uint_as_float(__float_as_uint(s) & 0xFF800000u);
+    return s;
+}
+
+// clamp to the finite range; NaN stays NaN
+template <int FMT>
+__device__ __forceinline__ float sat(float v) {
+    constexpr float F = FMT == FMT_E4M3FN ? 448.0f : 57344.0f;
+    const float c = __builtin_amdgcn_fmed3f(v, -F, F);
+    return v != v ? v : c;
+}
+
+// two binary32 -> two fp8 codes in the low 16 bits
+template <int FMT>
+__device__ __forceinline__ uint32_t cvt2(float a, float b) {
+    if constexpr (FMT == FMT_E4M3FN)
+        return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(sat<FMT>(a), sat<FMT>(b), 0, false) & 0xFFFFu;
+    else
+        return (uint32_t)__builtin_amdgcn_cvt_pk_bf8_f32(sat<FMT>(a), sat<FMT>(b), 0, false) & 0xFFFFu;
+}
+
+// four binary32 -> four fp8 codes packed little-endian in a dword
+template <int FMT>
+__device__ __forceinline__ uint32_t cvt4(float a, float b, float c, float d) {
+    int r;
+    if constexpr (FMT == FMT_E4M3FN) {
+        r = __builtin_amdgcn_cvt_pk_fp8_f32(sat<FMT>(a), sat<FMT>(b), 0, false);
+        r = __builtin_amdgcn_cvt_pk_fp8_f32(sat<FMT>(c), sat<FMT>(d), r, true);
+    } else {
+        r = __builtin_amdgcn_cvt_pk_bf8_f32(sat<FMT>(a), sat<FMT>(b), 0, false);
+        r = __builtin_amdgcn_cvt_pk_bf8_f32(sat<FMT>(c), sat<FMT>(d), r, true);
+    }
+    return (uint32_t)r;
+}
+
+// 8 bfloat16 (one 128-bit load) times 8 scales -> 8 fp8 codes (two dwords)
+template <int FMT>
+__device__ __forceinline__ uint2 cast8(const uint4& v, const float (&s)[8]) {
+    uint2 r;
+    r.x = cvt4<FMT>(bf16_lo(v.x) * s[0], bf16_hi(v.x) * s[1], bf16_lo(v.y) * s[2], bf16_hi(v.y) * s[3]);
+    r.y = cvt4<FMT>(bf16_lo(v.z) * s[4], bf16_hi(v.z) * s[5], bf16_lo(v.w) * s[6], bf16_hi(v.w) * s[7]);
+    return r;
+}
+template <int FMT>
+__device__ __forceinline__ uint2 cast8(const uint4& v, float s) {
+    uint2 r;
+    r.x = cvt4<FMT>(bf16_lo(v.x) * s, bf16_hi(v.x) * s, bf16_lo(v.y) * s, bf16_hi(v.y) * s);
+    r.y = cvt4<FMT>(bf16_lo(v.z) * s, bf16_hi(v.z) * s, bf16_lo(v.w) * s, bf16_hi(v.w) * s);
+    return r;
+}
+
+}  // namespace fp8k

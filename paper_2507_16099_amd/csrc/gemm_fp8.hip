@@ -1,0 +1,268 @@
+// Scaled FP8 GEMM for gfx950 on the CDNA4 matrix cores
+// (v_mfma_f32_16x16x128_f8f6f4): out[M,N] = (A[M,K] . B[N,K]^T) / (sa * sb).
+//
+// The paper (Section 2.1) only says that the FP8 products run on "specialized
+// GEMM kernels"; this is this library's own kernel.
+//
+// Layout of the work
+//   - Both operands have the contraction axis contiguous.  A workgroup owns a
+//     BM x BN tile of the output and walks K in steps of 128 bytes.
+//   - Each K step stages BM + BN rows of 128 bytes in LDS.  A row is eight
+//     16-byte chunks; chunk c of a row is stored at chunk position c ^ key(row)
+//     so that the 128-bit LDS reads of one MFMA operand (16 rows, same logical
+//     chunk) fall into different banks.
+//   - One MFMA takes 16 rows x 128 K-bytes of each operand: lane l supplies the
+//     32 bytes (chunks 2*(l/16) and 2*(l/16)+1) of row l%16.  The assignment of
+//     K bytes to lanes is the same for both operands, which is all a dot
+//     product needs.
+//   - The B tile is the FIRST MFMA operand and the A tile the second, so a lane
+//     ends up with accumulators for one output row m and several n.  The rows
+//     of a 64-wide B group are dealt to the four MFMA tiles such that lane l
+//     holds 16 CONSECUTIVE n (n = 16*(l/16) + 4*t + r for tile t, register r):
+//     the epilogue scales, rounds to bfloat16 and stores 32 contiguous bytes
+//     per lane straight from registers.
+//   - Workgroup ids are remapped so that each XCD (ids are dealt round-robin to
+//     the 8 XCDs) works on one contiguous range of tiles, walked in groups of
+//     tile rows, which keeps the operand panels of concurrently running tiles
+//     in that XCD's L2.
+#include "fp8_device.hpp"
+#include "launchers.hpp"
+
+#include <cstdlib>
+
+namespace fp8k {
+
+typedef int v8i_t __attribute__((ext_vector_type(8)));
+typedef float v4f_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+constexpr int BK = 128;          // bytes of K per step
+constexpr int GROUP_M = 4;       // tile rows walked together
+constexpr int NUM_XCD = 8;
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    f32x2_t v = {a, b};
+    bf16x2_t h = __builtin_convertvector(v, bf16x2_t);
+    uint32_t r;
+    __builtin_memcpy(&r, &h, 4);
+    return r;
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, bool OUT_F32>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_tn_kernel(
+    const uint8_t* __restrict__ A, int64_t lda, const uint8_t* __restrict__ B, int64_t ldb,
+    const float* __restrict__ scale_a, int row_a, const float* __restrict__ scale_b, int row_b, int M, int N,
+    int K, void* __restrict__ out, int64_t ld_out, int tiles_m, int tiles_n) {
+    constexpr int NT = WAVES_M * WAVES_N * 64;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int FM = WM / 16;       // A fragments (16 rows each) per wave
+    constexpr int NG = WN / 64;       // 64-wide B groups per wave
+    constexpr int FN = NG * 4;        // B fragments per wave
+    constexpr int NLA = BM * 8 / NT;  // 16-byte chunks each thread stages per step
+    constexpr int NLB = BN * 8 / NT;
+    constexpr int STAGE = (BM + BN) * BK;
+    static_assert(WM % 16 == 0 && WN % 64 == 0 && (BM * 8) % NT == 0 && (BN * 8) % NT == 0 && (NT / 8) % 32 == 0, "tile");
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    // ---- workgroup -> tile
+    const int ntiles = tiles_m * tiles_n;
+    const int per_xcd = gridDim.x / NUM_XCD;
+    const int logical = (blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
+    if (logical >= ntiles) return;
+    const int in_group = GROUP_M * tiles_n;
+    const int first_m = (logical / in_group) * GROUP_M;
+    const int gsize = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
+    const int tm = first_m + (logical % in_group) % gsize;
+    const int tn = (logical % in_group) / gsize;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+
+    // ---- global -> LDS staging: thread t owns LDS chunk slots i*NT + t
+    const int srow = tid >> 3, spc = tid & 7;
+    const int ca = spc ^ (srow & 7);                                   // logical chunk, A rows
+    const int cb = spc ^ ((srow & 3) | ((srow >> 2) & 4));             // logical chunk, B rows
+    const uint8_t* a_ptr = A + (int64_t)(m0 + srow) * lda + ca * 16;
+    const uint8_t* b_ptr = B + (int64_t)(n0 + srow) * ldb + cb * 16;
+    const int64_t a_step = (int64_t)(NT / 8) * lda, b_step = (int64_t)(NT / 8) * ldb;
+
+    uint4 ra[NLA], rb[NLB];
+    auto gload = [&](int k0) {
+        const bool ka = k0 + ca * 16 < K, kb = k0 + cb * 16 < K;
+#pragma unroll
+        for (int i = 0; i < NLA; ++i) {
+            const bool ok = ka && (m0 + srow + i * (NT / 8) < M);
+            ra[i] = ok ? *reinterpret_cast<const uint4*>(a_ptr + i * a_step + k0) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < NLB; ++i) {
+            const bool ok = kb && (n0 + srow + i * (NT / 8) < N);
+            rb[i] = ok ? *reinterpret_cast<const uint4*>(b_ptr + i * b_step + k0) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto lstore = [&](int stage) {
+        uint8_t* as = smem + stage * STAGE + tid * 16;
+        uint8_t* bs = as + BM * BK;
+#pragma unroll
+        for (int i = 0; i < NLA; ++i) *reinterpret_cast<uint4*>(as + i * NT * 16) = ra[i];
+#pragma unroll
+        for (int i = 0; i < NLB; ++i) *reinterpret_cast<uint4*>(bs + i * NT * 16) = rb[i];
+    };
+
+    // ---- LDS -> MFMA operands
+    const int key = lane & 7;
+    const int off_lo = ((2 * (lane >> 4)) ^ key) << 4, off_hi = ((2 * (lane >> 4) + 1) ^ key) << 4;
+    const int a_row_off = (wm0 + (lane & 15)) * BK;
+    const int b_row_off = (wn0 + 16 * ((lane & 15) >> 2) + (lane & 3)) * BK;
+
+    v4f_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[i][j] = v4f_t{0.f, 0.f, 0.f, 0.f};
+
+    auto frag = [&](const uint8_t* base) {
+        const uint4 lo = *reinterpret_cast<const uint4*>(base + off_lo);
+        const uint4 hi = *reinterpret_cast<const uint4*>(base + off_hi);
+        return v8i_t{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+    };
+    auto compute = [&](int stage) {
+        const uint8_t* as = smem + stage * STAGE + a_row_off;
+        const uint8_t* bs = smem + stage * STAGE + BM * BK + b_row_off;
+        v8i_t bf[FN];
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) bf[g * 4 + t] = frag(bs + (64 * g + 4 * t) * BK);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const v8i_t af = frag(as + 16 * i * BK);
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[j], af, acc[i][j], FB, FA, 0, 0, 0, 0);
+        }
+    };
+
+    // ---- main loop, two LDS stages
+    const int ksteps = (K + BK - 1) / BK;
+    gload(0);
+    lstore(0);
+    __syncthreads();
+    for (int kt = 0; kt < ksteps; ++kt) {
+        const bool more = kt + 1 < ksteps;
+        if (more) gload((kt + 1) * BK);
+        compute(kt & 1);
+        if (more) lstore((kt + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: (acc * 1/sa) * 1/sb, round, store 16 consecutive n per lane
+    const float inv_a_t = row_a ? 0.f : 1.0f / scale_a[0];
+    const float inv_b_t = row_b ? 0.f : 1.0f / scale_b[0];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const int nb = n0 + wn0 + 64 * g + 16 * (lane >> 4);
+        float inv_b[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) inv_b[e] = row_b ? ((nb + e < N) ? 1.0f / scale_b[nb + e] : 0.f) : inv_b_t;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int m = m0 + wm0 + 16 * i + (lane & 15);
+            if (m >= M || nb >= N) continue;
+            const float inv_a = row_a ? 1.0f / scale_a[m] : inv_a_t;
+            float v[16];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[4 * t + r] = (acc[i][g * 4 + t][r] * inv_a) * inv_b[4 * t + r];
+            if constexpr (OUT_F32) {
+                float* dst = static_cast<float*>(out) + (int64_t)m * ld_out + nb;
+                if (nb + 16 <= N) {
+#pragma unroll
+                    for (int e = 0; e < 16; e += 4)
+                        *reinterpret_cast<float4*>(dst + e) = make_float4(v[e], v[e + 1], v[e + 2], v[e + 3]);
+                } else {
+                    for (int e = 0; nb + e < N; ++e) dst[e] = v[e];
+                }
+            } else {
+                uint16_t* dst = static_cast<uint16_t*>(out) + (int64_t)m * ld_out + nb;
+                uint32_t p[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) p[e] = pack_bf16(v[2 * e], v[2 * e + 1]);
+                if (nb + 16 <= N) {
+                    *reinterpret_cast<uint4*>(dst) = make_uint4(p[0], p[1], p[2], p[3]);
+                    *reinterpret_cast<uint4*>(dst + 8) = make_uint4(p[4], p[5], p[6], p[7]);
+                } else {
+                    for (int e = 0; nb + e < N; ++e) dst[e] = (uint16_t)(p[e >> 1] >> ((e & 1) * 16));
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, bool OUT_F32>
+static hipError_t launch_variant(const uint8_t* a, int64_t lda, const float* sa, int row_a, const uint8_t* b,
+                                 int64_t ldb, const float* sb, int row_b, int M, int N, int K, void* out,
+                                 int64_t ld_out, hipStream_t st) {
+    auto kern = gemm_fp8_tn_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, OUT_F32>;
+    constexpr int lds = 2 * (BM + BN) * BK;
+    static bool attr_done = false;  // one attribute per instantiation; idempotent, so a race is harmless
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const int64_t ntiles = (int64_t)tiles_m * tiles_n;
+    const int64_t grid = (ntiles + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
+    if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
+    kern<<<dim3((unsigned)grid), dim3(WAVES_M * WAVES_N * 64), lds, st>>>(a, lda, b, ldb, sa, row_a, sb, row_b, M, N,
+                                                                          K, out, ld_out, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+template <int FA, int FB, bool OUT_F32>
+static hipError_t launch_fmt(int variant, const uint8_t* a, int64_t lda, const float* sa, int row_a,
+                             const uint8_t* b, int64_t ldb, const float* sb, int row_b, int M, int N, int K,
+                             void* out, int64_t ld_out, hipStream_t st) {
+    if (variant == 1)
+        return launch_variant<256, 256, 2, 4, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
+    return launch_variant<128, 128, 2, 2, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
+}
+
+// Tile choice: large problems take the 256 x 256 tile, small ones the
+// 128 x 128 tile (more workgroups).  FP8MI355_GEMM_VARIANT=0|1 overrides
+// (tuning and test aid).
+static int pick_variant(int64_t M, int64_t N) {
+    if (const char* e = std::getenv("FP8MI355_GEMM_VARIANT")) {
+        const int v = std::atoi(e);
+        if (v == 0 || v == 1) return v;
+    }
+    const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
+    return tiles256 >= 256 ? 1 : 0;
+}
+
+hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
+                           const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int row_b,
+                           int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
+                           hipStream_t st) {
+    if (M == 0 || N == 0) return hipSuccess;
+    const int v = pick_variant(M, N);
+    const int m = (int)M, n = (int)N, k = (int)K;
+#define FP8K_GEMM(FA_, FB_)                                                                                     \
+    if (fmt_a == FA_ && fmt_b == FB_)                                                                           \
+        return out_f32 ? launch_fmt<FA_, FB_, true>(v, a, lda, scale_a, row_a, b, ldb, scale_b, row_b, m, n, k, out, ld_out, st) \
+                       : launch_fmt<FA_, FB_, false>(v, a, lda, scale_a, row_a, b, ldb, scale_b, row_b, m, n, k, out, ld_out, st)
+    FP8K_GEMM(FMT_E4M3FN, FMT_E4M3FN);
+    FP8K_GEMM(FMT_E5M2, FMT_E4M3FN);
+    FP8K_GEMM(FMT_E4M3FN, FMT_E5M2);
+    FP8K_GEMM(FMT_E5M2, FMT_E5M2);
+#undef FP8K_GEMM
+    return hipErrorInvalidValue;
+}
+
+}  // namespace fp8k

@@ -1,0 +1,34 @@
+// Internal launch functions behind the C ABI.  Arguments are assumed valid
+// (the ABI layer checks them); every function only enqueues work on `st`.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fp8k {
+
+hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st);
+
+hipError_t launch_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran, float* out,
+                       hipStream_t st);
+
+hipError_t launch_scale(const float* amax, int64_t n, int fmt, int flags, float* out, hipStream_t st);
+
+// transpose != 0: q is [cols, rows]; q_plain (optional, transpose only) also
+// receives the untransposed codes.
+hipError_t launch_cast(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int gran,
+                       int fmt, int transpose, uint8_t* q, int64_t ld_out, uint8_t* q_plain, int64_t ld_plain,
+                       hipStream_t st);
+
+// single-pass rowwise amax+scale+cast; hipErrorNotSupported if a row is too
+// long to keep in registers.
+hipError_t launch_quant_row(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, int flags, uint8_t* q,
+                            int64_t ld_out, float* scale_out, hipStream_t st);
+
+// out[M,N] = (a[M,K] . b[N,K]^T) / (sa * sb); scale_a/scale_b have one entry
+// (row_a / row_b == 0) or one per row.
+hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
+                           const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int row_b,
+                           int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
+                           hipStream_t st);
+
+}  // namespace fp8k

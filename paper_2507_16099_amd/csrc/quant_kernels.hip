@@ -1,0 +1,459 @@
+// amax / scale / cast / fused quantization kernels for gfx950 (HBM-bound).
+//
+// Every kernel reads bfloat16 with 128-bit loads laid out so that one
+// wavefront instruction touches whole 128-byte lines, and writes fp8 codes
+// with 64- or 128-bit stores.  Groups follow the paper's Appendix A: one scale
+// per tensor, per row, or per column.
+#include "fp8_device.hpp"
+#include "launchers.hpp"
+
+namespace fp8k {
+
+// ---------------------------------------------------------------- fill
+__global__ void fill_u32_kernel(uint32_t* p, int64_t n, uint32_t v) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    fill_u32_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(p, n, v);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- amax
+// One group of TX threads per row; TY = 256 / TX rows per block.
+// single != 0: every row folds into out[0] with an atomic max (tensorwise
+// amax of a matrix whose rows are not contiguous in memory).
+template <int TX>
+__global__ __launch_bounds__(256) void amax_rows_kernel(const uint16_t* __restrict__ x, int64_t rows,
+                                                         int64_t cols, int64_t ld,
+                                                         float* __restrict__ out, int single) {
+    constexpr int TY = 256 / TX;
+    const int tx = threadIdx.x % TX, ty = threadIdx.x / TX;
+    const int64_t r = (int64_t)blockIdx.x * TY + ty;
+    uint32_t acc = 0;
+    if (r < rows) {
+        const uint16_t* row = x + r * ld;
+        const uint4* rv = reinterpret_cast<const uint4*>(row);
+        const int64_t nvec = cols >> 3;
+#pragma unroll 4
+        for (int64_t v = tx; v < nvec; v += TX) acc = pk_absmax4(acc, rv[v]);
+        for (int64_t c = (nvec << 3) + tx; c < cols; c += TX) acc = pk_absmax(acc, (uint32_t)row[c]);
+    }
+    uint32_t m = pk_fold(acc);
+    m = wave_max_u32<(TX < 64 ? TX : 64)>(m);
+    if constexpr (TX > 64) {
+        __shared__ uint32_t part[256 / 64];
+        const int wave = threadIdx.x / 64;
+        if ((threadIdx.x & 63) == 0) part[wave] = m;
+        __syncthreads();
+        constexpr int WPR = TX / 64;  // waves per row
+        const int w0 = ty * WPR;
+        m = part[w0];
+#pragma unroll
+        for (int i = 1; i < WPR; ++i) m = part[w0 + i] > m ? part[w0 + i] : m;
+    }
+    if (r < rows && tx == 0) {
+        if (single) atomicMax(reinterpret_cast<uint32_t*>(out), m << 16);
+        else out[r] = mag_to_float(m);
+    }
+}
+
+// Tensorwise amax of a contiguous array of n bfloat16: grid-stride over
+// 128-bit vectors, block reduction, one atomic max per block (out zeroed).
+__global__ __launch_bounds__(256) void amax_flat_kernel(const uint16_t* __restrict__ x, int64_t n,
+                                                         float* __restrict__ out) {
+    const uint4* xv = reinterpret_cast<const uint4*>(x);
+    const int64_t nvec = n >> 3;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    uint32_t acc = 0;
+#pragma unroll 8
+    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < nvec; v += stride) acc = pk_absmax4(acc, xv[v]);
+    if (blockIdx.x == 0)
+        for (int64_t c = (nvec << 3) + threadIdx.x; c < n; c += 256) acc = pk_absmax(acc, (uint32_t)x[c]);
+    uint32_t m = wave_max_u32<64>(pk_fold(acc));
+    __shared__ uint32_t part[4];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x / 64] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = part[0];
+        for (int i = 1; i < 4; ++i) m = part[i] > m ? part[i] : m;
+        atomicMax(reinterpret_cast<uint32_t*>(out), m << 16);
+    }
+}
+
+// Column amax: a block owns 512 columns (64 lanes x 8) and rows_per_block rows;
+// its four wavefronts take every fourth row.  out must be zeroed beforehand.
+__global__ __launch_bounds__(256) void amax_cols_kernel(const uint16_t* __restrict__ x, int64_t rows,
+                                                         int64_t cols, int64_t ld,
+                                                         float* __restrict__ out, int64_t rows_per_block) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t c0 = (int64_t)blockIdx.x * 512 + lane * 8;
+    const int64_t r_begin = (int64_t)blockIdx.y * rows_per_block;
+    const int64_t r_end = r_begin + rows_per_block < rows ? r_begin + rows_per_block : rows;
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    if (c0 < cols) {
+        const uint16_t* p = x + c0;
+#pragma unroll 8
+        for (int64_t r = r_begin + wave; r < r_end; r += 4) {
+            const uint4 v = *reinterpret_cast<const uint4*>(p + r * ld);
+            acc.x = pk_absmax(acc.x, v.x);
+            acc.y = pk_absmax(acc.y, v.y);
+            acc.z = pk_absmax(acc.z, v.z);
+            acc.w = pk_absmax(acc.w, v.w);
+        }
+    }
+    __shared__ uint4 part[4][64];
+    part[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0 && c0 < cols) {
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const uint4 o = part[w][lane];
+            acc.x = pk_absmax(acc.x, o.x);
+            acc.y = pk_absmax(acc.y, o.y);
+            acc.z = pk_absmax(acc.z, o.z);
+            acc.w = pk_absmax(acc.w, o.w);
+        }
+        const uint32_t w4[4] = {acc.x, acc.y, acc.z, acc.w};
+        uint32_t* o = reinterpret_cast<uint32_t*>(out);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t mag = (e & 1) ? (w4[e >> 1] >> 16) : (w4[e >> 1] & 0xFFFFu);
+            if (c0 + e < cols && mag) atomicMax(o + c0 + e, mag << 16);
+        }
+    }
+}
+
+hipError_t launch_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran, float* out,
+                       hipStream_t st) {
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    if (rows == 0 || cols == 0) {
+        // empty groups have amax 0
+        const int64_t n = gran == GRAN_TENSOR ? 1 : (gran == GRAN_ROW ? rows : cols);
+        return launch_fill_u32(reinterpret_cast<uint32_t*>(out), n, 0u, st);
+    }
+    if (gran == GRAN_TENSOR && (ld == cols || rows == 1)) {
+        hipError_t e = launch_fill_u32(reinterpret_cast<uint32_t*>(out), 1, 0u, st);
+        if (e != hipSuccess) return e;
+        const int64_t n = rows * cols;
+        int64_t blocks = (n / 8 + 256 * 8 - 1) / (256 * 8);
+        if (blocks < 1) blocks = 1;
+        if (blocks > 4096) blocks = 4096;
+        amax_flat_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(xp, n, out);
+        return hipGetLastError();
+    }
+    if (gran == GRAN_TENSOR || gran == GRAN_ROW) {
+        const int single = gran == GRAN_TENSOR;
+        if (single) {
+            hipError_t e = launch_fill_u32(reinterpret_cast<uint32_t*>(out), 1, 0u, st);
+            if (e != hipSuccess) return e;
+        }
+        const int64_t nvec = cols / 8;
+        if (nvec <= 16) {
+            amax_rows_kernel<16><<<dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st>>>(xp, rows, cols, ld, out, single);
+        } else if (nvec <= 64) {
+            amax_rows_kernel<64><<<dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st>>>(xp, rows, cols, ld, out, single);
+        } else {
+            amax_rows_kernel<256><<<dim3((unsigned)rows), dim3(256), 0, st>>>(xp, rows, cols, ld, out, single);
+        }
+        return hipGetLastError();
+    }
+    // GRAN_COL
+    hipError_t e = launch_fill_u32(reinterpret_cast<uint32_t*>(out), cols, 0u, st);
+    if (e != hipSuccess) return e;
+    int64_t rpb = 256;
+    while ((rows + rpb - 1) / rpb > 65535) rpb *= 2;
+    dim3 grid((unsigned)((cols + 511) / 512), (unsigned)((rows + rpb - 1) / rpb));
+    amax_cols_kernel<<<grid, dim3(256), 0, st>>>(xp, rows, cols, ld, out, rpb);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- scale
+__global__ void scale_kernel(const float* __restrict__ amax, int64_t n, int fmt, int flags,
+                             float* __restrict__ out) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = scale_from_amax(amax[i], fmt, flags);
+}
+
+hipError_t launch_scale(const float* amax, int64_t n, int fmt, int flags, float* out, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    scale_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(amax, n, fmt, flags, out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- cast
+// Row-major cast: a thread converts 16 consecutive elements of one row
+// (two 128-bit loads, one 128-bit store).  blockDim = (TX, TY).
+template <int FMT, int GRAN>
+__global__ __launch_bounds__(256) void cast_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                    int64_t ld, const float* __restrict__ scale,
+                                                    uint8_t* __restrict__ q, int64_t ld_out) {
+    const int64_t c = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 16;
+    if (c >= cols) return;
+    float s_t = 0.0f;
+    if constexpr (GRAN == GRAN_TENSOR) s_t = scale[0];
+    for (int64_t r = (int64_t)blockIdx.y * blockDim.y + threadIdx.y; r < rows; r += (int64_t)gridDim.y * blockDim.y) {
+        const uint16_t* src = x + r * ld + c;
+        uint8_t* dst = q + r * ld_out + c;
+        if constexpr (GRAN == GRAN_ROW) s_t = scale[r];
+        if (c + 16 <= cols) {
+            const uint4 v0 = reinterpret_cast<const uint4*>(src)[0];
+            const uint4 v1 = reinterpret_cast<const uint4*>(src)[1];
+            uint2 lo, hi;
+            if constexpr (GRAN == GRAN_COL) {
+                float s[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s[e] = scale[c + e];
+                lo = cast8<FMT>(v0, s);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s[e] = scale[c + 8 + e];
+                hi = cast8<FMT>(v1, s);
+            } else {
+                lo = cast8<FMT>(v0, s_t);
+                hi = cast8<FMT>(v1, s_t);
+            }
+            *reinterpret_cast<uint4*>(dst) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        } else {
+            for (int e = 0; c + e < cols; ++e) {
+                const float s = GRAN == GRAN_COL ? scale[c + e] : s_t;
+                const float p = __uint_as_float((uint32_t)src[e] << 16) * s;
+                dst[e] = (uint8_t)(cvt2<FMT>(p, p) & 0xFFu);
+            }
+        }
+    }
+}
+
+// 4x4 byte transpose: rows a,b,c,d (byte j = column j) -> o[j] = column j
+__device__ __forceinline__ void transpose4x4_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d, uint32_t (&o)[4]) {
+    const uint32_t t0 = __builtin_amdgcn_perm(b, a, 0x05010400u);
+    const uint32_t t1 = __builtin_amdgcn_perm(b, a, 0x07030602u);
+    const uint32_t u0 = __builtin_amdgcn_perm(d, c, 0x05010400u);
+    const uint32_t u1 = __builtin_amdgcn_perm(d, c, 0x07030602u);
+    o[0] = __builtin_amdgcn_perm(u0, t0, 0x05040100u);
+    o[1] = __builtin_amdgcn_perm(u0, t0, 0x07060302u);
+    o[2] = __builtin_amdgcn_perm(u1, t1, 0x05040100u);
+    o[3] = __builtin_amdgcn_perm(u1, t1, 0x07060302u);
+}
+
+// Transposing cast.  A block converts a 128 x 128 tile: each thread loads an
+// 8 x 8 sub-block (eight 128-bit loads), converts it, transposes the bytes in
+// registers and parks eight 64-bit column pieces in LDS; the block then
+// streams the tile out as rows of the transposed matrix with 128-bit stores.
+// q_plain != nullptr additionally writes the untransposed codes (the
+// tensorwise recipe needs both layouts of the same tensor in the backward).
+// LDS tile: 128 output rows x 128 bytes; the 8-byte slot index is XORed with
+// 2 * ((row / 8) & 7) so that a wavefront's column pieces spread over banks.
+template <int FMT, int GRAN>
+__global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __restrict__ x, int64_t rows,
+                                                              int64_t cols, int64_t ld,
+                                                              const float* __restrict__ scale,
+                                                              uint8_t* __restrict__ qt, int64_t ld_t,
+                                                              uint8_t* __restrict__ q_plain, int64_t ld_plain) {
+    __shared__ __attribute__((aligned(16))) uint2 tile[128 * 16];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int64_t r0 = (int64_t)blockIdx.y * 128, c0 = (int64_t)blockIdx.x * 128;
+    const int64_t c = c0 + tx * 8;
+
+    float s_col[8];
+    float s_t = 0.0f;
+    if constexpr (GRAN == GRAN_TENSOR) s_t = scale[0];
+    if constexpr (GRAN == GRAN_COL) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s_col[e] = (c + e < cols) ? scale[c + e] : 0.0f;
+    }
+
+    uint32_t w[8][2];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int64_t r = r0 + ty * 8 + j;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (r < rows) {
+            const uint16_t* src = x + r * ld + c;
+            if (c + 8 <= cols) {
+                v = *reinterpret_cast<const uint4*>(src);
+            } else if (c < cols) {
+                uint32_t t[4] = {0, 0, 0, 0};
+                for (int e = 0; c + e < cols; ++e) t[e >> 1] |= (uint32_t)src[e] << ((e & 1) * 16);
+                v = make_uint4(t[0], t[1], t[2], t[3]);
+            }
+        }
+        uint2 b;
+        if constexpr (GRAN == GRAN_COL) {
+            b = cast8<FMT>(v, s_col);
+        } else {
+            if constexpr (GRAN == GRAN_ROW) s_t = (r < rows) ? scale[r] : 0.0f;
+            b = cast8<FMT>(v, s_t);
+        }
+        w[j][0] = b.x;
+        w[j][1] = b.y;
+        if (q_plain != nullptr && r < rows) {
+            uint8_t* dst = q_plain + r * ld_plain + c;
+            if (c + 8 <= cols) {
+                *reinterpret_cast<uint2*>(dst) = b;
+            } else {
+                for (int e = 0; c + e < cols; ++e) dst[e] = (uint8_t)((e < 4 ? b.x >> (8 * e) : b.y >> (8 * (e - 4))) & 0xFFu);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint32_t lo[4], hi[4];
+        transpose4x4_bytes(w[0][h], w[1][h], w[2][h], w[3][h], lo);
+        transpose4x4_bytes(w[4][h], w[5][h], w[6][h], w[7][h], hi);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int cc = tx * 8 + h * 4 + i;  // output row inside the tile
+            tile[cc * 16 + (ty ^ (2 * (tx & 7)))] = make_uint2(lo[i], hi[i]);
+        }
+    }
+    __syncthreads();
+
+    const uint4* tile16 = reinterpret_cast<const uint4*>(tile);
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int cc = it * 32 + (threadIdx.x >> 3), p = threadIdx.x & 7;
+        const int64_t oc = c0 + cc, orow = r0 + p * 16;
+        if (oc >= cols || orow >= rows) continue;
+        const uint4 v = tile16[cc * 8 + (p ^ ((cc >> 3) & 7))];
+        uint8_t* dst = qt + oc * ld_t + orow;
+        if (orow + 16 <= rows) {
+            *reinterpret_cast<uint4*>(dst) = v;
+        } else {
+            const uint32_t t[4] = {v.x, v.y, v.z, v.w};
+            for (int e = 0; orow + e < rows; ++e) dst[e] = (uint8_t)((t[e >> 2] >> (8 * (e & 3))) & 0xFFu);
+        }
+    }
+}
+
+template <int FMT, int GRAN>
+static hipError_t launch_cast_t(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, const float* scale,
+                                int transpose, uint8_t* q, int64_t ld_out, uint8_t* q_plain, int64_t ld_plain,
+                                hipStream_t st) {
+    if (transpose) {
+        const int64_t gx = (cols + 127) / 128, gy = (rows + 127) / 128;
+        if (gy > 65535) return hipErrorInvalidValue;
+        cast_transpose_kernel<FMT, GRAN><<<dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, st>>>(
+            x, rows, cols, ld, scale, q, ld_out, q_plain, ld_plain);
+        return hipGetLastError();
+    }
+    const int64_t items = (cols + 15) / 16;
+    int tx = 1;
+    while (tx < items && tx < 256) tx *= 2;
+    const int ty = 256 / tx;
+    int64_t gy = (rows + ty - 1) / ty;
+    if (gy > 65535) gy = 65535;
+    dim3 grid((unsigned)((items + tx - 1) / tx), (unsigned)gy);
+    cast_kernel<FMT, GRAN><<<grid, dim3(tx, ty), 0, st>>>(x, rows, cols, ld, scale, q, ld_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_cast(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int gran,
+                       int fmt, int transpose, uint8_t* q, int64_t ld_out, uint8_t* q_plain, int64_t ld_plain,
+                       hipStream_t st) {
+    if (rows == 0 || cols == 0) return hipSuccess;
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+#define FP8K_CAST(F, G) \
+    if (fmt == F && gran == G) return launch_cast_t<F, G>(xp, rows, cols, ld, scale, transpose, q, ld_out, q_plain, ld_plain, st)
+    FP8K_CAST(FMT_E4M3FN, GRAN_TENSOR);
+    FP8K_CAST(FMT_E4M3FN, GRAN_ROW);
+    FP8K_CAST(FMT_E4M3FN, GRAN_COL);
+    FP8K_CAST(FMT_E5M2, GRAN_TENSOR);
+    FP8K_CAST(FMT_E5M2, GRAN_ROW);
+    FP8K_CAST(FMT_E5M2, GRAN_COL);
+#undef FP8K_CAST
+    return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------- fused rowwise quantize
+// amax -> scale -> cast of whole rows in ONE pass over HBM: a group of TX
+// threads owns a row and keeps it in registers (NV 128-bit vectors per
+// thread) between the reduction and the conversion.
+template <int FMT, int TX, int NV>
+__global__ __launch_bounds__(256) void quant_row_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                         int64_t ld, int flags, uint8_t* __restrict__ q,
+                                                         int64_t ld_out, float* __restrict__ scale_out) {
+    constexpr int TY = 256 / TX;
+    const int tx = threadIdx.x % TX, ty = threadIdx.x / TX;
+    const int64_t r = (int64_t)blockIdx.x * TY + ty;
+    const bool live = r < rows;
+    const int64_t nvec = cols >> 3;
+    const int ntail = (int)(cols & 7);
+    const uint16_t* row = x + (live ? r : 0) * ld;
+    const uint4* rv = reinterpret_cast<const uint4*>(row);
+
+    uint4 v[NV];
+    uint32_t acc = 0;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int64_t vi = tx + (int64_t)j * TX;
+        v[j] = (live && vi < nvec) ? rv[vi] : make_uint4(0, 0, 0, 0);
+    }
+    uint32_t tail = 0;
+    if (live && tx < ntail) tail = row[(nvec << 3) + tx];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) acc = pk_absmax4(acc, v[j]);
+    acc = pk_absmax(acc, tail);
+
+    uint32_t m = wave_max_u32<(TX < 64 ? TX : 64)>(pk_fold(acc));
+    if constexpr (TX > 64) {
+        __shared__ uint32_t part[256 / 64];
+        if ((threadIdx.x & 63) == 0) part[threadIdx.x / 64] = m;
+        __syncthreads();
+        constexpr int WPR = TX / 64;
+        const int w0 = ty * WPR;
+        m = part[w0];
+#pragma unroll
+        for (int i = 1; i < WPR; ++i) m = part[w0 + i] > m ? part[w0 + i] : m;
+    }
+    if (!live) return;
+    const float s = scale_from_amax(mag_to_float(m), FMT, flags);
+    if (tx == 0) scale_out[r] = s;
+
+    uint8_t* dst = q + r * ld_out;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int64_t vi = tx + (int64_t)j * TX;
+        if (vi < nvec) reinterpret_cast<uint2*>(dst)[vi] = cast8<FMT>(v[j], s);
+    }
+    if (tx < ntail) {
+        const float p = __uint_as_float(tail << 16) * s;
+        dst[(nvec << 3) + tx] = (uint8_t)(cvt2<FMT>(p, p) & 0xFFu);
+    }
+}
+
+template <int FMT>
+static bool launch_quant_row_t(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, int flags, uint8_t* q,
+                               int64_t ld_out, float* scale_out, hipStream_t st) {
+    const int64_t nvec = cols / 8;
+#define FP8K_QR(TX, NV)                                                                              \
+    quant_row_kernel<FMT, TX, NV><<<dim3((unsigned)((rows + (256 / TX) - 1) / (256 / TX))), dim3(256), 0, st>>>( \
+        x, rows, cols, ld, flags, q, ld_out, scale_out)
+    if (nvec <= 16) FP8K_QR(16, 1);
+    else if (nvec <= 64) FP8K_QR(64, 1);
+    else if (nvec <= 256) FP8K_QR(256, 1);
+    else if (nvec <= 512) FP8K_QR(256, 2);
+    else if (nvec <= 1024) FP8K_QR(256, 4);
+    else if (nvec <= 2048) FP8K_QR(256, 8);
+    else if (nvec <= 4096) FP8K_QR(256, 16);
+    else return false;
+#undef FP8K_QR
+    return true;
+}
+
+// returns hipErrorNotSupported when a row does not fit in registers (the
+// caller then runs amax, scale and cast as separate passes)
+hipError_t launch_quant_row(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, int flags, uint8_t* q,
+                            int64_t ld_out, float* scale_out, hipStream_t st) {
+    if (rows == 0) return hipSuccess;
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    const bool ok = fmt == FMT_E4M3FN
+                        ? launch_quant_row_t<FMT_E4M3FN>(xp, rows, cols, ld, flags, q, ld_out, scale_out, st)
+                        : launch_quant_row_t<FMT_E5M2>(xp, rows, cols, ld, flags, q, ld_out, scale_out, st);
+    if (!ok) return hipErrorNotSupported;
+    return hipGetLastError();
+}
+
+}  // namespace fp8k

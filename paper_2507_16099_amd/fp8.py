@@ -1,0 +1,222 @@
+"""ctypes binding of the C ABI declared in include/fp8mi355.h.
+
+Same names as the C entry points.  Tensors are torch CUDA (ROCm) tensors:
+bfloat16 inputs as ``torch.bfloat16`` (or raw ``uint16``/``int16`` bits), fp8
+codes as ``torch.uint8``, scales as ``torch.float32``.  Work is enqueued on
+torch's current stream.  There is no fallback: if the library cannot be loaded
+an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+FP8_E4M3FN, FP8_E5M2 = 0, 1
+FP8_TENSOR, FP8_ROW, FP8_COL = 0, 1, 2
+FP8_POW2_SCALE, FP8_TRANSPOSE_OUT, FP8_OUT_FP32 = 1, 2, 4
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libfp8mi355.so")
+_lib = None
+
+
+class Fp8Error(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"fp8mi355 error {code}: {msg}")
+        self.code = code
+
+
+class _CRecipe(C.Structure):
+    _fields_ = [("gran", C.c_int), ("fmt_x", C.c_int), ("fmt_w", C.c_int), ("fmt_dy", C.c_int), ("flags", C.c_int)]
+
+
+@dataclass(frozen=True)
+class Recipe:
+    gran: int = FP8_TENSOR
+    fmt_x: int = FP8_E4M3FN
+    fmt_w: int = FP8_E4M3FN
+    fmt_dy: int = FP8_E5M2
+    flags: int = 0
+
+    def c(self) -> _CRecipe:
+        return _CRecipe(self.gran, self.fmt_x, self.fmt_w, self.fmt_dy, self.flags)
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> C.CDLL:
+    """Load libfp8mi355.so (built in-tree by paper_2507_16099_amd/build.py)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python -m paper_2507_16099_amd.build` "
+                          "(or __graft_entry__.build()); there is no fallback path")
+    L = C.CDLL(_LIB_PATH)
+    i64, vp, ci = C.c_int64, C.c_void_p, C.c_int
+    L.fp8_last_error.restype = C.c_char_p
+    L.fp8_last_error.argtypes = []
+    L.fp8_version.restype = C.c_char_p
+    L.fp8_version.argtypes = []
+    L.fp8_amax.restype = ci
+    L.fp8_amax.argtypes = [vp, i64, i64, i64, ci, vp, vp]
+    L.fp8_scale.restype = ci
+    L.fp8_scale.argtypes = [vp, i64, ci, ci, vp, vp]
+    L.fp8_cast.restype = ci
+    L.fp8_cast.argtypes = [vp, i64, i64, i64, vp, ci, ci, ci, vp, i64, vp]
+    L.fp8_quantize.restype = ci
+    L.fp8_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, i64, vp, vp]
+    L.fp8_scaled_mm.restype = ci
+    L.fp8_scaled_mm.argtypes = [vp, i64, ci, vp, ci, vp, i64, ci, vp, ci, i64, i64, i64, vp, i64, ci, vp]
+    L.fp8_linear_workspace_bytes.restype = C.c_size_t
+    L.fp8_linear_workspace_bytes.argtypes = [i64, i64, i64, C.POINTER(_CRecipe), ci]
+    L.fp8_linear_fwd.restype = ci
+    L.fp8_linear_fwd.argtypes = [vp, vp, i64, i64, i64, C.POINTER(_CRecipe), vp, vp, C.c_size_t, vp]
+    L.fp8_linear_bwd.restype = ci
+    L.fp8_linear_bwd.argtypes = [vp, vp, vp, i64, i64, i64, C.POINTER(_CRecipe), vp, vp, vp, C.c_size_t, vp]
+    _lib = L
+    return L
+
+
+def fp8_last_error() -> str:
+    return load_library().fp8_last_error().decode()
+
+
+def fp8_version() -> str:
+    return load_library().fp8_version().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise Fp8Error(rc, fp8_last_error())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t) -> int | None:
+    return None if t is None else t.data_ptr()
+
+
+def _mat(t: torch.Tensor, itemsize: int):
+    """(rows, cols, ld) of a 2-D tensor whose last dimension is contiguous."""
+    assert t.is_cuda and t.dim() == 2 and t.element_size() == itemsize, (t.shape, t.dtype, t.device)
+    assert t.shape[1] <= 1 or t.stride(1) == 1, "last dimension must be contiguous"
+    ld = t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
+    return t.shape[0], t.shape[1], ld
+
+
+def _groups(gran: int, rows: int, cols: int) -> int:
+    return 1 if gran == FP8_TENSOR else (rows if gran == FP8_ROW else cols)
+
+
+def _pad16(n: int) -> int:
+    return (n + 15) // 16 * 16
+
+
+def fp8_amax(x: torch.Tensor, gran: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    rows, cols, ld = _mat(x, 2)
+    if out is None:
+        out = torch.empty(max(_groups(gran, rows, cols), 0), dtype=torch.float32, device=x.device)
+    _check(load_library().fp8_amax(_ptr(x), rows, cols, ld, gran, _ptr(out), _stream()))
+    return out
+
+
+def fp8_scale(amax: torch.Tensor, fmt: int, flags: int = 0, out: torch.Tensor | None = None) -> torch.Tensor:
+    assert amax.is_cuda and amax.dtype == torch.float32 and amax.is_contiguous()
+    if out is None:
+        out = torch.empty_like(amax)
+    _check(load_library().fp8_scale(_ptr(amax), amax.numel(), fmt, flags, _ptr(out), _stream()))
+    return out
+
+
+def _alloc_q(rows: int, cols: int, flags: int, device) -> torch.Tensor:
+    """fp8 output with a leading dimension padded to 16 (returned as a view)."""
+    r, c = (cols, rows) if flags & FP8_TRANSPOSE_OUT else (rows, cols)
+    return torch.empty((r, _pad16(c)), dtype=torch.uint8, device=device)[:, :c]
+
+
+def fp8_cast(x: torch.Tensor, scale: torch.Tensor, gran: int, fmt: int, flags: int = 0,
+             out: torch.Tensor | None = None) -> torch.Tensor:
+    rows, cols, ld = _mat(x, 2)
+    if out is None:
+        out = _alloc_q(rows, cols, flags, x.device)
+    _, _, ld_out = _mat(out, 1)
+    _check(load_library().fp8_cast(_ptr(x), rows, cols, ld, _ptr(scale), gran, fmt, flags, _ptr(out), ld_out, _stream()))
+    return out
+
+
+def fp8_quantize(x: torch.Tensor, gran: int, fmt: int, flags: int = 0, out: torch.Tensor | None = None,
+                 scale_out: torch.Tensor | None = None):
+    rows, cols, ld = _mat(x, 2)
+    if out is None:
+        out = _alloc_q(rows, cols, flags, x.device)
+    if scale_out is None:
+        scale_out = torch.empty(_groups(gran, rows, cols), dtype=torch.float32, device=x.device)
+    _, _, ld_out = _mat(out, 1)
+    _check(load_library().fp8_quantize(_ptr(x), rows, cols, ld, gran, fmt, flags, _ptr(out), ld_out,
+                                       _ptr(scale_out), _stream()))
+    return out, scale_out
+
+
+def fp8_scaled_mm(a: torch.Tensor, fmt_a: int, scale_a: torch.Tensor, gran_a: int,
+                  b: torch.Tensor, fmt_b: int, scale_b: torch.Tensor, gran_b: int,
+                  flags: int = 0, out: torch.Tensor | None = None) -> torch.Tensor:
+    M, K, lda = _mat(a, 1)
+    N, Kb, ldb = _mat(b, 1)
+    assert K == Kb, (a.shape, b.shape)
+    if out is None:
+        dt = torch.float32 if flags & FP8_OUT_FP32 else torch.bfloat16
+        pad = 4 if flags & FP8_OUT_FP32 else 8
+        out = torch.empty((M, (N + pad - 1) // pad * pad), dtype=dt, device=a.device)[:, :N]
+    _, _, ld_out = _mat(out, out.element_size())
+    _check(load_library().fp8_scaled_mm(_ptr(a), lda, fmt_a, _ptr(scale_a), gran_a, _ptr(b), ldb, fmt_b,
+                                        _ptr(scale_b), gran_b, M, N, K, _ptr(out), ld_out, flags, _stream()))
+    return out
+
+
+def fp8_linear_workspace_bytes(M: int, K: int, N: int, recipe: Recipe, bwd: bool) -> int:
+    r = recipe.c()
+    n = load_library().fp8_linear_workspace_bytes(M, K, N, C.byref(r), int(bwd))
+    if n == 0:
+        raise Fp8Error(-2, fp8_last_error())
+    return int(n)
+
+
+def fp8_linear_fwd(x: torch.Tensor, w: torch.Tensor, recipe: Recipe, y: torch.Tensor | None = None,
+                   workspace: torch.Tensor | None = None) -> torch.Tensor:
+    M, K, ldx = _mat(x, 2)
+    N, Kw, ldw = _mat(w, 2)
+    assert K == Kw and ldx == K and ldw == K, "x and w must be dense [M,K] / [N,K]"
+    if workspace is None:
+        workspace = torch.empty(fp8_linear_workspace_bytes(M, K, N, recipe, False), dtype=torch.uint8, device=x.device)
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    r = recipe.c()
+    _check(load_library().fp8_linear_fwd(_ptr(x), _ptr(w), M, K, N, C.byref(r), _ptr(y), _ptr(workspace),
+                                         workspace.numel(), _stream()))
+    return y
+
+
+def fp8_linear_bwd(dy: torch.Tensor, x: torch.Tensor, w: torch.Tensor, recipe: Recipe,
+                   dx: torch.Tensor | None = None, dw: torch.Tensor | None = None,
+                   workspace: torch.Tensor | None = None, need_dx: bool = True, need_dw: bool = True):
+    M, N, _ = _mat(dy, 2)
+    K = x.shape[1]
+    assert x.shape == (M, K) and w.shape == (N, K) and dy.is_contiguous() and x.is_contiguous() and w.is_contiguous()
+    if workspace is None:
+        workspace = torch.empty(fp8_linear_workspace_bytes(M, K, N, recipe, True), dtype=torch.uint8, device=x.device)
+    if dx is None and need_dx:
+        dx = torch.empty((M, K), dtype=torch.bfloat16, device=x.device)
+    if dw is None and need_dw:
+        dw = torch.empty((N, K), dtype=torch.bfloat16, device=x.device)
+    r = recipe.c()
+    _check(load_library().fp8_linear_bwd(_ptr(dy), _ptr(x), _ptr(w), M, K, N, C.byref(r), _ptr(dx), _ptr(dw),
+                                         _ptr(workspace), workspace.numel(), _stream()))
+    return dx, dw

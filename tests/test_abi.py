@@ -1,0 +1,95 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2507_16099_amd as fp8
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "fp8mi355.h")
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(fp8_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = fp8.load_library()
+    names = _declared()
+    assert {"fp8_amax", "fp8_scale", "fp8_cast", "fp8_scaled_mm", "fp8_linear_fwd", "fp8_linear_bwd",
+            "fp8_quantize", "fp8_linear_workspace_bytes", "fp8_last_error", "fp8_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert "gfx950" in fp8.fp8_version()
+
+
+def test_binding_has_the_same_names():
+    for n in _declared():
+        assert callable(getattr(fp8, n)), n
+
+
+def test_enum_values_match_header():
+    src = open(HEADER).read()
+    for name in ("FP8_E4M3FN", "FP8_E5M2", "FP8_TENSOR", "FP8_ROW", "FP8_COL", "FP8_POW2_SCALE",
+                 "FP8_TRANSPOSE_OUT", "FP8_OUT_FP32"):
+        m = re.search(name + r"\s*=\s*(-?\d+)", src)
+        assert m and int(m.group(1)) == getattr(fp8, name), name
+
+
+def test_argument_errors_are_reported_without_a_gpu():
+    L = fp8.load_library()
+    buf = (C.c_char * 4096)()
+    p = C.addressof(buf)
+    p16 = (p + 15) // 16 * 16
+    # NULL input
+    assert L.fp8_amax(None, 4, 8, 8, 0, p16, None) == -1
+    assert "NULL" in fp8.fp8_last_error()
+    # unknown granularity / format / flag bits
+    assert L.fp8_amax(p16, 4, 8, 8, 7, p16, None) == -3
+    assert L.fp8_scale(p16, 4, 9, 0, p16, None) == -3
+    assert L.fp8_cast(p16, 4, 8, 8, p16, 0, 0, 64, p16, 16, None) == -3
+    # shapes
+    assert L.fp8_amax(p16, -1, 8, 8, 0, p16, None) == -2
+    assert L.fp8_amax(p16, 4, 16, 8, 0, p16, None) == -2            # ld < cols
+    assert L.fp8_scaled_mm(p16, 16, 0, p16, 0, p16, 16, 0, p16, 0, 4, 4, 8, p16, 8, 0, None) == -2   # K % 16
+    # alignment
+    assert L.fp8_amax(p16 + 2, 4, 8, 8, 0, p16, None) == -4
+    assert L.fp8_amax(p16, 4, 8, 12, 0, p16, None) == -4            # ld % 8
+    assert L.fp8_cast(p16, 4, 16, 16, p16, 0, 0, 0, p16, 24, None) == -4   # ld_out % 16
+    assert fp8.fp8_last_error() != ""
+    # recipe checks and workspace size
+    r = fp8.Recipe(gran=fp8.FP8_COL).c()
+    assert L.fp8_linear_workspace_bytes(64, 64, 64, C.byref(r), 0) == 0
+    r = fp8.Recipe(gran=fp8.FP8_ROW).c()
+    n = L.fp8_linear_workspace_bytes(64, 128, 32, C.byref(r), 0)
+    assert n >= 64 * 128 + 32 * 128 + 4 * (64 + 32)
+    nb = L.fp8_linear_workspace_bytes(64, 128, 32, C.byref(r), 1)
+    assert nb >= 2 * 64 * 32 + 128 * 32 + 128 * 64
+    assert L.fp8_linear_fwd(p16, p16, 64, 128, 32, C.byref(r), p16, p16, 16, None) in (-4, -5)
+    assert L.fp8_linear_fwd(p16, p16, 64, 120, 32, C.byref(r), p16, p16, 1 << 20, None) == -2
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    import paper_2507_16099_amd.fp8 as mod
+    monkeypatch.setattr(mod, "_lib", None)
+    monkeypatch.setattr(mod, "_LIB_PATH", "/nonexistent/libfp8mi355.so")
+    with pytest.raises(ImportError):
+        mod.load_library()
+
+
+def test_product_does_not_reach_the_oracle():
+    """No file of the GPU package mentions the oracle, and vice versa."""
+    pkg = os.path.join(ROOT, "paper_2507_16099_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                assert "oracle" not in open(os.path.join(dirpath, f)).read().lower(), f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            txt = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2507_16099_amd" not in txt and "fp8mi355" not in txt, f

@@ -1,0 +1,131 @@
+"""GPU parity: scaled FP8 GEMM vs the CPU oracle.
+
+Tolerance: the matrix cores sum the products in an order of their own, so the
+result is compared by relative Frobenius error <= 1e-3 - the bfloat16 output
+against the oracle's fp32 result rounded to bfloat16 by the oracle, the fp32
+output against the oracle's fp32 result.  Where every partial sum is exactly
+representable (small integers, power-of-two scales) the results must be
+identical bit for bit, which catches any layout or indexing mistake."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import synthetic_inputs as si
+from oracle import fp8_oracle as orc
+from tests.gpu_util import dev_f32, dev_u8, host_bf16_bits, host_f32
+
+pytestmark = pytest.mark.gpu
+
+import paper_2507_16099_amd as fp8  # noqa: E402
+
+TOL = 1e-3
+
+
+@pytest.fixture(params=["0", "1"], ids=["tile128", "tile256"])
+def variant(request):
+    old = os.environ.get("FP8MI355_GEMM_VARIANT")
+    os.environ["FP8MI355_GEMM_VARIANT"] = request.param
+    yield request.param
+    if old is None:
+        os.environ.pop("FP8MI355_GEMM_VARIANT", None)
+    else:
+        os.environ["FP8MI355_GEMM_VARIANT"] = old
+
+
+def _rand_codes(shape, fmt, rng, emax_drop=2):
+    """Random finite codes, magnitudes kept a few binades under the top."""
+    mb = 3 if fmt == orc.E4M3FN else 2
+    top = (0x7E if fmt == orc.E4M3FN else 0x7B) - (emax_drop << mb)
+    c = rng.integers(0, top + 1, size=shape).astype(np.uint8)
+    return c | (rng.integers(0, 2, size=shape).astype(np.uint8) << 7)
+
+
+def _run(a, fa, sa, ga, b, fb, sb, gb, flags=0, lda=None, ldb=None):
+    out = fp8.fp8_scaled_mm(dev_u8(a, lda), fa, dev_f32(sa), ga, dev_u8(b, ldb), fb, dev_f32(sb), gb, flags)
+    torch.cuda.synchronize()
+    return out
+
+
+SHAPES = [(16, 16, 128), (1, 1, 16), (33, 17, 256), (128, 128, 128), (200, 300, 400), (256, 512, 512),
+          (257, 129, 144), (500, 70, 1040), (64, 1000, 2048)]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_exact_on_small_integers(variant, M, N, K):
+    rng = np.random.default_rng(M * 7 + N)
+    ai = rng.integers(-2, 3, size=(M, K))
+    bi = rng.integers(-2, 3, size=(N, K))
+    for fa, fb in ((orc.E4M3FN, orc.E4M3FN), (orc.E5M2, orc.E4M3FN), (orc.E4M3FN, orc.E5M2), (orc.E5M2, orc.E5M2)):
+        a = orc.encode_array((ai * 0.5).astype(np.float32), fa)
+        b = orc.encode_array((bi * 4.0).astype(np.float32), fb)
+        sa = (2.0 ** rng.integers(-3, 4, size=M)).astype(np.float32)
+        sb = (2.0 ** rng.integers(-3, 4, size=N)).astype(np.float32)
+        want = orc.scaled_mm(a, fa, sa, orc.ROW, b, fb, sb, orc.ROW)
+        exact = (ai @ bi.T) * 2.0 / sa[:, None] / sb[None, :]
+        assert (want.out32 == exact.astype(np.float32)).all()
+        got32 = host_f32(_run(a, fa, sa, fp8.FP8_ROW, b, fb, sb, fp8.FP8_ROW, fp8.FP8_OUT_FP32))
+        assert (got32 == want.out32).all(), (M, N, K, fa, fb, np.argwhere(got32 != want.out32)[:4])
+        got16 = host_bf16_bits(_run(a, fa, sa, fp8.FP8_ROW, b, fb, sb, fp8.FP8_ROW))
+        assert (got16 == want.out16).all(), (M, N, K, fa, fb)
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+@pytest.mark.parametrize("ga,gb", [(orc.TENSOR, orc.TENSOR), (orc.ROW, orc.ROW), (orc.ROW, orc.TENSOR), (orc.TENSOR, orc.ROW)])
+def test_random_codes_within_tolerance(variant, M, N, K, ga, gb):
+    rng = np.random.default_rng(M + 3 * N + K)
+    for fa, fb in ((orc.E4M3FN, orc.E4M3FN), (orc.E5M2, orc.E4M3FN)):
+        a, b = _rand_codes((M, K), fa, rng), _rand_codes((N, K), fb, rng)
+        sa = rng.uniform(0.5, 300, 1 if ga == orc.TENSOR else M).astype(np.float32)
+        sb = rng.uniform(0.5, 300, 1 if gb == orc.TENSOR else N).astype(np.float32)
+        want = orc.scaled_mm(a, fa, sa, ga, b, fb, sb, gb)
+        got32 = host_f32(_run(a, fa, sa, ga, b, fb, sb, gb, fp8.FP8_OUT_FP32))
+        got16 = si.bf16_bits_to_f32(host_bf16_bits(_run(a, fa, sa, ga, b, fb, sb, gb)))
+        e32 = orc.rel_frobenius(got32, want.out32)
+        e16 = orc.rel_frobenius(got16, si.bf16_bits_to_f32(want.out16))
+        assert e32 <= TOL and e16 <= TOL, (M, N, K, fa, fb, e32, e16)
+        # and close to the binary64 shadow (the quantity both sides approximate)
+        assert orc.rel_frobenius(got32, want.acc64) <= 5e-5
+
+
+def test_padded_leading_dimensions_and_output_view(variant):
+    rng = np.random.default_rng(3)
+    M, N, K = 70, 90, 160
+    a, b = _rand_codes((M, K), orc.E4M3FN, rng), _rand_codes((N, K), orc.E4M3FN, rng)
+    sa, sb = np.array([3.0], np.float32), np.array([0.25], np.float32)
+    want = orc.scaled_mm(a, orc.E4M3FN, sa, orc.TENSOR, b, orc.E4M3FN, sb, orc.TENSOR)
+    out = torch.full((M, 128), -7.0, dtype=torch.float32, device="cuda")
+    fp8.fp8_scaled_mm(dev_u8(a, 256), 0, dev_f32(sa), 0, dev_u8(b, 192), 0, dev_f32(sb), 0, fp8.FP8_OUT_FP32, out=out[:, :N])
+    got = host_f32(out)
+    assert orc.rel_frobenius(got[:, :N], want.out32) <= 1e-5
+    assert (got[:, N:] == -7.0).all()          # nothing written outside the view
+
+
+def test_zero_k_and_empty():
+    a = torch.empty((4, 0), dtype=torch.uint8, device="cuda")
+    b = torch.empty((6, 0), dtype=torch.uint8, device="cuda")
+    s = dev_f32(np.array([2.0], np.float32))
+    out = fp8.fp8_scaled_mm(a, 0, s, 0, b, 0, s, 0, fp8.FP8_OUT_FP32)
+    assert (host_f32(out) == 0).all()
+    e = fp8.fp8_scaled_mm(torch.empty((0, 32), dtype=torch.uint8, device="cuda"), 0, s, 0,
+                          torch.empty((5, 32), dtype=torch.uint8, device="cuda"), 0, s, 0)
+    assert e.shape == (0, 5)
+
+
+def test_full_size_llama_ffn_forward_gemm_sampled_rows():
+    """Benchmark shape (M=16384, K=4096, N=14336) in the launch configuration
+    the benchmark times; the oracle recomputes a stratified sample of output
+    rows over all N columns and the full contraction."""
+    wl = si.WORKLOADS[si.BENCH_WORKLOAD]
+    xq, sx = orc.quantize(wl.x(), orc.ROW, orc.E4M3FN)
+    wq, sw = orc.quantize(wl.w(), orc.ROW, orc.E4M3FN)
+    rows = si.stratified_rows(wl.M, 48)
+    want = orc.scaled_mm(xq, orc.E4M3FN, sx, orc.ROW, wq, orc.E4M3FN, sw, orc.ROW, rows)
+    got = fp8.fp8_scaled_mm(dev_u8(xq), 0, dev_f32(sx), fp8.FP8_ROW, dev_u8(wq), 0, dev_f32(sw), fp8.FP8_ROW)
+    idx = torch.from_numpy(rows).cuda()
+    g = si.bf16_bits_to_f32(host_bf16_bits(got[idx]))
+    err = orc.rel_frobenius(g, si.bf16_bits_to_f32(want.out16))
+    assert err <= TOL, err
+    frac_identical = float((host_bf16_bits(got[idx]) == want.out16).mean())
+    assert frac_identical > 0.97, frac_identical

@@ -1,0 +1,132 @@
+"""GPU parity: fp8 linear forward / backward vs the CPU oracle, through the
+C ABI entry points fp8_linear_fwd and fp8_linear_bwd."""
+import numpy as np
+import pytest
+import torch
+
+import synthetic_inputs as si
+from oracle import fp8_oracle as orc
+from tests.gpu_util import dev_bf16, host_bf16_bits
+
+pytestmark = pytest.mark.gpu
+
+import paper_2507_16099_amd as fp8  # noqa: E402
+
+TOL = 1e-3
+
+
+def _recipes(wl: si.Workload):
+    gran = orc.ROW if wl.recipe == si.ROWWISE else orc.TENSOR
+    o = orc.Recipe(gran=gran, pow2=wl.pow2)
+    g = fp8.Recipe(gran=fp8.FP8_ROW if gran == orc.ROW else fp8.FP8_TENSOR,
+                   flags=fp8.FP8_POW2_SCALE if wl.pow2 else 0)
+    return o, g
+
+
+def _cmp(got_t: torch.Tensor, want: orc.MMResult, rows=None, min_identical=0.97):
+    g = got_t if rows is None else got_t[torch.from_numpy(rows).cuda()]
+    gb = host_bf16_bits(g)
+    err = orc.rel_frobenius(si.bf16_bits_to_f32(gb), si.bf16_bits_to_f32(want.out16))
+    assert err <= TOL, err
+    ident = float((gb == want.out16).mean())
+    assert ident >= min_identical, ident
+    return err, ident
+
+
+def test_config1_tensorwise_forward_full_matrix():
+    wl = si.WORKLOADS["c1_tensorwise_fwd_256x512x512"]
+    x, w = wl.x(), wl.w()
+    o, g = _recipes(wl)
+    y = fp8.fp8_linear_fwd(dev_bf16(x), dev_bf16(w), g)
+    want, _, _ = orc.linear_fwd(x, w, o)
+    _cmp(y, want)
+
+
+SMALL = [(384, 256, 512), (208, 176, 272), (16, 16, 16), (1024, 384, 640)]
+
+
+@pytest.mark.parametrize("M,K,N", SMALL)
+@pytest.mark.parametrize("base", ["c2_llama3_8b_ffn_rowwise", "c3_llama3_8b_qkv_tensorwise",
+                                  "c4_llama3_70b_up_rowwise_pow2"])
+def test_fwd_bwd_small_shapes(M, K, N, base):
+    wl = si.scaled_down(si.WORKLOADS[base], M, K, N)
+    x, w, dy = wl.x(), wl.w(), wl.dy()
+    o, g = _recipes(wl)
+    xd, wd, dyd = dev_bf16(x), dev_bf16(w), dev_bf16(dy)
+    y = fp8.fp8_linear_fwd(xd, wd, g)
+    dx, dw = fp8.fp8_linear_bwd(dyd, xd, wd, g)
+    _cmp(y, orc.linear_fwd(x, w, o)[0])
+    _cmp(dx, orc.linear_bwd_dx(dy, w, o)[0])
+    _cmp(dw, orc.linear_bwd_dw(dy, x, o)[0])
+    # dx only / dw only give the same answers
+    dx2, none = fp8.fp8_linear_bwd(dyd, xd, wd, g, need_dw=False)
+    none2, dw2 = fp8.fp8_linear_bwd(dyd, xd, wd, g, need_dx=False)
+    assert none is None and none2 is None
+    assert torch.equal(dx2.view(torch.int16), dx.view(torch.int16))
+    assert torch.equal(dw2.view(torch.int16), dw.view(torch.int16))
+
+
+def test_exact_integer_linear_with_pow2_scales():
+    rng = np.random.default_rng(52)
+    M, K, N = 256, 384, 128
+    xi, wi, gi = (rng.integers(-3, 4, size=s) for s in ((M, K), (N, K), (M, N)))
+    xi[:, 0] = 4; xi[0, :] = 4; wi[:, 0] = 4; wi[0, :] = 4; gi[:, 0] = 4; gi[0, :] = 4
+    x, w, dy = (si.f32_to_bf16_bits(v.astype(np.float32)) for v in (xi, wi, gi))
+    xd, wd, dyd = dev_bf16(x), dev_bf16(w), dev_bf16(dy)
+    for gran in (fp8.FP8_TENSOR, fp8.FP8_ROW):
+        r = fp8.Recipe(gran=gran, flags=fp8.FP8_POW2_SCALE)
+        y = fp8.fp8_linear_fwd(xd, wd, r).float().cpu().numpy()
+        dx, dw = fp8.fp8_linear_bwd(dyd, xd, wd, r)
+        assert (y == (xi @ wi.T)).all()
+        assert (dx.float().cpu().numpy() == (gi @ wi)).all()
+        assert (dw.float().cpu().numpy() == (gi.T @ xi)).all()
+
+
+def test_outlier_workload_rowwise_vs_tensorwise():
+    """Outlier-heavy activations (Student-t with hot columns) at reduced size:
+    parity for both recipes, and the paper's Appendix A observation that
+    tensorwise scaling loses more to underflow than rowwise."""
+    errs = {}
+    for name in ("c5_outlier_rowwise", "c5_outlier_tensorwise"):
+        wl = si.scaled_down(si.WORKLOADS[name], 512, 1024, 768)
+        x, w = wl.x(), wl.w()
+        o, g = _recipes(wl)
+        y = fp8.fp8_linear_fwd(dev_bf16(x), dev_bf16(w), g)
+        want, xo, _ = orc.linear_fwd(x, w, o)
+        _cmp(y, want, min_identical=0.95)
+        ref = orc.bf16_mm_f64(x, w)
+        errs[name] = orc.rel_frobenius(si.bf16_bits_to_f32(host_bf16_bits(y)), ref)
+    assert errs["c5_outlier_rowwise"] < errs["c5_outlier_tensorwise"]
+
+
+def test_workspace_too_small_and_bad_shapes_are_rejected():
+    r = fp8.Recipe(gran=fp8.FP8_ROW)
+    x = torch.zeros((32, 64), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((48, 64), dtype=torch.bfloat16, device="cuda")
+    need = fp8.fp8_linear_workspace_bytes(32, 64, 48, r, False)
+    ws = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(fp8.Fp8Error) as ei:
+        fp8.fp8_linear_fwd(x, w, r, workspace=ws)
+    assert ei.value.code == -5
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_linear_workspace_bytes(32, 60, 48, r, False)      # K not a multiple of 16
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_linear_workspace_bytes(40, 64, 48, r, True)       # M not a multiple of 16 in backward
+
+
+def test_full_size_llama_ffn_fwd_bwd_sampled():
+    """The benchmark workload end to end (rowwise, M=16384, K=4096, N=14336):
+    forward and both backward products, each checked on a stratified sample
+    of output rows that the oracle recomputes from its own quantized operands."""
+    wl = si.WORKLOADS[si.BENCH_WORKLOAD]
+    x, w, dy = wl.x(), wl.w(), wl.dy()
+    o, g = _recipes(wl)
+    xd, wd, dyd = dev_bf16(x), dev_bf16(w), dev_bf16(dy)
+    y = fp8.fp8_linear_fwd(xd, wd, g)
+    dx, dw = fp8.fp8_linear_bwd(dyd, xd, wd, g)
+    torch.cuda.synchronize()
+    rows_m = si.stratified_rows(wl.M, 24)
+    rows_n = si.stratified_rows(wl.N, 24)
+    print("fwd", _cmp(y, orc.linear_fwd(x, w, o, rows_m)[0], rows_m), flush=True)
+    print("dx", _cmp(dx, orc.linear_bwd_dx(dy, w, o, rows_m)[0], rows_m), flush=True)
+    print("dw", _cmp(dw, orc.linear_bwd_dw(dy, x, o, rows_n)[0], rows_n), flush=True)
