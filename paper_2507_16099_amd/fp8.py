@@ -108,6 +108,8 @@ def _mat(t: torch.Tensor, itemsize: int):
     """(rows, cols, ld) of a 2-D tensor whose last dimension is contiguous."""
     assert t.is_cuda and t.dim() == 2 and t.element_size() == itemsize, (t.shape, t.dtype, t.device)
     assert t.shape[1] <= 1 or t.stride(1) == 1, "last dimension must be contiguous"
+    if t.numel() == 0:
+        return t.shape[0], t.shape[1], (t.shape[1] + 15) // 16 * 16
     ld = t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
     return t.shape[0], t.shape[1], ld
 
