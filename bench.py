@@ -53,7 +53,7 @@ def main() -> int:
     ap.add_argument("--workload", default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-legs", action="store_true")
-    ap.add_argument("--cpu-sample-rows", type=int, default=192)
+    ap.add_argument("--cpu-sample-rows", type=int, default=2048)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
