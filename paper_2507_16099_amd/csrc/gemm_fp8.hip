@@ -11,10 +11,13 @@
 //     16-byte chunks; chunk c of a row is stored at chunk position c ^ key(row)
 //     so that the 128-bit LDS reads of one MFMA operand (16 rows, same logical
 //     chunk) fall into different banks.
-//   - One MFMA takes 16 rows x 128 K-bytes of each operand: lane l supplies the
-//     32 bytes (chunks 2*(l/16) and 2*(l/16)+1) of row l%16.  The assignment of
-//     K bytes to lanes is the same for both operands, which is all a dot
-//     product needs.
+//   - One MFMA takes 16 rows x 128 K-bytes of each operand: lane l supplies 32
+//     bytes of row l%16, here chunks l/16 and l/16 + 4.  The assignment of K
+//     bytes to lanes is the same for both operands, which is all a dot product
+//     needs; this one makes every 64-lane 128-bit LDS read touch each of the
+//     16 bank groups (16 bytes wide, 256-byte wrap) exactly four times, the
+//     conflict-free pattern (chunks 2*(l/16), 2*(l/16)+1 would use only half
+//     of the bank groups and run at half the LDS rate).
 //   - The B tile is the FIRST MFMA operand and the A tile the second, so a lane
 //     ends up with accumulators for one output row m and several n.  The rows
 //     of a 64-wide B group are dealt to the four MFMA tiles such that lane l
@@ -114,7 +117,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_tn_kernel(
 
     // ---- LDS -> MFMA operands
     const int key = lane & 7;
-    const int off_lo = ((2 * (lane >> 4)) ^ key) << 4, off_hi = ((2 * (lane >> 4) + 1) ^ key) << 4;
+    const int off_lo = ((lane >> 4) ^ key) << 4, off_hi = (((lane >> 4) + 4) ^ key) << 4;
     const int a_row_off = (wm0 + (lane & 15)) * BK;
     const int b_row_off = (wn0 + 16 * ((lane & 15) >> 2) + (lane & 3)) * BK;
 
@@ -229,21 +232,25 @@ template <int FA, int FB, bool OUT_F32>
 static hipError_t launch_fmt(int variant, const uint8_t* a, int64_t lda, const float* sa, int row_a,
                              const uint8_t* b, int64_t ldb, const float* sb, int row_b, int M, int N, int K,
                              void* out, int64_t ld_out, hipStream_t st) {
-    if (variant == 1)
+    if (variant == 2)
+        return launch_variant<256, 256, 2, 2, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
+    if (variant == 1 || variant == 3)
         return launch_variant<256, 256, 2, 4, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
     return launch_variant<128, 128, 2, 2, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
 }
 
-// Tile choice: large problems take the 256 x 256 tile, small ones the
-// 128 x 128 tile (more workgroups).  FP8MI355_GEMM_VARIANT=0|1 overrides
-// (tuning and test aid).
+// Kernel choice: problems with at least one 256 x 256 tile per CU take the
+// software-pipelined kernel (variant 3), smaller ones the 128 x 128 tile of
+// this file (more workgroups).  FP8MI355_GEMM_VARIANT=0..3 overrides (tuning
+// and test aid): 0 = 128x128 / 4 waves, 1 = 256x256 / 8 waves, 2 = 256x256 /
+// 4 waves (all register-staged), 3 = pipelined.
 static int pick_variant(int64_t M, int64_t N) {
     if (const char* e = std::getenv("FP8MI355_GEMM_VARIANT")) {
         const int v = std::atoi(e);
-        if (v == 0 || v == 1) return v;
+        if (v >= 0 && v <= 3) return v;
     }
     const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
-    return tiles256 >= 256 ? 1 : 0;
+    return tiles256 >= 256 ? 3 : 0;
 }
 
 hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
@@ -252,6 +259,9 @@ hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float
                            hipStream_t st) {
     if (M == 0 || N == 0) return hipSuccess;
     const int v = pick_variant(M, N);
+    if (v == 3 && gemm_fp8_pipelined_supported(lda, ldb))   // else: fall through to the 256 x 256 register-staged kernel
+        return launch_gemm_fp8_pipelined(a, lda, fmt_a, scale_a, row_a, b, ldb, fmt_b, scale_b, row_b, M, N, K, out,
+                                         ld_out, out_f32, st);
     const int m = (int)M, n = (int)N, k = (int)K;
 #define FP8K_GEMM(FA_, FB_)                                                                                     \
     if (fmt_a == FA_ && fmt_b == FB_)                                                                           \

@@ -31,4 +31,11 @@ hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float
                            int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
                            hipStream_t st);
 
+// 256 x 256 software-pipelined kernel (direct-to-LDS loads); same contract.
+bool gemm_fp8_pipelined_supported(int64_t lda, int64_t ldb);
+hipError_t launch_gemm_fp8_pipelined(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
+                                     const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int row_b,
+                                     int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
+                                     hipStream_t st);
+
 }  // namespace fp8k

@@ -23,7 +23,7 @@ import paper_2507_16099_amd as fp8  # noqa: E402
 TOL = 1e-3
 
 
-@pytest.fixture(params=["0", "1"], ids=["tile128", "tile256"])
+@pytest.fixture(params=["0", "1", "3"], ids=["tile128", "tile256", "pipelined"])
 def variant(request):
     old = os.environ.get("FP8MI355_GEMM_VARIANT")
     os.environ["FP8MI355_GEMM_VARIANT"] = request.param
