@@ -11,8 +11,8 @@
 //   - Global -> LDS goes through buffer_load_dwordx4 ... lds (no staging
 //     registers): one wave instruction fills 1024 contiguous LDS bytes = 8 rows
 //     of 128 K-bytes.  Lane l fills (row l/8, chunk slot l%8) and therefore
-//     fetches logical 16-byte chunk (l%8) ^ (row & 7) of that row: the XOR
-//     swizzle is applied on the global side.  Rows past M / N are cut off by
+//     fetches logical 16-byte chunk (l%8) ^ key(row) of that row, key(row) =
+//     (row >> 1) & 7: the XOR swizzle is applied on the global side.  Rows past M / N are cut off by
 //     the buffer descriptor's size (the hardware returns zeros), chunks past K
 //     by pointing the lane's offset outside the descriptor.
 //   - Two LDS stages of 64 KB.  The loads of step k+2 are issued in the middle
@@ -21,8 +21,12 @@
 //     of latency cover.
 //   - LDS -> registers in K halves: a 32x32x64 MFMA takes 32 rows x 64 bytes,
 //     lane l supplying chunks {h, h+2} (h = l/32) of the half for row l%32.
-//     Both operands use the same assignment.  With key = row & 7 every 64-lane
-//     128-bit read touches each of the 16 bank groups four times (no conflict).
+//     Both operands use the same assignment.  A 64-lane 128-bit LDS read is
+//     served as two halves of 32 lanes, and within a half each of the 16 bank
+//     groups (16 bytes wide, 256-byte wrap) may be hit twice: with key(row) =
+//     (row >> 1) & 7 the 32 rows of a fragment give every (row parity, chunk
+//     slot) pair exactly twice, so the reads run at the full 256 B/clk
+//     (key = row & 7 measures at half of that).
 //     Two register sets alternate: while the matrix cores work on one K half,
 //     the fragments of the next half are read.
 //   - The B tile is the first MFMA operand, A the second: a lane's accumulators
@@ -42,6 +46,7 @@
 namespace fp8k {
 
 typedef int v4i_t __attribute__((ext_vector_type(4)));
+typedef unsigned v4u_t __attribute__((ext_vector_type(4)));
 typedef int v8i_t __attribute__((ext_vector_type(8)));
 typedef float v16f_t __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -107,7 +112,9 @@ __global__ __launch_bounds__(pl::NT) void gemm_fp8_pipelined_kernel(
 
     // wave w fills row groups w, w+4, ... (8 rows each) of both operand tiles
     const int lrow = lane >> 3;                         // row inside the 8-row group
-    const int lchunk = (lane & 7) ^ lrow;               // logical chunk this lane fetches (key = row & 7)
+    // logical chunk this lane fetches: slot ^ key(row), key(row) = (row >> 1) & 7 with
+    // row = 8 * (4 * i + wave) + lrow, i.e. 4 * (wave & 1) + lrow / 2 for every i
+    const int lchunk = (lane & 7) ^ (4 * (wave & 1) + (lrow >> 1));
     const uint32_t va0 = (uint32_t)((wave * 8 + lrow) * (int)lda + lchunk * 16);
     const uint32_t vb0 = (uint32_t)((wave * 8 + lrow) * (int)ldb + lchunk * 16);
     const uint32_t va_step = (uint32_t)(32 * (int)lda), vb_step = (uint32_t)(32 * (int)ldb);
@@ -131,7 +138,7 @@ __global__ __launch_bounds__(pl::NT) void gemm_fp8_pipelined_kernel(
     const int l32 = lane & 31, h = lane >> 5;
     const int perm = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);   // B row for MFMA row index l32
     const int a_row_off = (wm0 + l32) * BK, b_row_off = (wn0 + perm) * BK;
-    const int key_a = l32 & 7, key_b = perm & 7;
+    const int key_a = (l32 >> 1) & 7, key_b = (perm >> 1) & 7;
     // chunk offsets for K half 0: {h, h+2}; half 1 adds 4 to the logical chunk
     int offa[2][2], offb[2][2];
 #pragma unroll
@@ -303,7 +310,9 @@ __global__ __launch_bounds__(pl::NT) void gemm_fp8_pipelined_kernel(
             if (m < M && n < N) {
                 uint16_t* dst = obase + (int64_t)m * ld_out;
                 if (n + 8 <= N) {
-                    *reinterpret_cast<uint4*>(dst) = v;
+                    // streaming store: the output is not read again by this kernel and
+                    // should not push the operand panels out of L2
+                    __builtin_nontemporal_store(v4u_t{v.x, v.y, v.z, v.w}, reinterpret_cast<v4u_t*>(dst));
                 } else {
                     const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
                     for (int e = 0; n + e < N; ++e) dst[e] = (uint16_t)(w4[e >> 1] >> ((e & 1) * 16));
