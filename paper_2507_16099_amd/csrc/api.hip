@@ -63,8 +63,15 @@ int quantize_impl(const void* x, int64_t rows, int64_t cols, int64_t ld, int gra
         if (e == hipSuccess) return FP8_OK;
         if (e != hipErrorNotSupported) return hip_fail(e, "quant_row");
     }
-    // scale_out doubles as the amax buffer: fp8_scale may run in place
-    FP8_TRY(fp8k::launch_amax(x, rows, cols, ld, gran, scale_out, st));
+    // scale_out doubles as the amax buffer: fp8_scale may run in place.  For a
+    // per-column quantization with transposed output, the output buffer itself
+    // (cols x ld_out bytes, overwritten by the cast afterwards) serves as the
+    // scratch matrix of the two-level column amax.
+    hipError_t ea = hipErrorNotSupported;
+    if (gran == FP8_COL && transpose && q_plain == nullptr)
+        ea = fp8k::launch_amax_cols_two_level(x, rows, cols, ld, scale_out, q, (size_t)cols * (size_t)ld_out, st);
+    if (ea == hipErrorNotSupported) ea = fp8k::launch_amax(x, rows, cols, ld, gran, scale_out, st);
+    if (ea != hipSuccess) return hip_fail(ea, "amax");
     FP8_TRY(fp8k::launch_scale(scale_out, n_groups(gran, rows, cols), format, pow2, scale_out, st));
     FP8_TRY(fp8k::launch_cast(x, rows, cols, ld, scale_out, gran, format, transpose, q, ld_out, q_plain, ld_plain, st));
     return FP8_OK;
@@ -165,7 +172,7 @@ static int check_q_out(const char* fn, const uint8_t* q, int64_t rows, int64_t c
         if (!q) return fail(FP8_ERR_NULL, "%s: q_out is NULL", fn);
         if (!aligned(q, 16)) return fail(FP8_ERR_ALIGN, "%s: q_out not 16-byte aligned", fn);
         if (ld_out % 16 != 0) return fail(FP8_ERR_ALIGN, "%s: ld_out=%lld not a multiple of 16", fn, (long long)ld_out);
-        if (transpose && (rows + 127) / 128 > 65535) return fail(FP8_ERR_SHAPE, "%s: too many rows for a transposed cast", fn);
+        if (transpose && (cols + 127) / 128 > 65535) return fail(FP8_ERR_SHAPE, "%s: too many columns for a transposed cast", fn);
     }
     return FP8_OK;
 }
@@ -274,7 +281,7 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
     if (!workspace) return fail(FP8_ERR_NULL, "fp8_linear_bwd: workspace is NULL");
     if (!aligned(dx, 16) || !aligned(dw, 16) || !aligned(workspace, 256))
         return fail(FP8_ERR_ALIGN, "fp8_linear_bwd: dx, dw (16) / workspace (256) misaligned");
-    if ((M + 127) / 128 > 65535 || (N + 127) / 128 > 65535) return fail(FP8_ERR_SHAPE, "fp8_linear_bwd: M or N too large");
+    if ((K + 127) / 128 > 65535 || (N + 127) / 128 > 65535) return fail(FP8_ERR_SHAPE, "fp8_linear_bwd: K or N too large");
     const BwdPlan p = plan_bwd(M, K, N, recipe->gran);
     if (workspace_bytes < p.total)
         return fail(FP8_ERR_WORKSPACE, "fp8_linear_bwd: workspace %zu < %zu bytes", workspace_bytes, p.total);

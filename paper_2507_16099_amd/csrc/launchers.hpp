@@ -11,6 +11,11 @@ hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st);
 hipError_t launch_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran, float* out,
                        hipStream_t st);
 
+// column amax of a tall matrix via a [G, cols] scratch matrix of partial maxima
+// (hipErrorNotSupported: shape does not suit it, use launch_amax)
+hipError_t launch_amax_cols_two_level(const void* x, int64_t rows, int64_t cols, int64_t ld, float* out,
+                                      void* scratch, size_t scratch_bytes, hipStream_t st);
+
 hipError_t launch_scale(const float* amax, int64_t n, int fmt, int flags, float* out, hipStream_t st);
 
 // transpose != 0: q is [cols, rows]; q_plain (optional, transpose only) also

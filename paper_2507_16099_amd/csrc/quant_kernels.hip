@@ -22,6 +22,14 @@ hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st) {
 }
 
 // ---------------------------------------------------------------- amax
+// Atomic max on the bits of a non-negative float.  Thousands of workgroups
+// fold into the same few words; same-address atomics serialise in L2, so a
+// plain load first drops every contribution that cannot raise the value (the
+// stored maximum only grows, hence a stale read is harmless).
+__device__ __forceinline__ void atomic_max_bits(uint32_t* addr, uint32_t bits) {
+    if (bits > __builtin_nontemporal_load(addr)) atomicMax(addr, bits);
+}
+
 // One group of TX threads per row; TY = 256 / TX rows per block.
 // single != 0: every row folds into out[0] with an atomic max (tensorwise
 // amax of a matrix whose rows are not contiguous in memory).
@@ -55,21 +63,29 @@ __global__ __launch_bounds__(256) void amax_rows_kernel(const uint16_t* __restri
         for (int i = 1; i < WPR; ++i) m = part[w0 + i] > m ? part[w0 + i] : m;
     }
     if (r < rows && tx == 0) {
-        if (single) atomicMax(reinterpret_cast<uint32_t*>(out), m << 16);
+        if (single) atomic_max_bits(reinterpret_cast<uint32_t*>(out), m << 16);
         else out[r] = mag_to_float(m);
     }
 }
 
-// Tensorwise amax of a contiguous array of n bfloat16: grid-stride over
-// 128-bit vectors, block reduction, one atomic max per block (out zeroed).
+// Tensorwise amax of a contiguous array of n bfloat16.  A block owns a
+// contiguous chunk of 256 x 8 vectors; every thread issues its eight 128-bit
+// loads back to back (all in flight together), then reduces.  One integer
+// atomic max per block (out zeroed beforehand).
 __global__ __launch_bounds__(256) void amax_flat_kernel(const uint16_t* __restrict__ x, int64_t n,
                                                          float* __restrict__ out) {
     const uint4* xv = reinterpret_cast<const uint4*>(x);
     const int64_t nvec = n >> 3;
-    const int64_t stride = (int64_t)gridDim.x * 256;
+    const int64_t base = (int64_t)blockIdx.x * (256 * 8) + threadIdx.x;
+    uint4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int64_t i = base + j * 256;
+        v[j] = i < nvec ? xv[i] : make_uint4(0, 0, 0, 0);
+    }
     uint32_t acc = 0;
-#pragma unroll 8
-    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < nvec; v += stride) acc = pk_absmax4(acc, xv[v]);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc = pk_absmax4(acc, v[j]);
     if (blockIdx.x == 0)
         for (int64_t c = (nvec << 3) + threadIdx.x; c < n; c += 256) acc = pk_absmax(acc, (uint32_t)x[c]);
     uint32_t m = wave_max_u32<64>(pk_fold(acc));
@@ -79,15 +95,18 @@ __global__ __launch_bounds__(256) void amax_flat_kernel(const uint16_t* __restri
     if (threadIdx.x == 0) {
         m = part[0];
         for (int i = 1; i < 4; ++i) m = part[i] > m ? part[i] : m;
-        atomicMax(reinterpret_cast<uint32_t*>(out), m << 16);
+        atomic_max_bits(reinterpret_cast<uint32_t*>(out), m << 16);
     }
 }
 
-// Column amax: a block owns 512 columns (64 lanes x 8) and rows_per_block rows;
-// its four wavefronts take every fourth row.  out must be zeroed beforehand.
-__global__ __launch_bounds__(256) void amax_cols_kernel(const uint16_t* __restrict__ x, int64_t rows,
-                                                         int64_t cols, int64_t ld,
-                                                         float* __restrict__ out, int64_t rows_per_block) {
+// Column amax: a block of 8 wavefronts owns 512 columns (64 lanes x 8) and
+// rows_per_block rows; wavefront w takes rows w, w+8, ...  out must be zeroed
+// beforehand.
+constexpr int AMAX_COLS_WAVES = 8;
+__global__ __launch_bounds__(AMAX_COLS_WAVES * 64) void amax_cols_kernel(const uint16_t* __restrict__ x, int64_t rows,
+                                                                          int64_t cols, int64_t ld,
+                                                                          float* __restrict__ out,
+                                                                          int64_t rows_per_block) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t c0 = (int64_t)blockIdx.x * 512 + lane * 8;
     const int64_t r_begin = (int64_t)blockIdx.y * rows_per_block;
@@ -96,7 +115,7 @@ __global__ __launch_bounds__(256) void amax_cols_kernel(const uint16_t* __restri
     if (c0 < cols) {
         const uint16_t* p = x + c0;
 #pragma unroll 8
-        for (int64_t r = r_begin + wave; r < r_end; r += 4) {
+        for (int64_t r = r_begin + wave; r < r_end; r += AMAX_COLS_WAVES) {
             const uint4 v = *reinterpret_cast<const uint4*>(p + r * ld);
             acc.x = pk_absmax(acc.x, v.x);
             acc.y = pk_absmax(acc.y, v.y);
@@ -104,12 +123,12 @@ __global__ __launch_bounds__(256) void amax_cols_kernel(const uint16_t* __restri
             acc.w = pk_absmax(acc.w, v.w);
         }
     }
-    __shared__ uint4 part[4][64];
+    __shared__ uint4 part[AMAX_COLS_WAVES][64];
     part[wave][lane] = acc;
     __syncthreads();
     if (wave == 0 && c0 < cols) {
 #pragma unroll
-        for (int w = 1; w < 4; ++w) {
+        for (int w = 1; w < AMAX_COLS_WAVES; ++w) {
             const uint4 o = part[w][lane];
             acc.x = pk_absmax(acc.x, o.x);
             acc.y = pk_absmax(acc.y, o.y);
@@ -117,13 +136,90 @@ __global__ __launch_bounds__(256) void amax_cols_kernel(const uint16_t* __restri
             acc.w = pk_absmax(acc.w, o.w);
         }
         const uint32_t w4[4] = {acc.x, acc.y, acc.z, acc.w};
-        uint32_t* o = reinterpret_cast<uint32_t*>(out);
+        uint32_t* o = reinterpret_cast<uint32_t*>(out) + c0;
+        // current maxima of my eight columns in two loads (stale values are fine:
+        // they only grow), then atomics only where this block can raise them
+        uint32_t cur[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (c0 + 8 <= cols) {
+            const uint4 lo = *reinterpret_cast<const uint4*>(o);
+            const uint4 hi = *reinterpret_cast<const uint4*>(o + 4);
+            cur[0] = lo.x; cur[1] = lo.y; cur[2] = lo.z; cur[3] = lo.w;
+            cur[4] = hi.x; cur[5] = hi.y; cur[6] = hi.z; cur[7] = hi.w;
+        }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const uint32_t mag = (e & 1) ? (w4[e >> 1] >> 16) : (w4[e >> 1] & 0xFFFFu);
-            if (c0 + e < cols && mag) atomicMax(o + c0 + e, mag << 16);
+            const uint32_t bits = ((e & 1) ? (w4[e >> 1] >> 16) : (w4[e >> 1] & 0xFFFFu)) << 16;
+            if (c0 + e < cols && bits > cur[e]) atomicMax(o + e, bits);
         }
     }
+}
+
+// Column maxima, first level, for tall matrices: the matrix is streamed row by
+// row exactly like the rowwise kernels do (a block reads whole rows, 128-bit
+// loads, full lines), every thread keeps the running packed maxima of its own
+// 8 * NV columns, and block b folds rows b, b + G, b + 2G, ...  The result is a
+// [G, cols] matrix of bfloat16 magnitudes (same layout as the input rows) that
+// the second level reduces with amax_cols_kernel.  This replaces thousands of
+// strided 1 KB reads by long sequential ones.
+template <int NV>
+__global__ __launch_bounds__(256) void colmax_partial_kernel(const uint16_t* __restrict__ x, int64_t rows,
+                                                              int64_t cols, int64_t ld,
+                                                              uint16_t* __restrict__ part, int64_t ld_part) {
+    const int64_t nvec = cols >> 3;
+    const int ntail = (int)(cols & 7);
+    uint4 acc[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) acc[j] = make_uint4(0, 0, 0, 0);
+    uint32_t tail = 0;
+    for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
+        const uint16_t* row = x + r * ld;
+        const uint4* rv = reinterpret_cast<const uint4*>(row);
+        uint4 v[NV];
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int64_t vi = threadIdx.x + (int64_t)j * 256;
+            v[j] = vi < nvec ? rv[vi] : make_uint4(0, 0, 0, 0);
+        }
+        if ((int)threadIdx.x < ntail) tail = pk_absmax(tail, (uint32_t)row[(nvec << 3) + threadIdx.x]);
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            acc[j].x = pk_absmax(acc[j].x, v[j].x);
+            acc[j].y = pk_absmax(acc[j].y, v[j].y);
+            acc[j].z = pk_absmax(acc[j].z, v[j].z);
+            acc[j].w = pk_absmax(acc[j].w, v[j].w);
+        }
+    }
+    uint16_t* prow = part + (int64_t)blockIdx.x * ld_part;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int64_t vi = threadIdx.x + (int64_t)j * 256;
+        if (vi < nvec) reinterpret_cast<uint4*>(prow)[vi] = acc[j];
+    }
+    if ((int)threadIdx.x < ntail) prow[(nvec << 3) + threadIdx.x] = (uint16_t)tail;
+}
+
+// Two-level column amax through a scratch matrix (at least G * ld_part
+// bfloat16, 16-byte aligned).  Returns hipErrorNotSupported if the shape does
+// not suit it (few rows, very wide rows): the caller then uses launch_amax.
+hipError_t launch_amax_cols_two_level(const void* x, int64_t rows, int64_t cols, int64_t ld, float* out,
+                                      void* scratch, size_t scratch_bytes, hipStream_t st) {
+    const int64_t nvec = cols / 8;
+    const int64_t ld_part = (cols + 7) / 8 * 8;
+    int64_t G = 1024;
+    while (G > 64 && (size_t)(G * ld_part * 2) > scratch_bytes) G /= 2;
+    if (rows < 8 * G || nvec > 256 * 16 || (size_t)(G * ld_part * 2) > scratch_bytes) return hipErrorNotSupported;
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    uint16_t* part = static_cast<uint16_t*>(scratch);
+#define FP8K_CP(NV) colmax_partial_kernel<NV><<<dim3((unsigned)G), dim3(256), 0, st>>>(xp, rows, cols, ld, part, ld_part)
+    if (nvec <= 256) FP8K_CP(1);
+    else if (nvec <= 512) FP8K_CP(2);
+    else if (nvec <= 1024) FP8K_CP(4);
+    else if (nvec <= 2048) FP8K_CP(8);
+    else FP8K_CP(16);
+#undef FP8K_CP
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_amax(part, G, cols, ld_part, GRAN_COL, out, st);
 }
 
 hipError_t launch_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran, float* out,
@@ -140,7 +236,7 @@ hipError_t launch_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, in
         const int64_t n = rows * cols;
         int64_t blocks = (n / 8 + 256 * 8 - 1) / (256 * 8);
         if (blocks < 1) blocks = 1;
-        if (blocks > 4096) blocks = 4096;
+        if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
         amax_flat_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(xp, n, out);
         return hipGetLastError();
     }
@@ -166,7 +262,7 @@ hipError_t launch_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, in
     int64_t rpb = 256;
     while ((rows + rpb - 1) / rpb > 65535) rpb *= 2;
     dim3 grid((unsigned)((cols + 511) / 512), (unsigned)((rows + rpb - 1) / rpb));
-    amax_cols_kernel<<<grid, dim3(256), 0, st>>>(xp, rows, cols, ld, out, rpb);
+    amax_cols_kernel<<<grid, dim3(AMAX_COLS_WAVES * 64), 0, st>>>(xp, rows, cols, ld, out, rpb);
     return hipGetLastError();
 }
 
@@ -237,23 +333,29 @@ __device__ __forceinline__ void transpose4x4_bytes(uint32_t a, uint32_t b, uint3
     o[3] = __builtin_amdgcn_perm(u1, t1, 0x07060302u);
 }
 
-// Transposing cast.  A block converts a 128 x 128 tile: each thread loads an
-// 8 x 8 sub-block (eight 128-bit loads), converts it, transposes the bytes in
-// registers and parks eight 64-bit column pieces in LDS; the block then
-// streams the tile out as rows of the transposed matrix with 128-bit stores.
+// Transposing cast.  A block converts a TR x 128 tile (TR = 128 or 256 input
+// rows): each thread loads 8 x 8 sub-blocks (eight 128-bit loads each),
+// converts them, transposes the bytes in registers and parks eight 64-bit
+// column pieces in LDS; the block then streams the tile out as rows of the
+// transposed matrix with 128-bit stores (TR contiguous bytes per output row).
 // q_plain != nullptr additionally writes the untransposed codes (the
 // tensorwise recipe needs both layouts of the same tensor in the backward).
-// LDS tile: 128 output rows x 128 bytes; the 8-byte slot index is XORed with
+// LDS tile: 128 output rows x TR bytes; the 8-byte slot index is XORed with
 // 2 * ((row / 8) & 7) so that a wavefront's column pieces spread over banks.
-template <int FMT, int GRAN>
+template <int FMT, int GRAN, int TR>
 __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __restrict__ x, int64_t rows,
                                                               int64_t cols, int64_t ld,
                                                               const float* __restrict__ scale,
                                                               uint8_t* __restrict__ qt, int64_t ld_t,
                                                               uint8_t* __restrict__ q_plain, int64_t ld_plain) {
-    __shared__ __attribute__((aligned(16))) uint2 tile[128 * 16];
+    constexpr int SLOTS = TR / 8;   // 8-byte slots per output row
+    constexpr int PARTS = TR / 16;  // 16-byte parts per output row
+    __shared__ __attribute__((aligned(16))) uint2 tile[128 * SLOTS];
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-    const int64_t r0 = (int64_t)blockIdx.y * 128, c0 = (int64_t)blockIdx.x * 128;
+    // blockIdx.x walks down the input rows: workgroups that run together then
+    // write neighbouring segments of the same output rows (and spread over all
+    // memory channels instead of piling onto the few that one 4 KB window maps to)
+    const int64_t r0 = (int64_t)blockIdx.x * TR, c0 = (int64_t)blockIdx.y * 128;
     const int64_t c = c0 + tx * 8;
 
     float s_col[8];
@@ -264,60 +366,63 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
         for (int e = 0; e < 8; ++e) s_col[e] = (c + e < cols) ? scale[c + e] : 0.0f;
     }
 
-    uint32_t w[8][2];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int64_t r = r0 + ty * 8 + j;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (r < rows) {
-            const uint16_t* src = x + r * ld + c;
-            if (c + 8 <= cols) {
-                v = *reinterpret_cast<const uint4*>(src);
-            } else if (c < cols) {
-                uint32_t t[4] = {0, 0, 0, 0};
-                for (int e = 0; c + e < cols; ++e) t[e >> 1] |= (uint32_t)src[e] << ((e & 1) * 16);
-                v = make_uint4(t[0], t[1], t[2], t[3]);
+    for (int rh = 0; rh < TR / 128; ++rh) {
+        uint32_t w[8][2];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int64_t r = r0 + rh * 128 + ty * 8 + j;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (r < rows) {
+                const uint16_t* src = x + r * ld + c;
+                if (c + 8 <= cols) {
+                    v = *reinterpret_cast<const uint4*>(src);
+                } else if (c < cols) {
+                    uint32_t t[4] = {0, 0, 0, 0};
+                    for (int e = 0; c + e < cols; ++e) t[e >> 1] |= (uint32_t)src[e] << ((e & 1) * 16);
+                    v = make_uint4(t[0], t[1], t[2], t[3]);
+                }
             }
-        }
-        uint2 b;
-        if constexpr (GRAN == GRAN_COL) {
-            b = cast8<FMT>(v, s_col);
-        } else {
-            if constexpr (GRAN == GRAN_ROW) s_t = (r < rows) ? scale[r] : 0.0f;
-            b = cast8<FMT>(v, s_t);
-        }
-        w[j][0] = b.x;
-        w[j][1] = b.y;
-        if (q_plain != nullptr && r < rows) {
-            uint8_t* dst = q_plain + r * ld_plain + c;
-            if (c + 8 <= cols) {
-                *reinterpret_cast<uint2*>(dst) = b;
+            uint2 b;
+            if constexpr (GRAN == GRAN_COL) {
+                b = cast8<FMT>(v, s_col);
             } else {
-                for (int e = 0; c + e < cols; ++e) dst[e] = (uint8_t)((e < 4 ? b.x >> (8 * e) : b.y >> (8 * (e - 4))) & 0xFFu);
+                if constexpr (GRAN == GRAN_ROW) s_t = (r < rows) ? scale[r] : 0.0f;
+                b = cast8<FMT>(v, s_t);
+            }
+            w[j][0] = b.x;
+            w[j][1] = b.y;
+            if (q_plain != nullptr && r < rows) {
+                uint8_t* dst = q_plain + r * ld_plain + c;
+                if (c + 8 <= cols) {
+                    *reinterpret_cast<uint2*>(dst) = b;
+                } else {
+                    for (int e = 0; c + e < cols; ++e) dst[e] = (uint8_t)((e < 4 ? b.x >> (8 * e) : b.y >> (8 * (e - 4))) & 0xFFu);
+                }
             }
         }
-    }
-
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        uint32_t lo[4], hi[4];
-        transpose4x4_bytes(w[0][h], w[1][h], w[2][h], w[3][h], lo);
-        transpose4x4_bytes(w[4][h], w[5][h], w[6][h], w[7][h], hi);
+        for (int h = 0; h < 2; ++h) {
+            uint32_t lo[4], hi[4];
+            transpose4x4_bytes(w[0][h], w[1][h], w[2][h], w[3][h], lo);
+            transpose4x4_bytes(w[4][h], w[5][h], w[6][h], w[7][h], hi);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int cc = tx * 8 + h * 4 + i;  // output row inside the tile
-            tile[cc * 16 + (ty ^ (2 * (tx & 7)))] = make_uint2(lo[i], hi[i]);
+            for (int i = 0; i < 4; ++i) {
+                const int cc = tx * 8 + h * 4 + i;  // output row inside the tile
+                tile[cc * SLOTS + ((rh * 16 + ty) ^ (2 * (tx & 7)))] = make_uint2(lo[i], hi[i]);
+            }
         }
     }
     __syncthreads();
 
     const uint4* tile16 = reinterpret_cast<const uint4*>(tile);
+    constexpr int ROWS_PER_IT = 256 / PARTS;
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int cc = it * 32 + (threadIdx.x >> 3), p = threadIdx.x & 7;
+    for (int it = 0; it < 128 / ROWS_PER_IT; ++it) {
+        const int cc = it * ROWS_PER_IT + (threadIdx.x / PARTS), p = threadIdx.x % PARTS;
         const int64_t oc = c0 + cc, orow = r0 + p * 16;
         if (oc >= cols || orow >= rows) continue;
-        const uint4 v = tile16[cc * 8 + (p ^ ((cc >> 3) & 7))];
+        const uint4 v = tile16[cc * PARTS + (p ^ ((cc >> 3) & 7))];
         uint8_t* dst = qt + oc * ld_t + orow;
         if (orow + 16 <= rows) {
             *reinterpret_cast<uint4*>(dst) = v;
@@ -333,9 +438,11 @@ static hipError_t launch_cast_t(const uint16_t* x, int64_t rows, int64_t cols, i
                                 int transpose, uint8_t* q, int64_t ld_out, uint8_t* q_plain, int64_t ld_plain,
                                 hipStream_t st) {
     if (transpose) {
+        // 128-row tiles measured best (256-row tiles: same on the 470 MB gradient
+        // tensor, slower on the smaller operands)
         const int64_t gx = (cols + 127) / 128, gy = (rows + 127) / 128;
-        if (gy > 65535) return hipErrorInvalidValue;
-        cast_transpose_kernel<FMT, GRAN><<<dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, st>>>(
+        if (gx > 65535) return hipErrorInvalidValue;
+        cast_transpose_kernel<FMT, GRAN, 128><<<dim3((unsigned)gy, (unsigned)gx), dim3(256), 0, st>>>(
             x, rows, cols, ld, scale, q, ld_out, q_plain, ld_plain);
         return hipGetLastError();
     }
