@@ -91,6 +91,29 @@ def test_random_codes_within_tolerance(variant, M, N, K, ga, gb):
         assert orc.rel_frobenius(got32, want.acc64) <= TOL
 
 
+@pytest.mark.parametrize("M,N,K", [(4608, 4608, 384), (4500, 4400, 400), (8192, 2304, 128)])
+def test_many_tiles_per_workgroup_exact(M, N, K):
+    """More 256 x 256 tiles than CUs: the persistent kernel walks several tiles
+    per workgroup (with the next tile's first loads issued during the previous
+    tile's last step).  Exact on small integers, ragged edges included."""
+    rng = np.random.default_rng(M + N + K)
+    ai = rng.integers(-2, 3, size=(M, K))
+    bi = rng.integers(-2, 3, size=(N, K))
+    a = orc.encode_array((ai * 0.5).astype(np.float32), orc.E5M2)
+    b = orc.encode_array((bi * 4.0).astype(np.float32), orc.E4M3FN)
+    sa = (2.0 ** rng.integers(-3, 4, size=M)).astype(np.float32)
+    sb = (2.0 ** rng.integers(-3, 4, size=N)).astype(np.float32)
+    exact = ((ai @ bi.T) * 2.0 / sa[:, None] / sb[None, :]).astype(np.float32)
+    got16 = host_bf16_bits(_run(a, orc.E5M2, sa, fp8.FP8_ROW, b, orc.E4M3FN, sb, fp8.FP8_ROW))
+    assert (got16 == orc.f32_to_bf16(exact)).all()
+    got32 = host_f32(_run(a, orc.E5M2, sa, fp8.FP8_ROW, b, orc.E4M3FN, sb, fp8.FP8_ROW, fp8.FP8_OUT_FP32))
+    assert (got32 == exact).all()
+    # a sample of rows against the oracle proper
+    rows = si.stratified_rows(M, 16)
+    want = orc.scaled_mm(a, orc.E5M2, sa, orc.ROW, b, orc.E4M3FN, sb, orc.ROW, rows)
+    assert (got32[rows] == want.out32).all()
+
+
 def test_padded_leading_dimensions_and_output_view(variant):
     rng = np.random.default_rng(3)
     M, N, K = 70, 90, 160
