@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfp8mi355.so")
-SOURCES = ["quant_kernels.hip", "gemm_fp8.hip", "gemm_fp8_pipelined.hip", "api.hip"]
+SOURCES = ["quant_kernels.hip", "gemm_fp8.hip", "gemm_fp8_pipelined.hip", "gemm_fp8_snake.hip", "api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are disabled on purpose (the compiler would
 # otherwise form v_pk_*_f32 from plain float code)
@@ -25,7 +25,7 @@ def _compile(src: str) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
-    noise = ("is not a recognized feature", "warning generated", "warnings generated", "reserved registers: m0", "lds_dma16", "may not be preserved", "^")
+    noise = ("is not a recognized feature", "warning generated", "warnings generated", "reserved registers: m0", "lds_dma16", "sn_lds_dma16", "may not be preserved", "^")
     err = "\n".join(l for l in r.stderr.splitlines()
                     if l.strip() and not any(n in l for n in noise) and not l.lstrip().startswith((":", "|")) and not l.lstrip()[:1].isdigit())
     if err.strip():

@@ -234,23 +234,24 @@ static hipError_t launch_fmt(int variant, const uint8_t* a, int64_t lda, const f
                              void* out, int64_t ld_out, hipStream_t st) {
     if (variant == 2)
         return launch_variant<256, 256, 2, 2, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
-    if (variant == 1 || variant == 3)
+    if (variant == 1 || variant == 3 || variant == 4)
         return launch_variant<256, 256, 2, 4, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
     return launch_variant<128, 128, 2, 2, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
 }
 
 // Kernel choice: problems with at least one 256 x 256 tile per CU take the
-// software-pipelined kernel (variant 3), smaller ones the 128 x 128 tile of
-// this file (more workgroups).  FP8MI355_GEMM_VARIANT=0..3 overrides (tuning
-// and test aid): 0 = 128x128 / 4 waves, 1 = 256x256 / 8 waves, 2 = 256x256 /
-// 4 waves (all register-staged), 3 = pipelined.
+// 16x16x128 "snake" kernel (variant 4, gemm_fp8_snake.hip), smaller ones the
+// 128 x 128 tile of this file (more workgroups).  FP8MI355_GEMM_VARIANT=0..4
+// overrides (tuning and test aid): 0 = 128x128 / 4 waves, 1 = 256x256 / 8
+// waves, 2 = 256x256 / 4 waves (all register-staged), 3 = pipelined 32x32x64
+// (gemm_fp8_pipelined.hip), 4 = snake.
 static int pick_variant(int64_t M, int64_t N) {
     if (const char* e = std::getenv("FP8MI355_GEMM_VARIANT")) {
         const int v = std::atoi(e);
-        if (v >= 0 && v <= 3) return v;
+        if (v >= 0 && v <= 4) return v;
     }
     const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
-    return tiles256 >= 256 ? 3 : 0;
+    return tiles256 >= 256 ? 4 : 0;
 }
 
 hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
@@ -259,6 +260,9 @@ hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float
                            hipStream_t st) {
     if (M == 0 || N == 0) return hipSuccess;
     const int v = pick_variant(M, N);
+    if (v == 4 && gemm_fp8_pipelined_supported(lda, ldb))
+        return launch_gemm_fp8_snake(a, lda, fmt_a, scale_a, row_a, b, ldb, fmt_b, scale_b, row_b, M, N, K, out, ld_out,
+                                     out_f32, st);
     if (v == 3 && gemm_fp8_pipelined_supported(lda, ldb))   // else: fall through to the 256 x 256 register-staged kernel
         return launch_gemm_fp8_pipelined(a, lda, fmt_a, scale_a, row_a, b, ldb, fmt_b, scale_b, row_b, M, N, K, out,
                                          ld_out, out_f32, st);

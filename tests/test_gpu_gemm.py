@@ -23,7 +23,7 @@ import paper_2507_16099_amd as fp8  # noqa: E402
 TOL = 1e-3
 
 
-@pytest.fixture(params=["0", "1", "3"], ids=["tile128", "tile256", "pipelined"])
+@pytest.fixture(params=["0", "1", "3", "4"], ids=["tile128", "tile256", "pipelined", "snake"])
 def variant(request):
     old = os.environ.get("FP8MI355_GEMM_VARIANT")
     os.environ["FP8MI355_GEMM_VARIANT"] = request.param
