@@ -45,6 +45,20 @@ def _event_time_ms(fn, iters: int, warmup: int, torch) -> float:
     return start.elapsed_time(stop) / iters
 
 
+def _profiled_traffic(workload: str):
+    """HBM bytes per launch of the forward GEMM as measured with rocprofv3 --pmc
+    (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size); kept as a
+    figure in profiles/ because counters cannot be read from inside this script."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("gemm_fwd_traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -54,6 +68,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-legs", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=2048)
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="launch a 1 GiB device copy and every kernel of the step twice, then exit "
+                         "(run under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -113,6 +130,17 @@ def main() -> int:
         fp8.fp8_linear_fwd(x, w, recipe, y=y, workspace=ws_f)
         if wl.backward:
             fp8.fp8_linear_bwd(dy, x, w, recipe, dx=dx, dw=dw, workspace=ws_b)
+
+    if args.traffic_probe:
+        # reference for the counters: a plain copy of known size (1 GiB read + 1 GiB written)
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)
+            step()
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": wl.name, "copy_bytes_each_way": 1 << 30}))
+        return 0
 
     for _ in range(args.warmup):
         step()
@@ -200,9 +228,9 @@ def main() -> int:
                              "speedup": round(bf_ms / fp8_ms, 3),
                              "bf16_TFLOP/s": round(flop_step / (bf_ms * 1e-3) / 1e12, 1),
                              "comparator": "torch.matmul bf16 (vendor BLAS), benchmark only"}
-        result["roofline"] = {"kernel": "gemm_fp8_tn_kernel (forward GEMM)", "bound": "mfma",
+        result["roofline"] = {"kernel": "forward scaled GEMM (gemm_fp8_snake_kernel<e4m3,e4m3,bf16>)", "bound": "mfma",
                               "achieved": round(fwd_tf, 1), "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
-                              "frac": round(fwd_tf / FP8_PEAK_TFLOPS, 4), "traffic": None,
+                              "frac": round(fwd_tf / FP8_PEAK_TFLOPS, 4), "traffic": _profiled_traffic(wl.name),
                               "flop_per_launch": 2.0 * M * N * K, "avg_launch_ms": round(fwd_ms, 4)}
 
     # ------------------------------------------------ CPU oracle baseline
