@@ -130,3 +130,62 @@ def test_full_size_llama_ffn_fwd_bwd_sampled():
     print("fwd", _cmp(y, orc.linear_fwd(x, w, o, rows_m)[0], rows_m), flush=True)
     print("dx", _cmp(dx, orc.linear_bwd_dx(dy, w, o, rows_m)[0], rows_m), flush=True)
     print("dw", _cmp(dw, orc.linear_bwd_dw(dy, x, o, rows_n)[0], rows_n), flush=True)
+
+
+def _full_size_check(name, rows=16, bwd=True, min_identical=0.97):
+    wl = si.WORKLOADS[name]
+    x, w = wl.x(), wl.w()
+    o, g = _recipes(wl)
+    xd, wd = dev_bf16(x), dev_bf16(w)
+    y = fp8.fp8_linear_fwd(xd, wd, g)
+    rows_m = si.stratified_rows(wl.M, rows)
+    out = {"fwd": _cmp(y, orc.linear_fwd(x, w, o, rows_m)[0], rows_m, min_identical)}
+    del y
+    if bwd and wl.backward:
+        dy = wl.dy()
+        dyd = dev_bf16(dy)
+        dx, dw = fp8.fp8_linear_bwd(dyd, xd, wd, g)
+        torch.cuda.synchronize()
+        rows_n = si.stratified_rows(wl.N, rows)
+        out["dx"] = _cmp(dx, orc.linear_bwd_dx(dy, w, o, rows_m)[0], rows_m)
+        out["dw"] = _cmp(dw, orc.linear_bwd_dw(dy, x, o, rows_n)[0], rows_n)
+    print(name, out, flush=True)
+    return out
+
+
+@pytest.mark.parametrize("name", ["c3_llama3_8b_qkv_tensorwise", "c3_llama3_8b_oproj_tensorwise",
+                                  "c3_llama3_8b_down_tensorwise"])
+def test_full_size_attention_projections_tensorwise(name):
+    """Llama-3-8B QKV / O / down projections, tensorwise scaling, forward and
+    backward at full size; sampled output rows against the oracle."""
+    _full_size_check(name)
+
+
+@pytest.mark.parametrize("name", ["c4_llama3_70b_up_rowwise_pow2", "c4_llama3_70b_down_rowwise_pow2"])
+def test_full_size_llama70b_rowwise_pow2(name):
+    """Llama-3-70B FFN shapes, rowwise scaling with power-of-two scales."""
+    _full_size_check(name, rows=8)
+
+
+def test_full_size_outlier_stress_rowwise_vs_tensorwise():
+    """Outlier-heavy activations (Student-t(3), 4 of 4096 columns x100) at full
+    size: bytes and scales of X bit-exact, saturation / underflow counts
+    reported by the oracle, forward output on sampled rows, and tensorwise
+    losing more to underflow than rowwise (the paper's Appendix A)."""
+    stats = {}
+    for name in ("c5_outlier_rowwise", "c5_outlier_tensorwise"):
+        wl = si.WORKLOADS[name]
+        x = wl.x()
+        o, g = _recipes(wl)
+        gran_o = orc.ROW if wl.recipe == si.ROWWISE else orc.TENSOR
+        q, s = fp8.fp8_quantize(dev_bf16(x), g.gran, fp8.FP8_E4M3FN)
+        wq, ws = orc.quantize(x, gran_o, orc.E4M3FN)
+        assert (s.cpu().numpy().view(np.uint32) == ws.view(np.uint32)).all()
+        assert (q.cpu().numpy() == wq).all()
+        st = orc.cast_stats(x, ws, gran_o, orc.E4M3FN)
+        stats[name] = st
+        print(name, st, flush=True)
+        _full_size_check(name, rows=16, bwd=False, min_identical=0.95)   # heavy tails: more near-ties in bf16
+    r, t = stats["c5_outlier_rowwise"], stats["c5_outlier_tensorwise"]
+    assert t.n_zero > 5 * max(1, r.n_zero) and r.sqnr_db > t.sqnr_db
+    assert r.n_sat <= 4096 and t.n_sat <= 1     # only amax elements can be clamped under dynamic scaling
