@@ -115,6 +115,23 @@ int fp8_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran
                  int flags, uint8_t* q_out, int64_t ld_out, float* scale_out, void* stream);
 
 /*
+ * one tensor quantized along BOTH axes (Appendix A, rowwise recipe: the output
+ * gradient feeds dX = dY W with one scale per row and dW = dY^T X with one
+ * scale per column).  Results are identical to
+ *   fp8_quantize(x, ..., FP8_ROW, format, flags, q_row, ld_row, scale_row) and
+ *   fp8_quantize(x, ..., FP8_COL, format, flags | FP8_TRANSPOSE_OUT, q_col_t, ld_col_t, scale_col),
+ * but x is read twice instead of three times: the column maxima are gathered
+ * in the pass that writes the rowwise codes.
+ *   q_row [rows, cols] (ld_row), scale_row [rows]; q_col_t [cols, rows]
+ *   (ld_col_t), scale_col [cols].  The four outputs must not overlap; q_col_t
+ *   is also used as scratch before it receives its codes.
+ *   flags: FP8_POW2_SCALE only.
+ */
+int fp8_quantize_row_col(const void* x, int64_t rows, int64_t cols, int64_t ld, int format, int flags,
+                         uint8_t* q_row, int64_t ld_row, float* scale_row,
+                         uint8_t* q_col_t, int64_t ld_col_t, float* scale_col, void* stream);
+
+/*
  * scaled GEMM on FP8 matrix cores (Section 2.1: "specialized GEMM kernels").
  *   out[m, n] = ( sum_k dec(a[m, k]) * dec(b[n, k]) ) / (sa * sb)
  *   a [M, K] and b [N, K] are fp8 codes with the contraction axis contiguous

@@ -6,7 +6,7 @@ from .fp8 import (  # noqa: F401
     FP8_E4M3FN, FP8_E5M2, FP8_TENSOR, FP8_ROW, FP8_COL,
     FP8_POW2_SCALE, FP8_TRANSPOSE_OUT, FP8_OUT_FP32,
     Fp8Error, Recipe, library_path, load_library,
-    fp8_amax, fp8_scale, fp8_cast, fp8_quantize, fp8_scaled_mm,
+    fp8_amax, fp8_scale, fp8_cast, fp8_quantize, fp8_quantize_row_col, fp8_scaled_mm,
     fp8_linear_workspace_bytes, fp8_linear_fwd, fp8_linear_bwd,
     fp8_last_error, fp8_version,
 )

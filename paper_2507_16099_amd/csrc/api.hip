@@ -77,6 +77,28 @@ int quantize_impl(const void* x, int64_t rows, int64_t cols, int64_t ld, int gra
     return FP8_OK;
 }
 
+// rowwise codes and per-column transposed codes of one tensor, the column
+// maxima gathered while the rowwise codes are written (q_col_t holds the
+// first-level maxima until the cast overwrites it)
+int quantize_row_col_impl(const void* x, int64_t rows, int64_t cols, int64_t ld, int format, int flags,
+                          uint8_t* q_row, int64_t ld_row, float* scale_row, uint8_t* q_col_t, int64_t ld_col_t,
+                          float* scale_col, hipStream_t st) {
+    const int pow2 = flags & FP8_POW2_SCALE;
+    hipError_t e = hipErrorNotSupported;
+    if (rows > 0 && cols > 0)
+        e = fp8k::launch_quant_row_colmax(x, rows, cols, ld, format, pow2, q_row, ld_row, scale_row, scale_col, q_col_t,
+                                          (size_t)(cols - 1) * (size_t)ld_col_t + (size_t)rows, st);
+    if (e == hipSuccess) {
+        FP8_TRY(fp8k::launch_scale(scale_col, cols, format, pow2, scale_col, st));
+        FP8_TRY(fp8k::launch_cast(x, rows, cols, ld, scale_col, FP8_COL, format, 1, q_col_t, ld_col_t, nullptr, 0, st));
+        return FP8_OK;
+    }
+    if (e != hipErrorNotSupported) return hip_fail(e, "quant_row_colmax");
+    if (int rc = quantize_impl(x, rows, cols, ld, FP8_ROW, format, pow2, q_row, ld_row, nullptr, 0, scale_row, st)) return rc;
+    return quantize_impl(x, rows, cols, ld, FP8_COL, format, pow2 | FP8_TRANSPOSE_OUT, q_col_t, ld_col_t, nullptr, 0,
+                         scale_col, st);
+}
+
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct FwdPlan {
@@ -208,6 +230,21 @@ int fp8_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran
                          static_cast<hipStream_t>(stream));
 }
 
+int fp8_quantize_row_col(const void* x, int64_t rows, int64_t cols, int64_t ld, int format, int flags,
+                         uint8_t* q_row, int64_t ld_row, float* scale_row, uint8_t* q_col_t, int64_t ld_col_t,
+                         float* scale_col, void* stream) {
+    g_err[0] = 0;
+    if (!fmt_ok(format)) return fail(FP8_ERR_ENUM, "fp8_quantize_row_col: unknown format %d", format);
+    if (flags & ~FP8_POW2_SCALE) return fail(FP8_ERR_ENUM, "fp8_quantize_row_col: flags=%d has unknown bits", flags);
+    if (int rc = check_bf16("fp8_quantize_row_col", x, rows, cols, ld)) return rc;
+    if (int rc = check_q_out("fp8_quantize_row_col(q_row)", q_row, rows, cols, ld_row, 0)) return rc;
+    if (int rc = check_q_out("fp8_quantize_row_col(q_col_t)", q_col_t, rows, cols, ld_col_t, 1)) return rc;
+    if ((rows > 0 && !scale_row) || (cols > 0 && !scale_col)) return fail(FP8_ERR_NULL, "fp8_quantize_row_col: scale output is NULL");
+    if (!aligned(scale_row, 4) || !aligned(scale_col, 4)) return fail(FP8_ERR_ALIGN, "fp8_quantize_row_col: scales not 4-byte aligned");
+    return quantize_row_col_impl(x, rows, cols, ld, format, flags, q_row, ld_row, scale_row, q_col_t, ld_col_t, scale_col,
+                                 static_cast<hipStream_t>(stream));
+}
+
 int fp8_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int gran_a, const uint8_t* b,
                   int64_t ldb, int fmt_b, const float* scale_b, int gran_b, int64_t M, int64_t N, int64_t K,
                   void* out, int64_t ld_out, int flags, void* stream) {
@@ -312,13 +349,18 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
         return FP8_OK;
     }
     // rowwise: every operand re-quantized along the contraction axis of its GEMM
+    const bool both = dx && dw;
+    if (both)   // dY along N (rows) and along M (columns, transposed) from two reads instead of three
+        if (int rc = quantize_row_col_impl(dy, M, N, N, recipe->fmt_dy, fl, gq, N, sg, gqt, M, sgt, st)) return rc;
     if (dx) {  // dX = dY W, contraction over N
-        if (int rc = quantize_impl(dy, M, N, N, FP8_ROW, recipe->fmt_dy, fl, gq, N, nullptr, 0, sg, st)) return rc;
+        if (!both)
+            if (int rc = quantize_impl(dy, M, N, N, FP8_ROW, recipe->fmt_dy, fl, gq, N, nullptr, 0, sg, st)) return rc;
         if (int rc = quantize_impl(w, N, K, K, FP8_COL, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st)) return rc;
         FP8_TRY(fp8k::launch_gemm_fp8(gq, N, recipe->fmt_dy, sg, 1, wt, N, recipe->fmt_w, swt, 1, M, K, N, dx, K, 0, st));
     }
     if (dw) {  // dW = dY^T X, contraction over M
-        if (int rc = quantize_impl(dy, M, N, N, FP8_COL, recipe->fmt_dy, fl | T, gqt, M, nullptr, 0, sgt, st)) return rc;
+        if (!both)
+            if (int rc = quantize_impl(dy, M, N, N, FP8_COL, recipe->fmt_dy, fl | T, gqt, M, nullptr, 0, sgt, st)) return rc;
         if (int rc = quantize_impl(x, M, K, K, FP8_COL, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st)) return rc;
         FP8_TRY(fp8k::launch_gemm_fp8(gqt, M, recipe->fmt_dy, sgt, 1, xt, M, recipe->fmt_x, sxt, 1, N, K, M, dw, K, 0, st));
     }

@@ -34,8 +34,10 @@
 //     group are 16 consecutive n);
 //   - the B tile is the first MFMA operand, A the second: a lane's accumulators
 //     belong to one output row m.  The epilogue scales by the reciprocal scales
-//     (computed once per tile into LDS), rounds to bfloat16, parks the quadrant
-//     in LDS and streams out whole 256-byte rows with non-temporal stores.
+//     (computed once per tile into LDS while the first stage is in flight),
+//     rounds to bfloat16 and, 16 rows at a time, parks them in LDS and streams
+//     out whole 256-byte rows with non-temporal stores, so the stores of one
+//     group of rows overlap the arithmetic of the next.
 #include "fp8_device.hpp"
 #include "launchers.hpp"
 
@@ -199,8 +201,17 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
     // number of steps gets one phantom step whose loads are all out of range (zeros).
     const int ksteps = (K + BK - 1) / BK;
     const int kpairs = (ksteps + 1) / 2;
+    // reciprocal scales of the tile's 256 rows and 256 columns (one correctly
+    // rounded divide per thread), computed while the first stage is in flight;
+    // the tables sit behind the two stages, where no load ever lands
+    float* inv_tab = reinterpret_cast<float*>(smem + 2 * STAGE);       // [0,256): 1/sa, [256,512): 1/sb
+    if (ksteps > 0) issue_loads(0, 0);
+    {
+        const int m = m0 + tid, n = n0 + tid;
+        inv_tab[tid] = row_a ? (m < M ? 1.0f / scale_a[m] : 0.f) : 1.0f / scale_a[0];
+        inv_tab[256 + tid] = row_b ? (n < N ? 1.0f / scale_b[n] : 0.f) : 1.0f / scale_b[0];
+    }
     if (ksteps > 0) {
-        issue_loads(0, 0);
         sn_wait_all_vmem();
         __syncthreads();                       // stage 0 landed for every wave
         issue_loads(1, BK);                    // (out of range if there is no step 1)
@@ -245,34 +256,31 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
 
     // ---- epilogue.  Lane holds output row m = 16*fi + l%16 and, per 64-wide B group,
     //      the 16 consecutive columns 16*g + 4*t + r (fragment t, accumulator r).
-    float* inv_tab = reinterpret_cast<float*>(smem + 2 * STAGE);       // [0,256): 1/sa, [256,512): 1/sb
-    {
-        const int m = m0 + tid, n = n0 + tid;
-        inv_tab[tid] = row_a ? (m < M ? 1.0f / scale_a[m] : 0.f) : 1.0f / scale_a[0];
-        inv_tab[256 + tid] = row_b ? (n < N ? 1.0f / scale_b[n] : 0.f) : 1.0f / scale_b[0];
-    }
-    __syncthreads();   // tables visible; every wave is past its last LDS read of the stages
+    __syncthreads();   // tables visible; nobody's trailing refill can land in the staging rows below
 
+    float inv_b[2][16];
 #pragma unroll
-    for (int grp = 0; grp < 2; ++grp) {
-        const int nl = wn0 + 64 * grp + 16 * g;            // first of this lane's 16 columns (tile-local)
-        float inv_b[16];
+    for (int grp = 0; grp < 2; ++grp)
 #pragma unroll
         for (int e = 0; e < 16; e += 4) {
-            const float4 t4 = *reinterpret_cast<const float4*>(inv_tab + 256 + nl + e);
-            inv_b[e] = t4.x; inv_b[e + 1] = t4.y; inv_b[e + 2] = t4.z; inv_b[e + 3] = t4.w;
+            const float4 t4 = *reinterpret_cast<const float4*>(inv_tab + 256 + wn0 + 64 * grp + 16 * g + e);
+            inv_b[grp][e] = t4.x; inv_b[grp][e + 1] = t4.y; inv_b[grp][e + 2] = t4.z; inv_b[grp][e + 3] = t4.w;
         }
+
+    if constexpr (OUT_F32) {
 #pragma unroll
         for (int fi = 0; fi < 8; ++fi) {
             const int r_loc = 16 * fi + r16;               // row inside the wave's quadrant
             const float inv_a = inv_tab[wm0 + r_loc];
-            float v[16];
+            const int m = m0 + wm0 + r_loc;
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+            for (int grp = 0; grp < 2; ++grp) {
+                float v[16];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) v[4 * t + r] = (acc[fi][grp * 4 + t][r] * inv_a) * inv_b[4 * t + r];
-            if constexpr (OUT_F32) {
-                const int m = m0 + wm0 + r_loc, nb = n0 + nl;
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[4 * t + r] = (acc[fi][grp * 4 + t][r] * inv_a) * inv_b[grp][4 * t + r];
+                const int nb = n0 + wn0 + 64 * grp + 16 * g;
                 if (m < M && nb < N) {
                     float* dst = static_cast<float*>(out) + (int64_t)m * ld_out + nb;
                     if (nb + 16 <= N) {
@@ -283,41 +291,57 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
                         for (int e = 0; nb + e < N; ++e) dst[e] = v[e];
                     }
                 }
-            } else {
-                // park in this wave's 32 KB of LDS: row = 256 bytes = 16 chunks, chunk c
-                // stored at c ^ (row & 15)
-                uint32_t p[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) p[e] = sn_pack_bf16(v[2 * e], v[2 * e + 1]);
-                uint8_t* row = smem + wave * 32768 + r_loc * 256;
-                const int c = 8 * grp + 2 * g;
-                *reinterpret_cast<uint4*>(row + ((c ^ (r_loc & 15)) << 4)) = make_uint4(p[0], p[1], p[2], p[3]);
-                *reinterpret_cast<uint4*>(row + (((c + 1) ^ (r_loc & 15)) << 4)) = make_uint4(p[4], p[5], p[6], p[7]);
             }
         }
-    }
-    if constexpr (!OUT_F32) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const uint8_t* q = smem + wave * 32768;
-        const int c = lane & 15;
-        const int n = n0 + wn0 + c * 8;
-        uint16_t* obase = static_cast<uint16_t*>(out) + n;
-#pragma unroll 8
-        for (int it = 0; it < 32; ++it) {
-            const int r_loc = it * 4 + (lane >> 4);
-            const int m = m0 + wm0 + r_loc;
-            const uint4 v = *reinterpret_cast<const uint4*>(q + r_loc * 256 + ((c ^ (r_loc & 15)) << 4));
-            if (m < M && n < N) {
-                uint16_t* dst = obase + (int64_t)m * ld_out;
-                if (n + 8 <= N) {
+    } else {
+        // bfloat16: 16 rows at a time are scaled, rounded, parked in this wave's own
+        // 32 KB of LDS (row = 256 bytes = 16 chunks, chunk c stored at c ^ (row & 15))
+        // and streamed out as whole 256-byte rows, so the stores of one group of
+        // rows overlap the arithmetic of the next.  LDS operations of one wave
+        // execute in order; the wave barrier only keeps the compiler from moving
+        // the reads above the writes.
+        uint8_t* q = smem + wave * 32768;
+        const int c_rd = lane & 15;                        // chunk this lane streams out
+        const int n_rd = n0 + wn0 + c_rd * 8;
+        const bool interior = m0 + BM <= M && n0 + BN <= N;
+        uint16_t* orow = static_cast<uint16_t*>(out) + (int64_t)(m0 + wm0 + (lane >> 4)) * ld_out + n_rd;
+#pragma unroll
+        for (int fi = 0; fi < 8; ++fi) {
+            const int r_loc = 16 * fi + r16;
+            const float inv_a = inv_tab[wm0 + r_loc];
+            uint8_t* row = q + r_loc * 256;
+#pragma unroll
+            for (int grp = 0; grp < 2; ++grp) {
+                uint32_t p[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int e0 = 2 * e, e1 = 2 * e + 1;
+                    p[e] = sn_pack_bf16((acc[fi][grp * 4 + (e0 >> 2)][e0 & 3] * inv_a) * inv_b[grp][e0],
+                                        (acc[fi][grp * 4 + (e1 >> 2)][e1 & 3] * inv_a) * inv_b[grp][e1]);
+                }
+                const int c = 8 * grp + 2 * g;
+                *reinterpret_cast<uint4*>(row + ((c ^ r16) << 4)) = make_uint4(p[0], p[1], p[2], p[3]);
+                *reinterpret_cast<uint4*>(row + (((c + 1) ^ r16) << 4)) = make_uint4(p[4], p[5], p[6], p[7]);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int rr = 16 * fi + 4 * it + (lane >> 4);      // row in the quadrant
+                const uint4 v = *reinterpret_cast<const uint4*>(q + rr * 256 + ((c_rd ^ (rr & 15)) << 4));
+                uint16_t* dst = orow + (int64_t)(16 * fi + 4 * it) * ld_out;
+                if (interior) {
                     // streaming store: the output is not read again by this kernel and
                     // should not push the operand panels out of L2
                     __builtin_nontemporal_store(v4u_s{v.x, v.y, v.z, v.w}, reinterpret_cast<v4u_s*>(dst));
-                } else {
-                    const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
-                    for (int e = 0; n + e < N; ++e) dst[e] = (uint16_t)(w4[e >> 1] >> ((e & 1) * 16));
+                } else if (m0 + wm0 + rr < M && n_rd < N) {
+                    if (n_rd + 8 <= N) {
+                        __builtin_nontemporal_store(v4u_s{v.x, v.y, v.z, v.w}, reinterpret_cast<v4u_s*>(dst));
+                    } else {
+                        const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+                        for (int e = 0; n_rd + e < N; ++e) dst[e] = (uint16_t)(w4[e >> 1] >> ((e & 1) * 16));
+                    }
                 }
             }
         }

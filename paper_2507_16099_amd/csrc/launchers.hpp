@@ -36,6 +36,13 @@ hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float
                            int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
                            hipStream_t st);
 
+// Rowwise quantization (codes q, scales scale_out) and the column maxima
+// amax_cols[c] = max_r |x[r, c]| from a single read of x; scratch holds the
+// first-level column maxima.  hipErrorNotSupported if the shape does not suit.
+hipError_t launch_quant_row_colmax(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, int flags,
+                                   uint8_t* q, int64_t ld_out, float* scale_out, float* amax_cols, void* scratch,
+                                   size_t scratch_bytes, hipStream_t st);
+
 // 256 x 256 software-pipelined kernel (direct-to-LDS loads); same contract.
 bool gemm_fp8_pipelined_supported(int64_t lda, int64_t ldb);
 hipError_t launch_gemm_fp8_pipelined(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,

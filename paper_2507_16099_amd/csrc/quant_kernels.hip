@@ -295,8 +295,8 @@ __global__ __launch_bounds__(256) void cast_kernel(const uint16_t* __restrict__ 
         uint8_t* dst = q + r * ld_out + c;
         if constexpr (GRAN == GRAN_ROW) s_t = scale[r];
         if (c + 16 <= cols) {
-            const uint4 v0 = reinterpret_cast<const uint4*>(src)[0];
-            const uint4 v1 = reinterpret_cast<const uint4*>(src)[1];
+            const uint4 v0 = load_stream(src);
+            const uint4 v1 = load_stream(src + 8);
             uint2 lo, hi;
             if constexpr (GRAN == GRAN_COL) {
                 float s[8];
@@ -310,7 +310,7 @@ __global__ __launch_bounds__(256) void cast_kernel(const uint16_t* __restrict__ 
                 lo = cast8<FMT>(v0, s_t);
                 hi = cast8<FMT>(v1, s_t);
             }
-            *reinterpret_cast<uint4*>(dst) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            store_stream(dst, make_uint4(lo.x, lo.y, hi.x, hi.y));
         } else {
             for (int e = 0; c + e < cols; ++e) {
                 const float s = GRAN == GRAN_COL ? scale[c + e] : s_t;
@@ -347,15 +347,21 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
                                                               int64_t cols, int64_t ld,
                                                               const float* __restrict__ scale,
                                                               uint8_t* __restrict__ qt, int64_t ld_t,
-                                                              uint8_t* __restrict__ q_plain, int64_t ld_plain) {
+                                                              uint8_t* __restrict__ q_plain, int64_t ld_plain,
+                                                              int nx, int ny) {
     constexpr int SLOTS = TR / 8;   // 8-byte slots per output row
     constexpr int PARTS = TR / 16;  // 16-byte parts per output row
     __shared__ __attribute__((aligned(16))) uint2 tile[128 * SLOTS];
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-    // blockIdx.x walks down the input rows: workgroups that run together then
-    // write neighbouring segments of the same output rows (and spread over all
-    // memory channels instead of piling onto the few that one 4 KB window maps to)
-    const int64_t r0 = (int64_t)blockIdx.x * TR, c0 = (int64_t)blockIdx.y * 128;
+    // 1-D grid walked in patches of 16 x 16 tiles (input-row tiles fastest): the
+    // workgroups in flight together read 4 KB runs of the input rows and write
+    // 2 KB runs of the output rows, instead of isolated 256-byte / 128-byte pieces
+    constexpr int PX = 16, PY = 16;
+    const int pxc = (nx + PX - 1) / PX;
+    const int patch = blockIdx.x / (PX * PY), within = blockIdx.x % (PX * PY);
+    const int bx = (patch % pxc) * PX + within % PX, by = (patch / pxc) * PY + within / PX;
+    if (bx >= nx || by >= ny) return;
+    const int64_t r0 = (int64_t)bx * TR, c0 = (int64_t)by * 128;
     const int64_t c = c0 + tx * 8;
 
     float s_col[8];
@@ -376,7 +382,7 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
             if (r < rows) {
                 const uint16_t* src = x + r * ld + c;
                 if (c + 8 <= cols) {
-                    v = *reinterpret_cast<const uint4*>(src);
+                    v = load_stream(src);
                 } else if (c < cols) {
                     uint32_t t[4] = {0, 0, 0, 0};
                     for (int e = 0; c + e < cols; ++e) t[e >> 1] |= (uint32_t)src[e] << ((e & 1) * 16);
@@ -395,7 +401,7 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
             if (q_plain != nullptr && r < rows) {
                 uint8_t* dst = q_plain + r * ld_plain + c;
                 if (c + 8 <= cols) {
-                    *reinterpret_cast<uint2*>(dst) = b;
+                    store_stream(dst, b);
                 } else {
                     for (int e = 0; c + e < cols; ++e) dst[e] = (uint8_t)((e < 4 ? b.x >> (8 * e) : b.y >> (8 * (e - 4))) & 0xFFu);
                 }
@@ -425,7 +431,7 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
         const uint4 v = tile16[cc * PARTS + (p ^ ((cc >> 3) & 7))];
         uint8_t* dst = qt + oc * ld_t + orow;
         if (orow + 16 <= rows) {
-            *reinterpret_cast<uint4*>(dst) = v;
+            store_stream(dst, v);
         } else {
             const uint32_t t[4] = {v.x, v.y, v.z, v.w};
             for (int e = 0; orow + e < rows; ++e) dst[e] = (uint8_t)((t[e >> 2] >> (8 * (e & 3))) & 0xFFu);
@@ -441,9 +447,10 @@ static hipError_t launch_cast_t(const uint16_t* x, int64_t rows, int64_t cols, i
         // 128-row tiles measured best (256-row tiles: same on the 470 MB gradient
         // tensor, slower on the smaller operands)
         const int64_t gx = (cols + 127) / 128, gy = (rows + 127) / 128;
-        if (gx > 65535) return hipErrorInvalidValue;
-        cast_transpose_kernel<FMT, GRAN, 128><<<dim3((unsigned)gy, (unsigned)gx), dim3(256), 0, st>>>(
-            x, rows, cols, ld, scale, q, ld_out, q_plain, ld_plain);
+        const int64_t total = ((gy + 15) / 16) * ((gx + 15) / 16) * 256;
+        if (total > 0x7FFFFFFF) return hipErrorInvalidValue;
+        cast_transpose_kernel<FMT, GRAN, 128><<<dim3((unsigned)total), dim3(256), 0, st>>>(
+            x, rows, cols, ld, scale, q, ld_out, q_plain, ld_plain, (int)gy, (int)gx);
         return hipGetLastError();
     }
     const int64_t items = (cols + 15) / 16;
@@ -496,7 +503,7 @@ __global__ __launch_bounds__(256) void quant_row_kernel(const uint16_t* __restri
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
         const int64_t vi = tx + (int64_t)j * TX;
-        v[j] = (live && vi < nvec) ? rv[vi] : make_uint4(0, 0, 0, 0);
+        v[j] = (live && vi < nvec) ? load_stream(rv + vi) : make_uint4(0, 0, 0, 0);
     }
     uint32_t tail = 0;
     if (live && tx < ntail) tail = row[(nvec << 3) + tx];
@@ -523,7 +530,7 @@ __global__ __launch_bounds__(256) void quant_row_kernel(const uint16_t* __restri
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
         const int64_t vi = tx + (int64_t)j * TX;
-        if (vi < nvec) reinterpret_cast<uint2*>(dst)[vi] = cast8<FMT>(v[j], s);
+        if (vi < nvec) store_stream(reinterpret_cast<uint2*>(dst) + vi, cast8<FMT>(v[j], s));
     }
     if (tx < ntail) {
         const float p = __uint_as_float(tail << 16) * s;
@@ -562,5 +569,120 @@ hipError_t launch_quant_row(const void* x, int64_t rows, int64_t cols, int64_t l
     if (!ok) return hipErrorNotSupported;
     return hipGetLastError();
 }
+
+// ------------------------------ fused rowwise quantize + column maxima (first level)
+// The gradient of a rowwise-scaled linear layer is quantized twice: per row for
+// dX = dY W and per column for dW = dY^T X (Appendix A).  This kernel serves
+// both from ONE read: block b walks rows b, b + G, b + 2G, ...; a row sits in
+// registers while its maximum is reduced and its codes are written (as in
+// quant_row_kernel), and every thread also folds the row into the running
+// maxima of its own 8 * NV columns.  The block's column maxima go to row b of
+// a [G, cols] matrix of bfloat16 magnitudes, which amax_cols_kernel reduces;
+// the per-column cast then reads the tensor a second (and last) time.
+// The next row is requested before the current one is reduced.  The per-row
+// wave maxima alternate between two LDS slots, so one barrier per row is enough.
+template <int FMT, int NV>
+__global__ __launch_bounds__(256) void quant_row_colmax_kernel(const uint16_t* __restrict__ x, int64_t rows,
+                                                                int64_t cols, int64_t ld, int flags,
+                                                                uint8_t* __restrict__ q, int64_t ld_out,
+                                                                float* __restrict__ scale_out,
+                                                                uint16_t* __restrict__ part, int64_t ld_part) {
+    const int64_t nvec = cols >> 3;     // cols is a multiple of 8 (checked by the launcher)
+    const int tid = threadIdx.x;
+    __shared__ uint32_t red[2][4];
+    uint4 cmax[NV], v[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) cmax[j] = make_uint4(0, 0, 0, 0);
+    int64_t r = blockIdx.x;
+    if (r < rows) {
+        const uint4* rv = reinterpret_cast<const uint4*>(x + r * ld);
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int64_t vi = tid + (int64_t)j * 256;
+            v[j] = vi < nvec ? rv[vi] : make_uint4(0, 0, 0, 0);
+        }
+    }
+    int slot = 0;
+    for (; r < rows; r += gridDim.x) {
+        const int64_t rn = r + gridDim.x;
+        uint4 nv[NV];
+        if (rn < rows) {
+            const uint4* rv = reinterpret_cast<const uint4*>(x + rn * ld);
+#pragma unroll
+            for (int j = 0; j < NV; ++j) {
+                const int64_t vi = tid + (int64_t)j * 256;
+                nv[j] = vi < nvec ? rv[vi] : make_uint4(0, 0, 0, 0);
+            }
+        }
+        uint32_t acc = 0;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            cmax[j].x = pk_absmax(cmax[j].x, v[j].x);
+            cmax[j].y = pk_absmax(cmax[j].y, v[j].y);
+            cmax[j].z = pk_absmax(cmax[j].z, v[j].z);
+            cmax[j].w = pk_absmax(cmax[j].w, v[j].w);
+            acc = pk_absmax4(acc, v[j]);
+        }
+        uint32_t m = wave_max_u32<64>(pk_fold(acc));
+        if ((tid & 63) == 0) red[slot][tid >> 6] = m;
+        __syncthreads();
+        m = red[slot][0];
+#pragma unroll
+        for (int i = 1; i < 4; ++i) m = red[slot][i] > m ? red[slot][i] : m;
+        slot ^= 1;
+        const float s = scale_from_amax(mag_to_float(m), FMT, flags);
+        if (tid == 0) scale_out[r] = s;
+        uint8_t* dst = q + r * ld_out;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int64_t vi = tid + (int64_t)j * 256;
+            if (vi < nvec) store_stream(reinterpret_cast<uint2*>(dst) + vi, cast8<FMT>(v[j], s));
+        }
+        if (rn < rows) {
+#pragma unroll
+            for (int j = 0; j < NV; ++j) v[j] = nv[j];
+        }
+    }
+    uint16_t* prow = part + (int64_t)blockIdx.x * ld_part;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int64_t vi = tid + (int64_t)j * 256;
+        if (vi < nvec) reinterpret_cast<uint4*>(prow)[vi] = cmax[j];
+    }
+}
+
+// Rowwise codes + scales of x, and amax_cols[c] = max_r |x[r, c]|, from one read
+// of x.  scratch: at least 256 * round_up(cols, 8) * 2 bytes, 16-byte aligned
+// (more lets more blocks run).  hipErrorNotSupported if the shape does not suit
+// (cols not a multiple of 8, rows too few or too wide for registers).
+hipError_t launch_quant_row_colmax(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, int flags,
+                                   uint8_t* q, int64_t ld_out, float* scale_out, float* amax_cols, void* scratch,
+                                   size_t scratch_bytes, hipStream_t st) {
+    const int64_t nvec = cols / 8;
+    if (cols % 8 != 0 || nvec > 256 * 16 || nvec < 64) return hipErrorNotSupported;
+    const int64_t ld_part = cols;
+    int64_t G = 1024;
+    while (G >= 256 && (rows < 8 * G || (size_t)(G * ld_part * 2) > scratch_bytes)) G /= 2;
+    if (G < 256) return hipErrorNotSupported;
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    uint16_t* part = static_cast<uint16_t*>(scratch);
+#define FP8K_QRC(FMT, NV)                                                                                     \
+    quant_row_colmax_kernel<FMT, NV><<<dim3((unsigned)G), dim3(256), 0, st>>>(xp, rows, cols, ld, flags, q, ld_out, \
+                                                                              scale_out, part, ld_part)
+#define FP8K_QRC_NV(FMT)                 \
+    if (nvec <= 256) FP8K_QRC(FMT, 1);   \
+    else if (nvec <= 512) FP8K_QRC(FMT, 2);  \
+    else if (nvec <= 1024) FP8K_QRC(FMT, 4); \
+    else if (nvec <= 2048) FP8K_QRC(FMT, 8); \
+    else FP8K_QRC(FMT, 16)
+    if (fmt == FMT_E4M3FN) { FP8K_QRC_NV(FMT_E4M3FN); }
+    else { FP8K_QRC_NV(FMT_E5M2); }
+#undef FP8K_QRC_NV
+#undef FP8K_QRC
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_amax(part, G, cols, ld_part, GRAN_COL, amax_cols, st);
+}
+
 
 }  // namespace fp8k

@@ -71,6 +71,8 @@ def load_library() -> C.CDLL:
     L.fp8_cast.argtypes = [vp, i64, i64, i64, vp, ci, ci, ci, vp, i64, vp]
     L.fp8_quantize.restype = ci
     L.fp8_quantize.argtypes = [vp, i64, i64, i64, ci, ci, ci, vp, i64, vp, vp]
+    L.fp8_quantize_row_col.restype = ci
+    L.fp8_quantize_row_col.argtypes = [vp, i64, i64, i64, ci, ci, vp, i64, vp, vp, i64, vp, vp]
     L.fp8_scaled_mm.restype = ci
     L.fp8_scaled_mm.argtypes = [vp, i64, ci, vp, ci, vp, i64, ci, vp, ci, i64, i64, i64, vp, i64, ci, vp]
     L.fp8_linear_workspace_bytes.restype = C.c_size_t
@@ -165,6 +167,26 @@ def fp8_quantize(x: torch.Tensor, gran: int, fmt: int, flags: int = 0, out: torc
     _check(load_library().fp8_quantize(_ptr(x), rows, cols, ld, gran, fmt, flags, _ptr(out), ld_out,
                                        _ptr(scale_out), _stream()))
     return out, scale_out
+
+
+def fp8_quantize_row_col(x: torch.Tensor, fmt: int, flags: int = 0, q_row: torch.Tensor | None = None,
+                         scale_row: torch.Tensor | None = None, q_col_t: torch.Tensor | None = None,
+                         scale_col: torch.Tensor | None = None):
+    """Rowwise codes [rows, cols] + scales [rows] and per-column codes, transposed [cols, rows], + scales [cols]."""
+    rows, cols, ld = _mat(x, 2)
+    if q_row is None:
+        q_row = _alloc_q(rows, cols, 0, x.device)
+    if q_col_t is None:
+        q_col_t = _alloc_q(rows, cols, FP8_TRANSPOSE_OUT, x.device)
+    if scale_row is None:
+        scale_row = torch.empty(rows, dtype=torch.float32, device=x.device)
+    if scale_col is None:
+        scale_col = torch.empty(cols, dtype=torch.float32, device=x.device)
+    _, _, ld_row = _mat(q_row, 1)
+    _, _, ld_col_t = _mat(q_col_t, 1)
+    _check(load_library().fp8_quantize_row_col(_ptr(x), rows, cols, ld, fmt, flags, _ptr(q_row), ld_row, _ptr(scale_row),
+                                               _ptr(q_col_t), ld_col_t, _ptr(scale_col), _stream()))
+    return q_row, scale_row, q_col_t, scale_col
 
 
 def fp8_scaled_mm(a: torch.Tensor, fmt_a: int, scale_a: torch.Tensor, gran_a: int,

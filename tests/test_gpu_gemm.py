@@ -23,15 +23,24 @@ import paper_2507_16099_amd as fp8  # noqa: E402
 TOL = 1e-3
 
 
-@pytest.fixture(params=["0", "1", "3", "4"], ids=["tile128", "tile256", "pipelined", "snake"])
-def variant(request):
+def _force_variant(value):
     old = os.environ.get("FP8MI355_GEMM_VARIANT")
-    os.environ["FP8MI355_GEMM_VARIANT"] = request.param
-    yield request.param
+    os.environ["FP8MI355_GEMM_VARIANT"] = value
+    yield value
     if old is None:
         os.environ.pop("FP8MI355_GEMM_VARIANT", None)
     else:
         os.environ["FP8MI355_GEMM_VARIANT"] = old
+
+
+@pytest.fixture(params=["0", "1", "3", "4"], ids=["tile128", "tile256", "pipelined", "snake"])
+def variant(request):
+    yield from _force_variant(request.param)
+
+
+@pytest.fixture(params=["3", "4"], ids=["pipelined", "snake"])
+def big_variant(request):
+    yield from _force_variant(request.param)
 
 
 def _rand_codes(shape, fmt, rng, emax_drop=2):
@@ -91,11 +100,11 @@ def test_random_codes_within_tolerance(variant, M, N, K, ga, gb):
         assert orc.rel_frobenius(got32, want.acc64) <= TOL
 
 
-@pytest.mark.parametrize("M,N,K", [(4608, 4608, 384), (4500, 4400, 400), (8192, 2304, 128)])
-def test_many_tiles_per_workgroup_exact(M, N, K):
-    """More 256 x 256 tiles than CUs: the persistent kernel walks several tiles
-    per workgroup (with the next tile's first loads issued during the previous
-    tile's last step).  Exact on small integers, ragged edges included."""
+@pytest.mark.parametrize("M,N,K", [(4608, 4608, 384), (4500, 4400, 400), (8192, 2304, 128), (5000, 4100, 16)])
+def test_many_tiles_per_workgroup_exact(big_variant, M, N, K):
+    """More 256 x 256 tiles than CUs (several rounds of workgroups per CU, the
+    XCD-aware tile order in full swing).  Exact on small integers, ragged edges
+    and a single short K step included."""
     rng = np.random.default_rng(M + N + K)
     ai = rng.integers(-2, 3, size=(M, K))
     bi = rng.integers(-2, 3, size=(N, K))

@@ -147,6 +147,46 @@ def test_quantize_zero_rows_and_outliers():
         assert (_bits(host_f32(s)) == _bits(ws)).all() and (host_u8(q) == wq).all()
 
 
+@pytest.mark.parametrize("rows,cols,ld", [
+    (2048, 512, 512),        # smallest shape of the fused pass: 256 blocks x 8 rows, one vector per thread
+    (4100, 1024, 1032),      # ragged row count, padded leading dimension
+    (8197, 2048, 2048),      # 1024 blocks, two vectors per thread
+    (2500, 4104, 4104),      # partly filled last vector column
+    (2050, 14336, 14336),    # benchmark row length (8 vectors per thread)
+    (2048, 16392, 16392),    # 16 vectors per thread
+    (100, 200, 200), (3000, 100, 104), (2048, 8, 8), (2047, 512, 512),   # shapes served by the separate passes
+])
+def test_quantize_row_and_column_in_two_reads(rows, cols, ld):
+    """fp8_quantize_row_col == rowwise quantization + per-column transposed
+    quantization of the oracle, bytes and scales bit for bit."""
+    x = si.normal_bf16((rows, cols), 1e-3, seed=12, stream=rows + cols)
+    x[rows // 2, :] = 0                      # an all-zero row ...
+    x[:, cols // 3] = 0x8000                 # ... and an all-(negative-)zero column
+    x[rows - 1, cols - 1] = 0x4e00           # a large last element (5.4e8): last row, last column
+    xd = dev_bf16(x, ld)
+    for fmt, flags in ((orc.E5M2, 0), (orc.E4M3FN, fp8.FP8_POW2_SCALE)):
+        qr, sr, qc, sc = fp8.fp8_quantize_row_col(xd, fmt, flags)
+        wr, wsr = orc.quantize(x, orc.ROW, fmt, flags)
+        wc, wsc = orc.quantize(x, orc.COL, fmt, flags | orc.TRANSPOSE_OUT)
+        assert (_bits(host_f32(sr)) == _bits(wsr)).all(), (rows, cols, fmt, flags)
+        assert (_bits(host_f32(sc)) == _bits(wsc)).all(), (rows, cols, fmt, flags)
+        assert (host_u8(qr) == wr).all(), (rows, cols, fmt, flags)
+        assert (host_u8(qc) == wc).all(), (rows, cols, fmt, flags)
+
+
+def test_quantize_row_col_rejects_bad_arguments():
+    x = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_quantize_row_col(x, 7)
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_quantize_row_col(x, fp8.FP8_E5M2, fp8.FP8_TRANSPOSE_OUT)
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_quantize_row_col(x, fp8.FP8_E5M2, 0, q_col_t=torch.empty((64, 48), dtype=torch.uint8, device="cuda"))
+    e = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    qr, sr, qc, sc = fp8.fp8_quantize_row_col(e, fp8.FP8_E5M2)
+    assert qr.shape == (0, 64) and sr.numel() == 0 and (host_f32(sc) == np.float32(57344.0 / 1e-12)).all()
+
+
 def test_empty_inputs_are_accepted():
     e = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
     assert fp8.fp8_amax(e, fp8.FP8_ROW).numel() == 0
@@ -177,3 +217,18 @@ def test_quantize_full_size_llama_ffn_operands():
         wq, ws = orc.quantize(bits, orc.TENSOR, orc.E4M3FN)
         assert (_bits(host_f32(s)) == _bits(ws)).all() and (host_u8(q) == wq).all(), name
         del d, q, s
+
+
+def test_quantize_full_size_llama_ffn_gradient_both_axes():
+    """dY [16384, 14336] of the benchmark workload through the two-read entry
+    point (e5m2): rowwise codes for dX, per-column transposed codes for dW."""
+    wl = si.WORKLOADS[si.BENCH_WORKLOAD]
+    bits = wl.dy()
+    qr, sr, qc, sc = fp8.fp8_quantize_row_col(dev_bf16(bits), fp8.FP8_E5M2)
+    wr, wsr = orc.quantize(bits, orc.ROW, orc.E5M2)
+    assert (_bits(host_f32(sr)) == _bits(wsr)).all()
+    assert (host_u8(qr) == wr).all()
+    del wr
+    wc, wsc = orc.quantize(bits, orc.COL, orc.E5M2, orc.TRANSPOSE_OUT)
+    assert (_bits(host_f32(sc)) == _bits(wsc)).all()
+    assert (host_u8(qc) == wc).all()
