@@ -68,11 +68,16 @@ int quantize_impl(const void* x, int64_t rows, int64_t cols, int64_t ld, int gra
     // (cols x ld_out bytes, overwritten by the cast afterwards) serves as the
     // scratch matrix of the two-level column amax.
     hipError_t ea = hipErrorNotSupported;
-    if (gran == FP8_COL && transpose && q_plain == nullptr)
-        ea = fp8k::launch_amax_cols_two_level(x, rows, cols, ld, scale_out, q, (size_t)cols * (size_t)ld_out, st);
-    if (ea == hipErrorNotSupported) ea = fp8k::launch_amax(x, rows, cols, ld, gran, scale_out, st);
-    if (ea != hipSuccess) return hip_fail(ea, "amax");
-    FP8_TRY(fp8k::launch_scale(scale_out, n_groups(gran, rows, cols), format, pow2, scale_out, st));
+    if (gran == FP8_COL && transpose && q_plain == nullptr && rows > 0 && cols > 0)
+        ea = fp8k::launch_col_scales_two_level(x, rows, cols, ld, format, pow2, scale_out, q,
+                                               (size_t)(cols - 1) * (size_t)ld_out + (size_t)rows, st);
+    if (ea == hipErrorNotSupported) {
+        ea = fp8k::launch_amax(x, rows, cols, ld, gran, scale_out, st);
+        if (ea != hipSuccess) return hip_fail(ea, "amax");
+        FP8_TRY(fp8k::launch_scale(scale_out, n_groups(gran, rows, cols), format, pow2, scale_out, st));
+    } else if (ea != hipSuccess) {
+        return hip_fail(ea, "column scales");
+    }
     FP8_TRY(fp8k::launch_cast(x, rows, cols, ld, scale_out, gran, format, transpose, q, ld_out, q_plain, ld_plain, st));
     return FP8_OK;
 }
@@ -89,7 +94,6 @@ int quantize_row_col_impl(const void* x, int64_t rows, int64_t cols, int64_t ld,
         e = fp8k::launch_quant_row_colmax(x, rows, cols, ld, format, pow2, q_row, ld_row, scale_row, scale_col, q_col_t,
                                           (size_t)(cols - 1) * (size_t)ld_col_t + (size_t)rows, st);
     if (e == hipSuccess) {
-        FP8_TRY(fp8k::launch_scale(scale_col, cols, format, pow2, scale_col, st));
         FP8_TRY(fp8k::launch_cast(x, rows, cols, ld, scale_col, FP8_COL, format, 1, q_col_t, ld_col_t, nullptr, 0, st));
         return FP8_OK;
     }
@@ -349,21 +353,24 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
         return FP8_OK;
     }
     // rowwise: every operand re-quantized along the contraction axis of its GEMM
+    // (dX = dY W contracts over N, dW = dY^T X over M).  All quantizations first,
+    // then the GEMMs back to back.
     const bool both = dx && dw;
-    if (both)   // dY along N (rows) and along M (columns, transposed) from two reads instead of three
+    if (both) {   // dY along N (rows) and along M (columns, transposed) from two reads instead of three
         if (int rc = quantize_row_col_impl(dy, M, N, N, recipe->fmt_dy, fl, gq, N, sg, gqt, M, sgt, st)) return rc;
-    if (dx) {  // dX = dY W, contraction over N
-        if (!both)
-            if (int rc = quantize_impl(dy, M, N, N, FP8_ROW, recipe->fmt_dy, fl, gq, N, nullptr, 0, sg, st)) return rc;
+    } else if (dx) {
+        if (int rc = quantize_impl(dy, M, N, N, FP8_ROW, recipe->fmt_dy, fl, gq, N, nullptr, 0, sg, st)) return rc;
+    } else {
+        if (int rc = quantize_impl(dy, M, N, N, FP8_COL, recipe->fmt_dy, fl | T, gqt, M, nullptr, 0, sgt, st)) return rc;
+    }
+    if (dx)
         if (int rc = quantize_impl(w, N, K, K, FP8_COL, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st)) return rc;
-        FP8_TRY(fp8k::launch_gemm_fp8(gq, N, recipe->fmt_dy, sg, 1, wt, N, recipe->fmt_w, swt, 1, M, K, N, dx, K, 0, st));
-    }
-    if (dw) {  // dW = dY^T X, contraction over M
-        if (!both)
-            if (int rc = quantize_impl(dy, M, N, N, FP8_COL, recipe->fmt_dy, fl | T, gqt, M, nullptr, 0, sgt, st)) return rc;
+    if (dw)
         if (int rc = quantize_impl(x, M, K, K, FP8_COL, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st)) return rc;
+    if (dx)
+        FP8_TRY(fp8k::launch_gemm_fp8(gq, N, recipe->fmt_dy, sg, 1, wt, N, recipe->fmt_w, swt, 1, M, K, N, dx, K, 0, st));
+    if (dw)
         FP8_TRY(fp8k::launch_gemm_fp8(gqt, M, recipe->fmt_dy, sgt, 1, xt, M, recipe->fmt_x, sxt, 1, N, K, M, dw, K, 0, st));
-    }
     return FP8_OK;
 }
 

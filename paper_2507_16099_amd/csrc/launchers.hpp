@@ -11,10 +11,10 @@ hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st);
 hipError_t launch_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran, float* out,
                        hipStream_t st);
 
-// column amax of a tall matrix via a [G, cols] scratch matrix of partial maxima
-// (hipErrorNotSupported: shape does not suit it, use launch_amax)
-hipError_t launch_amax_cols_two_level(const void* x, int64_t rows, int64_t cols, int64_t ld, float* out,
-                                      void* scratch, size_t scratch_bytes, hipStream_t st);
+// per-column scales of a tall matrix via a [G, cols] scratch matrix of partial
+// maxima (hipErrorNotSupported: shape does not suit it, use launch_amax + launch_scale)
+hipError_t launch_col_scales_two_level(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, int flags,
+                                       float* scale_out, void* scratch, size_t scratch_bytes, hipStream_t st);
 
 hipError_t launch_scale(const float* amax, int64_t n, int fmt, int flags, float* out, hipStream_t st);
 
@@ -36,11 +36,11 @@ hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float
                            int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
                            hipStream_t st);
 
-// Rowwise quantization (codes q, scales scale_out) and the column maxima
-// amax_cols[c] = max_r |x[r, c]| from a single read of x; scratch holds the
-// first-level column maxima.  hipErrorNotSupported if the shape does not suit.
+// Rowwise quantization (codes q, scales scale_out) and the per-column scales
+// scale_cols[c] = scale(max_r |x[r, c]|) from a single read of x; scratch holds
+// the first-level column maxima.  hipErrorNotSupported if the shape does not suit.
 hipError_t launch_quant_row_colmax(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, int flags,
-                                   uint8_t* q, int64_t ld_out, float* scale_out, float* amax_cols, void* scratch,
+                                   uint8_t* q, int64_t ld_out, float* scale_out, float* scale_cols, void* scratch,
                                    size_t scratch_bytes, hipStream_t st);
 
 // 256 x 256 software-pipelined kernel (direct-to-LDS loads); same contract.

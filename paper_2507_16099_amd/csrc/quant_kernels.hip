@@ -198,11 +198,72 @@ __global__ __launch_bounds__(256) void colmax_partial_kernel(const uint16_t* __r
     if ((int)threadIdx.x < ntail) prow[(nvec << 3) + threadIdx.x] = (uint16_t)tail;
 }
 
-// Two-level column amax through a scratch matrix (at least G * ld_part
-// bfloat16, 16-byte aligned).  Returns hipErrorNotSupported if the shape does
-// not suit it (few rows, very wide rows): the caller then uses launch_amax.
-hipError_t launch_amax_cols_two_level(const void* x, int64_t rows, int64_t cols, int64_t ld, float* out,
-                                      void* scratch, size_t scratch_bytes, hipStream_t st) {
+// Column maxima, second level, and the scales in the same kernel: the [G, cols]
+// matrix of first-level magnitudes (G <= 1024) is small, so this is a latency
+// problem.  A block of 1024 threads owns 128 columns; thread (row group
+// t / 16, lane t % 16) folds rows t/16, t/16 + 64, ... of its 8 columns with
+// all of its (at most 16) loads in flight at once; the four row groups of a
+// wavefront combine by shuffles, the sixteen wavefronts through LDS, and 16
+// threads turn the 128 maxima into scales.  No atomics, nothing to zero first.
+__global__ __launch_bounds__(1024) void colmax_final_scale_kernel(const uint16_t* __restrict__ part, int G,
+                                                                   int64_t cols, int64_t ld_part, int fmt, int flags,
+                                                                   float* __restrict__ scale_out) {
+    const int tid = threadIdx.x, cl = tid & 15, rg = tid >> 4;
+    const int64_t c = (int64_t)blockIdx.x * 128 + cl * 8;
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    if (c < cols) {
+        const uint16_t* p = part + c;
+#pragma unroll 16
+        for (int g = rg; g < G; g += 64) {
+            const uint4 v = *reinterpret_cast<const uint4*>(p + (int64_t)g * ld_part);
+            acc.x = pk_absmax(acc.x, v.x);
+            acc.y = pk_absmax(acc.y, v.y);
+            acc.z = pk_absmax(acc.z, v.z);
+            acc.w = pk_absmax(acc.w, v.w);
+        }
+    }
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+        acc.x = pk_absmax(acc.x, (uint32_t)__shfl_xor((int)acc.x, off, 64));
+        acc.y = pk_absmax(acc.y, (uint32_t)__shfl_xor((int)acc.y, off, 64));
+        acc.z = pk_absmax(acc.z, (uint32_t)__shfl_xor((int)acc.z, off, 64));
+        acc.w = pk_absmax(acc.w, (uint32_t)__shfl_xor((int)acc.w, off, 64));
+    }
+    __shared__ uint4 sm[16][16];
+    if ((tid & 63) < 16) sm[tid >> 6][cl] = acc;
+    __syncthreads();
+    if (tid < 16 && c < cols) {
+#pragma unroll
+        for (int w = 1; w < 16; ++w) {
+            const uint4 o = sm[w][tid];
+            acc.x = pk_absmax(acc.x, o.x);
+            acc.y = pk_absmax(acc.y, o.y);
+            acc.z = pk_absmax(acc.z, o.z);
+            acc.w = pk_absmax(acc.w, o.w);
+        }
+        const uint32_t wds[4] = {acc.x, acc.y, acc.z, acc.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t mag = (wds[e >> 1] >> ((e & 1) * 16)) & 0x7FFFu;
+            if (c + e < cols) scale_out[c + e] = scale_from_amax(mag_to_float(mag), fmt, flags);
+        }
+    }
+}
+
+static hipError_t launch_colmax_final_scale(const uint16_t* part, int64_t G, int64_t cols, int64_t ld_part, int fmt,
+                                            int flags, float* scale_out, hipStream_t st) {
+    colmax_final_scale_kernel<<<dim3((unsigned)((cols + 127) / 128)), dim3(1024), 0, st>>>(part, (int)G, cols, ld_part, fmt,
+                                                                                         flags, scale_out);
+    return hipGetLastError();
+}
+
+// Per-column SCALES of a tall matrix in two levels through a scratch matrix (at
+// least G * ld_part bfloat16, 16-byte aligned): scale_out[c] =
+// scale(max_r |x[r, c]|).  Returns hipErrorNotSupported if the shape does not
+// suit it (few rows, very wide rows): the caller then uses launch_amax and
+// launch_scale.
+hipError_t launch_col_scales_two_level(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, int flags,
+                                       float* scale_out, void* scratch, size_t scratch_bytes, hipStream_t st) {
     const int64_t nvec = cols / 8;
     const int64_t ld_part = (cols + 7) / 8 * 8;
     int64_t G = 1024;
@@ -219,7 +280,7 @@ hipError_t launch_amax_cols_two_level(const void* x, int64_t rows, int64_t cols,
 #undef FP8K_CP
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_amax(part, G, cols, ld_part, GRAN_COL, out, st);
+    return launch_colmax_final_scale(part, G, cols, ld_part, fmt, flags, scale_out, st);
 }
 
 hipError_t launch_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran, float* out,
@@ -579,40 +640,42 @@ hipError_t launch_quant_row(const void* x, int64_t rows, int64_t cols, int64_t l
 // maxima of its own 8 * NV columns.  The block's column maxima go to row b of
 // a [G, cols] matrix of bfloat16 magnitudes, which amax_cols_kernel reduces;
 // the per-column cast then reads the tensor a second (and last) time.
-// The next row is requested before the current one is reduced.  The per-row
-// wave maxima alternate between two LDS slots, so one barrier per row is enough.
+// With up to four vectors per thread the next row is requested before the
+// current one is reduced; wider rows rely on the other resident blocks to keep
+// loads in flight (a second row in registers would halve the occupancy).  The
+// per-row wave maxima alternate between two LDS slots, so one barrier per row
+// is enough.
 template <int FMT, int NV>
 __global__ __launch_bounds__(256) void quant_row_colmax_kernel(const uint16_t* __restrict__ x, int64_t rows,
                                                                 int64_t cols, int64_t ld, int flags,
                                                                 uint8_t* __restrict__ q, int64_t ld_out,
                                                                 float* __restrict__ scale_out,
                                                                 uint16_t* __restrict__ part, int64_t ld_part) {
+    constexpr bool PREFETCH = NV <= 4;
     const int64_t nvec = cols >> 3;     // cols is a multiple of 8 (checked by the launcher)
     const int tid = threadIdx.x;
     __shared__ uint32_t red[2][4];
     uint4 cmax[NV], v[NV];
 #pragma unroll
     for (int j = 0; j < NV; ++j) cmax[j] = make_uint4(0, 0, 0, 0);
-    int64_t r = blockIdx.x;
-    if (r < rows) {
+    auto load_row = [&](int64_t r, uint4 (&dst)[NV]) {
         const uint4* rv = reinterpret_cast<const uint4*>(x + r * ld);
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
             const int64_t vi = tid + (int64_t)j * 256;
-            v[j] = vi < nvec ? rv[vi] : make_uint4(0, 0, 0, 0);
+            dst[j] = vi < nvec ? rv[vi] : make_uint4(0, 0, 0, 0);
         }
-    }
+    };
+    int64_t r = blockIdx.x;
+    if (PREFETCH && r < rows) load_row(r, v);
     int slot = 0;
     for (; r < rows; r += gridDim.x) {
         const int64_t rn = r + gridDim.x;
-        uint4 nv[NV];
-        if (rn < rows) {
-            const uint4* rv = reinterpret_cast<const uint4*>(x + rn * ld);
-#pragma unroll
-            for (int j = 0; j < NV; ++j) {
-                const int64_t vi = tid + (int64_t)j * 256;
-                nv[j] = vi < nvec ? rv[vi] : make_uint4(0, 0, 0, 0);
-            }
+        uint4 nv[PREFETCH ? NV : 1];
+        if constexpr (PREFETCH) {
+            if (rn < rows) load_row(rn, nv);
+        } else {
+            load_row(r, v);
         }
         uint32_t acc = 0;
 #pragma unroll
@@ -638,9 +701,11 @@ __global__ __launch_bounds__(256) void quant_row_colmax_kernel(const uint16_t* _
             const int64_t vi = tid + (int64_t)j * 256;
             if (vi < nvec) store_stream(reinterpret_cast<uint2*>(dst) + vi, cast8<FMT>(v[j], s));
         }
-        if (rn < rows) {
+        if constexpr (PREFETCH) {
+            if (rn < rows) {
 #pragma unroll
-            for (int j = 0; j < NV; ++j) v[j] = nv[j];
+                for (int j = 0; j < NV; ++j) v[j] = nv[j];
+            }
         }
     }
     uint16_t* prow = part + (int64_t)blockIdx.x * ld_part;
@@ -651,24 +716,42 @@ __global__ __launch_bounds__(256) void quant_row_colmax_kernel(const uint16_t* _
     }
 }
 
-// Rowwise codes + scales of x, and amax_cols[c] = max_r |x[r, c]|, from one read
-// of x.  scratch: at least 256 * round_up(cols, 8) * 2 bytes, 16-byte aligned
-// (more lets more blocks run).  hipErrorNotSupported if the shape does not suit
+// number of blocks of the kernel that the device keeps resident at once
+template <typename K>
+static int resident_blocks(K kernel) {
+    int per_cu = 0, dev = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess) return 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    return per_cu * cus;
+}
+
+// Rowwise codes + scales of x, and the per-column scales scale_cols[c] =
+// scale(max_r |x[r, c]|), from one read of x.  scratch: at least 128 * cols * 2 bytes, 16-byte aligned (more lets
+// more blocks run).  hipErrorNotSupported if the shape does not suit
 // (cols not a multiple of 8, rows too few or too wide for registers).
 hipError_t launch_quant_row_colmax(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, int flags,
-                                   uint8_t* q, int64_t ld_out, float* scale_out, float* amax_cols, void* scratch,
+                                   uint8_t* q, int64_t ld_out, float* scale_out, float* scale_cols, void* scratch,
                                    size_t scratch_bytes, hipStream_t st) {
     const int64_t nvec = cols / 8;
     if (cols % 8 != 0 || nvec > 256 * 16 || nvec < 64) return hipErrorNotSupported;
     const int64_t ld_part = cols;
-    int64_t G = 1024;
-    while (G >= 256 && (rows < 8 * G || (size_t)(G * ld_part * 2) > scratch_bytes)) G /= 2;
-    if (G < 256) return hipErrorNotSupported;
     const uint16_t* xp = static_cast<const uint16_t*>(x);
     uint16_t* part = static_cast<uint16_t*>(scratch);
+    // G blocks, all resident at once (a second, partly filled round of blocks would
+    // idle most of the chip), each with at least 8 rows, G rows of scratch
+    int64_t G = 0;
 #define FP8K_QRC(FMT, NV)                                                                                     \
-    quant_row_colmax_kernel<FMT, NV><<<dim3((unsigned)G), dim3(256), 0, st>>>(xp, rows, cols, ld, flags, q, ld_out, \
-                                                                              scale_out, part, ld_part)
+    do {                                                                                                      \
+        static int resident = -1;   /* per kernel; a race only repeats the query */                           \
+        if (resident < 0) resident = resident_blocks(quant_row_colmax_kernel<FMT, NV>);                        \
+        G = resident < 1024 ? resident : 1024;                                                                \
+        if (G > rows / 8) G = rows / 8;                                                                       \
+        if ((size_t)(G * ld_part * 2) > scratch_bytes) G = (int64_t)(scratch_bytes / (size_t)(ld_part * 2));  \
+        if (G < 128) return hipErrorNotSupported;                                                             \
+        quant_row_colmax_kernel<FMT, NV><<<dim3((unsigned)G), dim3(256), 0, st>>>(xp, rows, cols, ld, flags, q, ld_out, \
+                                                                                  scale_out, part, ld_part);  \
+    } while (0)
 #define FP8K_QRC_NV(FMT)                 \
     if (nvec <= 256) FP8K_QRC(FMT, 1);   \
     else if (nvec <= 512) FP8K_QRC(FMT, 2);  \
@@ -681,7 +764,7 @@ hipError_t launch_quant_row_colmax(const void* x, int64_t rows, int64_t cols, in
 #undef FP8K_QRC
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_amax(part, G, cols, ld_part, GRAN_COL, amax_cols, st);
+    return launch_colmax_final_scale(part, G, cols, ld_part, fmt, flags, scale_cols, st);
 }
 
 

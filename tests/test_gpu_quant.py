@@ -154,7 +154,8 @@ def test_quantize_zero_rows_and_outliers():
     (2500, 4104, 4104),      # partly filled last vector column
     (2050, 14336, 14336),    # benchmark row length (8 vectors per thread)
     (2048, 16392, 16392),    # 16 vectors per thread
-    (100, 200, 200), (3000, 100, 104), (2048, 8, 8), (2047, 512, 512),   # shapes served by the separate passes
+    (2047, 512, 512),        # fewer blocks than the device could hold
+    (100, 200, 200), (3000, 100, 104), (2048, 8, 8), (1000, 512, 512),   # shapes served by the separate passes
 ])
 def test_quantize_row_and_column_in_two_reads(rows, cols, ld):
     """fp8_quantize_row_col == rowwise quantization + per-column transposed
