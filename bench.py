@@ -59,6 +59,96 @@ def _profiled_traffic(workload: str):
     return None
 
 
+def _sweep(torch, fp8, dev, iters: int) -> dict:
+    """When is the fp8 linear faster than bf16 (Section 2.1 and the appendix on
+    microbenchmarks)?  Forward + backward of one linear layer, dynamic
+    quantization included, against the same three products in bf16 by the
+    vendor BLAS, over a grid of forward shapes.  Linear layer only (no
+    normalisation / activation around it)."""
+    rows = []
+    sizes = (1024, 2048, 4096, 8192, 16384)
+    for M in (1024, 4096, 16384):
+        for K in sizes:
+            for N in sizes:
+                x = torch.randn((M, K), device=dev).to(torch.bfloat16)
+                w = (torch.randn((N, K), device=dev) * 0.02).to(torch.bfloat16)
+                dy = (torch.randn((M, N), device=dev) * 1e-3).to(torch.bfloat16)
+                y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+                dx = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+                dw = torch.empty((N, K), dtype=torch.bfloat16, device=dev)
+
+                def bf16_step():
+                    torch.matmul(x, w.t(), out=y)
+                    torch.matmul(dy, w, out=dx)
+                    torch.matmul(dy.t(), x, out=dw)
+                entry = {"M": M, "K": K, "N": N, "bf16_ms": round(_event_time_ms(bf16_step, iters, 2, torch), 4)}
+                for tag, gran in (("rowwise", fp8.FP8_ROW), ("tensorwise", fp8.FP8_TENSOR)):
+                    r = fp8.Recipe(gran=gran)
+                    wf = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, False), dtype=torch.uint8, device=dev)
+                    wb = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, True), dtype=torch.uint8, device=dev)
+
+                    def fp8_step():
+                        fp8.fp8_linear_fwd(x, w, r, y=y, workspace=wf)
+                        fp8.fp8_linear_bwd(dy, x, w, r, dx=dx, dw=dw, workspace=wb)
+                    ms = _event_time_ms(fp8_step, iters, 2, torch)
+                    entry[f"fp8_{tag}_ms"] = round(ms, 4)
+                    entry[f"speedup_{tag}"] = round(entry["bf16_ms"] / ms, 3)
+                    entry[f"fp8_{tag}_TFLOP/s"] = round(6.0 * M * N * K / (ms * 1e-3) / 1e12, 1)
+                rows.append(entry)
+                del x, w, dy, y, dx, dw
+    return {"sweep": "fp8 linear fwd+bwd (quantization included) vs bf16 torch.matmul x3, one MI355X",
+            "iters": iters, "rows": rows}
+
+
+def _decode(torch, fp8, dev, iters: int) -> dict:
+    """Inference with weights quantized once (Section 3: dynamic activation +
+    weight FP8 quantization, per row), few tokens per step: the GEMM streams the
+    weight once, so the roofline is HBM (N*K bytes per launch).  Weights rotate
+    through > 1.5 GB of copies, as the layers of a model would, so that nothing
+    is served from the last-level cache.  bf16 comparator: torch.matmul."""
+    rows = []
+    shapes = (("llama3_8b_qkv", 6144, 4096), ("llama3_8b_o", 4096, 4096), ("llama3_8b_ffn_up", 14336, 4096),
+              ("llama3_8b_ffn_down", 4096, 14336), ("llama3_70b_ffn_up", 28672, 8192), ("llama3_70b_ffn_down", 8192, 28672))
+    E4, ROW = fp8.FP8_E4M3FN, fp8.FP8_ROW
+    for name, N, K in shapes:
+        ncopy = max(2, -(-1_600_000_000 // (N * K)))
+        ws = [(torch.randn((N, K), device=dev) * 0.02).to(torch.bfloat16) for _ in range(ncopy)]
+        q = [fp8.fp8_quantize(w, ROW, E4) for w in ws]
+        for M in (1, 8, 16, 32):
+            x = torch.randn((M, K), device=dev).to(torch.bfloat16)
+            y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+            wsp = torch.empty(fp8.fp8_linear_prequantized_workspace_bytes(M, K), dtype=torch.uint8, device=dev)
+            xq, sx = fp8.fp8_quantize(x, ROW, E4)
+            st = {"i": 0}
+
+            def full():
+                i = st["i"] = (st["i"] + 1) % len(q)
+                fp8.fp8_linear_fwd_prequantized(x, q[i][0], E4, q[i][1], ROW, E4, ROW, 0, y=y, workspace=wsp)
+
+            def gemm():
+                i = st["i"] = (st["i"] + 1) % len(q)
+                fp8.fp8_scaled_mm(xq, E4, sx, ROW, q[i][0], E4, q[i][1], ROW, 0, out=y)
+
+            def bf16():
+                i = st["i"] = (st["i"] + 1) % len(ws)
+                torch.matmul(x, ws[i].t(), out=y)
+            t_full = _event_time_ms(full, iters, len(q), torch)
+            t_gemm = _event_time_ms(gemm, iters, len(q), torch)
+            t_bf16 = _event_time_ms(bf16, iters, len(ws), torch)
+            gbs = N * K / (t_gemm * 1e-3) / 1e9
+            rows.append({"layer": name, "M": M, "N": N, "K": K, "fp8_linear_us": round(t_full * 1e3, 2),
+                         "fp8_gemm_us": round(t_gemm * 1e3, 2), "weight_stream_GB/s": round(gbs, 1),
+                         "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "bf16_matmul_us": round(t_bf16 * 1e3, 2),
+                         "speedup_vs_bf16": round(t_bf16 / t_full, 3)})
+        del ws, q
+        torch.cuda.empty_cache()
+    return {"decode": "fp8_linear_fwd_prequantized (rowwise activations and weights) vs torch.matmul bf16, one MI355X; "
+                      "both cycle through > 1.6 GB of fp8 weight copies (and their bf16 originals)",
+            "roofline": {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "algorithmic_bytes_per_launch": "N*K weight bytes"},
+            "iters": iters, "rows": rows}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -68,6 +158,11 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-legs", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=2048)
+    ap.add_argument("--sweep", action="store_true",
+                    help="fp8 vs bf16 linear fwd+bwd over a grid of (M, K, N); prints a JSON table and exits")
+    ap.add_argument("--decode", action="store_true",
+                    help="inference with pre-quantized weights at decode batch sizes (weight-streaming GEMM); "
+                         "prints a JSON table and exits")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="launch a 1 GiB device copy and every kernel of the step twice, then exit "
                          "(run under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`)")
@@ -90,6 +185,14 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+
+    if args.sweep:
+        print(json.dumps(_sweep(torch, fp8, dev, max(5, args.steps // 2))))
+        return 0
+
+    if args.decode:
+        print(json.dumps(_decode(torch, fp8, dev, max(10, args.steps))))
+        return 0
 
     wl = si.WORKLOADS[args.workload or si.BENCH_WORKLOAD]
     M, K, N = wl.M, wl.K, wl.N

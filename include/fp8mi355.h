@@ -182,6 +182,25 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
                    const fp8_recipe* recipe, void* dx, void* dw, void* workspace,
                    size_t workspace_bytes, void* stream);
 
+/*
+ * inference-style forward with a weight that was quantized ONCE beforehand
+ * (Section 3: float8 dynamic activation + float8 weight quantization, per
+ * tensor or per row):  Y = X W^T with
+ *   wq [N, K] fp8 codes (format fmt_w, leading dimension ldw) and scale_w
+ *   ([1] for gran_w == FP8_TENSOR, [N] for FP8_ROW), e.g. from fp8_quantize;
+ *   x [M, K] bfloat16 (dense rows), quantized dynamically inside the call with
+ *   granularity gran_x (TENSOR | ROW) to format fmt_x; flags: FP8_POW2_SCALE
+ *   (for the activation scales).  y [M, N] bfloat16, leading dimension ld_y.
+ * workspace: fp8_linear_prequantized_workspace_bytes(M, K) bytes, 256-byte
+ * aligned (activation codes and scales).  With few rows (M <= 32, decoding) the
+ * GEMM streams wq once and is bound by that HBM read.
+ */
+size_t fp8_linear_prequantized_workspace_bytes(int64_t M, int64_t K);
+int fp8_linear_fwd_prequantized(const void* x, int64_t M, int64_t K, int fmt_x, int gran_x, int flags,
+                                const uint8_t* wq, int64_t ldw, int fmt_w, const float* scale_w, int gran_w,
+                                int64_t N, void* y, int64_t ld_y, void* workspace, size_t workspace_bytes,
+                                void* stream);
+
 #ifdef __cplusplus
 }
 #endif

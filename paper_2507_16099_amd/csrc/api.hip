@@ -374,4 +374,43 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
     return FP8_OK;
 }
 
+size_t fp8_linear_prequantized_workspace_bytes(int64_t M, int64_t K) {
+    g_err[0] = 0;
+    if (M < 0 || K < 0 || M > kMaxDim || K > kMaxDim) {
+        fail(FP8_ERR_SHAPE, "fp8_linear_prequantized_workspace_bytes: M=%lld K=%lld out of range", (long long)M, (long long)K);
+        return 0;
+    }
+    return align_up((size_t)M * (size_t)K, 256) + align_up(sizeof(float) * (size_t)(M > 0 ? M : 1), 256) + 256;
+}
+
+int fp8_linear_fwd_prequantized(const void* x, int64_t M, int64_t K, int fmt_x, int gran_x, int flags, const uint8_t* wq,
+                                int64_t ldw, int fmt_w, const float* scale_w, int gran_w, int64_t N, void* y,
+                                int64_t ld_y, void* workspace, size_t workspace_bytes, void* stream) {
+    g_err[0] = 0;
+    const char* fn = "fp8_linear_fwd_prequantized";
+    if (!fmt_ok(fmt_x) || !fmt_ok(fmt_w)) return fail(FP8_ERR_ENUM, "%s: unknown fp8 format", fn);
+    if ((gran_x != FP8_TENSOR && gran_x != FP8_ROW) || (gran_w != FP8_TENSOR && gran_w != FP8_ROW))
+        return fail(FP8_ERR_ENUM, "%s: granularity must be FP8_TENSOR or FP8_ROW", fn);
+    if (flags & ~FP8_POW2_SCALE) return fail(FP8_ERR_ENUM, "%s: flags=%d has unknown bits", fn, flags);
+    if (M < 0 || K < 0 || N < 0 || M > kMaxDim || K > kMaxDim || N > kMaxDim)
+        return fail(FP8_ERR_SHAPE, "%s: M=%lld K=%lld N=%lld out of range", fn, (long long)M, (long long)K, (long long)N);
+    if (K % 16 != 0) return fail(FP8_ERR_SHAPE, "%s: K=%lld must be a multiple of 16", fn, (long long)K);
+    if (ldw < K || ld_y < N) return fail(FP8_ERR_SHAPE, "%s: leading dimension too small", fn);
+    if (int rc = check_bf16(fn, x, M, K, K)) return rc;
+    if (M == 0 || N == 0) return FP8_OK;
+    if (!y || !workspace || !scale_w || (K > 0 && !wq)) return fail(FP8_ERR_NULL, "%s: NULL pointer", fn);
+    if (!aligned(y, 16) || !aligned(wq, 16) || !aligned(workspace, 256) || !aligned(scale_w, 4))
+        return fail(FP8_ERR_ALIGN, "%s: y, wq (16) / workspace (256) / scale_w (4) misaligned", fn);
+    if (ldw % 16 != 0 || ld_y % 8 != 0) return fail(FP8_ERR_ALIGN, "%s: ldw %% 16 and ld_y %% 8 must be 0", fn);
+    const size_t need = fp8_linear_prequantized_workspace_bytes(M, K);
+    if (workspace_bytes < need) return fail(FP8_ERR_WORKSPACE, "%s: workspace %zu < %zu bytes", fn, workspace_bytes, need);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t* xq = static_cast<uint8_t*>(workspace);
+    float* sx = reinterpret_cast<float*>(xq + align_up((size_t)M * (size_t)K, 256));
+    if (int rc = quantize_impl(x, M, K, K, gran_x, fmt_x, flags, xq, K, nullptr, 0, sx, st)) return rc;
+    FP8_TRY(fp8k::launch_gemm_fp8(xq, K, fmt_x, sx, gran_x == FP8_ROW, wq, ldw, fmt_w, scale_w, gran_w == FP8_ROW, M, N, K, y,
+                                  ld_y, 0, st));
+    return FP8_OK;
+}
+
 }  // extern "C"

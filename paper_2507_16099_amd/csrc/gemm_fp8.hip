@@ -234,24 +234,29 @@ static hipError_t launch_fmt(int variant, const uint8_t* a, int64_t lda, const f
                              void* out, int64_t ld_out, hipStream_t st) {
     if (variant == 2)
         return launch_variant<256, 256, 2, 2, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
-    if (variant == 1 || variant == 3 || variant == 4)
+    if (variant == 1 || variant >= 3)
         return launch_variant<256, 256, 2, 4, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
     return launch_variant<128, 128, 2, 2, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
 }
 
-// Kernel choice: problems with at least one 256 x 256 tile per CU take the
-// 16x16x128 "snake" kernel (variant 4, gemm_fp8_snake.hip), smaller ones the
-// 128 x 128 tile of this file (more workgroups).  FP8MI355_GEMM_VARIANT=0..4
-// overrides (tuning and test aid): 0 = 128x128 / 4 waves, 1 = 256x256 / 8
-// waves, 2 = 256x256 / 4 waves (all register-staged), 3 = pipelined 32x32x64
-// (gemm_fp8_pipelined.hip), 4 = snake.
+// Kernel choice: the few-row kernel of gemm_fp8_skinny.hip (variant 5) for
+// M <= 32 (measured 2-7x faster there; from 33 to 64 rows its loads of A
+// through the L1 cache cost as much as the tiled kernels' padding); otherwise the 16x16x128 "snake" kernel (variant 4,
+// gemm_fp8_snake.hip) as soon as its 256 x 256 tiles keep more than a quarter
+// of the CUs busy (measured: equal to the 128 x 128 tile of this file at 64
+// tiles, 10-80 % faster from 96 tiles on), and the 128 x 128 tile (more
+// workgroups) below that.  FP8MI355_GEMM_VARIANT=0..5 overrides (tuning and
+// test aid): 0 = 128x128 / 4 waves, 1 = 256x256 / 8 waves, 2 = 256x256 / 4
+// waves (all register-staged), 3 = pipelined 32x32x64
+// (gemm_fp8_pipelined.hip), 4 = snake, 5 = few-row kernel (only where M <= 64).
 static int pick_variant(int64_t M, int64_t N) {
     if (const char* e = std::getenv("FP8MI355_GEMM_VARIANT")) {
         const int v = std::atoi(e);
-        if (v >= 0 && v <= 4) return v;
+        if (v >= 0 && v <= 5) return v;
     }
+    if (M <= 32) return 5;
     const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
-    return tiles256 >= 256 ? 4 : 0;
+    return tiles256 > 64 ? 4 : 0;
 }
 
 hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
@@ -260,6 +265,9 @@ hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float
                            hipStream_t st) {
     if (M == 0 || N == 0) return hipSuccess;
     const int v = pick_variant(M, N);
+    if (v == 5 && M <= 64 && K > 0)
+        return launch_gemm_fp8_skinny(a, lda, fmt_a, scale_a, row_a, b, ldb, fmt_b, scale_b, row_b, M, N, K, out, ld_out,
+                                      out_f32, st);
     if (v == 4 && gemm_fp8_pipelined_supported(lda, ldb))
         return launch_gemm_fp8_snake(a, lda, fmt_a, scale_a, row_a, b, ldb, fmt_b, scale_b, row_b, M, N, K, out, ld_out,
                                      out_f32, st);

@@ -56,4 +56,12 @@ hipError_t launch_gemm_fp8_snake(const uint8_t* a, int64_t lda, int fmt_a, const
                                  int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
                                  hipStream_t st);
 
+// few rows of A (M <= 64, the decode shape of inference): B is streamed once
+// from HBM by wavefronts that load their MFMA operands straight from global
+// memory; same contract otherwise.
+hipError_t launch_gemm_fp8_skinny(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
+                                  const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int row_b,
+                                  int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
+                                  hipStream_t st);
+
 }  // namespace fp8k

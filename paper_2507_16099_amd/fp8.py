@@ -79,6 +79,11 @@ def load_library() -> C.CDLL:
     L.fp8_linear_workspace_bytes.argtypes = [i64, i64, i64, C.POINTER(_CRecipe), ci]
     L.fp8_linear_fwd.restype = ci
     L.fp8_linear_fwd.argtypes = [vp, vp, i64, i64, i64, C.POINTER(_CRecipe), vp, vp, C.c_size_t, vp]
+    L.fp8_linear_prequantized_workspace_bytes.restype = C.c_size_t
+    L.fp8_linear_prequantized_workspace_bytes.argtypes = [i64, i64]
+    L.fp8_linear_fwd_prequantized.restype = ci
+    L.fp8_linear_fwd_prequantized.argtypes = [vp, i64, i64, ci, ci, ci, vp, i64, ci, vp, ci, i64, vp, i64, vp,
+                                              C.c_size_t, vp]
     L.fp8_linear_bwd.restype = ci
     L.fp8_linear_bwd.argtypes = [vp, vp, vp, i64, i64, i64, C.POINTER(_CRecipe), vp, vp, vp, C.c_size_t, vp]
     _lib = L
@@ -244,3 +249,28 @@ def fp8_linear_bwd(dy: torch.Tensor, x: torch.Tensor, w: torch.Tensor, recipe: R
     _check(load_library().fp8_linear_bwd(_ptr(dy), _ptr(x), _ptr(w), M, K, N, C.byref(r), _ptr(dx), _ptr(dw),
                                          _ptr(workspace), workspace.numel(), _stream()))
     return dx, dw
+
+
+def fp8_linear_prequantized_workspace_bytes(M: int, K: int) -> int:
+    n = load_library().fp8_linear_prequantized_workspace_bytes(M, K)
+    if n == 0:
+        raise Fp8Error(-2, fp8_last_error())
+    return n
+
+
+def fp8_linear_fwd_prequantized(x: torch.Tensor, wq: torch.Tensor, fmt_w: int, scale_w: torch.Tensor, gran_w: int,
+                                fmt_x: int = FP8_E4M3FN, gran_x: int = FP8_ROW, flags: int = 0,
+                                y: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Y = X W^T with a weight quantized beforehand (codes wq [N, K], scales scale_w) and x quantized per call."""
+    M, K, ldx = _mat(x, 2)
+    N, Kw, ldw = _mat(wq, 1)
+    assert K == Kw and ldx == K, (x.shape, wq.shape)
+    if y is None:
+        y = torch.empty((M, (N + 7) // 8 * 8), dtype=torch.bfloat16, device=x.device)[:, :N]
+    _, _, ld_y = _mat(y, 2)
+    if workspace is None:
+        workspace = torch.empty(fp8_linear_prequantized_workspace_bytes(M, K), dtype=torch.uint8, device=x.device)
+    _check(load_library().fp8_linear_fwd_prequantized(_ptr(x), M, K, fmt_x, gran_x, flags, _ptr(wq), ldw, fmt_w,
+                                                      _ptr(scale_w), gran_w, N, _ptr(y), ld_y, _ptr(workspace),
+                                                      workspace.numel(), _stream()))
+    return y

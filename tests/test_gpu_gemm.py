@@ -123,6 +123,46 @@ def test_many_tiles_per_workgroup_exact(big_variant, M, N, K):
     assert (got32[rows] == want.out32).all()
 
 
+SKINNY = [(1, 16, 16), (1, 4096, 4096), (5, 100, 400), (16, 1000, 2048), (17, 24, 128), (33, 4104, 1040),
+          (64, 14336, 4096), (48, 2048, 8208), (8, 300, 144), (32, 8208, 272), (20, 12304, 144), (32, 14336, 4096)]
+
+
+@pytest.mark.parametrize("M,N,K", SKINNY)
+def test_few_rows_exact_on_small_integers(M, N, K):
+    """M <= 64 takes the kernel that streams B once (the decode shape of
+    inference with pre-quantized weights): every K split and every count of
+    16-row groups, exact on small integers, padded leading dimensions."""
+    rng = np.random.default_rng(M * 11 + N + K)
+    ai = rng.integers(-2, 3, size=(M, K))
+    bi = rng.integers(-2, 3, size=(N, K))
+    for fa, fb in ((orc.E4M3FN, orc.E4M3FN), (orc.E5M2, orc.E4M3FN), (orc.E4M3FN, orc.E5M2)):
+        a = orc.encode_array((ai * 0.5).astype(np.float32), fa)
+        b = orc.encode_array((bi * 4.0).astype(np.float32), fb)
+        sa = (2.0 ** rng.integers(-3, 4, size=M)).astype(np.float32)
+        sb = (2.0 ** rng.integers(-3, 4, size=N)).astype(np.float32)
+        want = orc.scaled_mm(a, fa, sa, orc.ROW, b, fb, sb, orc.ROW)
+        lda, ldb = (K + 15) // 16 * 16 + 16, (K + 15) // 16 * 16 + 32
+        got32 = host_f32(_run(a, fa, sa, fp8.FP8_ROW, b, fb, sb, fp8.FP8_ROW, fp8.FP8_OUT_FP32, lda, ldb))
+        assert (got32 == want.out32).all(), (M, N, K, fa, fb, np.argwhere(got32 != want.out32)[:4])
+        got16 = host_bf16_bits(_run(a, fa, sa, fp8.FP8_ROW, b, fb, sb, fp8.FP8_ROW, 0, lda, ldb))
+        assert (got16 == want.out16).all(), (M, N, K, fa, fb)
+
+
+@pytest.mark.parametrize("M,N,K", SKINNY)
+@pytest.mark.parametrize("ga,gb", [(orc.TENSOR, orc.TENSOR), (orc.ROW, orc.ROW), (orc.ROW, orc.TENSOR)])
+def test_few_rows_random_codes_within_tolerance(M, N, K, ga, gb):
+    rng = np.random.default_rng(M + 3 * N + K)
+    a, b = _rand_codes((M, K), orc.E4M3FN, rng), _rand_codes((N, K), orc.E4M3FN, rng)
+    sa = rng.uniform(0.5, 300, 1 if ga == orc.TENSOR else M).astype(np.float32)
+    sb = rng.uniform(0.5, 300, 1 if gb == orc.TENSOR else N).astype(np.float32)
+    want = orc.scaled_mm(a, orc.E4M3FN, sa, ga, b, orc.E4M3FN, sb, gb)
+    got32 = host_f32(_run(a, orc.E4M3FN, sa, ga, b, orc.E4M3FN, sb, gb, fp8.FP8_OUT_FP32))
+    got16 = si.bf16_bits_to_f32(host_bf16_bits(_run(a, orc.E4M3FN, sa, ga, b, orc.E4M3FN, sb, gb)))
+    assert orc.rel_frobenius(got32, want.out32) <= TOL
+    assert orc.rel_frobenius(got16, si.bf16_bits_to_f32(want.out16)) <= TOL
+    assert orc.rel_frobenius(got32, want.acc64) <= TOL
+
+
 def test_padded_leading_dimensions_and_output_view(variant):
     rng = np.random.default_rng(3)
     M, N, K = 70, 90, 160

@@ -189,3 +189,69 @@ def test_full_size_outlier_stress_rowwise_vs_tensorwise():
     r, t = stats["c5_outlier_rowwise"], stats["c5_outlier_tensorwise"]
     assert t.n_zero > 5 * max(1, r.n_zero) and r.sqnr_db > t.sqnr_db
     assert r.n_sat <= 4096 and t.n_sat <= 1     # only amax elements can be clamped under dynamic scaling
+
+
+# ------------------------------------------------ inference: weight quantized once
+
+@pytest.mark.parametrize("M", [1, 7, 16, 32, 33, 300])
+@pytest.mark.parametrize("K,N", [(512, 384), (4096, 1000), (1040, 4104)])
+@pytest.mark.parametrize("gran", [orc.ROW, orc.TENSOR])
+def test_forward_with_prequantized_weight(M, K, N, gran):
+    """Weight codes and scales produced once (here by the library's own
+    fp8_quantize, checked against the oracle), activations quantized per call:
+    few rows take the kernel that streams the weight once, more rows the tiled
+    kernels; both must agree with the oracle's forward."""
+    wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)
+    x, w = wl.x(), wl.w()
+    ggran = fp8.FP8_ROW if gran == orc.ROW else fp8.FP8_TENSOR
+    wq, sw = fp8.fp8_quantize(dev_bf16(w), ggran, fp8.FP8_E4M3FN)
+    owq, osw = orc.quantize(w, gran, orc.E4M3FN)
+    assert (wq.cpu().numpy() == owq).all() and (sw.cpu().numpy().view(np.uint32) == osw.view(np.uint32)).all()
+    y = fp8.fp8_linear_fwd_prequantized(dev_bf16(x), wq, fp8.FP8_E4M3FN, sw, ggran, fp8.FP8_E4M3FN, ggran)
+    want, _, _ = orc.linear_fwd(x, w, orc.Recipe(gran=gran))
+    _cmp(y, want, min_identical=0.95)
+
+
+def test_prequantized_forward_exact_on_integers_and_mixed_granularity():
+    """Small integers and power-of-two scales: bit-exact; per-tensor weight scale
+    with per-row activation scales (the two granularities are independent)."""
+    rng = np.random.default_rng(5)
+    M, K, N = 9, 640, 264
+    xi = rng.integers(-3, 4, size=(M, K))
+    wi = rng.integers(-3, 4, size=(N, K))
+    x = si.f32_to_bf16_bits((xi * 2.0).astype(np.float32))
+    w = si.f32_to_bf16_bits((wi * 0.25).astype(np.float32))
+    wq, sw = fp8.fp8_quantize(dev_bf16(w), fp8.FP8_TENSOR, fp8.FP8_E4M3FN, fp8.FP8_POW2_SCALE)
+    y = fp8.fp8_linear_fwd_prequantized(dev_bf16(x), wq, fp8.FP8_E4M3FN, sw, fp8.FP8_TENSOR, fp8.FP8_E4M3FN, fp8.FP8_ROW,
+                                        fp8.FP8_POW2_SCALE)
+    exact = (xi @ wi.T).astype(np.float32) * 0.5
+    rows_all_zero = ~xi.any(axis=1)
+    assert not rows_all_zero.any()
+    assert (host_bf16_bits(y) == orc.f32_to_bf16(exact)).all()
+
+
+def test_prequantized_forward_rejects_bad_arguments():
+    x = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda")
+    wq = torch.zeros((32, 64), dtype=torch.uint8, device="cuda")
+    sw = torch.ones(32, device="cuda")
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_linear_fwd_prequantized(x, wq, 5, sw, fp8.FP8_ROW)
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_linear_fwd_prequantized(x, wq, fp8.FP8_E4M3FN, sw, fp8.FP8_COL)
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_linear_fwd_prequantized(x, wq, fp8.FP8_E4M3FN, sw, fp8.FP8_ROW,
+                                        workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    y = fp8.fp8_linear_fwd_prequantized(x[:0], wq, fp8.FP8_E4M3FN, sw, fp8.FP8_ROW)
+    assert y.shape == (0, 32)
+
+
+def test_full_size_decode_step_llama_ffn_weight():
+    """Decode batch of 16 tokens against the full Llama-3-8B FFN up-projection
+    weight [14336, 4096], rowwise scales: the whole output against the oracle."""
+    wl = si.WORKLOADS[si.BENCH_WORKLOAD]
+    w = wl.w()
+    x = si.scaled_down(wl, 16, wl.K, wl.N).x()
+    wq, sw = fp8.fp8_quantize(dev_bf16(w), fp8.FP8_ROW, fp8.FP8_E4M3FN)
+    y = fp8.fp8_linear_fwd_prequantized(dev_bf16(x), wq, fp8.FP8_E4M3FN, sw, fp8.FP8_ROW)
+    want, _, _ = orc.linear_fwd(x, w, orc.Recipe(gran=orc.ROW))
+    _cmp(y, want)
