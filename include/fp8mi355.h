@@ -54,7 +54,8 @@ enum fp8_gran { FP8_TENSOR = 0, FP8_ROW = 1, FP8_COL = 2 };
 enum fp8_flags {
     FP8_POW2_SCALE    = 1, /* round the scale down to a power of two            */
     FP8_TRANSPOSE_OUT = 2, /* fp8_cast / fp8_quantize write q[c, r] not q[r, c] */
-    FP8_OUT_FP32      = 4  /* fp8_scaled_mm writes fp32 instead of bfloat16     */
+    FP8_OUT_FP32      = 4, /* fp8_scaled_mm writes fp32 instead of bfloat16     */
+    FP8_GRAD_WEIGHT_HP = 8 /* recipe flag: dW is computed in bfloat16, not FP8  */
 };
 
 enum fp8_status {
@@ -148,7 +149,9 @@ int fp8_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a
 
 /* Recipe of a linear layer (Appendix A): gran is FP8_TENSOR ("tensorwise") or
  * FP8_ROW ("rowwise": every operand scaled along the contraction axis of the
- * GEMM it feeds).  flags: FP8_POW2_SCALE. */
+ * GEMM it feeds).  flags: FP8_POW2_SCALE, FP8_GRAD_WEIGHT_HP (with FP8_ROW this
+ * is the "rowwise_gw_hp" recipe: the forward and dX run in FP8, the weight
+ * gradient dW = dY^T X is computed from the unquantized bfloat16 tensors). */
 typedef struct fp8_recipe {
     int gran;
     int fmt_x;  /* format of activations, normally FP8_E4M3FN */
@@ -181,6 +184,16 @@ int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N
 int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int64_t K, int64_t N,
                    const fp8_recipe* recipe, void* dx, void* dw, void* workspace,
                    size_t workspace_bytes, void* stream);
+
+/*
+ * weight gradient in high precision (Appendix A, rowwise_gw_hp: the grad_weight
+ * GEMM kept in bfloat16):  dw[n, k] = sum_m dy[m, n] * x[m, k]
+ *   dy [M, N] and x [M, K] bfloat16, dense rows; products and sums in fp32 on
+ *   the bfloat16 matrix cores; dw [N, K] bfloat16 (round to nearest even).
+ *   K and N multiples of 8; M arbitrary.  This is what fp8_linear_bwd runs for dW
+ *   when the recipe carries FP8_GRAD_WEIGHT_HP.
+ */
+int fp8_grad_weight_hp(const void* dy, const void* x, int64_t M, int64_t K, int64_t N, void* dw, void* stream);
 
 /*
  * inference-style forward with a weight that was quantized ONCE beforehand

@@ -295,6 +295,17 @@ def linear_bwd_dw(dy, x, recipe: Recipe, rows=None):
     return _mm(go, xo, rows), go, xo
 
 
+def linear_bwd_dw_hp(dy, x, rows=None):
+    """Weight gradient of the rowwise_gw_hp recipe (Appendix A: the grad_weight
+    GEMM stays in bfloat16): dW[n,k] = sum_m dY[m,n] X[m,k] on the unquantized
+    inputs.  The definition written out: binary64 sums of the exact products
+    (orc_bf16_mm_f64 on the transposed operands), rounded to binary32 and then
+    to bfloat16.  Returns (out32, out16); rows selects output rows n."""
+    acc = bf16_mm_f64(np.ascontiguousarray(dy.T), np.ascontiguousarray(x.T), rows)
+    out32 = acc.astype(np.float32)
+    return out32, f32_to_bf16(out32)
+
+
 def rel_frobenius(got: np.ndarray, ref: np.ndarray) -> float:
     g = np.asarray(got, dtype=np.float64)
     r = np.asarray(ref, dtype=np.float64)

@@ -147,7 +147,8 @@ int check_recipe(const char* fn, const fp8_recipe* r) {
         return fail(FP8_ERR_ENUM, "%s: recipe.gran=%d must be FP8_TENSOR or FP8_ROW", fn, r->gran);
     if (!fmt_ok(r->fmt_x) || !fmt_ok(r->fmt_w) || !fmt_ok(r->fmt_dy))
         return fail(FP8_ERR_ENUM, "%s: unknown fp8 format in recipe", fn);
-    if (r->flags & ~FP8_POW2_SCALE) return fail(FP8_ERR_ENUM, "%s: recipe.flags=%d has unknown bits", fn, r->flags);
+    if (r->flags & ~(FP8_POW2_SCALE | FP8_GRAD_WEIGHT_HP))
+        return fail(FP8_ERR_ENUM, "%s: recipe.flags=%d has unknown bits", fn, r->flags);
     return FP8_OK;
 }
 
@@ -334,6 +335,14 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
     const int fl = recipe->flags & FP8_POW2_SCALE;
     const int T = FP8_TRANSPOSE_OUT;
 
+    if (dw && (recipe->flags & FP8_GRAD_WEIGHT_HP)) {
+        // dW from the unquantized tensors on the bfloat16 matrix cores; the FP8 part below then
+        // only has dX left to do (and quantizes dY along N only)
+        FP8_TRY(fp8k::launch_gemm_bf16_at_b(dy, N, x, K, N, K, M, dw, K, st));
+        dw = nullptr;
+        if (!dx) return FP8_OK;
+    }
+
     if (recipe->gran == FP8_TENSOR) {
         // one scale per tensor; dY is converted once into both layouts
         uint8_t* plain = dx ? gq : nullptr;
@@ -371,6 +380,21 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
         FP8_TRY(fp8k::launch_gemm_fp8(gq, N, recipe->fmt_dy, sg, 1, wt, N, recipe->fmt_w, swt, 1, M, K, N, dx, K, 0, st));
     if (dw)
         FP8_TRY(fp8k::launch_gemm_fp8(gqt, M, recipe->fmt_dy, sgt, 1, xt, M, recipe->fmt_x, sxt, 1, N, K, M, dw, K, 0, st));
+    return FP8_OK;
+}
+
+int fp8_grad_weight_hp(const void* dy, const void* x, int64_t M, int64_t K, int64_t N, void* dw, void* stream) {
+    g_err[0] = 0;
+    const char* fn = "fp8_grad_weight_hp";
+    if (M < 0 || K < 0 || N < 0 || M > kMaxDim || K > kMaxDim || N > kMaxDim)
+        return fail(FP8_ERR_SHAPE, "%s: M=%lld K=%lld N=%lld out of range", fn, (long long)M, (long long)K, (long long)N);
+    if (K % 8 != 0 || N % 8 != 0) return fail(FP8_ERR_SHAPE, "%s: K=%lld and N=%lld must be multiples of 8", fn, (long long)K, (long long)N);
+    if (int rc = check_bf16("fp8_grad_weight_hp(dy)", dy, M, N, N)) return rc;
+    if (int rc = check_bf16("fp8_grad_weight_hp(x)", x, M, K, K)) return rc;
+    if (N == 0 || K == 0) return FP8_OK;
+    if (!dw) return fail(FP8_ERR_NULL, "%s: dw is NULL", fn);
+    if (!aligned(dw, 16)) return fail(FP8_ERR_ALIGN, "%s: dw not 16-byte aligned", fn);
+    FP8_TRY(fp8k::launch_gemm_bf16_at_b(dy, N, x, K, N, K, M, dw, K, static_cast<hipStream_t>(stream)));
     return FP8_OK;
 }
 

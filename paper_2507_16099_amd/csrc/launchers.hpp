@@ -64,4 +64,11 @@ hipError_t launch_gemm_fp8_skinny(const uint8_t* a, int64_t lda, int fmt_a, cons
                                   int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
                                   hipStream_t st);
 
+// bfloat16 GEMM with the contraction on the rows of both operands:
+// out[I, J] = a[C, I]^T b[C, J], fp32 accumulate, bfloat16 out (the weight gradient
+// dW = dY^T X kept in high precision).  I, J and the leading dimensions are
+// multiples of 8 elements, pointers 16-byte aligned.
+hipError_t launch_gemm_bf16_at_b(const void* a, int64_t lda, const void* b, int64_t ldb, int64_t I, int64_t J, int64_t C,
+                                 void* out, int64_t ld_out, hipStream_t st);
+
 }  // namespace fp8k

@@ -16,7 +16,7 @@ import torch
 
 FP8_E4M3FN, FP8_E5M2 = 0, 1
 FP8_TENSOR, FP8_ROW, FP8_COL = 0, 1, 2
-FP8_POW2_SCALE, FP8_TRANSPOSE_OUT, FP8_OUT_FP32 = 1, 2, 4
+FP8_POW2_SCALE, FP8_TRANSPOSE_OUT, FP8_OUT_FP32, FP8_GRAD_WEIGHT_HP = 1, 2, 4, 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfp8mi355.so")
@@ -84,6 +84,8 @@ def load_library() -> C.CDLL:
     L.fp8_linear_fwd_prequantized.restype = ci
     L.fp8_linear_fwd_prequantized.argtypes = [vp, i64, i64, ci, ci, ci, vp, i64, ci, vp, ci, i64, vp, i64, vp,
                                               C.c_size_t, vp]
+    L.fp8_grad_weight_hp.restype = ci
+    L.fp8_grad_weight_hp.argtypes = [vp, vp, i64, i64, i64, vp, vp]
     L.fp8_linear_bwd.restype = ci
     L.fp8_linear_bwd.argtypes = [vp, vp, vp, i64, i64, i64, C.POINTER(_CRecipe), vp, vp, vp, C.c_size_t, vp]
     _lib = L
@@ -274,3 +276,15 @@ def fp8_linear_fwd_prequantized(x: torch.Tensor, wq: torch.Tensor, fmt_w: int, s
                                                       _ptr(scale_w), gran_w, N, _ptr(y), ld_y, _ptr(workspace),
                                                       workspace.numel(), _stream()))
     return y
+
+
+def fp8_grad_weight_hp(dy: torch.Tensor, x: torch.Tensor, dw: torch.Tensor | None = None) -> torch.Tensor:
+    """dW [N, K] = dY [M, N]^T X [M, K] in bfloat16 (fp32 accumulate), no quantization."""
+    M, N, ldg = _mat(dy, 2)
+    Mx, K, ldx = _mat(x, 2)
+    assert M == Mx and (M == 0 or (ldg == N and ldx == K)), (dy.shape, x.shape)
+    if dw is None:
+        dw = torch.empty((N, K), dtype=torch.bfloat16, device=dy.device)
+    assert dw.is_contiguous() and tuple(dw.shape) == (N, K)
+    _check(load_library().fp8_grad_weight_hp(_ptr(dy), _ptr(x), M, K, N, _ptr(dw), _stream()))
+    return dw

@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
     lib = fp8.load_library()
     names = _declared()
     assert {"fp8_amax", "fp8_scale", "fp8_cast", "fp8_scaled_mm", "fp8_linear_fwd", "fp8_linear_bwd",
-            "fp8_quantize", "fp8_quantize_row_col", "fp8_linear_fwd_prequantized",
+            "fp8_quantize", "fp8_quantize_row_col", "fp8_linear_fwd_prequantized", "fp8_grad_weight_hp",
             "fp8_linear_prequantized_workspace_bytes", "fp8_linear_workspace_bytes", "fp8_last_error", "fp8_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -37,7 +37,7 @@ def test_binding_has_the_same_names():
 def test_enum_values_match_header():
     src = open(HEADER).read()
     for name in ("FP8_E4M3FN", "FP8_E5M2", "FP8_TENSOR", "FP8_ROW", "FP8_COL", "FP8_POW2_SCALE",
-                 "FP8_TRANSPOSE_OUT", "FP8_OUT_FP32"):
+                 "FP8_TRANSPOSE_OUT", "FP8_OUT_FP32", "FP8_GRAD_WEIGHT_HP"):
         m = re.search(name + r"\s*=\s*(-?\d+)", src)
         assert m and int(m.group(1)) == getattr(fp8, name), name
 

@@ -255,3 +255,74 @@ def test_full_size_decode_step_llama_ffn_weight():
     y = fp8.fp8_linear_fwd_prequantized(dev_bf16(x), wq, fp8.FP8_E4M3FN, sw, fp8.FP8_ROW)
     want, _, _ = orc.linear_fwd(x, w, orc.Recipe(gran=orc.ROW))
     _cmp(y, want)
+
+
+# ------------------------------------------------ rowwise_gw_hp: weight gradient in bfloat16
+
+GW_SHAPES = [(16, 8, 8), (64, 256, 256), (100, 72, 264), (513, 520, 136), (1000, 256, 1024), (4096, 768, 512)]
+
+
+@pytest.mark.parametrize("M,K,N", GW_SHAPES)
+def test_grad_weight_hp_exact_on_small_integers(M, K, N):
+    """Integer-valued inputs: every product and partial sum is exact in fp32,
+    so any mistake in the transposing load, the LDS layout or the output
+    indexing shows as a wrong integer (ragged tiles and contraction tails
+    included)."""
+    rng = np.random.default_rng(M + K + N)
+    gi, xi = rng.integers(-4, 5, size=(M, N)), rng.integers(-4, 5, size=(M, K))
+    dy = si.f32_to_bf16_bits(gi.astype(np.float32))
+    x = si.f32_to_bf16_bits(xi.astype(np.float32))
+    dw = fp8.fp8_grad_weight_hp(dev_bf16(dy), dev_bf16(x))
+    _, want16 = orc.linear_bwd_dw_hp(dy, x)
+    got = host_bf16_bits(dw)
+    assert (got == want16).all(), (M, K, N, np.argwhere(got != want16)[:4])
+
+
+@pytest.mark.parametrize("M,K,N", GW_SHAPES)
+def test_grad_weight_hp_random_inputs(M, K, N):
+    wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)
+    dy, x = wl.dy(), wl.x()
+    dw = fp8.fp8_grad_weight_hp(dev_bf16(dy), dev_bf16(x))
+    want32, want16 = orc.linear_bwd_dw_hp(dy, x)
+    got = host_bf16_bits(dw)
+    err = orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want16))
+    assert err <= TOL, err
+    assert float((got == want16).mean()) > 0.98
+    # and against the unrounded sums: only the final bfloat16 rounding (2^-9 relative at most) separates them
+    assert orc.rel_frobenius(si.bf16_bits_to_f32(got), want32) <= 2.5e-3
+
+
+@pytest.mark.parametrize("M,K,N", [(384, 256, 512), (208, 176, 272), (1024, 384, 640)])
+def test_backward_with_high_precision_weight_gradient(M, K, N):
+    """rowwise_gw_hp: dX exactly as in the rowwise recipe (FP8), dW from the
+    unquantized tensors."""
+    wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)
+    x, w, dy = wl.x(), wl.w(), wl.dy()
+    g = fp8.Recipe(gran=fp8.FP8_ROW, flags=fp8.FP8_GRAD_WEIGHT_HP)
+    xd, wd, dyd = dev_bf16(x), dev_bf16(w), dev_bf16(dy)
+    dx, dw = fp8.fp8_linear_bwd(dyd, xd, wd, g)
+    o = orc.Recipe(gran=orc.ROW)
+    _cmp(dx, orc.linear_bwd_dx(dy, w, o)[0])
+    _, want16 = orc.linear_bwd_dw_hp(dy, x)
+    got = host_bf16_bits(dw)
+    assert orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want16)) <= TOL
+    # same dX as the plain rowwise recipe, bit for bit
+    dx2, _ = fp8.fp8_linear_bwd(dyd, xd, wd, fp8.Recipe(gran=fp8.FP8_ROW))
+    assert torch.equal(dx.view(torch.int16), dx2.view(torch.int16))
+    # dW only
+    _, dw_only = fp8.fp8_linear_bwd(dyd, xd, wd, g, need_dx=False)
+    assert torch.equal(dw_only.view(torch.int16), dw.view(torch.int16))
+
+
+def test_full_size_grad_weight_hp_sampled_rows():
+    """dW [14336, 4096] of the benchmark workload, contraction over 16384 tokens:
+    a stratified sample of output rows recomputed by the oracle in binary64."""
+    wl = si.WORKLOADS[si.BENCH_WORKLOAD]
+    dy, x = wl.dy(), wl.x()
+    dw = fp8.fp8_grad_weight_hp(dev_bf16(dy), dev_bf16(x))
+    rows = si.stratified_rows(wl.N, 24)
+    want32, want16 = orc.linear_bwd_dw_hp(dy, x, rows)
+    got = host_bf16_bits(dw[torch.from_numpy(rows).cuda()])
+    err = orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want16))
+    assert err <= TOL, err
+    assert float((got == want16).mean()) > 0.98

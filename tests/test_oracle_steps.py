@@ -321,3 +321,41 @@ def test_outliers_hurt_tensorwise_more_than_rowwise():
     st_r = orc.cast_stats(x, orc.scale(orc.amax(x, orc.ROW), orc.E4M3FN), orc.ROW, orc.E4M3FN)
     assert st_t.n_zero > 5 * max(1, st_r.n_zero)
     assert st_r.sqnr_db > st_t.sqnr_db
+
+
+# ------------------------------------- weight gradient in high precision (rowwise_gw_hp)
+
+def test_grad_weight_hp_is_the_plain_transposed_product():
+    """Pins of the definition dW[n,k] = sum_m dY[m,n] X[m,k] (Appendix A,
+    rowwise_gw_hp): numpy binary64 on the unquantized values (a transposed or
+    swapped operand fails it: the shapes are all different), exact small
+    integers bit for bit, and the row selection."""
+    M, K, N = 37, 24, 40
+    dy = si.normal_bf16((M, N), 1e-3, 51, 0)
+    x = si.normal_bf16((M, K), 1.0, 51, 1)
+    want = si.bf16_bits_to_f32(dy).astype(np.float64).T @ si.bf16_bits_to_f32(x).astype(np.float64)
+    out32, out16 = orc.linear_bwd_dw_hp(dy, x)
+    assert out32.shape == (N, K) and np.allclose(out32, want, rtol=1e-6, atol=0)
+    assert (out16 == orc.f32_to_bf16(want.astype(np.float32))).all()
+    rows = np.array([3, 39, 0], np.int64)
+    s32, s16 = orc.linear_bwd_dw_hp(dy, x, rows)
+    assert (s32 == out32[rows]).all() and (s16 == out16[rows]).all()
+    rng = np.random.default_rng(2)
+    gi, xi = rng.integers(-4, 5, size=(M, N)), rng.integers(-4, 5, size=(M, K))
+    e32, e16 = orc.linear_bwd_dw_hp(si.f32_to_bf16_bits(gi.astype(np.float32)), si.f32_to_bf16_bits(xi.astype(np.float32)))
+    assert (e32 == (gi.T @ xi).astype(np.float32)).all()
+    assert (si.bf16_bits_to_f32(e16) == si.bf16_bits_to_f32(orc.f32_to_bf16((gi.T @ xi).astype(np.float32)))).all()
+
+
+def test_grad_weight_hp_is_closer_to_the_true_gradient_than_the_fp8_one():
+    """What the recipe is for (Appendix A): on the same inputs the bfloat16
+    weight gradient has a far smaller error against the binary64 product than
+    the rowwise FP8 one."""
+    M, K, N = 256, 64, 48
+    dy = si.normal_bf16((M, N), 1e-3, 52, 0)
+    x = si.normal_bf16((M, K), 1.0, 52, 1)
+    true = si.bf16_bits_to_f32(dy).astype(np.float64).T @ si.bf16_bits_to_f32(x).astype(np.float64)
+    hp32, _ = orc.linear_bwd_dw_hp(dy, x)
+    lp = orc.linear_bwd_dw(dy, x, orc.Recipe(gran=orc.ROW))[0]
+    e_hp, e_lp = orc.rel_frobenius(hp32, true), orc.rel_frobenius(lp.out32, true)
+    assert e_hp < 1e-6 and 5e-3 < e_lp < 0.2, (e_hp, e_lp)
