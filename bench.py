@@ -364,6 +364,22 @@ def main() -> int:
             del gqt, xt
         torch.cuda.empty_cache()
 
+        if wl.backward and rowwise:
+            # rowwise_gw_hp recipe: dW in bfloat16 from the unquantized tensors (same flops, bf16 matrix-core peak)
+            ms = _event_time_ms(lambda: fp8.fp8_grad_weight_hp(dy, x, dw), it, wu, torch)
+            tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+            kernels["gemm_dw_bf16_hp"] = {"ms": round(ms, 4), "TFLOP/s": round(tf, 1),
+                                          "frac_of_bf16_peak": round(tf / BF16_PEAK_TFLOPS, 4)}
+            hp = fp8.Recipe(gran=fp8.FP8_ROW, flags=recipe.flags | fp8.FP8_GRAD_WEIGHT_HP)
+
+            def hp_step():
+                fp8.fp8_linear_fwd(x, w, hp, y=y, workspace=ws_f)
+                fp8.fp8_linear_bwd(dy, x, w, hp, dx=dx, dw=dw, workspace=ws_b)
+            hp_ms = _event_time_ms(hp_step, max(3, args.steps // 2), 2, torch)
+            result["rowwise_gw_hp"] = {"ms_per_step": round(hp_ms, 4),
+                                       "TFLOP/s": round(flop_step / (hp_ms * 1e-3) / 1e12, 1),
+                                       "note": "same step with the weight gradient kept in bfloat16 (Appendix A)"}
+
         # vendor FP8 GEMM on the forward operands (context only; never linked into the library)
         try:
             a8 = xq.view(torch.float8_e4m3fn)
