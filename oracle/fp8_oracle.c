@@ -323,6 +323,112 @@ void orc_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_
     }
 }
 
+/* ------------------------------------------------------------------ MX blocks
+ *
+ * Microscaling (the paper lists the MX formats, "mxfp8 for training", among
+ * its prototype features; the format and its conversion are defined by the
+ * OCP Microscaling Formats (MX) specification v1.0, Sections 5 and 6.3):
+ * 32 consecutive elements along the contraction axis share one power-of-two
+ * scale X stored as an E8M0 byte (value 2^(byte - 127); 255 = NaN), and the
+ * elements are FP8 codes P_i with  value_i = X * dec(P_i).
+ *
+ * Conversion of a block V_0..V_31 (Section 6.3 of that specification):
+ *   shared_exp = floor(log2(max_i |V_i|)) - emax_elem      (emax_elem = 8 for E4M3: 448 = 1.75 * 2^8,
+ *                                                            15 for E5M2: 57344 = 1.75 * 2^15)
+ *   X = 2^shared_exp, E8M0 byte = shared_exp + 127 clamped to [0, 254]
+ *   P_i = FP8 of V_i / X, round to nearest even, magnitudes above the largest
+ *         normal clamped to it (the block maximum lands in [2^emax, 2^(emax+1))
+ *         before rounding, so it can round past 448 / 57344 and saturate).
+ * Reading where the specification leaves a choice: an all-zero block gets the
+ * byte 0 (X = 2^-127) and all-zero codes.  NaN / Inf inputs: unspecified here
+ * ("parity unpinned").
+ */
+static int orc_emax_elem(int fmt) { return fmt == ORC_E4M3FN ? 8 : 15; }
+
+void orc_mx_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, int fmt,
+                     uint8_t* q, int64_t ld_q, uint8_t* e8m0, int64_t ld_e) {
+    const int64_t nblk = cols / 32;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t b = 0; b < nblk; ++b) {
+            const uint16_t* v = x + r * ld + b * 32;
+            double amax = 0.0;
+            for (int i = 0; i < 32; ++i) {
+                const double a = fabs((double)orc_bf16_to_f32(v[i]));
+                if (a > amax) amax = a;
+            }
+            int byte = 0;
+            if (amax > 0.0) {
+                int e;
+                (void)frexp(amax, &e);            /* amax = f * 2^e, 0.5 <= f < 1: floor(log2 amax) = e - 1 */
+                const int shared = (e - 1) - orc_emax_elem(fmt);
+                byte = shared + 127;
+                if (byte < 0) byte = 0;
+                if (byte > 254) byte = 254;
+            }
+            e8m0[r * ld_e + b] = (uint8_t)byte;
+            const double X = ldexp(1.0, byte - 127);
+            for (int i = 0; i < 32; ++i) {
+                /* V / X is exact in binary64; as a binary32 it is exact too unless it is
+                 * far below the smallest FP8 subnormal, where the code is a signed zero anyway */
+                const float scaled = (float)((double)orc_bf16_to_f32(v[i]) / X);
+                q[r * ld_q + b * 32 + i] = orc_fp8_encode_bits(scaled, fmt);
+            }
+        }
+    }
+}
+
+/* value of an MX element: X * dec(P) in binary64 (exact) */
+double orc_mx_value(uint8_t code, int fmt, uint8_t e8m0) {
+    return ldexp((double)orc_fp8_decode(code, fmt), (int)e8m0 - 127);
+}
+
+/*
+ * MX matrix product on two block-scaled operands, both K-contiguous, blocks of
+ * 32 along K (K % 32 == 0):
+ *   out[m, n] = sum_blocks 2^(ea[m,blk] - 127) * 2^(eb[n,blk] - 127) * sum_{k in blk} dec(a[m,k]) * dec(b[n,k])
+ * Order: products of a block summed k-ascending in binary32, scaled by the
+ * (exact) power of two, blocks added in ascending order in binary32; a
+ * binary64 shadow of the same sum is returned in acc64.  out16 = bfloat16 RNE.
+ */
+void orc_mx_mm(const uint8_t* a, int64_t lda, int fmt_a, const uint8_t* ea, int64_t ld_ea,
+               const uint8_t* b, int64_t ldb, int fmt_b, const uint8_t* eb, int64_t ld_eb,
+               int64_t M, int64_t N, int64_t K, const int64_t* row_idx, int64_t n_rows_out,
+               float* out32, uint16_t* out16, double* acc64) {
+    float lut_a[256], lut_b[256];
+    for (int c = 0; c < 256; ++c) {
+        lut_a[c] = orc_fp8_decode((uint8_t)c, fmt_a);
+        lut_b[c] = orc_fp8_decode((uint8_t)c, fmt_b);
+    }
+    const int64_t rows = row_idx ? n_rows_out : M;
+    const int64_t nblk = K / 32;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        for (int64_t n = 0; n < N; ++n) {
+            const int64_t m = row_idx ? row_idx[i] : i;
+            float acc = 0.0f;
+            double accd = 0.0;
+            for (int64_t blk = 0; blk < nblk; ++blk) {
+                const uint8_t* ar = a + m * lda + blk * 32;
+                const uint8_t* br = b + n * ldb + blk * 32;
+                float p = 0.0f;
+                double pd = 0.0;
+                for (int k = 0; k < 32; ++k) {
+                    const float fa = lut_a[ar[k]], fb = lut_b[br[k]];
+                    p = p + fa * fb;
+                    pd = pd + (double)fa * (double)fb;
+                }
+                const int e = (int)ea[m * ld_ea + blk] + (int)eb[n * ld_eb + blk] - 254;
+                acc = acc + ldexpf(p, e);
+                accd = accd + ldexp(pd, e);
+            }
+            if (out32) out32[i * N + n] = acc;
+            if (out16) out16[i * N + n] = orc_f32_to_bf16(acc);
+            if (acc64) acc64[i * N + n] = accd;
+        }
+    }
+}
+
 /*
  * High-precision linear on the unquantized bfloat16 operands (report only:
  * measures the quantization error of the fp8 path, not used for parity).

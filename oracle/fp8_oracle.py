@@ -77,6 +77,12 @@ def lib() -> C.CDLL:
         L.orc_scaled_mm.restype = None
         L.orc_scaled_mm.argtypes = [vp, i64, ci, vp, ci, vp, i64, ci, vp, ci,
                                     i64, i64, i64, vp, i64, vp, vp, vp]
+        L.orc_mx_quantize.restype = None
+        L.orc_mx_quantize.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp, i64]
+        L.orc_mx_value.restype = C.c_double
+        L.orc_mx_value.argtypes = [C.c_uint8, ci, C.c_uint8]
+        L.orc_mx_mm.restype = None
+        L.orc_mx_mm.argtypes = [vp, i64, ci, vp, i64, vp, i64, ci, vp, i64, i64, i64, i64, vp, i64, vp, vp, vp]
         L.orc_bf16_mm_f64.restype = None
         L.orc_bf16_mm_f64.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i64, vp]
         _lib = L
@@ -293,6 +299,50 @@ def linear_bwd_dw(dy, x, recipe: Recipe, rows=None):
     go = _operand(dy, recipe, recipe.fmt_dy, False)
     xo = _operand(x, recipe, recipe.fmt_x, False)
     return _mm(go, xo, rows), go, xo
+
+
+# ------------------------------------------------------------- MX blocks
+
+MX_BLOCK = 32
+
+
+def mx_quantize(x: np.ndarray, fmt: int):
+    """Blocks of 32 along the last axis -> (codes [rows, cols], E8M0 bytes [rows, cols / 32])."""
+    rows, cols, ld = _check2d(x, np.uint16)
+    assert cols % MX_BLOCK == 0
+    q = np.empty((rows, cols), np.uint8)
+    e = np.empty((rows, cols // MX_BLOCK), np.uint8)
+    lib().orc_mx_quantize(_p(x), rows, cols, ld, fmt, _p(q), cols, _p(e), cols // MX_BLOCK)
+    return q, e
+
+
+def mx_value(code: int, fmt: int, e8m0: int) -> float:
+    return float(lib().orc_mx_value(code, fmt, e8m0))
+
+
+def mx_mm(a, fmt_a, ea, b, fmt_b, eb, rows=None) -> MMResult:
+    """out[m, n] = sum over blocks of 2^(ea-127) 2^(eb-127) sum_k dec(a) dec(b); a [M,K], b [N,K]."""
+    M, K, lda = _check2d(a, np.uint8)
+    N, Kb, ldb = _check2d(b, np.uint8)
+    assert K == Kb and K % MX_BLOCK == 0
+    ea = np.ascontiguousarray(ea, dtype=np.uint8)
+    eb = np.ascontiguousarray(eb, dtype=np.uint8)
+    assert ea.shape == (M, K // MX_BLOCK) and eb.shape == (N, K // MX_BLOCK)
+    idx = None if rows is None else np.ascontiguousarray(rows, dtype=np.int64)
+    R = M if idx is None else idx.size
+    o32 = np.empty((R, N), np.float32)
+    o16 = np.empty((R, N), np.uint16)
+    a64 = np.empty((R, N), np.float64)
+    lib().orc_mx_mm(_p(a), lda, fmt_a, _p(ea), K // MX_BLOCK, _p(b), ldb, fmt_b, _p(eb), K // MX_BLOCK,
+                    M, N, K, _p(idx), R, _p(o32), _p(o16), _p(a64))
+    return MMResult(o32, o16, a64)
+
+
+def mx_linear_fwd(x, w, fmt_x=E4M3FN, fmt_w=E4M3FN, rows=None) -> MMResult:
+    """Y = X W^T with both operands in MX blocks of 32 along K."""
+    xq, xe = mx_quantize(x, fmt_x)
+    wq, we = mx_quantize(w, fmt_w)
+    return mx_mm(xq, fmt_x, xe, wq, fmt_w, we, rows)
 
 
 def linear_bwd_dw_hp(dy, x, rows=None):
