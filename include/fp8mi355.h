@@ -214,6 +214,35 @@ int fp8_linear_fwd_prequantized(const void* x, int64_t M, int64_t K, int fmt_x, 
                                 int64_t N, void* y, int64_t ld_y, void* workspace, size_t workspace_bytes,
                                 void* stream);
 
+/*
+ * MX (microscaling) FP8, the finer scaling granularity that the paper lists
+ * among its prototype features ("MX formats: ... mxfp8 for training"); format
+ * and conversion follow the OCP Microscaling Formats (MX) specification v1.0:
+ * every block of 32 consecutive elements along the contraction axis has one
+ * power-of-two scale, stored as an E8M0 byte (value 2^(byte - 127)).
+ *
+ * fp8_mx_quantize: x [rows, cols] bfloat16, blocks along the columns
+ *   (cols % 32 == 0).  byte = floor(log2(block maximum)) - emax(format) + 127,
+ *   clamped to [0, 254] (emax = 8 for E4M3, 15 for E5M2; all-zero block: 0);
+ *   q = fp8( x / 2^(byte - 127) ), round to nearest even, saturating.
+ *   q_out [rows, cols] (ld_q % 16 == 0), e8m0_out [rows, cols / 32] (ld_e % 4 == 0).
+ * fp8_mx_scaled_mm: out[m, n] = sum over blocks of
+ *   2^(ea[m,blk]-127) * 2^(eb[n,blk]-127) * sum_{k in blk} dec(a[m,k]) * dec(b[n,k]),
+ *   a [M, K], b [N, K] codes, ea [M, K/32], eb [N, K/32]; the scales are applied by
+ *   the matrix-core instruction itself (v_mfma_scale_f32_16x16x128_f8f6f4).
+ *   K % 128 == 0; ld_ea, ld_eb multiples of 4; out bfloat16 or fp32 (FP8_OUT_FP32).
+ * fp8_mx_linear_fwd: Y = X W^T with both operands quantized per call into MX
+ *   blocks along K; workspace of fp8_mx_linear_workspace_bytes(M, K, N) bytes.
+ */
+int fp8_mx_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int format,
+                    uint8_t* q_out, int64_t ld_q, uint8_t* e8m0_out, int64_t ld_e, void* stream);
+int fp8_mx_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const uint8_t* ea, int64_t ld_ea,
+                     const uint8_t* b, int64_t ldb, int fmt_b, const uint8_t* eb, int64_t ld_eb,
+                     int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int flags, void* stream);
+size_t fp8_mx_linear_workspace_bytes(int64_t M, int64_t K, int64_t N);
+int fp8_mx_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N, int fmt_x, int fmt_w,
+                      void* y, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

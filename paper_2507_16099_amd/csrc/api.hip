@@ -437,4 +437,92 @@ int fp8_linear_fwd_prequantized(const void* x, int64_t M, int64_t K, int fmt_x, 
     return FP8_OK;
 }
 
+int fp8_mx_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int format, uint8_t* q_out, int64_t ld_q,
+                    uint8_t* e8m0_out, int64_t ld_e, void* stream) {
+    g_err[0] = 0;
+    const char* fn = "fp8_mx_quantize";
+    if (!fmt_ok(format)) return fail(FP8_ERR_ENUM, "%s: unknown format %d", fn, format);
+    if (int rc = check_bf16(fn, x, rows, cols, ld)) return rc;
+    if (cols % 32 != 0) return fail(FP8_ERR_SHAPE, "%s: cols=%lld must be a multiple of the block size 32", fn, (long long)cols);
+    if (int rc = check_q_out(fn, q_out, rows, cols, ld_q, 0)) return rc;
+    if (ld_e < cols / 32 || ld_e % 4 != 0) return fail(FP8_ERR_SHAPE, "%s: ld_e=%lld must be >= cols/32 and a multiple of 4", fn, (long long)ld_e);
+    if (rows > 0 && cols > 0 && !e8m0_out) return fail(FP8_ERR_NULL, "%s: e8m0_out is NULL", fn);
+    if (!aligned(e8m0_out, 4)) return fail(FP8_ERR_ALIGN, "%s: e8m0_out not 4-byte aligned", fn);
+    FP8_TRY(fp8k::launch_mx_quant(x, rows, cols, ld, format, q_out, ld_q, e8m0_out, ld_e, static_cast<hipStream_t>(stream)));
+    return FP8_OK;
+}
+
+int fp8_mx_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const uint8_t* ea, int64_t ld_ea, const uint8_t* b,
+                     int64_t ldb, int fmt_b, const uint8_t* eb, int64_t ld_eb, int64_t M, int64_t N, int64_t K, void* out,
+                     int64_t ld_out, int flags, void* stream) {
+    g_err[0] = 0;
+    const char* fn = "fp8_mx_scaled_mm";
+    if (!fmt_ok(fmt_a) || !fmt_ok(fmt_b)) return fail(FP8_ERR_ENUM, "%s: unknown format", fn);
+    if (flags & ~FP8_OUT_FP32) return fail(FP8_ERR_ENUM, "%s: flags=%d has unknown bits", fn, flags);
+    if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim)
+        return fail(FP8_ERR_SHAPE, "%s: M=%lld N=%lld K=%lld out of range", fn, (long long)M, (long long)N, (long long)K);
+    if (K % 128 != 0) return fail(FP8_ERR_SHAPE, "%s: K=%lld must be a multiple of 128", fn, (long long)K);
+    if (lda < K || ldb < K || ld_out < N || ld_ea < K / 32 || ld_eb < K / 32) return fail(FP8_ERR_SHAPE, "%s: leading dimension too small", fn);
+    if (M > 0 && N > 0) {
+        if (!out || (K > 0 && (!a || !b || !ea || !eb))) return fail(FP8_ERR_NULL, "%s: NULL pointer", fn);
+        if (!aligned(a, 16) || !aligned(b, 16) || !aligned(out, 16) || !aligned(ea, 4) || !aligned(eb, 4))
+            return fail(FP8_ERR_ALIGN, "%s: a, b, out (16) / ea, eb (4) misaligned", fn);
+        if (lda % 16 != 0 || ldb % 16 != 0 || ld_ea % 4 != 0 || ld_eb % 4 != 0)
+            return fail(FP8_ERR_ALIGN, "%s: lda, ldb must be multiples of 16, ld_ea, ld_eb of 4", fn);
+        const int64_t out_align = (flags & FP8_OUT_FP32) ? 4 : 8;
+        if (ld_out % out_align != 0) return fail(FP8_ERR_ALIGN, "%s: ld_out=%lld must be a multiple of %lld", fn, (long long)ld_out, (long long)out_align);
+    }
+    FP8_TRY(fp8k::launch_gemm_mxfp8(a, lda, fmt_a, ea, ld_ea, b, ldb, fmt_b, eb, ld_eb, M, N, K, out, ld_out,
+                                    (flags & FP8_OUT_FP32) ? 1 : 0, static_cast<hipStream_t>(stream)));
+    return FP8_OK;
+}
+
+namespace {
+struct MxPlan { size_t xq, wq, xe, we, total; };
+MxPlan plan_mx(int64_t M, int64_t K, int64_t N) {
+    MxPlan p{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    p.xq = take((size_t)M * K);
+    p.wq = take((size_t)N * K);
+    p.xe = take((size_t)M * (K / 32));
+    p.we = take((size_t)N * (K / 32));
+    p.total = o;
+    return p;
+}
+}  // namespace
+
+size_t fp8_mx_linear_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+    g_err[0] = 0;
+    if (M < 0 || K < 0 || N < 0 || M > kMaxDim || K > kMaxDim || N > kMaxDim || K % 128 != 0) {
+        fail(FP8_ERR_SHAPE, "fp8_mx_linear_workspace_bytes: M=%lld K=%lld N=%lld (K must be a multiple of 128)", (long long)M, (long long)K, (long long)N);
+        return 0;
+    }
+    const size_t t = plan_mx(M, K, N).total;
+    return t ? t : 256;
+}
+
+int fp8_mx_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N, int fmt_x, int fmt_w, void* y,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    g_err[0] = 0;
+    const char* fn = "fp8_mx_linear_fwd";
+    if (!fmt_ok(fmt_x) || !fmt_ok(fmt_w)) return fail(FP8_ERR_ENUM, "%s: unknown fp8 format", fn);
+    if (int rc = check_linear_dims(fn, M, K, N, false)) return rc;
+    if (K % 128 != 0) return fail(FP8_ERR_SHAPE, "%s: K=%lld must be a multiple of 128", fn, (long long)K);
+    if (int rc = check_bf16("fp8_mx_linear_fwd(x)", x, M, K, K)) return rc;
+    if (int rc = check_bf16("fp8_mx_linear_fwd(w)", w, N, K, K)) return rc;
+    if (M == 0 || N == 0) return FP8_OK;
+    if (!y || !workspace) return fail(FP8_ERR_NULL, "%s: y or workspace is NULL", fn);
+    if (!aligned(y, 16) || !aligned(workspace, 256)) return fail(FP8_ERR_ALIGN, "%s: y (16) / workspace (256) misaligned", fn);
+    const MxPlan p = plan_mx(M, K, N);
+    if (workspace_bytes < p.total) return fail(FP8_ERR_WORKSPACE, "%s: workspace %zu < %zu bytes", fn, workspace_bytes, p.total);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    FP8_TRY(fp8k::launch_mx_quant(x, M, K, K, fmt_x, ws + p.xq, K, ws + p.xe, K / 32, st));
+    FP8_TRY(fp8k::launch_mx_quant(w, N, K, K, fmt_w, ws + p.wq, K, ws + p.we, K / 32, st));
+    FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.xq, K, fmt_x, ws + p.xe, K / 32, ws + p.wq, K, fmt_w, ws + p.we, K / 32, M, N, K, y,
+                                    N, 0, st));
+    return FP8_OK;
+}
+
 }  // extern "C"

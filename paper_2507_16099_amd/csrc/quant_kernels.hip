@@ -768,4 +768,56 @@ hipError_t launch_quant_row_colmax(const void* x, int64_t rows, int64_t cols, in
 }
 
 
+// ------------------------------------------------------------ MX block quantization
+// Blocks of 32 consecutive elements of a row share one power-of-two scale
+// (OCP MX specification v1.0, Section 6.3): shared exponent = floor(log2(block
+// maximum)) - emax of the element format (8 for E4M3, 15 for E5M2), stored as
+// the E8M0 byte exponent + 127 (clamped to [0, 254]; an all-zero block gets 0);
+// elements = x * 2^-exponent (exact), saturating round-to-nearest-even cast.
+// Four lanes own a block (one 128-bit load each); the maximum is taken on the
+// bfloat16 magnitude bits, whose exponent field gives floor(log2) directly.
+template <int FMT>
+__global__ __launch_bounds__(256) void mx_quant_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                        int64_t ld, uint8_t* __restrict__ q, int64_t ld_q,
+                                                        uint8_t* __restrict__ e8m0, int64_t ld_e) {
+    const int64_t vpr = cols >> 3;                      // 128-bit vectors per row (cols % 32 == 0)
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const bool live = v < rows * vpr;
+    const int64_t r = live ? v / vpr : 0, cv = live ? v % vpr : 0;
+    const uint4 d = live ? load_stream(x + r * ld + cv * 8) : make_uint4(0, 0, 0, 0);
+    uint32_t m = pk_fold(pk_absmax4(0u, d));
+    uint32_t o = (uint32_t)__shfl_xor((int)m, 1, 64);
+    m = o > m ? o : m;
+    o = (uint32_t)__shfl_xor((int)m, 2, 64);
+    m = o > m ? o : m;                                   // block maximum, 15 magnitude bits of bfloat16
+    constexpr int EMAX = FMT == FMT_E4M3FN ? 8 : 15;
+    int byte = 0;
+    if (m != 0) {
+        const int ef = (int)(m >> 7);
+        // normal: 2^(ef - 127) * 1.f; subnormal: mantissa * 2^-133
+        const int fl = ef > 0 ? ef - 127 : (31 - __builtin_clz(m)) - 133;
+        byte = fl - EMAX + 127;
+        byte = byte < 0 ? 0 : (byte > 254 ? 254 : byte);
+    }
+    // 2^(127 - byte): byte <= 246 for bfloat16 input, so the factor is a normal binary32
+    const float factor = __uint_as_float((uint32_t)(254 - byte) << 23);
+    if (!live) return;
+    store_stream(q + r * ld_q + cv * 8, cast8<FMT>(d, factor));
+    if ((threadIdx.x & 3) == 0) e8m0[r * ld_e + (cv >> 2)] = (uint8_t)byte;
+}
+
+hipError_t launch_mx_quant(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, uint8_t* q, int64_t ld_q,
+                           uint8_t* e8m0, int64_t ld_e, hipStream_t st) {
+    if (rows == 0 || cols == 0) return hipSuccess;
+    const int64_t nvec = rows * (cols / 8);
+    const int64_t blocks = (nvec + 255) / 256;
+    if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    if (fmt == FMT_E4M3FN)
+        mx_quant_kernel<FMT_E4M3FN><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(xp, rows, cols, ld, q, ld_q, e8m0, ld_e);
+    else
+        mx_quant_kernel<FMT_E5M2><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(xp, rows, cols, ld, q, ld_q, e8m0, ld_e);
+    return hipGetLastError();
+}
+
 }  // namespace fp8k

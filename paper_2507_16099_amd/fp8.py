@@ -84,6 +84,14 @@ def load_library() -> C.CDLL:
     L.fp8_linear_fwd_prequantized.restype = ci
     L.fp8_linear_fwd_prequantized.argtypes = [vp, i64, i64, ci, ci, ci, vp, i64, ci, vp, ci, i64, vp, i64, vp,
                                               C.c_size_t, vp]
+    L.fp8_mx_quantize.restype = ci
+    L.fp8_mx_quantize.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp, i64, vp]
+    L.fp8_mx_scaled_mm.restype = ci
+    L.fp8_mx_scaled_mm.argtypes = [vp, i64, ci, vp, i64, vp, i64, ci, vp, i64, i64, i64, i64, vp, i64, ci, vp]
+    L.fp8_mx_linear_workspace_bytes.restype = C.c_size_t
+    L.fp8_mx_linear_workspace_bytes.argtypes = [i64, i64, i64]
+    L.fp8_mx_linear_fwd.restype = ci
+    L.fp8_mx_linear_fwd.argtypes = [vp, vp, i64, i64, i64, ci, ci, vp, vp, C.c_size_t, vp]
     L.fp8_grad_weight_hp.restype = ci
     L.fp8_grad_weight_hp.argtypes = [vp, vp, i64, i64, i64, vp, vp]
     L.fp8_linear_bwd.restype = ci
@@ -288,3 +296,55 @@ def fp8_grad_weight_hp(dy: torch.Tensor, x: torch.Tensor, dw: torch.Tensor | Non
     assert dw.is_contiguous() and tuple(dw.shape) == (N, K)
     _check(load_library().fp8_grad_weight_hp(_ptr(dy), _ptr(x), M, K, N, _ptr(dw), _stream()))
     return dw
+
+
+def fp8_mx_quantize(x: torch.Tensor, fmt: int, q: torch.Tensor | None = None, e8m0: torch.Tensor | None = None):
+    """MX blocks of 32 along the last axis: codes [rows, cols] and E8M0 bytes [rows, cols / 32]."""
+    rows, cols, ld = _mat(x, 2)
+    if q is None:
+        q = _alloc_q(rows, cols, 0, x.device)
+    if e8m0 is None:
+        nb = cols // 32
+        e8m0 = torch.empty((rows, (nb + 3) // 4 * 4), dtype=torch.uint8, device=x.device)[:, :nb]
+    _, _, ld_q = _mat(q, 1)
+    _, _, ld_e = _mat(e8m0, 1)
+    _check(load_library().fp8_mx_quantize(_ptr(x), rows, cols, ld, fmt, _ptr(q), ld_q, _ptr(e8m0), ld_e, _stream()))
+    return q, e8m0
+
+
+def fp8_mx_scaled_mm(a: torch.Tensor, fmt_a: int, ea: torch.Tensor, b: torch.Tensor, fmt_b: int, eb: torch.Tensor,
+                     flags: int = 0, out: torch.Tensor | None = None) -> torch.Tensor:
+    M, K, lda = _mat(a, 1)
+    N, Kb, ldb = _mat(b, 1)
+    assert K == Kb, (a.shape, b.shape)
+    _, _, ld_ea = _mat(ea, 1)
+    _, _, ld_eb = _mat(eb, 1)
+    if out is None:
+        dt = torch.float32 if flags & FP8_OUT_FP32 else torch.bfloat16
+        pad = 4 if flags & FP8_OUT_FP32 else 8
+        out = torch.empty((M, (N + pad - 1) // pad * pad), dtype=dt, device=a.device)[:, :N]
+    _, _, ld_out = _mat(out, out.element_size())
+    _check(load_library().fp8_mx_scaled_mm(_ptr(a), lda, fmt_a, _ptr(ea), ld_ea, _ptr(b), ldb, fmt_b, _ptr(eb), ld_eb,
+                                           M, N, K, _ptr(out), ld_out, flags, _stream()))
+    return out
+
+
+def fp8_mx_linear_workspace_bytes(M: int, K: int, N: int) -> int:
+    n = load_library().fp8_mx_linear_workspace_bytes(M, K, N)
+    if n == 0:
+        raise Fp8Error(-2, fp8_last_error())
+    return n
+
+
+def fp8_mx_linear_fwd(x: torch.Tensor, w: torch.Tensor, fmt_x: int = FP8_E4M3FN, fmt_w: int = FP8_E4M3FN,
+                      y: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    M, K = x.shape
+    N = w.shape[0]
+    assert w.shape == (N, K) and x.is_contiguous() and w.is_contiguous()
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(fp8_mx_linear_workspace_bytes(M, K, N), dtype=torch.uint8, device=x.device)
+    _check(load_library().fp8_mx_linear_fwd(_ptr(x), _ptr(w), M, K, N, fmt_x, fmt_w, _ptr(y), _ptr(workspace),
+                                            workspace.numel(), _stream()))
+    return y

@@ -1,0 +1,131 @@
+"""GPU parity: MX (microscaling) block quantization, the block-scaled FP8 GEMM
+and the MX forward vs the CPU oracle.  Codes and E8M0 bytes bit for bit; the
+GEMM by relative Frobenius error <= 1e-3 (the matrix cores add the scaled
+products in an order of their own), bit for bit where every partial sum is
+exactly representable."""
+import numpy as np
+import pytest
+import torch
+
+import synthetic_inputs as si
+from oracle import fp8_oracle as orc
+from tests.gpu_util import dev_bf16, dev_u8, host_bf16_bits, host_f32, host_u8
+
+pytestmark = pytest.mark.gpu
+
+import paper_2507_16099_amd as fp8  # noqa: E402
+
+TOL = 1e-3
+FMTS = [orc.E4M3FN, orc.E5M2]
+
+
+def _dev_e(e):
+    rows, nb = e.shape
+    full = torch.zeros((rows, (nb + 3) // 4 * 4), dtype=torch.uint8, device="cuda")
+    full[:, :nb] = torch.from_numpy(np.ascontiguousarray(e)).cuda()
+    return full[:, :nb]
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+def test_mx_quantize_all_bf16_patterns(fmt):
+    """Every finite bfloat16 value, in blocks that mix magnitudes (a permutation
+    of all patterns) and in blocks of similar magnitude (sorted order)."""
+    allp = si.all_bf16_patterns().reshape(-1)
+    finite = allp[np.isfinite(si.bf16_bits_to_f32(allp))]
+    n = finite.size // 32 * 32
+    rng = np.random.default_rng(1)
+    for arr in (finite[:n], rng.permutation(finite)[:n]):
+        x = np.ascontiguousarray(arr.reshape(-1, 960))          # 65280 finite patterns = 68 rows of 30 blocks
+        q, e = fp8.fp8_mx_quantize(dev_bf16(x), fmt)
+        wq, we = orc.mx_quantize(x, fmt)
+        assert (host_u8(e) == we).all(), np.argwhere(host_u8(e) != we)[:4]
+        assert (host_u8(q) == wq).all(), np.argwhere(host_u8(q) != wq)[:4]
+
+
+@pytest.mark.parametrize("rows,cols,ld", [(1, 32, 32), (7, 96, 104), (300, 1024, 1024), (33, 4128, 4128), (5, 14336, 14336)])
+@pytest.mark.parametrize("fmt", FMTS)
+def test_mx_quantize_shapes(rows, cols, ld, fmt):
+    x = si.student_t_outlier_bf16((rows, cols), 3.0, 0.01, 100.0, seed=4, stream=rows)
+    x[rows // 2, :32] = 0
+    x[0, cols - 32:] = 0x8000
+    q, e = fp8.fp8_mx_quantize(dev_bf16(x, ld), fmt)
+    wq, we = orc.mx_quantize(x, fmt)
+    assert (host_u8(e) == we).all() and (host_u8(q) == wq).all()
+
+
+SHAPES = [(16, 16, 128), (33, 17, 256), (200, 300, 384), (256, 512, 512), (257, 129, 1280), (500, 70, 1024)]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_mx_gemm_exact_on_small_integers(M, N, K):
+    """Integer codes and power-of-two block scales: exact, so every mistake in the
+    assignment of blocks, scale bytes and rows to lanes shows up."""
+    rng = np.random.default_rng(M + N + K)
+    ai, bi = rng.integers(-3, 4, size=(M, K)), rng.integers(-3, 4, size=(N, K))
+    for fa, fb in ((orc.E4M3FN, orc.E4M3FN), (orc.E5M2, orc.E4M3FN), (orc.E4M3FN, orc.E5M2)):
+        a = orc.encode_array(ai.astype(np.float32), fa)
+        b = orc.encode_array(bi.astype(np.float32), fb)
+        # block scales within a factor of 4 of each other: with |sum per block| < 2^9 and at most 40
+        # blocks every partial sum then fits the 24-bit significand whatever the order of addition
+        ea = rng.integers(126, 129, size=(M, K // 32)).astype(np.uint8)
+        eb = rng.integers(126, 129, size=(N, K // 32)).astype(np.uint8)
+        want = orc.mx_mm(a, fa, ea, b, fb, eb)
+        got32 = host_f32(fp8.fp8_mx_scaled_mm(dev_u8(a), fa, _dev_e(ea), dev_u8(b), fb, _dev_e(eb), fp8.FP8_OUT_FP32))
+        assert (got32 == want.out32).all(), (M, N, K, fa, fb, np.argwhere(got32 != want.out32)[:4])
+        got16 = host_bf16_bits(fp8.fp8_mx_scaled_mm(dev_u8(a), fa, _dev_e(ea), dev_u8(b), fb, _dev_e(eb)))
+        assert (got16 == want.out16).all()
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_mx_gemm_random_codes(M, N, K):
+    rng = np.random.default_rng(M + 3 * N + K)
+    a = rng.integers(0, 0x78, size=(M, K)).astype(np.uint8) | (rng.integers(0, 2, size=(M, K)).astype(np.uint8) << 7)
+    b = rng.integers(0, 0x78, size=(N, K)).astype(np.uint8) | (rng.integers(0, 2, size=(N, K)).astype(np.uint8) << 7)
+    ea = rng.integers(100, 150, size=(M, K // 32)).astype(np.uint8)
+    eb = rng.integers(100, 150, size=(N, K // 32)).astype(np.uint8)
+    want = orc.mx_mm(a, orc.E4M3FN, ea, b, orc.E4M3FN, eb)
+    got32 = host_f32(fp8.fp8_mx_scaled_mm(dev_u8(a), 0, _dev_e(ea), dev_u8(b), 0, _dev_e(eb), fp8.FP8_OUT_FP32))
+    assert orc.rel_frobenius(got32, want.out32) <= TOL
+    assert orc.rel_frobenius(got32, want.acc64) <= TOL
+
+
+@pytest.mark.parametrize("M,K,N", [(64, 128, 64), (384, 256, 512), (208, 1152, 272), (1024, 384, 640)])
+def test_mx_linear_forward(M, K, N):
+    wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)
+    x, w = wl.x(), wl.w()
+    y = fp8.fp8_mx_linear_fwd(dev_bf16(x), dev_bf16(w))
+    want = orc.mx_linear_fwd(x, w)
+    got = host_bf16_bits(y)
+    assert orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want.out16)) <= TOL
+    assert float((got == want.out16).mean()) > 0.95
+
+
+def test_mx_rejects_bad_arguments():
+    x = torch.zeros((4, 48), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_mx_quantize(x, fp8.FP8_E4M3FN)                    # cols not a multiple of 32
+    a = torch.zeros((16, 64), dtype=torch.uint8, device="cuda")
+    e = torch.zeros((16, 4), dtype=torch.uint8, device="cuda")[:, :2]
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_mx_scaled_mm(a, 0, e, a, 0, e)                     # K not a multiple of 128
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_mx_linear_workspace_bytes(16, 96, 16)
+
+
+def test_mx_full_size_llama_ffn_forward_sampled_rows():
+    """Benchmark shape: X [16384, 4096], W [14336, 4096]; codes and scale bytes of
+    both operands on the whole tensors, the product on a stratified sample of rows."""
+    wl = si.WORKLOADS[si.BENCH_WORKLOAD]
+    x, w = wl.x(), wl.w()
+    xq, xe = fp8.fp8_mx_quantize(dev_bf16(x), fp8.FP8_E4M3FN)
+    wq, we = fp8.fp8_mx_quantize(dev_bf16(w), fp8.FP8_E4M3FN)
+    oxq, oxe = orc.mx_quantize(x, orc.E4M3FN)
+    owq, owe = orc.mx_quantize(w, orc.E4M3FN)
+    assert (host_u8(xq) == oxq).all() and (host_u8(xe) == oxe).all()
+    assert (host_u8(wq) == owq).all() and (host_u8(we) == owe).all()
+    y = fp8.fp8_mx_scaled_mm(xq, 0, xe, wq, 0, we)
+    rows = si.stratified_rows(wl.M, 32)
+    want = orc.mx_mm(oxq, orc.E4M3FN, oxe, owq, orc.E4M3FN, owe, rows)
+    got = host_bf16_bits(y[torch.from_numpy(rows).cuda()])
+    assert orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want.out16)) <= TOL
+    assert float((got == want.out16).mean()) > 0.97
