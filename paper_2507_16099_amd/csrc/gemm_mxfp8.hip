@@ -5,9 +5,10 @@
 // lane, 32 K-bytes of one operand row and ONE scale byte for them.
 //     out[m, n] = sum_blk 2^(ea[m,blk]-127) 2^(eb[n,blk]-127) sum_{k in blk} dec(a[m,k]) dec(b[n,k])
 //
-// Structure: the register-staged scheme of gemm_fp8.hip (256 x 256 tile, 8
-// wavefronts of 128 x 64, two LDS stages, next step's global loads in flight
-// during the MFMAs).  How the instruction pairs data and scales (measured with
+// Structure: the register-staged scheme of gemm_fp8.hip (256 x 256 tile, two LDS
+// stages, next step's global loads in flight during the MFMAs) with 4
+// wavefronts of 128 x 128 (one per SIMD: with 8 wavefronts the fragments, the
+// scales and the staging registers no longer fit beside 128 accumulators).  How the instruction pairs data and scales (measured with
 // one-hot blocks; it is the layout the plain kernels already use): lane
 // (l % 16, g = l / 16) supplies the 16-byte chunks g and g + 4 of its row's 128
 // K-bytes, and the scale byte in lane (l % 16, g) is the one of block g
@@ -33,8 +34,8 @@ typedef float f32x2_m __attribute__((ext_vector_type(2)));
 
 namespace mx {
 constexpr int BM = 256, BN = 256, BK = 128;
-constexpr int NT = 512;                      // 8 wavefronts, 2 (m) x 4 (n)
-constexpr int WM = 128, WN = 64;
+constexpr int NT = 256;                      // 4 wavefronts, 2 (m) x 2 (n): one per SIMD, 512 registers each
+constexpr int WM = 128, WN = 128;
 constexpr int FM = WM / 16, FN = WN / 16;
 constexpr int TILE = (BM + BN) * BK;         // 64 KB of codes
 constexpr int STAGE = TILE + (BM + BN) * 4;  // + one dword of scales per row
@@ -69,42 +70,46 @@ __global__ __launch_bounds__(mx::NT) void gemm_mxfp8_kernel(
     const int m0 = tm * BM, n0 = tn * BN;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave >> 2) * WM, wn0 = (wave & 3) * WN;
+    const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
 
-    // ---- global -> registers -> LDS: thread t owns chunk slot t & 7 of rows (t >> 3) + 64 i
+    // ---- global -> registers -> LDS: thread t owns chunk slot t & 7 of rows (t >> 3) + 32 i, i = 0..7.
+    //      The B key depends on bit 5 of the row, i.e. on the parity of i.
     const int srow = tid >> 3, spc = tid & 7;
     const int ca = spc ^ ((srow >> 1) & 7);
-    const int cb = spc ^ (((srow >> 1) & 1) | (((srow >> 4) & 3) << 1));
+    const int cb_e = spc ^ (((srow >> 1) & 1) | (((srow >> 4) & 3) << 1));
+    const int cb_o = spc ^ (((srow >> 1) & 1) | ((((srow >> 4) + 2) & 3) << 1));
     const uint8_t* a_ptr = A + (int64_t)(m0 + srow) * lda + ca * 16;
-    const uint8_t* b_ptr = B + (int64_t)(n0 + srow) * ldb + cb * 16;
-    const int64_t a_step = 64 * lda, b_step = 64 * ldb;
-    // scales: thread t < 256 owns A row t, the others B row t - 256
-    const int srow_s = tid & 255;
-    const bool s_is_b = tid >= 256;
-    const bool s_ok = s_is_b ? (n0 + srow_s < N) : (m0 + srow_s < M);
-    const uint8_t* s_ptr = s_is_b ? EB + (int64_t)(n0 + srow_s) * ld_eb : EA + (int64_t)(m0 + srow_s) * ld_ea;
+    const uint8_t* b_ptr = B + (int64_t)(n0 + srow) * ldb;
+    const int64_t a_step = 32 * lda, b_step = 32 * ldb;
+    // scales: thread t owns A row t and B row t of the tile
+    const bool sa_ok = m0 + tid < M, sb_ok = n0 + tid < N;
+    const uint8_t* sa_ptr = EA + (int64_t)(m0 + tid) * ld_ea;
+    const uint8_t* sb_ptr = EB + (int64_t)(n0 + tid) * ld_eb;
 
-    uint4 ra[4], rb[4];
-    uint32_t rs;
+    uint4 ra[8], rb[8];
+    uint32_t rsa, rsb;
     auto gload = [&](int kt) {
-        const int k0 = kt * BK;
-        const bool ka = k0 + ca * 16 < K, kb = k0 + cb * 16 < K;
+        const int k0 = kt * BK;                      // K % 128 == 0: every chunk of a step is inside K
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            ra[i] = (ka && m0 + srow + 64 * i < M) ? *reinterpret_cast<const uint4*>(a_ptr + i * a_step + k0) : make_uint4(0, 0, 0, 0);
-            rb[i] = (kb && n0 + srow + 64 * i < N) ? *reinterpret_cast<const uint4*>(b_ptr + i * b_step + k0) : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < 8; ++i) {
+            ra[i] = (m0 + srow + 32 * i < M) ? *reinterpret_cast<const uint4*>(a_ptr + i * a_step + k0) : make_uint4(0, 0, 0, 0);
+            rb[i] = (n0 + srow + 32 * i < N)
+                        ? *reinterpret_cast<const uint4*>(b_ptr + i * b_step + k0 + ((i & 1) ? cb_o : cb_e) * 16)
+                        : make_uint4(0, 0, 0, 0);
         }
-        rs = s_ok ? *reinterpret_cast<const uint32_t*>(s_ptr + 4 * kt) : 0u;   // K % 128 == 0: a full dword per step
+        rsa = sa_ok ? *reinterpret_cast<const uint32_t*>(sa_ptr + 4 * kt) : 0u;   // blocks 4 kt .. 4 kt + 3 of the row
+        rsb = sb_ok ? *reinterpret_cast<const uint32_t*>(sb_ptr + 4 * kt) : 0u;
     };
     auto lstore = [&](int stage) {
         uint8_t* as = smem + stage * STAGE + tid * 16;
         uint8_t* bs = as + BM * BK;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 8; ++i) {
             *reinterpret_cast<uint4*>(as + i * NT * 16) = ra[i];
             *reinterpret_cast<uint4*>(bs + i * NT * 16) = rb[i];
         }
-        *reinterpret_cast<uint32_t*>(smem + stage * STAGE + TILE + tid * 4) = rs;   // [0,256) A rows, [256,512) B rows
+        *reinterpret_cast<uint32_t*>(smem + stage * STAGE + TILE + tid * 4) = rsa;            // A rows
+        *reinterpret_cast<uint32_t*>(smem + stage * STAGE + TILE + BM * 4 + tid * 4) = rsb;   // B rows
     };
 
     // ---- LDS -> MFMA operands
@@ -112,7 +117,7 @@ __global__ __launch_bounds__(mx::NT) void gemm_mxfp8_kernel(
     const int key_a = (li >> 1) & 7;
     const int key_b = ((li >> 1) & 1) | ((li >> 2) << 1);
     const int a_lo = (wm0 + li) * BK + ((g ^ key_a) << 4), a_hi = (wm0 + li) * BK + (((g + 4) ^ key_a) << 4);
-    const int b_row = wn0 + 16 * (li >> 2) + (li & 3);          // + 4 t for fragment t
+    const int b_row = wn0 + 16 * (li >> 2) + (li & 3);          // + 64 grp + 4 t for fragment (grp, t)
     const int b_lo = BM * BK + b_row * BK + ((g ^ key_b) << 4), b_hi = BM * BK + b_row * BK + (((g + 4) ^ key_b) << 4);
     const int sa_off = TILE + (wm0 + li) * 4 + g, sb_off = TILE + BM * 4 + b_row * 4 + g;
 
@@ -132,9 +137,10 @@ __global__ __launch_bounds__(mx::NT) void gemm_mxfp8_kernel(
         v8i_m bf[FN];
         int sb[FN];
 #pragma unroll
-        for (int t = 0; t < FN; ++t) {
-            bf[t] = frag(base + 4 * t * BK, b_lo, b_hi);
-            sb[t] = base[sb_off + 16 * t];
+        for (int j = 0; j < FN; ++j) {               // fragment j = (grp, t) = (j / 4, j % 4)
+            const int rows = 64 * (j >> 2) + 4 * (j & 3);
+            bf[j] = frag(base + rows * BK, b_lo, b_hi);
+            sb[j] = base[sb_off + rows * 4];
         }
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
@@ -160,36 +166,39 @@ __global__ __launch_bounds__(mx::NT) void gemm_mxfp8_kernel(
         }
     }
 
-    // ---- epilogue: lane holds out[m0 + wm0 + 16 i + l%16][n0 + wn0 + 16 g + 4 t + r]
-    const int nb = n0 + wn0 + 16 * g;
+    // ---- epilogue: lane holds out[m0 + wm0 + 16 i + l%16][n0 + wn0 + 64 grp + 16 g + 4 t + r]
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
-        const int m = m0 + wm0 + 16 * i + li;
-        if (m >= M || nb >= N) continue;
-        float v[16];
+    for (int grp = 0; grp < FN / 4; ++grp) {
+        const int nb = n0 + wn0 + 64 * grp + 16 * g;
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+        for (int i = 0; i < FM; ++i) {
+            const int m = m0 + wm0 + 16 * i + li;
+            if (m >= M || nb >= N) continue;
+            float v[16];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) v[4 * t + r] = acc[i][t][r];
-        if constexpr (OUT_F32) {
-            float* dst = static_cast<float*>(out) + (int64_t)m * ld_out + nb;
-            if (nb + 16 <= N) {
+            for (int t = 0; t < 4; ++t)
 #pragma unroll
-                for (int e = 0; e < 16; e += 4)
-                    *reinterpret_cast<float4*>(dst + e) = make_float4(v[e], v[e + 1], v[e + 2], v[e + 3]);
+                for (int r = 0; r < 4; ++r) v[4 * t + r] = acc[i][grp * 4 + t][r];
+            if constexpr (OUT_F32) {
+                float* dst = static_cast<float*>(out) + (int64_t)m * ld_out + nb;
+                if (nb + 16 <= N) {
+#pragma unroll
+                    for (int e = 0; e < 16; e += 4)
+                        *reinterpret_cast<float4*>(dst + e) = make_float4(v[e], v[e + 1], v[e + 2], v[e + 3]);
+                } else {
+                    for (int e = 0; nb + e < N; ++e) dst[e] = v[e];
+                }
             } else {
-                for (int e = 0; nb + e < N; ++e) dst[e] = v[e];
-            }
-        } else {
-            uint16_t* dst = static_cast<uint16_t*>(out) + (int64_t)m * ld_out + nb;
-            uint32_t p[8];
+                uint16_t* dst = static_cast<uint16_t*>(out) + (int64_t)m * ld_out + nb;
+                uint32_t p[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) p[e] = mx_pack_bf16(v[2 * e], v[2 * e + 1]);
-            if (nb + 16 <= N) {
-                *reinterpret_cast<uint4*>(dst) = make_uint4(p[0], p[1], p[2], p[3]);
-                *reinterpret_cast<uint4*>(dst + 8) = make_uint4(p[4], p[5], p[6], p[7]);
-            } else {
-                for (int e = 0; nb + e < N; ++e) dst[e] = (uint16_t)(p[e >> 1] >> ((e & 1) * 16));
+                for (int e = 0; e < 8; ++e) p[e] = mx_pack_bf16(v[2 * e], v[2 * e + 1]);
+                if (nb + 16 <= N) {
+                    *reinterpret_cast<uint4*>(dst) = make_uint4(p[0], p[1], p[2], p[3]);
+                    *reinterpret_cast<uint4*>(dst + 8) = make_uint4(p[4], p[5], p[6], p[7]);
+                } else {
+                    for (int e = 0; nb + e < N; ++e) dst[e] = (uint16_t)(p[e >> 1] >> ((e & 1) * 16));
+                }
             }
         }
     }
