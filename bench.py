@@ -380,6 +380,20 @@ def main() -> int:
                                        "TFLOP/s": round(flop_step / (hp_ms * 1e-3) / 1e12, 1),
                                        "note": "same step with the weight gradient kept in bfloat16 (Appendix A)"}
 
+        # MX (microscaling) forward: block quantization of X and W, block-scaled GEMM
+        if K % 128 == 0:
+            mq = lambda inp, q, e: fp8.fp8_mx_quantize(inp, E4) if q is None else fp8.fp8_mx_quantize(inp, E4, q, e)
+            xm, xe = cast_leg("mx_quant_x", x, mq, M * K, 3)
+            wm, we = fp8.fp8_mx_quantize(w, E4)
+            ms = _event_time_ms(lambda: fp8.fp8_mx_scaled_mm(xm, E4, xe, wm, E4, we, 0, out=y), it, wu, torch)
+            tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+            kernels["mx_gemm_fwd"] = {"ms": round(ms, 4), "TFLOP/s": round(tf, 1), "frac_of_fp8_peak": round(tf / FP8_PEAK_TFLOPS, 4)}
+            wsm = torch.empty(fp8.fp8_mx_linear_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
+            ms = _event_time_ms(lambda: fp8.fp8_mx_linear_fwd(x, w, y=y, workspace=wsm), max(3, args.steps // 2), 2, torch)
+            result["mx_linear_fwd"] = {"ms": round(ms, 4), "TFLOP/s": round(2.0 * M * N * K / (ms * 1e-3) / 1e12, 1),
+                                       "note": "forward with both operands in MX blocks of 32 along K (E8M0 scales applied by the matrix cores)"}
+            del xm, xe, wm, we, wsm
+
         # vendor FP8 GEMM on the forward operands (context only; never linked into the library)
         try:
             a8 = xq.view(torch.float8_e4m3fn)

@@ -25,6 +25,8 @@
 #include "fp8_device.hpp"
 #include "launchers.hpp"
 
+#include <cstdlib>
+
 namespace fp8k {
 
 typedef int v8i_m __attribute__((ext_vector_type(8)));
@@ -233,6 +235,15 @@ hipError_t launch_gemm_mxfp8(const uint8_t* a, int64_t lda, int fmt_a, const uin
                              const uint8_t* b, int64_t ldb, int fmt_b, const uint8_t* eb, int64_t ld_eb, int64_t M,
                              int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32, hipStream_t st) {
     if (M == 0 || N == 0) return hipSuccess;
+    // large problems: the LDS-DMA kernel (FP8MI355_MX_VARIANT=0 forces this file's kernel, 1 the other)
+    {
+        const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
+        const char* e = std::getenv("FP8MI355_MX_VARIANT");
+        const bool big = e ? std::atoi(e) == 1 : tiles256 > 64;
+        if (big && K > 0 && gemm_fp8_pipelined_supported(lda, ldb) && ld_ea < (1 << 23) && ld_eb < (1 << 23))
+            return launch_gemm_mxfp8_snake(a, lda, fmt_a, ea, ld_ea, b, ldb, fmt_b, eb, ld_eb, M, N, K, out, ld_out, out_f32,
+                                           st);
+    }
     const int m = (int)M, n = (int)N, k = (int)K;
 #define FP8K_MX(FA_, FB_)                                                                                  \
     if (fmt_a == FA_ && fmt_b == FB_)                                                                      \

@@ -1,0 +1,397 @@
+// MX (microscaling) FP8 GEMM for gfx950, the block-scaled form of the "snake"
+// kernel of gemm_fp8_snake.hip (same 256 x 256 tile, four wavefronts of 128 x 128,
+// LDS-DMA loads, four-phase schedule, LDS layout and swizzle keys; see there).
+//     out[m, n] = sum_blk 2^(ea[m,blk]-127) 2^(eb[n,blk]-127) sum_{k in blk} dec(a[m,k]) dec(b[n,k])
+// with one E8M0 byte per row and block of 32 K-bytes (OCP MX specification v1.0).
+// What is added: v_mfma_scale_f32_16x16x128_f8f6f4 takes, in lane (l % 16, g = l / 16),
+// the scale byte of block g of operand row l % 16 (the 128 K-bytes of a step are 4
+// blocks; the hardware routes each scale to the lanes that hold its block's bytes,
+// which in this layout are chunks g and g + 4 of lanes ...).  Every K step therefore
+// also brings one dword of scales per tile row into LDS (two extra LDS-DMA loads
+// per wavefront: 64 A rows and 64 B rows), and every fragment read is followed by a
+// one-byte LDS read of its scale.  The epilogue has no scaling left to do.
+#include "fp8_device.hpp"
+#include "launchers.hpp"
+
+#include <type_traits>
+
+namespace fp8k {
+
+typedef int v4i_x __attribute__((ext_vector_type(4)));
+typedef unsigned v4u_x __attribute__((ext_vector_type(4)));
+typedef int v8i_x __attribute__((ext_vector_type(8)));
+typedef float v4f_x __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2_x __attribute__((ext_vector_type(2)));
+typedef float f32x2_x __attribute__((ext_vector_type(2)));
+
+namespace msn {
+constexpr int BM = 256, BN = 256, BK = 128;
+constexpr int NT = 256;
+constexpr int WM = 128, WN = 128;
+constexpr int TILE = (BM + BN) * BK;     // 64 KB of codes
+constexpr int STAGE = TILE + (BM + BN) * 4;   // + one dword of scales per row
+constexpr int GROUP_M = 4;
+constexpr int NUM_XCD = 8;
+}  // namespace msn
+
+__device__ __forceinline__ uint32_t msn_pack_bf16(float a, float b) {
+    f32x2_x v = {a, b};
+    bf16x2_x h = __builtin_convertvector(v, bf16x2_x);
+    uint32_t r;
+    __builtin_memcpy(&r, &h, 4);
+    return r;
+}
+
+// 16 bytes per lane from a raw buffer straight into LDS at lds_addr + lane * 16
+// (lds_addr wave-uniform).  Out-of-range lanes deliver zeros.  Inline assembly
+// on purpose: the compiler must not know that these loads write LDS, or it
+// would drain them before every LDS read and undo the prefetch.
+__device__ __forceinline__ void msn_lds_dma16(v4i_x rsrc, uint32_t lds_addr, uint32_t voffset) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voffset), "s"(rsrc)
+                 : "memory", "m0");
+}
+// 4 bytes per lane into LDS at lds_addr + lane * 4 (the scales of 64 rows)
+__device__ __forceinline__ void msn_lds_dma4(v4i_x rsrc, uint32_t lds_addr, uint32_t voffset) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voffset), "s"(rsrc)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ void msn_wait_all_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+template <int FA, int FB, bool OUT_F32>
+__global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
+    const uint8_t* __restrict__ A, int64_t lda, const uint8_t* __restrict__ EA, int64_t ld_ea,
+    const uint8_t* __restrict__ B, int64_t ldb, const uint8_t* __restrict__ EB, int64_t ld_eb, int M, int N,
+    int K, void* __restrict__ out, int64_t ld_out, int tiles_m, int tiles_n) {
+    using namespace msn;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    // ---- workgroup -> tile (XCD-aware: ids are dealt round-robin to the 8 XCDs;
+    //      each XCD gets a contiguous range of tiles walked in groups of tile rows)
+    const int ntiles = tiles_m * tiles_n;
+    const int per_xcd = gridDim.x / NUM_XCD;
+    const int logical = (blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
+    if (logical >= ntiles) return;
+    const int in_group = GROUP_M * tiles_n;
+    const int first_m = (logical / in_group) * GROUP_M;
+    const int gsize = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
+    const int tm = first_m + (logical % in_group) % gsize;
+    const int tn = (logical % in_group) / gsize;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
+
+    // ---- buffer descriptors of this tile's operand panels (raw buffers, sizes in bytes)
+    const int rows_a = M - m0 < BM ? M - m0 : BM, rows_b = N - n0 < BN ? N - n0 : BN;
+    const uint64_t pa = reinterpret_cast<uint64_t>(A + (int64_t)m0 * lda);
+    const uint64_t pb = reinterpret_cast<uint64_t>(B + (int64_t)n0 * ldb);
+    const v4i_x rsrc_a = {(int)(uint32_t)pa, (int)(uint32_t)(pa >> 32), (int)((int64_t)(rows_a - 1) * lda + K), 0x00020000};
+    const v4i_x rsrc_b = {(int)(uint32_t)pb, (int)(uint32_t)(pb >> 32), (int)((int64_t)(rows_b - 1) * ldb + K), 0x00020000};
+
+    // scale panels: rows m0.. of EA, n0.. of EB, K / 32 bytes per row; wave w fetches rows 64 w + lane
+    const uint64_t pea = reinterpret_cast<uint64_t>(EA + (int64_t)m0 * ld_ea);
+    const uint64_t peb = reinterpret_cast<uint64_t>(EB + (int64_t)n0 * ld_eb);
+    const v4i_x rsrc_ea = {(int)(uint32_t)pea, (int)(uint32_t)(pea >> 32), (int)((int64_t)(rows_a - 1) * ld_ea + K / 32), 0x00020000};
+    const v4i_x rsrc_eb = {(int)(uint32_t)peb, (int)(uint32_t)(peb >> 32), (int)((int64_t)(rows_b - 1) * ld_eb + K / 32), 0x00020000};
+    const uint32_t vea0 = (uint32_t)((wave * 64 + lane) * (int)ld_ea), veb0 = (uint32_t)((wave * 64 + lane) * (int)ld_eb);
+    const uint32_t lds_sc = (uint32_t)(size_t)smem + (uint32_t)TILE + (uint32_t)wave * 256u;   // + BM * 4 for B
+
+    // ---- global -> LDS.  Wave w fills row groups w, w+4, ... (8 rows each) of both
+    //      tiles; lane l fills (row l/8, chunk slot l%8) with logical chunk slot ^ key(row),
+    //      row = 8 * (4 * i + w) + l/8 for load i.
+    const int lrow = lane >> 3;
+    const int ca = (lane & 7) ^ ((4 * (wave & 1) + (lrow >> 1)) & 7);                 // A: (row >> 1) & 7
+    const int cb_e = (lane & 7) ^ (((lrow >> 1) & 1) | (((wave >> 1) & 3) << 1));     // B, even i: (row >> 4) & 3 = wave >> 1
+    const int cb_o = (lane & 7) ^ (((lrow >> 1) & 1) | (((2 + (wave >> 1)) & 3) << 1)); // B, odd i
+    const uint32_t va0 = (uint32_t)((wave * 8 + lrow) * (int)lda + ca * 16);
+    const uint32_t vb0_e = (uint32_t)((wave * 8 + lrow) * (int)ldb + cb_e * 16);
+    const uint32_t vb0_o = (uint32_t)((wave * 8 + lrow) * (int)ldb + cb_o * 16);
+    const uint32_t va_step = (uint32_t)(32 * (int)lda), vb_step = (uint32_t)(32 * (int)ldb);
+    const uint32_t lds_base = (uint32_t)(size_t)smem + (uint32_t)wave * 1024u;
+    // a panel offset never reaches 2^31 (checked on the host): adding 2^31 puts a
+    // lane outside its descriptor and zeros arrive
+    constexpr uint32_t OOB = 0x80000000u;
+
+    auto issue_loads = [&](int stage, int k0) {
+        const uint32_t ka = (k0 + ca * 16 < K) ? (uint32_t)k0 : OOB;
+        const uint32_t ke = (k0 + cb_e * 16 < K) ? (uint32_t)k0 : OOB;
+        const uint32_t ko = (k0 + cb_o * 16 < K) ? (uint32_t)k0 : OOB;
+        const uint32_t la = lds_base + (uint32_t)(stage * STAGE), lb = la + BM * BK;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) msn_lds_dma16(rsrc_a, la + i * 4096, va0 + (uint32_t)i * va_step + ka);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            msn_lds_dma16(rsrc_b, lb + i * 4096, ((i & 1) ? vb0_o + ko : vb0_e + ke) + (uint32_t)i * vb_step);
+        const uint32_t ks = k0 < K ? (uint32_t)(k0 >> 5) : OOB;      // byte offset of this step's 4 blocks in a scale row
+        msn_lds_dma4(rsrc_ea, lds_sc + (uint32_t)(stage * STAGE), vea0 + ks);
+        msn_lds_dma4(rsrc_eb, lds_sc + (uint32_t)(stage * STAGE) + BM * 4, veb0 + ks);
+    };
+
+    // ---- LDS -> fragments
+    const int r16 = lane & 15, g = lane >> 4;
+    const int key_a = (r16 >> 1) & 7;
+    const int key_b = ((r16 >> 1) & 1) | ((r16 >> 2) << 1);
+    int offa[2], offb[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        offa[c] = (wm0 + r16) * BK + (((g + 4 * c) ^ key_a) << 4);
+        offb[c] = BM * BK + (wn0 + 16 * (r16 >> 2) + (r16 & 3)) * BK + (((g + 4 * c) ^ key_b) << 4);
+    }
+    const int offsa = TILE + (wm0 + r16) * 4 + g;                                    // scale byte of block g of this lane's A row
+    const int offsb = TILE + BM * 4 + (wn0 + 16 * (r16 >> 2) + (r16 & 3)) * 4 + g;   // ... B row
+    v8i_x af[2][4], bf[2][4];   // [half][fragment in half]
+    int sa[2], sb[2];           // their scale bytes: byte f of sa[half] belongs to fragment f (selected by op_sel)
+    auto read_a = [&](const uint8_t* s, int half, int f) {
+        const int row_off = (half * 4 + f) * 16 * BK;
+        const uint4 x0 = *reinterpret_cast<const uint4*>(s + offa[0] + row_off);
+        const uint4 x1 = *reinterpret_cast<const uint4*>(s + offa[1] + row_off);
+        af[half][f] = v8i_x{(int)x0.x, (int)x0.y, (int)x0.z, (int)x0.w, (int)x1.x, (int)x1.y, (int)x1.z, (int)x1.w};
+    };
+    // the four scale bytes of a fragment half, packed into one register
+    auto scales_a = [&](const uint8_t* s, int half) {
+        const int o = offsa + half * 256;
+        return (int)((uint32_t)s[o] | ((uint32_t)s[o + 64] << 8) | ((uint32_t)s[o + 128] << 16) | ((uint32_t)s[o + 192] << 24));
+    };
+    auto scales_b = [&](const uint8_t* s, int half) {
+        const int o = offsb + half * 256;
+        return (int)((uint32_t)s[o] | ((uint32_t)s[o + 16] << 8) | ((uint32_t)s[o + 32] << 16) | ((uint32_t)s[o + 48] << 24));
+    };
+    auto read_b = [&](const uint8_t* s, int half, int f) {
+        const int row_off = (half * 64 + f * 4) * BK;   // group `half`, fragment t = f
+        const uint4 x0 = *reinterpret_cast<const uint4*>(s + offb[0] + row_off);
+        const uint4 x1 = *reinterpret_cast<const uint4*>(s + offb[1] + row_off);
+        bf[half][f] = v8i_x{(int)x0.x, (int)x0.y, (int)x0.z, (int)x0.w, (int)x1.x, (int)x1.y, (int)x1.z, (int)x1.w};
+    };
+
+    v4f_x acc[8][8];   // [A fragment][B fragment]
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = v4f_x{0.f, 0.f, 0.f, 0.f};
+
+    // MFMA number t of a phase pairs A fragment t / 4 with B fragment t % 4: the byte selectors of the
+    // two packed scale registers are immediates
+    auto mfma_sel = [&](int t, const v8i_x& b, const v8i_x& a, const v4f_x& c, int sbp, int sap) -> v4f_x {
+        switch (t) {
+#define MSN_CASE(T) case T: return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b, a, c, FB, FA, (T) & 3, sbp, (T) >> 2, sap);
+            MSN_CASE(0) MSN_CASE(1) MSN_CASE(2) MSN_CASE(3) MSN_CASE(4) MSN_CASE(5) MSN_CASE(6) MSN_CASE(7)
+            MSN_CASE(8) MSN_CASE(9) MSN_CASE(10) MSN_CASE(11) MSN_CASE(12) MSN_CASE(13) MSN_CASE(14)
+#undef MSN_CASE
+            default: return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b, a, c, FB, FA, 3, sbp, 3, sap);
+        }
+    };
+
+    // one phase: 16 MFMAs of A half AH x B half BH; in its slots, optionally the
+    // reads of one fragment half (RD_A: 1 = A half RH, 0 = B half RH, -1 = none)
+    // from stage `rs`, and eight LDS-DMA loads (DMA: 0 = A part, 1 = B part, -1 = none).
+    auto phase = [&](auto ah_t, auto bh_t, auto rda_t, auto rh_t, auto dma_t, const uint8_t* rs, uint32_t la, uint32_t lb,
+                     uint32_t ka, uint32_t ke, uint32_t ko, uint32_t lsc, uint32_t ks) {
+        constexpr int AH = decltype(ah_t)::value, BH = decltype(bh_t)::value, RDA = decltype(rda_t)::value,
+                      RH = decltype(rh_t)::value, DMA = decltype(dma_t)::value;
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const int i = t >> 2, j = t & 3;
+            acc[AH * 4 + i][BH * 4 + j] = mfma_sel(t, bf[BH][j], af[AH][i], acc[AH * 4 + i][BH * 4 + j], sb[BH], sa[AH]);
+            if constexpr (RDA == 1) { if (t % 2 == 0 && t < 8) read_a(rs, RH, t / 2); }
+            if constexpr (RDA == 0) { if (t % 2 == 0 && t < 8) read_b(rs, RH, t / 2); }
+            if constexpr (DMA == 0) { if (t % 2 == 1) msn_lds_dma16(rsrc_a, la + (t / 2) * 4096, va0 + (uint32_t)(t / 2) * va_step + ka); }
+            if constexpr (DMA == 1) {
+                if (t % 2 == 1)
+                    msn_lds_dma16(rsrc_b, lb + (t / 2) * 4096, (((t / 2) & 1) ? vb0_o + ko : vb0_e + ke) + (uint32_t)(t / 2) * vb_step);
+            }
+            // scales of the half that was read in slots 0..6, packed (the half is not in use in this phase)
+            if constexpr (RDA == 1) { if (t == 10) sa[RH] = scales_a(rs, RH); }
+            if constexpr (RDA == 0) { if (t == 10) sb[RH] = scales_b(rs, RH); }
+            // the refill of the scales rides in a slot that has neither a read nor a data load
+            if constexpr (DMA == 0) { if (t == 8) msn_lds_dma4(rsrc_ea, lsc, vea0 + ks); }
+            if constexpr (DMA == 1) { if (t == 8) msn_lds_dma4(rsrc_eb, lsc + BM * 4, veb0 + ks); }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using IN = std::integral_constant<int, -1>;
+
+    // K steps are processed in pairs (the B halves swap roles every step); an odd
+    // number of steps gets one phantom step whose loads are all out of range (zeros).
+    const int ksteps = (K + BK - 1) / BK;
+    const int kpairs = (ksteps + 1) / 2;
+    if (ksteps > 0) issue_loads(0, 0);
+    if (ksteps > 0) {
+        msn_wait_all_vmem();
+        __syncthreads();                       // stage 0 landed for every wave
+        issue_loads(1, BK);                    // (out of range if there is no step 1)
+#pragma unroll
+        for (int f = 0; f < 4; ++f) { read_a(smem, 0, f); read_b(smem, 0, f); }
+        sa[0] = scales_a(smem, 0);
+        sb[0] = scales_b(smem, 0);
+        sa[1] = sb[1] = 0;
+        __builtin_amdgcn_sched_barrier(0);
+
+        for (int kp = 0; kp < kpairs; ++kp) {
+#pragma unroll
+            for (int par = 0; par < 2; ++par) {
+                const int k = 2 * kp + par;
+                const uint8_t* s_cur = smem + par * STAGE;
+                const uint8_t* s_nxt = smem + (par ^ 1) * STAGE;
+                const int k2 = (k + 2) * BK;   // refill of this step's buffer (all out of range past K)
+                const uint32_t ka = (k2 + ca * 16 < K) ? (uint32_t)k2 : OOB;
+                const uint32_t ke = (k2 + cb_e * 16 < K) ? (uint32_t)k2 : OOB;
+                const uint32_t ko = (k2 + cb_o * 16 < K) ? (uint32_t)k2 : OOB;
+                const uint32_t la = lds_base + (uint32_t)(par * STAGE), lb = la + BM * BK;
+                const uint32_t lsc = lds_sc + (uint32_t)(par * STAGE);
+                const uint32_t ks = k2 < K ? (uint32_t)(k2 >> 5) : OOB;
+                if (par == 0) {
+                    // even step: B order 0,1,1,0.  Holds A0, B0 of this step.
+                    phase(I0{}, I0{}, I0{}, I1{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks);   // (A0,B0) | read B1 of this step
+                    phase(I0{}, I1{}, I1{}, I1{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks);   // (A0,B1) | read A1 of this step
+                    msn_wait_all_vmem();                // my part of step k+1 has landed
+                    __syncthreads();                   // ... and everyone's; this step's buffer is read out
+                    __builtin_amdgcn_sched_barrier(0);
+                    phase(I1{}, I1{}, I1{}, I0{}, I0{}, s_nxt, la, lb, ka, ke, ko, lsc, ks);   // (A1,B1) | read A0 of step k+1, refill A
+                    phase(I1{}, I0{}, I0{}, I1{}, I1{}, s_nxt, la, lb, ka, ke, ko, lsc, ks);   // (A1,B0) | read B1 of step k+1, refill B
+                } else {
+                    // odd step: B order 1,0,0,1.  Holds A0, B1 of this step.
+                    phase(I0{}, I1{}, I0{}, I0{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks);   // (A0,B1) | read B0 of this step
+                    phase(I0{}, I0{}, I1{}, I1{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks);   // (A0,B0) | read A1 of this step
+                    msn_wait_all_vmem();
+                    __syncthreads();
+                    __builtin_amdgcn_sched_barrier(0);
+                    phase(I1{}, I0{}, I1{}, I0{}, I0{}, s_nxt, la, lb, ka, ke, ko, lsc, ks);   // (A1,B0) | read A0 of step k+1, refill A
+                    phase(I1{}, I1{}, I0{}, I0{}, I1{}, s_nxt, la, lb, ka, ke, ko, lsc, ks);   // (A1,B1) | read B0 of step k+1, refill B
+                }
+            }
+        }
+        msn_wait_all_vmem();    // trailing (out-of-range) refills must not land in the epilogue's LDS
+    }
+
+    // ---- epilogue.  Lane holds output row m = 16*fi + l%16 and, per 64-wide B group,
+    //      the 16 consecutive columns 16*g + 4*t + r (fragment t, accumulator r).
+    __syncthreads();   // nobody's trailing refill can land in the staging rows below
+
+    if constexpr (OUT_F32) {
+#pragma unroll
+        for (int fi = 0; fi < 8; ++fi) {
+            const int r_loc = 16 * fi + r16;               // row inside the wave's quadrant
+            const int m = m0 + wm0 + r_loc;
+#pragma unroll
+            for (int grp = 0; grp < 2; ++grp) {
+                float v[16];
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[4 * t + r] = acc[fi][grp * 4 + t][r];
+                const int nb = n0 + wn0 + 64 * grp + 16 * g;
+                if (m < M && nb < N) {
+                    float* dst = static_cast<float*>(out) + (int64_t)m * ld_out + nb;
+                    if (nb + 16 <= N) {
+#pragma unroll
+                        for (int e = 0; e < 16; e += 4)
+                            *reinterpret_cast<float4*>(dst + e) = make_float4(v[e], v[e + 1], v[e + 2], v[e + 3]);
+                    } else {
+                        for (int e = 0; nb + e < N; ++e) dst[e] = v[e];
+                    }
+                }
+            }
+        }
+    } else {
+        // bfloat16: 16 rows at a time are scaled, rounded, parked in this wave's own
+        // 32 KB of LDS (row = 256 bytes = 16 chunks, chunk c stored at c ^ (row & 15))
+        // and streamed out as whole 256-byte rows, so the stores of one group of
+        // rows overlap the arithmetic of the next.  LDS operations of one wave
+        // execute in order; the wave barrier only keeps the compiler from moving
+        // the reads above the writes.
+        uint8_t* q = smem + wave * 32768;
+        const int c_rd = lane & 15;                        // chunk this lane streams out
+        const int n_rd = n0 + wn0 + c_rd * 8;
+        const bool interior = m0 + BM <= M && n0 + BN <= N;
+        uint16_t* orow = static_cast<uint16_t*>(out) + (int64_t)(m0 + wm0 + (lane >> 4)) * ld_out + n_rd;
+#pragma unroll
+        for (int fi = 0; fi < 8; ++fi) {
+            const int r_loc = 16 * fi + r16;
+            uint8_t* row = q + r_loc * 256;
+#pragma unroll
+            for (int grp = 0; grp < 2; ++grp) {
+                uint32_t p[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int e0 = 2 * e, e1 = 2 * e + 1;
+                    p[e] = msn_pack_bf16(acc[fi][grp * 4 + (e0 >> 2)][e0 & 3], acc[fi][grp * 4 + (e1 >> 2)][e1 & 3]);
+                }
+                const int c = 8 * grp + 2 * g;
+                *reinterpret_cast<uint4*>(row + ((c ^ r16) << 4)) = make_uint4(p[0], p[1], p[2], p[3]);
+                *reinterpret_cast<uint4*>(row + (((c + 1) ^ r16) << 4)) = make_uint4(p[4], p[5], p[6], p[7]);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int rr = 16 * fi + 4 * it + (lane >> 4);      // row in the quadrant
+                const uint4 v = *reinterpret_cast<const uint4*>(q + rr * 256 + ((c_rd ^ (rr & 15)) << 4));
+                uint16_t* dst = orow + (int64_t)(16 * fi + 4 * it) * ld_out;
+                if (interior) {
+                    // streaming store: the output is not read again by this kernel and
+                    // should not push the operand panels out of L2
+                    __builtin_nontemporal_store(v4u_x{v.x, v.y, v.z, v.w}, reinterpret_cast<v4u_x*>(dst));
+                } else if (m0 + wm0 + rr < M && n_rd < N) {
+                    if (n_rd + 8 <= N) {
+                        __builtin_nontemporal_store(v4u_x{v.x, v.y, v.z, v.w}, reinterpret_cast<v4u_x*>(dst));
+                    } else {
+                        const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+                        for (int e = 0; n_rd + e < N; ++e) dst[e] = (uint16_t)(w4[e >> 1] >> ((e & 1) * 16));
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int FA, int FB, bool OUT_F32>
+static hipError_t launch_msn(const uint8_t* a, int64_t lda, const uint8_t* ea, int64_t ld_ea, const uint8_t* b, int64_t ldb,
+                             const uint8_t* eb, int64_t ld_eb, int M, int N, int K, void* out, int64_t ld_out,
+                             hipStream_t st) {
+    using namespace msn;
+    auto kern = gemm_mxfp8_snake_kernel<FA, FB, OUT_F32>;
+    constexpr int lds = 2 * STAGE;
+    static bool attr_done = false;          // idempotent, a race is harmless
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const int64_t ntiles = (int64_t)tiles_m * tiles_n;
+    const int64_t grid = (ntiles + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
+    if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
+    kern<<<dim3((unsigned)grid), dim3(NT), lds, st>>>(a, lda, ea, ld_ea, b, ldb, eb, ld_eb, M, N, K, out, ld_out, tiles_m,
+                                                      tiles_n);
+    return hipGetLastError();
+}
+
+// same contract as launch_gemm_mxfp8; additionally lda, ldb < 2^23 and ld_ea, ld_eb < 2^23
+// (buffer offsets are 32-bit)
+hipError_t launch_gemm_mxfp8_snake(const uint8_t* a, int64_t lda, int fmt_a, const uint8_t* ea, int64_t ld_ea,
+                                   const uint8_t* b, int64_t ldb, int fmt_b, const uint8_t* eb, int64_t ld_eb, int64_t M,
+                                   int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32, hipStream_t st) {
+    if (M == 0 || N == 0) return hipSuccess;
+    const int m = (int)M, n = (int)N, k = (int)K;
+#define FP8K_MSN(FA_, FB_)                                                                                  \
+    if (fmt_a == FA_ && fmt_b == FB_)                                                                       \
+        return out_f32 ? launch_msn<FA_, FB_, true>(a, lda, ea, ld_ea, b, ldb, eb, ld_eb, m, n, k, out, ld_out, st) \
+                       : launch_msn<FA_, FB_, false>(a, lda, ea, ld_ea, b, ldb, eb, ld_eb, m, n, k, out, ld_out, st)
+    FP8K_MSN(FMT_E4M3FN, FMT_E4M3FN);
+    FP8K_MSN(FMT_E5M2, FMT_E4M3FN);
+    FP8K_MSN(FMT_E4M3FN, FMT_E5M2);
+    FP8K_MSN(FMT_E5M2, FMT_E5M2);
+#undef FP8K_MSN
+    return hipErrorInvalidValue;
+}
+
+}  // namespace fp8k

@@ -79,5 +79,9 @@ hipError_t launch_mx_quant(const void* x, int64_t rows, int64_t cols, int64_t ld
 hipError_t launch_gemm_mxfp8(const uint8_t* a, int64_t lda, int fmt_a, const uint8_t* ea, int64_t ld_ea,
                              const uint8_t* b, int64_t ldb, int fmt_b, const uint8_t* eb, int64_t ld_eb, int64_t M,
                              int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32, hipStream_t st);
+// the same product on the LDS-DMA "snake" schedule (large problems; leading dimensions below 2^23)
+hipError_t launch_gemm_mxfp8_snake(const uint8_t* a, int64_t lda, int fmt_a, const uint8_t* ea, int64_t ld_ea,
+                                   const uint8_t* b, int64_t ldb, int fmt_b, const uint8_t* eb, int64_t ld_eb, int64_t M,
+                                   int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32, hipStream_t st);
 
 }  // namespace fp8k

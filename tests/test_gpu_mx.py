@@ -56,8 +56,21 @@ def test_mx_quantize_shapes(rows, cols, ld, fmt):
 SHAPES = [(16, 16, 128), (33, 17, 256), (200, 300, 384), (256, 512, 512), (257, 129, 1280), (500, 70, 1024)]
 
 
+@pytest.fixture(params=["0", "1"], ids=["staged", "snake"])
+def mx_variant(request):
+    """Both MX GEMM kernels on every shape (the dispatch would pick by problem size)."""
+    import os
+    old = os.environ.get("FP8MI355_MX_VARIANT")
+    os.environ["FP8MI355_MX_VARIANT"] = request.param
+    yield request.param
+    if old is None:
+        os.environ.pop("FP8MI355_MX_VARIANT", None)
+    else:
+        os.environ["FP8MI355_MX_VARIANT"] = old
+
+
 @pytest.mark.parametrize("M,N,K", SHAPES)
-def test_mx_gemm_exact_on_small_integers(M, N, K):
+def test_mx_gemm_exact_on_small_integers(mx_variant, M, N, K):
     """Integer codes and power-of-two block scales: exact, so every mistake in the
     assignment of blocks, scale bytes and rows to lanes shows up."""
     rng = np.random.default_rng(M + N + K)
@@ -77,7 +90,7 @@ def test_mx_gemm_exact_on_small_integers(M, N, K):
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
-def test_mx_gemm_random_codes(M, N, K):
+def test_mx_gemm_random_codes(mx_variant, M, N, K):
     rng = np.random.default_rng(M + 3 * N + K)
     a = rng.integers(0, 0x78, size=(M, K)).astype(np.uint8) | (rng.integers(0, 2, size=(M, K)).astype(np.uint8) << 7)
     b = rng.integers(0, 0x78, size=(N, K)).astype(np.uint8) | (rng.integers(0, 2, size=(N, K)).astype(np.uint8) << 7)
