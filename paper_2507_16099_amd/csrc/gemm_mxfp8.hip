@@ -134,6 +134,20 @@ __global__ __launch_bounds__(mx::NT) void gemm_mxfp8_kernel(
         const uint4 x1 = *reinterpret_cast<const uint4*>(base + hi);
         return v8i_m{(int)x0.x, (int)x0.y, (int)x0.z, (int)x0.w, (int)x1.x, (int)x1.y, (int)x1.z, (int)x1.w};
     };
+    // The scaled MFMA as inline assembly with the accumulator tied to the destination: through the
+    // builtin the compiler picks a different destination and copies every accumulator back.  An
+    // accumulator is touched once per 64 MFMAs and read by other instructions only after the loop.
+    auto mfma = [&](v4f_m& c, const v8i_m& b, const v8i_m& a, int sbv, int sav) {
+#define MX_MFMA(FMT)                                                                               \
+    asm volatile("v_mfma_scale_f32_16x16x128_f8f6f4 %0, %1, %2, %0, %3, %4 op_sel_hi:[0,0,0]" FMT \
+                 : "+a"(c)                                                                         \
+                 : "v"(b), "v"(a), "v"(sbv), "v"(sav))
+        if constexpr (FB == 0 && FA == 0) MX_MFMA("");
+        if constexpr (FB == 1 && FA == 0) MX_MFMA(" cbsz:1");
+        if constexpr (FB == 0 && FA == 1) MX_MFMA(" blgp:1");
+        if constexpr (FB == 1 && FA == 1) MX_MFMA(" cbsz:1 blgp:1");
+#undef MX_MFMA
+    };
     auto compute = [&](int stage) {
         const uint8_t* base = smem + stage * STAGE;
         v8i_m bf[FN];
@@ -149,8 +163,7 @@ __global__ __launch_bounds__(mx::NT) void gemm_mxfp8_kernel(
             const v8i_m af = frag(base + 16 * i * BK, a_lo, a_hi);
             const int sa = base[sa_off + 64 * i];
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[j], af, acc[i][j], FB, FA, 0, sb[j], 0, sa);
+            for (int j = 0; j < FN; ++j) mfma(acc[i][j], bf[j], af, sb[j], sa);
         }
     };
 

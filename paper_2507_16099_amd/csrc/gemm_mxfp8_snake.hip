@@ -175,16 +175,46 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
         for (int j = 0; j < 8; ++j) acc[i][j] = v4f_x{0.f, 0.f, 0.f, 0.f};
 
     // MFMA number t of a phase pairs A fragment t / 4 with B fragment t % 4: the byte selectors of the
-    // two packed scale registers are immediates
-    auto mfma_sel = [&](int t, const v8i_x& b, const v8i_x& a, const v4f_x& c, int sbp, int sap) -> v4f_x {
-        switch (t) {
-#define MSN_CASE(T) case T: return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b, a, c, FB, FA, (T) & 3, sbp, (T) >> 2, sap);
-            MSN_CASE(0) MSN_CASE(1) MSN_CASE(2) MSN_CASE(3) MSN_CASE(4) MSN_CASE(5) MSN_CASE(6) MSN_CASE(7)
-            MSN_CASE(8) MSN_CASE(9) MSN_CASE(10) MSN_CASE(11) MSN_CASE(12) MSN_CASE(13) MSN_CASE(14)
-#undef MSN_CASE
-            default: return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b, a, c, FB, FA, 3, sbp, 3, sap);
-        }
+    // two packed scale registers are immediates.  Written as inline assembly with the accumulator
+    // tied to the destination: through the builtin the compiler gives the scaled MFMA a destination
+    // different from its accumulator input and copies every accumulator back (three extra moves per
+    // MFMA in this loop).  The instructions around it are far enough apart for its result and operand
+    // hazards: an accumulator is touched once per 16 MFMAs and read by other instructions only after
+    // the loop's last barrier; the scale registers are packed at least one phase before their use.
+#define MSN_CASE(T, SEL, FMT)                                                                                  \
+    case T:                                                                                                    \
+        asm volatile("v_mfma_scale_f32_16x16x128_f8f6f4 %0, %1, %2, %0, %3, %4 " SEL FMT                       \
+                     : "+a"(c)                                                                                 \
+                     : "v"(b), "v"(a), "v"(sbp), "v"(sap));                                                    \
+        break;
+#define MSN_ALL(FMT)                                                                                           \
+    switch (t) {                                                                                               \
+            MSN_CASE(0, "op_sel:[0,0,0] op_sel_hi:[0,0,0]", FMT) \
+            MSN_CASE(1, "op_sel:[1,0,0] op_sel_hi:[0,0,0]", FMT) \
+            MSN_CASE(2, "op_sel:[0,0,0] op_sel_hi:[1,0,0]", FMT) \
+            MSN_CASE(3, "op_sel:[1,0,0] op_sel_hi:[1,0,0]", FMT) \
+            MSN_CASE(4, "op_sel:[0,1,0] op_sel_hi:[0,0,0]", FMT) \
+            MSN_CASE(5, "op_sel:[1,1,0] op_sel_hi:[0,0,0]", FMT) \
+            MSN_CASE(6, "op_sel:[0,1,0] op_sel_hi:[1,0,0]", FMT) \
+            MSN_CASE(7, "op_sel:[1,1,0] op_sel_hi:[1,0,0]", FMT) \
+            MSN_CASE(8, "op_sel:[0,0,0] op_sel_hi:[0,1,0]", FMT) \
+            MSN_CASE(9, "op_sel:[1,0,0] op_sel_hi:[0,1,0]", FMT) \
+            MSN_CASE(10, "op_sel:[0,0,0] op_sel_hi:[1,1,0]", FMT) \
+            MSN_CASE(11, "op_sel:[1,0,0] op_sel_hi:[1,1,0]", FMT) \
+            MSN_CASE(12, "op_sel:[0,1,0] op_sel_hi:[0,1,0]", FMT) \
+            MSN_CASE(13, "op_sel:[1,1,0] op_sel_hi:[0,1,0]", FMT) \
+            MSN_CASE(14, "op_sel:[0,1,0] op_sel_hi:[1,1,0]", FMT) \
+            MSN_CASE(15, "op_sel:[1,1,0] op_sel_hi:[1,1,0]", FMT)                                             \
+    }
+    auto mfma_sel = [&](int t, const v8i_x& b, const v8i_x& a, v4f_x c, int sbp, int sap) -> v4f_x {
+        if constexpr (FB == 0 && FA == 0) { MSN_ALL("") }
+        if constexpr (FB == 1 && FA == 0) { MSN_ALL(" cbsz:1") }
+        if constexpr (FB == 0 && FA == 1) { MSN_ALL(" blgp:1") }
+        if constexpr (FB == 1 && FA == 1) { MSN_ALL(" cbsz:1 blgp:1") }
+        return c;
     };
+#undef MSN_ALL
+#undef MSN_CASE
 
     // one phase: 16 MFMAs of A half AH x B half BH; in its slots, optionally the
     // reads of one fragment half (RD_A: 1 = A half RH, 0 = B half RH, -1 = none)
