@@ -43,6 +43,20 @@ def big_variant(request):
     yield from _force_variant(request.param)
 
 
+@pytest.fixture(params=["0", "1"], ids=["direct", "lds_dma"])
+def few_rows_form(request):
+    """Both forms of the few-row kernel (operands straight into registers, or
+    through a wave-private LDS ring), with the few-row kernel forced for every
+    M <= 64."""
+    old = os.environ.get("FP8MI355_SKINNY_DMA")
+    os.environ["FP8MI355_SKINNY_DMA"] = request.param
+    yield from _force_variant("5")
+    if old is None:
+        os.environ.pop("FP8MI355_SKINNY_DMA", None)
+    else:
+        os.environ["FP8MI355_SKINNY_DMA"] = old
+
+
 def _rand_codes(shape, fmt, rng, emax_drop=2):
     """Random finite codes, magnitudes kept a few binades under the top."""
     mb = 3 if fmt == orc.E4M3FN else 2
@@ -128,7 +142,7 @@ SKINNY = [(1, 16, 16), (1, 4096, 4096), (5, 100, 400), (16, 1000, 2048), (17, 24
 
 
 @pytest.mark.parametrize("M,N,K", SKINNY)
-def test_few_rows_exact_on_small_integers(M, N, K):
+def test_few_rows_exact_on_small_integers(few_rows_form, M, N, K):
     """M <= 64 takes the kernel that streams B once (the decode shape of
     inference with pre-quantized weights): every K split and every count of
     16-row groups, exact on small integers, padded leading dimensions."""
@@ -150,7 +164,7 @@ def test_few_rows_exact_on_small_integers(M, N, K):
 
 @pytest.mark.parametrize("M,N,K", SKINNY)
 @pytest.mark.parametrize("ga,gb", [(orc.TENSOR, orc.TENSOR), (orc.ROW, orc.ROW), (orc.ROW, orc.TENSOR)])
-def test_few_rows_random_codes_within_tolerance(M, N, K, ga, gb):
+def test_few_rows_random_codes_within_tolerance(few_rows_form, M, N, K, ga, gb):
     rng = np.random.default_rng(M + 3 * N + K)
     a, b = _rand_codes((M, K), orc.E4M3FN, rng), _rand_codes((N, K), orc.E4M3FN, rng)
     sa = rng.uniform(0.5, 300, 1 if ga == orc.TENSOR else M).astype(np.float32)
