@@ -345,6 +345,23 @@ def mx_linear_fwd(x, w, fmt_x=E4M3FN, fmt_w=E4M3FN, rows=None) -> MMResult:
     return mx_mm(xq, fmt_x, xe, wq, fmt_w, we, rows)
 
 
+def mx_linear_bwd(dy, x, w, fmt_dy=E4M3FN, fmt_x=E4M3FN, fmt_w=E4M3FN, rows_dx=None, rows_dw=None):
+    """Backward of the MX linear layer.  The blocks of 32 run along each
+    product's own contraction axis (OCP MX v1.0 Section 6.2: the scaled dot
+    product is defined over blocks of the contracted index), so every operand is
+    re-quantized from its bfloat16 original in the orientation the product needs:
+      dX[m,k] = sum_n dY[m,n] W[n,k]:  dY in blocks along N, W^T [K,N] in blocks along N;
+      dW[n,k] = sum_m dY[m,n] X[m,k]:  dY^T [N,M] and X^T [K,M] in blocks along M.
+    Returns (dx, dw) as MMResult; rows_dx / rows_dw select output rows."""
+    dyq, dye = mx_quantize(dy, fmt_dy)
+    wtq, wte = mx_quantize(np.ascontiguousarray(w.T), fmt_w)
+    dx = mx_mm(dyq, fmt_dy, dye, wtq, fmt_w, wte, rows_dx)
+    dytq, dyte = mx_quantize(np.ascontiguousarray(dy.T), fmt_dy)
+    xtq, xte = mx_quantize(np.ascontiguousarray(x.T), fmt_x)
+    dw = mx_mm(dytq, fmt_dy, dyte, xtq, fmt_x, xte, rows_dw)
+    return dx, dw
+
+
 def linear_bwd_dw_hp(dy, x, rows=None):
     """Weight gradient of the rowwise_gw_hp recipe (Appendix A: the grad_weight
     GEMM stays in bfloat16): dW[n,k] = sum_m dY[m,n] X[m,k] on the unquantized

@@ -155,3 +155,51 @@ def test_mx_keeps_small_blocks_that_rowwise_scaling_flushes():
     row = orc.linear_fwd(x, w, orc.Recipe(gran=orc.ROW))[0]
     e_mx, e_row = orc.rel_frobenius(mx.out32, true), orc.rel_frobenius(row.out32, true)
     assert e_mx < 0.08 and e_row > 0.9, (e_mx, e_row)
+
+
+def test_mx_linear_bwd_exact_on_integers_and_block_axes():
+    """Small integers survive MX quantization unchanged, so both gradients must
+    equal the integer products exactly (catches a transposed or swapped operand).
+    Scaling every other row of dY (or of W) by 2^-20 then shows which axis the
+    blocks run along: a block ALONG such a row keeps it (own exponent), a block
+    ACROSS 32 rows loses the small rows (below half the smallest subnormal of
+    the shared exponent)."""
+    rng = np.random.default_rng(11)
+    M, K, N = 64, 96, 32
+    dyi, xi, wi = rng.integers(-3, 4, size=(M, N)), rng.integers(-3, 4, size=(M, K)), rng.integers(-3, 4, size=(N, K))
+    dyi[0::2][dyi[0::2] == 0] = 3          # every block across rows holds a full-size element
+    wi[0::2][wi[0::2] == 0] = 3
+    dy, x, w = (_bf16(a.astype(np.float32)) for a in (dyi, xi, wi))
+    dx, dw = orc.mx_linear_bwd(dy, x, w)
+    assert (dx.out32 == (dyi @ wi).astype(np.float32)).all()
+    assert (dw.out32 == (dyi.T @ xi).astype(np.float32)).all()
+    assert dx.out32.shape == (M, K) and dw.out32.shape == (N, K)
+
+    small = np.where(np.arange(M) % 2 == 1, 2.0 ** -20, 1.0)[:, None]
+    dy_s = _bf16((dyi * small).astype(np.float32))
+    dx, dw = orc.mx_linear_bwd(dy_s, x, w)
+    assert (dx.out32 == ((dyi * small) @ wi).astype(np.float32)).all()            # blocks along N: rows keep their range
+    dy_flushed = np.where(np.arange(M)[:, None] % 2 == 1, 0, dyi)
+    assert (dw.out32 == (dy_flushed.T @ xi).astype(np.float32)).all()            # blocks along M: small rows are lost
+
+    small_n = np.where(np.arange(N) % 2 == 1, 2.0 ** -20, 1.0)[:, None]
+    w_s = _bf16((wi * small_n).astype(np.float32))
+    dx, _ = orc.mx_linear_bwd(dy, x, w_s)
+    w_flushed = np.where(np.arange(N)[:, None] % 2 == 1, 0, wi)
+    assert (dx.out32 == (dyi @ w_flushed).astype(np.float32)).all()              # W is blocked along N for dX
+    assert (orc.mx_linear_fwd(x, w_s).out32 == (xi @ (wi * small_n).T).astype(np.float32)).all()   # and along K forward
+
+
+def test_mx_linear_bwd_close_to_the_unquantized_gradients():
+    M, K, N = 96, 128, 64
+    dy = si.normal_bf16((M, N), 1e-3, seed=5, stream=0)
+    x = si.normal_bf16((M, K), 1.0, seed=5, stream=1)
+    w = si.normal_bf16((N, K), 0.02, seed=5, stream=2)
+    dx, dw = orc.mx_linear_bwd(dy, x, w)
+    true_dx = orc.bf16_mm_f64(dy, np.ascontiguousarray(w.T))
+    true_dw = orc.bf16_mm_f64(np.ascontiguousarray(dy.T), np.ascontiguousarray(x.T))
+    assert orc.rel_frobenius(dx.out32, true_dx) < 0.06
+    assert orc.rel_frobenius(dw.out32, true_dw) < 0.06
+    rows = np.array([5, 63], np.int64)
+    sx, sw = orc.mx_linear_bwd(dy, x, w, rows_dx=rows, rows_dw=rows)
+    assert (sx.out32 == dx.out32[rows]).all() and (sw.out32 == dw.out32[rows]).all()
