@@ -392,7 +392,23 @@ def main() -> int:
             ms = _event_time_ms(lambda: fp8.fp8_mx_linear_fwd(x, w, y=y, workspace=wsm), max(3, args.steps // 2), 2, torch)
             result["mx_linear_fwd"] = {"ms": round(ms, 4), "TFLOP/s": round(2.0 * M * N * K / (ms * 1e-3) / 1e12, 1),
                                        "note": "forward with both operands in MX blocks of 32 along K (E8M0 scales applied by the matrix cores)"}
-            del xm, xe, wm, we, wsm
+            del xm, xe, wm, we
+            if wl.backward and M % 128 == 0 and N % 128 == 0:
+                mqt = lambda inp, q, e: fp8.fp8_mx_quantize_t(inp, E4) if q is None else fp8.fp8_mx_quantize_t(inp, E4, q, e)
+                cast_leg("mx_quant_dy_t", dy, mqt, M * N, 3)
+                cast_leg("mx_quant_x_t", x, mqt, M * K, 3)
+                torch.cuda.empty_cache()
+                wsb = torch.empty(fp8.fp8_mx_linear_bwd_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
+
+                def mx_step():
+                    fp8.fp8_mx_linear_fwd(x, w, y=y, workspace=wsm)
+                    fp8.fp8_mx_linear_bwd(dy, x, w, dx=dx, dw=dw, workspace=wsb)
+                ms = _event_time_ms(mx_step, max(3, args.steps // 2), 2, torch)
+                result["mx_linear_fwd_bwd"] = {"ms_per_step": round(ms, 4), "TFLOP/s": round(flop_step / (ms * 1e-3) / 1e12, 1),
+                                               "note": "forward + backward with every operand in MX blocks along the contracted axis "
+                                                       "(6 block quantizations + 3 block-scaled GEMMs)"}
+                del wsb
+            del wsm
 
         # vendor FP8 GEMM on the forward operands (context only; never linked into the library)
         try:

@@ -233,15 +233,34 @@ int fp8_linear_fwd_prequantized(const void* x, int64_t M, int64_t K, int fmt_x, 
  *   K % 128 == 0; ld_ea, ld_eb multiples of 4; out bfloat16 or fp32 (FP8_OUT_FP32).
  * fp8_mx_linear_fwd: Y = X W^T with both operands quantized per call into MX
  *   blocks along K; workspace of fp8_mx_linear_workspace_bytes(M, K, N) bytes.
+ * fp8_mx_quantize_t: the same conversion with the blocks running down the
+ *   columns of x [rows, cols] (rows % 32 == 0) and the result written transposed:
+ *   qt_out [cols, rows] (ld_q % 16 == 0), e8m0_t_out [cols, rows / 32] (ld_e % 4 == 0),
+ *   equal to fp8_mx_quantize of the transposed matrix.  It produces the
+ *   contraction-contiguous operands of the backward products.
+ * fp8_mx_linear_bwd: dX [M, K] = dY W and dW [N, K] = dY^T X (bfloat16; either
+ *   output may be NULL).  The MX specification (Section 6.2) defines the scaled
+ *   dot product over blocks of the contracted index, so each operand is
+ *   re-quantized from its bfloat16 original with the blocks along that product's
+ *   contraction axis: dY along N and W^T along N for dX, dY^T along M and X^T
+ *   along M for dW.  M % 128 == 0, N % 128 == 0, K % 8 == 0; dy [M, N], x [M, K],
+ *   w [N, K] dense bfloat16; workspace of fp8_mx_linear_bwd_workspace_bytes bytes,
+ *   256-byte aligned.
  */
 int fp8_mx_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int format,
                     uint8_t* q_out, int64_t ld_q, uint8_t* e8m0_out, int64_t ld_e, void* stream);
+int fp8_mx_quantize_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int format,
+                      uint8_t* qt_out, int64_t ld_q, uint8_t* e8m0_t_out, int64_t ld_e, void* stream);
 int fp8_mx_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const uint8_t* ea, int64_t ld_ea,
                      const uint8_t* b, int64_t ldb, int fmt_b, const uint8_t* eb, int64_t ld_eb,
                      int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int flags, void* stream);
 size_t fp8_mx_linear_workspace_bytes(int64_t M, int64_t K, int64_t N);
 int fp8_mx_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N, int fmt_x, int fmt_w,
                       void* y, void* workspace, size_t workspace_bytes, void* stream);
+size_t fp8_mx_linear_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N);
+int fp8_mx_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int64_t K, int64_t N, int fmt_dy,
+                      int fmt_x, int fmt_w, void* dx, void* dw, void* workspace, size_t workspace_bytes,
+                      void* stream);
 
 #ifdef __cplusplus
 }

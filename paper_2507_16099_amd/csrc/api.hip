@@ -452,6 +452,21 @@ int fp8_mx_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int f
     return FP8_OK;
 }
 
+int fp8_mx_quantize_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int format, uint8_t* qt_out, int64_t ld_q,
+                      uint8_t* e8m0_t_out, int64_t ld_e, void* stream) {
+    g_err[0] = 0;
+    const char* fn = "fp8_mx_quantize_t";
+    if (!fmt_ok(format)) return fail(FP8_ERR_ENUM, "%s: unknown format %d", fn, format);
+    if (int rc = check_bf16(fn, x, rows, cols, ld)) return rc;
+    if (rows % 32 != 0) return fail(FP8_ERR_SHAPE, "%s: rows=%lld must be a multiple of the block size 32", fn, (long long)rows);
+    if (int rc = check_q_out(fn, qt_out, cols, rows, ld_q, 0)) return rc;
+    if (ld_e < rows / 32 || ld_e % 4 != 0) return fail(FP8_ERR_SHAPE, "%s: ld_e=%lld must be >= rows/32 and a multiple of 4", fn, (long long)ld_e);
+    if (rows > 0 && cols > 0 && !e8m0_t_out) return fail(FP8_ERR_NULL, "%s: e8m0_t_out is NULL", fn);
+    if (!aligned(e8m0_t_out, 4)) return fail(FP8_ERR_ALIGN, "%s: e8m0_t_out not 4-byte aligned", fn);
+    FP8_TRY(fp8k::launch_mx_quant_t(x, rows, cols, ld, format, qt_out, ld_q, e8m0_t_out, ld_e, static_cast<hipStream_t>(stream)));
+    return FP8_OK;
+}
+
 int fp8_mx_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const uint8_t* ea, int64_t ld_ea, const uint8_t* b,
                      int64_t ldb, int fmt_b, const uint8_t* eb, int64_t ld_eb, int64_t M, int64_t N, int64_t K, void* out,
                      int64_t ld_out, int flags, void* stream) {
@@ -522,6 +537,84 @@ int fp8_mx_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_
     FP8_TRY(fp8k::launch_mx_quant(w, N, K, K, fmt_w, ws + p.wq, K, ws + p.we, K / 32, st));
     FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.xq, K, fmt_x, ws + p.xe, K / 32, ws + p.wq, K, fmt_w, ws + p.we, K / 32, M, N, K, y,
                                     N, 0, st));
+    return FP8_OK;
+}
+
+namespace {
+// workspace of the MX backward: the four re-quantized operands and their block scales
+struct MxBwdPlan { size_t dyq, dye, wtq, wte, dytq, dyte, xtq, xte, total; };
+MxBwdPlan plan_mx_bwd(int64_t M, int64_t K, int64_t N) {
+    MxBwdPlan p{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    p.dyq = take((size_t)M * N);
+    p.dye = take((size_t)M * (N / 32));
+    p.wtq = take((size_t)K * N);
+    p.wte = take((size_t)K * (N / 32));
+    p.dytq = take((size_t)N * M);
+    p.dyte = take((size_t)N * (M / 32));
+    p.xtq = take((size_t)K * M);
+    p.xte = take((size_t)K * (M / 32));
+    p.total = o;
+    return p;
+}
+int check_mx_bwd_dims(const char* fn, int64_t M, int64_t K, int64_t N) {
+    if (M < 0 || K < 0 || N < 0 || M > kMaxDim || K > kMaxDim || N > kMaxDim)
+        return fail(FP8_ERR_SHAPE, "%s: M=%lld K=%lld N=%lld out of range", fn, (long long)M, (long long)K, (long long)N);
+    if (M % 128 != 0 || N % 128 != 0)
+        return fail(FP8_ERR_SHAPE, "%s: the backward contracts over M and N: M=%lld, N=%lld must be multiples of 128", fn,
+                    (long long)M, (long long)N);
+    if (K % 8 != 0) return fail(FP8_ERR_SHAPE, "%s: K=%lld must be a multiple of 8 (dense bfloat16 rows)", fn, (long long)K);
+    return FP8_OK;
+}
+}  // namespace
+
+size_t fp8_mx_linear_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+    g_err[0] = 0;
+    if (check_mx_bwd_dims("fp8_mx_linear_bwd_workspace_bytes", M, K, N)) return 0;
+    const size_t t = plan_mx_bwd(M, K, N).total;
+    return t ? t : 256;
+}
+
+int fp8_mx_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int64_t K, int64_t N, int fmt_dy,
+                      int fmt_x, int fmt_w, void* dx, void* dw, void* workspace, size_t workspace_bytes, void* stream) {
+    g_err[0] = 0;
+    const char* fn = "fp8_mx_linear_bwd";
+    if (!fmt_ok(fmt_dy) || !fmt_ok(fmt_x) || !fmt_ok(fmt_w)) return fail(FP8_ERR_ENUM, "%s: unknown fp8 format", fn);
+    if (int rc = check_mx_bwd_dims(fn, M, K, N)) return rc;
+    if (int rc = check_bf16("fp8_mx_linear_bwd(dy)", dy, M, N, N)) return rc;
+    if (dx) if (int rc = check_bf16("fp8_mx_linear_bwd(w)", w, N, K, K)) return rc;
+    if (dw) if (int rc = check_bf16("fp8_mx_linear_bwd(x)", x, M, K, K)) return rc;
+    if (!dx && !dw) return FP8_OK;
+    if (M == 0 || N == 0 || K == 0) {
+        // an empty contraction leaves an all-zero gradient
+        hipStream_t st0 = static_cast<hipStream_t>(stream);
+        if (dx && M > 0 && K > 0) FP8_TRY(fp8k::launch_fill_u32(static_cast<uint32_t*>(dx), M * K / 2, 0u, st0));
+        if (dw && N > 0 && K > 0) FP8_TRY(fp8k::launch_fill_u32(static_cast<uint32_t*>(dw), N * K / 2, 0u, st0));
+        return FP8_OK;
+    }
+    if (!workspace) return fail(FP8_ERR_NULL, "%s: workspace is NULL", fn);
+    if ((dx && !aligned(dx, 16)) || (dw && !aligned(dw, 16)) || !aligned(workspace, 256))
+        return fail(FP8_ERR_ALIGN, "%s: dx, dw (16) / workspace (256) misaligned", fn);
+    const MxBwdPlan p = plan_mx_bwd(M, K, N);
+    if (workspace_bytes < p.total) return fail(FP8_ERR_WORKSPACE, "%s: workspace %zu < %zu bytes", fn, workspace_bytes, p.total);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    // all quantizations first, then the products back to back
+    if (dx) {
+        FP8_TRY(fp8k::launch_mx_quant(dy, M, N, N, fmt_dy, ws + p.dyq, N, ws + p.dye, N / 32, st));
+        FP8_TRY(fp8k::launch_mx_quant_t(w, N, K, K, fmt_w, ws + p.wtq, N, ws + p.wte, N / 32, st));
+    }
+    if (dw) {
+        FP8_TRY(fp8k::launch_mx_quant_t(dy, M, N, N, fmt_dy, ws + p.dytq, M, ws + p.dyte, M / 32, st));
+        FP8_TRY(fp8k::launch_mx_quant_t(x, M, K, K, fmt_x, ws + p.xtq, M, ws + p.xte, M / 32, st));
+    }
+    if (dx)
+        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dyq, N, fmt_dy, ws + p.dye, N / 32, ws + p.wtq, N, fmt_w, ws + p.wte, N / 32,
+                                        M, K, N, dx, K, 0, st));
+    if (dw)
+        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dytq, M, fmt_dy, ws + p.dyte, M / 32, ws + p.xtq, M, fmt_x, ws + p.xte, M / 32,
+                                        N, K, M, dw, K, 0, st));
     return FP8_OK;
 }
 

@@ -829,4 +829,134 @@ hipError_t launch_mx_quant(const void* x, int64_t rows, int64_t cols, int64_t ld
     return hipGetLastError();
 }
 
+// MX block quantization with the blocks running DOWN the columns of x and the
+// output written transposed: qt [cols, rows] codes and et [cols, rows / 32] E8M0
+// bytes, i.e. the K-contiguous operand of a product that contracts over the
+// rows of x (the backward products of the MX linear layer).  rows % 32 == 0.
+// Same tile scheme as the transposing cast above (128 x 128 tile, 8 x 8 register
+// blocks, byte transpose, swizzled LDS tile, 128-bit streaming stores); a
+// wavefront holds exactly one block of 32 rows (4 thread rows x 8), so the
+// block maxima of its 128 columns are two cross-lane steps away.
+template <int FMT>
+__global__ __launch_bounds__(256) void mx_quant_t_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                          int64_t ld, uint8_t* __restrict__ qt, int64_t ld_t,
+                                                          uint8_t* __restrict__ et, int64_t ld_e, int nx, int ny) {
+    constexpr int TR = 128, SLOTS = TR / 8, PARTS = TR / 16;
+    constexpr int EMAX = FMT == FMT_E4M3FN ? 8 : 15;
+    __shared__ __attribute__((aligned(16))) uint2 tile[128 * SLOTS];
+    __shared__ __attribute__((aligned(16))) uint8_t ebytes[128 * 4];   // [column of the tile][block of the tile]
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    constexpr int PX = 16, PY = 16;
+    const int pxc = (nx + PX - 1) / PX;
+    const int patch = blockIdx.x / (PX * PY), within = blockIdx.x % (PX * PY);
+    const int bx = (patch % pxc) * PX + within % PX, by = (patch / pxc) * PY + within / PX;
+    if (bx >= nx || by >= ny) return;
+    const int64_t r0 = (int64_t)bx * TR, c0 = (int64_t)by * 128;
+    const int64_t c = c0 + tx * 8;
+
+    uint4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int64_t r = r0 + ty * 8 + j;
+        v[j] = make_uint4(0, 0, 0, 0);
+        if (r < rows) {
+            const uint16_t* src = x + r * ld + c;
+            if (c + 8 <= cols) {
+                v[j] = load_stream(src);
+            } else if (c < cols) {
+                uint32_t t[4] = {0, 0, 0, 0};
+                for (int e = 0; c + e < cols; ++e) t[e >> 1] |= (uint32_t)src[e] << ((e & 1) * 16);
+                v[j] = make_uint4(t[0], t[1], t[2], t[3]);
+            }
+        }
+    }
+    // maxima of the 8 columns over this thread's 8 rows (two 15-bit magnitudes per register), then over the
+    // 4 thread rows of the wavefront (lanes l, l ^ 16, l ^ 32, l ^ 48)
+    uint32_t m[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        m[0] = pk_absmax(m[0], v[j].x);
+        m[1] = pk_absmax(m[1], v[j].y);
+        m[2] = pk_absmax(m[2], v[j].z);
+        m[3] = pk_absmax(m[3], v[j].w);
+    }
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) m[i] = pk_absmax(m[i], (uint32_t)__shfl_xor((int)m[i], off, 64));
+    float factor[8];
+    uint32_t bytes_lo = 0, bytes_hi = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const uint32_t mag = (m[e >> 1] >> ((e & 1) * 16)) & 0x7FFFu;
+        int byte = 0;
+        if (mag != 0) {
+            const int ef = (int)(mag >> 7);
+            const int fl = ef > 0 ? ef - 127 : (31 - __builtin_clz(mag)) - 133;
+            byte = fl - EMAX + 127;
+            byte = byte < 0 ? 0 : (byte > 254 ? 254 : byte);
+        }
+        factor[e] = __uint_as_float((uint32_t)(254 - byte) << 23);
+        if (e < 4) bytes_lo |= (uint32_t)byte << (8 * e); else bytes_hi |= (uint32_t)byte << (8 * (e - 4));
+    }
+    if ((ty & 3) == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            ebytes[(tx * 8 + e) * 4 + (ty >> 2)] = (uint8_t)(((e < 4 ? bytes_lo : bytes_hi) >> (8 * (e & 3))) & 0xFFu);
+    }
+
+    uint32_t w[8][2];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint2 b = cast8<FMT>(v[j], factor);
+        w[j][0] = b.x;
+        w[j][1] = b.y;
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint32_t lo[4], hi[4];
+        transpose4x4_bytes(w[0][h], w[1][h], w[2][h], w[3][h], lo);
+        transpose4x4_bytes(w[4][h], w[5][h], w[6][h], w[7][h], hi);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int cc = tx * 8 + h * 4 + i;  // output row inside the tile
+            tile[cc * SLOTS + (ty ^ (2 * (tx & 7)))] = make_uint2(lo[i], hi[i]);
+        }
+    }
+    __syncthreads();
+
+    const uint4* tile16 = reinterpret_cast<const uint4*>(tile);
+    constexpr int ROWS_PER_IT = 256 / PARTS;
+#pragma unroll
+    for (int it = 0; it < 128 / ROWS_PER_IT; ++it) {
+        const int cc = it * ROWS_PER_IT + (threadIdx.x / PARTS), p = threadIdx.x % PARTS;
+        const int64_t oc = c0 + cc, orow = r0 + p * 16;
+        if (oc >= cols || orow >= rows) continue;      // rows % 32 == 0: a 16-byte piece is inside or outside
+        store_stream(qt + oc * ld_t + orow, tile16[cc * PARTS + (p ^ ((cc >> 3) & 7))]);
+    }
+    if (threadIdx.x < 128 && c0 + threadIdx.x < cols) {
+        uint8_t* dst = et + (c0 + threadIdx.x) * ld_e + r0 / 32;
+        const uint32_t four = reinterpret_cast<const uint32_t*>(ebytes)[threadIdx.x];
+        if (r0 + TR <= rows) {
+            *reinterpret_cast<uint32_t*>(dst) = four;   // ld_e % 4 == 0 and r0 / 32 % 4 == 0
+        } else {
+            for (int b = 0; r0 + 32 * b < rows; ++b) dst[b] = (uint8_t)((four >> (8 * b)) & 0xFFu);
+        }
+    }
+}
+
+hipError_t launch_mx_quant_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, uint8_t* qt, int64_t ld_t,
+                             uint8_t* et, int64_t ld_e, hipStream_t st) {
+    if (rows == 0 || cols == 0) return hipSuccess;
+    const int64_t gx = (cols + 127) / 128, gy = (rows + 127) / 128;
+    const int64_t total = ((gy + 15) / 16) * ((gx + 15) / 16) * 256;
+    if (total > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    if (fmt == FMT_E4M3FN)
+        mx_quant_t_kernel<FMT_E4M3FN><<<dim3((unsigned)total), dim3(256), 0, st>>>(xp, rows, cols, ld, qt, ld_t, et, ld_e, (int)gy, (int)gx);
+    else
+        mx_quant_t_kernel<FMT_E5M2><<<dim3((unsigned)total), dim3(256), 0, st>>>(xp, rows, cols, ld, qt, ld_t, et, ld_e, (int)gy, (int)gx);
+    return hipGetLastError();
+}
+
 }  // namespace fp8k

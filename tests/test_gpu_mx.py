@@ -142,3 +142,84 @@ def test_mx_full_size_llama_ffn_forward_sampled_rows():
     got = host_bf16_bits(y[torch.from_numpy(rows).cuda()])
     assert orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want.out16)) <= TOL
     assert float((got == want.out16).mean()) > 0.97
+
+
+# ----------------------------------------------------------------- backward
+@pytest.mark.parametrize("fmt", FMTS)
+def test_mx_quantize_t_all_bf16_patterns(fmt):
+    """Blocks down the columns, transposed output == the oracle on the transposed matrix."""
+    allp = si.all_bf16_patterns().reshape(-1)
+    finite = allp[np.isfinite(si.bf16_bits_to_f32(allp))]
+    rng = np.random.default_rng(2)
+    for arr in (finite[:65280], rng.permutation(finite)[:65280]):
+        xt = np.ascontiguousarray(arr.reshape(-1, 960))           # [68, 960]: the transposed matrix, blocks along its rows
+        x = np.ascontiguousarray(xt.T)                            # [960, 68]
+        qt, et = fp8.fp8_mx_quantize_t(dev_bf16(x, 72), fmt)
+        wq, we = orc.mx_quantize(xt, fmt)
+        assert (host_u8(et) == we).all(), np.argwhere(host_u8(et) != we)[:4]
+        assert (host_u8(qt) == wq).all(), np.argwhere(host_u8(qt) != wq)[:4]
+
+
+@pytest.mark.parametrize("rows,cols,ld", [(32, 8, 8), (96, 7, 8), (128, 128, 128), (160, 300, 304), (1024, 1000, 1000),
+                                          (4128, 33, 40), (2080, 2056, 2056)])
+@pytest.mark.parametrize("fmt", FMTS)
+def test_mx_quantize_t_shapes(rows, cols, ld, fmt):
+    x = si.student_t_outlier_bf16((rows, cols), 3.0, 0.01, 100.0, seed=6, stream=rows)
+    x[:32, cols // 2] = 0
+    x[rows - 32:, 0] = 0x8000
+    qt, et = fp8.fp8_mx_quantize_t(dev_bf16(x, ld), fmt)
+    wq, we = orc.mx_quantize(np.ascontiguousarray(x.T), fmt)
+    assert tuple(qt.shape) == (cols, rows) and tuple(et.shape) == (cols, rows // 32)
+    assert (host_u8(et) == we).all() and (host_u8(qt) == wq).all()
+
+
+@pytest.mark.parametrize("M,K,N", [(128, 64, 128), (256, 8, 128), (384, 272, 512), (1024, 384, 640), (128, 1152, 256)])
+def test_mx_linear_backward(M, K, N):
+    wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)
+    x, w, dy = wl.x(), wl.w(), wl.dy()
+    for fmt_dy in FMTS:
+        dx, dw = fp8.fp8_mx_linear_bwd(dev_bf16(dy), dev_bf16(x), dev_bf16(w), fmt_dy=fmt_dy)
+        wx, ww = orc.mx_linear_bwd(dy, x, w, fmt_dy=fmt_dy)
+        for got, want in ((host_bf16_bits(dx), wx), (host_bf16_bits(dw), ww)):
+            assert got.shape == want.out16.shape
+            assert orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want.out16)) <= TOL
+            assert float((got == want.out16).mean()) > 0.95
+
+
+def test_mx_linear_backward_exact_on_integers_and_single_outputs():
+    rng = np.random.default_rng(8)
+    M, K, N = 256, 96, 128
+    dyi, xi, wi = rng.integers(-3, 4, size=(M, N)), rng.integers(-3, 4, size=(M, K)), rng.integers(-3, 4, size=(N, K))
+    dy, x, w = (si.f32_to_bf16_bits(a.astype(np.float32)) for a in (dyi, xi, wi))
+    dx, dw = fp8.fp8_mx_linear_bwd(dev_bf16(dy), dev_bf16(x), dev_bf16(w))
+    assert (si.bf16_bits_to_f32(host_bf16_bits(dx)) == si.bf16_bits_to_f32(orc.f32_to_bf16((dyi @ wi).astype(np.float32)))).all()
+    assert (si.bf16_bits_to_f32(host_bf16_bits(dw)) == si.bf16_bits_to_f32(orc.f32_to_bf16((dyi.T @ xi).astype(np.float32)))).all()
+    only_dx, none = fp8.fp8_mx_linear_bwd(dev_bf16(dy), dev_bf16(x), dev_bf16(w), need_dw=False)
+    assert none is None and torch.equal(only_dx, dx)
+    none, only_dw = fp8.fp8_mx_linear_bwd(dev_bf16(dy), dev_bf16(x), dev_bf16(w), need_dx=False)
+    assert none is None and torch.equal(only_dw, dw)
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_mx_linear_bwd_workspace_bytes(100, 64, 128)          # M not a multiple of 128
+    xb = torch.zeros((48, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_mx_quantize_t(xb, fp8.FP8_E4M3FN)                   # rows not a multiple of 32
+
+
+def test_mx_full_size_llama_ffn_backward_sampled_rows():
+    """Benchmark shape: the four re-quantized operands bit for bit on the whole
+    tensors, both gradients on a stratified sample of output rows."""
+    wl = si.WORKLOADS[si.BENCH_WORKLOAD]
+    x, w, dy = wl.x(), wl.w(), wl.dy()
+    dxd, dwd = dev_bf16(x), dev_bf16(w)
+    dyd = dev_bf16(dy)
+    for name, src, host in (("w", dwd, w), ("x", dxd, x), ("dy", dyd, dy)):
+        qt, et = fp8.fp8_mx_quantize_t(src, fp8.FP8_E4M3FN)
+        oq, oe = orc.mx_quantize(np.ascontiguousarray(host.T), orc.E4M3FN)
+        assert (host_u8(qt) == oq).all() and (host_u8(et) == oe).all(), name
+        del qt, et, oq, oe
+    dx, dw = fp8.fp8_mx_linear_bwd(dyd, dxd, dwd)
+    rx, rw = si.stratified_rows(wl.M, 16), si.stratified_rows(wl.N, 16)
+    wx, ww = orc.mx_linear_bwd(dy, x, w, rows_dx=rx, rows_dw=rw)
+    for got, want in ((host_bf16_bits(dx[torch.from_numpy(rx).cuda()]), wx), (host_bf16_bits(dw[torch.from_numpy(rw).cuda()]), ww)):
+        assert orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want.out16)) <= TOL
+        assert float((got == want.out16).mean()) > 0.97
