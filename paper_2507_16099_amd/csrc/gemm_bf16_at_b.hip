@@ -26,6 +26,8 @@
 #include "fp8_device.hpp"
 #include "launchers.hpp"
 
+#include <cstdlib>
+
 namespace fp8k {
 
 typedef __bf16 v8bf_t __attribute__((ext_vector_type(8)));
@@ -193,6 +195,14 @@ hipError_t launch_gemm_bf16_at_b(const void* a, int64_t lda, const void* b, int6
                                  void* out, int64_t ld_out, hipStream_t st) {
     using namespace bt;
     if (I == 0 || J == 0) return hipSuccess;
+    {
+        // more than 64 tiles: the LDS-DMA kernel (FP8MI355_BF16_VARIANT=0 / 1 forces one of the two)
+        const int64_t tiles = ((I + BI - 1) / BI) * ((J + BJ - 1) / BJ);
+        const char* e = std::getenv("FP8MI355_BF16_VARIANT");
+        const bool want = e ? std::atoi(e) != 0 : tiles > 64;
+        if (want && gemm_bf16_at_b_snake_fits(lda, ldb, I, J, C))
+            return launch_gemm_bf16_at_b_snake(a, lda, b, ldb, I, J, C, out, ld_out, st);
+    }
     static bool attr_done = false;          // idempotent, a race is harmless
     constexpr int lds = 2 * STAGE;
     if (!attr_done) {

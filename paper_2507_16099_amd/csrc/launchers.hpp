@@ -71,6 +71,12 @@ hipError_t launch_gemm_fp8_skinny(const uint8_t* a, int64_t lda, int fmt_a, cons
 hipError_t launch_gemm_bf16_at_b(const void* a, int64_t lda, const void* b, int64_t ldb, int64_t I, int64_t J, int64_t C,
                                  void* out, int64_t ld_out, hipStream_t st);
 
+// the same product on the LDS-DMA "snake" schedule with transposing LDS reads (large problems;
+// _fits tells whether the 32-bit buffer offsets reach)
+bool gemm_bf16_at_b_snake_fits(int64_t lda, int64_t ldb, int64_t I, int64_t J, int64_t C);
+hipError_t launch_gemm_bf16_at_b_snake(const void* a, int64_t lda, const void* b, int64_t ldb, int64_t I, int64_t J,
+                                       int64_t C, void* out, int64_t ld_out, hipStream_t st);
+
 // MX (microscaling) FP8: blocks of 32 along the contiguous axis, one E8M0 byte per block
 // (cols % 32 == 0), and the GEMM whose matrix-core instruction applies the block scales
 // (K % 128 == 0, ld_ea and ld_eb multiples of 4, 4-byte aligned scale pointers)

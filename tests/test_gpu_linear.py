@@ -259,11 +259,25 @@ def test_full_size_decode_step_llama_ffn_weight():
 
 # ------------------------------------------------ rowwise_gw_hp: weight gradient in bfloat16
 
-GW_SHAPES = [(16, 8, 8), (64, 256, 256), (100, 72, 264), (513, 520, 136), (1000, 256, 1024), (4096, 768, 512)]
+GW_SHAPES = [(16, 8, 8), (64, 256, 256), (100, 72, 264), (513, 520, 136), (1000, 256, 1024), (4096, 768, 512),
+             (130, 1032, 2312)]
+
+
+@pytest.fixture(params=["0", "1"], ids=["register_staged", "lds_dma"])
+def bf16_variant(request):
+    """Both bfloat16 kernels on every shape (the dispatch would pick by problem size)."""
+    import os
+    old = os.environ.get("FP8MI355_BF16_VARIANT")
+    os.environ["FP8MI355_BF16_VARIANT"] = request.param
+    yield request.param
+    if old is None:
+        os.environ.pop("FP8MI355_BF16_VARIANT", None)
+    else:
+        os.environ["FP8MI355_BF16_VARIANT"] = old
 
 
 @pytest.mark.parametrize("M,K,N", GW_SHAPES)
-def test_grad_weight_hp_exact_on_small_integers(M, K, N):
+def test_grad_weight_hp_exact_on_small_integers(bf16_variant, M, K, N):
     """Integer-valued inputs: every product and partial sum is exact in fp32,
     so any mistake in the transposing load, the LDS layout or the output
     indexing shows as a wrong integer (ragged tiles and contraction tails
@@ -279,7 +293,7 @@ def test_grad_weight_hp_exact_on_small_integers(M, K, N):
 
 
 @pytest.mark.parametrize("M,K,N", GW_SHAPES)
-def test_grad_weight_hp_random_inputs(M, K, N):
+def test_grad_weight_hp_random_inputs(bf16_variant, M, K, N):
     wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)
     dy, x = wl.dy(), wl.x()
     dw = fp8.fp8_grad_weight_hp(dev_bf16(dy), dev_bf16(x))
