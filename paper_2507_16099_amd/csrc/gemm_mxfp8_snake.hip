@@ -30,6 +30,7 @@ constexpr int NT = 256;
 constexpr int WM = 128, WN = 128;
 constexpr int TILE = (BM + BN) * BK;     // 64 KB of codes
 constexpr int STAGE = TILE + (BM + BN) * 4;   // + one dword of scales per row
+constexpr int SCBUF = (BM + BN) * 16;         // scales of four K steps, 16 bytes per row (SC16 mode)
 constexpr int GROUP_M = 4;
 constexpr int NUM_XCD = 8;
 }  // namespace msn
@@ -61,7 +62,10 @@ __device__ __forceinline__ void msn_lds_dma4(v4i_x rsrc, uint32_t lds_addr, uint
 }
 __device__ __forceinline__ void msn_wait_all_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-template <int FA, int FB, bool OUT_F32>
+// SC16 (K a multiple of 512): the scale bytes are fetched 16 per row at a time (four K steps, two buffers
+// behind the stages) instead of 4 per row and K step.  A scale load touches one cache line per lane
+// whatever its width; one dword per lane and step doubled the kernel's cache-line traffic and cost 20 %.
+template <int FA, int FB, bool OUT_F32, bool SC16>
 __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
     const uint8_t* __restrict__ A, int64_t lda, const uint8_t* __restrict__ EA, int64_t ld_ea,
     const uint8_t* __restrict__ B, int64_t ldb, const uint8_t* __restrict__ EB, int64_t ld_eb, int M, int N,
@@ -100,6 +104,7 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
     const v4i_x rsrc_eb = {(int)(uint32_t)peb, (int)(uint32_t)(peb >> 32), (int)((int64_t)(rows_b - 1) * ld_eb + K / 32), 0x00020000};
     const uint32_t vea0 = (uint32_t)((wave * 64 + lane) * (int)ld_ea), veb0 = (uint32_t)((wave * 64 + lane) * (int)ld_eb);
     const uint32_t lds_sc = (uint32_t)(size_t)smem + (uint32_t)TILE + (uint32_t)wave * 256u;   // + BM * 4 for B
+    const uint32_t lds_sc16 = (uint32_t)(size_t)smem + (uint32_t)(2 * STAGE) + (uint32_t)wave * 1024u;   // + SCBUF per buffer, + BM * 16 for B
 
     // ---- global -> LDS.  Wave w fills row groups w, w+4, ... (8 rows each) of both
     //      tiles; lane l fills (row l/8, chunk slot l%8) with logical chunk slot ^ key(row),
@@ -127,9 +132,16 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             msn_lds_dma16(rsrc_b, lb + i * 4096, ((i & 1) ? vb0_o + ko : vb0_e + ke) + (uint32_t)i * vb_step);
-        const uint32_t ks = k0 < K ? (uint32_t)(k0 >> 5) : OOB;      // byte offset of this step's 4 blocks in a scale row
-        msn_lds_dma4(rsrc_ea, lds_sc + (uint32_t)(stage * STAGE), vea0 + ks);
-        msn_lds_dma4(rsrc_eb, lds_sc + (uint32_t)(stage * STAGE) + BM * 4, veb0 + ks);
+        if constexpr (SC16) {
+            if (k0 == 0) {   // scales of steps 0..3 into scale buffer 0
+                msn_lds_dma16(rsrc_ea, lds_sc16, vea0);
+                msn_lds_dma16(rsrc_eb, lds_sc16 + BM * 16, veb0);
+            }
+        } else {
+            const uint32_t ks = k0 < K ? (uint32_t)(k0 >> 5) : OOB;      // byte offset of this step's 4 blocks in a scale row
+            msn_lds_dma4(rsrc_ea, lds_sc + (uint32_t)(stage * STAGE), vea0 + ks);
+            msn_lds_dma4(rsrc_eb, lds_sc + (uint32_t)(stage * STAGE) + BM * 4, veb0 + ks);
+        }
     };
 
     // ---- LDS -> fragments
@@ -142,8 +154,9 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
         offa[c] = (wm0 + r16) * BK + (((g + 4 * c) ^ key_a) << 4);
         offb[c] = BM * BK + (wn0 + 16 * (r16 >> 2) + (r16 & 3)) * BK + (((g + 4 * c) ^ key_b) << 4);
     }
-    const int offsa = TILE + (wm0 + r16) * 4 + g;                                    // scale byte of block g of this lane's A row
-    const int offsb = TILE + BM * 4 + (wn0 + 16 * (r16 >> 2) + (r16 & 3)) * 4 + g;   // ... B row
+    constexpr int RS = SC16 ? 16 : 4;       // bytes per row in the scale area
+    const int offsa = (SC16 ? 0 : TILE) + (wm0 + r16) * RS + g;                                     // scale byte of block g of this lane's A row
+    const int offsb = (SC16 ? 0 : TILE) + BM * RS + (wn0 + 16 * (r16 >> 2) + (r16 & 3)) * RS + g;   // ... B row
     v8i_x af[2][4], bf[2][4];   // [half][fragment in half]
     int sa[2], sb[2];           // their scale bytes: byte f of sa[half] belongs to fragment f (selected by op_sel)
     auto read_a = [&](const uint8_t* s, int half, int f) {
@@ -153,14 +166,19 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
         af[half][f] = v8i_x{(int)x0.x, (int)x0.y, (int)x0.z, (int)x0.w, (int)x1.x, (int)x1.y, (int)x1.z, (int)x1.w};
     };
     // the four scale bytes of a fragment half, packed into one register
-    auto scales_a = [&](const uint8_t* s, int half) {
-        const int o = offsa + half * 256;
-        return (int)((uint32_t)s[o] | ((uint32_t)s[o + 64] << 8) | ((uint32_t)s[o + 128] << 16) | ((uint32_t)s[o + 192] << 24));
+    // (read and packing are separate steps so that the main loop can put MFMAs between them:
+    // packed right after the reads, every packing waited out the LDS latency)
+    auto scales_a_read = [&](const uint8_t* s, int half, uint32_t (&raw)[4]) {
+        const int o = offsa + half * (64 * RS);
+        raw[0] = s[o]; raw[1] = s[o + 16 * RS]; raw[2] = s[o + 32 * RS]; raw[3] = s[o + 48 * RS];
     };
-    auto scales_b = [&](const uint8_t* s, int half) {
-        const int o = offsb + half * 256;
-        return (int)((uint32_t)s[o] | ((uint32_t)s[o + 16] << 8) | ((uint32_t)s[o + 32] << 16) | ((uint32_t)s[o + 48] << 24));
+    auto scales_b_read = [&](const uint8_t* s, int half, uint32_t (&raw)[4]) {
+        const int o = offsb + half * (64 * RS);
+        raw[0] = s[o]; raw[1] = s[o + 4 * RS]; raw[2] = s[o + 8 * RS]; raw[3] = s[o + 12 * RS];
     };
+    auto scales_pack = [&](const uint32_t (&raw)[4]) { return (int)(raw[0] | (raw[1] << 8) | (raw[2] << 16) | (raw[3] << 24)); };
+    auto scales_a = [&](const uint8_t* s, int half) { uint32_t raw[4]; scales_a_read(s, half, raw); return scales_pack(raw); };
+    auto scales_b = [&](const uint8_t* s, int half) { uint32_t raw[4]; scales_b_read(s, half, raw); return scales_pack(raw); };
     auto read_b = [&](const uint8_t* s, int half, int f) {
         const int row_off = (half * 64 + f * 4) * BK;   // group `half`, fragment t = f
         const uint4 x0 = *reinterpret_cast<const uint4*>(s + offb[0] + row_off);
@@ -220,9 +238,10 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
     // reads of one fragment half (RD_A: 1 = A half RH, 0 = B half RH, -1 = none)
     // from stage `rs`, and eight LDS-DMA loads (DMA: 0 = A part, 1 = B part, -1 = none).
     auto phase = [&](auto ah_t, auto bh_t, auto rda_t, auto rh_t, auto dma_t, const uint8_t* rs, uint32_t la, uint32_t lb,
-                     uint32_t ka, uint32_t ke, uint32_t ko, uint32_t lsc, uint32_t ks) {
+                     uint32_t ka, uint32_t ke, uint32_t ko, uint32_t lsc, uint32_t ks, const uint8_t* rsc, bool sc_issue) {
         constexpr int AH = decltype(ah_t)::value, BH = decltype(bh_t)::value, RDA = decltype(rda_t)::value,
                       RH = decltype(rh_t)::value, DMA = decltype(dma_t)::value;
+        uint32_t raw[4] = {0, 0, 0, 0};
 #pragma unroll
         for (int t = 0; t < 16; ++t) {
             const int i = t >> 2, j = t & 3;
@@ -235,11 +254,17 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
                     msn_lds_dma16(rsrc_b, lb + (t / 2) * 4096, (((t / 2) & 1) ? vb0_o + ko : vb0_e + ke) + (uint32_t)(t / 2) * vb_step);
             }
             // scales of the half that was read in slots 0..6, packed (the half is not in use in this phase)
-            if constexpr (RDA == 1) { if (t == 10) sa[RH] = scales_a(rs, RH); }
-            if constexpr (RDA == 0) { if (t == 10) sb[RH] = scales_b(rs, RH); }
+            if constexpr (RDA == 1) { if (t == 9) scales_a_read(rsc, RH, raw); if (t == 14) sa[RH] = scales_pack(raw); }
+            if constexpr (RDA == 0) { if (t == 9) scales_b_read(rsc, RH, raw); if (t == 14) sb[RH] = scales_pack(raw); }
             // the refill of the scales rides in a slot that has neither a read nor a data load
-            if constexpr (DMA == 0) { if (t == 8) msn_lds_dma4(rsrc_ea, lsc, vea0 + ks); }
-            if constexpr (DMA == 1) { if (t == 8) msn_lds_dma4(rsrc_eb, lsc + BM * 4, veb0 + ks); }
+            if constexpr (SC16) {
+                // (lsc, ks: scale buffer and byte offset of the next group of four steps)
+                if constexpr (DMA == 0) { if (t == 8 && sc_issue) msn_lds_dma16(rsrc_ea, lsc, vea0 + ks); }
+                if constexpr (DMA == 1) { if (t == 8 && sc_issue) msn_lds_dma16(rsrc_eb, lsc + BM * 16, veb0 + ks); }
+            } else {
+                if constexpr (DMA == 0) { if (t == 8) msn_lds_dma4(rsrc_ea, lsc, vea0 + ks); }
+                if constexpr (DMA == 1) { if (t == 8) msn_lds_dma4(rsrc_eb, lsc + BM * 4, veb0 + ks); }
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -258,8 +283,8 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
         issue_loads(1, BK);                    // (out of range if there is no step 1)
 #pragma unroll
         for (int f = 0; f < 4; ++f) { read_a(smem, 0, f); read_b(smem, 0, f); }
-        sa[0] = scales_a(smem, 0);
-        sb[0] = scales_b(smem, 0);
+        sa[0] = scales_a(SC16 ? smem + 2 * STAGE : smem, 0);
+        sb[0] = scales_b(SC16 ? smem + 2 * STAGE : smem, 0);
         sa[1] = sb[1] = 0;
         __builtin_amdgcn_sched_barrier(0);
 
@@ -274,26 +299,32 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
                 const uint32_t ke = (k2 + cb_e * 16 < K) ? (uint32_t)k2 : OOB;
                 const uint32_t ko = (k2 + cb_o * 16 < K) ? (uint32_t)k2 : OOB;
                 const uint32_t la = lds_base + (uint32_t)(par * STAGE), lb = la + BM * BK;
-                const uint32_t lsc = lds_sc + (uint32_t)(par * STAGE);
-                const uint32_t ks = k2 < K ? (uint32_t)(k2 >> 5) : OOB;
+                // SC16: the scales of step kk sit in buffer (kk / 4) % 2 at byte 4 * (kk % 4) of their row; the group
+                // of steps 4q+4.. is fetched during step 4q+1 into the buffer that steps 4q-4.. have left
+                const int q1 = (k >> 2) + 1;
+                const bool sc_issue = SC16 && (k & 3) == 1 && q1 * 512 < K;
+                const uint32_t lsc = SC16 ? lds_sc16 + (uint32_t)((q1 & 1) * SCBUF) : lds_sc + (uint32_t)(par * STAGE);
+                const uint32_t ks = SC16 ? (uint32_t)(q1 * 16) : (k2 < K ? (uint32_t)(k2 >> 5) : OOB);
+                const uint8_t* c_cur = SC16 ? smem + 2 * STAGE + ((k >> 2) & 1) * SCBUF + (k & 3) * 4 : s_cur;
+                const uint8_t* c_nxt = SC16 ? smem + 2 * STAGE + (((k + 1) >> 2) & 1) * SCBUF + ((k + 1) & 3) * 4 : s_nxt;
                 if (par == 0) {
                     // even step: B order 0,1,1,0.  Holds A0, B0 of this step.
-                    phase(I0{}, I0{}, I0{}, I1{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks);   // (A0,B0) | read B1 of this step
-                    phase(I0{}, I1{}, I1{}, I1{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks);   // (A0,B1) | read A1 of this step
+                    phase(I0{}, I0{}, I0{}, I1{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks, c_cur, sc_issue);   // (A0,B0) | read B1 of this step
+                    phase(I0{}, I1{}, I1{}, I1{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks, c_cur, sc_issue);   // (A0,B1) | read A1 of this step
                     msn_wait_all_vmem();                // my part of step k+1 has landed
                     __syncthreads();                   // ... and everyone's; this step's buffer is read out
                     __builtin_amdgcn_sched_barrier(0);
-                    phase(I1{}, I1{}, I1{}, I0{}, I0{}, s_nxt, la, lb, ka, ke, ko, lsc, ks);   // (A1,B1) | read A0 of step k+1, refill A
-                    phase(I1{}, I0{}, I0{}, I1{}, I1{}, s_nxt, la, lb, ka, ke, ko, lsc, ks);   // (A1,B0) | read B1 of step k+1, refill B
+                    phase(I1{}, I1{}, I1{}, I0{}, I0{}, s_nxt, la, lb, ka, ke, ko, lsc, ks, c_nxt, sc_issue);   // (A1,B1) | read A0 of step k+1, refill A
+                    phase(I1{}, I0{}, I0{}, I1{}, I1{}, s_nxt, la, lb, ka, ke, ko, lsc, ks, c_nxt, sc_issue);   // (A1,B0) | read B1 of step k+1, refill B
                 } else {
                     // odd step: B order 1,0,0,1.  Holds A0, B1 of this step.
-                    phase(I0{}, I1{}, I0{}, I0{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks);   // (A0,B1) | read B0 of this step
-                    phase(I0{}, I0{}, I1{}, I1{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks);   // (A0,B0) | read A1 of this step
+                    phase(I0{}, I1{}, I0{}, I0{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks, c_cur, sc_issue);   // (A0,B1) | read B0 of this step
+                    phase(I0{}, I0{}, I1{}, I1{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks, c_cur, sc_issue);   // (A0,B0) | read A1 of this step
                     msn_wait_all_vmem();
                     __syncthreads();
                     __builtin_amdgcn_sched_barrier(0);
-                    phase(I1{}, I0{}, I1{}, I0{}, I0{}, s_nxt, la, lb, ka, ke, ko, lsc, ks);   // (A1,B0) | read A0 of step k+1, refill A
-                    phase(I1{}, I1{}, I0{}, I0{}, I1{}, s_nxt, la, lb, ka, ke, ko, lsc, ks);   // (A1,B1) | read B0 of step k+1, refill B
+                    phase(I1{}, I0{}, I1{}, I0{}, I0{}, s_nxt, la, lb, ka, ke, ko, lsc, ks, c_nxt, sc_issue);   // (A1,B0) | read A0 of step k+1, refill A
+                    phase(I1{}, I1{}, I0{}, I0{}, I1{}, s_nxt, la, lb, ka, ke, ko, lsc, ks, c_nxt, sc_issue);   // (A1,B1) | read B0 of step k+1, refill B
                 }
             }
         }
@@ -382,13 +413,13 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
     }
 }
 
-template <int FA, int FB, bool OUT_F32>
+template <int FA, int FB, bool OUT_F32, bool SC16>
 static hipError_t launch_msn(const uint8_t* a, int64_t lda, const uint8_t* ea, int64_t ld_ea, const uint8_t* b, int64_t ldb,
                              const uint8_t* eb, int64_t ld_eb, int M, int N, int K, void* out, int64_t ld_out,
                              hipStream_t st) {
     using namespace msn;
-    auto kern = gemm_mxfp8_snake_kernel<FA, FB, OUT_F32>;
-    constexpr int lds = 2 * STAGE;
+    auto kern = gemm_mxfp8_snake_kernel<FA, FB, OUT_F32, SC16>;
+    constexpr int lds = 2 * STAGE + (SC16 ? 2 * SCBUF : 0);
     static bool attr_done = false;          // idempotent, a race is harmless
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -412,10 +443,13 @@ hipError_t launch_gemm_mxfp8_snake(const uint8_t* a, int64_t lda, int fmt_a, con
                                    int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32, hipStream_t st) {
     if (M == 0 || N == 0) return hipSuccess;
     const int m = (int)M, n = (int)N, k = (int)K;
+    const bool sc16 = K > 0 && K % 512 == 0;   // whole 16-byte scale chunks per row
 #define FP8K_MSN(FA_, FB_)                                                                                  \
     if (fmt_a == FA_ && fmt_b == FB_)                                                                       \
-        return out_f32 ? launch_msn<FA_, FB_, true>(a, lda, ea, ld_ea, b, ldb, eb, ld_eb, m, n, k, out, ld_out, st) \
-                       : launch_msn<FA_, FB_, false>(a, lda, ea, ld_ea, b, ldb, eb, ld_eb, m, n, k, out, ld_out, st)
+        return sc16 ? (out_f32 ? launch_msn<FA_, FB_, true, true>(a, lda, ea, ld_ea, b, ldb, eb, ld_eb, m, n, k, out, ld_out, st)   \
+                               : launch_msn<FA_, FB_, false, true>(a, lda, ea, ld_ea, b, ldb, eb, ld_eb, m, n, k, out, ld_out, st)) \
+                    : (out_f32 ? launch_msn<FA_, FB_, true, false>(a, lda, ea, ld_ea, b, ldb, eb, ld_eb, m, n, k, out, ld_out, st)  \
+                               : launch_msn<FA_, FB_, false, false>(a, lda, ea, ld_ea, b, ldb, eb, ld_eb, m, n, k, out, ld_out, st))
     FP8K_MSN(FMT_E4M3FN, FMT_E4M3FN);
     FP8K_MSN(FMT_E5M2, FMT_E4M3FN);
     FP8K_MSN(FMT_E4M3FN, FMT_E5M2);
