@@ -76,6 +76,39 @@ def test_argument_errors_are_reported_without_a_gpu():
     assert L.fp8_linear_fwd(p16, p16, 64, 120, 32, C.byref(r), p16, p16, 1 << 20, None) == -2
 
 
+def test_argument_errors_of_the_later_entry_points():
+    """The entry points added for the weight-gradient-in-bf16 recipe, inference
+    with pre-quantized weights and MX block scaling reject bad arguments on the
+    host, before any launch."""
+    L = fp8.load_library()
+    buf = (C.c_char * 8192)()
+    p = (C.addressof(buf) + 255) // 256 * 256
+    # fp8_quantize_row_col: format, leading dimensions
+    assert L.fp8_quantize_row_col(p, 64, 64, 64, 5, 0, p, 64, p, p, 64, p, None) == -3
+    assert L.fp8_quantize_row_col(p, 64, 64, 32, 0, 0, p, 64, p, p, 64, p, None) == -2
+    # fp8_grad_weight_hp: NULL output, ragged dims
+    assert L.fp8_grad_weight_hp(p, p, 64, 64, 64, None, None) == -1
+    assert L.fp8_grad_weight_hp(p, p, 64, 60, 64, p, None) == -2
+    # prequantized forward: granularity of the weight scales, workspace too small
+    assert L.fp8_linear_fwd_prequantized(p, 16, 64, 0, 1, 0, p, 64, 0, p, 2, 32, p, 32, p, 1 << 20, None) == -3
+    assert L.fp8_linear_fwd_prequantized(p, 16, 64, 0, 1, 0, p, 64, 0, p, 1, 32, p, 32, p, 16, None) == -5
+    assert L.fp8_linear_prequantized_workspace_bytes(16, 64) >= 16 * 64 + 16 * 4
+    # MX: block size, scale leading dimension, contraction length of the GEMM
+    assert L.fp8_mx_quantize(p, 4, 48, 48, 0, p, 48, p, 4, None) == -2
+    assert L.fp8_mx_quantize(p, 4, 64, 64, 0, p, 64, p, 2, None) == -2           # ld_e % 4
+    assert L.fp8_mx_quantize_t(p, 48, 64, 64, 0, p, 48, p, 4, None) == -2         # rows % 32
+    assert L.fp8_mx_quantize_t(p, 64, 64, 64, 7, p, 64, p, 4, None) == -3
+    assert L.fp8_mx_scaled_mm(p, 64, 0, p, 4, p, 64, 0, p, 4, 16, 16, 64, p, 16, 0, None) == -2   # K % 128
+    assert L.fp8_mx_scaled_mm(p, 128, 0, p, 4, p, 128, 0, p, 4, 16, 16, 128, p, 16, 8, None) == -3  # unknown flag
+    assert L.fp8_mx_linear_workspace_bytes(16, 96, 16) == 0
+    assert L.fp8_mx_linear_bwd_workspace_bytes(100, 64, 128) == 0                # M % 128
+    assert L.fp8_mx_linear_bwd_workspace_bytes(128, 64, 256) >= 2 * 128 * 256 + 64 * 256 + 64 * 128
+    assert L.fp8_mx_linear_bwd(p, p, p, 128, 64, 128, 0, 0, 9, p, p, p, 1 << 20, None) == -3
+    assert L.fp8_mx_linear_bwd(p, p, p, 128, 64, 128, 0, 0, 0, p, p, p, 16, None) == -5
+    assert L.fp8_mx_linear_bwd(p, p, p, 128, 64, 128, 0, 0, 0, None, None, p, 16, None) == 0   # nothing asked for
+    assert "workspace" in fp8.fp8_last_error() or fp8.fp8_last_error() == ""
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     import paper_2507_16099_amd.fp8 as mod
     monkeypatch.setattr(mod, "_lib", None)
