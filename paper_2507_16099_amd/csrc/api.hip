@@ -147,8 +147,11 @@ int check_recipe(const char* fn, const fp8_recipe* r) {
         return fail(FP8_ERR_ENUM, "%s: recipe.gran=%d must be FP8_TENSOR or FP8_ROW", fn, r->gran);
     if (!fmt_ok(r->fmt_x) || !fmt_ok(r->fmt_w) || !fmt_ok(r->fmt_dy))
         return fail(FP8_ERR_ENUM, "%s: unknown fp8 format in recipe", fn);
-    if (r->flags & ~(FP8_POW2_SCALE | FP8_GRAD_WEIGHT_HP))
+    if (r->flags & ~(FP8_POW2_SCALE | FP8_GRAD_WEIGHT_HP | FP8_SAVE_FOR_BWD))
         return fail(FP8_ERR_ENUM, "%s: recipe.flags=%d has unknown bits", fn, r->flags);
+    if ((r->flags & FP8_SAVE_FOR_BWD) && r->gran != FP8_TENSOR)
+        return fail(FP8_ERR_ENUM, "%s: FP8_SAVE_FOR_BWD applies to the tensorwise recipe only (rowwise operands are "
+                                  "re-quantized along another axis in the backward)", fn);
     return FP8_OK;
 }
 
@@ -281,7 +284,12 @@ size_t fp8_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, const fp8_rec
     g_err[0] = 0;
     if (check_recipe("fp8_linear_workspace_bytes", recipe)) return 0;
     if (check_linear_dims("fp8_linear_workspace_bytes", M, K, N, bwd != 0)) return 0;
-    const size_t t = bwd ? plan_bwd(M, K, N, recipe->gran).total : plan_fwd(M, K, N, recipe->gran).total;
+    size_t t = bwd ? plan_bwd(M, K, N, recipe->gran).total : plan_fwd(M, K, N, recipe->gran).total;
+    // shared workspace: the backward's layout (it holds the saved copies), then the forward's own buffers
+    if (recipe->flags & FP8_SAVE_FOR_BWD) {
+        if (check_linear_dims("fp8_linear_workspace_bytes", M, K, N, true)) return 0;
+        t = plan_bwd(M, K, N, recipe->gran).total + plan_fwd(M, K, N, recipe->gran).total;
+    }
     return t ? t : 256;
 }
 
@@ -296,9 +304,26 @@ int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N
     if (!y || !workspace) return fail(FP8_ERR_NULL, "fp8_linear_fwd: y or workspace is NULL");
     if (!aligned(y, 16) || !aligned(workspace, 256)) return fail(FP8_ERR_ALIGN, "fp8_linear_fwd: y (16) / workspace (256) misaligned");
     const FwdPlan p = plan_fwd(M, K, N, recipe->gran);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (recipe->flags & FP8_SAVE_FOR_BWD) {
+        // tensorwise with saved copies: X and W are converted once into both layouts; the transposed
+        // codes and the scales go where the backward's plan expects them
+        if (int rc = check_linear_dims("fp8_linear_fwd", M, K, N, true)) return rc;
+        const BwdPlan b = plan_bwd(M, K, N, recipe->gran);
+        if (workspace_bytes < b.total + p.total)
+            return fail(FP8_ERR_WORKSPACE, "fp8_linear_fwd: workspace %zu < %zu bytes", workspace_bytes, b.total + p.total);
+        if ((K + 127) / 128 > 65535) return fail(FP8_ERR_SHAPE, "fp8_linear_fwd: K too large");
+        uint8_t* wsb = static_cast<uint8_t*>(workspace);
+        uint8_t* wsf = wsb + b.total;
+        const int fl = recipe->flags & FP8_POW2_SCALE;
+        float *sxt = reinterpret_cast<float*>(wsb + b.sxt), *swt = reinterpret_cast<float*>(wsb + b.swt);
+        if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | FP8_TRANSPOSE_OUT, wsb + b.xt, M, wsf + p.xq, K, sxt, st)) return rc;
+        if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | FP8_TRANSPOSE_OUT, wsb + b.wt, N, wsf + p.wq, K, swt, st)) return rc;
+        FP8_TRY(fp8k::launch_gemm_fp8(wsf + p.xq, K, recipe->fmt_x, sxt, 0, wsf + p.wq, K, recipe->fmt_w, swt, 0, M, N, K, y, N, 0, st));
+        return FP8_OK;
+    }
     if (workspace_bytes < p.total)
         return fail(FP8_ERR_WORKSPACE, "fp8_linear_fwd: workspace %zu < %zu bytes", workspace_bytes, p.total);
-    hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* ws = static_cast<uint8_t*>(workspace);
     uint8_t *xq = ws + p.xq, *wq = ws + p.wq;
     float *sx = reinterpret_cast<float*>(ws + p.sx), *sw = reinterpret_cast<float*>(ws + p.sw);
@@ -317,16 +342,18 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
     if (int rc = check_recipe("fp8_linear_bwd", recipe)) return rc;
     if (int rc = check_linear_dims("fp8_linear_bwd", M, K, N, true)) return rc;
     if (int rc = check_bf16("fp8_linear_bwd(dy)", dy, M, N, N)) return rc;
-    if (dw) if (int rc = check_bf16("fp8_linear_bwd(x)", x, M, K, K)) return rc;
-    if (dx) if (int rc = check_bf16("fp8_linear_bwd(w)", w, N, K, K)) return rc;
+    const bool saved = (recipe->flags & FP8_SAVE_FOR_BWD) != 0;   // codes of X and W left by the forward
+    if (dw && !saved) if (int rc = check_bf16("fp8_linear_bwd(x)", x, M, K, K)) return rc;
+    if (dx && !saved) if (int rc = check_bf16("fp8_linear_bwd(w)", w, N, K, K)) return rc;
     if (M == 0 || N == 0 || K == 0 || (!dx && !dw)) return FP8_OK;
     if (!workspace) return fail(FP8_ERR_NULL, "fp8_linear_bwd: workspace is NULL");
     if (!aligned(dx, 16) || !aligned(dw, 16) || !aligned(workspace, 256))
         return fail(FP8_ERR_ALIGN, "fp8_linear_bwd: dx, dw (16) / workspace (256) misaligned");
     if ((K + 127) / 128 > 65535 || (N + 127) / 128 > 65535) return fail(FP8_ERR_SHAPE, "fp8_linear_bwd: K or N too large");
     const BwdPlan p = plan_bwd(M, K, N, recipe->gran);
-    if (workspace_bytes < p.total)
-        return fail(FP8_ERR_WORKSPACE, "fp8_linear_bwd: workspace %zu < %zu bytes", workspace_bytes, p.total);
+    if (workspace_bytes < p.total + (saved ? plan_fwd(M, K, N, recipe->gran).total : 0))
+        return fail(FP8_ERR_WORKSPACE, "fp8_linear_bwd: workspace %zu < %zu bytes", workspace_bytes,
+                    p.total + (saved ? plan_fwd(M, K, N, recipe->gran).total : 0));
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* ws = static_cast<uint8_t*>(workspace);
     uint8_t *gq = ws + p.gq, *gqt = ws + p.gqt, *wt = ws + p.wt, *xt = ws + p.xt;
@@ -352,11 +379,13 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
             if (int rc = quantize_impl(dy, M, N, N, FP8_TENSOR, recipe->fmt_dy, fl, gq, N, nullptr, 0, sg, st)) return rc;
         }
         if (dx) {
-            if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st)) return rc;
+            if (!saved)
+                if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st)) return rc;
             FP8_TRY(fp8k::launch_gemm_fp8(gq, N, recipe->fmt_dy, sg, 0, wt, N, recipe->fmt_w, swt, 0, M, K, N, dx, K, 0, st));
         }
         if (dw) {
-            if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st)) return rc;
+            if (!saved)
+                if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st)) return rc;
             FP8_TRY(fp8k::launch_gemm_fp8(gqt, M, recipe->fmt_dy, sg, 0, xt, M, recipe->fmt_x, sxt, 0, N, K, M, dw, K, 0, st));
         }
         return FP8_OK;

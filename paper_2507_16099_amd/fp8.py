@@ -16,7 +16,7 @@ import torch
 
 FP8_E4M3FN, FP8_E5M2 = 0, 1
 FP8_TENSOR, FP8_ROW, FP8_COL = 0, 1, 2
-FP8_POW2_SCALE, FP8_TRANSPOSE_OUT, FP8_OUT_FP32, FP8_GRAD_WEIGHT_HP = 1, 2, 4, 8
+FP8_POW2_SCALE, FP8_TRANSPOSE_OUT, FP8_OUT_FP32, FP8_GRAD_WEIGHT_HP, FP8_SAVE_FOR_BWD = 1, 2, 4, 8, 16
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfp8mi355.so")
@@ -239,6 +239,7 @@ def fp8_linear_fwd(x: torch.Tensor, w: torch.Tensor, recipe: Recipe, y: torch.Te
     M, K, ldx = _mat(x, 2)
     N, Kw, ldw = _mat(w, 2)
     assert K == Kw and ldx == K and ldw == K, "x and w must be dense [M,K] / [N,K]"
+    assert workspace is not None or not (recipe.flags & FP8_SAVE_FOR_BWD), "pass the workspace the backward will reuse"
     if workspace is None:
         workspace = torch.empty(fp8_linear_workspace_bytes(M, K, N, recipe, False), dtype=torch.uint8, device=x.device)
     if y is None:
@@ -252,15 +253,25 @@ def fp8_linear_fwd(x: torch.Tensor, w: torch.Tensor, recipe: Recipe, y: torch.Te
 def fp8_linear_bwd(dy: torch.Tensor, x: torch.Tensor, w: torch.Tensor, recipe: Recipe,
                    dx: torch.Tensor | None = None, dw: torch.Tensor | None = None,
                    workspace: torch.Tensor | None = None, need_dx: bool = True, need_dw: bool = True):
+    """x, w: the layer's inputs, or (with FP8_SAVE_FOR_BWD, where the forward left their fp8 copies in
+    the workspace) just their shapes as tuples (M, K) and (N, K)."""
     M, N, _ = _mat(dy, 2)
-    K = x.shape[1]
-    assert x.shape == (M, K) and w.shape == (N, K) and dy.is_contiguous() and x.is_contiguous() and w.is_contiguous()
+    K = x.shape[1] if isinstance(x, torch.Tensor) else x[1]
+    if recipe.flags & FP8_SAVE_FOR_BWD:
+        assert workspace is not None, "the backward reuses the forward's workspace"
+        assert tuple(x.shape if isinstance(x, torch.Tensor) else x) == (M, K)
+        assert tuple(w.shape if isinstance(w, torch.Tensor) else w) == (N, K)
+        x = x if isinstance(x, torch.Tensor) else None
+        w = w if isinstance(w, torch.Tensor) else None
+    else:
+        assert x.shape == (M, K) and w.shape == (N, K) and x.is_contiguous() and w.is_contiguous()
+    assert dy.is_contiguous()
     if workspace is None:
-        workspace = torch.empty(fp8_linear_workspace_bytes(M, K, N, recipe, True), dtype=torch.uint8, device=x.device)
+        workspace = torch.empty(fp8_linear_workspace_bytes(M, K, N, recipe, True), dtype=torch.uint8, device=dy.device)
     if dx is None and need_dx:
-        dx = torch.empty((M, K), dtype=torch.bfloat16, device=x.device)
+        dx = torch.empty((M, K), dtype=torch.bfloat16, device=dy.device)
     if dw is None and need_dw:
-        dw = torch.empty((N, K), dtype=torch.bfloat16, device=x.device)
+        dw = torch.empty((N, K), dtype=torch.bfloat16, device=dy.device)
     r = recipe.c()
     _check(load_library().fp8_linear_bwd(_ptr(dy), _ptr(x), _ptr(w), M, K, N, C.byref(r), _ptr(dx), _ptr(dw),
                                          _ptr(workspace), workspace.numel(), _stream()))

@@ -191,6 +191,41 @@ def test_full_size_outlier_stress_rowwise_vs_tensorwise():
     assert r.n_sat <= 4096 and t.n_sat <= 1     # only amax elements can be clamped under dynamic scaling
 
 
+# ------------------------------------------------ tensorwise: fp8 copies saved by the forward
+
+@pytest.mark.parametrize("M,K,N", [(64, 64, 64), (208, 176, 272), (512, 1024, 768), (1024, 384, 640)])
+@pytest.mark.parametrize("pow2", [False, True])
+def test_tensorwise_backward_reuses_the_forward_copies(M, K, N, pow2):
+    """FP8_SAVE_FOR_BWD: X and W are converted once (both layouts from one read),
+    the backward quantizes dY only.  Same codes and scales as the stateless
+    calls, so the outputs are identical bit for bit, and they match the oracle."""
+    wl = si.scaled_down(si.WORKLOADS["c3_llama3_8b_qkv_tensorwise"], M, K, N)
+    x, w, dy = wl.x(), wl.w(), wl.dy()
+    xd, wd, dyd = dev_bf16(x), dev_bf16(w), dev_bf16(dy)
+    fl = fp8.FP8_POW2_SCALE if pow2 else 0
+    plain = fp8.Recipe(gran=fp8.FP8_TENSOR, flags=fl)
+    saved = fp8.Recipe(gran=fp8.FP8_TENSOR, flags=fl | fp8.FP8_SAVE_FOR_BWD)
+    y0 = fp8.fp8_linear_fwd(xd, wd, plain)
+    dx0, dw0 = fp8.fp8_linear_bwd(dyd, xd, wd, plain)
+    ws = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, saved, True), dtype=torch.uint8, device="cuda")
+    y1 = fp8.fp8_linear_fwd(xd, wd, saved, workspace=ws)
+    dx1, dw1 = fp8.fp8_linear_bwd(dyd, (M, K), (N, K), saved, workspace=ws)     # x and w are not read again
+    for a, b in ((y0, y1), (dx0, dx1), (dw0, dw1)):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    o = orc.Recipe(gran=orc.TENSOR, pow2=pow2)
+    _cmp(y1, orc.linear_fwd(x, w, o)[0])
+    _cmp(dx1, orc.linear_bwd_dx(dy, w, o)[0])
+    _cmp(dw1, orc.linear_bwd_dw(dy, x, o)[0])
+    # one output only
+    only_dx, none = fp8.fp8_linear_bwd(dyd, (M, K), (N, K), saved, workspace=ws, need_dw=False)
+    assert none is None and torch.equal(only_dx.view(torch.int16), dx0.view(torch.int16))
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_linear_workspace_bytes(M, K, N, fp8.Recipe(gran=fp8.FP8_ROW, flags=fp8.FP8_SAVE_FOR_BWD), True)
+    with pytest.raises(fp8.Fp8Error):                                             # the stateless size is too small
+        small = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, plain, False), dtype=torch.uint8, device="cuda")
+        fp8.fp8_linear_fwd(xd, wd, saved, workspace=small)
+
+
 # ------------------------------------------------ inference: weight quantized once
 
 @pytest.mark.parametrize("M", [1, 7, 16, 32, 33, 300])
