@@ -102,6 +102,34 @@ def _sweep(torch, fp8, dev, iters: int) -> dict:
             "iters": iters, "rows": rows}
 
 
+def _data_probe(torch, fp8, dev, iters: int) -> dict:
+    """How much of the forward GEMM's rate depends on the operand DATA: the same
+    kernel and launch on the benchmark shape with operands that do not toggle
+    (all codes equal) and with realistic ones.  The difference is the board's
+    power limit at work (the clock drops under toggling data), not the schedule."""
+    import synthetic_inputs as si
+    wl = si.WORKLOADS[si.BENCH_WORKLOAD]
+    M, K, N = wl.M, wl.K, wl.N
+    sa = torch.rand(M, device=dev) + 0.5
+    sb = torch.rand(N, device=dev) + 0.5
+    out = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    x = torch.randn((M, K), device=dev).to(torch.bfloat16)
+    w = (torch.randn((N, K), device=dev) * 0.02).to(torch.bfloat16)
+    cases = {
+        "all_zero_codes": (torch.zeros((M, K), dtype=torch.uint8, device=dev), torch.zeros((N, K), dtype=torch.uint8, device=dev)),
+        "constant_codes_1.0": (torch.full((M, K), 0x38, dtype=torch.uint8, device=dev), torch.full((N, K), 0x38, dtype=torch.uint8, device=dev)),
+        "uniform_random_codes": (torch.randint(0, 0x70, (M, K), dtype=torch.uint8, device=dev), torch.randint(0, 0x70, (N, K), dtype=torch.uint8, device=dev)),
+        "rowwise_quantized_gaussian": (fp8.fp8_quantize(x, fp8.FP8_ROW, fp8.FP8_E4M3FN)[0], fp8.fp8_quantize(w, fp8.FP8_ROW, fp8.FP8_E4M3FN)[0]),
+    }
+    rows = {}
+    for name, (a, b) in cases.items():
+        best = min(_event_time_ms(lambda: fp8.fp8_scaled_mm(a, 0, sa, fp8.FP8_ROW, b, 0, sb, fp8.FP8_ROW, 0, out=out), iters, 3, torch)
+                   for _ in range(3))
+        rows[name] = {"ms": round(best, 4), "TFLOP/s": round(2.0 * M * N * K / (best * 1e-3) / 1e12, 1),
+                      "frac_of_fp8_peak": round(2.0 * M * N * K / (best * 1e-3) / 1e12 / FP8_PEAK_TFLOPS, 4)}
+    return {"data_probe": f"forward GEMM M={M} K={K} N={N}, same kernel, operands of different bit activity", "rows": rows}
+
+
 def _decode(torch, fp8, dev, iters: int) -> dict:
     """Inference with weights quantized once (Section 3: dynamic activation +
     weight FP8 quantization, per row), few tokens per step: the GEMM streams the
@@ -165,6 +193,8 @@ def main() -> int:
     ap.add_argument("--decode", action="store_true",
                     help="inference with pre-quantized weights at decode batch sizes (weight-streaming GEMM); "
                          "prints a JSON table and exits")
+    ap.add_argument("--data-probe", action="store_true",
+                    help="time the forward GEMM with operands that do not toggle and with realistic ones, then exit")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="launch a 1 GiB device copy and every kernel of the step twice, then exit "
                          "(run under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`)")
@@ -194,6 +224,10 @@ def main() -> int:
 
     if args.decode:
         print(json.dumps(_decode(torch, fp8, dev, max(10, args.steps))))
+        return 0
+
+    if args.data_probe:
+        print(json.dumps(_data_probe(torch, fp8, dev, max(10, args.steps))))
         return 0
 
     wl = si.WORKLOADS[args.workload or si.BENCH_WORKLOAD]
