@@ -787,48 +787,60 @@ template <int FMT, bool DENSE>
 __global__ __launch_bounds__(256) void mx_quant_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
                                                         int64_t ld, uint8_t* __restrict__ q, int64_t ld_q,
                                                         uint8_t* __restrict__ e8m0, int64_t ld_e) {
-    const int64_t vpr = cols >> 3;                      // 128-bit vectors per row (cols % 32 == 0)
-    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const bool live = v < rows * vpr;
-    // DENSE: all three matrices have no row padding, so the flat vector index addresses them directly
-    // (no 64-bit division per thread)
-    int64_t xo, qo, eo;
-    if constexpr (DENSE) {
-        xo = v * 8; qo = v * 8; eo = v >> 2;
-    } else {
-        const int64_t r = live ? v / vpr : 0, cv = live ? v % vpr : 0;
-        xo = r * ld + cv * 8; qo = r * ld_q + cv * 8; eo = r * ld_e + (cv >> 2);
-    }
-    const uint4 d = live ? load_stream(x + xo) : make_uint4(0, 0, 0, 0);
-    uint32_t m = pk_fold(pk_absmax4(0u, d));
-    uint32_t o = (uint32_t)__shfl_xor((int)m, 1, 64);
-    m = o > m ? o : m;
-    o = (uint32_t)__shfl_xor((int)m, 2, 64);
-    m = o > m ? o : m;                                   // block maximum, 15 magnitude bits of bfloat16
+    constexpr int U = DENSE ? 4 : 1;                    // vectors per thread, all loads issued before the first use
     constexpr int EMAX = FMT == FMT_E4M3FN ? 8 : 15;
-    int byte = 0;
-    if (m != 0) {
-        const int ef = (int)(m >> 7);
-        // normal: 2^(ef - 127) * 1.f; subnormal: mantissa * 2^-133
-        const int fl = ef > 0 ? ef - 127 : (31 - __builtin_clz(m)) - 133;
-        byte = fl - EMAX + 127;
-        byte = byte < 0 ? 0 : (byte > 254 ? 254 : byte);
+    const int64_t vpr = cols >> 3;                      // 128-bit vectors per row (cols % 32 == 0)
+    const int64_t nvec = rows * vpr;
+    const int64_t v0 = (int64_t)blockIdx.x * (256 * U) + threadIdx.x;
+    uint4 d[U];
+    int64_t xo[U], qo[U], eo[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t v = v0 + u * 256;
+        const bool live = v < nvec;
+        // DENSE: all three matrices have no row padding, so the flat vector index addresses them directly
+        // (no 64-bit division per thread)
+        if constexpr (DENSE) {
+            xo[u] = v * 8; qo[u] = v * 8; eo[u] = v >> 2;
+        } else {
+            const int64_t r = live ? v / vpr : 0, cv = live ? v % vpr : 0;
+            xo[u] = r * ld + cv * 8; qo[u] = r * ld_q + cv * 8; eo[u] = r * ld_e + (cv >> 2);
+        }
+        d[u] = live ? load_stream(x + xo[u]) : make_uint4(0, 0, 0, 0);
     }
-    // 2^(127 - byte): byte <= 246 for bfloat16 input, so the factor is a normal binary32
-    const float factor = __uint_as_float((uint32_t)(254 - byte) << 23);
-    if (!live) return;
-    store_stream(q + qo, cast8<FMT>(d, factor));
-    if ((threadIdx.x & 3) == 0) e8m0[eo] = (uint8_t)byte;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        uint32_t m = pk_fold(pk_absmax4(0u, d[u]));
+        uint32_t o = (uint32_t)__shfl_xor((int)m, 1, 64);
+        m = o > m ? o : m;
+        o = (uint32_t)__shfl_xor((int)m, 2, 64);
+        m = o > m ? o : m;                                   // block maximum, 15 magnitude bits of bfloat16
+        int byte = 0;
+        if (m != 0) {
+            const int ef = (int)(m >> 7);
+            // normal: 2^(ef - 127) * 1.f; subnormal: mantissa * 2^-133
+            const int fl = ef > 0 ? ef - 127 : (31 - __builtin_clz(m)) - 133;
+            byte = fl - EMAX + 127;
+            byte = byte < 0 ? 0 : (byte > 254 ? 254 : byte);
+        }
+        // 2^(127 - byte): byte <= 246 for bfloat16 input, so the factor is a normal binary32
+        const float factor = __uint_as_float((uint32_t)(254 - byte) << 23);
+        if (v0 + u * 256 < nvec) {
+            store_stream(q + qo[u], cast8<FMT>(d[u], factor));
+            if ((threadIdx.x & 3) == 0) e8m0[eo[u]] = (uint8_t)byte;
+        }
+    }
 }
 
 hipError_t launch_mx_quant(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, uint8_t* q, int64_t ld_q,
                            uint8_t* e8m0, int64_t ld_e, hipStream_t st) {
     if (rows == 0 || cols == 0) return hipSuccess;
     const int64_t nvec = rows * (cols / 8);
-    const int64_t blocks = (nvec + 255) / 256;
+    const bool dense = ld == cols && ld_q == cols && ld_e == cols / 32;
+    const int64_t per_block = dense ? 1024 : 256;       // the dense kernel takes 4 vectors per thread
+    const int64_t blocks = (nvec + per_block - 1) / per_block;
     if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
     const uint16_t* xp = static_cast<const uint16_t*>(x);
-    const bool dense = ld == cols && ld_q == cols && ld_e == cols / 32;
 #define FP8K_MXQ(FMT, D) mx_quant_kernel<FMT, D><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(xp, rows, cols, ld, q, ld_q, e8m0, ld_e)
     if (fmt == FMT_E4M3FN) { if (dense) FP8K_MXQ(FMT_E4M3FN, true); else FP8K_MXQ(FMT_E4M3FN, false); }
     else { if (dense) FP8K_MXQ(FMT_E5M2, true); else FP8K_MXQ(FMT_E5M2, false); }
