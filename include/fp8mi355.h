@@ -247,6 +247,10 @@ int fp8_linear_fwd_prequantized(const void* x, int64_t M, int64_t K, int fmt_x, 
  *   qt_out [cols, rows] (ld_q % 16 == 0), e8m0_t_out [cols, rows / 32] (ld_e % 4 == 0),
  *   equal to fp8_mx_quantize of the transposed matrix.  It produces the
  *   contraction-contiguous operands of the backward products.
+ * fp8_mx_quantize_row_col: both of the above from ONE read of x (rows % 32 == 0,
+ *   cols % 32 == 0): q_row / e_row as fp8_mx_quantize writes them, q_col_t / e_col_t
+ *   as fp8_mx_quantize_t does.  A tensor needed in both orientations (the gradient
+ *   in the backward) costs 4 bytes of HBM traffic per element instead of 6.
  * fp8_mx_linear_bwd: dX [M, K] = dY W and dW [N, K] = dY^T X (bfloat16; either
  *   output may be NULL).  The MX specification (Section 6.2) defines the scaled
  *   dot product over blocks of the contracted index, so each operand is
@@ -260,6 +264,9 @@ int fp8_mx_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int f
                     uint8_t* q_out, int64_t ld_q, uint8_t* e8m0_out, int64_t ld_e, void* stream);
 int fp8_mx_quantize_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int format,
                       uint8_t* qt_out, int64_t ld_q, uint8_t* e8m0_t_out, int64_t ld_e, void* stream);
+int fp8_mx_quantize_row_col(const void* x, int64_t rows, int64_t cols, int64_t ld, int format,
+                            uint8_t* q_row, int64_t ld_row, uint8_t* e_row, int64_t ld_er,
+                            uint8_t* q_col_t, int64_t ld_col_t, uint8_t* e_col_t, int64_t ld_ec, void* stream);
 int fp8_mx_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const uint8_t* ea, int64_t ld_ea,
                      const uint8_t* b, int64_t ldb, int fmt_b, const uint8_t* eb, int64_t ld_eb,
                      int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int flags, void* stream);

@@ -492,7 +492,28 @@ int fp8_mx_quantize_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int
     if (ld_e < rows / 32 || ld_e % 4 != 0) return fail(FP8_ERR_SHAPE, "%s: ld_e=%lld must be >= rows/32 and a multiple of 4", fn, (long long)ld_e);
     if (rows > 0 && cols > 0 && !e8m0_t_out) return fail(FP8_ERR_NULL, "%s: e8m0_t_out is NULL", fn);
     if (!aligned(e8m0_t_out, 4)) return fail(FP8_ERR_ALIGN, "%s: e8m0_t_out not 4-byte aligned", fn);
-    FP8_TRY(fp8k::launch_mx_quant_t(x, rows, cols, ld, format, qt_out, ld_q, e8m0_t_out, ld_e, static_cast<hipStream_t>(stream)));
+    FP8_TRY(fp8k::launch_mx_quant_t(x, rows, cols, ld, format, qt_out, ld_q, e8m0_t_out, ld_e, nullptr, 0, nullptr, 0,
+                                    static_cast<hipStream_t>(stream)));
+    return FP8_OK;
+}
+
+int fp8_mx_quantize_row_col(const void* x, int64_t rows, int64_t cols, int64_t ld, int format, uint8_t* q_row,
+                            int64_t ld_row, uint8_t* e_row, int64_t ld_er, uint8_t* q_col_t, int64_t ld_col_t,
+                            uint8_t* e_col_t, int64_t ld_ec, void* stream) {
+    g_err[0] = 0;
+    const char* fn = "fp8_mx_quantize_row_col";
+    if (!fmt_ok(format)) return fail(FP8_ERR_ENUM, "%s: unknown format %d", fn, format);
+    if (int rc = check_bf16(fn, x, rows, cols, ld)) return rc;
+    if (rows % 32 != 0 || cols % 32 != 0)
+        return fail(FP8_ERR_SHAPE, "%s: rows=%lld and cols=%lld must be multiples of the block size 32", fn, (long long)rows, (long long)cols);
+    if (int rc = check_q_out("fp8_mx_quantize_row_col(q_row)", q_row, rows, cols, ld_row, 0)) return rc;
+    if (int rc = check_q_out("fp8_mx_quantize_row_col(q_col_t)", q_col_t, cols, rows, ld_col_t, 0)) return rc;
+    if (ld_er < cols / 32 || ld_er % 4 != 0 || ld_ec < rows / 32 || ld_ec % 4 != 0)
+        return fail(FP8_ERR_SHAPE, "%s: ld_er=%lld, ld_ec=%lld must cover the blocks and be multiples of 4", fn, (long long)ld_er, (long long)ld_ec);
+    if (rows > 0 && cols > 0 && (!e_row || !e_col_t)) return fail(FP8_ERR_NULL, "%s: scale output is NULL", fn);
+    if (!aligned(e_row, 4) || !aligned(e_col_t, 4)) return fail(FP8_ERR_ALIGN, "%s: scale outputs not 4-byte aligned", fn);
+    FP8_TRY(fp8k::launch_mx_quant_t(x, rows, cols, ld, format, q_col_t, ld_col_t, e_col_t, ld_ec, q_row, ld_row, e_row, ld_er,
+                                    static_cast<hipStream_t>(stream)));
     return FP8_OK;
 }
 
@@ -630,14 +651,15 @@ int fp8_mx_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, i
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* ws = static_cast<uint8_t*>(workspace);
     // all quantizations first, then the products back to back
-    if (dx) {
+    if (dx && dw) {   // the gradient in both orientations from one read
+        FP8_TRY(fp8k::launch_mx_quant_t(dy, M, N, N, fmt_dy, ws + p.dytq, M, ws + p.dyte, M / 32, ws + p.dyq, N, ws + p.dye, N / 32, st));
+    } else if (dx) {
         FP8_TRY(fp8k::launch_mx_quant(dy, M, N, N, fmt_dy, ws + p.dyq, N, ws + p.dye, N / 32, st));
-        FP8_TRY(fp8k::launch_mx_quant_t(w, N, K, K, fmt_w, ws + p.wtq, N, ws + p.wte, N / 32, st));
+    } else {
+        FP8_TRY(fp8k::launch_mx_quant_t(dy, M, N, N, fmt_dy, ws + p.dytq, M, ws + p.dyte, M / 32, nullptr, 0, nullptr, 0, st));
     }
-    if (dw) {
-        FP8_TRY(fp8k::launch_mx_quant_t(dy, M, N, N, fmt_dy, ws + p.dytq, M, ws + p.dyte, M / 32, st));
-        FP8_TRY(fp8k::launch_mx_quant_t(x, M, K, K, fmt_x, ws + p.xtq, M, ws + p.xte, M / 32, st));
-    }
+    if (dx) FP8_TRY(fp8k::launch_mx_quant_t(w, N, K, K, fmt_w, ws + p.wtq, N, ws + p.wte, N / 32, nullptr, 0, nullptr, 0, st));
+    if (dw) FP8_TRY(fp8k::launch_mx_quant_t(x, M, K, K, fmt_x, ws + p.xtq, M, ws + p.xte, M / 32, nullptr, 0, nullptr, 0, st));
     if (dx)
         FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dyq, N, fmt_dy, ws + p.dye, N / 32, ws + p.wtq, N, fmt_w, ws + p.wte, N / 32,
                                         M, K, N, dx, K, 0, st));

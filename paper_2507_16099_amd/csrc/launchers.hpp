@@ -82,9 +82,12 @@ hipError_t launch_gemm_bf16_at_b_snake(const void* a, int64_t lda, const void* b
 // (K % 128 == 0, ld_ea and ld_eb multiples of 4, 4-byte aligned scale pointers)
 hipError_t launch_mx_quant(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, uint8_t* q, int64_t ld_q,
                            uint8_t* e8m0, int64_t ld_e, hipStream_t st);
-// blocks of 32 down the columns of x (rows % 32 == 0), output transposed: qt [cols, rows], et [cols, rows / 32]
+// blocks of 32 down the columns of x (rows % 32 == 0), output transposed: qt [cols, rows], et [cols, rows / 32];
+// with q_row != nullptr also the blocks along the rows (cols % 32 == 0) from the same read: q_row [rows, cols],
+// e_row [rows, cols / 32] (ld_er % 4 == 0)
 hipError_t launch_mx_quant_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, uint8_t* qt, int64_t ld_t,
-                             uint8_t* et, int64_t ld_e, hipStream_t st);
+                             uint8_t* et, int64_t ld_e, uint8_t* q_row, int64_t ld_row, uint8_t* e_row, int64_t ld_er,
+                             hipStream_t st);
 hipError_t launch_gemm_mxfp8(const uint8_t* a, int64_t lda, int fmt_a, const uint8_t* ea, int64_t ld_ea,
                              const uint8_t* b, int64_t ldb, int fmt_b, const uint8_t* eb, int64_t ld_eb, int64_t M,
                              int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32, hipStream_t st);

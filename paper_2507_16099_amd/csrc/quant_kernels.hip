@@ -856,14 +856,22 @@ hipError_t launch_mx_quant(const void* x, int64_t rows, int64_t cols, int64_t ld
 // blocks, byte transpose, swizzled LDS tile, 128-bit streaming stores); a
 // wavefront holds exactly one block of 32 rows (4 thread rows x 8), so the
 // block maxima of its 128 columns are two cross-lane steps away.
-template <int FMT>
+// ROWS_TOO: the same read also yields the quantization with the blocks running ALONG the rows
+// (q_row [rows, cols], e_row [rows, cols / 32]; cols % 32 == 0): the four threads that hold 32
+// consecutive elements of a row combine their maxima with two cross-lane steps.  A tensor that is
+// needed in both orientations (the gradient in the backward) then costs 4 bytes per element
+// instead of 6.
+template <int FMT, bool ROWS_TOO>
 __global__ __launch_bounds__(256) void mx_quant_t_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
                                                           int64_t ld, uint8_t* __restrict__ qt, int64_t ld_t,
-                                                          uint8_t* __restrict__ et, int64_t ld_e, int nx, int ny) {
+                                                          uint8_t* __restrict__ et, int64_t ld_e,
+                                                          uint8_t* __restrict__ q_row, int64_t ld_row,
+                                                          uint8_t* __restrict__ e_row, int64_t ld_er, int nx, int ny) {
     constexpr int TR = 128, SLOTS = TR / 8, PARTS = TR / 16;
     constexpr int EMAX = FMT == FMT_E4M3FN ? 8 : 15;
     __shared__ __attribute__((aligned(16))) uint2 tile[128 * SLOTS];
     __shared__ __attribute__((aligned(16))) uint8_t ebytes[128 * 4];   // [column of the tile][block of the tile]
+    __shared__ __attribute__((aligned(16))) uint8_t rbytes[ROWS_TOO ? 128 * 4 : 4];   // [row of the tile][column block of the tile]
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
     constexpr int PX = 16, PY = 16;
     const int pxc = (nx + PX - 1) / PX;
@@ -887,6 +895,29 @@ __global__ __launch_bounds__(256) void mx_quant_t_kernel(const uint16_t* __restr
                 for (int e = 0; c + e < cols; ++e) t[e >> 1] |= (uint32_t)src[e] << ((e & 1) * 16);
                 v[j] = make_uint4(t[0], t[1], t[2], t[3]);
             }
+        }
+    }
+    if constexpr (ROWS_TOO) {
+        // blocks along the rows: row r0 + 8 ty + j, columns c0 + 32 (tx / 4) .. + 31 (the tile is inside the
+        // matrix in this direction or the block is not stored: cols % 32 == 0)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            uint32_t mr = pk_fold(pk_absmax4(0u, v[j]));
+            uint32_t o = (uint32_t)__shfl_xor((int)mr, 1, 64);
+            mr = o > mr ? o : mr;
+            o = (uint32_t)__shfl_xor((int)mr, 2, 64);
+            mr = o > mr ? o : mr;
+            int byte = 0;
+            if (mr != 0) {
+                const int ef = (int)(mr >> 7);
+                const int fl = ef > 0 ? ef - 127 : (31 - __builtin_clz(mr)) - 133;
+                byte = fl - EMAX + 127;
+                byte = byte < 0 ? 0 : (byte > 254 ? 254 : byte);
+            }
+            const float f = __uint_as_float((uint32_t)(254 - byte) << 23);
+            const int64_t r = r0 + ty * 8 + j;
+            if (r < rows && c < cols) store_stream(q_row + r * ld_row + c, cast8<FMT>(v[j], f));
+            if ((tx & 3) == 0) rbytes[(ty * 8 + j) * 4 + (tx >> 2)] = (uint8_t)byte;
         }
     }
     // maxima of the 8 columns over this thread's 8 rows (two 15-bit magnitudes per register), then over the
@@ -962,19 +993,33 @@ __global__ __launch_bounds__(256) void mx_quant_t_kernel(const uint16_t* __restr
             for (int b = 0; r0 + 32 * b < rows; ++b) dst[b] = (uint8_t)((four >> (8 * b)) & 0xFFu);
         }
     }
+    if constexpr (ROWS_TOO) {
+        // the tile's 128 x 4 row-direction scale bytes, one dword per row (threads 128..255)
+        const int rr = (int)threadIdx.x - 128;
+        if (rr >= 0 && r0 + rr < rows) {
+            uint8_t* dst = e_row + (r0 + rr) * ld_er + c0 / 32;
+            const uint32_t four = reinterpret_cast<const uint32_t*>(rbytes)[rr];
+            if (c0 + 128 <= cols) {
+                *reinterpret_cast<uint32_t*>(dst) = four;   // ld_er % 4 == 0 and c0 / 32 % 4 == 0
+            } else {
+                for (int b = 0; c0 + 32 * b < cols; ++b) dst[b] = (uint8_t)((four >> (8 * b)) & 0xFFu);
+            }
+        }
+    }
 }
 
 hipError_t launch_mx_quant_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, uint8_t* qt, int64_t ld_t,
-                             uint8_t* et, int64_t ld_e, hipStream_t st) {
+                             uint8_t* et, int64_t ld_e, uint8_t* q_row, int64_t ld_row, uint8_t* e_row, int64_t ld_er,
+                             hipStream_t st) {
     if (rows == 0 || cols == 0) return hipSuccess;
     const int64_t gx = (cols + 127) / 128, gy = (rows + 127) / 128;
     const int64_t total = ((gy + 15) / 16) * ((gx + 15) / 16) * 256;
     if (total > 0x7FFFFFFF) return hipErrorInvalidValue;
     const uint16_t* xp = static_cast<const uint16_t*>(x);
-    if (fmt == FMT_E4M3FN)
-        mx_quant_t_kernel<FMT_E4M3FN><<<dim3((unsigned)total), dim3(256), 0, st>>>(xp, rows, cols, ld, qt, ld_t, et, ld_e, (int)gy, (int)gx);
-    else
-        mx_quant_t_kernel<FMT_E5M2><<<dim3((unsigned)total), dim3(256), 0, st>>>(xp, rows, cols, ld, qt, ld_t, et, ld_e, (int)gy, (int)gx);
+#define FP8K_MXT(FMT, R) mx_quant_t_kernel<FMT, R><<<dim3((unsigned)total), dim3(256), 0, st>>>(xp, rows, cols, ld, qt, ld_t, et, ld_e, q_row, ld_row, e_row, ld_er, (int)gy, (int)gx)
+    if (fmt == FMT_E4M3FN) { if (q_row) FP8K_MXT(FMT_E4M3FN, true); else FP8K_MXT(FMT_E4M3FN, false); }
+    else { if (q_row) FP8K_MXT(FMT_E5M2, true); else FP8K_MXT(FMT_E5M2, false); }
+#undef FP8K_MXT
     return hipGetLastError();
 }
 

@@ -173,6 +173,21 @@ def test_mx_quantize_t_shapes(rows, cols, ld, fmt):
     assert (host_u8(et) == we).all() and (host_u8(qt) == wq).all()
 
 
+@pytest.mark.parametrize("rows,cols,ld", [(32, 32, 32), (96, 160, 168), (128, 128, 128), (160, 288, 288), (1024, 992, 992),
+                                          (4128, 64, 64), (2080, 2080, 2080)])
+@pytest.mark.parametrize("fmt", FMTS)
+def test_mx_quantize_row_col_shapes(rows, cols, ld, fmt):
+    """Both orientations from one read == the two single-orientation conversions of the oracle."""
+    x = si.student_t_outlier_bf16((rows, cols), 3.0, 0.01, 100.0, seed=7, stream=rows + cols)
+    x[:32, cols // 2] = 0
+    x[rows // 2, :32] = 0x8000
+    q_row, e_row, q_col_t, e_col_t = fp8.fp8_mx_quantize_row_col(dev_bf16(x, ld), fmt)
+    wq, we = orc.mx_quantize(x, fmt)
+    wqt, wet = orc.mx_quantize(np.ascontiguousarray(x.T), fmt)
+    assert (host_u8(e_row) == we).all() and (host_u8(q_row) == wq).all()
+    assert (host_u8(e_col_t) == wet).all() and (host_u8(q_col_t) == wqt).all()
+
+
 @pytest.mark.parametrize("M,K,N", [(128, 64, 128), (256, 8, 128), (384, 272, 512), (1024, 384, 640), (128, 1152, 256)])
 def test_mx_linear_backward(M, K, N):
     wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)
@@ -217,6 +232,12 @@ def test_mx_full_size_llama_ffn_backward_sampled_rows():
         oq, oe = orc.mx_quantize(np.ascontiguousarray(host.T), orc.E4M3FN)
         assert (host_u8(qt) == oq).all() and (host_u8(et) == oe).all(), name
         del qt, et, oq, oe
+    q_row, e_row, q_col_t, e_col_t = fp8.fp8_mx_quantize_row_col(dyd, fp8.FP8_E4M3FN)       # the gradient, one read
+    oq, oe = orc.mx_quantize(dy, orc.E4M3FN)
+    assert (host_u8(q_row) == oq).all() and (host_u8(e_row) == oe).all()
+    oq, oe = orc.mx_quantize(np.ascontiguousarray(dy.T), orc.E4M3FN)
+    assert (host_u8(q_col_t) == oq).all() and (host_u8(e_col_t) == oe).all()
+    del q_row, e_row, q_col_t, e_col_t, oq, oe
     dx, dw = fp8.fp8_mx_linear_bwd(dyd, dxd, dwd)
     rx, rw = si.stratified_rows(wl.M, 16), si.stratified_rows(wl.N, 16)
     wx, ww = orc.mx_linear_bwd(dy, x, w, rows_dx=rx, rows_dw=rw)
