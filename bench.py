@@ -82,16 +82,15 @@ def _sweep(torch, fp8, dev, iters: int) -> dict:
                     torch.matmul(dy, w, out=dx)
                     torch.matmul(dy.t(), x, out=dw)
                 entry = {"M": M, "K": K, "N": N, "bf16_ms": round(_event_time_ms(bf16_step, iters, 2, torch), 4)}
-                # tensorwise: the forward leaves the transposed fp8 copies of X and W for the backward
-                # (one scale per tensor, so they stay valid): 3 quantizations per step instead of 5
-                for tag, gran, fl in (("rowwise", fp8.FP8_ROW, 0), ("tensorwise", fp8.FP8_TENSOR, fp8.FP8_SAVE_FOR_BWD)):
-                    r = fp8.Recipe(gran=gran, flags=fl)
-                    wb = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, True), dtype=torch.uint8, device=dev)
-                    wf = wb if fl else torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, False), dtype=torch.uint8, device=dev)
+                # forward and backward share one workspace (FP8_SAVE_FOR_BWD): the forward also makes the fp8
+                # copies of X and W that the backward needs (tensorwise: 3 quantizations per step instead of 5)
+                for tag, gran in (("rowwise", fp8.FP8_ROW), ("tensorwise", fp8.FP8_TENSOR)):
+                    r = fp8.Recipe(gran=gran, flags=fp8.FP8_SAVE_FOR_BWD)
+                    wf = wb = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, True), dtype=torch.uint8, device=dev)
 
                     def fp8_step():
                         fp8.fp8_linear_fwd(x, w, r, y=y, workspace=wf)
-                        fp8.fp8_linear_bwd(dy, x, w, r, dx=dx, dw=dw, workspace=wb)
+                        fp8.fp8_linear_bwd(dy, (M, K), (N, K), r, dx=dx, dw=dw, workspace=wb)
                     ms = _event_time_ms(fp8_step, iters, 2, torch)
                     entry[f"fp8_{tag}_ms"] = round(ms, 4)
                     entry[f"speedup_{tag}"] = round(entry["bf16_ms"] / ms, 3)
@@ -265,10 +264,24 @@ def main() -> int:
     ws_f = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, recipe, False), dtype=torch.uint8, device=dev)
     ws_b = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, recipe, True), dtype=torch.uint8, device=dev)
 
-    def step():
+    def stateless_step():
         fp8.fp8_linear_fwd(x, w, recipe, y=y, workspace=ws_f)
         if wl.backward:
             fp8.fp8_linear_bwd(dy, x, w, recipe, dx=dx, dw=dw, workspace=ws_b)
+
+    # The timed step: forward and backward share one workspace (FP8_SAVE_FOR_BWD), so the fp8 copies of
+    # X and W that the backward needs are made by the forward from the same read as its own.  Every
+    # step still quantizes X, W and dY from their bfloat16 originals (dynamic scaling); codes, scales and
+    # results are identical to the stateless calls (tested bit for bit).
+    if wl.backward:
+        recipe_s = fp8.Recipe(gran=recipe.gran, flags=recipe.flags | fp8.FP8_SAVE_FOR_BWD)
+        ws_s = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, recipe_s, True), dtype=torch.uint8, device=dev)
+
+        def step():
+            fp8.fp8_linear_fwd(x, w, recipe_s, y=y, workspace=ws_s)
+            fp8.fp8_linear_bwd(dy, (M, K), (N, K), recipe_s, dx=dx, dw=dw, workspace=ws_s)
+    else:
+        step = stateless_step
 
     if args.traffic_probe:
         # reference for the counters: a plain copy of known size (1 GiB read + 1 GiB written)
@@ -300,8 +313,13 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "fp8_e4m3fn/e5m2 x fp32-accumulate -> bf16", "data": "synthetic",
         "config": {"workload": wl.name, "M": M, "K": K, "N": N, "recipe": wl.recipe, "pow2_scales": wl.pow2,
-                   "pass": "fwd+bwd" if wl.backward else "fwd", "flop_per_step": flop_step},
+                   "pass": "fwd+bwd" if wl.backward else "fwd", "flop_per_step": flop_step,
+                   "workspace": "shared by forward and backward (FP8_SAVE_FOR_BWD)" if wl.backward else "forward only"},
     }
+    if wl.backward:
+        ms0 = _event_time_ms(stateless_step, max(3, args.steps // 2), 2, torch)
+        result["stateless_step"] = {"ms_per_step": round(ms0, 4), "TFLOP/s": round(flop_step / (ms0 * 1e-3) / 1e12, 1),
+                                    "note": "separate workspaces: the backward re-reads X and W for its own copies"}
 
     # ------------------------------------------------ per-kernel legs
     if not args.no_kernel_legs:

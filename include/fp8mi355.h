@@ -56,8 +56,8 @@ enum fp8_flags {
     FP8_TRANSPOSE_OUT = 2, /* fp8_cast / fp8_quantize write q[c, r] not q[r, c] */
     FP8_OUT_FP32      = 4, /* fp8_scaled_mm writes fp32 instead of bfloat16     */
     FP8_GRAD_WEIGHT_HP = 8, /* recipe flag: dW is computed in bfloat16, not FP8  */
-    FP8_SAVE_FOR_BWD  = 16 /* recipe flag (tensorwise): the forward leaves the transposed fp8 copies
-                              of X and W in the workspace and the backward reuses them        */
+    FP8_SAVE_FOR_BWD  = 16 /* recipe flag: the forward leaves the transposed fp8 copies of X and W
+                              in the workspace and the backward reuses them                    */
 };
 
 enum fp8_status {
@@ -154,13 +154,18 @@ int fp8_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a
  * GEMM it feeds).  flags: FP8_POW2_SCALE, FP8_GRAD_WEIGHT_HP (with FP8_ROW this
  * is the "rowwise_gw_hp" recipe: the forward and dX run in FP8, the weight
  * gradient dW = dY^T X is computed from the unquantized bfloat16 tensors).
- * FP8_SAVE_FOR_BWD (FP8_TENSOR only): with one scale per tensor the backward
- * needs the same codes of X and W as the forward, only transposed (Appendix A:
- * tensorwise scaling computes a single scaling factor for each tensor), so the
- * forward can produce both layouts from one read and the backward quantizes dY
- * alone: 3 quantizations per step instead of 5.  Both calls must carry the flag
- * and get the SAME workspace, of fp8_linear_workspace_bytes(..., bwd = 1)
- * bytes, untouched in between; x and w may then be NULL in fp8_linear_bwd. */
+ * FP8_SAVE_FOR_BWD: the fp8 copies of X and W that the backward needs do not
+ * depend on the gradient, so the forward can make them from the same read as
+ * its own and leave them in the workspace; the backward then quantizes dY alone.
+ * Tensorwise (Appendix A: a single scaling factor for each tensor): the same
+ * codes, only transposed - one conversion into both layouts, 3 quantizations
+ * per step instead of 5.  Rowwise: the per-column, transposed codes of X and W
+ * next to the rowwise ones, two reads of each tensor per step instead of
+ * three.  Codes, scales and results are the same as without the flag.  Both
+ * calls must carry the flag and get the SAME workspace, of
+ * fp8_linear_workspace_bytes(..., bwd = 1) bytes, untouched in between; x and w
+ * may then be NULL in fp8_linear_bwd (x is still read for dW when the recipe
+ * also carries FP8_GRAD_WEIGHT_HP). */
 typedef struct fp8_recipe {
     int gran;
     int fmt_x;  /* format of activations, normally FP8_E4M3FN */

@@ -149,9 +149,6 @@ int check_recipe(const char* fn, const fp8_recipe* r) {
         return fail(FP8_ERR_ENUM, "%s: unknown fp8 format in recipe", fn);
     if (r->flags & ~(FP8_POW2_SCALE | FP8_GRAD_WEIGHT_HP | FP8_SAVE_FOR_BWD))
         return fail(FP8_ERR_ENUM, "%s: recipe.flags=%d has unknown bits", fn, r->flags);
-    if ((r->flags & FP8_SAVE_FOR_BWD) && r->gran != FP8_TENSOR)
-        return fail(FP8_ERR_ENUM, "%s: FP8_SAVE_FOR_BWD applies to the tensorwise recipe only (rowwise operands are "
-                                  "re-quantized along another axis in the backward)", fn);
     return FP8_OK;
 }
 
@@ -306,8 +303,10 @@ int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N
     const FwdPlan p = plan_fwd(M, K, N, recipe->gran);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (recipe->flags & FP8_SAVE_FOR_BWD) {
-        // tensorwise with saved copies: X and W are converted once into both layouts; the transposed
-        // codes and the scales go where the backward's plan expects them
+        // The copies of X and W that the backward needs do not depend on the gradient, so they are made
+        // here, from the same read as the forward's: the transposed codes and their scales go where the
+        // backward's plan expects them.  Tensorwise: one conversion into both layouts.  Rowwise: the
+        // rowwise codes for this GEMM plus the per-column (transposed) ones for dX / dW.
         if (int rc = check_linear_dims("fp8_linear_fwd", M, K, N, true)) return rc;
         const BwdPlan b = plan_bwd(M, K, N, recipe->gran);
         if (workspace_bytes < b.total + p.total)
@@ -317,9 +316,20 @@ int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N
         uint8_t* wsf = wsb + b.total;
         const int fl = recipe->flags & FP8_POW2_SCALE;
         float *sxt = reinterpret_cast<float*>(wsb + b.sxt), *swt = reinterpret_cast<float*>(wsb + b.swt);
-        if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | FP8_TRANSPOSE_OUT, wsb + b.xt, M, wsf + p.xq, K, sxt, st)) return rc;
-        if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | FP8_TRANSPOSE_OUT, wsb + b.wt, N, wsf + p.wq, K, swt, st)) return rc;
-        FP8_TRY(fp8k::launch_gemm_fp8(wsf + p.xq, K, recipe->fmt_x, sxt, 0, wsf + p.wq, K, recipe->fmt_w, swt, 0, M, N, K, y, N, 0, st));
+        if (recipe->gran == FP8_TENSOR) {
+            if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | FP8_TRANSPOSE_OUT, wsb + b.xt, M, wsf + p.xq, K, sxt, st)) return rc;
+            if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | FP8_TRANSPOSE_OUT, wsb + b.wt, N, wsf + p.wq, K, swt, st)) return rc;
+            FP8_TRY(fp8k::launch_gemm_fp8(wsf + p.xq, K, recipe->fmt_x, sxt, 0, wsf + p.wq, K, recipe->fmt_w, swt, 0, M, N, K, y, N, 0, st));
+            return FP8_OK;
+        }
+        float *sx = reinterpret_cast<float*>(wsf + p.sx), *sw = reinterpret_cast<float*>(wsf + p.sw);
+        if (recipe->flags & FP8_GRAD_WEIGHT_HP) {   // dW will come from the bfloat16 X: no fp8 copy of X to keep
+            if (int rc = quantize_impl(x, M, K, K, FP8_ROW, recipe->fmt_x, fl, wsf + p.xq, K, nullptr, 0, sx, st)) return rc;
+        } else {
+            if (int rc = quantize_row_col_impl(x, M, K, K, recipe->fmt_x, fl, wsf + p.xq, K, sx, wsb + b.xt, M, sxt, st)) return rc;
+        }
+        if (int rc = quantize_row_col_impl(w, N, K, K, recipe->fmt_w, fl, wsf + p.wq, K, sw, wsb + b.wt, N, swt, st)) return rc;
+        FP8_TRY(fp8k::launch_gemm_fp8(wsf + p.xq, K, recipe->fmt_x, sx, 1, wsf + p.wq, K, recipe->fmt_w, sw, 1, M, N, K, y, N, 0, st));
         return FP8_OK;
     }
     if (workspace_bytes < p.total)
@@ -343,7 +353,7 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
     if (int rc = check_linear_dims("fp8_linear_bwd", M, K, N, true)) return rc;
     if (int rc = check_bf16("fp8_linear_bwd(dy)", dy, M, N, N)) return rc;
     const bool saved = (recipe->flags & FP8_SAVE_FOR_BWD) != 0;   // codes of X and W left by the forward
-    if (dw && !saved) if (int rc = check_bf16("fp8_linear_bwd(x)", x, M, K, K)) return rc;
+    if (dw && (!saved || (recipe->flags & FP8_GRAD_WEIGHT_HP))) if (int rc = check_bf16("fp8_linear_bwd(x)", x, M, K, K)) return rc;
     if (dx && !saved) if (int rc = check_bf16("fp8_linear_bwd(w)", w, N, K, K)) return rc;
     if (M == 0 || N == 0 || K == 0 || (!dx && !dw)) return FP8_OK;
     if (!workspace) return fail(FP8_ERR_NULL, "fp8_linear_bwd: workspace is NULL");
@@ -401,9 +411,9 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
     } else {
         if (int rc = quantize_impl(dy, M, N, N, FP8_COL, recipe->fmt_dy, fl | T, gqt, M, nullptr, 0, sgt, st)) return rc;
     }
-    if (dx)
+    if (dx && !saved)
         if (int rc = quantize_impl(w, N, K, K, FP8_COL, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st)) return rc;
-    if (dw)
+    if (dw && !saved)
         if (int rc = quantize_impl(x, M, K, K, FP8_COL, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st)) return rc;
     if (dx)
         FP8_TRY(fp8k::launch_gemm_fp8(gq, N, recipe->fmt_dy, sg, 1, wt, N, recipe->fmt_w, swt, 1, M, K, N, dx, K, 0, st));

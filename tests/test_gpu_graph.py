@@ -18,7 +18,7 @@ def _bits(t):
     return t.view(torch.int16).clone()
 
 
-@pytest.mark.parametrize("recipe", ["rowwise", "tensorwise", "tensorwise_saved", "rowwise_gw_hp", "mx"])
+@pytest.mark.parametrize("recipe", ["rowwise", "rowwise_saved", "tensorwise", "tensorwise_saved", "rowwise_gw_hp", "mx"])
 def test_step_replays_from_a_hip_graph(recipe):
     M, K, N = 1024, 512, 768
     wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)
@@ -40,9 +40,10 @@ def test_step_replays_from_a_hip_graph(recipe):
     else:
         r = {"rowwise": fp8.Recipe(gran=fp8.FP8_ROW), "tensorwise": fp8.Recipe(gran=fp8.FP8_TENSOR),
              "tensorwise_saved": fp8.Recipe(gran=fp8.FP8_TENSOR, flags=fp8.FP8_SAVE_FOR_BWD),
+             "rowwise_saved": fp8.Recipe(gran=fp8.FP8_ROW, flags=fp8.FP8_SAVE_FOR_BWD),
              "rowwise_gw_hp": fp8.Recipe(gran=fp8.FP8_ROW, flags=fp8.FP8_GRAD_WEIGHT_HP)}[recipe]
         ws_b = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, True), dtype=torch.uint8, device="cuda")
-        ws_f = ws_b if recipe == "tensorwise_saved" else torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, False),
+        ws_f = ws_b if recipe.endswith("_saved") else torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, False),
                                                                      dtype=torch.uint8, device="cuda")
 
         def step():

@@ -191,39 +191,65 @@ def test_full_size_outlier_stress_rowwise_vs_tensorwise():
     assert r.n_sat <= 4096 and t.n_sat <= 1     # only amax elements can be clamped under dynamic scaling
 
 
-# ------------------------------------------------ tensorwise: fp8 copies saved by the forward
+# ------------------------------------------------ fp8 copies of X and W saved by the forward
 
-@pytest.mark.parametrize("M,K,N", [(64, 64, 64), (208, 176, 272), (512, 1024, 768), (1024, 384, 640)])
-@pytest.mark.parametrize("pow2", [False, True])
-def test_tensorwise_backward_reuses_the_forward_copies(M, K, N, pow2):
-    """FP8_SAVE_FOR_BWD: X and W are converted once (both layouts from one read),
-    the backward quantizes dY only.  Same codes and scales as the stateless
-    calls, so the outputs are identical bit for bit, and they match the oracle."""
-    wl = si.scaled_down(si.WORKLOADS["c3_llama3_8b_qkv_tensorwise"], M, K, N)
+@pytest.mark.parametrize("M,K,N", [(64, 64, 64), (208, 176, 272), (512, 1024, 768), (1024, 384, 640), (2048, 1024, 256)])
+@pytest.mark.parametrize("recipe", ["tensorwise", "tensorwise_pow2", "rowwise", "rowwise_pow2", "rowwise_gw_hp"])
+def test_backward_reuses_the_forward_copies(M, K, N, recipe):
+    """FP8_SAVE_FOR_BWD: the copies of X and W that the backward needs are made by
+    the forward (tensorwise: both layouts from one conversion; rowwise: the
+    per-column transposed codes next to the rowwise ones) and the backward
+    quantizes dY only.  Same codes and scales as the stateless calls, so the
+    outputs are identical bit for bit, and they match the oracle."""
+    base = "c3_llama3_8b_qkv_tensorwise" if recipe.startswith("tensorwise") else "c2_llama3_8b_ffn_rowwise"
+    wl = si.scaled_down(si.WORKLOADS[base], M, K, N)
     x, w, dy = wl.x(), wl.w(), wl.dy()
     xd, wd, dyd = dev_bf16(x), dev_bf16(w), dev_bf16(dy)
-    fl = fp8.FP8_POW2_SCALE if pow2 else 0
-    plain = fp8.Recipe(gran=fp8.FP8_TENSOR, flags=fl)
-    saved = fp8.Recipe(gran=fp8.FP8_TENSOR, flags=fl | fp8.FP8_SAVE_FOR_BWD)
+    pow2 = recipe.endswith("pow2")
+    hp = recipe.endswith("gw_hp")
+    gran = fp8.FP8_TENSOR if recipe.startswith("tensorwise") else fp8.FP8_ROW
+    fl = (fp8.FP8_POW2_SCALE if pow2 else 0) | (fp8.FP8_GRAD_WEIGHT_HP if hp else 0)
+    plain = fp8.Recipe(gran=gran, flags=fl)
+    saved = fp8.Recipe(gran=gran, flags=fl | fp8.FP8_SAVE_FOR_BWD)
     y0 = fp8.fp8_linear_fwd(xd, wd, plain)
     dx0, dw0 = fp8.fp8_linear_bwd(dyd, xd, wd, plain)
     ws = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, saved, True), dtype=torch.uint8, device="cuda")
     y1 = fp8.fp8_linear_fwd(xd, wd, saved, workspace=ws)
-    dx1, dw1 = fp8.fp8_linear_bwd(dyd, (M, K), (N, K), saved, workspace=ws)     # x and w are not read again
-    for a, b in ((y0, y1), (dx0, dx1), (dw0, dw1)):
-        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
-    o = orc.Recipe(gran=orc.TENSOR, pow2=pow2)
+    x_arg = xd if hp else (M, K)                  # the bfloat16 weight gradient still reads X
+    dx1, dw1 = fp8.fp8_linear_bwd(dyd, x_arg, (N, K), saved, workspace=ws)
+    for a_, b_ in ((y0, y1), (dx0, dx1), (dw0, dw1)):
+        assert torch.equal(a_.view(torch.int16), b_.view(torch.int16))
+    o = orc.Recipe(gran=orc.TENSOR if gran == fp8.FP8_TENSOR else orc.ROW, pow2=pow2)
     _cmp(y1, orc.linear_fwd(x, w, o)[0])
     _cmp(dx1, orc.linear_bwd_dx(dy, w, o)[0])
-    _cmp(dw1, orc.linear_bwd_dw(dy, x, o)[0])
+    if not hp:
+        _cmp(dw1, orc.linear_bwd_dw(dy, x, o)[0])
     # one output only
-    only_dx, none = fp8.fp8_linear_bwd(dyd, (M, K), (N, K), saved, workspace=ws, need_dw=False)
+    only_dx, none = fp8.fp8_linear_bwd(dyd, x_arg, (N, K), saved, workspace=ws, need_dw=False)
     assert none is None and torch.equal(only_dx.view(torch.int16), dx0.view(torch.int16))
-    with pytest.raises(fp8.Fp8Error):
-        fp8.fp8_linear_workspace_bytes(M, K, N, fp8.Recipe(gran=fp8.FP8_ROW, flags=fp8.FP8_SAVE_FOR_BWD), True)
+    none, only_dw = fp8.fp8_linear_bwd(dyd, x_arg, (N, K), saved, workspace=ws, need_dx=False)
+    assert none is None and torch.equal(only_dw.view(torch.int16), dw0.view(torch.int16))
     with pytest.raises(fp8.Fp8Error):                                             # the stateless size is too small
         small = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, plain, False), dtype=torch.uint8, device="cuda")
         fp8.fp8_linear_fwd(xd, wd, saved, workspace=small)
+
+
+def test_full_size_step_with_saved_copies_matches_the_stateless_calls():
+    """The benchmark workload with FP8_SAVE_FOR_BWD (the configuration bench.py
+    times): bit-identical to the stateless forward and backward, which the
+    sampled-row tests above compare with the oracle."""
+    wl = si.WORKLOADS[si.BENCH_WORKLOAD]
+    M, K, N = wl.M, wl.K, wl.N
+    xd, wd, dyd = dev_bf16(wl.x()), dev_bf16(wl.w()), dev_bf16(wl.dy())
+    _, g = _recipes(wl)
+    y0 = fp8.fp8_linear_fwd(xd, wd, g)
+    dx0, dw0 = fp8.fp8_linear_bwd(dyd, xd, wd, g)
+    saved = fp8.Recipe(gran=g.gran, flags=g.flags | fp8.FP8_SAVE_FOR_BWD)
+    ws = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, saved, True), dtype=torch.uint8, device="cuda")
+    y1 = fp8.fp8_linear_fwd(xd, wd, saved, workspace=ws)
+    dx1, dw1 = fp8.fp8_linear_bwd(dyd, (M, K), (N, K), saved, workspace=ws)
+    for a_, b_ in ((y0, y1), (dx0, dx1), (dw0, dw1)):
+        assert torch.equal(a_.view(torch.int16), b_.view(torch.int16))
 
 
 # ------------------------------------------------ inference: weight quantized once
