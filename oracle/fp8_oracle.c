@@ -449,3 +449,61 @@ void orc_bf16_mm_f64(const uint16_t* a, int64_t lda, const uint16_t* b, int64_t 
         }
     }
 }
+
+/*
+ * Round a binary64 value to bfloat16, to nearest, ties to even, in ONE rounding
+ * (going through binary32 first would round twice).  Written from the format:
+ * 8 exponent bits (bias 127), 7 fraction bits, subnormals with quantum 2^-133.
+ */
+uint16_t orc_f64_to_bf16(double d) {
+    if (isnan(d)) return 0x7FC0;
+    const uint16_t sign = signbit(d) ? 0x8000 : 0;
+    const double a = fabs(d);
+    if (a == 0.0) return sign;
+    if (isinf(a)) return sign | 0x7F80;
+    int e;
+    (void)frexp(a, &e);                       /* a = m * 2^e, m in [0.5, 1): leading bit has weight 2^(e-1) */
+    int E = e - 1;
+    if (E < -126) E = -126;                   /* subnormal range: fixed quantum */
+    const double quantum = ldexp(1.0, E - 7);
+    const double n = rint(a / quantum);       /* exact division by a power of two; rint = ties to even */
+    const double v = n * quantum;             /* representable in bfloat16 (or 2^128 = overflow) */
+    if (v >= ldexp(1.0, 128)) return sign | 0x7F80;
+    const float f = (float)v;                 /* exact */
+    return sign | (uint16_t)(f32_bits(f) >> 16);
+}
+
+/*
+ * Layer normalisation over the last axis, the operation in front of the linear
+ * layer in the paper's float8 microbenchmark (appendix "Float8 Training
+ * Microbenchmarks": LayerNorm + Linear + Sigmoid), whose output is what the
+ * forward casts to float8.  Definition, in binary64:
+ *   mean_r = sum_c x[r,c] / C;  var_r = sum_c (x[r,c] - mean_r)^2 / C   (biased)
+ *   rstd_r = 1 / sqrt(var_r + eps)
+ *   h[r,c] = (x[r,c] - mean_r) * rstd_r * gamma[c] + beta[c]            (beta == NULL: 0)
+ * h is rounded once to bfloat16 (the tensor a bfloat16 model materialises).
+ */
+void orc_layernorm(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, const uint16_t* gamma,
+                   const uint16_t* beta, double eps, uint16_t* h, int64_t ld_h, double* mean_out, double* rstd_out) {
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        const uint16_t* row = x + r * ld;
+        double sum = 0.0;
+        for (int64_t c = 0; c < cols; ++c) sum += (double)orc_bf16_to_f32(row[c]);
+        const double mean = sum / (double)cols;
+        double sq = 0.0;
+        for (int64_t c = 0; c < cols; ++c) {
+            const double dlt = (double)orc_bf16_to_f32(row[c]) - mean;
+            sq += dlt * dlt;
+        }
+        const double rstd = 1.0 / sqrt(sq / (double)cols + eps);
+        for (int64_t c = 0; c < cols; ++c) {
+            const double g = (double)orc_bf16_to_f32(gamma[c]);
+            const double b = beta ? (double)orc_bf16_to_f32(beta[c]) : 0.0;
+            h[r * ld_h + c] = orc_f64_to_bf16(((double)orc_bf16_to_f32(row[c]) - mean) * rstd * g + b);
+        }
+        if (mean_out) mean_out[r] = mean;
+        if (rstd_out) rstd_out[r] = rstd;
+    }
+}
+

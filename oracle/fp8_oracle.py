@@ -85,6 +85,10 @@ def lib() -> C.CDLL:
         L.orc_mx_mm.argtypes = [vp, i64, ci, vp, i64, vp, i64, ci, vp, i64, i64, i64, i64, vp, i64, vp, vp, vp]
         L.orc_bf16_mm_f64.restype = None
         L.orc_bf16_mm_f64.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i64, vp]
+        L.orc_f64_to_bf16.restype = C.c_uint16
+        L.orc_f64_to_bf16.argtypes = [C.c_double]
+        L.orc_layernorm.restype = None
+        L.orc_layernorm.argtypes = [vp, i64, i64, i64, vp, vp, C.c_double, vp, i64, vp, vp]
         _lib = L
     return _lib
 
@@ -371,6 +375,33 @@ def linear_bwd_dw_hp(dy, x, rows=None):
     acc = bf16_mm_f64(np.ascontiguousarray(dy.T), np.ascontiguousarray(x.T), rows)
     out32 = acc.astype(np.float32)
     return out32, f32_to_bf16(out32)
+
+
+def f64_to_bf16(d: float) -> int:
+    return int(lib().orc_f64_to_bf16(float(d)))
+
+
+def layernorm(x: np.ndarray, gamma: np.ndarray, beta: np.ndarray | None, eps: float):
+    """LayerNorm over the last axis in binary64, output rounded once to bfloat16:
+    (h bits [rows, cols], mean [rows] f64, rstd [rows] f64)."""
+    rows, cols, ld = _check2d(x, np.uint16)
+    gamma = np.ascontiguousarray(gamma, dtype=np.uint16)
+    assert gamma.shape == (cols,)
+    if beta is not None:
+        beta = np.ascontiguousarray(beta, dtype=np.uint16)
+        assert beta.shape == (cols,)
+    h = np.empty((rows, cols), np.uint16)
+    mean = np.empty(rows, np.float64)
+    rstd = np.empty(rows, np.float64)
+    lib().orc_layernorm(_p(x), rows, cols, ld, _p(gamma), _p(beta), float(eps), _p(h), cols, _p(mean), _p(rstd))
+    return h, mean, rstd
+
+
+def layernorm_quantize(x, gamma, beta, eps, fmt=E4M3FN, pow2=False):
+    """The normalised bfloat16 tensor and its rowwise dynamic quantization (codes, scales)."""
+    h, mean, rstd = layernorm(x, gamma, beta, eps)
+    q, s = quantize(h, ROW, fmt, POW2_SCALE if pow2 else 0)
+    return h, q, s, mean, rstd
 
 
 def rel_frobenius(got: np.ndarray, ref: np.ndarray) -> float:
