@@ -434,6 +434,33 @@ def main() -> int:
                                        "TFLOP/s": round(flop_step / (hp_ms * 1e-3) / 1e12, 1),
                                        "note": "same step with the weight gradient kept in bfloat16 (Appendix A)"}
 
+        # LayerNorm in front of the linear with the cast fused into its epilogue (the block of the paper's
+        # microbenchmark appendix), against the unfused pair: a framework LayerNorm, then the rowwise quantize
+        if rowwise and K % 8 == 0 and K <= 16384:
+            gamma = (torch.rand(K, device=dev) + 0.5).to(torch.bfloat16)
+            beta = (torch.rand(K, device=dev) - 0.5).to(torch.bfloat16)
+
+            def lnq(inp, *o):
+                if o[0] is None:
+                    r5 = fp8.fp8_layernorm_quantize(inp, gamma, beta, 1e-5, E4, fl & fp8.FP8_POW2_SCALE, want_stats=False)
+                    return (r5[0], r5[1], r5[2])
+                fp8.fp8_layernorm_quantize(inp, gamma, beta, 1e-5, E4, fl & fp8.FP8_POW2_SCALE, out=(o[0], o[1], o[2], None, None))
+            cast_leg("layernorm_quant_x_fused", x, lnq, M * K, 5)
+            xs_ln = rotated(x)
+            qs_ln = [fp8.fp8_quantize(t_, gran, E4, fl) for t_ in xs_ln]
+            st_ln = {"i": 0}
+
+            def unfused():
+                i = st_ln["i"] = (st_ln["i"] + 1) % len(xs_ln)
+                hh = torch.nn.functional.layer_norm(xs_ln[i], (K,), gamma, beta, 1e-5)
+                fp8.fp8_quantize(hh, gran, E4, fl, out=qs_ln[i][0], scale_out=qs_ln[i][1])
+            ms = _event_time_ms(unfused, max(it, 2 * len(xs_ln)), len(xs_ln), torch)
+            kernels["layernorm_then_quant_x_unfused"] = {"ms": round(ms, 4), "bytes_per_elem": 7,
+                                                         "GB/s": round(M * K * 7 / (ms * 1e-3) / 1e9, 1),
+                                                         "comparator": "torch layer_norm (bf16) + fp8_quantize rowwise"}
+            del xs_ln, qs_ln
+            torch.cuda.empty_cache()
+
         # MX (microscaling) forward: block quantization of X and W, block-scaled GEMM
         if K % 128 == 0:
             mq = lambda inp, q, e: fp8.fp8_mx_quantize(inp, E4) if q is None else fp8.fp8_mx_quantize(inp, E4, q, e)

@@ -229,6 +229,27 @@ int fp8_linear_fwd_prequantized(const void* x, int64_t M, int64_t K, int fmt_x, 
                                 void* stream);
 
 /*
+ * Layer normalisation with the float8 cast fused into its epilogue: the block
+ * in front of the linear layer in the paper's float8 microbenchmark (appendix
+ * "Float8 Training Microbenchmarks": LayerNorm + Linear + Sigmoid), where the
+ * paper leaves the fusion of the dynamic cast into the neighbouring operation
+ * to the compiler.  One pass over x:
+ *   mean_r = sum_c x[r,c] / cols,  var_r = sum_c (x[r,c] - mean_r)^2 / cols,
+ *   h[r,c] = (x[r,c] - mean_r) / sqrt(var_r + eps) * gamma[c] + beta[c]
+ *   (statistics and normalisation in binary64, h rounded once to bfloat16),
+ *   then scale_out[r], q_out[r,:] = the rowwise quantization of the bfloat16 row
+ *   h[r,:], exactly what fp8_quantize(FP8_ROW) gives on h (flags: FP8_POW2_SCALE).
+ * x [rows, cols] bfloat16 (ld), gamma [cols] bfloat16, beta [cols] bfloat16 or
+ * NULL (zero); cols a multiple of 8, at most 16384.  Outputs: q_out [rows, cols]
+ * (ld_q % 16 == 0), scale_out [rows]; optional (NULL to skip): h_out [rows, cols]
+ * bfloat16 (ld_h), mean_out [rows], rstd_out [rows] fp32 (for a backward pass).
+ */
+int fp8_layernorm_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, const void* gamma,
+                           const void* beta, double eps, int format, int flags, void* h_out, int64_t ld_h,
+                           uint8_t* q_out, int64_t ld_q, float* scale_out, float* mean_out, float* rstd_out,
+                           void* stream);
+
+/*
  * MX (microscaling) FP8, the finer scaling granularity that the paper lists
  * among its prototype features ("MX formats: ... mxfp8 for training"); format
  * and conversion follow the OCP Microscaling Formats (MX) specification v1.0:

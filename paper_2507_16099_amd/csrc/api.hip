@@ -476,6 +476,31 @@ int fp8_linear_fwd_prequantized(const void* x, int64_t M, int64_t K, int fmt_x, 
     return FP8_OK;
 }
 
+int fp8_layernorm_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, const void* gamma, const void* beta,
+                           double eps, int format, int flags, void* h_out, int64_t ld_h, uint8_t* q_out, int64_t ld_q,
+                           float* scale_out, float* mean_out, float* rstd_out, void* stream) {
+    g_err[0] = 0;
+    const char* fn = "fp8_layernorm_quantize";
+    if (!fmt_ok(format)) return fail(FP8_ERR_ENUM, "%s: unknown format %d", fn, format);
+    if (flags & ~FP8_POW2_SCALE) return fail(FP8_ERR_ENUM, "%s: flags=%d has unknown bits", fn, flags);
+    if (int rc = check_bf16(fn, x, rows, cols, ld)) return rc;
+    if (cols % 8 != 0 || cols > 16384)
+        return fail(FP8_ERR_SHAPE, "%s: cols=%lld must be a multiple of 8 and at most 16384", fn, (long long)cols);
+    if (!(eps >= 0.0)) return fail(FP8_ERR_SHAPE, "%s: eps must be non-negative", fn);
+    if (int rc = check_q_out(fn, q_out, rows, cols, ld_q, 0)) return rc;
+    if (rows > 0 && cols > 0) {
+        if (!gamma || !scale_out) return fail(FP8_ERR_NULL, "%s: gamma or scale_out is NULL", fn);
+        if (!aligned(gamma, 16) || !aligned(beta, 16) || !aligned(h_out, 16))
+            return fail(FP8_ERR_ALIGN, "%s: gamma, beta and h_out must be 16-byte aligned", fn);
+        if (h_out && (ld_h < cols || ld_h % 8 != 0)) return fail(FP8_ERR_SHAPE, "%s: ld_h=%lld must be >= cols and a multiple of 8", fn, (long long)ld_h);
+        if (!aligned(scale_out, 4) || !aligned(mean_out, 4) || !aligned(rstd_out, 4))
+            return fail(FP8_ERR_ALIGN, "%s: scale_out, mean_out, rstd_out not 4-byte aligned", fn);
+    }
+    FP8_TRY(fp8k::launch_layernorm_quant_row(x, rows, cols, ld, gamma, beta, eps, format, flags & FP8_POW2_SCALE, h_out, ld_h,
+                                             q_out, ld_q, scale_out, mean_out, rstd_out, static_cast<hipStream_t>(stream)));
+    return FP8_OK;
+}
+
 int fp8_mx_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int format, uint8_t* q_out, int64_t ld_q,
                     uint8_t* e8m0_out, int64_t ld_e, void* stream) {
     g_err[0] = 0;

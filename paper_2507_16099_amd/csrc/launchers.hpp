@@ -77,6 +77,12 @@ bool gemm_bf16_at_b_snake_fits(int64_t lda, int64_t ldb, int64_t I, int64_t J, i
 hipError_t launch_gemm_bf16_at_b_snake(const void* a, int64_t lda, const void* b, int64_t ldb, int64_t I, int64_t J,
                                        int64_t C, void* out, int64_t ld_out, hipStream_t st);
 
+// layer normalisation over the rows with the rowwise fp8 quantization of its bfloat16 result fused in
+// (cols % 8 == 0, cols <= 16384, else hipErrorNotSupported; h, mean_out, rstd_out optional)
+hipError_t launch_layernorm_quant_row(const void* x, int64_t rows, int64_t cols, int64_t ld, const void* gamma,
+                                      const void* beta, double eps, int fmt, int flags, void* h, int64_t ld_h, uint8_t* q,
+                                      int64_t ld_q, float* scale_out, float* mean_out, float* rstd_out, hipStream_t st);
+
 // MX (microscaling) FP8: blocks of 32 along the contiguous axis, one E8M0 byte per block
 // (cols % 32 == 0), and the GEMM whose matrix-core instruction applies the block scales
 // (K % 128 == 0, ld_ea and ld_eb multiples of 4, 4-byte aligned scale pointers)

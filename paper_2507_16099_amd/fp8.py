@@ -84,6 +84,8 @@ def load_library() -> C.CDLL:
     L.fp8_linear_fwd_prequantized.restype = ci
     L.fp8_linear_fwd_prequantized.argtypes = [vp, i64, i64, ci, ci, ci, vp, i64, ci, vp, ci, i64, vp, i64, vp,
                                               C.c_size_t, vp]
+    L.fp8_layernorm_quantize.restype = ci
+    L.fp8_layernorm_quantize.argtypes = [vp, i64, i64, i64, vp, vp, C.c_double, ci, ci, vp, i64, vp, i64, vp, vp, vp, vp]
     L.fp8_mx_quantize.restype = ci
     L.fp8_mx_quantize.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp, i64, vp]
     L.fp8_mx_quantize_t.restype = ci
@@ -315,6 +317,28 @@ def fp8_grad_weight_hp(dy: torch.Tensor, x: torch.Tensor, dw: torch.Tensor | Non
     assert dw.is_contiguous() and tuple(dw.shape) == (N, K)
     _check(load_library().fp8_grad_weight_hp(_ptr(dy), _ptr(x), M, K, N, _ptr(dw), _stream()))
     return dw
+
+
+def fp8_layernorm_quantize(x: torch.Tensor, gamma: torch.Tensor, beta: torch.Tensor | None, eps: float,
+                           fmt: int = FP8_E4M3FN, flags: int = 0, want_h: bool = True, want_stats: bool = True, out=None):
+    """LayerNorm over the last axis with the rowwise fp8 quantization of its bfloat16 result fused in.
+    Returns (h or None, q, scale, mean or None, rstd or None); out: the same five to write into."""
+    rows, cols, ld = _mat(x, 2)
+    assert gamma.is_contiguous() and gamma.numel() == cols and gamma.element_size() == 2
+    assert beta is None or (beta.is_contiguous() and beta.numel() == cols and beta.element_size() == 2)
+    if out is None:
+        h = torch.empty((rows, cols), dtype=torch.bfloat16, device=x.device) if want_h else None
+        q = _alloc_q(rows, cols, 0, x.device)
+        s = torch.empty(rows, dtype=torch.float32, device=x.device)
+        mean = torch.empty(rows, dtype=torch.float32, device=x.device) if want_stats else None
+        rstd = torch.empty(rows, dtype=torch.float32, device=x.device) if want_stats else None
+    else:
+        h, q, s, mean, rstd = out
+    ld_h = _mat(h, 2)[2] if h is not None else 0
+    _check(load_library().fp8_layernorm_quantize(_ptr(x), rows, cols, ld, _ptr(gamma), _ptr(beta), float(eps), fmt, flags,
+                                                 _ptr(h), ld_h, _ptr(q), _mat(q, 1)[2], _ptr(s), _ptr(mean), _ptr(rstd),
+                                                 _stream()))
+    return h, q, s, mean, rstd
 
 
 def fp8_mx_quantize(x: torch.Tensor, fmt: int, q: torch.Tensor | None = None, e8m0: torch.Tensor | None = None):
