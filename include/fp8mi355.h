@@ -56,6 +56,7 @@ enum fp8_flags {
     FP8_TRANSPOSE_OUT = 2, /* fp8_cast / fp8_quantize write q[c, r] not q[r, c] */
     FP8_OUT_FP32      = 4, /* fp8_scaled_mm writes fp32 instead of bfloat16     */
     FP8_GRAD_WEIGHT_HP = 8, /* recipe flag: dW is computed in bfloat16, not FP8  */
+    FP8_EPILOGUE_SIGMOID = 32, /* fp8_scaled_mm: out = bfloat16(sigmoid(result)) instead of bfloat16(result) */
     FP8_SAVE_FOR_BWD  = 16 /* recipe flag: the forward leaves the transposed fp8 copies of X and W
                               in the workspace and the backward reuses them                    */
 };
@@ -143,6 +144,11 @@ int fp8_quantize_row_col(const void* x, int64_t rows, int64_t cols, int64_t ld, 
  *   sb likewise with n.  Accumulation is fp32; out is [M, N] bfloat16
  *   (round to nearest even) or fp32 with FP8_OUT_FP32, leading dimension
  *   ld_out.  K must be a multiple of 16; M and N are arbitrary.
+ *   FP8_EPILOGUE_SIGMOID (not with FP8_OUT_FP32; lda, ldb < 2^23): the logistic
+ *   function 1 / (1 + exp(-v)) is applied to the fp32 value v before the rounding
+ *   to bfloat16 - the activation behind the linear layer in the paper's float8
+ *   microbenchmark (appendix "Float8 Training Microbenchmarks"), fused into the
+ *   GEMM's epilogue.
  */
 int fp8_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int gran_a,
                   const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int gran_b,

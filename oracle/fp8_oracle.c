@@ -507,3 +507,13 @@ void orc_layernorm(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, co
     }
 }
 
+/*
+ * Logistic function of a dequantized GEMM result, the activation behind the linear
+ * layer in the same microbenchmark: y = 1 / (1 + exp(-v)) in binary64 on the fp32
+ * value v, rounded once to bfloat16.
+ */
+void orc_sigmoid_bf16(const float* v, int64_t n, uint16_t* out) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) out[i] = orc_f64_to_bf16(1.0 / (1.0 + exp(-(double)v[i])));
+}
+

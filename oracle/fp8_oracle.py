@@ -87,6 +87,8 @@ def lib() -> C.CDLL:
         L.orc_bf16_mm_f64.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i64, vp]
         L.orc_f64_to_bf16.restype = C.c_uint16
         L.orc_f64_to_bf16.argtypes = [C.c_double]
+        L.orc_sigmoid_bf16.restype = None
+        L.orc_sigmoid_bf16.argtypes = [vp, i64, vp]
         L.orc_layernorm.restype = None
         L.orc_layernorm.argtypes = [vp, i64, i64, i64, vp, vp, C.c_double, vp, i64, vp, vp]
         _lib = L
@@ -379,6 +381,14 @@ def linear_bwd_dw_hp(dy, x, rows=None):
 
 def f64_to_bf16(d: float) -> int:
     return int(lib().orc_f64_to_bf16(float(d)))
+
+
+def sigmoid_bf16(v: np.ndarray) -> np.ndarray:
+    """bfloat16 bits of 1 / (1 + exp(-v)) for fp32 v (binary64 evaluation, one rounding)."""
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    out = np.empty(v.shape, np.uint16)
+    lib().orc_sigmoid_bf16(_p(v), v.size, _p(out))
+    return out
 
 
 def layernorm(x: np.ndarray, gamma: np.ndarray, beta: np.ndarray | None, eps: float):

@@ -257,7 +257,9 @@ int fp8_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a
     if (!fmt_ok(fmt_a) || !fmt_ok(fmt_b)) return fail(FP8_ERR_ENUM, "fp8_scaled_mm: unknown format");
     if ((gran_a != FP8_TENSOR && gran_a != FP8_ROW) || (gran_b != FP8_TENSOR && gran_b != FP8_ROW))
         return fail(FP8_ERR_ENUM, "fp8_scaled_mm: granularity must be FP8_TENSOR or FP8_ROW");
-    if (flags & ~FP8_OUT_FP32) return fail(FP8_ERR_ENUM, "fp8_scaled_mm: flags=%d has unknown bits", flags);
+    if (flags & ~(FP8_OUT_FP32 | FP8_EPILOGUE_SIGMOID)) return fail(FP8_ERR_ENUM, "fp8_scaled_mm: flags=%d has unknown bits", flags);
+    if ((flags & FP8_EPILOGUE_SIGMOID) && (flags & FP8_OUT_FP32))
+        return fail(FP8_ERR_ENUM, "fp8_scaled_mm: the sigmoid epilogue writes bfloat16 (not with FP8_OUT_FP32)");
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim)
         return fail(FP8_ERR_SHAPE, "fp8_scaled_mm: M=%lld N=%lld K=%lld out of range", (long long)M, (long long)N, (long long)K);
     if (K % 16 != 0) return fail(FP8_ERR_SHAPE, "fp8_scaled_mm: K=%lld must be a multiple of 16", (long long)K);
@@ -271,6 +273,14 @@ int fp8_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a
         if (ld_out % out_align != 0)
             return fail(FP8_ERR_ALIGN, "fp8_scaled_mm: ld_out=%lld must be a multiple of %lld", (long long)ld_out, (long long)out_align);
         if (!aligned(scale_a, 4) || !aligned(scale_b, 4)) return fail(FP8_ERR_ALIGN, "fp8_scaled_mm: scales not 4-byte aligned");
+    }
+    if (flags & FP8_EPILOGUE_SIGMOID) {
+        // the fused activation lives in the LDS-DMA kernel's epilogue, which handles every shape
+        if (!fp8k::gemm_fp8_pipelined_supported(lda, ldb))
+            return fail(FP8_ERR_SHAPE, "fp8_scaled_mm: the sigmoid epilogue needs lda, ldb below 2^23");
+        FP8_TRY(fp8k::launch_gemm_fp8_snake(a, lda, fmt_a, scale_a, gran_a == FP8_ROW, b, ldb, fmt_b, scale_b, gran_b == FP8_ROW,
+                                            M, N, K, out, ld_out, 0, static_cast<hipStream_t>(stream), 1));
+        return FP8_OK;
     }
     FP8_TRY(fp8k::launch_gemm_fp8(a, lda, fmt_a, scale_a, gran_a == FP8_ROW, b, ldb, fmt_b, scale_b, gran_b == FP8_ROW,
                                   M, N, K, out, ld_out, (flags & FP8_OUT_FP32) ? 1 : 0, static_cast<hipStream_t>(stream)));

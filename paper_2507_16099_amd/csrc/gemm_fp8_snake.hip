@@ -81,7 +81,12 @@ __device__ __forceinline__ void sn_lds_dma16(v4i_s rsrc, uint32_t lds_addr, uint
 }
 __device__ __forceinline__ void sn_wait_all_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-template <int FA, int FB, bool OUT_F32>
+// logistic function of the dequantized result, for the fused activation epilogue (ACT)
+__device__ __forceinline__ float sn_sigmoid(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
+
+// ACT (bfloat16 output only): out = bfloat16(sigmoid(dequantized product)), the activation behind the
+// linear layer in the paper's float8 microbenchmark, applied to the fp32 value before it is rounded
+template <int FA, int FB, bool OUT_F32, bool ACT = false>
 __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
     const uint8_t* __restrict__ A, int64_t lda, const uint8_t* __restrict__ B, int64_t ldb,
     const float* __restrict__ scale_a, int row_a, const float* __restrict__ scale_b, int row_b, int M, int N,
@@ -316,8 +321,10 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const int e0 = 2 * e, e1 = 2 * e + 1;
-                    p[e] = sn_pack_bf16((acc[fi][grp * 4 + (e0 >> 2)][e0 & 3] * inv_a) * inv_b[grp][e0],
-                                        (acc[fi][grp * 4 + (e1 >> 2)][e1 & 3] * inv_a) * inv_b[grp][e1]);
+                    float u0 = (acc[fi][grp * 4 + (e0 >> 2)][e0 & 3] * inv_a) * inv_b[grp][e0];
+                    float u1 = (acc[fi][grp * 4 + (e1 >> 2)][e1 & 3] * inv_a) * inv_b[grp][e1];
+                    if constexpr (ACT) { u0 = sn_sigmoid(u0); u1 = sn_sigmoid(u1); }
+                    p[e] = sn_pack_bf16(u0, u1);
                 }
                 const int c = 8 * grp + 2 * g;
                 *reinterpret_cast<uint4*>(row + ((c ^ r16) << 4)) = make_uint4(p[0], p[1], p[2], p[3]);
@@ -348,12 +355,12 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
     }
 }
 
-template <int FA, int FB, bool OUT_F32>
+template <int FA, int FB, bool OUT_F32, bool ACT = false>
 static hipError_t launch_sn(const uint8_t* a, int64_t lda, const float* sa, int row_a, const uint8_t* b, int64_t ldb,
                             const float* sb, int row_b, int M, int N, int K, void* out, int64_t ld_out,
                             hipStream_t st) {
     using namespace sn;
-    auto kern = gemm_fp8_snake_kernel<FA, FB, OUT_F32>;
+    auto kern = gemm_fp8_snake_kernel<FA, FB, OUT_F32, ACT>;
     constexpr int lds = 2 * STAGE + 2048;   // two stages + the reciprocal-scale tables of the epilogue
     static bool attr_done = false;          // idempotent, a race is harmless
     if (!attr_done) {
@@ -374,9 +381,18 @@ static hipError_t launch_sn(const uint8_t* a, int64_t lda, const float* sa, int 
 hipError_t launch_gemm_fp8_snake(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
                                  const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int row_b,
                                  int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
-                                 hipStream_t st) {
+                                 hipStream_t st, int act) {
     if (M == 0 || N == 0) return hipSuccess;
+    if (act && out_f32) return hipErrorInvalidValue;
     const int m = (int)M, n = (int)N, k = (int)K;
+#define FP8K_SNA(FA_, FB_)                                                                                 \
+    if (act && fmt_a == FA_ && fmt_b == FB_)                                                               \
+        return launch_sn<FA_, FB_, false, true>(a, lda, scale_a, row_a, b, ldb, scale_b, row_b, m, n, k, out, ld_out, st)
+    FP8K_SNA(FMT_E4M3FN, FMT_E4M3FN);
+    FP8K_SNA(FMT_E5M2, FMT_E4M3FN);
+    FP8K_SNA(FMT_E4M3FN, FMT_E5M2);
+    FP8K_SNA(FMT_E5M2, FMT_E5M2);
+#undef FP8K_SNA
 #define FP8K_SN(FA_, FB_)                                                                                  \
     if (fmt_a == FA_ && fmt_b == FB_)                                                                      \
         return out_f32 ? launch_sn<FA_, FB_, true>(a, lda, scale_a, row_a, b, ldb, scale_b, row_b, m, n, k, out, ld_out, st) \

@@ -51,10 +51,11 @@ hipError_t launch_gemm_fp8_pipelined(const uint8_t* a, int64_t lda, int fmt_a, c
                                      hipStream_t st);
 
 // 256 x 256 kernel on 16x16x128 MFMAs with the four-phase "snake" schedule; same contract.
+// act != 0 (bfloat16 output only): the logistic function applied to the fp32 result before rounding
 hipError_t launch_gemm_fp8_snake(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
                                  const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int row_b,
                                  int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
-                                 hipStream_t st);
+                                 hipStream_t st, int act = 0);
 
 // few rows of A (M <= 64, the decode shape of inference): B is streamed once
 // from HBM by wavefronts that load their MFMA operands straight from global

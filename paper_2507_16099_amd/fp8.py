@@ -17,6 +17,7 @@ import torch
 FP8_E4M3FN, FP8_E5M2 = 0, 1
 FP8_TENSOR, FP8_ROW, FP8_COL = 0, 1, 2
 FP8_POW2_SCALE, FP8_TRANSPOSE_OUT, FP8_OUT_FP32, FP8_GRAD_WEIGHT_HP, FP8_SAVE_FOR_BWD = 1, 2, 4, 8, 16
+FP8_EPILOGUE_SIGMOID = 32
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfp8mi355.so")

@@ -38,7 +38,7 @@ def test_binding_has_the_same_names():
 def test_enum_values_match_header():
     src = open(HEADER).read()
     for name in ("FP8_E4M3FN", "FP8_E5M2", "FP8_TENSOR", "FP8_ROW", "FP8_COL", "FP8_POW2_SCALE",
-                 "FP8_TRANSPOSE_OUT", "FP8_OUT_FP32", "FP8_GRAD_WEIGHT_HP", "FP8_SAVE_FOR_BWD"):
+                 "FP8_TRANSPOSE_OUT", "FP8_OUT_FP32", "FP8_GRAD_WEIGHT_HP", "FP8_SAVE_FOR_BWD", "FP8_EPILOGUE_SIGMOID"):
         m = re.search(name + r"\s*=\s*(-?\d+)", src)
         assert m and int(m.group(1)) == getattr(fp8, name), name
 

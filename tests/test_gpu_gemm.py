@@ -177,6 +177,26 @@ def test_few_rows_random_codes_within_tolerance(few_rows_form, M, N, K, ga, gb):
     assert orc.rel_frobenius(got32, want.acc64) <= TOL
 
 
+@pytest.mark.parametrize("M,N,K", [(16, 16, 128), (200, 300, 400), (257, 129, 144), (1024, 768, 512), (4500, 4400, 400)])
+def test_sigmoid_epilogue(M, N, K):
+    """FP8_EPILOGUE_SIGMOID: bfloat16(sigmoid(dequantized product)); a floating-point
+    output, compared with the oracle's binary64 sigmoid of its fp32 product."""
+    rng = np.random.default_rng(M + N + K)
+    a, b = _rand_codes((M, K), orc.E4M3FN, rng, 6), _rand_codes((N, K), orc.E4M3FN, rng, 6)
+    sa = rng.uniform(2.0, 8.0, M).astype(np.float32)
+    sb = rng.uniform(2.0, 8.0, N).astype(np.float32)
+    want = orc.scaled_mm(a, orc.E4M3FN, sa, orc.ROW, b, orc.E4M3FN, sb, orc.ROW)
+    assert np.abs(want.out32).max() > 2.0 and np.abs(want.out32).std() > 0.3      # the curved part of the function is in play
+    y = _run(a, orc.E4M3FN, sa, fp8.FP8_ROW, b, orc.E4M3FN, sb, fp8.FP8_ROW, fp8.FP8_EPILOGUE_SIGMOID)
+    got = si.bf16_bits_to_f32(host_bf16_bits(y))
+    ref = si.bf16_bits_to_f32(orc.sigmoid_bf16(want.out32))
+    assert orc.rel_frobenius(got, ref) <= TOL
+    assert np.abs(got - ref).max() <= 2.0 ** -7                   # at most two bfloat16 steps of a value near 1
+    assert float((got == ref).mean()) > 0.9
+    with pytest.raises(fp8.Fp8Error):
+        _run(a, orc.E4M3FN, sa, fp8.FP8_ROW, b, orc.E4M3FN, sb, fp8.FP8_ROW, fp8.FP8_EPILOGUE_SIGMOID | fp8.FP8_OUT_FP32)
+
+
 def test_padded_leading_dimensions_and_output_view(variant):
     rng = np.random.default_rng(3)
     M, N, K = 70, 90, 160

@@ -113,3 +113,18 @@ def test_statistics_of_the_output_and_quantization():
     wq, ws = orc.quantize(h, orc.ROW, orc.E4M3FN)
     assert (h2 == h).all() and (q == wq).all() and (s.view(np.uint32) == ws.view(np.uint32)).all()
     assert (np.abs(_f(h)).max(axis=1) * s <= 448.0 * (1 + 2 ** -23)).all()
+
+
+def test_sigmoid_closed_forms_and_symmetry():
+    # sigmoid(ln 3) = 3/4, sigmoid(ln 7) = 7/8, sigmoid(-ln 3) = 1/4, sigmoid(0) = 1/2: all bfloat16 numbers
+    v = np.array([0.0, math.log(3.0), math.log(7.0), -math.log(3.0), 40.0, -200.0], np.float32)
+    y = orc.sigmoid_bf16(v)
+    assert list(y[:4]) == [0x3F00, 0x3F40, 0x3F60, 0x3E80]
+    assert y[4] == 0x3F80 and y[5] == 0x0000                      # saturates to 1 and underflows to 0
+    rng = np.random.default_rng(2)
+    z = (rng.standard_normal(4096) * 3).astype(np.float32)
+    a, b = _f(orc.sigmoid_bf16(z)).astype(np.float64), _f(orc.sigmoid_bf16(-z)).astype(np.float64)
+    assert np.abs(a + b - 1.0).max() <= 2.0 ** -8                 # sigmoid(-v) = 1 - sigmoid(v), up to the two roundings
+    zs = np.sort(z)
+    assert (np.diff(_f(orc.sigmoid_bf16(zs))) >= 0).all()         # monotone
+    assert ((a > 0) & (a <= 1)).all()
