@@ -101,6 +101,71 @@ def _sweep(torch, fp8, dev, iters: int) -> dict:
             "iters": iters, "rows": rows}
 
 
+def _block(torch, fp8, dev, iters: int) -> dict:
+    """The paper's microbenchmark block (appendix "Float8 Training Microbenchmarks"):
+    LayerNorm -> Linear -> Sigmoid, forward and backward, float8 (rowwise) against
+    bfloat16.  Three variants of the same computation:
+      bf16:       framework LayerNorm, vendor-BLAS matmuls, framework sigmoid;
+      fp8:        the same framework ops around fp8_linear_fwd / fp8_linear_bwd;
+      fp8_fused:  the forward's casts fused by hand where the paper relies on the compiler:
+                  fp8_layernorm_quantize (normalisation + cast of the activations) and the
+                  sigmoid inside the GEMM's epilogue; backward as in `fp8`.
+    The backward of the normalisation and of the sigmoid are framework ops in all three."""
+    E4, ROW = fp8.FP8_E4M3FN, fp8.FP8_ROW
+    F = torch.nn.functional
+    rows = []
+    shapes = [(M, K, N) for M in (4096, 16384) for K in (2048, 4096, 8192) for N in (2048, 4096, 8192)]
+    shapes.append((16384, 4096, 14336))
+    r = fp8.Recipe(gran=ROW)
+    for M, K, N in shapes:
+        x = torch.randn((M, K), device=dev).to(torch.bfloat16)
+        w = (torch.randn((N, K), device=dev) * 0.02).to(torch.bfloat16)
+        g = (torch.rand(K, device=dev) + 0.5).to(torch.bfloat16)
+        b = (torch.rand(K, device=dev) - 0.5).to(torch.bfloat16)
+        dy = (torch.randn((M, N), device=dev) * 1e-3).to(torch.bfloat16)
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        dh = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+        dw = torch.empty((N, K), dtype=torch.bfloat16, device=dev)
+        wf = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, False), dtype=torch.uint8, device=dev)
+        wb = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, True), dtype=torch.uint8, device=dev)
+        lnq = fp8.fp8_layernorm_quantize(x, g, b, 1e-5, E4)
+        wq = fp8.fp8_quantize(w, ROW, E4)
+
+        def ln_sig_bwd(h, mean, rstd, yy, linear_bwd):
+            dz = dy * yy * (1 - yy)
+            linear_bwd(dz, h)
+            torch.ops.aten.native_layer_norm_backward(dh, x, [K], mean, rstd, g, b, [True, True, True])
+
+        def bf16_step():
+            h, mean, rstd = torch.native_layer_norm(x, [K], g, b, 1e-5)
+            yy = torch.sigmoid(torch.matmul(h, w.t()))
+
+            def lb(dz, hh):
+                torch.matmul(dz, w, out=dh)
+                torch.matmul(dz.t(), hh, out=dw)
+            ln_sig_bwd(h, mean, rstd, yy, lb)
+
+        def fp8_step():
+            h, mean, rstd = torch.native_layer_norm(x, [K], g, b, 1e-5)
+            fp8.fp8_linear_fwd(h, w, r, y=y, workspace=wf)
+            yy = torch.sigmoid(y)
+            ln_sig_bwd(h, mean, rstd, yy, lambda dz, hh: fp8.fp8_linear_bwd(dz, hh, w, r, dx=dh, dw=dw, workspace=wb))
+
+        def fused_step():
+            h, hq, sh, mean, rstd = fp8.fp8_layernorm_quantize(x, g, b, 1e-5, E4, out=lnq)
+            fp8.fp8_quantize(w, ROW, E4, out=wq[0], scale_out=wq[1])
+            fp8.fp8_scaled_mm(hq, E4, sh, ROW, wq[0], E4, wq[1], ROW, fp8.FP8_EPILOGUE_SIGMOID, out=y)
+            ln_sig_bwd(h, mean.view(M, 1), rstd.view(M, 1), y, lambda dz, hh: fp8.fp8_linear_bwd(dz, hh, w, r, dx=dh, dw=dw, workspace=wb))
+
+        t_bf, t_f8, t_fu = (_event_time_ms(f, iters, 2, torch) for f in (bf16_step, fp8_step, fused_step))
+        rows.append({"M": M, "K": K, "N": N, "bf16_ms": round(t_bf, 4), "fp8_ms": round(t_f8, 4), "fp8_fused_fwd_ms": round(t_fu, 4),
+                     "speedup_fp8": round(t_bf / t_f8, 3), "speedup_fp8_fused_fwd": round(t_bf / t_fu, 3)})
+        del x, w, dy, y, dh, dw, wf, wb, lnq, wq
+        torch.cuda.empty_cache()
+    return {"block": "LayerNorm + Linear + Sigmoid forward and backward, float8 rowwise vs bfloat16, one MI355X",
+            "iters": iters, "rows": rows}
+
+
 def _data_probe(torch, fp8, dev, iters: int) -> dict:
     """How much of the forward GEMM's rate depends on the operand DATA: the same
     kernel and launch on the benchmark shape with operands that do not toggle
@@ -192,6 +257,8 @@ def main() -> int:
     ap.add_argument("--decode", action="store_true",
                     help="inference with pre-quantized weights at decode batch sizes (weight-streaming GEMM); "
                          "prints a JSON table and exits")
+    ap.add_argument("--block", action="store_true",
+                    help="LayerNorm + Linear + Sigmoid forward and backward, float8 vs bfloat16 over shapes, then exit")
     ap.add_argument("--data-probe", action="store_true",
                     help="time the forward GEMM with operands that do not toggle and with realistic ones, then exit")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -223,6 +290,10 @@ def main() -> int:
 
     if args.decode:
         print(json.dumps(_decode(torch, fp8, dev, max(10, args.steps))))
+        return 0
+
+    if args.block:
+        print(json.dumps(_block(torch, fp8, dev, max(5, args.steps // 2))))
         return 0
 
     if args.data_probe:
