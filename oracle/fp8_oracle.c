@@ -517,3 +517,22 @@ void orc_sigmoid_bf16(const float* v, int64_t n, uint16_t* out) {
     for (int64_t i = 0; i < n; ++i) out[i] = orc_f64_to_bf16(1.0 / (1.0 + exp(-(double)v[i])));
 }
 
+/*
+ * Gradient through the sigmoid behind the linear layer (same microbenchmark block):
+ * with y = sigmoid(z) stored in bfloat16 and the incoming gradient dy in bfloat16,
+ *   dz = dy * y * (1 - y),
+ * evaluated in binary32, one operation at a time, left to right: t1 = dy * y (exact:
+ * two 8-bit significands), t2 = 1 - y, dz = t1 * t2, then rounded to bfloat16 - the
+ * tensor that the backward of the linear layer quantizes.
+ */
+void orc_sigmoid_bwd(const uint16_t* dy, const uint16_t* y, int64_t n, uint16_t* dz) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        const float g = orc_bf16_to_f32(dy[i]), s = orc_bf16_to_f32(y[i]);
+        volatile float t1 = g * s;
+        volatile float t2 = 1.0f - s;
+        volatile float t = t1 * t2;
+        dz[i] = orc_f32_to_bf16(t);
+    }
+}
+

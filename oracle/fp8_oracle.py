@@ -87,6 +87,8 @@ def lib() -> C.CDLL:
         L.orc_bf16_mm_f64.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i64, vp]
         L.orc_f64_to_bf16.restype = C.c_uint16
         L.orc_f64_to_bf16.argtypes = [C.c_double]
+        L.orc_sigmoid_bwd.restype = None
+        L.orc_sigmoid_bwd.argtypes = [vp, vp, i64, vp]
         L.orc_sigmoid_bf16.restype = None
         L.orc_sigmoid_bf16.argtypes = [vp, i64, vp]
         L.orc_layernorm.restype = None
@@ -389,6 +391,16 @@ def sigmoid_bf16(v: np.ndarray) -> np.ndarray:
     out = np.empty(v.shape, np.uint16)
     lib().orc_sigmoid_bf16(_p(v), v.size, _p(out))
     return out
+
+
+def sigmoid_bwd(dy: np.ndarray, y: np.ndarray) -> np.ndarray:
+    """bfloat16 bits of dz = dy * y * (1 - y) (binary32, one operation at a time), same shape as dy."""
+    dy = np.ascontiguousarray(dy, dtype=np.uint16)
+    y = np.ascontiguousarray(y, dtype=np.uint16)
+    assert dy.shape == y.shape
+    dz = np.empty(dy.shape, np.uint16)
+    lib().orc_sigmoid_bwd(_p(dy), _p(y), dy.size, _p(dz))
+    return dz
 
 
 def layernorm(x: np.ndarray, gamma: np.ndarray, beta: np.ndarray | None, eps: float):

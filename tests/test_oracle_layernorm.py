@@ -128,3 +128,31 @@ def test_sigmoid_closed_forms_and_symmetry():
     zs = np.sort(z)
     assert (np.diff(_f(orc.sigmoid_bf16(zs))) >= 0).all()         # monotone
     assert ((a > 0) & (a <= 1)).all()
+
+
+def test_sigmoid_bwd_closed_forms():
+    # y = 1/2: dz = dy / 4 exactly; y = 3/4: dz = 3 dy / 16 exactly; y in {0, 1}: 0
+    dy = _bf16([1.0, -2.0, 3.0, 1.0, 5.0, -7.0, 1.0])
+    y = _bf16([0.5, 0.5, 0.75, 0.25, 0.0, 1.0, 0.875])
+    dz = _f(orc.sigmoid_bwd(dy, y))
+    assert list(dz) == [0.25, -0.5, 0.5625, 0.1875, 0.0, -0.0, 0.109375]
+    # symmetric in y <-> 1 - y wherever 1 - y is a bfloat16 number, odd in dy
+    ys = _bf16(np.arange(1, 128) / 128.0)
+    g = _bf16(np.full(127, 1.5))
+    a, b = orc.sigmoid_bwd(g, ys), orc.sigmoid_bwd(g, _bf16(1.0 - _f(ys)))
+    assert (a == b).all()
+    assert (_f(orc.sigmoid_bwd(_bf16(-_f(g)), ys)) == -_f(a)).all()
+    # the result is the bfloat16 nearest to the exact product (the binary32 steps lose nothing that matters
+    # for numbers of this size): compare with exact rational arithmetic
+    from fractions import Fraction
+    rng = np.random.default_rng(5)
+    gy = _bf16(rng.standard_normal(300))
+    yy = _bf16(rng.uniform(0.01, 0.99, 300))
+    got = orc.sigmoid_bwd(gy, yy)
+    for i in range(300):
+        exact = Fraction(float(_f(gy[i:i+1])[0])) * Fraction(float(_f(yy[i:i+1])[0])) * (1 - Fraction(float(_f(yy[i:i+1])[0])))
+        lo, hi = sorted((float(_f(got[i:i+1])[0]), float(exact)))
+        # within half a bfloat16 step (2^-9 relative) plus the binary32 rounding of the last product
+        assert abs(Fraction(float(_f(got[i:i+1])[0])) - exact) <= abs(exact) * Fraction(1, 2 ** 8)
+    # peak of y (1 - y) at y = 1/2
+    assert _f(orc.sigmoid_bwd(_bf16([1.0] * 3), _bf16([0.4375, 0.5, 0.5625]))).argmax() == 1
