@@ -109,8 +109,10 @@ def _block(torch, fp8, dev, iters: int) -> dict:
       fp8:        the same framework ops around fp8_linear_fwd / fp8_linear_bwd;
       fp8_fused:  the forward's casts fused by hand where the paper relies on the compiler:
                   fp8_layernorm_quantize (normalisation + cast of the activations) and the
-                  sigmoid inside the GEMM's epilogue; backward as in `fp8`.
-    The backward of the normalisation and of the sigmoid are framework ops in all three."""
+                  sigmoid inside the GEMM's epilogue; backward as in `fp8`;
+      fp8_fused_fwd_bwd: additionally the gradient through the sigmoid formed inside the
+                  backward's quantization passes (fp8_linear_bwd_sigmoid).
+    The backward of the normalisation is a framework op in all four."""
     E4, ROW = fp8.FP8_E4M3FN, fp8.FP8_ROW
     F = torch.nn.functional
     rows = []
@@ -127,7 +129,7 @@ def _block(torch, fp8, dev, iters: int) -> dict:
         dh = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
         dw = torch.empty((N, K), dtype=torch.bfloat16, device=dev)
         wf = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, False), dtype=torch.uint8, device=dev)
-        wb = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, True), dtype=torch.uint8, device=dev)
+        wb = torch.empty(fp8.fp8_linear_bwd_sigmoid_workspace_bytes(M, K, N, r), dtype=torch.uint8, device=dev)
         lnq = fp8.fp8_layernorm_quantize(x, g, b, 1e-5, E4)
         wq = fp8.fp8_quantize(w, ROW, E4)
 
@@ -157,9 +159,17 @@ def _block(torch, fp8, dev, iters: int) -> dict:
             fp8.fp8_scaled_mm(hq, E4, sh, ROW, wq[0], E4, wq[1], ROW, fp8.FP8_EPILOGUE_SIGMOID, out=y)
             ln_sig_bwd(h, mean.view(M, 1), rstd.view(M, 1), y, lambda dz, hh: fp8.fp8_linear_bwd(dz, hh, w, r, dx=dh, dw=dw, workspace=wb))
 
-        t_bf, t_f8, t_fu = (_event_time_ms(f, iters, 2, torch) for f in (bf16_step, fp8_step, fused_step))
+        def fused_fwd_bwd_step():
+            h, hq, sh, mean, rstd = fp8.fp8_layernorm_quantize(x, g, b, 1e-5, E4, out=lnq)
+            fp8.fp8_quantize(w, ROW, E4, out=wq[0], scale_out=wq[1])
+            fp8.fp8_scaled_mm(hq, E4, sh, ROW, wq[0], E4, wq[1], ROW, fp8.FP8_EPILOGUE_SIGMOID, out=y)
+            fp8.fp8_linear_bwd_sigmoid(dy, y, h, w, r, dx=dh, dw=dw, workspace=wb)
+            torch.ops.aten.native_layer_norm_backward(dh, x, [K], mean.view(M, 1), rstd.view(M, 1), g, b, [True, True, True])
+
+        t_bf, t_f8, t_fu, t_fb = (_event_time_ms(f, iters, 2, torch) for f in (bf16_step, fp8_step, fused_step, fused_fwd_bwd_step))
         rows.append({"M": M, "K": K, "N": N, "bf16_ms": round(t_bf, 4), "fp8_ms": round(t_f8, 4), "fp8_fused_fwd_ms": round(t_fu, 4),
-                     "speedup_fp8": round(t_bf / t_f8, 3), "speedup_fp8_fused_fwd": round(t_bf / t_fu, 3)})
+                     "fp8_fused_fwd_bwd_ms": round(t_fb, 4), "speedup_fp8": round(t_bf / t_f8, 3),
+                     "speedup_fp8_fused_fwd": round(t_bf / t_fu, 3), "speedup_fp8_fused_fwd_bwd": round(t_bf / t_fb, 3)})
         del x, w, dy, y, dh, dw, wf, wb, lnq, wq
         torch.cuda.empty_cache()
     return {"block": "LayerNorm + Linear + Sigmoid forward and backward, float8 rowwise vs bfloat16, one MI355X",

@@ -206,6 +206,22 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
                    size_t workspace_bytes, void* stream);
 
 /*
+ * backward through Sigmoid + Linear (the block of the paper's float8 microbenchmark,
+ * appendix "Float8 Training Microbenchmarks"): y [M, N] bfloat16 is the stored sigmoid
+ * output, dy [M, N] the gradient arriving at it.  The gradient of the linear layer's
+ * output,  dz = dy * y * (1 - y)  (binary32, one operation at a time, rounded to
+ * bfloat16), takes the place of dY in fp8_linear_bwd; with the rowwise recipe and
+ * M >= 1024, N a multiple of 8 in [512, 32768] it is formed inside the two
+ * quantization passes and never stored, otherwise it is written once into the
+ * workspace.  Everything else as fp8_linear_bwd (including FP8_SAVE_FOR_BWD, where
+ * the shared workspace must then have fp8_linear_bwd_sigmoid_workspace_bytes bytes).
+ */
+size_t fp8_linear_bwd_sigmoid_workspace_bytes(int64_t M, int64_t K, int64_t N, const fp8_recipe* recipe);
+int fp8_linear_bwd_sigmoid(const void* dy, const void* y, const void* x, const void* w, int64_t M, int64_t K,
+                           int64_t N, const fp8_recipe* recipe, void* dx, void* dw, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
+/*
  * weight gradient in high precision (Appendix A, rowwise_gw_hp: the grad_weight
  * GEMM kept in bfloat16):  dw[n, k] = sum_m dy[m, n] * x[m, k]
  *   dy [M, N] and x [M, K] bfloat16, dense rows; products and sums in fp32 on

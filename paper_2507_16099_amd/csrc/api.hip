@@ -432,6 +432,70 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
     return FP8_OK;
 }
 
+namespace {
+// shapes and recipes for which the gradient through the sigmoid is quantized without being materialised
+bool sigmoid_bwd_fused(int64_t M, int64_t N, const fp8_recipe* r) {
+    return r->gran == FP8_ROW && !(r->flags & FP8_GRAD_WEIGHT_HP) && N % 8 == 0 && N / 8 >= 64 && N / 8 <= 4096 && M >= 1024;
+}
+}  // namespace
+
+size_t fp8_linear_bwd_sigmoid_workspace_bytes(int64_t M, int64_t K, int64_t N, const fp8_recipe* recipe) {
+    const size_t base = fp8_linear_workspace_bytes(M, K, N, recipe, 1);
+    if (base == 0) return 0;
+    return sigmoid_bwd_fused(M, N, recipe) ? base : align_up(base, 256) + align_up((size_t)M * (size_t)N * 2, 256);
+}
+
+int fp8_linear_bwd_sigmoid(const void* dy, const void* y, const void* x, const void* w, int64_t M, int64_t K, int64_t N,
+                           const fp8_recipe* recipe, void* dx, void* dw, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+    g_err[0] = 0;
+    const char* fn = "fp8_linear_bwd_sigmoid";
+    if (int rc = check_recipe(fn, recipe)) return rc;
+    if (int rc = check_linear_dims(fn, M, K, N, true)) return rc;
+    if (int rc = check_bf16("fp8_linear_bwd_sigmoid(dy)", dy, M, N, N)) return rc;
+    if (int rc = check_bf16("fp8_linear_bwd_sigmoid(y)", y, M, N, N)) return rc;
+    if (M == 0 || N == 0 || K == 0 || (!dx && !dw)) return FP8_OK;
+    if (!workspace) return fail(FP8_ERR_NULL, "%s: workspace is NULL", fn);
+    if (!aligned(workspace, 256)) return fail(FP8_ERR_ALIGN, "%s: workspace not 256-byte aligned", fn);
+    const size_t need = fp8_linear_bwd_sigmoid_workspace_bytes(M, K, N, recipe);
+    if (need == 0) return FP8_ERR_SHAPE;
+    if (workspace_bytes < need) return fail(FP8_ERR_WORKSPACE, "%s: workspace %zu < %zu bytes", fn, workspace_bytes, need);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    const size_t base = fp8_linear_workspace_bytes(M, K, N, recipe, 1);
+    if (!sigmoid_bwd_fused(M, N, recipe)) {
+        // small or unusual shapes, other recipes: dz = dy * y * (1 - y) is written out once and the ordinary
+        // backward runs on it
+        uint8_t* dz = ws + align_up(base, 256);
+        FP8_TRY(fp8k::launch_sigmoid_bwd(dy, y, M * N, dz, st));
+        return fp8_linear_bwd(dz, x, w, M, K, N, recipe, dx, dw, workspace, base, stream);
+    }
+    // rowwise: dz is formed inside the two quantization passes (never stored), then the usual products
+    const bool saved = (recipe->flags & FP8_SAVE_FOR_BWD) != 0;
+    if (dw && !saved) if (int rc = check_bf16("fp8_linear_bwd_sigmoid(x)", x, M, K, K)) return rc;
+    if (dx && !saved) if (int rc = check_bf16("fp8_linear_bwd_sigmoid(w)", w, N, K, K)) return rc;
+    if (!aligned(dx, 16) || !aligned(dw, 16)) return fail(FP8_ERR_ALIGN, "%s: dx, dw not 16-byte aligned", fn);
+    if ((K + 127) / 128 > 65535 || (N + 127) / 128 > 65535) return fail(FP8_ERR_SHAPE, "%s: K or N too large", fn);
+    const BwdPlan p = plan_bwd(M, K, N, recipe->gran);
+    uint8_t *gq = ws + p.gq, *gqt = ws + p.gqt, *wt = ws + p.wt, *xt = ws + p.xt;
+    float *sg = reinterpret_cast<float*>(ws + p.sg), *sgt = reinterpret_cast<float*>(ws + p.sgt);
+    float *swt = reinterpret_cast<float*>(ws + p.swt), *sxt = reinterpret_cast<float*>(ws + p.sxt);
+    const int fl = recipe->flags & FP8_POW2_SCALE;
+    const int T = FP8_TRANSPOSE_OUT;
+    hipError_t e = fp8k::launch_quant_row_col_sigmoid_bwd(dy, y, M, N, N, recipe->fmt_dy, fl, gq, N, sg, gqt, M, sgt, st);
+    if (e == hipErrorNotSupported) return fail(FP8_ERR_SHAPE, "%s: shape not supported by the fused gradient quantization", fn);
+    if (e != hipSuccess) return hip_fail(e, "quant_row_col_sigmoid_bwd");
+    if (dx && !saved)
+        if (int rc = quantize_impl(w, N, K, K, FP8_COL, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st)) return rc;
+    if (dw && !saved)
+        if (int rc = quantize_impl(x, M, K, K, FP8_COL, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st)) return rc;
+    if (dx)
+        FP8_TRY(fp8k::launch_gemm_fp8(gq, N, recipe->fmt_dy, sg, 1, wt, N, recipe->fmt_w, swt, 1, M, K, N, dx, K, 0, st));
+    if (dw)
+        FP8_TRY(fp8k::launch_gemm_fp8(gqt, M, recipe->fmt_dy, sgt, 1, xt, M, recipe->fmt_x, sxt, 1, N, K, M, dw, K, 0, st));
+    return FP8_OK;
+}
+
 int fp8_grad_weight_hp(const void* dy, const void* x, int64_t M, int64_t K, int64_t N, void* dw, void* stream) {
     g_err[0] = 0;
     const char* fn = "fp8_grad_weight_hp";

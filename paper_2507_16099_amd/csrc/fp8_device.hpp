@@ -136,4 +136,18 @@ __device__ __forceinline__ uint2 cast8(const uint4& v, float s) {
     return r;
 }
 
+// Gradient through a sigmoid whose output y is stored in bfloat16: dz = dy * y * (1 - y), evaluated in
+// binary32 one operation at a time, left to right (no contraction), rounded to bfloat16; 8 elements.
+__device__ __forceinline__ uint32_t sigmoid_bwd_bf16_bits(float g, float y) {
+    const float t = __fmul_rn(__fmul_rn(g, y), __fsub_rn(1.0f, y));
+    const uint32_t b = __float_as_uint(t);
+    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;      // finite inputs: round to nearest even
+}
+__device__ __forceinline__ uint32_t sigmoid_bwd_pair(uint32_t g2, uint32_t y2) {
+    return sigmoid_bwd_bf16_bits(bf16_lo(g2), bf16_lo(y2)) | (sigmoid_bwd_bf16_bits(bf16_hi(g2), bf16_hi(y2)) << 16);
+}
+__device__ __forceinline__ uint4 sigmoid_bwd8(const uint4& g, const uint4& y) {
+    return make_uint4(sigmoid_bwd_pair(g.x, y.x), sigmoid_bwd_pair(g.y, y.y), sigmoid_bwd_pair(g.z, y.z), sigmoid_bwd_pair(g.w, y.w));
+}
+
 }  // namespace fp8k

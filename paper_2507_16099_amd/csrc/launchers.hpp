@@ -78,6 +78,13 @@ bool gemm_bf16_at_b_snake_fits(int64_t lda, int64_t ldb, int64_t I, int64_t J, i
 hipError_t launch_gemm_bf16_at_b_snake(const void* a, int64_t lda, const void* b, int64_t ldb, int64_t I, int64_t J,
                                        int64_t C, void* out, int64_t ld_out, hipStream_t st);
 
+// gradient through a stored sigmoid output, dz = dy * y * (1 - y): quantized along both axes without being
+// materialised (hipErrorNotSupported for shapes the fused kernels do not take), or materialised (dense bf16)
+hipError_t launch_quant_row_col_sigmoid_bwd(const void* dy, const void* y, int64_t rows, int64_t cols, int64_t ld,
+                                            int fmt, int flags, uint8_t* q_row, int64_t ld_row, float* scale_row,
+                                            uint8_t* q_col_t, int64_t ld_col_t, float* scale_col, hipStream_t st);
+hipError_t launch_sigmoid_bwd(const void* dy, const void* y, int64_t n, void* dz, hipStream_t st);
+
 // layer normalisation over the rows with the rowwise fp8 quantization of its bfloat16 result fused in
 // (cols % 8 == 0, cols <= 16384, else hipErrorNotSupported; h, mean_out, rstd_out optional)
 hipError_t launch_layernorm_quant_row(const void* x, int64_t rows, int64_t cols, int64_t ld, const void* gamma,

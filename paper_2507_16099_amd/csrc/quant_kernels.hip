@@ -410,13 +410,15 @@ __device__ __forceinline__ void transpose4x4_bytes(uint32_t a, uint32_t b, uint3
 // tensorwise recipe needs both layouts of the same tensor in the backward).
 // LDS tile: 128 output rows x TR bytes; the 8-byte slot index is XORed with
 // 2 * ((row / 8) & 7) so that a wavefront's column pieces spread over banks.
-template <int FMT, int GRAN, int TR>
+// ACT: the tensor to cast is x * y * (1 - y) (gradient through a stored sigmoid output y of the same shape and
+// leading dimension, cols a multiple of 8), formed on the fly.
+template <int FMT, int GRAN, int TR, bool ACT = false>
 __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __restrict__ x, int64_t rows,
                                                               int64_t cols, int64_t ld,
                                                               const float* __restrict__ scale,
                                                               uint8_t* __restrict__ qt, int64_t ld_t,
                                                               uint8_t* __restrict__ q_plain, int64_t ld_plain,
-                                                              int nx, int ny) {
+                                                              int nx, int ny, const uint16_t* __restrict__ yact = nullptr) {
     constexpr int SLOTS = TR / 8;   // 8-byte slots per output row
     constexpr int PARTS = TR / 16;  // 16-byte parts per output row
     __shared__ __attribute__((aligned(16))) uint2 tile[128 * SLOTS];
@@ -451,6 +453,7 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
                 const uint16_t* src = x + r * ld + c;
                 if (c + 8 <= cols) {
                     v = load_stream(src);
+                    if constexpr (ACT) v = sigmoid_bwd8(v, load_stream(yact + r * ld + c));
                 } else if (c < cols) {
                     uint32_t t[4] = {0, 0, 0, 0};
                     for (int e = 0; c + e < cols; ++e) t[e >> 1] |= (uint32_t)src[e] << ((e & 1) * 16);
@@ -652,12 +655,16 @@ hipError_t launch_quant_row(const void* x, int64_t rows, int64_t cols, int64_t l
 // loads in flight (a second row in registers would halve the occupancy).  The
 // per-row wave maxima alternate between two LDS slots, so one barrier per row
 // is enough.
-template <int FMT, int NV>
+// ACT: the tensor to quantize is dz = x * y * (1 - y), formed on the fly from the gradient x and the stored
+// sigmoid output y (same shape and leading dimension): the backward through Sigmoid + Linear never
+// materialises dz.
+template <int FMT, int NV, bool ACT = false>
 __global__ __launch_bounds__(256) void quant_row_colmax_kernel(const uint16_t* __restrict__ x, int64_t rows,
                                                                 int64_t cols, int64_t ld, int flags,
                                                                 uint8_t* __restrict__ q, int64_t ld_out,
                                                                 float* __restrict__ scale_out,
-                                                                uint16_t* __restrict__ part, int64_t ld_part) {
+                                                                uint16_t* __restrict__ part, int64_t ld_part,
+                                                                const uint16_t* __restrict__ yact = nullptr) {
     constexpr bool PREFETCH = NV <= 4;
     const int64_t nvec = cols >> 3;     // cols is a multiple of 8 (checked by the launcher)
     const int tid = threadIdx.x;
@@ -671,6 +678,14 @@ __global__ __launch_bounds__(256) void quant_row_colmax_kernel(const uint16_t* _
         for (int j = 0; j < NV; ++j) {
             const int64_t vi = tid + (int64_t)j * 256;
             dst[j] = vi < nvec ? rv[vi] : make_uint4(0, 0, 0, 0);
+        }
+        if constexpr (ACT) {
+            const uint4* yv = reinterpret_cast<const uint4*>(yact + r * ld);
+#pragma unroll
+            for (int j = 0; j < NV; ++j) {
+                const int64_t vi = tid + (int64_t)j * 256;
+                if (vi < nvec) dst[j] = sigmoid_bwd8(dst[j], yv[vi]);
+            }
         }
     };
     int64_t r = blockIdx.x;
@@ -774,6 +789,79 @@ hipError_t launch_quant_row_colmax(const void* x, int64_t rows, int64_t cols, in
     return launch_colmax_final_scale(part, G, cols, ld_part, fmt, flags, scale_cols, st);
 }
 
+
+// The gradient through Sigmoid + Linear, quantized along both axes without materialising
+// dz = dy * y * (1 - y): rowwise codes + scales and per-column scales from one read of (dy, y), then
+// the per-column transposed codes from a second.  Same conditions as launch_quant_row_colmax
+// (hipErrorNotSupported otherwise: the caller then materialises dz).
+hipError_t launch_quant_row_col_sigmoid_bwd(const void* dy, const void* y, int64_t rows, int64_t cols, int64_t ld,
+                                            int fmt, int flags, uint8_t* q_row, int64_t ld_row, float* scale_row,
+                                            uint8_t* q_col_t, int64_t ld_col_t, float* scale_col, hipStream_t st) {
+    const int64_t nvec = cols / 8;
+    if (cols % 8 != 0 || nvec > 256 * 16 || nvec < 64) return hipErrorNotSupported;
+    const uint16_t* xp = static_cast<const uint16_t*>(dy);
+    const uint16_t* yp = static_cast<const uint16_t*>(y);
+    const int64_t ld_part = cols;
+    uint16_t* part = reinterpret_cast<uint16_t*>(q_col_t);          // overwritten by the transposed codes afterwards
+    const size_t scratch_bytes = (size_t)(cols - 1) * (size_t)ld_col_t + (size_t)rows;
+    int64_t G = 0;
+#define FP8K_QRCA(FMT, NV)                                                                                    \
+    do {                                                                                                      \
+        static int resident = -1;                                                                             \
+        if (resident < 0) resident = resident_blocks(quant_row_colmax_kernel<FMT, NV, true>);                  \
+        G = resident < 1024 ? resident : 1024;                                                                \
+        if (G > rows / 8) G = rows / 8;                                                                       \
+        if ((size_t)(G * ld_part * 2) > scratch_bytes) G = (int64_t)(scratch_bytes / (size_t)(ld_part * 2));  \
+        if (G < 128) return hipErrorNotSupported;                                                             \
+        quant_row_colmax_kernel<FMT, NV, true><<<dim3((unsigned)G), dim3(256), 0, st>>>(                       \
+            xp, rows, cols, ld, flags, q_row, ld_row, scale_row, part, ld_part, yp);                          \
+    } while (0)
+#define FP8K_QRCA_NV(FMT)                 \
+    if (nvec <= 256) FP8K_QRCA(FMT, 1);   \
+    else if (nvec <= 512) FP8K_QRCA(FMT, 2);  \
+    else if (nvec <= 1024) FP8K_QRCA(FMT, 4); \
+    else if (nvec <= 2048) FP8K_QRCA(FMT, 8); \
+    else FP8K_QRCA(FMT, 16)
+    if (fmt == FMT_E4M3FN) { FP8K_QRCA_NV(FMT_E4M3FN); }
+    else { FP8K_QRCA_NV(FMT_E5M2); }
+#undef FP8K_QRCA_NV
+#undef FP8K_QRCA
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = launch_colmax_final_scale(part, G, cols, ld_part, fmt, flags, scale_col, st);
+    if (e != hipSuccess) return e;
+    const int64_t gx = (cols + 127) / 128, gy = (rows + 127) / 128;
+    const int64_t total = ((gy + 15) / 16) * ((gx + 15) / 16) * 256;
+    if (total > 0x7FFFFFFF) return hipErrorInvalidValue;
+    if (fmt == FMT_E4M3FN)
+        cast_transpose_kernel<FMT_E4M3FN, GRAN_COL, 128, true><<<dim3((unsigned)total), dim3(256), 0, st>>>(
+            xp, rows, cols, ld, scale_col, q_col_t, ld_col_t, nullptr, 0, (int)gy, (int)gx, yp);
+    else
+        cast_transpose_kernel<FMT_E5M2, GRAN_COL, 128, true><<<dim3((unsigned)total), dim3(256), 0, st>>>(
+            xp, rows, cols, ld, scale_col, q_col_t, ld_col_t, nullptr, 0, (int)gy, (int)gx, yp);
+    return hipGetLastError();
+}
+
+// dz = dy * y * (1 - y) materialised (bfloat16, dense): the fallback for shapes the fused kernels do not take
+__global__ __launch_bounds__(256) void sigmoid_bwd_kernel(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ y,
+                                                           int64_t n, uint16_t* __restrict__ dz) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v * 8 + 8 <= n) {
+        const uint4 g = load_stream(dy + v * 8), s = load_stream(y + v * 8);
+        store_stream(dz + v * 8, sigmoid_bwd8(g, s));
+    } else {
+        for (int64_t i = v * 8; i < n; ++i)
+            dz[i] = (uint16_t)sigmoid_bwd_bf16_bits(__uint_as_float((uint32_t)dy[i] << 16), __uint_as_float((uint32_t)y[i] << 16));
+    }
+}
+hipError_t launch_sigmoid_bwd(const void* dy, const void* y, int64_t n, void* dz, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    const int64_t blocks = ((n + 7) / 8 + 255) / 256;
+    if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    sigmoid_bwd_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(static_cast<const uint16_t*>(dy), static_cast<const uint16_t*>(y), n,
+                                                                      static_cast<uint16_t*>(dz));
+    return hipGetLastError();
+}
 
 // ------------------------------------------------------------ MX block quantization
 // Blocks of 32 consecutive elements of a row share one power-of-two scale

@@ -85,6 +85,10 @@ def load_library() -> C.CDLL:
     L.fp8_linear_fwd_prequantized.restype = ci
     L.fp8_linear_fwd_prequantized.argtypes = [vp, i64, i64, ci, ci, ci, vp, i64, ci, vp, ci, i64, vp, i64, vp,
                                               C.c_size_t, vp]
+    L.fp8_linear_bwd_sigmoid_workspace_bytes.restype = C.c_size_t
+    L.fp8_linear_bwd_sigmoid_workspace_bytes.argtypes = [i64, i64, i64, vp]
+    L.fp8_linear_bwd_sigmoid.restype = ci
+    L.fp8_linear_bwd_sigmoid.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, C.c_size_t, vp]
     L.fp8_layernorm_quantize.restype = ci
     L.fp8_layernorm_quantize.argtypes = [vp, i64, i64, i64, vp, vp, C.c_double, ci, ci, vp, i64, vp, i64, vp, vp, vp, vp]
     L.fp8_mx_quantize.restype = ci
@@ -280,6 +284,37 @@ def fp8_linear_bwd(dy: torch.Tensor, x: torch.Tensor, w: torch.Tensor, recipe: R
     r = recipe.c()
     _check(load_library().fp8_linear_bwd(_ptr(dy), _ptr(x), _ptr(w), M, K, N, C.byref(r), _ptr(dx), _ptr(dw),
                                          _ptr(workspace), workspace.numel(), _stream()))
+    return dx, dw
+
+
+def fp8_linear_bwd_sigmoid_workspace_bytes(M: int, K: int, N: int, recipe: Recipe) -> int:
+    r = recipe.c()
+    n = load_library().fp8_linear_bwd_sigmoid_workspace_bytes(M, K, N, C.byref(r))
+    if n == 0:
+        raise Fp8Error(-2, fp8_last_error())
+    return int(n)
+
+
+def fp8_linear_bwd_sigmoid(dy: torch.Tensor, y: torch.Tensor, x, w, recipe: Recipe, dx: torch.Tensor | None = None,
+                           dw: torch.Tensor | None = None, workspace: torch.Tensor | None = None,
+                           need_dx: bool = True, need_dw: bool = True):
+    """Backward through Sigmoid + Linear: as fp8_linear_bwd with dY = dy * y * (1 - y), y the stored sigmoid output."""
+    M, N, _ = _mat(dy, 2)
+    assert tuple(y.shape) == (M, N) and dy.is_contiguous() and y.is_contiguous() and y.element_size() == 2
+    K = x.shape[1] if isinstance(x, torch.Tensor) else x[1]
+    x = x if isinstance(x, torch.Tensor) else None
+    w = w if isinstance(w, torch.Tensor) else None
+    assert x is None or (tuple(x.shape) == (M, K) and x.is_contiguous())
+    assert w is None or (tuple(w.shape) == (N, K) and w.is_contiguous())
+    if workspace is None:
+        workspace = torch.empty(fp8_linear_bwd_sigmoid_workspace_bytes(M, K, N, recipe), dtype=torch.uint8, device=dy.device)
+    if dx is None and need_dx:
+        dx = torch.empty((M, K), dtype=torch.bfloat16, device=dy.device)
+    if dw is None and need_dw:
+        dw = torch.empty((N, K), dtype=torch.bfloat16, device=dy.device)
+    r = recipe.c()
+    _check(load_library().fp8_linear_bwd_sigmoid(_ptr(dy), _ptr(y), _ptr(x), _ptr(w), M, K, N, C.byref(r), _ptr(dx), _ptr(dw),
+                                                 _ptr(workspace), workspace.numel(), _stream()))
     return dx, dw
 
 
