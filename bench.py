@@ -45,6 +45,33 @@ def _event_time_ms(fn, iters: int, warmup: int, torch) -> float:
     return start.elapsed_time(stop) / iters
 
 
+def _graph_time_ms(fn, iters: int, torch) -> float:
+    """The same step replayed from a HIP graph: the launches are submitted by the
+    runtime in one go, so the host's per-call cost (which dominates small shapes)
+    is out of the measurement.  Captured after an eager warm-up on a side stream."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(2):
+            fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        fn()
+    for _ in range(2):
+        g.replay()
+    torch.cuda.synchronize()
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(iters):
+        g.replay()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
 def _profiled_traffic(workload: str):
     """HBM bytes per launch of the forward GEMM as measured with rocprofv3 --pmc
     (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size); kept as a
@@ -81,7 +108,8 @@ def _sweep(torch, fp8, dev, iters: int) -> dict:
                     torch.matmul(x, w.t(), out=y)
                     torch.matmul(dy, w, out=dx)
                     torch.matmul(dy.t(), x, out=dw)
-                entry = {"M": M, "K": K, "N": N, "bf16_ms": round(_event_time_ms(bf16_step, iters, 2, torch), 4)}
+                entry = {"M": M, "K": K, "N": N, "bf16_ms": round(_event_time_ms(bf16_step, iters, 2, torch), 4),
+                         "bf16_graph_ms": round(_graph_time_ms(bf16_step, iters, torch), 4)}
                 # forward and backward share one workspace (FP8_SAVE_FOR_BWD): the forward also makes the fp8
                 # copies of X and W that the backward needs (tensorwise: 3 quantizations per step instead of 5)
                 for tag, gran in (("rowwise", fp8.FP8_ROW), ("tensorwise", fp8.FP8_TENSOR)):
@@ -95,9 +123,13 @@ def _sweep(torch, fp8, dev, iters: int) -> dict:
                     entry[f"fp8_{tag}_ms"] = round(ms, 4)
                     entry[f"speedup_{tag}"] = round(entry["bf16_ms"] / ms, 3)
                     entry[f"fp8_{tag}_TFLOP/s"] = round(6.0 * M * N * K / (ms * 1e-3) / 1e12, 1)
+                    gms = _graph_time_ms(fp8_step, iters, torch)
+                    entry[f"fp8_{tag}_graph_ms"] = round(gms, 4)
+                    entry[f"speedup_{tag}_graph"] = round(entry["bf16_graph_ms"] / gms, 3)
                 rows.append(entry)
                 del x, w, dy, y, dx, dw
-    return {"sweep": "fp8 linear fwd+bwd (quantization included) vs bf16 torch.matmul x3, one MI355X",
+    return {"sweep": "fp8 linear fwd+bwd (quantization included) vs bf16 torch.matmul x3, one MI355X; *_graph_ms: the same step "
+                     "replayed from a HIP graph (no per-call host cost)",
             "iters": iters, "rows": rows}
 
 
