@@ -55,9 +55,15 @@ int64_t n_groups(int gran, int64_t rows, int64_t cols) {
 // amax -> scale -> cast of one operand; amax_tmp has n_groups floats
 int quantize_impl(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran, int format, int flags,
                   uint8_t* q, int64_t ld_out, uint8_t* q_plain, int64_t ld_plain, float* scale_out,
-                  hipStream_t st) {
+                  hipStream_t st, float* part = nullptr) {
     const int transpose = (flags & FP8_TRANSPOSE_OUT) ? 1 : 0;
     const int pow2 = flags & FP8_POW2_SCALE;
+    // dense tensor, one scale, scratch for the per-block maxima at hand: two launches instead of four
+    if (gran == FP8_TENSOR && part != nullptr && ld == cols) {
+        FP8_TRY(fp8k::launch_quant_tensor(x, rows, cols, format, pow2, transpose, q, ld_out, q_plain, ld_plain, scale_out,
+                                          part, st));
+        return FP8_OK;
+    }
     if (gran == FP8_ROW && !transpose) {
         hipError_t e = fp8k::launch_quant_row(x, rows, cols, ld, format, pow2, q, ld_out, scale_out, st);
         if (e == hipSuccess) return FP8_OK;
@@ -105,11 +111,12 @@ int quantize_row_col_impl(const void* x, int64_t rows, int64_t cols, int64_t ld,
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// part: per-block maxima of the tensorwise amax pass (one tensor at a time: the casts consume them in stream order)
 struct FwdPlan {
-    size_t xq, wq, sx, sw, total;
+    size_t xq, wq, sx, sw, part, total;
 };
 struct BwdPlan {
-    size_t gq, gqt, wt, xt, sg, sgt, swt, sxt, total;
+    size_t gq, gqt, wt, xt, sg, sgt, swt, sxt, part, total;
 };
 
 FwdPlan plan_fwd(int64_t M, int64_t K, int64_t N, int gran) {
@@ -120,6 +127,7 @@ FwdPlan plan_fwd(int64_t M, int64_t K, int64_t N, int gran) {
     p.wq = take((size_t)N * K);
     p.sx = take(sizeof(float) * (gran == FP8_ROW ? (size_t)M : 1));
     p.sw = take(sizeof(float) * (gran == FP8_ROW ? (size_t)N : 1));
+    p.part = take(sizeof(float) * fp8k::TENSOR_PARTIALS);
     p.total = o;
     return p;
 }
@@ -137,6 +145,7 @@ BwdPlan plan_bwd(int64_t M, int64_t K, int64_t N, int gran) {
     p.sgt = take(sizeof(float) * (row ? (size_t)N : 1));
     p.swt = take(sizeof(float) * (row ? (size_t)K : 1));
     p.sxt = take(sizeof(float) * (row ? (size_t)K : 1));
+    p.part = take(sizeof(float) * fp8k::TENSOR_PARTIALS);
     p.total = o;
     return p;
 }
@@ -327,8 +336,8 @@ int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N
         const int fl = recipe->flags & FP8_POW2_SCALE;
         float *sxt = reinterpret_cast<float*>(wsb + b.sxt), *swt = reinterpret_cast<float*>(wsb + b.swt);
         if (recipe->gran == FP8_TENSOR) {
-            if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | FP8_TRANSPOSE_OUT, wsb + b.xt, M, wsf + p.xq, K, sxt, st)) return rc;
-            if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | FP8_TRANSPOSE_OUT, wsb + b.wt, N, wsf + p.wq, K, swt, st)) return rc;
+            if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | FP8_TRANSPOSE_OUT, wsb + b.xt, M, wsf + p.xq, K, sxt, st, reinterpret_cast<float*>(wsf + p.part))) return rc;
+            if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | FP8_TRANSPOSE_OUT, wsb + b.wt, N, wsf + p.wq, K, swt, st, reinterpret_cast<float*>(wsf + p.part))) return rc;
             FP8_TRY(fp8k::launch_gemm_fp8(wsf + p.xq, K, recipe->fmt_x, sxt, 0, wsf + p.wq, K, recipe->fmt_w, swt, 0, M, N, K, y, N, 0, st));
             return FP8_OK;
         }
@@ -348,8 +357,9 @@ int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N
     uint8_t *xq = ws + p.xq, *wq = ws + p.wq;
     float *sx = reinterpret_cast<float*>(ws + p.sx), *sw = reinterpret_cast<float*>(ws + p.sw);
     const int g = recipe->gran, fl = recipe->flags & FP8_POW2_SCALE;
-    if (int rc = quantize_impl(x, M, K, K, g, recipe->fmt_x, fl, xq, K, nullptr, 0, sx, st)) return rc;
-    if (int rc = quantize_impl(w, N, K, K, g, recipe->fmt_w, fl, wq, K, nullptr, 0, sw, st)) return rc;
+    float* part = reinterpret_cast<float*>(ws + p.part);
+    if (int rc = quantize_impl(x, M, K, K, g, recipe->fmt_x, fl, xq, K, nullptr, 0, sx, st, part)) return rc;
+    if (int rc = quantize_impl(w, N, K, K, g, recipe->fmt_w, fl, wq, K, nullptr, 0, sw, st, part)) return rc;
     FP8_TRY(fp8k::launch_gemm_fp8(xq, K, recipe->fmt_x, sx, g == FP8_ROW, wq, K, recipe->fmt_w, sw, g == FP8_ROW, M, N, K,
                                   y, N, 0, st));
     return FP8_OK;
@@ -392,20 +402,21 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
 
     if (recipe->gran == FP8_TENSOR) {
         // one scale per tensor; dY is converted once into both layouts
+        float* part = reinterpret_cast<float*>(ws + p.part);
         uint8_t* plain = dx ? gq : nullptr;
         if (dw) {
-            if (int rc = quantize_impl(dy, M, N, N, FP8_TENSOR, recipe->fmt_dy, fl | T, gqt, M, plain, N, sg, st)) return rc;
+            if (int rc = quantize_impl(dy, M, N, N, FP8_TENSOR, recipe->fmt_dy, fl | T, gqt, M, plain, N, sg, st, part)) return rc;
         } else {
-            if (int rc = quantize_impl(dy, M, N, N, FP8_TENSOR, recipe->fmt_dy, fl, gq, N, nullptr, 0, sg, st)) return rc;
+            if (int rc = quantize_impl(dy, M, N, N, FP8_TENSOR, recipe->fmt_dy, fl, gq, N, nullptr, 0, sg, st, part)) return rc;
         }
         if (dx) {
             if (!saved)
-                if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st)) return rc;
+                if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st, part)) return rc;
             FP8_TRY(fp8k::launch_gemm_fp8(gq, N, recipe->fmt_dy, sg, 0, wt, N, recipe->fmt_w, swt, 0, M, K, N, dx, K, 0, st));
         }
         if (dw) {
             if (!saved)
-                if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st)) return rc;
+                if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st, part)) return rc;
             FP8_TRY(fp8k::launch_gemm_fp8(gqt, M, recipe->fmt_dy, sg, 0, xt, M, recipe->fmt_x, sxt, 0, N, K, M, dw, K, 0, st));
         }
         return FP8_OK;

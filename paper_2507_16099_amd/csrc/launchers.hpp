@@ -16,6 +16,12 @@ hipError_t launch_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, in
 hipError_t launch_col_scales_two_level(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, int flags,
                                        float* scale_out, void* scratch, size_t scratch_bytes, hipStream_t st);
 
+// tensorwise quantization of a dense tensor in two launches (per-block maxima, then a cast that derives the
+// scale itself); part: scratch for TENSOR_PARTIALS floats
+constexpr int TENSOR_PARTIALS = 512;
+hipError_t launch_quant_tensor(const void* x, int64_t rows, int64_t cols, int fmt, int flags, int transpose, uint8_t* q,
+                               int64_t ld_out, uint8_t* q_plain, int64_t ld_plain, float* scale_out, float* part,
+                               hipStream_t st);
 hipError_t launch_scale(const float* amax, int64_t n, int fmt, int flags, float* out, hipStream_t st);
 
 // transpose != 0: q is [cols, rows]; q_plain (optional, transpose only) also

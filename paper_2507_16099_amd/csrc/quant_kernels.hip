@@ -71,7 +71,9 @@ __global__ __launch_bounds__(256) void amax_rows_kernel(const uint16_t* __restri
 // Tensorwise amax of a contiguous array of n bfloat16.  A block owns a
 // contiguous chunk of 256 x 8 vectors; every thread issues its eight 128-bit
 // loads back to back (all in flight together), then reduces.  One integer
-// atomic max per block (out zeroed beforehand).
+// atomic max per block (out zeroed beforehand); PART: the block's maximum goes to
+// out[blockIdx.x] instead (nothing to zero, the reader combines the gridDim.x values).
+template <bool PART>
 __global__ __launch_bounds__(256) void amax_flat_kernel(const uint16_t* __restrict__ x, int64_t n,
                                                          float* __restrict__ out) {
     const uint4* xv = reinterpret_cast<const uint4*>(x);
@@ -99,8 +101,35 @@ __global__ __launch_bounds__(256) void amax_flat_kernel(const uint16_t* __restri
     if (threadIdx.x == 0) {
         m = part[0];
         for (int i = 1; i < 4; ++i) m = part[i] > m ? part[i] : m;
-        atomic_max_bits(reinterpret_cast<uint32_t*>(out), m << 16);
+        if constexpr (PART) reinterpret_cast<uint32_t*>(out)[blockIdx.x] = m << 16;
+        else atomic_max_bits(reinterpret_cast<uint32_t*>(out), m << 16);
     }
+}
+
+// The tensor's scale from the per-block maxima of amax_flat_kernel<true> (n_part of them, bits of
+// non-negative floats): computed by the first wavefront of every block of the cast that follows, so that
+// neither a zeroing nor a scale kernel sits between the two passes.  Returns the scale to all threads
+// (contains a barrier: call it from uniform control flow).
+template <int FMT>
+__device__ __forceinline__ float tensor_scale_from_partials(const float* part, int n_part, int sflags, int tid,
+                                                            bool writer, float* scale_out) {
+    __shared__ float bc;
+    if (tid < 64) {
+        const uint32_t* pp = reinterpret_cast<const uint32_t*>(part);
+        uint32_t m = 0;
+        for (int i = tid; i < n_part; i += 64) {
+            const uint32_t v = pp[i];
+            m = v > m ? v : m;
+        }
+        m = wave_max_u32<64>(m);
+        const float s = scale_from_amax(__uint_as_float(m), FMT, sflags);
+        if (tid == 0) {
+            bc = s;
+            if (writer) scale_out[0] = s;
+        }
+    }
+    __syncthreads();
+    return bc;
 }
 
 // Column amax: a block of 8 wavefronts owns 512 columns (64 lanes x 8) and
@@ -305,7 +334,7 @@ hipError_t launch_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, in
         // thousands of them cost more than the read itself (measured on 134 MB: 512 blocks 23 us,
         // 32768 blocks 52 us)
         if (blocks > 512) blocks = 512;
-        amax_flat_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(xp, n, out);
+        amax_flat_kernel<false><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(xp, n, out);
         return hipGetLastError();
     }
     if (gran == GRAN_TENSOR || gran == GRAN_ROW) {
@@ -353,11 +382,19 @@ hipError_t launch_scale(const float* amax, int64_t n, int fmt, int flags, float*
 template <int FMT, int GRAN>
 __global__ __launch_bounds__(256) void cast_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
                                                     int64_t ld, const float* __restrict__ scale,
-                                                    uint8_t* __restrict__ q, int64_t ld_out) {
+                                                    uint8_t* __restrict__ q, int64_t ld_out, int n_part = 0,
+                                                    int sflags = 0, float* __restrict__ scale_out = nullptr) {
     const int64_t c = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 16;
-    if (c >= cols) return;
     float s_t = 0.0f;
-    if constexpr (GRAN == GRAN_TENSOR) s_t = scale[0];
+    if constexpr (GRAN == GRAN_TENSOR) {
+        // n_part > 0: scale points at the per-block maxima of the amax pass instead of at the scale
+        if (n_part > 0)
+            s_t = tensor_scale_from_partials<FMT>(scale, n_part, sflags, threadIdx.y * blockDim.x + threadIdx.x,
+                                                  blockIdx.x == 0 && blockIdx.y == 0, scale_out);
+        else
+            s_t = scale[0];
+    }
+    if (c >= cols) return;
     for (int64_t r = (int64_t)blockIdx.y * blockDim.y + threadIdx.y; r < rows; r += (int64_t)gridDim.y * blockDim.y) {
         const uint16_t* src = x + r * ld + c;
         uint8_t* dst = q + r * ld_out + c;
@@ -418,7 +455,9 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
                                                               const float* __restrict__ scale,
                                                               uint8_t* __restrict__ qt, int64_t ld_t,
                                                               uint8_t* __restrict__ q_plain, int64_t ld_plain,
-                                                              int nx, int ny, const uint16_t* __restrict__ yact = nullptr) {
+                                                              int nx, int ny, const uint16_t* __restrict__ yact = nullptr,
+                                                              int n_part = 0, int sflags = 0,
+                                                              float* __restrict__ scale_out = nullptr) {
     constexpr int SLOTS = TR / 8;   // 8-byte slots per output row
     constexpr int PARTS = TR / 16;  // 16-byte parts per output row
     __shared__ __attribute__((aligned(16))) uint2 tile[128 * SLOTS];
@@ -436,7 +475,9 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
 
     float s_col[8];
     float s_t = 0.0f;
-    if constexpr (GRAN == GRAN_TENSOR) s_t = scale[0];
+    if constexpr (GRAN == GRAN_TENSOR) {
+        if (n_part == 0) s_t = scale[0];
+    }
     if constexpr (GRAN == GRAN_COL) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) s_col[e] = (c + e < cols) ? scale[c + e] : 0.0f;
@@ -445,6 +486,7 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
 #pragma unroll
     for (int rh = 0; rh < TR / 128; ++rh) {
         uint32_t w[8][2];
+        uint4 vv[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int64_t r = r0 + rh * 128 + ty * 8 + j;
@@ -460,6 +502,18 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
                     v = make_uint4(t[0], t[1], t[2], t[3]);
                 }
             }
+            vv[j] = v;
+        }
+        if constexpr (GRAN == GRAN_TENSOR) {
+            // n_part > 0: scale points at the per-block maxima of the amax pass instead of at the scale; the
+            // scale is derived here, behind the tile's loads, so that its latency hides under them
+            if (rh == 0 && n_part > 0)
+                s_t = tensor_scale_from_partials<FMT>(scale, n_part, sflags, threadIdx.x, blockIdx.x == 0, scale_out);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int64_t r = r0 + rh * 128 + ty * 8 + j;
+            const uint4 v = vv[j];
             uint2 b;
             if constexpr (GRAN == GRAN_COL) {
                 b = cast8<FMT>(v, s_col);
@@ -513,7 +567,7 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
 template <int FMT, int GRAN>
 static hipError_t launch_cast_t(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, const float* scale,
                                 int transpose, uint8_t* q, int64_t ld_out, uint8_t* q_plain, int64_t ld_plain,
-                                hipStream_t st) {
+                                hipStream_t st, int n_part = 0, int sflags = 0, float* scale_out = nullptr) {
     if (transpose) {
         // 128-row tiles measured best (256-row tiles: same on the 470 MB gradient
         // tensor, slower on the smaller operands)
@@ -521,7 +575,7 @@ static hipError_t launch_cast_t(const uint16_t* x, int64_t rows, int64_t cols, i
         const int64_t total = ((gy + 15) / 16) * ((gx + 15) / 16) * 256;
         if (total > 0x7FFFFFFF) return hipErrorInvalidValue;
         cast_transpose_kernel<FMT, GRAN, 128><<<dim3((unsigned)total), dim3(256), 0, st>>>(
-            x, rows, cols, ld, scale, q, ld_out, q_plain, ld_plain, (int)gy, (int)gx);
+            x, rows, cols, ld, scale, q, ld_out, q_plain, ld_plain, (int)gy, (int)gx, nullptr, n_part, sflags, scale_out);
         return hipGetLastError();
     }
     const int64_t items = (cols + 15) / 16;
@@ -531,8 +585,31 @@ static hipError_t launch_cast_t(const uint16_t* x, int64_t rows, int64_t cols, i
     int64_t gy = (rows + ty - 1) / ty;
     if (gy > 65535) gy = 65535;
     dim3 grid((unsigned)((items + tx - 1) / tx), (unsigned)gy);
-    cast_kernel<FMT, GRAN><<<grid, dim3(tx, ty), 0, st>>>(x, rows, cols, ld, scale, q, ld_out);
+    cast_kernel<FMT, GRAN><<<grid, dim3(tx, ty), 0, st>>>(x, rows, cols, ld, scale, q, ld_out, n_part, sflags, scale_out);
     return hipGetLastError();
+}
+
+// Tensorwise quantization of a dense tensor in two launches: per-block maxima into part (room for
+// TENSOR_PARTIALS floats), then the cast, every block of which derives the scale from them; scale_out[0]
+// receives the scale.  Same codes and scale as launch_amax + launch_scale + launch_cast.
+hipError_t launch_quant_tensor(const void* x, int64_t rows, int64_t cols, int fmt, int flags, int transpose, uint8_t* q,
+                               int64_t ld_out, uint8_t* q_plain, int64_t ld_plain, float* scale_out, float* part,
+                               hipStream_t st) {
+    if (rows == 0 || cols == 0) return hipSuccess;
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    const int64_t n = rows * cols;
+    int64_t blocks = (n / 8 + 256 * 8 - 1) / (256 * 8);
+    if (blocks < 1) blocks = 1;
+    if (blocks > TENSOR_PARTIALS) blocks = TENSOR_PARTIALS;
+    amax_flat_kernel<true><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(xp, n, part);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int sfl = flags & 1;
+    if (fmt == FMT_E4M3FN)
+        return launch_cast_t<FMT_E4M3FN, GRAN_TENSOR>(xp, rows, cols, cols, part, transpose, q, ld_out, q_plain, ld_plain, st,
+                                                      (int)blocks, sfl, scale_out);
+    return launch_cast_t<FMT_E5M2, GRAN_TENSOR>(xp, rows, cols, cols, part, transpose, q, ld_out, q_plain, ld_plain, st,
+                                                (int)blocks, sfl, scale_out);
 }
 
 hipError_t launch_cast(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int gran,

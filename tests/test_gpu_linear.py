@@ -252,6 +252,37 @@ def test_full_size_step_with_saved_copies_matches_the_stateless_calls():
         assert torch.equal(a_.view(torch.int16), b_.view(torch.int16))
 
 
+@pytest.mark.parametrize("M,K,N", [(16, 16, 16), (208, 176, 272), (1024, 512, 768), (2048, 4096, 1024), (4096, 4096, 2048)])
+@pytest.mark.parametrize("pow2", [False, True])
+def test_tensorwise_linear_equals_the_separate_calls(M, K, N, pow2):
+    """Inside the linear entry points a tensorwise quantization takes two launches (per-block maxima,
+    then a cast whose blocks derive the scale from them).  The codes and the scale must be those of
+    fp8_quantize (amax, scale, cast as separate kernels), which the quantization tests compare with
+    the oracle byte for byte: so the three products equal fp8_scaled_mm on fp8_quantize's outputs
+    bit for bit.  Sizes from one block of maxima to the full 512."""
+    wl = si.scaled_down(si.WORKLOADS["c3_llama3_8b_qkv_tensorwise"], M, K, N)
+    xd, wd, dyd = dev_bf16(wl.x()), dev_bf16(wl.w()), dev_bf16(wl.dy())
+    fl = fp8.FP8_POW2_SCALE if pow2 else 0
+    T, E4, E5, TT = fp8.FP8_TENSOR, fp8.FP8_E4M3FN, fp8.FP8_E5M2, fp8.FP8_TRANSPOSE_OUT
+    xq, sx = fp8.fp8_quantize(xd, T, E4, fl)
+    wq, sw = fp8.fp8_quantize(wd, T, E4, fl)
+    gq, sg = fp8.fp8_quantize(dyd, T, E5, fl)
+    xt, _ = fp8.fp8_quantize(xd, T, E4, fl | TT)
+    wt, _ = fp8.fp8_quantize(wd, T, E4, fl | TT)
+    gt, _ = fp8.fp8_quantize(dyd, T, E5, fl | TT)
+    y0 = fp8.fp8_scaled_mm(xq, E4, sx, T, wq, E4, sw, T)
+    dx0 = fp8.fp8_scaled_mm(gq, E5, sg, T, wt, E4, sw, T)
+    dw0 = fp8.fp8_scaled_mm(gt, E5, sg, T, xt, E4, sx, T)
+    for flags in (fl, fl | fp8.FP8_SAVE_FOR_BWD):
+        r = fp8.Recipe(gran=T, flags=flags)
+        ws = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, True), dtype=torch.uint8, device="cuda")
+        ws.fill_(0xA5)
+        y1 = fp8.fp8_linear_fwd(xd, wd, r, workspace=ws)
+        dx1, dw1 = fp8.fp8_linear_bwd(dyd, xd, wd, r, workspace=ws)
+        for a_, b_ in ((y0, y1), (dx0, dx1), (dw0, dw1)):
+            assert torch.equal(a_.contiguous().view(torch.int16), b_.view(torch.int16))
+
+
 # ------------------------------------------------ inference: weight quantized once
 
 @pytest.mark.parametrize("M", [1, 7, 16, 32, 33, 300])
