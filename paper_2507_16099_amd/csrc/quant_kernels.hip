@@ -233,21 +233,24 @@ __global__ __launch_bounds__(256) void colmax_partial_kernel(const uint16_t* __r
 
 // Column maxima, second level, and the scales in the same kernel: the [G, cols]
 // matrix of first-level magnitudes (G <= 1024) is small, so this is a latency
-// problem.  A block of 1024 threads owns 128 columns; thread (row group
-// t / 16, lane t % 16) folds rows t/16, t/16 + 64, ... of its 8 columns with
-// all of its (at most 16) loads in flight at once; the four row groups of a
-// wavefront combine by shuffles, the sixteen wavefronts through LDS, and 16
-// threads turn the 128 maxima into scales.  No atomics, nothing to zero first.
+// problem.  A block of 1024 threads owns CL * 8 columns (CL = 8: 128-byte row
+// pieces, twice the blocks of CL = 16); thread (row group t / CL, lane t % CL)
+// folds rows t/CL, t/CL + 1024/CL, ... of its 8 columns with all of its loads in
+// flight at once; the row groups of a wavefront combine by shuffles, the sixteen
+// wavefronts through LDS, and CL threads turn the maxima into scales.  No
+// atomics, nothing to zero first.
+template <int CL>
 __global__ __launch_bounds__(1024) void colmax_final_scale_kernel(const uint16_t* __restrict__ part, int G,
                                                                    int64_t cols, int64_t ld_part, int fmt, int flags,
                                                                    float* __restrict__ scale_out) {
-    const int tid = threadIdx.x, cl = tid & 15, rg = tid >> 4;
-    const int64_t c = (int64_t)blockIdx.x * 128 + cl * 8;
+    constexpr int RG = 1024 / CL;   // row groups
+    const int tid = threadIdx.x, cl = tid % CL, rg = tid / CL;
+    const int64_t c = (int64_t)blockIdx.x * (CL * 8) + cl * 8;
     uint4 acc = make_uint4(0, 0, 0, 0);
     if (c < cols) {
         const uint16_t* p = part + c;
 #pragma unroll 16
-        for (int g = rg; g < G; g += 64) {
+        for (int g = rg; g < G; g += RG) {
             const uint4 v = *reinterpret_cast<const uint4*>(p + (int64_t)g * ld_part);
             acc.x = pk_absmax(acc.x, v.x);
             acc.y = pk_absmax(acc.y, v.y);
@@ -256,16 +259,16 @@ __global__ __launch_bounds__(1024) void colmax_final_scale_kernel(const uint16_t
         }
     }
 #pragma unroll
-    for (int off = 16; off <= 32; off <<= 1) {
+    for (int off = CL; off <= 32; off <<= 1) {
         acc.x = pk_absmax(acc.x, (uint32_t)__shfl_xor((int)acc.x, off, 64));
         acc.y = pk_absmax(acc.y, (uint32_t)__shfl_xor((int)acc.y, off, 64));
         acc.z = pk_absmax(acc.z, (uint32_t)__shfl_xor((int)acc.z, off, 64));
         acc.w = pk_absmax(acc.w, (uint32_t)__shfl_xor((int)acc.w, off, 64));
     }
-    __shared__ uint4 sm[16][16];
-    if ((tid & 63) < 16) sm[tid >> 6][cl] = acc;
+    __shared__ uint4 sm[16][CL];
+    if ((tid & 63) < CL) sm[tid >> 6][cl] = acc;
     __syncthreads();
-    if (tid < 16 && c < cols) {
+    if (tid < CL && c < cols) {
 #pragma unroll
         for (int w = 1; w < 16; ++w) {
             const uint4 o = sm[w][tid];
@@ -285,8 +288,13 @@ __global__ __launch_bounds__(1024) void colmax_final_scale_kernel(const uint16_t
 
 static hipError_t launch_colmax_final_scale(const uint16_t* part, int64_t G, int64_t cols, int64_t ld_part, int fmt,
                                             int flags, float* scale_out, hipStream_t st) {
-    colmax_final_scale_kernel<<<dim3((unsigned)((cols + 127) / 128)), dim3(1024), 0, st>>>(part, (int)G, cols, ld_part, fmt,
-                                                                                         flags, scale_out);
+    // blocks of 64 columns (128-byte row pieces) unless that would be more blocks than the device has units for
+    if (cols <= 64 * 256)
+        colmax_final_scale_kernel<8><<<dim3((unsigned)((cols + 63) / 64)), dim3(1024), 0, st>>>(part, (int)G, cols, ld_part,
+                                                                                            fmt, flags, scale_out);
+    else
+        colmax_final_scale_kernel<16><<<dim3((unsigned)((cols + 127) / 128)), dim3(1024), 0, st>>>(part, (int)G, cols, ld_part,
+                                                                                              fmt, flags, scale_out);
     return hipGetLastError();
 }
 
