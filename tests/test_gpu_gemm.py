@@ -33,7 +33,7 @@ def _force_variant(value):
         os.environ["FP8MI355_GEMM_VARIANT"] = old
 
 
-@pytest.fixture(params=["0", "1", "3", "4"], ids=["tile128", "tile256", "pipelined", "snake"])
+@pytest.fixture(params=["0", "1", "3", "4", "6"], ids=["tile128", "tile256", "pipelined", "snake", "tile64"])
 def variant(request):
     yield from _force_variant(request.param)
 
