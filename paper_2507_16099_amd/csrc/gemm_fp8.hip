@@ -36,6 +36,7 @@
 namespace fp8k {
 
 typedef int v8i_t __attribute__((ext_vector_type(8)));
+typedef int v4i_t __attribute__((ext_vector_type(4)));
 typedef float v4f_t __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
@@ -52,7 +53,10 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     return r;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, bool OUT_F32>
+// PD: how many K steps ahead of the matrix cores the global loads run (register sets in flight).  A
+// workgroup that is alone on its CU has nothing else to hide the load latency with (about 1 us per step
+// at PD = 1, whatever the tile); the small tiles, used when there are few of them, take PD = 4.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, bool OUT_F32, int PD = 1>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_tn_kernel(
     const uint8_t* __restrict__ A, int64_t lda, const uint8_t* __restrict__ B, int64_t ldb,
     const float* __restrict__ scale_a, int row_a, const float* __restrict__ scale_b, int row_b, int M, int N,
@@ -88,31 +92,66 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_tn_kernel(
     const int srow = tid >> 3, spc = tid & 7;
     const int ca = spc ^ (srow & 7);                                   // logical chunk, A rows
     const int cb = spc ^ ((srow & 3) | ((srow >> 2) & 4));             // logical chunk, B rows
+    // PD == 1: plain global loads, guarded by branches (any size of tensor).  PD > 1: buffer loads, which
+    // return zeros beyond the end of the tensor without a branch, so that the loop body is straight-line
+    // code and the compiler leaves the loads of later steps in flight (a branch around a load makes it
+    // drain them all); the launcher uses this form only where 32-bit offsets suffice.
     const uint8_t* a_ptr = A + (int64_t)(m0 + srow) * lda + ca * 16;
     const uint8_t* b_ptr = B + (int64_t)(n0 + srow) * ldb + cb * 16;
     const int64_t a_step = (int64_t)(NT / 8) * lda, b_step = (int64_t)(NT / 8) * ldb;
+    const __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(A), 0, PD > 1 ? (int)((int64_t)(M - 1) * lda + K) : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_b = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(B), 0, PD > 1 ? (int)((int64_t)(N - 1) * ldb + K) : 0, 0x00020000);
+    constexpr uint32_t OUTSIDE = 0x80000000u;   // beyond any tensor this form is used for
+    uint32_t va[NLA], vb[NLB];                  // byte offsets of this thread's rows (PD > 1)
+#pragma unroll
+    for (int i = 0; i < NLA; ++i) {
+        const int r = m0 + srow + i * (NT / 8);
+        va[i] = r < M ? (uint32_t)r * (uint32_t)lda + ca * 16 : OUTSIDE;
+    }
+#pragma unroll
+    for (int i = 0; i < NLB; ++i) {
+        const int r = n0 + srow + i * (NT / 8);
+        vb[i] = r < N ? (uint32_t)r * (uint32_t)ldb + cb * 16 : OUTSIDE;
+    }
 
-    uint4 ra[NLA], rb[NLB];
-    auto gload = [&](int k0) {
+    uint4 ra[PD][NLA], rb[PD][NLB];
+    auto gload = [&](int k0, uint4 (&xa)[NLA], uint4 (&xb)[NLB]) {
         const bool ka = k0 + ca * 16 < K, kb = k0 + cb * 16 < K;
+        if constexpr (PD > 1) {
 #pragma unroll
-        for (int i = 0; i < NLA; ++i) {
-            const bool ok = ka && (m0 + srow + i * (NT / 8) < M);
-            ra[i] = ok ? *reinterpret_cast<const uint4*>(a_ptr + i * a_step + k0) : make_uint4(0, 0, 0, 0);
-        }
+            for (int i = 0; i < NLA; ++i) {
+                const uint32_t off = (ka && va[i] != OUTSIDE) ? va[i] + (uint32_t)k0 : OUTSIDE;
+                const v4i_t v = __builtin_amdgcn_raw_buffer_load_b128(rs_a, (int)off, 0, 0);
+                xa[i] = make_uint4((uint32_t)v.x, (uint32_t)v.y, (uint32_t)v.z, (uint32_t)v.w);
+            }
 #pragma unroll
-        for (int i = 0; i < NLB; ++i) {
-            const bool ok = kb && (n0 + srow + i * (NT / 8) < N);
-            rb[i] = ok ? *reinterpret_cast<const uint4*>(b_ptr + i * b_step + k0) : make_uint4(0, 0, 0, 0);
+            for (int i = 0; i < NLB; ++i) {
+                const uint32_t off = (kb && vb[i] != OUTSIDE) ? vb[i] + (uint32_t)k0 : OUTSIDE;
+                const v4i_t v = __builtin_amdgcn_raw_buffer_load_b128(rs_b, (int)off, 0, 0);
+                xb[i] = make_uint4((uint32_t)v.x, (uint32_t)v.y, (uint32_t)v.z, (uint32_t)v.w);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NLA; ++i) {
+                const bool ok = ka && (m0 + srow + i * (NT / 8) < M);
+                xa[i] = ok ? *reinterpret_cast<const uint4*>(a_ptr + i * a_step + k0) : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < NLB; ++i) {
+                const bool ok = kb && (n0 + srow + i * (NT / 8) < N);
+                xb[i] = ok ? *reinterpret_cast<const uint4*>(b_ptr + i * b_step + k0) : make_uint4(0, 0, 0, 0);
+            }
         }
     };
-    auto lstore = [&](int stage) {
+    auto lstore = [&](int stage, const uint4 (&xa)[NLA], const uint4 (&xb)[NLB]) {
         uint8_t* as = smem + stage * STAGE + tid * 16;
         uint8_t* bs = as + BM * BK;
 #pragma unroll
-        for (int i = 0; i < NLA; ++i) *reinterpret_cast<uint4*>(as + i * NT * 16) = ra[i];
+        for (int i = 0; i < NLA; ++i) *reinterpret_cast<uint4*>(as + i * NT * 16) = xa[i];
 #pragma unroll
-        for (int i = 0; i < NLB; ++i) *reinterpret_cast<uint4*>(bs + i * NT * 16) = rb[i];
+        for (int i = 0; i < NLB; ++i) *reinterpret_cast<uint4*>(bs + i * NT * 16) = xb[i];
     };
 
     // ---- LDS -> MFMA operands
@@ -149,17 +188,27 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_tn_kernel(
         }
     };
 
-    // ---- main loop, two LDS stages
+    // ---- main loop, two LDS stages; step s travels through register set s % PD.  The step count is
+    // rounded up to a multiple of PD (steps beyond K load zeros), which keeps the unrolled body free of
+    // conditions.
     const int ksteps = (K + BK - 1) / BK;
-    gload(0);
-    lstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < ksteps; ++kt) {
-        const bool more = kt + 1 < ksteps;
-        if (more) gload((kt + 1) * BK);
-        compute(kt & 1);
-        if (more) lstore((kt + 1) & 1);
+    const int kpad = (ksteps + PD - 1) / PD * PD;
+    if (ksteps > 0) {
+        gload(0, ra[0], rb[0]);
+        lstore(0, ra[0], rb[0]);
         __syncthreads();
+#pragma unroll
+        for (int s_ = 1; s_ < PD; ++s_) gload(s_ * BK, ra[s_], rb[s_]);
+        for (int kb = 0; kb < kpad; kb += PD) {
+#pragma unroll
+            for (int u = 0; u < PD; ++u) {
+                const int kt = kb + u;
+                gload((kt + PD) * BK, ra[u], rb[u]);   // set u is free: step kt sits in LDS
+                compute(kt & 1);
+                lstore((kt + 1) & 1, ra[(u + 1) % PD], rb[(u + 1) % PD]);
+                __syncthreads();
+            }
+        }
     }
 
     // ---- epilogue: (acc * 1/sa) * 1/sb, round, store 16 consecutive n per lane
@@ -206,11 +255,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_tn_kernel(
     }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, bool OUT_F32>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, bool OUT_F32, int PD = 1>
 static hipError_t launch_variant(const uint8_t* a, int64_t lda, const float* sa, int row_a, const uint8_t* b,
                                  int64_t ldb, const float* sb, int row_b, int M, int N, int K, void* out,
                                  int64_t ld_out, hipStream_t st) {
-    auto kern = gemm_fp8_tn_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, OUT_F32>;
+    auto kern = gemm_fp8_tn_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, OUT_F32, PD>;
     constexpr int lds = 2 * (BM + BN) * BK;
     static bool attr_done = false;  // one attribute per instantiation; idempotent, so a race is harmless
     if (!attr_done) {
@@ -233,7 +282,9 @@ static hipError_t launch_fmt(int variant, const uint8_t* a, int64_t lda, const f
                              const uint8_t* b, int64_t ldb, const float* sb, int row_b, int M, int N, int K,
                              void* out, int64_t ld_out, hipStream_t st) {
     if (variant == 6)
-        return launch_variant<64, 64, 4, 1, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
+        return launch_variant<64, 64, 4, 1, FA, FB, OUT_F32, 4>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
+    if (variant == 7)
+        return launch_variant<128, 128, 2, 2, FA, FB, OUT_F32, 3>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
     if (variant == 2)
         return launch_variant<256, 256, 2, 2, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
     if (variant == 1 || (variant >= 3 && variant <= 5))
@@ -246,15 +297,17 @@ static hipError_t launch_fmt(int variant, const uint8_t* a, int64_t lda, const f
 // through the L1 cache cost as much as the tiled kernels' padding); otherwise the 16x16x128 "snake" kernel (variant 4,
 // gemm_fp8_snake.hip) as soon as its 256 x 256 tiles keep more than a quarter
 // of the CUs busy (measured: equal to the 128 x 128 tile of this file at 64
-// tiles, 10-80 % faster from 96 tiles on), and the 128 x 128 tile (more
-// workgroups) below that.  FP8MI355_GEMM_VARIANT=0..5 overrides (tuning and
+// tiles, 10-80 % faster from 96 tiles on), and 128 x 128 or 64 x 64 tiles (more
+// workgroups) below that.  FP8MI355_GEMM_VARIANT=0..7 overrides (tuning and
 // test aid): 0 = 128x128 / 4 waves, 1 = 256x256 / 8 waves, 2 = 256x256 / 4
 // waves (all register-staged), 3 = pipelined 32x32x64
-// (gemm_fp8_pipelined.hip), 4 = snake, 5 = few-row kernel (only where M <= 64).
+// (gemm_fp8_pipelined.hip), 4 = snake, 5 = few-row kernel (only where M <= 64),
+// 6 = 64x64 / 4 waves with loads 4 steps ahead, 7 = 128x128 / 4 waves with loads
+// 3 steps ahead (both register-staged through buffer loads).
 static int pick_variant(int64_t M, int64_t N) {
     if (const char* e = std::getenv("FP8MI355_GEMM_VARIANT")) {
         const int v = std::atoi(e);
-        if (v >= 0 && v <= 6) return v;
+        if (v >= 0 && v <= 7) return v;
     }
     if (M <= 32) return 5;
     const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
@@ -263,7 +316,7 @@ static int pick_variant(int64_t M, int64_t N) {
     // step whatever the tile), so more, smaller tiles finish sooner (64 x 64: 1.3-1.9x faster up to 128 tiles
     // of 128 x 128, equal at 256)
     const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
-    return tiles128 <= 128 ? 6 : 0;
+    return tiles128 <= 128 ? 6 : 7;   // (launch_gemm_fp8 falls back to 0 where their 32-bit offsets do not reach)
 }
 
 hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
@@ -271,7 +324,10 @@ hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float
                            int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
                            hipStream_t st) {
     if (M == 0 || N == 0) return hipSuccess;
-    const int v = pick_variant(M, N);
+    int v = pick_variant(M, N);
+    // the forms with loads several steps ahead address their operands with 32-bit byte offsets (a tile may
+    // reach up to 127 rows past the end)
+    if ((v == 6 || v == 7) && ((M + 128) * lda + K >= (int64_t)1 << 31 || (N + 128) * ldb + K >= (int64_t)1 << 31)) v = 0;
     if (v == 5 && M <= 64 && K > 0)
         return launch_gemm_fp8_skinny(a, lda, fmt_a, scale_a, row_a, b, ldb, fmt_b, scale_b, row_b, M, N, K, out, ld_out,
                                       out_f32, st);

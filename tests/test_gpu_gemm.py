@@ -33,7 +33,7 @@ def _force_variant(value):
         os.environ["FP8MI355_GEMM_VARIANT"] = old
 
 
-@pytest.fixture(params=["0", "1", "3", "4", "6"], ids=["tile128", "tile256", "pipelined", "snake", "tile64"])
+@pytest.fixture(params=["0", "1", "3", "4", "6", "7"], ids=["tile128", "tile256", "pipelined", "snake", "tile64", "tile128_ahead"])
 def variant(request):
     yield from _force_variant(request.param)
 
