@@ -846,14 +846,19 @@ hipError_t launch_quant_row_colmax(const void* x, int64_t rows, int64_t cols, in
     const uint16_t* xp = static_cast<const uint16_t*>(x);
     uint16_t* part = static_cast<uint16_t*>(scratch);
     // G blocks, all resident at once (a second, partly filled round of blocks would
-    // idle most of the chip), each with at least 8 rows, G rows of scratch
+    // idle most of the chip), each with at least 8 rows (fewer where that would leave CUs without a block:
+    // a 1024 x 16384 tensor took 24 us with 128 blocks), G rows of scratch
     int64_t G = 0;
 #define FP8K_QRC(FMT, NV)                                                                                     \
     do {                                                                                                      \
         static int resident = -1;   /* per kernel; a race only repeats the query */                           \
         if (resident < 0) resident = resident_blocks(quant_row_colmax_kernel<FMT, NV>);                        \
         G = resident < 1024 ? resident : 1024;                                                                \
-        if (G > rows / 8) G = rows / 8;                                                                       \
+        { /* at least 8 rows per block, but not fewer than 256 blocks while each still has 2 rows */          \
+            int64_t cap = rows / 8;                                                                           \
+            if (cap < 256) cap = rows / 2 < 256 ? rows / 2 : 256;                                             \
+            if (G > cap) G = cap;                                                                             \
+        }                                                                                                     \
         if ((size_t)(G * ld_part * 2) > scratch_bytes) G = (int64_t)(scratch_bytes / (size_t)(ld_part * 2));  \
         if (G < 128) return hipErrorNotSupported;                                                             \
         quant_row_colmax_kernel<FMT, NV><<<dim3((unsigned)G), dim3(256), 0, st>>>(xp, rows, cols, ld, flags, q, ld_out, \
@@ -895,7 +900,11 @@ hipError_t launch_quant_row_col_sigmoid_bwd(const void* dy, const void* y, int64
         static int resident = -1;                                                                             \
         if (resident < 0) resident = resident_blocks(quant_row_colmax_kernel<FMT, NV, true>);                  \
         G = resident < 1024 ? resident : 1024;                                                                \
-        if (G > rows / 8) G = rows / 8;                                                                       \
+        { /* at least 8 rows per block, but not fewer than 256 blocks while each still has 2 rows */          \
+            int64_t cap = rows / 8;                                                                           \
+            if (cap < 256) cap = rows / 2 < 256 ? rows / 2 : 256;                                             \
+            if (G > cap) G = cap;                                                                             \
+        }                                                                                                     \
         if ((size_t)(G * ld_part * 2) > scratch_bytes) G = (int64_t)(scratch_bytes / (size_t)(ld_part * 2));  \
         if (G < 128) return hipErrorNotSupported;                                                             \
         quant_row_colmax_kernel<FMT, NV, true><<<dim3((unsigned)G), dim3(256), 0, st>>>(                       \

@@ -155,6 +155,8 @@ def test_quantize_zero_rows_and_outliers():
     (2050, 14336, 14336),    # benchmark row length (8 vectors per thread)
     (2048, 16392, 16392),    # 16 vectors per thread
     (2047, 512, 512),        # fewer blocks than the device could hold
+    (1024, 16384, 16384),    # few long rows: 256 blocks x 4 rows
+    (600, 1024, 1024), (256, 2048, 2056), (255, 512, 512),   # down to two rows per block; 255 rows: separate passes
     (100, 200, 200), (3000, 100, 104), (2048, 8, 8), (1000, 512, 512),   # shapes served by the separate passes
 ])
 def test_quantize_row_and_column_in_two_reads(rows, cols, ld):
