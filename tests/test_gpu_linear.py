@@ -66,6 +66,43 @@ def test_fwd_bwd_small_shapes(M, K, N, base):
     assert torch.equal(dw2.view(torch.int16), dw.view(torch.int16))
 
 
+def _random_shapes(n, seed):
+    """Seeded shapes (multiples of 16) that cross the boundaries of the kernel choices: the 64 / 128 / 256
+    GEMM tiles, the single-pass row kernels, the fused rows-and-column-maxima pass (from 256 rows on)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        M = int(rng.choice([16, 48, 240, 256, 272, 528, 1040, 2064])) + 16 * int(rng.integers(0, 3))
+        K = 16 * int(rng.integers(1, 70))
+        N = int(rng.choice([16, 64, 144, 512, 528, 1040, 1552])) + 16 * int(rng.integers(0, 3))
+        out.append((M, K, N))
+    return out
+
+
+@pytest.mark.parametrize("M,K,N", _random_shapes(24, 77))
+def test_fwd_bwd_random_shapes_all_recipes(M, K, N):
+    """Forward and both gradients against the oracle on seeded random shapes, for the tensorwise,
+    rowwise and power-of-two rowwise recipes, stateless and with the forward's copies saved."""
+    wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)
+    x, w, dy = wl.x(), wl.w(), wl.dy()
+    xd, wd, dyd = dev_bf16(x), dev_bf16(w), dev_bf16(dy)
+    for gran, pow2 in ((fp8.FP8_TENSOR, False), (fp8.FP8_ROW, False), (fp8.FP8_ROW, True)):
+        o = orc.Recipe(gran=orc.TENSOR if gran == fp8.FP8_TENSOR else orc.ROW, pow2=pow2)
+        want = (orc.linear_fwd(x, w, o)[0], orc.linear_bwd_dx(dy, w, o)[0], orc.linear_bwd_dw(dy, x, o)[0])
+        fl = fp8.FP8_POW2_SCALE if pow2 else 0
+        g = fp8.Recipe(gran=gran, flags=fl)
+        y = fp8.fp8_linear_fwd(xd, wd, g)
+        dx, dw = fp8.fp8_linear_bwd(dyd, xd, wd, g)
+        for got, wnt in zip((y, dx, dw), want):
+            _cmp(got, wnt, min_identical=0.95)
+        gs = fp8.Recipe(gran=gran, flags=fl | fp8.FP8_SAVE_FOR_BWD)
+        ws = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, gs, True), dtype=torch.uint8, device="cuda")
+        y1 = fp8.fp8_linear_fwd(xd, wd, gs, workspace=ws)
+        dx1, dw1 = fp8.fp8_linear_bwd(dyd, (M, K), (N, K), gs, workspace=ws)
+        for a_, b_ in ((y, y1), (dx, dx1), (dw, dw1)):
+            assert torch.equal(a_.view(torch.int16), b_.view(torch.int16)), (M, K, N, gran, pow2)
+
+
 def test_exact_integer_linear_with_pow2_scales():
     rng = np.random.default_rng(52)
     M, K, N = 256, 384, 128
