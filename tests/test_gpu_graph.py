@@ -18,7 +18,8 @@ def _bits(t):
     return t.view(torch.int16).clone()
 
 
-@pytest.mark.parametrize("recipe", ["rowwise", "rowwise_saved", "tensorwise", "tensorwise_saved", "rowwise_gw_hp", "mx"])
+@pytest.mark.parametrize("recipe", ["rowwise", "rowwise_saved", "tensorwise", "tensorwise_saved", "rowwise_gw_hp", "mx",
+                                    "rowwise_sigmoid"])
 def test_step_replays_from_a_hip_graph(recipe):
     M, K, N = 1024, 512, 768
     wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)
@@ -37,6 +38,22 @@ def test_step_replays_from_a_hip_graph(recipe):
         def step():
             fp8.fp8_mx_linear_fwd(x, w, y=y, workspace=ws_f)
             fp8.fp8_mx_linear_bwd(dy, x, w, dx=dx, dw=dw, workspace=ws_b)
+    elif recipe == "rowwise_sigmoid":
+        # sigmoid inside the forward GEMM's epilogue, its gradient inside the backward's quantization
+        r = fp8.Recipe(gran=fp8.FP8_ROW)
+        ws_f = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, False), dtype=torch.uint8, device="cuda")
+        ws_b = torch.empty(fp8.fp8_linear_bwd_sigmoid_workspace_bytes(M, K, N, r), dtype=torch.uint8, device="cuda")
+        xq = torch.empty((M, K), dtype=torch.uint8, device="cuda")
+        wq = torch.empty((N, K), dtype=torch.uint8, device="cuda")
+        sx = torch.empty(M, dtype=torch.float32, device="cuda")
+        sw = torch.empty(N, dtype=torch.float32, device="cuda")
+
+        def step():
+            fp8.fp8_quantize(x, fp8.FP8_ROW, fp8.FP8_E4M3FN, out=xq, scale_out=sx)
+            fp8.fp8_quantize(w, fp8.FP8_ROW, fp8.FP8_E4M3FN, out=wq, scale_out=sw)
+            fp8.fp8_scaled_mm(xq, fp8.FP8_E4M3FN, sx, fp8.FP8_ROW, wq, fp8.FP8_E4M3FN, sw, fp8.FP8_ROW,
+                              fp8.FP8_EPILOGUE_SIGMOID, out=y)
+            fp8.fp8_linear_bwd_sigmoid(dy, y, x, w, r, dx=dx, dw=dw, workspace=ws_b)
     else:
         r = {"rowwise": fp8.Recipe(gran=fp8.FP8_ROW), "tensorwise": fp8.Recipe(gran=fp8.FP8_TENSOR),
              "tensorwise_saved": fp8.Recipe(gran=fp8.FP8_TENSOR, flags=fp8.FP8_SAVE_FOR_BWD),
