@@ -208,6 +208,52 @@ def _block(torch, fp8, dev, iters: int) -> dict:
             "iters": iters, "rows": rows}
 
 
+def _configs(torch, fp8, dev, iters: int) -> dict:
+    """Every synthetic workload of the configuration list (the Llama-3 8B / 70B
+    linear shapes and the outlier case) on its own seeded data: the fp8 step of
+    its recipe (forward only where the configuration has no backward) against
+    the same products in bfloat16 by the vendor BLAS."""
+    import synthetic_inputs as si
+
+    def dev_bf16(bits):
+        return torch.from_numpy(bits.view("int16")).to(dev).view(torch.bfloat16)
+
+    rows = []
+    for name, wl in si.WORKLOADS.items():
+        M, K, N = wl.M, wl.K, wl.N
+        x, w = dev_bf16(wl.x()), dev_bf16(wl.w())
+        dy = dev_bf16(wl.dy()) if wl.backward else None
+        gran = fp8.FP8_ROW if wl.recipe == si.ROWWISE else fp8.FP8_TENSOR
+        fl = (fp8.FP8_POW2_SCALE if wl.pow2 else 0) | (fp8.FP8_SAVE_FOR_BWD if wl.backward else 0)
+        r = fp8.Recipe(gran=gran, flags=fl)
+        ws = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, wl.backward), dtype=torch.uint8, device=dev)
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        dx = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+        dw = torch.empty((N, K), dtype=torch.bfloat16, device=dev)
+
+        def fp8_step():
+            fp8.fp8_linear_fwd(x, w, r, y=y, workspace=ws)
+            if wl.backward:
+                fp8.fp8_linear_bwd(dy, (M, K), (N, K), r, dx=dx, dw=dw, workspace=ws)
+
+        def bf16_step():
+            torch.matmul(x, w.t(), out=y)
+            if wl.backward:
+                torch.matmul(dy, w, out=dx)
+                torch.matmul(dy.t(), x, out=dw)
+        t8 = _event_time_ms(fp8_step, iters, 3, torch)
+        tb = _event_time_ms(bf16_step, iters, 3, torch)
+        flop = (6.0 if wl.backward else 2.0) * M * N * K
+        rows.append({"workload": name, "M": M, "K": K, "N": N, "recipe": "rowwise" if gran == fp8.FP8_ROW else "tensorwise",
+                     "pow2_scales": bool(wl.pow2), "pass": "fwd+bwd" if wl.backward else "fwd",
+                     "fp8_ms": round(t8, 4), "fp8_TFLOP/s": round(flop / t8 / 1e9, 1), "bf16_ms": round(tb, 4),
+                     "speedup": round(tb / t8, 3)})
+        del x, w, dy, y, dx, dw, ws
+        torch.cuda.empty_cache()
+    return {"configs": "fp8 linear step (dynamic quantization included) vs bf16 torch.matmul on every synthetic workload, one MI355X",
+            "iters": iters, "rows": rows}
+
+
 def _data_probe(torch, fp8, dev, iters: int) -> dict:
     """How much of the forward GEMM's rate depends on the operand DATA: the same
     kernel and launch on the benchmark shape with operands that do not toggle
@@ -301,6 +347,8 @@ def main() -> int:
                          "prints a JSON table and exits")
     ap.add_argument("--block", action="store_true",
                     help="LayerNorm + Linear + Sigmoid forward and backward, float8 vs bfloat16 over shapes, then exit")
+    ap.add_argument("--configs", action="store_true",
+                    help="the fp8 step of every synthetic workload (Llama-3 8B / 70B shapes, outlier case) vs bf16, then exit")
     ap.add_argument("--data-probe", action="store_true",
                     help="time the forward GEMM with operands that do not toggle and with realistic ones, then exit")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -336,6 +384,10 @@ def main() -> int:
 
     if args.block:
         print(json.dumps(_block(torch, fp8, dev, max(5, args.steps // 2))))
+        return 0
+
+    if args.configs:
+        print(json.dumps(_configs(torch, fp8, dev, max(10, args.steps))))
         return 0
 
     if args.data_probe:
