@@ -378,6 +378,54 @@ void orc_mx_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, 
     }
 }
 
+/* ------------------------------------------------------- blockwise FP8
+ *
+ * "Blockwise FP8: FP8 blockwise quantization introduced by DeepSeek" is on the
+ * paper's list of prototype features; the paper gives no further detail.  The
+ * recipe (DeepSeek-V3 technical report, Section 3.3.2 "fine-grained
+ * quantization"): activations are scaled per tile of 1 x 128 elements (one
+ * token, 128 channels along the contraction axis), weights per block of
+ * 128 x 128, each scale chosen so that the block's amax lands on the largest
+ * FP8 value, and the partial sums of every 128 contracted elements are
+ * dequantized with the two block scales.
+ * Readings: the scale is that of the tensorwise / rowwise recipes applied to
+ * the block, s = fp32(FMAX / max(amax, 1e-12)), rounded DOWN to a power of two
+ * (mantissa cleared) so that CDNA4's block-scaled matrix instruction can apply
+ * its reciprocal as an E8M0 byte: byte = 127 - log2(s), dequantized value =
+ * 2^(byte - 127) * dec(code).  The byte of a block is written for every row of
+ * the block and every group of 32 columns in it, i.e. in the layout of the MX
+ * scales ([rows, cols / 32]), so orc_mx_mm is the product of two blockwise
+ * operands as well.  br x bc is the block (1 x 128 or 128 x 128; any br >= 1 and
+ * bc a multiple of 32 work); blocks at the bottom edge may be partial, cols must
+ * be a multiple of bc.
+ */
+void orc_block_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, int64_t br, int64_t bc, int fmt,
+                        uint8_t* q, int64_t ld_q, uint8_t* e8m0, int64_t ld_e) {
+    const int64_t nrb = (rows + br - 1) / br, ncb = cols / bc;
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int64_t rb = 0; rb < nrb; ++rb) {
+        for (int64_t cb = 0; cb < ncb; ++cb) {
+            const int64_t r0 = rb * br, r1 = r0 + br < rows ? r0 + br : rows, c0 = cb * bc;
+            float amax = 0.0f;
+            for (int64_t r = r0; r < r1; ++r)
+                for (int64_t c = c0; c < c0 + bc; ++c) {
+                    const float a = fabsf(orc_bf16_to_f32(x[r * ld + c]));
+                    if (a > amax) amax = a;
+                }
+            float s;
+            orc_scale(&amax, 1, fmt, ORC_POW2_SCALE, &s);
+            int byte = 127 - ((int)(f32_bits(s) >> 23) - 127);      /* s = 2^k, k = exponent field - 127 */
+            if (byte < 0) byte = 0;
+            if (byte > 254) byte = 254;
+            for (int64_t r = r0; r < r1; ++r) {
+                for (int64_t j = 0; j < bc / 32; ++j) e8m0[r * ld_e + c0 / 32 + j] = (uint8_t)byte;
+                for (int64_t c = c0; c < c0 + bc; ++c)
+                    q[r * ld_q + c] = orc_fp8_encode_bits(orc_bf16_to_f32(x[r * ld + c]) * s, fmt);
+            }
+        }
+    }
+}
+
 /* value of an MX element: X * dec(P) in binary64 (exact) */
 double orc_mx_value(uint8_t code, int fmt, uint8_t e8m0) {
     return ldexp((double)orc_fp8_decode(code, fmt), (int)e8m0 - 127);

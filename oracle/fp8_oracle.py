@@ -79,6 +79,8 @@ def lib() -> C.CDLL:
                                     i64, i64, i64, vp, i64, vp, vp, vp]
         L.orc_mx_quantize.restype = None
         L.orc_mx_quantize.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp, i64]
+        L.orc_block_quantize.restype = None
+        L.orc_block_quantize.argtypes = [vp, i64, i64, i64, i64, i64, ci, vp, i64, vp, i64]
         L.orc_mx_value.restype = C.c_double
         L.orc_mx_value.argtypes = [C.c_uint8, ci, C.c_uint8]
         L.orc_mx_mm.restype = None
@@ -322,6 +324,25 @@ def mx_quantize(x: np.ndarray, fmt: int):
     e = np.empty((rows, cols // MX_BLOCK), np.uint8)
     lib().orc_mx_quantize(_p(x), rows, cols, ld, fmt, _p(q), cols, _p(e), cols // MX_BLOCK)
     return q, e
+
+
+def block_quantize(x: np.ndarray, br: int, bc: int, fmt: int):
+    """Blockwise FP8 (blocks of br x bc, power-of-two scales) -> (codes [rows, cols], E8M0 bytes
+    [rows, cols / 32] in the layout of the MX scales: a block's byte repeated over its rows and
+    its groups of 32 columns)."""
+    rows, cols, ld = _check2d(x, np.uint16)
+    assert br >= 1 and bc % MX_BLOCK == 0 and cols % bc == 0
+    q = np.empty((rows, cols), np.uint8)
+    e = np.empty((rows, cols // MX_BLOCK), np.uint8)
+    lib().orc_block_quantize(_p(x), rows, cols, ld, br, bc, fmt, _p(q), cols, _p(e), cols // MX_BLOCK)
+    return q, e
+
+
+def block_linear_fwd(x, w, fmt_x=E4M3FN, fmt_w=E4M3FN, rows=None) -> MMResult:
+    """Y = X W^T, X in tiles of 1 x 128 along K, W in blocks of 128 x 128 (DeepSeek-style blockwise FP8)."""
+    xq, xe = block_quantize(x, 1, 128, fmt_x)
+    wq, we = block_quantize(w, 128, 128, fmt_w)
+    return mx_mm(xq, fmt_x, xe, wq, fmt_w, we, rows)
 
 
 def mx_value(code: int, fmt: int, e8m0: int) -> float:
