@@ -639,6 +639,15 @@ def main() -> int:
             result["mx_linear_fwd"] = {"ms": round(ms, 4), "TFLOP/s": round(2.0 * M * N * K / (ms * 1e-3) / 1e12, 1),
                                        "note": "forward with both operands in MX blocks of 32 along K (E8M0 scales applied by the matrix cores)"}
             del xm, xe, wm, we
+            # blockwise FP8 (1 x 128 tiles of X, 128 x 128 blocks of W, power-of-two scales): same GEMM, other quantizers
+            bq1 = lambda inp, q, e: fp8.fp8_block_quantize(inp, 1, E4) if q is None else fp8.fp8_block_quantize(inp, 1, E4, q, e)
+            bq128 = lambda inp, q, e: fp8.fp8_block_quantize(inp, 128, E4) if q is None else fp8.fp8_block_quantize(inp, 128, E4, q, e)
+            cast_leg("block_quant_x_1x128", x, bq1, M * K, 3)
+            cast_leg("block_quant_w_128x128", w, bq128, N * K, 3)
+            ms = _event_time_ms(lambda: fp8.fp8_block_linear_fwd(x, w, y=y, workspace=wsm), max(3, args.steps // 2), 2, torch)
+            result["block_linear_fwd"] = {"ms": round(ms, 4), "TFLOP/s": round(2.0 * M * N * K / (ms * 1e-3) / 1e12, 1),
+                                          "note": "forward with X in tiles of 1 x 128 and W in blocks of 128 x 128 (blockwise FP8, power-of-two "
+                                                  "scales applied by the matrix cores)"}
             if wl.backward and M % 128 == 0 and N % 128 == 0:
                 mqt = lambda inp, q, e: fp8.fp8_mx_quantize_t(inp, E4) if q is None else fp8.fp8_mx_quantize_t(inp, E4, q, e)
                 cast_leg("mx_quant_dy_t", dy, mqt, M * N, 3)

@@ -326,6 +326,32 @@ int fp8_mx_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, i
                       int fmt_x, int fmt_w, void* dx, void* dw, void* workspace, size_t workspace_bytes,
                       void* stream);
 
+/*
+ * Blockwise FP8 ("Blockwise FP8: FP8 blockwise quantization introduced by
+ * DeepSeek" on the paper's list of prototype features; the recipe is that of the
+ * DeepSeek-V3 technical report, Section 3.3.2): activations are scaled per tile of
+ * 1 x 128 elements along the contraction axis, weights per block of 128 x 128.
+ * Here the scale of a block is s = fp32(FMAX / max(amax, 1e-12)) rounded DOWN to a
+ * power of two, q = fp8(x * s) (round to nearest even; nothing saturates), and
+ * 1 / s is stored as an E8M0 byte (127 - log2 s) in the layout of the MX scales:
+ * e8m0_out [rows, cols / 32] holds the byte of a block four times per 128 columns
+ * and, for 128 x 128 blocks, in every row of the block.  The operands therefore go
+ * straight into fp8_mx_scaled_mm, whose matrix instruction applies the scales.
+ *
+ * fp8_block_quantize: x [rows, cols] bfloat16, cols % 128 == 0; block_rows = 1
+ *   (tiles of 1 x 128) or 128 (blocks of 128 x 128, the last row of blocks may be
+ *   partial); q_out [rows, cols] (ld_q % 16 == 0), e8m0_out (ld_e % 4 == 0).  One
+ *   pass over HBM in both cases.
+ * fp8_block_linear_fwd: Y = X W^T, X [M, K] in tiles of 1 x 128 along K, W [N, K] in
+ *   blocks of 128 x 128; K % 128 == 0; y [M, N] bfloat16; workspace of
+ *   fp8_block_linear_workspace_bytes(M, K, N) bytes, 256-byte aligned.
+ */
+int fp8_block_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int block_rows, int format,
+                       uint8_t* q_out, int64_t ld_q, uint8_t* e8m0_out, int64_t ld_e, void* stream);
+size_t fp8_block_linear_workspace_bytes(int64_t M, int64_t K, int64_t N);
+int fp8_block_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N, int fmt_x, int fmt_w,
+                         void* y, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -710,6 +710,50 @@ int fp8_mx_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_
     return FP8_OK;
 }
 
+int fp8_block_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int block_rows, int format, uint8_t* q_out,
+                       int64_t ld_q, uint8_t* e8m0_out, int64_t ld_e, void* stream) {
+    g_err[0] = 0;
+    const char* fn = "fp8_block_quantize";
+    if (!fmt_ok(format)) return fail(FP8_ERR_ENUM, "%s: unknown format %d", fn, format);
+    if (block_rows != 1 && block_rows != 128) return fail(FP8_ERR_ENUM, "%s: block_rows=%d must be 1 or 128", fn, block_rows);
+    if (int rc = check_bf16(fn, x, rows, cols, ld)) return rc;
+    if (cols % 128 != 0) return fail(FP8_ERR_SHAPE, "%s: cols=%lld must be a multiple of the block width 128", fn, (long long)cols);
+    if (block_rows == 128 && rows > (int64_t)65535 * 128) return fail(FP8_ERR_SHAPE, "%s: rows=%lld too large", fn, (long long)rows);
+    if (int rc = check_q_out(fn, q_out, rows, cols, ld_q, 0)) return rc;
+    if (ld_e < cols / 32 || ld_e % 4 != 0) return fail(FP8_ERR_SHAPE, "%s: ld_e=%lld must be >= cols/32 and a multiple of 4", fn, (long long)ld_e);
+    if (rows > 0 && cols > 0 && !e8m0_out) return fail(FP8_ERR_NULL, "%s: e8m0_out is NULL", fn);
+    if (!aligned(e8m0_out, 4)) return fail(FP8_ERR_ALIGN, "%s: e8m0_out not 4-byte aligned", fn);
+    FP8_TRY(fp8k::launch_block_quant(x, rows, cols, ld, block_rows, format, q_out, ld_q, e8m0_out, ld_e, static_cast<hipStream_t>(stream)));
+    return FP8_OK;
+}
+
+size_t fp8_block_linear_workspace_bytes(int64_t M, int64_t K, int64_t N) { return fp8_mx_linear_workspace_bytes(M, K, N); }
+
+int fp8_block_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N, int fmt_x, int fmt_w, void* y,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+    g_err[0] = 0;
+    const char* fn = "fp8_block_linear_fwd";
+    if (!fmt_ok(fmt_x) || !fmt_ok(fmt_w)) return fail(FP8_ERR_ENUM, "%s: unknown fp8 format", fn);
+    if (int rc = check_linear_dims(fn, M, K, N, false)) return rc;
+    if (K % 128 != 0) return fail(FP8_ERR_SHAPE, "%s: K=%lld must be a multiple of 128", fn, (long long)K);
+    if (N > (int64_t)65535 * 128) return fail(FP8_ERR_SHAPE, "%s: N=%lld too large", fn, (long long)N);
+    if (int rc = check_bf16("fp8_block_linear_fwd(x)", x, M, K, K)) return rc;
+    if (int rc = check_bf16("fp8_block_linear_fwd(w)", w, N, K, K)) return rc;
+    if (M == 0 || N == 0) return FP8_OK;
+    if (!y || !workspace) return fail(FP8_ERR_NULL, "%s: y or workspace is NULL", fn);
+    if (!aligned(y, 16) || !aligned(workspace, 256)) return fail(FP8_ERR_ALIGN, "%s: y (16) / workspace (256) misaligned", fn);
+    const MxPlan p = plan_mx(M, K, N);
+    if (workspace_bytes < p.total) return fail(FP8_ERR_WORKSPACE, "%s: workspace %zu < %zu bytes", fn, workspace_bytes, p.total);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    // X in tiles of 1 x 128 along K, W in blocks of 128 x 128; the block-scaled GEMM applies the power-of-two scales
+    FP8_TRY(fp8k::launch_block_quant(x, M, K, K, 1, fmt_x, ws + p.xq, K, ws + p.xe, K / 32, st));
+    FP8_TRY(fp8k::launch_block_quant(w, N, K, K, 128, fmt_w, ws + p.wq, K, ws + p.we, K / 32, st));
+    FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.xq, K, fmt_x, ws + p.xe, K / 32, ws + p.wq, K, fmt_w, ws + p.we, K / 32, M, N, K, y,
+                                    N, 0, st));
+    return FP8_OK;
+}
+
 namespace {
 // workspace of the MX backward: the four re-quantized operands and their block scales
 struct MxBwdPlan { size_t dyq, dye, wtq, wte, dytq, dyte, xtq, xte, total; };

@@ -22,6 +22,9 @@ constexpr int TENSOR_PARTIALS = 512;
 hipError_t launch_quant_tensor(const void* x, int64_t rows, int64_t cols, int fmt, int flags, int transpose, uint8_t* q,
                                int64_t ld_out, uint8_t* q_plain, int64_t ld_plain, float* scale_out, float* part,
                                hipStream_t st);
+// blockwise FP8 (tiles of 1 x 128 or blocks of 128 x 128, power-of-two scales as E8M0 bytes in the MX layout)
+hipError_t launch_block_quant(const void* x, int64_t rows, int64_t cols, int64_t ld, int block_rows, int fmt, uint8_t* q,
+                              int64_t ld_q, uint8_t* e8m0, int64_t ld_e, hipStream_t st);
 hipError_t launch_scale(const float* amax, int64_t n, int fmt, int flags, float* out, hipStream_t st);
 
 // transpose != 0: q is [cols, rows]; q_plain (optional, transpose only) also

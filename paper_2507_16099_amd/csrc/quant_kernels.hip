@@ -1030,6 +1030,128 @@ hipError_t launch_mx_quant(const void* x, int64_t rows, int64_t cols, int64_t ld
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------ blockwise FP8
+// The blockwise recipe on the paper's list of prototype features ("FP8 blockwise
+// quantization introduced by DeepSeek"): activations in tiles of 1 x 128 along
+// the contraction axis, weights in blocks of 128 x 128.  The scale of a block
+// is that of the rowwise / tensorwise recipes applied to the block and rounded
+// down to a power of two, s = 2^k, so that its reciprocal is an E8M0 byte
+// (127 - k) that the block-scaled matrix instruction applies by itself; the
+// byte is written in the layout of the MX scales ([rows, cols / 32]: four
+// copies per 128 columns, one row of copies per row of a 128 x 128 block), which
+// makes the MX GEMM the product of two blockwise operands too.
+//
+// The power-of-two scale of a block from the 15 magnitude bits of its bfloat16 maximum, without the
+// binary64 division of scale_from_amax(., ., pow2): FMAX = 1.75 * 2^E (E = 8 / 15) and amax = m * 2^e with
+// 1 <= m < 2 in steps of 2^-7, so FMAX / amax = (1.75 / m) * 2^(E - e) lies in [2^(E-e), 2^(E-e+1)) for
+// m <= 1.75 and in (0.995 * 2^(E-e), ... ) rounded down to 2^(E-e-1) for m > 1.75 (1.75 / m <= 0.9956 there:
+// the binary32 rounding of the quotient cannot reach the next power of two).  Maxima not above 1e-12 (bits
+// below 0x2B8D: 2^-40 * (1 + 13/128) is the first bfloat16 above 1e-12) take the clamp's scale,
+// floor_pow2(fp32(FMAX * 1e12)) = 2^(40 + E).  Identical to the division for every bfloat16 maximum (tested
+// on all of them).  Returns the scale; byte receives 127 - log2(scale).
+template <int FMT>
+__device__ __forceinline__ float pow2_block_scale(uint32_t mag, uint32_t& byte) {
+    constexpr int E = FMT == FMT_E4M3FN ? 8 : 15;
+    int k = 40 + E;
+    if (mag >= 0x2B8Du) k = E - ((int)(mag >> 7) - 127) - ((mag & 0x7Fu) > 96u ? 1 : 0);
+    byte = (uint32_t)(127 - k);
+    return __uint_as_float((uint32_t)(k + 127) << 23);
+}
+
+// 1 x 128 tiles: a thread holds 8 elements of each of four tiles (all four loads in flight together), the 16
+// threads of a tile combine their maxima with four cross-lane steps.  cols % 128 == 0.
+template <int FMT>
+__global__ __launch_bounds__(256) void block_quant_1x128_kernel(const uint16_t* __restrict__ x, int64_t rows,
+                                                                 int64_t cols, int64_t ld, uint8_t* __restrict__ q,
+                                                                 int64_t ld_q, uint8_t* __restrict__ e8m0,
+                                                                 int64_t ld_e) {
+    constexpr int U = 4;
+    const int64_t vpr = cols >> 3, nvec = rows * vpr;          // a multiple of 16: tiles never straddle the end
+    const int64_t v0 = (int64_t)blockIdx.x * (256 * U) + threadIdx.x;
+    uint4 d[U];
+    int64_t r[U], cv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t v = v0 + u * 256;
+        const bool live = v < nvec;
+        r[u] = live ? v / vpr : 0;
+        cv[u] = live ? v % vpr : 0;
+        d[u] = live ? load_stream(x + r[u] * ld + cv[u] * 8) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        uint32_t m = pk_fold(pk_absmax4(0u, d[u]));
+#pragma unroll
+        for (int off = 1; off <= 8; off <<= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)m, off, 64);
+            m = o > m ? o : m;
+        }
+        uint32_t byte;
+        const float s = pow2_block_scale<FMT>(m, byte);
+        if (v0 + u * 256 < nvec) {
+            store_stream(q + r[u] * ld_q + cv[u] * 8, cast8<FMT>(d[u], s));
+            if ((threadIdx.x & 15) == 0)     // ld_e % 4 == 0 and (cv / 4) % 4 == 0: an aligned dword
+                *reinterpret_cast<uint32_t*>(e8m0 + r[u] * ld_e + (cv[u] >> 2)) = byte * 0x01010101u;
+        }
+    }
+}
+
+// 128 x 128 blocks: one workgroup per block, the block held in registers (8 x 8 elements per thread)
+// between the reduction and the conversion: one pass over HBM.  The bottom row of blocks may be partial.
+template <int FMT>
+__global__ __launch_bounds__(256) void block_quant_128x128_kernel(const uint16_t* __restrict__ x, int64_t rows,
+                                                                   int64_t cols, int64_t ld, uint8_t* __restrict__ q,
+                                                                   int64_t ld_q, uint8_t* __restrict__ e8m0,
+                                                                   int64_t ld_e) {
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int64_t r0 = (int64_t)blockIdx.y * 128, c0 = (int64_t)blockIdx.x * 128, c = c0 + tx * 8;
+    uint4 v[8];
+    uint32_t acc = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int64_t r = r0 + ty * 8 + j;
+        v[j] = r < rows ? load_stream(x + r * ld + c) : make_uint4(0, 0, 0, 0);
+        acc = pk_absmax4(acc, v[j]);
+    }
+    uint32_t m = wave_max_u32<64>(pk_fold(acc));
+    __shared__ uint32_t red[4];
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = red[0];
+#pragma unroll
+    for (int i = 1; i < 4; ++i) m = red[i] > m ? red[i] : m;
+    uint32_t byte;
+    const float s = pow2_block_scale<FMT>(m, byte);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int64_t r = r0 + ty * 8 + j;
+        if (r < rows) store_stream(q + r * ld_q + c, cast8<FMT>(v[j], s));
+    }
+    if (threadIdx.x < 128 && r0 + threadIdx.x < rows) {
+        *reinterpret_cast<uint32_t*>(e8m0 + (r0 + threadIdx.x) * ld_e + (c0 >> 5)) = byte * 0x01010101u;
+    }
+}
+
+// block_rows: 1 (tiles of 1 x 128) or 128 (blocks of 128 x 128); cols % 128 == 0
+hipError_t launch_block_quant(const void* x, int64_t rows, int64_t cols, int64_t ld, int block_rows, int fmt, uint8_t* q,
+                              int64_t ld_q, uint8_t* e8m0, int64_t ld_e, hipStream_t st) {
+    if (rows == 0 || cols == 0) return hipSuccess;
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    if (block_rows == 1) {
+        const int64_t blocks = (rows * (cols / 8) + 1023) / 1024;
+        if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+        if (fmt == FMT_E4M3FN) block_quant_1x128_kernel<FMT_E4M3FN><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(xp, rows, cols, ld, q, ld_q, e8m0, ld_e);
+        else block_quant_1x128_kernel<FMT_E5M2><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(xp, rows, cols, ld, q, ld_q, e8m0, ld_e);
+    } else {
+        const int64_t gy = (rows + 127) / 128;
+        if (gy > 65535) return hipErrorInvalidValue;
+        const dim3 grid((unsigned)(cols / 128), (unsigned)gy);
+        if (fmt == FMT_E4M3FN) block_quant_128x128_kernel<FMT_E4M3FN><<<grid, dim3(256), 0, st>>>(xp, rows, cols, ld, q, ld_q, e8m0, ld_e);
+        else block_quant_128x128_kernel<FMT_E5M2><<<grid, dim3(256), 0, st>>>(xp, rows, cols, ld, q, ld_q, e8m0, ld_e);
+    }
+    return hipGetLastError();
+}
+
 // MX block quantization with the blocks running DOWN the columns of x and the
 // output written transposed: qt [cols, rows] codes and et [cols, rows / 32] E8M0
 // bytes, i.e. the K-contiguous operand of a product that contracts over the

@@ -91,6 +91,12 @@ def load_library() -> C.CDLL:
     L.fp8_linear_bwd_sigmoid.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, vp, vp, C.c_size_t, vp]
     L.fp8_layernorm_quantize.restype = ci
     L.fp8_layernorm_quantize.argtypes = [vp, i64, i64, i64, vp, vp, C.c_double, ci, ci, vp, i64, vp, i64, vp, vp, vp, vp]
+    L.fp8_block_quantize.restype = ci
+    L.fp8_block_quantize.argtypes = [vp, i64, i64, i64, ci, ci, vp, i64, vp, i64, vp]
+    L.fp8_block_linear_workspace_bytes.restype = C.c_size_t
+    L.fp8_block_linear_workspace_bytes.argtypes = [i64, i64, i64]
+    L.fp8_block_linear_fwd.restype = ci
+    L.fp8_block_linear_fwd.argtypes = [vp, vp, i64, i64, i64, ci, ci, vp, vp, C.c_size_t, vp]
     L.fp8_mx_quantize.restype = ci
     L.fp8_mx_quantize.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp, i64, vp]
     L.fp8_mx_quantize_t.restype = ci
@@ -389,6 +395,45 @@ def fp8_mx_quantize(x: torch.Tensor, fmt: int, q: torch.Tensor | None = None, e8
     _, _, ld_e = _mat(e8m0, 1)
     _check(load_library().fp8_mx_quantize(_ptr(x), rows, cols, ld, fmt, _ptr(q), ld_q, _ptr(e8m0), ld_e, _stream()))
     return q, e8m0
+
+
+def fp8_block_quantize(x: torch.Tensor, block_rows: int, fmt: int, q: torch.Tensor | None = None,
+                       e8m0: torch.Tensor | None = None):
+    """Blockwise FP8: tiles of 1 x 128 (block_rows = 1) or blocks of 128 x 128 (block_rows = 128) with power-of-two
+    scales; codes [rows, cols] and E8M0 bytes [rows, cols / 32] in the layout of the MX scales."""
+    rows, cols, ld = _mat(x, 2)
+    if q is None:
+        q = _alloc_q(rows, cols, 0, x.device)
+    if e8m0 is None:
+        nb = cols // 32
+        e8m0 = torch.empty((rows, (nb + 3) // 4 * 4), dtype=torch.uint8, device=x.device)[:, :nb]
+    _, _, ld_q = _mat(q, 1)
+    _, _, ld_e = _mat(e8m0, 1)
+    _check(load_library().fp8_block_quantize(_ptr(x), rows, cols, ld, block_rows, fmt, _ptr(q), ld_q, _ptr(e8m0), ld_e,
+                                             _stream()))
+    return q, e8m0
+
+
+def fp8_block_linear_workspace_bytes(M: int, K: int, N: int) -> int:
+    n = load_library().fp8_block_linear_workspace_bytes(M, K, N)
+    if n == 0:
+        raise Fp8Error(-2, fp8_last_error())
+    return int(n)
+
+
+def fp8_block_linear_fwd(x: torch.Tensor, w: torch.Tensor, fmt_x: int = FP8_E4M3FN, fmt_w: int = FP8_E4M3FN,
+                         y: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Y = X W^T with X in tiles of 1 x 128 along K and W in blocks of 128 x 128 (blockwise FP8)."""
+    M, K = x.shape
+    N = w.shape[0]
+    assert w.shape == (N, K) and x.is_contiguous() and w.is_contiguous()
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(fp8_block_linear_workspace_bytes(M, K, N), dtype=torch.uint8, device=x.device)
+    _check(load_library().fp8_block_linear_fwd(_ptr(x), _ptr(w), M, K, N, fmt_x, fmt_w, _ptr(y), _ptr(workspace),
+                                               workspace.numel(), _stream()))
+    return y
 
 
 def fp8_mx_quantize_t(x: torch.Tensor, fmt: int, qt: torch.Tensor | None = None, e8m0_t: torch.Tensor | None = None):
