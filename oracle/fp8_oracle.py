@@ -345,6 +345,22 @@ def block_linear_fwd(x, w, fmt_x=E4M3FN, fmt_w=E4M3FN, rows=None) -> MMResult:
     return mx_mm(xq, fmt_x, xe, wq, fmt_w, we, rows)
 
 
+def block_linear_bwd(dy, x, w, fmt_dy=E4M3FN, fmt_x=E4M3FN, fmt_w=E4M3FN, rows_dx=None, rows_dw=None):
+    """Backward of the blockwise linear layer, each operand with its blocks along the contraction axis of
+    the product it feeds (the activation-like operands in tiles of 1 x 128 along that axis, the weight in
+    its 128 x 128 blocks):
+      dX[m,k] = sum_n dY[m,n] W[n,k]:  dY [M,N] in tiles along N, W^T [K,N] in blocks of 128 x 128;
+      dW[n,k] = sum_m dY[m,n] X[m,k]:  dY^T [N,M] and X^T [K,M] in tiles along M.
+    Returns (dx, dw) as MMResult; rows_dx / rows_dw select output rows."""
+    dyq, dye = block_quantize(dy, 1, 128, fmt_dy)
+    wtq, wte = block_quantize(np.ascontiguousarray(w.T), 128, 128, fmt_w)
+    dx = mx_mm(dyq, fmt_dy, dye, wtq, fmt_w, wte, rows_dx)
+    dytq, dyte = block_quantize(np.ascontiguousarray(dy.T), 1, 128, fmt_dy)
+    xtq, xte = block_quantize(np.ascontiguousarray(x.T), 1, 128, fmt_x)
+    dw = mx_mm(dytq, fmt_dy, dyte, xtq, fmt_x, xte, rows_dw)
+    return dx, dw
+
+
 def mx_value(code: int, fmt: int, e8m0: int) -> float:
     return float(lib().orc_mx_value(code, fmt, e8m0))
 

@@ -131,3 +131,30 @@ def test_blockwise_linear_equals_the_brute_force_sum_of_dequantized_products():
     # and it approximates the unquantized product to the accuracy of two e4m3 operands
     ref = si.bf16_bits_to_f32(x).astype(np.float64) @ si.bf16_bits_to_f32(w).astype(np.float64).T
     assert np.linalg.norm(want - ref) <= 0.06 * np.linalg.norm(ref)
+
+
+def test_blockwise_backward_equals_brute_force_and_square_blocks_transpose():
+    rng = np.random.default_rng(11)
+    M, K, N = 128, 256, 256
+    x = _bf16(rng.standard_normal((M, K)))
+    w = _bf16(rng.standard_normal((N, K)) * 0.02)
+    dy = _bf16(rng.standard_normal((M, N)) * 1e-3)
+    dx, dw = orc.block_linear_bwd(dy, x, w)
+    dec = orc.decode_table(orc.E4M3FN).astype(np.float64)
+
+    def deq(t, br):
+        q, e = orc.block_quantize(t, br, 128, orc.E4M3FN)
+        return dec[q] * 2.0 ** (e.astype(np.float64).repeat(32, axis=1) - 127)
+    # dX = deq(dY tiles along N) . deq(W^T blocks)^T ;  dW = deq(dY^T tiles along M) . deq(X^T tiles along M)^T
+    want_dx = deq(dy, 1) @ deq(np.ascontiguousarray(w.T), 128).T
+    want_dw = deq(np.ascontiguousarray(dy.T), 1) @ deq(np.ascontiguousarray(x.T), 1).T
+    assert np.allclose(dx.acc64, want_dx, rtol=1e-12, atol=0) and np.allclose(dw.acc64, want_dw, rtol=1e-12, atol=0)
+    # square blocks: the blockwise quantization of W^T is the transpose of that of W (codes and scale bytes)
+    q, e = orc.block_quantize(w, 128, 128, orc.E4M3FN)
+    qt, et = orc.block_quantize(np.ascontiguousarray(w.T), 128, 128, orc.E4M3FN)
+    assert (qt == q.T).all()
+    assert (et[::128, ::4] == e[::128, ::4].T).all()
+    # and both gradients approximate the unquantized ones to the accuracy of two e4m3 operands
+    f = lambda t: si.bf16_bits_to_f32(t).astype(np.float64)
+    assert np.linalg.norm(want_dx - f(dy) @ f(w)) <= 0.06 * np.linalg.norm(f(dy) @ f(w))
+    assert np.linalg.norm(want_dw - f(dy).T @ f(x)) <= 0.06 * np.linalg.norm(f(dy).T @ f(x))
