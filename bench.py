@@ -665,6 +665,16 @@ def main() -> int:
                 result["mx_linear_fwd_bwd"] = {"ms_per_step": round(ms, 4), "TFLOP/s": round(flop_step / (ms * 1e-3) / 1e12, 1),
                                                "note": "forward + backward with every operand in MX blocks along the contracted axis "
                                                        "(5 block-quantization passes, the gradient in both orientations from one read, + 3 block-scaled GEMMs)"}
+
+                def block_step():
+                    fp8.fp8_block_linear_fwd(x, w, y=y, workspace=wsm)
+                    fp8.fp8_block_linear_bwd(dy, x, w, dx=dx, dw=dw, workspace=wsb)
+                bqt = lambda inp, q, e: fp8.fp8_block_quantize_t(inp, 1, E4) if q is None else fp8.fp8_block_quantize_t(inp, 1, E4, q, e)
+                cast_leg("block_quant_dy_t_128x1", dy, bqt, M * N, 3)
+                ms = _event_time_ms(block_step, max(3, args.steps // 2), 2, torch)
+                result["block_linear_fwd_bwd"] = {"ms_per_step": round(ms, 4), "TFLOP/s": round(flop_step / (ms * 1e-3) / 1e12, 1),
+                                                  "note": "forward + backward of the blockwise recipe: 6 one-pass block quantizations (tiles of 1 x 128 "
+                                                          "along each product's contraction axis, the weight in 128 x 128 blocks) + 3 block-scaled GEMMs"}
                 del wsb
             del wsm
 

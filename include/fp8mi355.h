@@ -345,12 +345,28 @@ int fp8_mx_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, i
  * fp8_block_linear_fwd: Y = X W^T, X [M, K] in tiles of 1 x 128 along K, W [N, K] in
  *   blocks of 128 x 128; K % 128 == 0; y [M, N] bfloat16; workspace of
  *   fp8_block_linear_workspace_bytes(M, K, N) bytes, 256-byte aligned.
+ * fp8_block_quantize_t: the same conversion of the TRANSPOSED matrix, written
+ *   transposed: qt_out [cols, rows], e8m0_t_out [cols, rows / 32] equal
+ *   fp8_block_quantize of x^T with the given block_rows (1: tiles of 128 rows x 1
+ *   column of x; 128: blocks of 128 x 128, the same numbers as those of x itself).
+ *   rows % 128 == 0, cols % 8 == 0.  One pass over HBM.
+ * fp8_block_linear_bwd: dX [M, K] = dY W and dW [N, K] = dY^T X (bfloat16; either
+ *   may be NULL), each operand with its blocks along the contraction axis of the
+ *   product it feeds: dY in tiles along N and W^T in its 128 x 128 blocks for dX;
+ *   dY^T and X^T in tiles along M for dW.  M % 128 == 0, N % 128 == 0, K % 8 == 0;
+ *   workspace of fp8_block_linear_bwd_workspace_bytes bytes, 256-byte aligned.
  */
 int fp8_block_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int block_rows, int format,
                        uint8_t* q_out, int64_t ld_q, uint8_t* e8m0_out, int64_t ld_e, void* stream);
 size_t fp8_block_linear_workspace_bytes(int64_t M, int64_t K, int64_t N);
 int fp8_block_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N, int fmt_x, int fmt_w,
                          void* y, void* workspace, size_t workspace_bytes, void* stream);
+int fp8_block_quantize_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int block_rows, int format,
+                         uint8_t* qt_out, int64_t ld_q, uint8_t* e8m0_t_out, int64_t ld_e, void* stream);
+size_t fp8_block_linear_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N);
+int fp8_block_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int64_t K, int64_t N, int fmt_dy,
+                         int fmt_x, int fmt_w, void* dx, void* dw, void* workspace, size_t workspace_bytes,
+                         void* stream);
 
 #ifdef __cplusplus
 }

@@ -833,4 +833,65 @@ int fp8_mx_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, i
     return FP8_OK;
 }
 
+int fp8_block_quantize_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int block_rows, int format, uint8_t* qt_out,
+                         int64_t ld_q, uint8_t* e8m0_t_out, int64_t ld_e, void* stream) {
+    g_err[0] = 0;
+    const char* fn = "fp8_block_quantize_t";
+    if (!fmt_ok(format)) return fail(FP8_ERR_ENUM, "%s: unknown format %d", fn, format);
+    if (block_rows != 1 && block_rows != 128) return fail(FP8_ERR_ENUM, "%s: block_rows=%d must be 1 or 128", fn, block_rows);
+    if (int rc = check_bf16(fn, x, rows, cols, ld)) return rc;
+    if (rows % 128 != 0) return fail(FP8_ERR_SHAPE, "%s: rows=%lld must be a multiple of the block length 128", fn, (long long)rows);
+    if (cols % 8 != 0) return fail(FP8_ERR_SHAPE, "%s: cols=%lld must be a multiple of 8", fn, (long long)cols);
+    if (int rc = check_q_out(fn, qt_out, cols, rows, ld_q, 0)) return rc;
+    if (ld_e < rows / 32 || ld_e % 4 != 0) return fail(FP8_ERR_SHAPE, "%s: ld_e=%lld must be >= rows/32 and a multiple of 4", fn, (long long)ld_e);
+    if (rows > 0 && cols > 0 && !e8m0_t_out) return fail(FP8_ERR_NULL, "%s: e8m0_t_out is NULL", fn);
+    if (!aligned(e8m0_t_out, 4)) return fail(FP8_ERR_ALIGN, "%s: e8m0_t_out not 4-byte aligned", fn);
+    FP8_TRY(fp8k::launch_block_quant_t(x, rows, cols, ld, block_rows, format, qt_out, ld_q, e8m0_t_out, ld_e,
+                                       static_cast<hipStream_t>(stream)));
+    return FP8_OK;
+}
+
+size_t fp8_block_linear_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N) { return fp8_mx_linear_bwd_workspace_bytes(M, K, N); }
+
+int fp8_block_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int64_t K, int64_t N, int fmt_dy,
+                         int fmt_x, int fmt_w, void* dx, void* dw, void* workspace, size_t workspace_bytes, void* stream) {
+    g_err[0] = 0;
+    const char* fn = "fp8_block_linear_bwd";
+    if (!fmt_ok(fmt_dy) || !fmt_ok(fmt_x) || !fmt_ok(fmt_w)) return fail(FP8_ERR_ENUM, "%s: unknown fp8 format", fn);
+    if (int rc = check_mx_bwd_dims(fn, M, K, N)) return rc;
+    if (int rc = check_bf16("fp8_block_linear_bwd(dy)", dy, M, N, N)) return rc;
+    if (dx) if (int rc = check_bf16("fp8_block_linear_bwd(w)", w, N, K, K)) return rc;
+    if (dw) if (int rc = check_bf16("fp8_block_linear_bwd(x)", x, M, K, K)) return rc;
+    if (!dx && !dw) return FP8_OK;
+    if (M == 0 || N == 0 || K == 0) {
+        hipStream_t st0 = static_cast<hipStream_t>(stream);
+        if (dx && M > 0 && K > 0) FP8_TRY(fp8k::launch_fill_u32(static_cast<uint32_t*>(dx), M * K / 2, 0u, st0));
+        if (dw && N > 0 && K > 0) FP8_TRY(fp8k::launch_fill_u32(static_cast<uint32_t*>(dw), N * K / 2, 0u, st0));
+        return FP8_OK;
+    }
+    if (!workspace) return fail(FP8_ERR_NULL, "%s: workspace is NULL", fn);
+    if ((dx && !aligned(dx, 16)) || (dw && !aligned(dw, 16)) || !aligned(workspace, 256))
+        return fail(FP8_ERR_ALIGN, "%s: dx, dw (16) / workspace (256) misaligned", fn);
+    const MxBwdPlan p = plan_mx_bwd(M, K, N);
+    if (workspace_bytes < p.total) return fail(FP8_ERR_WORKSPACE, "%s: workspace %zu < %zu bytes", fn, workspace_bytes, p.total);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t* ws = static_cast<uint8_t*>(workspace);
+    // dX = dY W: dY in tiles along N, W^T [K, N] in its 128 x 128 blocks; dW = dY^T X: dY^T and X^T in tiles along M
+    if (dx) {
+        FP8_TRY(fp8k::launch_block_quant(dy, M, N, N, 1, fmt_dy, ws + p.dyq, N, ws + p.dye, N / 32, st));
+        FP8_TRY(fp8k::launch_block_quant_t(w, N, K, K, 128, fmt_w, ws + p.wtq, N, ws + p.wte, N / 32, st));
+    }
+    if (dw) {
+        FP8_TRY(fp8k::launch_block_quant_t(dy, M, N, N, 1, fmt_dy, ws + p.dytq, M, ws + p.dyte, M / 32, st));
+        FP8_TRY(fp8k::launch_block_quant_t(x, M, K, K, 1, fmt_x, ws + p.xtq, M, ws + p.xte, M / 32, st));
+    }
+    if (dx)
+        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dyq, N, fmt_dy, ws + p.dye, N / 32, ws + p.wtq, N, fmt_w, ws + p.wte, N / 32,
+                                        M, K, N, dx, K, 0, st));
+    if (dw)
+        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dytq, M, fmt_dy, ws + p.dyte, M / 32, ws + p.xtq, M, fmt_x, ws + p.xte, M / 32,
+                                        N, K, M, dw, K, 0, st));
+    return FP8_OK;
+}
+
 }  // extern "C"

@@ -1312,6 +1312,128 @@ __global__ __launch_bounds__(256) void mx_quant_t_kernel(const uint16_t* __restr
     }
 }
 
+// Blockwise FP8 of the TRANSPOSED matrix, written transposed: qt [cols, rows] and et [cols, rows / 32] are what
+// block_quant_* gives on x^T, i.e. the contraction-contiguous operands of the backward products.  rows % 128 == 0.
+//   SQUARE = false: tiles of 1 x 128 of x^T = 128 rows x 1 column of x (the activation-like operands of
+//     dW = dY^T X, whose contraction runs down the rows of dY and X): the column maxima over the tile's 128 rows
+//     come from the 8 rows of a thread, two cross-lane steps (4 thread rows of a wavefront) and LDS (4 wavefronts).
+//   SQUARE = true: blocks of 128 x 128 (the weight in dX = dY W; the same numbers as the forward's blocks of W).
+// Tile scheme, byte transpose, swizzled LDS tile and 128-bit streaming stores as in the transposing cast.
+template <int FMT, bool SQUARE>
+__global__ __launch_bounds__(256) void block_quant_t_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
+                                                             int64_t ld, uint8_t* __restrict__ qt, int64_t ld_t,
+                                                             uint8_t* __restrict__ et, int64_t ld_e, int nx, int ny) {
+    constexpr int TR = 128, SLOTS = TR / 8, PARTS = TR / 16;
+    __shared__ __attribute__((aligned(16))) uint2 tile[128 * SLOTS];
+    __shared__ uint32_t red[4][16][4];
+    __shared__ uint8_t ebytes[128];                                   // scale byte of each column of the tile
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4, wave = threadIdx.x >> 6;
+    constexpr int PX = 16, PY = 16;
+    const int pxc = (nx + PX - 1) / PX;
+    const int patch = blockIdx.x / (PX * PY), within = blockIdx.x % (PX * PY);
+    const int bx = (patch % pxc) * PX + within % PX, by = (patch / pxc) * PY + within / PX;
+    if (bx >= nx || by >= ny) return;
+    const int64_t r0 = (int64_t)bx * TR, c0 = (int64_t)by * 128;
+    const int64_t c = c0 + tx * 8;
+
+    uint4 v[8];
+    uint32_t m[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int64_t r = r0 + ty * 8 + j;                            // rows % 128 == 0: inside the matrix
+        v[j] = c + 8 <= cols ? load_stream(x + r * ld + c) : make_uint4(0, 0, 0, 0);   // cols % 8 == 0
+        m[0] = pk_absmax(m[0], v[j].x);
+        m[1] = pk_absmax(m[1], v[j].y);
+        m[2] = pk_absmax(m[2], v[j].z);
+        m[3] = pk_absmax(m[3], v[j].w);
+    }
+    float factor[8];
+    if constexpr (SQUARE) {
+        uint32_t a = pk_absmax(pk_absmax(m[0], m[1]), pk_absmax(m[2], m[3]));
+        a = wave_max_u32<64>(pk_fold(a));
+        if ((threadIdx.x & 63) == 0) red[wave][0][0] = a;
+        __syncthreads();
+        a = red[0][0][0];
+#pragma unroll
+        for (int w_ = 1; w_ < 4; ++w_) a = red[w_][0][0] > a ? red[w_][0][0] : a;
+        uint32_t byte;
+        const float s = pow2_block_scale<FMT>(a, byte);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) factor[e] = s;
+        if (threadIdx.x < 128) ebytes[threadIdx.x] = (uint8_t)byte;
+    } else {
+#pragma unroll
+        for (int off = 16; off <= 32; off <<= 1)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) m[i] = pk_absmax(m[i], (uint32_t)__shfl_xor((int)m[i], off, 64));
+        if ((threadIdx.x & 63) < 16) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[wave][tx][i] = m[i];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint32_t a = red[0][tx][i];
+#pragma unroll
+            for (int w_ = 1; w_ < 4; ++w_) a = pk_absmax(a, red[w_][tx][i]);
+            m[i] = a;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            uint32_t byte;
+            factor[e] = pow2_block_scale<FMT>((m[e >> 1] >> ((e & 1) * 16)) & 0x7FFFu, byte);
+            if (ty == 0) ebytes[tx * 8 + e] = (uint8_t)byte;
+        }
+    }
+
+    uint32_t w[8][2];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint2 b = cast8<FMT>(v[j], factor);
+        w[j][0] = b.x;
+        w[j][1] = b.y;
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint32_t lo[4], hi[4];
+        transpose4x4_bytes(w[0][h], w[1][h], w[2][h], w[3][h], lo);
+        transpose4x4_bytes(w[4][h], w[5][h], w[6][h], w[7][h], hi);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int cc = tx * 8 + h * 4 + i;  // output row inside the tile
+            tile[cc * SLOTS + (ty ^ (2 * (tx & 7)))] = make_uint2(lo[i], hi[i]);
+        }
+    }
+    __syncthreads();
+
+    const uint4* tile16 = reinterpret_cast<const uint4*>(tile);
+    constexpr int ROWS_PER_IT = 256 / PARTS;
+#pragma unroll
+    for (int it = 0; it < 128 / ROWS_PER_IT; ++it) {
+        const int cc = it * ROWS_PER_IT + (threadIdx.x / PARTS), p = threadIdx.x % PARTS;
+        const int64_t oc = c0 + cc;
+        if (oc >= cols) continue;
+        store_stream(qt + oc * ld_t + r0 + p * 16, tile16[cc * PARTS + (p ^ ((cc >> 3) & 7))]);
+    }
+    if (threadIdx.x < 128 && c0 + threadIdx.x < cols)                 // ld_e % 4 == 0 and (r0 / 32) % 4 == 0
+        *reinterpret_cast<uint32_t*>(et + (c0 + threadIdx.x) * ld_e + r0 / 32) = (uint32_t)ebytes[threadIdx.x] * 0x01010101u;
+}
+
+// block_rows: blocks of x^T, 1 (tiles of 1 x 128 of x^T) or 128 (128 x 128); rows % 128 == 0, cols % 8 == 0
+hipError_t launch_block_quant_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int block_rows, int fmt, uint8_t* qt,
+                                int64_t ld_t, uint8_t* et, int64_t ld_e, hipStream_t st) {
+    if (rows == 0 || cols == 0) return hipSuccess;
+    const int64_t gx = (cols + 127) / 128, gy = rows / 128;
+    const int64_t total = ((gy + 15) / 16) * ((gx + 15) / 16) * 256;
+    if (total > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+#define FP8K_BQT(FMT, SQ) block_quant_t_kernel<FMT, SQ><<<dim3((unsigned)total), dim3(256), 0, st>>>(xp, rows, cols, ld, qt, ld_t, et, ld_e, (int)gy, (int)gx)
+    if (fmt == FMT_E4M3FN) { if (block_rows == 128) FP8K_BQT(FMT_E4M3FN, true); else FP8K_BQT(FMT_E4M3FN, false); }
+    else { if (block_rows == 128) FP8K_BQT(FMT_E5M2, true); else FP8K_BQT(FMT_E5M2, false); }
+#undef FP8K_BQT
+    return hipGetLastError();
+}
+
 hipError_t launch_mx_quant_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, uint8_t* qt, int64_t ld_t,
                              uint8_t* et, int64_t ld_e, uint8_t* q_row, int64_t ld_row, uint8_t* e_row, int64_t ld_er,
                              hipStream_t st) {

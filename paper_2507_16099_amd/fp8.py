@@ -97,6 +97,12 @@ def load_library() -> C.CDLL:
     L.fp8_block_linear_workspace_bytes.argtypes = [i64, i64, i64]
     L.fp8_block_linear_fwd.restype = ci
     L.fp8_block_linear_fwd.argtypes = [vp, vp, i64, i64, i64, ci, ci, vp, vp, C.c_size_t, vp]
+    L.fp8_block_quantize_t.restype = ci
+    L.fp8_block_quantize_t.argtypes = [vp, i64, i64, i64, ci, ci, vp, i64, vp, i64, vp]
+    L.fp8_block_linear_bwd_workspace_bytes.restype = C.c_size_t
+    L.fp8_block_linear_bwd_workspace_bytes.argtypes = [i64, i64, i64]
+    L.fp8_block_linear_bwd.restype = ci
+    L.fp8_block_linear_bwd.argtypes = [vp, vp, vp, i64, i64, i64, ci, ci, ci, vp, vp, vp, C.c_size_t, vp]
     L.fp8_mx_quantize.restype = ci
     L.fp8_mx_quantize.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp, i64, vp]
     L.fp8_mx_quantize_t.restype = ci
@@ -434,6 +440,51 @@ def fp8_block_linear_fwd(x: torch.Tensor, w: torch.Tensor, fmt_x: int = FP8_E4M3
     _check(load_library().fp8_block_linear_fwd(_ptr(x), _ptr(w), M, K, N, fmt_x, fmt_w, _ptr(y), _ptr(workspace),
                                                workspace.numel(), _stream()))
     return y
+
+
+def fp8_block_quantize_t(x: torch.Tensor, block_rows: int, fmt: int, qt: torch.Tensor | None = None,
+                         e8m0_t: torch.Tensor | None = None):
+    """Blockwise FP8 of the transposed matrix, written transposed: codes [cols, rows], E8M0 bytes [cols, rows / 32]
+    (block_rows = 1: tiles of 128 rows x 1 column of x; 128: blocks of 128 x 128)."""
+    rows, cols, ld = _mat(x, 2)
+    if qt is None:
+        qt = _alloc_q(cols, rows, 0, x.device)
+    if e8m0_t is None:
+        nb = rows // 32
+        e8m0_t = torch.empty((cols, (nb + 3) // 4 * 4), dtype=torch.uint8, device=x.device)[:, :nb]
+    _, _, ld_q = _mat(qt, 1)
+    _, _, ld_e = _mat(e8m0_t, 1)
+    _check(load_library().fp8_block_quantize_t(_ptr(x), rows, cols, ld, block_rows, fmt, _ptr(qt), ld_q, _ptr(e8m0_t), ld_e,
+                                               _stream()))
+    return qt, e8m0_t
+
+
+def fp8_block_linear_bwd_workspace_bytes(M: int, K: int, N: int) -> int:
+    n = load_library().fp8_block_linear_bwd_workspace_bytes(M, K, N)
+    if n == 0:
+        raise Fp8Error(-2, fp8_last_error())
+    return int(n)
+
+
+def fp8_block_linear_bwd(dy: torch.Tensor, x: torch.Tensor, w: torch.Tensor, fmt_dy: int = FP8_E4M3FN,
+                         fmt_x: int = FP8_E4M3FN, fmt_w: int = FP8_E4M3FN, need_dx: bool = True, need_dw: bool = True,
+                         dx: torch.Tensor | None = None, dw: torch.Tensor | None = None,
+                         workspace: torch.Tensor | None = None):
+    """dX = dY W and dW = dY^T X of the blockwise linear layer (tiles of 1 x 128 along each product's contraction
+    axis, the weight in its 128 x 128 blocks)."""
+    M, N = dy.shape
+    K = x.shape[1]
+    assert x.shape == (M, K) and w.shape == (N, K) and dy.is_contiguous() and x.is_contiguous() and w.is_contiguous()
+    if need_dx and dx is None:
+        dx = torch.empty((M, K), dtype=torch.bfloat16, device=dy.device)
+    if need_dw and dw is None:
+        dw = torch.empty((N, K), dtype=torch.bfloat16, device=dy.device)
+    if workspace is None:
+        workspace = torch.empty(fp8_block_linear_bwd_workspace_bytes(M, K, N), dtype=torch.uint8, device=dy.device)
+    _check(load_library().fp8_block_linear_bwd(_ptr(dy), _ptr(x), _ptr(w), M, K, N, fmt_dy, fmt_x, fmt_w,
+                                               _ptr(dx) if need_dx else None, _ptr(dw) if need_dw else None,
+                                               _ptr(workspace), workspace.numel(), _stream()))
+    return dx, dw
 
 
 def fp8_mx_quantize_t(x: torch.Tensor, fmt: int, qt: torch.Tensor | None = None, e8m0_t: torch.Tensor | None = None):

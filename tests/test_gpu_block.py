@@ -130,3 +130,73 @@ def test_block_full_size_llama_ffn_forward_sampled_rows():
     got = host_bf16_bits(y[torch.from_numpy(rows).cuda()])
     assert orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want.out16)) <= TOL
     assert float((got == want.out16).mean()) > 0.97
+
+
+# ----------------------------------------------------------------- backward
+@pytest.mark.parametrize("rows,cols,ld", [(128, 8, 8), (128, 136, 136), (256, 384, 392), (384, 1000, 1000), (1024, 4096, 4096)])
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("br", [1, 128])
+def test_block_quantize_t_shapes(rows, cols, ld, br, fmt):
+    """Transposed output == the oracle's blockwise quantization of the transposed matrix."""
+    x = si.student_t_outlier_bf16((rows, cols), 3.0, 0.01, 100.0, seed=8, stream=rows + br)
+    x[:128, 0] = 0                           # an all-zero tile of 128 rows x 1 column
+    x[:, cols - 1] = 0x8000
+    qt, et = fp8.fp8_block_quantize_t(dev_bf16(x, ld), br, fmt)
+    wq, we = orc.block_quantize(np.ascontiguousarray(x.T), br, 128, fmt)
+    ge, gq = host_u8(et), host_u8(qt)
+    assert (ge == we).all(), (np.argwhere(ge != we)[:4], ge[ge != we][:4], we[ge != we][:4])
+    assert (gq == wq).all(), np.argwhere(gq != wq)[:4]
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+def test_block_quantize_t_every_magnitude_as_maximum(fmt):
+    mags = np.arange(0, 0x7F80, dtype=np.uint16)
+    rng = np.random.default_rng(12)
+    xt = np.zeros((mags.size, 128), np.uint16)                          # x^T: one tile of 1 x 128 per row
+    xt[np.arange(mags.size), rng.integers(0, 128, mags.size)] = mags | (rng.integers(0, 2, mags.size).astype(np.uint16) << 15)
+    x = np.ascontiguousarray(xt.T)                                      # [128, 32640]
+    qt, et = fp8.fp8_block_quantize_t(dev_bf16(x), 1, fmt)
+    wq, we = orc.block_quantize(xt, 1, 128, fmt)
+    assert (host_u8(et) == we).all() and (host_u8(qt) == wq).all()
+
+
+@pytest.mark.parametrize("M,N,K", [(128, 128, 128), (128, 256, 136), (384, 128, 520), (256, 384, 1000), (1024, 768, 512)])
+def test_block_linear_backward(M, N, K):
+    wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)
+    x, w, dy = wl.x(), wl.w(), wl.dy()
+    dx, dw = fp8.fp8_block_linear_bwd(dev_bf16(dy), dev_bf16(x), dev_bf16(w))
+    wx, ww = orc.block_linear_bwd(dy, x, w)
+    for got_t, want in ((dx, wx), (dw, ww)):
+        got = host_bf16_bits(got_t)
+        assert orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want.out16)) <= TOL
+        assert float((got == want.out16).mean()) > 0.97
+    # one output only: the same bits
+    a, none = fp8.fp8_block_linear_bwd(dev_bf16(dy), dev_bf16(x), dev_bf16(w), need_dw=False)
+    assert none is None and torch.equal(a.view(torch.int16), dx.view(torch.int16))
+    none, b = fp8.fp8_block_linear_bwd(dev_bf16(dy), dev_bf16(x), dev_bf16(w), need_dx=False)
+    assert none is None and torch.equal(b.view(torch.int16), dw.view(torch.int16))
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_block_linear_bwd_workspace_bytes(M + 64, K, N)          # M % 128
+
+
+def test_block_full_size_llama_ffn_backward_sampled_rows():
+    """Benchmark shape: the four re-quantized operands bit for bit on the whole tensors, both gradients on a
+    stratified sample of output rows."""
+    wl = si.WORKLOADS[si.BENCH_WORKLOAD]
+    x, w, dy = wl.x(), wl.w(), wl.dy()
+    xd, wd, dyd = dev_bf16(x), dev_bf16(w), dev_bf16(dy)
+    for name, src, host, br in (("w", wd, w, 128), ("x", xd, x, 1), ("dy", dyd, dy, 1)):
+        qt, et = fp8.fp8_block_quantize_t(src, br, fp8.FP8_E4M3FN)
+        oq, oe = orc.block_quantize(np.ascontiguousarray(host.T), br, 128, orc.E4M3FN)
+        assert (host_u8(qt) == oq).all() and (host_u8(et) == oe).all(), name
+        del qt, et, oq, oe
+    q, e = fp8.fp8_block_quantize(dyd, 1, fp8.FP8_E4M3FN)
+    oq, oe = orc.block_quantize(dy, 1, 128, orc.E4M3FN)
+    assert (host_u8(q) == oq).all() and (host_u8(e) == oe).all()
+    del q, e, oq, oe
+    dx, dw = fp8.fp8_block_linear_bwd(dyd, xd, wd)
+    rx, rw = si.stratified_rows(wl.M, 16), si.stratified_rows(wl.N, 16)
+    wx, ww = orc.block_linear_bwd(dy, x, w, rows_dx=rx, rows_dw=rw)
+    for got, want in ((host_bf16_bits(dx[torch.from_numpy(rx).cuda()]), wx), (host_bf16_bits(dw[torch.from_numpy(rw).cuda()]), ww)):
+        assert orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want.out16)) <= TOL
+        assert float((got == want.out16).mean()) > 0.97

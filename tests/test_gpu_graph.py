@@ -19,7 +19,7 @@ def _bits(t):
 
 
 @pytest.mark.parametrize("recipe", ["rowwise", "rowwise_saved", "tensorwise", "tensorwise_saved", "rowwise_gw_hp", "mx",
-                                    "rowwise_sigmoid"])
+                                    "rowwise_sigmoid", "block"])
 def test_step_replays_from_a_hip_graph(recipe):
     M, K, N = 1024, 512, 768
     wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)
@@ -31,7 +31,14 @@ def test_step_replays_from_a_hip_graph(recipe):
     y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     dx = torch.empty((M, K), dtype=torch.bfloat16, device="cuda")
     dw = torch.empty((N, K), dtype=torch.bfloat16, device="cuda")
-    if recipe == "mx":
+    if recipe == "block":
+        ws_f = torch.empty(fp8.fp8_block_linear_workspace_bytes(M, K, N), dtype=torch.uint8, device="cuda")
+        ws_b = torch.empty(fp8.fp8_block_linear_bwd_workspace_bytes(M, K, N), dtype=torch.uint8, device="cuda")
+
+        def step():
+            fp8.fp8_block_linear_fwd(x, w, y=y, workspace=ws_f)
+            fp8.fp8_block_linear_bwd(dy, x, w, dx=dx, dw=dw, workspace=ws_b)
+    elif recipe == "mx":
         ws_f = torch.empty(fp8.fp8_mx_linear_workspace_bytes(M, K, N), dtype=torch.uint8, device="cuda")
         ws_b = torch.empty(fp8.fp8_mx_linear_bwd_workspace_bytes(M, K, N), dtype=torch.uint8, device="cuda")
 
