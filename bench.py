@@ -673,8 +673,9 @@ def main() -> int:
                 cast_leg("block_quant_dy_t_128x1", dy, bqt, M * N, 3)
                 ms = _event_time_ms(block_step, max(3, args.steps // 2), 2, torch)
                 result["block_linear_fwd_bwd"] = {"ms_per_step": round(ms, 4), "TFLOP/s": round(flop_step / (ms * 1e-3) / 1e12, 1),
-                                                  "note": "forward + backward of the blockwise recipe: 6 one-pass block quantizations (tiles of 1 x 128 "
-                                                          "along each product's contraction axis, the weight in 128 x 128 blocks) + 3 block-scaled GEMMs"}
+                                                  "note": "forward + backward of the blockwise recipe: 5 one-pass block quantizations (tiles of 1 x 128 "
+                                                          "along each product's contraction axis, the weight in 128 x 128 blocks, the gradient in both "
+                                                          "orientations from one read) + 3 block-scaled GEMMs"}
                 del wsb
             del wsm
 

@@ -350,6 +350,10 @@ int fp8_mx_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, i
  *   fp8_block_quantize of x^T with the given block_rows (1: tiles of 128 rows x 1
  *   column of x; 128: blocks of 128 x 128, the same numbers as those of x itself).
  *   rows % 128 == 0, cols % 8 == 0.  One pass over HBM.
+ * fp8_block_quantize_row_col: the tiles of 1 x 128 along the rows of x (q_row,
+ *   e_row as fp8_block_quantize(block_rows = 1) writes them) and the tiles of
+ *   128 x 1 down its columns, transposed (q_col_t, e_col_t as fp8_block_quantize_t
+ *   (block_rows = 1) does) from ONE read of x; rows % 128 == 0, cols % 128 == 0.
  * fp8_block_linear_bwd: dX [M, K] = dY W and dW [N, K] = dY^T X (bfloat16; either
  *   may be NULL), each operand with its blocks along the contraction axis of the
  *   product it feeds: dY in tiles along N and W^T in its 128 x 128 blocks for dX;
@@ -363,6 +367,9 @@ int fp8_block_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int
                          void* y, void* workspace, size_t workspace_bytes, void* stream);
 int fp8_block_quantize_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int block_rows, int format,
                          uint8_t* qt_out, int64_t ld_q, uint8_t* e8m0_t_out, int64_t ld_e, void* stream);
+int fp8_block_quantize_row_col(const void* x, int64_t rows, int64_t cols, int64_t ld, int format,
+                               uint8_t* q_row, int64_t ld_row, uint8_t* e_row, int64_t ld_er,
+                               uint8_t* q_col_t, int64_t ld_col_t, uint8_t* e_col_t, int64_t ld_ec, void* stream);
 size_t fp8_block_linear_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N);
 int fp8_block_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int64_t K, int64_t N, int fmt_dy,
                          int fmt_x, int fmt_w, void* dx, void* dw, void* workspace, size_t workspace_bytes,

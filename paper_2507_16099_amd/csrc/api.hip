@@ -851,6 +851,26 @@ int fp8_block_quantize_t(const void* x, int64_t rows, int64_t cols, int64_t ld, 
     return FP8_OK;
 }
 
+int fp8_block_quantize_row_col(const void* x, int64_t rows, int64_t cols, int64_t ld, int format, uint8_t* q_row,
+                               int64_t ld_row, uint8_t* e_row, int64_t ld_er, uint8_t* q_col_t, int64_t ld_col_t,
+                               uint8_t* e_col_t, int64_t ld_ec, void* stream) {
+    g_err[0] = 0;
+    const char* fn = "fp8_block_quantize_row_col";
+    if (!fmt_ok(format)) return fail(FP8_ERR_ENUM, "%s: unknown format %d", fn, format);
+    if (int rc = check_bf16(fn, x, rows, cols, ld)) return rc;
+    if (rows % 128 != 0 || cols % 128 != 0)
+        return fail(FP8_ERR_SHAPE, "%s: rows=%lld and cols=%lld must be multiples of the tile length 128", fn, (long long)rows, (long long)cols);
+    if (int rc = check_q_out(fn, q_row, rows, cols, ld_row, 0)) return rc;
+    if (int rc = check_q_out(fn, q_col_t, cols, rows, ld_col_t, 0)) return rc;
+    if (ld_er < cols / 32 || ld_er % 4 != 0 || ld_ec < rows / 32 || ld_ec % 4 != 0)
+        return fail(FP8_ERR_SHAPE, "%s: ld_er=%lld / ld_ec=%lld must cover cols/32 / rows/32 and be multiples of 4", fn, (long long)ld_er, (long long)ld_ec);
+    if (rows > 0 && cols > 0 && (!e_row || !e_col_t)) return fail(FP8_ERR_NULL, "%s: a scale output is NULL", fn);
+    if (!aligned(e_row, 4) || !aligned(e_col_t, 4)) return fail(FP8_ERR_ALIGN, "%s: scale outputs not 4-byte aligned", fn);
+    FP8_TRY(fp8k::launch_block_quant_t(x, rows, cols, ld, 1, format, q_col_t, ld_col_t, e_col_t, ld_ec, static_cast<hipStream_t>(stream),
+                                       q_row, ld_row, e_row, ld_er));
+    return FP8_OK;
+}
+
 size_t fp8_block_linear_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N) { return fp8_mx_linear_bwd_workspace_bytes(M, K, N); }
 
 int fp8_block_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int64_t K, int64_t N, int fmt_dy,
@@ -877,14 +897,15 @@ int fp8_block_linear_bwd(const void* dy, const void* x, const void* w, int64_t M
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* ws = static_cast<uint8_t*>(workspace);
     // dX = dY W: dY in tiles along N, W^T [K, N] in its 128 x 128 blocks; dW = dY^T X: dY^T and X^T in tiles along M
-    if (dx) {
+    if (dx && dw) {   // the gradient in both orientations from one read
+        FP8_TRY(fp8k::launch_block_quant_t(dy, M, N, N, 1, fmt_dy, ws + p.dytq, M, ws + p.dyte, M / 32, st, ws + p.dyq, N, ws + p.dye, N / 32));
+    } else if (dx) {
         FP8_TRY(fp8k::launch_block_quant(dy, M, N, N, 1, fmt_dy, ws + p.dyq, N, ws + p.dye, N / 32, st));
-        FP8_TRY(fp8k::launch_block_quant_t(w, N, K, K, 128, fmt_w, ws + p.wtq, N, ws + p.wte, N / 32, st));
-    }
-    if (dw) {
+    } else {
         FP8_TRY(fp8k::launch_block_quant_t(dy, M, N, N, 1, fmt_dy, ws + p.dytq, M, ws + p.dyte, M / 32, st));
-        FP8_TRY(fp8k::launch_block_quant_t(x, M, K, K, 1, fmt_x, ws + p.xtq, M, ws + p.xte, M / 32, st));
     }
+    if (dx) FP8_TRY(fp8k::launch_block_quant_t(w, N, K, K, 128, fmt_w, ws + p.wtq, N, ws + p.wte, N / 32, st));
+    if (dw) FP8_TRY(fp8k::launch_block_quant_t(x, M, K, K, 1, fmt_x, ws + p.xtq, M, ws + p.xte, M / 32, st));
     if (dx)
         FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dyq, N, fmt_dy, ws + p.dye, N / 32, ws + p.wtq, N, fmt_w, ws + p.wte, N / 32,
                                         M, K, N, dx, K, 0, st));

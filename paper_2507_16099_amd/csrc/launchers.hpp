@@ -26,8 +26,10 @@ hipError_t launch_quant_tensor(const void* x, int64_t rows, int64_t cols, int fm
 hipError_t launch_block_quant(const void* x, int64_t rows, int64_t cols, int64_t ld, int block_rows, int fmt, uint8_t* q,
                               int64_t ld_q, uint8_t* e8m0, int64_t ld_e, hipStream_t st);
 // the same of the transposed matrix, written transposed (rows % 128 == 0, cols % 8 == 0)
+// q_row / e_row (optional, block_rows == 1, cols % 128 == 0): the tiles along the rows of x from the same read
 hipError_t launch_block_quant_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int block_rows, int fmt, uint8_t* qt,
-                                int64_t ld_t, uint8_t* et, int64_t ld_e, hipStream_t st);
+                                int64_t ld_t, uint8_t* et, int64_t ld_e, hipStream_t st, uint8_t* q_row = nullptr,
+                                int64_t ld_row = 0, uint8_t* e_row = nullptr, int64_t ld_er = 0);
 hipError_t launch_scale(const float* amax, int64_t n, int fmt, int flags, float* out, hipStream_t st);
 
 // transpose != 0: q is [cols, rows]; q_plain (optional, transpose only) also

@@ -1319,10 +1319,16 @@ __global__ __launch_bounds__(256) void mx_quant_t_kernel(const uint16_t* __restr
 //     come from the 8 rows of a thread, two cross-lane steps (4 thread rows of a wavefront) and LDS (4 wavefronts).
 //   SQUARE = true: blocks of 128 x 128 (the weight in dX = dY W; the same numbers as the forward's blocks of W).
 // Tile scheme, byte transpose, swizzled LDS tile and 128-bit streaming stores as in the transposing cast.
-template <int FMT, bool SQUARE>
+// ROWS_TOO (with SQUARE = false, cols % 128 == 0): the same read also yields the tiles of 1 x 128 ALONG the rows
+// of x (q_row [rows, cols], e_row [rows, cols / 32]): the 16 threads that hold a row of the tile combine their
+// maxima with four cross-lane steps.  The gradient, needed in both orientations by the backward, then costs
+// 4 bytes of HBM traffic per element instead of 6.
+template <int FMT, bool SQUARE, bool ROWS_TOO = false>
 __global__ __launch_bounds__(256) void block_quant_t_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
                                                              int64_t ld, uint8_t* __restrict__ qt, int64_t ld_t,
-                                                             uint8_t* __restrict__ et, int64_t ld_e, int nx, int ny) {
+                                                             uint8_t* __restrict__ et, int64_t ld_e, int nx, int ny,
+                                                             uint8_t* __restrict__ q_row = nullptr, int64_t ld_row = 0,
+                                                             uint8_t* __restrict__ e_row = nullptr, int64_t ld_er = 0) {
     constexpr int TR = 128, SLOTS = TR / 8, PARTS = TR / 16;
     __shared__ __attribute__((aligned(16))) uint2 tile[128 * SLOTS];
     __shared__ uint32_t red[4][16][4];
@@ -1346,6 +1352,22 @@ __global__ __launch_bounds__(256) void block_quant_t_kernel(const uint16_t* __re
         m[1] = pk_absmax(m[1], v[j].y);
         m[2] = pk_absmax(m[2], v[j].z);
         m[3] = pk_absmax(m[3], v[j].w);
+    }
+    if constexpr (ROWS_TOO) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            uint32_t mr = pk_fold(pk_absmax4(0u, v[j]));
+#pragma unroll
+            for (int off = 1; off <= 8; off <<= 1) {
+                const uint32_t o = (uint32_t)__shfl_xor((int)mr, off, 64);
+                mr = o > mr ? o : mr;
+            }
+            uint32_t byte;
+            const float sr = pow2_block_scale<FMT>(mr, byte);
+            const int64_t r = r0 + ty * 8 + j;
+            store_stream(q_row + r * ld_row + c, cast8<FMT>(v[j], sr));                   // cols % 128 == 0: inside
+            if (tx == 0) *reinterpret_cast<uint32_t*>(e_row + r * ld_er + (c0 >> 5)) = byte * 0x01010101u;
+        }
     }
     float factor[8];
     if constexpr (SQUARE) {
@@ -1419,17 +1441,22 @@ __global__ __launch_bounds__(256) void block_quant_t_kernel(const uint16_t* __re
         *reinterpret_cast<uint32_t*>(et + (c0 + threadIdx.x) * ld_e + r0 / 32) = (uint32_t)ebytes[threadIdx.x] * 0x01010101u;
 }
 
-// block_rows: blocks of x^T, 1 (tiles of 1 x 128 of x^T) or 128 (128 x 128); rows % 128 == 0, cols % 8 == 0
+// block_rows: blocks of x^T, 1 (tiles of 1 x 128 of x^T) or 128 (128 x 128); rows % 128 == 0, cols % 8 == 0.
+// q_row != nullptr (block_rows == 1, cols % 128 == 0): also the tiles of 1 x 128 along the rows of x.
 hipError_t launch_block_quant_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int block_rows, int fmt, uint8_t* qt,
-                                int64_t ld_t, uint8_t* et, int64_t ld_e, hipStream_t st) {
+                                int64_t ld_t, uint8_t* et, int64_t ld_e, hipStream_t st, uint8_t* q_row, int64_t ld_row,
+                                uint8_t* e_row, int64_t ld_er) {
     if (rows == 0 || cols == 0) return hipSuccess;
     const int64_t gx = (cols + 127) / 128, gy = rows / 128;
     const int64_t total = ((gy + 15) / 16) * ((gx + 15) / 16) * 256;
     if (total > 0x7FFFFFFF) return hipErrorInvalidValue;
     const uint16_t* xp = static_cast<const uint16_t*>(x);
-#define FP8K_BQT(FMT, SQ) block_quant_t_kernel<FMT, SQ><<<dim3((unsigned)total), dim3(256), 0, st>>>(xp, rows, cols, ld, qt, ld_t, et, ld_e, (int)gy, (int)gx)
-    if (fmt == FMT_E4M3FN) { if (block_rows == 128) FP8K_BQT(FMT_E4M3FN, true); else FP8K_BQT(FMT_E4M3FN, false); }
-    else { if (block_rows == 128) FP8K_BQT(FMT_E5M2, true); else FP8K_BQT(FMT_E5M2, false); }
+#define FP8K_BQT(FMT, SQ, RT) block_quant_t_kernel<FMT, SQ, RT><<<dim3((unsigned)total), dim3(256), 0, st>>>(xp, rows, cols, ld, qt, ld_t, et, ld_e, (int)gy, (int)gx, q_row, ld_row, e_row, ld_er)
+    if (q_row != nullptr) {
+        if (block_rows != 1 || cols % 128 != 0) return hipErrorInvalidValue;
+        if (fmt == FMT_E4M3FN) FP8K_BQT(FMT_E4M3FN, false, true); else FP8K_BQT(FMT_E5M2, false, true);
+    } else if (fmt == FMT_E4M3FN) { if (block_rows == 128) FP8K_BQT(FMT_E4M3FN, true, false); else FP8K_BQT(FMT_E4M3FN, false, false); }
+    else { if (block_rows == 128) FP8K_BQT(FMT_E5M2, true, false); else FP8K_BQT(FMT_E5M2, false, false); }
 #undef FP8K_BQT
     return hipGetLastError();
 }

@@ -103,6 +103,8 @@ def load_library() -> C.CDLL:
     L.fp8_block_linear_bwd_workspace_bytes.argtypes = [i64, i64, i64]
     L.fp8_block_linear_bwd.restype = ci
     L.fp8_block_linear_bwd.argtypes = [vp, vp, vp, i64, i64, i64, ci, ci, ci, vp, vp, vp, C.c_size_t, vp]
+    L.fp8_block_quantize_row_col.restype = ci
+    L.fp8_block_quantize_row_col.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp, i64, vp, i64, vp, i64, vp]
     L.fp8_mx_quantize.restype = ci
     L.fp8_mx_quantize.argtypes = [vp, i64, i64, i64, ci, vp, i64, vp, i64, vp]
     L.fp8_mx_quantize_t.restype = ci
@@ -515,6 +517,23 @@ def fp8_mx_quantize_row_col(x: torch.Tensor, fmt: int, out=None):
     _check(load_library().fp8_mx_quantize_row_col(_ptr(x), rows, cols, ld, fmt, _ptr(q_row), _mat(q_row, 1)[2], _ptr(e_row),
                                                   _mat(e_row, 1)[2], _ptr(q_col_t), _mat(q_col_t, 1)[2], _ptr(e_col_t),
                                                   _mat(e_col_t, 1)[2], _stream()))
+    return q_row, e_row, q_col_t, e_col_t
+
+
+def fp8_block_quantize_row_col(x: torch.Tensor, fmt: int, out=None):
+    """Blockwise tiles of 1 x 128 along the rows and, transposed, of 128 x 1 down the columns from one read:
+    (q_row [rows, cols], e_row [rows, cols/32], q_col_t [cols, rows], e_col_t [cols, rows/32])."""
+    rows, cols, ld = _mat(x, 2)
+    if out is None:
+        nb_r, nb_c = cols // 32, rows // 32
+        out = (_alloc_q(rows, cols, 0, x.device),
+               torch.empty((rows, (nb_r + 3) // 4 * 4), dtype=torch.uint8, device=x.device)[:, :nb_r],
+               _alloc_q(cols, rows, 0, x.device),
+               torch.empty((cols, (nb_c + 3) // 4 * 4), dtype=torch.uint8, device=x.device)[:, :nb_c])
+    q_row, e_row, q_col_t, e_col_t = out
+    _check(load_library().fp8_block_quantize_row_col(_ptr(x), rows, cols, ld, fmt, _ptr(q_row), _mat(q_row, 1)[2], _ptr(e_row),
+                                                     _mat(e_row, 1)[2], _ptr(q_col_t), _mat(q_col_t, 1)[2], _ptr(e_col_t),
+                                                     _mat(e_col_t, 1)[2], _stream()))
     return q_row, e_row, q_col_t, e_col_t
 
 

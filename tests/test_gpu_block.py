@@ -160,6 +160,21 @@ def test_block_quantize_t_every_magnitude_as_maximum(fmt):
     assert (host_u8(et) == we).all() and (host_u8(qt) == wq).all()
 
 
+@pytest.mark.parametrize("rows,cols,ld", [(128, 128, 128), (256, 384, 392), (384, 1024, 1024), (1024, 4096, 4096)])
+@pytest.mark.parametrize("fmt", FMTS)
+def test_block_quantize_row_col_from_one_read(rows, cols, ld, fmt):
+    x = si.student_t_outlier_bf16((rows, cols), 3.0, 0.01, 100.0, seed=9, stream=rows)
+    x[5, :128] = 0
+    x[:128, 7] = 0x8000
+    q_row, e_row, q_col_t, e_col_t = fp8.fp8_block_quantize_row_col(dev_bf16(x, ld), fmt)
+    wq, we = orc.block_quantize(x, 1, 128, fmt)
+    assert (host_u8(e_row) == we).all() and (host_u8(q_row) == wq).all()
+    wq, we = orc.block_quantize(np.ascontiguousarray(x.T), 1, 128, fmt)
+    assert (host_u8(e_col_t) == we).all() and (host_u8(q_col_t) == wq).all()
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_block_quantize_row_col(dev_bf16(x[:, :cols - 64] if cols > 128 else x[:64]), fmt)   # a dimension not % 128
+
+
 @pytest.mark.parametrize("M,N,K", [(128, 128, 128), (128, 256, 136), (384, 128, 520), (256, 384, 1000), (1024, 768, 512)])
 def test_block_linear_backward(M, N, K):
     wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)
@@ -190,10 +205,12 @@ def test_block_full_size_llama_ffn_backward_sampled_rows():
         oq, oe = orc.block_quantize(np.ascontiguousarray(host.T), br, 128, orc.E4M3FN)
         assert (host_u8(qt) == oq).all() and (host_u8(et) == oe).all(), name
         del qt, et, oq, oe
-    q, e = fp8.fp8_block_quantize(dyd, 1, fp8.FP8_E4M3FN)
+    q, e, qt, et = fp8.fp8_block_quantize_row_col(dyd, fp8.FP8_E4M3FN)          # the gradient, one read
     oq, oe = orc.block_quantize(dy, 1, 128, orc.E4M3FN)
     assert (host_u8(q) == oq).all() and (host_u8(e) == oe).all()
-    del q, e, oq, oe
+    oq, oe = orc.block_quantize(np.ascontiguousarray(dy.T), 1, 128, orc.E4M3FN)
+    assert (host_u8(qt) == oq).all() and (host_u8(et) == oe).all()
+    del q, e, qt, et, oq, oe
     dx, dw = fp8.fp8_block_linear_bwd(dyd, xd, wd)
     rx, rw = si.stratified_rows(wl.M, 16), si.stratified_rows(wl.N, 16)
     wx, ww = orc.block_linear_bwd(dy, x, w, rows_dx=rx, rows_dw=rw)
