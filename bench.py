@@ -275,11 +275,47 @@ def _data_probe(torch, fp8, dev, iters: int) -> dict:
     }
     rows = {}
     for name, (a, b) in cases.items():
-        best = min(_event_time_ms(lambda: fp8.fp8_scaled_mm(a, 0, sa, fp8.FP8_ROW, b, 0, sb, fp8.FP8_ROW, 0, out=out), iters, 3, torch)
-                   for _ in range(3))
+        run = lambda: fp8.fp8_scaled_mm(a, 0, sa, fp8.FP8_ROW, b, 0, sb, fp8.FP8_ROW, 0, out=out)
+        best = min(_event_time_ms(run, iters, 3, torch) for _ in range(3))
         rows[name] = {"ms": round(best, 4), "TFLOP/s": round(2.0 * M * N * K / (best * 1e-3) / 1e12, 1),
                       "frac_of_fp8_peak": round(2.0 * M * N * K / (best * 1e-3) / 1e12 / FP8_PEAK_TFLOPS, 4)}
-    return {"data_probe": f"forward GEMM M={M} K={K} N={N}, same kernel, operands of different bit activity", "rows": rows}
+        clk = _shader_clock_under_load(run, torch)
+        if clk:
+            rows[name]["shader_clock_MHz_under_load"] = clk
+    return {"data_probe": f"forward GEMM M={M} K={K} N={N}, same kernel, operands of different bit activity; the shader clock is "
+                          "what rocm-smi reports while the kernel runs back to back for 1.5 s (nominal 2400 MHz)", "rows": rows}
+
+
+def _shader_clock_under_load(run, torch, seconds: float = 1.5):
+    """Median of the shader clock that `rocm-smi --showclocks` reports while run() is launched back to
+    back (None if the tool is not there or prints something else)."""
+    import re
+    import subprocess
+    import threading
+    import time
+    samples, stop = [], threading.Event()
+
+    def poll():
+        while not stop.is_set():
+            try:
+                out = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=10).stdout
+                m = re.search(r'"sclk clock speed:"\s*:\s*"\((\d+)Mhz\)"', out)
+                if m:
+                    samples.append(int(m.group(1)))
+            except (OSError, subprocess.SubprocessError):
+                return
+            time.sleep(0.1)
+    th = threading.Thread(target=poll)
+    th.start()
+    t0 = time.time()
+    while time.time() - t0 < seconds:
+        for _ in range(20):
+            run()
+        torch.cuda.synchronize()
+    stop.set()
+    th.join()
+    samples = sorted(samples[1:])          # the first sample may predate the load
+    return samples[len(samples) // 2] if samples else None
 
 
 def _decode(torch, fp8, dev, iters: int) -> dict:
@@ -555,6 +591,7 @@ def main() -> int:
         copy_leg()
 
         fwd_ms, fwd_tf = gemm_leg("gemm_fwd", xq, E4, sx, wq, E4, sw, y)
+        fwd_clock = _shader_clock_under_load(lambda: fp8.fp8_scaled_mm(xq, E4, sx, gran, wq, E4, sw, gran, 0, out=y), torch, 1.0)
         tag = "row" if rowwise else "tensor"
         bpe = 3 if rowwise else 5
         cast_leg(f"quant_x_{tag}", x, q_fn(gran, E4, fl), M * K, bpe)
@@ -710,7 +747,11 @@ def main() -> int:
         result["roofline"] = {"kernel": "forward scaled GEMM (gemm_fp8_snake_kernel<e4m3,e4m3,bf16>)", "bound": "mfma",
                               "achieved": round(fwd_tf, 1), "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
                               "frac": round(fwd_tf / FP8_PEAK_TFLOPS, 4), "traffic": _profiled_traffic(wl.name),
-                              "flop_per_launch": 2.0 * M * N * K, "avg_launch_ms": round(fwd_ms, 4)}
+                              "flop_per_launch": 2.0 * M * N * K, "avg_launch_ms": round(fwd_ms, 4),
+                              "shader_clock_MHz_under_load": fwd_clock,
+                              "note": "the shader clock is what rocm-smi reports while this kernel runs back to back (nominal 2400 MHz: "
+                                      "the published peak assumes it); on operands that do not toggle the same launch holds 2.4 GHz and "
+                                      "0.71 of the peak (bench.py --data-probe)"}
 
     # ------------------------------------------------ CPU oracle baseline
     if not args.no_cpu_baseline:
