@@ -293,6 +293,8 @@ def _shader_clock_under_load(run, torch, seconds: float = 1.5):
     import subprocess
     import threading
     import time
+    if any(k.startswith(("ROCP_", "ROCPROF")) for k in os.environ):
+        return None                      # under a profiler: its environment would reach the child process too
     samples, stop = [], threading.Event()
 
     def poll():
