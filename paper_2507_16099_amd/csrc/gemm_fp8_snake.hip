@@ -41,6 +41,7 @@
 #include "fp8_device.hpp"
 #include "launchers.hpp"
 
+#include <cstdlib>
 #include <type_traits>
 
 namespace fp8k {
@@ -86,20 +87,30 @@ __device__ __forceinline__ float sn_sigmoid(float x) { return __builtin_amdgcn_r
 
 // ACT (bfloat16 output only): out = bfloat16(sigmoid(dequantized product)), the activation behind the
 // linear layer in the paper's float8 microbenchmark, applied to the fp32 value before it is rounded
-template <int FA, int FB, bool OUT_F32, bool ACT = false>
+//
+// HALF: a workgroup computes HALF a tile - of each wave's 128 x 128 quadrant the rows of ONE A half (64 rows),
+// against the whole width.  A launch covers `units` units starting at tile `tile_first`: whole tiles, or with
+// HALF the two halves of each tile.  The launcher uses it for the tiles of a last, at most half filled round
+// (the weight gradient of the benchmark has 3.5 rounds of tiles): twice as many workgroups of half the
+// duration keep every CU busy instead of half of them idling for a whole tile.  A K step is then two
+// phases: (A,B0) while B1 arrives, barrier, (A,B1) while the next step's A and B0 arrive and the buffer is
+// refilled (12 LDS-DMA loads: only the A rows of this half are fetched).
+template <int FA, int FB, bool OUT_F32, bool ACT = false, bool HALF = false>
 __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
     const uint8_t* __restrict__ A, int64_t lda, const uint8_t* __restrict__ B, int64_t ldb,
     const float* __restrict__ scale_a, int row_a, const float* __restrict__ scale_b, int row_b, int M, int N,
-    int K, void* __restrict__ out, int64_t ld_out, int tiles_m, int tiles_n) {
+    int K, void* __restrict__ out, int64_t ld_out, int tiles_m, int tiles_n, int tile_first, int units) {
     using namespace sn;
+    static_assert(!(HALF && OUT_F32), "half tiles are built for the bfloat16 epilogue only");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- workgroup -> tile (XCD-aware: ids are dealt round-robin to the 8 XCDs;
     //      each XCD gets a contiguous range of tiles walked in groups of tile rows)
-    const int ntiles = tiles_m * tiles_n;
     const int per_xcd = gridDim.x / NUM_XCD;
-    const int logical = (blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
-    if (logical >= ntiles) return;
+    const int unit = (blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
+    if (unit >= units) return;
+    const int logical = tile_first + (HALF ? unit >> 1 : unit);
+    const int ah = HALF ? __builtin_amdgcn_readfirstlane(unit & 1) : 0;     // which A half of every quadrant
     const int in_group = GROUP_M * tiles_n;
     const int first_m = (logical / in_group) * GROUP_M;
     const int gsize = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
@@ -139,8 +150,17 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
         const uint32_t ke = (k0 + cb_e * 16 < K) ? (uint32_t)k0 : OOB;
         const uint32_t ko = (k0 + cb_o * 16 < K) ? (uint32_t)k0 : OOB;
         const uint32_t la = lds_base + (uint32_t)(stage * STAGE), lb = la + BM * BK;
+        if constexpr (HALF) {
+            // load i covers tile rows [32 i, 32 i + 32): this half needs i = 2 ah + {0, 1, 4, 5}
 #pragma unroll
-        for (int i = 0; i < 8; ++i) sn_lds_dma16(rsrc_a, la + i * 4096, va0 + (uint32_t)i * va_step + ka);
+            for (int h = 0; h < 4; ++h) {
+                const int i = 2 * ah + (h & 1) + 4 * (h >> 1);
+                sn_lds_dma16(rsrc_a, la + (uint32_t)i * 4096u, va0 + (uint32_t)i * va_step + ka);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sn_lds_dma16(rsrc_a, la + i * 4096, va0 + (uint32_t)i * va_step + ka);
+        }
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             sn_lds_dma16(rsrc_b, lb + i * 4096, ((i & 1) ? vb0_o + ko : vb0_e + ke) + (uint32_t)i * vb_step);
@@ -153,7 +173,7 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
     int offa[2], offb[2];
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
-        offa[c] = (wm0 + r16) * BK + (((g + 4 * c) ^ key_a) << 4);
+        offa[c] = (wm0 + 64 * ah + r16) * BK + (((g + 4 * c) ^ key_a) << 4);
         offb[c] = BM * BK + (wn0 + 16 * (r16 >> 2) + (r16 & 3)) * BK + (((g + 4 * c) ^ key_b) << 4);
     }
     v8i_s af[2][4], bf[2][4];   // [half][fragment in half]
@@ -168,6 +188,15 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
         const uint4 x0 = *reinterpret_cast<const uint4*>(s + offb[0] + row_off);
         const uint4 x1 = *reinterpret_cast<const uint4*>(s + offb[1] + row_off);
         bf[half][f] = v8i_s{(int)x0.x, (int)x0.y, (int)x0.z, (int)x0.w, (int)x1.x, (int)x1.y, (int)x1.z, (int)x1.w};
+    };
+
+    // HALF: the four A fragments of this half (its rows are already in offa) into fragment set `dst`
+    auto read_ah = [&](const uint8_t* s, auto dst_t, int f) {
+        constexpr int DST = decltype(dst_t)::value;
+        const int row_off = f * 16 * BK;
+        const uint4 x0 = *reinterpret_cast<const uint4*>(s + offa[0] + row_off);
+        const uint4 x1 = *reinterpret_cast<const uint4*>(s + offa[1] + row_off);
+        af[DST][f] = v8i_s{(int)x0.x, (int)x0.y, (int)x0.z, (int)x0.w, (int)x1.x, (int)x1.y, (int)x1.z, (int)x1.w};
     };
 
     v4f_s acc[8][8];   // [A fragment][B fragment]
@@ -221,9 +250,56 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
         __syncthreads();                       // stage 0 landed for every wave
         issue_loads(1, BK);                    // (out of range if there is no step 1)
 #pragma unroll
-        for (int f = 0; f < 4; ++f) { read_a(smem, 0, f); read_b(smem, 0, f); }
+        for (int f = 0; f < 4; ++f) {
+            if constexpr (HALF) read_ah(smem, I0{}, f); else read_a(smem, 0, f);
+            read_b(smem, 0, f);
+        }
         __builtin_amdgcn_sched_barrier(0);
 
+        if constexpr (HALF) {
+            // two phases per step; fragment set of A and the stage alternate with the step's parity
+            auto hstep = [&](auto par_t, int k) {
+                constexpr int PAR = decltype(par_t)::value;
+                using PN = std::integral_constant<int, PAR ^ 1>;
+                const uint8_t* s_cur = smem + PAR * STAGE;
+                const uint8_t* s_nxt = smem + (PAR ^ 1) * STAGE;
+                const int k2 = (k + 2) * BK;
+                const uint32_t ka = (k2 + ca * 16 < K) ? (uint32_t)k2 : OOB;
+                const uint32_t ke = (k2 + cb_e * 16 < K) ? (uint32_t)k2 : OOB;
+                const uint32_t ko = (k2 + cb_o * 16 < K) ? (uint32_t)k2 : OOB;
+                const uint32_t la = lds_base + (uint32_t)(PAR * STAGE), lb = la + BM * BK;
+#pragma unroll
+                for (int t = 0; t < 16; ++t) {                  // (A, B0) | read B1 of this step
+                    const int i = t >> 2, j = t & 3;
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[0][j], af[PAR][i], acc[i][j], FB, FA, 0, 0, 0, 0);
+                    if (t % 2 == 0 && t < 8) read_b(s_cur, 1, t / 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                sn_wait_all_vmem();                // my part of step k+1 has landed
+                __syncthreads();                   // ... and everyone's; this step's buffer is read out
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int t = 0; t < 16; ++t) {                  // (A, B1) | read A, B0 of step k+1, refill (12 loads)
+                    const int i = t >> 2, j = t & 3;
+                    acc[i][4 + j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[1][j], af[PAR][i], acc[i][4 + j], FB, FA, 0, 0, 0, 0);
+                    if (t % 2 == 0 && t < 8) read_ah(s_nxt, PN{}, t / 2);
+                    if (t % 2 == 1 && t < 8) read_b(s_nxt, 0, t / 2);
+                    if (t >= 4 && t < 8) {
+                        const int ia = 2 * ah + ((t - 4) & 1) + 4 * ((t - 4) >> 1);
+                        sn_lds_dma16(rsrc_a, la + (uint32_t)ia * 4096u, va0 + (uint32_t)ia * va_step + ka);
+                    }
+                    if (t >= 8) {
+                        const int ib = t - 8;
+                        sn_lds_dma16(rsrc_b, lb + ib * 4096, ((ib & 1) ? vb0_o + ko : vb0_e + ke) + (uint32_t)ib * vb_step);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            for (int kp = 0; kp < kpairs; ++kp) {
+                hstep(I0{}, 2 * kp);
+                hstep(I1{}, 2 * kp + 1);
+            }
+        } else
         for (int kp = 0; kp < kpairs; ++kp) {
 #pragma unroll
             for (int par = 0; par < 2; ++par) {
@@ -309,10 +385,10 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
         const int c_rd = lane & 15;                        // chunk this lane streams out
         const int n_rd = n0 + wn0 + c_rd * 8;
         const bool interior = m0 + BM <= M && n0 + BN <= N;
-        uint16_t* orow = static_cast<uint16_t*>(out) + (int64_t)(m0 + wm0 + (lane >> 4)) * ld_out + n_rd;
+        uint16_t* orow = static_cast<uint16_t*>(out) + (int64_t)(m0 + wm0 + 64 * ah + (lane >> 4)) * ld_out + n_rd;
 #pragma unroll
-        for (int fi = 0; fi < 8; ++fi) {
-            const int r_loc = 16 * fi + r16;
+        for (int fi = 0; fi < (HALF ? 4 : 8); ++fi) {
+            const int r_loc = 64 * ah + 16 * fi + r16;
             const float inv_a = inv_tab[wm0 + r_loc];
             uint8_t* row = q + r_loc * 256;
 #pragma unroll
@@ -335,7 +411,7 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
-                const int rr = 16 * fi + 4 * it + (lane >> 4);      // row in the quadrant
+                const int rr = 64 * ah + 16 * fi + 4 * it + (lane >> 4);      // row in the quadrant
                 const uint4 v = *reinterpret_cast<const uint4*>(q + rr * 256 + ((c_rd ^ (rr & 15)) << 4));
                 uint16_t* dst = orow + (int64_t)(16 * fi + 4 * it) * ld_out;
                 if (interior) {
@@ -355,12 +431,12 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
     }
 }
 
-template <int FA, int FB, bool OUT_F32, bool ACT = false>
-static hipError_t launch_sn(const uint8_t* a, int64_t lda, const float* sa, int row_a, const uint8_t* b, int64_t ldb,
-                            const float* sb, int row_b, int M, int N, int K, void* out, int64_t ld_out,
-                            hipStream_t st) {
+template <int FA, int FB, bool OUT_F32, bool ACT, bool HALF>
+static hipError_t launch_sn_part(const uint8_t* a, int64_t lda, const float* sa, int row_a, const uint8_t* b, int64_t ldb,
+                                 const float* sb, int row_b, int M, int N, int K, void* out, int64_t ld_out, int tiles_m,
+                                 int tiles_n, int tile_first, int64_t units, hipStream_t st) {
     using namespace sn;
-    auto kern = gemm_fp8_snake_kernel<FA, FB, OUT_F32, ACT>;
+    auto kern = gemm_fp8_snake_kernel<FA, FB, OUT_F32, ACT, HALF>;
     constexpr int lds = 2 * STAGE + 2048;   // two stages + the reciprocal-scale tables of the epilogue
     static bool attr_done = false;          // idempotent, a race is harmless
     if (!attr_done) {
@@ -369,13 +445,51 @@ static hipError_t launch_sn(const uint8_t* a, int64_t lda, const float* sa, int 
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const int64_t ntiles = (int64_t)tiles_m * tiles_n;
-    const int64_t grid = (ntiles + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
+    const int64_t grid = (units + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
     if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
     kern<<<dim3((unsigned)grid), dim3(NT), lds, st>>>(a, lda, b, ldb, sa, row_a, sb, row_b, M, N, K, out, ld_out,
-                                                      tiles_m, tiles_n);
+                                                      tiles_m, tiles_n, tile_first, (int)units);
     return hipGetLastError();
+}
+
+// number of compute units of the current device (0 if the query fails)
+static int sn_compute_units() {
+    static int cus = -1;                    // a race only repeats the query
+    if (cus < 0) {
+        int dev = 0, n = 0;
+        cus = (hipGetDevice(&dev) == hipSuccess &&
+               hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess) ? n : 0;
+    }
+    return cus;
+}
+
+template <int FA, int FB, bool OUT_F32, bool ACT = false>
+static hipError_t launch_sn(const uint8_t* a, int64_t lda, const float* sa, int row_a, const uint8_t* b, int64_t ldb,
+                            const float* sb, int row_b, int M, int N, int K, void* out, int64_t ld_out,
+                            hipStream_t st) {
+    using namespace sn;
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const int64_t ntiles = (int64_t)tiles_m * tiles_n;
+    if (ntiles > 0x3FFFFFFF) return hipErrorInvalidValue;
+    if constexpr (!OUT_F32) {
+        // A last round that would fill at most half of the CUs runs as half tiles instead: twice the
+        // workgroups, half the duration each (FP8MI355_SNAKE_HALF=0 keeps whole tiles; tuning and test aid).
+        const char* e = std::getenv("FP8MI355_SNAKE_HALF");
+        const int cus = sn_compute_units();
+        const int64_t rest = cus > 0 ? ntiles % cus : 0;
+        if (!(e && e[0] == '0') && cus >= 16 && cus % NUM_XCD == 0 && rest > 0 && 2 * rest <= cus) {
+            const int64_t full = ntiles - rest;
+            if (full > 0) {
+                hipError_t err = launch_sn_part<FA, FB, OUT_F32, ACT, false>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out,
+                                                                            ld_out, tiles_m, tiles_n, 0, full, st);
+                if (err != hipSuccess) return err;
+            }
+            return launch_sn_part<FA, FB, OUT_F32, ACT, true>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, tiles_m,
+                                                              tiles_n, (int)full, 2 * rest, st);
+        }
+    }
+    return launch_sn_part<FA, FB, OUT_F32, ACT, false>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, tiles_m, tiles_n,
+                                                       0, ntiles, st);
 }
 
 hipError_t launch_gemm_fp8_snake(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,

@@ -137,6 +137,36 @@ def test_many_tiles_per_workgroup_exact(big_variant, M, N, K):
     assert (got32[rows] == want.out32).all()
 
 
+@pytest.mark.parametrize("M,N,K", [(2304, 2560, 640), (2300, 2500, 400), (4608, 4608, 384), (8192, 4352, 256), (16384, 4096, 128)])
+def test_half_tiles_of_a_partly_filled_last_round(M, N, K):
+    """When the last round of 256 x 256 tiles would fill at most half of the CUs, those tiles run as half tiles
+    (twice the workgroups, the rows of one A half each).  Same accumulation per output element, so the result
+    equals the whole-tile launch bit for bit - random codes, ragged edges, an odd number of K steps, the sigmoid
+    epilogue - and the oracle on sampled rows.  The last shape has no partial round (control)."""
+    rng = np.random.default_rng(M + N + K)
+    a, b = _rand_codes((M, K), orc.E5M2, rng), _rand_codes((N, K), orc.E4M3FN, rng)
+    sa = rng.uniform(0.5, 2.0, M).astype(np.float32)
+    sb = rng.uniform(0.5, 2.0, N).astype(np.float32)
+    old = os.environ.get("FP8MI355_SNAKE_HALF")
+    outs = {}
+    try:
+        for mode in ("0", "1"):
+            os.environ["FP8MI355_SNAKE_HALF"] = mode
+            outs[mode] = (host_bf16_bits(_run(a, orc.E5M2, sa, fp8.FP8_ROW, b, orc.E4M3FN, sb, fp8.FP8_ROW)),
+                          host_bf16_bits(_run(a, orc.E5M2, sa, fp8.FP8_ROW, b, orc.E4M3FN, sb, fp8.FP8_ROW, fp8.FP8_EPILOGUE_SIGMOID)))
+    finally:
+        if old is None:
+            os.environ.pop("FP8MI355_SNAKE_HALF", None)
+        else:
+            os.environ["FP8MI355_SNAKE_HALF"] = old
+    assert (outs["0"][0] == outs["1"][0]).all() and (outs["0"][1] == outs["1"][1]).all()
+    rows = si.stratified_rows(M, 24)
+    want = orc.scaled_mm(a, orc.E5M2, sa, orc.ROW, b, orc.E4M3FN, sb, orc.ROW, rows)
+    got = outs["1"][0][rows]
+    assert orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want.out16)) <= TOL
+    assert float((got == want.out16).mean()) > 0.97
+
+
 SKINNY = [(1, 16, 16), (1, 4096, 4096), (5, 100, 400), (16, 1000, 2048), (17, 24, 128), (33, 4104, 1040),
           (64, 14336, 4096), (48, 2048, 8208), (8, 300, 144), (32, 8208, 272), (20, 12304, 144), (32, 14336, 4096)]
 
