@@ -31,6 +31,7 @@
 #include "fp8_device.hpp"
 #include "launchers.hpp"
 
+#include <cstdlib>
 #include <type_traits>
 
 namespace fp8k {
@@ -72,17 +73,26 @@ __device__ __forceinline__ void bts_lds_dma16(v4i_t rsrc, uint32_t lds_addr, uin
 }
 __device__ __forceinline__ void bts_wait_all_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// HALF: a workgroup computes half a tile, the rows (i) of ONE A half of every wave's quadrant against the
+// whole width, as in the FP8 kernel: the launcher runs the tiles of a last round that would fill at most half
+// of the CUs this way (this kernel is bound by the LDS, not by power: a partly filled round costs a whole
+// one - 3.25 to 4 rounds of tiles all took 1.50-1.57 ms).  A launch covers `units` units from tile
+// `tile_first`: whole tiles, or with HALF the two halves of each tile.  Two phases per K step:
+// (A,B0) | read B1, barrier, (A,B1) | read A and B0 of the next step, refill (the A loads skip the other
+// half's columns: their lanes point past the end and nothing is fetched).
+template <bool HALF>
 __global__ __launch_bounds__(bts::NT) void gemm_bf16_at_b_snake_kernel(
     const uint16_t* __restrict__ A, int64_t lda, const uint16_t* __restrict__ B, int64_t ldb, int I, int J, int C,
-    uint16_t* __restrict__ out, int64_t ld_out, int tiles_i, int tiles_j) {
+    uint16_t* __restrict__ out, int64_t ld_out, int tiles_i, int tiles_j, int tile_first, int units) {
     using namespace bts;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- workgroup -> tile (XCD-aware, as in the FP8 kernel)
-    const int ntiles = tiles_i * tiles_j;
     const int per_xcd = gridDim.x / NUM_XCD;
-    const int logical = (blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
-    if (logical >= ntiles) return;
+    const int unit = (blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
+    if (unit >= units) return;
+    const int logical = tile_first + (HALF ? unit >> 1 : unit);
+    const int ah = HALF ? __builtin_amdgcn_readfirstlane(unit & 1) : 0;
     const int in_group = GROUP_I * tiles_j;
     const int first_i = (logical / in_group) * GROUP_I;
     const int gsize = tiles_i - first_i < GROUP_I ? tiles_i - first_i : GROUP_I;
@@ -109,8 +119,10 @@ __global__ __launch_bounds__(bts::NT) void gemm_bf16_at_b_snake_kernel(
     const int lrow = 2 * wave + (lane >> 5);
     const int slot = lane & 31;
     const int ch_e = slot ^ ((lrow & 3) << 1), ch_o = slot ^ (((lrow & 3) | 4) << 1);
-    const uint32_t va_e = (uint32_t)(lrow * (int)lda * 2 + ch_e * 16) + (ch_e * 8 < cols_a ? 0u : OOB);
-    const uint32_t va_o = (uint32_t)(lrow * (int)lda * 2 + ch_o * 16) + (ch_o * 8 < cols_a ? 0u : OOB);
+    // HALF: only the 64 columns of this A half in each quadrant (chunks with (chunk / 8) % 2 == ah) are fetched
+    const bool use_e = !HALF || ((ch_e >> 3) & 1) == ah, use_o = !HALF || ((ch_o >> 3) & 1) == ah;
+    const uint32_t va_e = (uint32_t)(lrow * (int)lda * 2 + ch_e * 16) + ((ch_e * 8 < cols_a && use_e) ? 0u : OOB);
+    const uint32_t va_o = (uint32_t)(lrow * (int)lda * 2 + ch_o * 16) + ((ch_o * 8 < cols_a && use_o) ? 0u : OOB);
     const uint32_t vb_e = (uint32_t)(lrow * (int)ldb * 2 + ch_e * 16) + (ch_e * 8 < cols_b ? 0u : OOB);
     const uint32_t vb_o = (uint32_t)(lrow * (int)ldb * 2 + ch_o * 16) + (ch_o * 8 < cols_b ? 0u : OOB);
     const uint32_t va_row8 = (uint32_t)(8 * (int)lda * 2), vb_row8 = (uint32_t)(8 * (int)ldb * 2);
@@ -153,6 +165,11 @@ __global__ __launch_bounds__(bts::NT) void gemm_bf16_at_b_snake_kernel(
     };
     v8bf_s af[2][4][2], bf[2][4][2];   // [half][fragment in half][k sub-step]
     auto read_a = [&](const uint8_t* s, int half, int f) { read_frag(s, base_a + (key5 ^ ((half * 4 + f) << 5)), af[half][f]); };
+    // HALF: fragment f of this workgroup's A half into fragment set `dst`
+    const int ah4 = ah << 7;                 // (4 * ah) << 5
+    auto read_ah = [&](const uint8_t* s, auto dst_t, int f) {
+        read_frag(s, base_a + (key5 ^ (ah4 | (f << 5))), af[decltype(dst_t)::value][f]);
+    };
     auto read_b = [&](const uint8_t* s, int half, int f) { read_frag(s, base_b + (key5 ^ ((half * 4 + f) << 5)), bf[half][f]); };
 
     v4f_t acc[8][8];   // [A fragment][B fragment]
@@ -200,9 +217,46 @@ __global__ __launch_bounds__(bts::NT) void gemm_bf16_at_b_snake_kernel(
         __syncthreads();
         issue_loads(1, 1);
 #pragma unroll
-        for (int f = 0; f < 4; ++f) { read_a(smem, 0, f); read_b(smem, 0, f); }
+        for (int f = 0; f < 4; ++f) {
+            if constexpr (HALF) read_ah(smem, I0{}, f); else read_a(smem, 0, f);
+            read_b(smem, 0, f);
+        }
         __builtin_amdgcn_sched_barrier(0);
 
+        if constexpr (HALF) {
+            auto hstep = [&](auto par_t, int k) {
+                constexpr int PAR = decltype(par_t)::value;
+                using PN = std::integral_constant<int, PAR ^ 1>;
+                const uint8_t* s_cur = smem + PAR * STAGE;
+                const uint8_t* s_nxt = smem + (PAR ^ 1) * STAGE;
+                const uint32_t sa_off = (uint32_t)(k + 2) * a_step, sb_off = (uint32_t)(k + 2) * b_step;
+                const uint32_t la = lds_base + (uint32_t)(PAR * STAGE), lb = la + PART;
+#pragma unroll
+                for (int t = 0; t < 32; ++t) {               // (A, B0) | read B1 of this step
+                    const int sub = t >> 4, i = (t & 15) >> 2, j = t & 3;
+                    mfma(acc[i][j], bf[0][j][sub], af[PAR][i][sub]);
+                    if (t % 4 == 0 && t < 16) read_b(s_cur, 1, t / 4);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                bts_wait_all_vmem();
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int t = 0; t < 32; ++t) {               // (A, B1) | read A, B0 of step k+1, refill both parts
+                    const int sub = t >> 4, i = (t & 15) >> 2, j = t & 3;
+                    mfma(acc[i][4 + j], bf[1][j][sub], af[PAR][i][sub]);
+                    if (t % 4 == 0 && t < 16) read_ah(s_nxt, PN{}, t / 4);
+                    if (t % 4 == 1 && t < 16) read_b(s_nxt, 0, t / 4);
+                    if (t % 4 == 2) dma_a(la, t / 4, sa_off);
+                    if (t % 4 == 3) dma_b(lb, t / 4, sb_off);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            for (int kp = 0; kp < kpairs; ++kp) {
+                hstep(I0{}, 2 * kp);
+                hstep(I1{}, 2 * kp + 1);
+            }
+        } else
         for (int kp = 0; kp < kpairs; ++kp) {
 #pragma unroll
             for (int par = 0; par < 2; ++par) {
@@ -242,10 +296,10 @@ __global__ __launch_bounds__(bts::NT) void gemm_bf16_at_b_snake_kernel(
     const int c_rd = lane & 15;
     const int n_rd = j0 + wj0 + c_rd * 8;
     const bool interior = i0 + BI <= I && j0 + BJ <= J;
-    uint16_t* orow = out + (int64_t)(i0 + wi0 + (lane >> 4)) * ld_out + n_rd;
+    uint16_t* orow = out + (int64_t)(i0 + wi0 + 64 * ah + (lane >> 4)) * ld_out + n_rd;
 #pragma unroll
-    for (int fi = 0; fi < 8; ++fi) {
-        const int r_loc = 16 * fi + r16;
+    for (int fi = 0; fi < (HALF ? 4 : 8); ++fi) {
+        const int r_loc = 64 * ah + 16 * fi + r16;
         uint8_t* row = q + r_loc * 256;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
@@ -258,7 +312,7 @@ __global__ __launch_bounds__(bts::NT) void gemm_bf16_at_b_snake_kernel(
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-            const int rr = 16 * fi + 4 * it + (lane >> 4);
+            const int rr = 64 * ah + 16 * fi + 4 * it + (lane >> 4);
             const uint4 v = *reinterpret_cast<const uint4*>(q + rr * 256 + ((c_rd ^ (rr & 15)) << 4));
             uint16_t* dst = orow + (int64_t)(16 * fi + 4 * it) * ld_out;
             if (interior) {
@@ -278,27 +332,55 @@ bool gemm_bf16_at_b_snake_fits(int64_t lda, int64_t ldb, int64_t I, int64_t J, i
     return I % 8 == 0 && J % 8 == 0 && C > 0 && (C + 4 * BC) * lda * 2 + 2 * ROWB < lim && (C + 4 * BC) * ldb * 2 + 2 * ROWB < lim;
 }
 
+template <bool HALF>
+static hipError_t bts_launch_part(const uint16_t* a, int64_t lda, const uint16_t* b, int64_t ldb, int I, int J, int C,
+                                  uint16_t* out, int64_t ld_out, int tiles_i, int tiles_j, int tile_first, int64_t units,
+                                  hipStream_t st) {
+    using namespace bts;
+    static bool attr_done = false;          // idempotent, a race is harmless
+    constexpr int lds = 2 * STAGE;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_at_b_snake_kernel<HALF>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    const int64_t grid = (units + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
+    if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
+    gemm_bf16_at_b_snake_kernel<HALF><<<dim3((unsigned)grid), dim3(NT), lds, st>>>(a, lda, b, ldb, I, J, C, out, ld_out, tiles_i,
+                                                                              tiles_j, tile_first, (int)units);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm_bf16_at_b_snake(const void* a, int64_t lda, const void* b, int64_t ldb, int64_t I, int64_t J,
                                        int64_t C, void* out, int64_t ld_out, hipStream_t st) {
     using namespace bts;
     if (I == 0 || J == 0) return hipSuccess;
     if (!gemm_bf16_at_b_snake_fits(lda, ldb, I, J, C)) return hipErrorInvalidValue;
-    static bool attr_done = false;          // idempotent, a race is harmless
-    constexpr int lds = 2 * STAGE;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_at_b_snake_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
     const int tiles_i = (int)((I + BI - 1) / BI), tiles_j = (int)((J + BJ - 1) / BJ);
     const int64_t ntiles = (int64_t)tiles_i * tiles_j;
-    const int64_t grid = (ntiles + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
-    if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
-    gemm_bf16_at_b_snake_kernel<<<dim3((unsigned)grid), dim3(NT), lds, st>>>(
-        static_cast<const uint16_t*>(a), lda, static_cast<const uint16_t*>(b), ldb, (int)I, (int)J, (int)C,
-        static_cast<uint16_t*>(out), ld_out, tiles_i, tiles_j);
-    return hipGetLastError();
+    if (ntiles > 0x3FFFFFFF) return hipErrorInvalidValue;
+    const uint16_t* ap = static_cast<const uint16_t*>(a);
+    const uint16_t* bp = static_cast<const uint16_t*>(b);
+    uint16_t* op = static_cast<uint16_t*>(out);
+    // a last round that would fill at most half of the CUs runs as half tiles (FP8MI355_SNAKE_HALF=0: whole tiles)
+    static int cus = -1;                    // a race only repeats the query
+    if (cus < 0) {
+        int dev = 0, n = 0;
+        cus = (hipGetDevice(&dev) == hipSuccess &&
+               hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess) ? n : 0;
+    }
+    const char* e = std::getenv("FP8MI355_SNAKE_HALF");
+    const int64_t rest = cus > 0 ? ntiles % cus : 0;
+    if (!(e && e[0] == '0') && cus >= 16 && cus % NUM_XCD == 0 && rest > 0 && 2 * rest <= cus) {
+        const int64_t full = ntiles - rest;
+        if (full > 0) {
+            hipError_t err = bts_launch_part<false>(ap, lda, bp, ldb, (int)I, (int)J, (int)C, op, ld_out, tiles_i, tiles_j, 0, full, st);
+            if (err != hipSuccess) return err;
+        }
+        return bts_launch_part<true>(ap, lda, bp, ldb, (int)I, (int)J, (int)C, op, ld_out, tiles_i, tiles_j, (int)full, 2 * rest, st);
+    }
+    return bts_launch_part<false>(ap, lda, bp, ldb, (int)I, (int)J, (int)C, op, ld_out, tiles_i, tiles_j, 0, ntiles, st);
 }
 
 }  // namespace fp8k

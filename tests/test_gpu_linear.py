@@ -1,5 +1,7 @@
 """GPU parity: fp8 linear forward / backward vs the CPU oracle, through the
 C ABI entry points fp8_linear_fwd and fp8_linear_bwd."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -455,6 +457,31 @@ def test_backward_with_high_precision_weight_gradient(M, K, N):
     # dW only
     _, dw_only = fp8.fp8_linear_bwd(dyd, xd, wd, g, need_dx=False)
     assert torch.equal(dw_only.view(torch.int16), dw.view(torch.int16))
+
+
+@pytest.mark.parametrize("M,K,N", [(512, 2560, 2304), (300, 2504, 2296), (640, 4352, 4096), (256, 4096, 4096)])
+def test_grad_weight_hp_half_tiles_of_a_partly_filled_last_round(M, K, N):
+    """dW [N, K] with a tile count whose last round would fill at most half of the CUs: those tiles run as half
+    tiles.  Same sums per element as whole tiles (bit-identical), exact on small integers; ragged edges and an
+    odd number of steps included; the last shape has no partial round (control)."""
+    rng = np.random.default_rng(M + K + N)
+    gi = rng.integers(-3, 4, (M, N)).astype(np.float32)
+    xi = rng.integers(-3, 4, (M, K)).astype(np.float32)
+    dyd, xd = dev_bf16(si.f32_to_bf16_bits(gi)), dev_bf16(si.f32_to_bf16_bits(xi))
+    old = os.environ.get("FP8MI355_SNAKE_HALF")
+    outs = {}
+    try:
+        for mode in ("0", "1"):
+            os.environ["FP8MI355_SNAKE_HALF"] = mode
+            outs[mode] = host_bf16_bits(fp8.fp8_grad_weight_hp(dyd, xd))
+    finally:
+        if old is None:
+            os.environ.pop("FP8MI355_SNAKE_HALF", None)
+        else:
+            os.environ["FP8MI355_SNAKE_HALF"] = old
+    assert (outs["0"] == outs["1"]).all()
+    want = si.f32_to_bf16_bits((gi.astype(np.float64).T @ xi.astype(np.float64)).astype(np.float32))
+    assert (outs["1"] == want).all()
 
 
 def test_full_size_grad_weight_hp_sampled_rows():
