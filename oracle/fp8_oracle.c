@@ -397,7 +397,7 @@ void orc_mx_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, 
  * scales ([rows, cols / 32]), so orc_mx_mm is the product of two blockwise
  * operands as well.  br x bc is the block (1 x 128 or 128 x 128; any br >= 1 and
  * bc a multiple of 32 work); blocks at the bottom edge may be partial, cols must
- * be a multiple of bc.
+ * be a multiple of bc.  NaN / Inf inputs: unspecified here ("parity unpinned").
  */
 void orc_block_quantize(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, int64_t br, int64_t bc, int fmt,
                         uint8_t* q, int64_t ld_q, uint8_t* e8m0, int64_t ld_e) {
