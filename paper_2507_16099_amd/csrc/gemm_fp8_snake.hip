@@ -81,6 +81,16 @@ __device__ __forceinline__ void sn_lds_dma16(v4i_s rsrc, uint32_t lds_addr, uint
                  : "memory", "m0");
 }
 __device__ __forceinline__ void sn_wait_all_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Workgroup barrier behind the wave's own LDS reads (no wait for loads in flight).
+__device__ __forceinline__ void sn_barrier_lds() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+// Wait until at most the five youngest loads are in flight (loads complete in issue order), own LDS reads done, barrier.
+__device__ __forceinline__ void sn_wait_vmem_but5_barrier() {
+    asm volatile("s_waitcnt vmcnt(5) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
 
 // logistic function of the dequantized result, for the fused activation epilogue (ACT)
 __device__ __forceinline__ float sn_sigmoid(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
@@ -207,22 +217,23 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
 
     // one phase: 16 MFMAs of A half AH x B half BH; in its slots, optionally the
     // reads of one fragment half (RD_A: 1 = A half RH, 0 = B half RH, -1 = none)
-    // from stage `rs`, and eight LDS-DMA loads (DMA: 0 = A part, 1 = B part, -1 = none).
-    auto phase = [&](auto ah_t, auto bh_t, auto rda_t, auto rh_t, auto dma_t, const uint8_t* rs, uint32_t la, uint32_t lb,
+    // from stage `rs`, and CNT of the step's sixteen LDS-DMA refill loads, from
+    // number L0 on (0-7: the B part, 8-15: the A part).
+    auto phase = [&](auto ah_t, auto bh_t, auto rda_t, auto rh_t, auto l0_t, auto cnt_t, const uint8_t* rs, uint32_t la, uint32_t lb,
                      uint32_t ka, uint32_t ke, uint32_t ko) {
         constexpr int AH = decltype(ah_t)::value, BH = decltype(bh_t)::value, RDA = decltype(rda_t)::value,
-                      RH = decltype(rh_t)::value, DMA = decltype(dma_t)::value;
+                      RH = decltype(rh_t)::value, L0 = decltype(l0_t)::value, CNT = decltype(cnt_t)::value;
 #pragma unroll
         for (int t = 0; t < 16; ++t) {
-            const int i = t >> 2, j = t & 3;
+            const int i = t >> 2, j = (i & 1) ? 3 - (t & 3) : (t & 3);   // boustrophedon: one operand stays between neighbours
             acc[AH * 4 + i][BH * 4 + j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
                 bf[BH][j], af[AH][i], acc[AH * 4 + i][BH * 4 + j], FB, FA, 0, 0, 0, 0);
             if constexpr (RDA == 1) { if (t % 2 == 0 && t < 8) read_a(rs, RH, t / 2); }
             if constexpr (RDA == 0) { if (t % 2 == 0 && t < 8) read_b(rs, RH, t / 2); }
-            if constexpr (DMA == 0) { if (t % 2 == 1) sn_lds_dma16(rsrc_a, la + (t / 2) * 4096, va0 + (uint32_t)(t / 2) * va_step + ka); }
-            if constexpr (DMA == 1) {
-                if (t % 2 == 1)
-                    sn_lds_dma16(rsrc_b, lb + (t / 2) * 4096, (((t / 2) & 1) ? vb0_o + ko : vb0_e + ke) + (uint32_t)(t / 2) * vb_step);
+            if (t % 2 == 1 && t / 2 < CNT) {
+                const int q = L0 + t / 2;
+                if (q < 8) sn_lds_dma16(rsrc_b, lb + q * 4096, ((q & 1) ? vb0_o + ko : vb0_e + ke) + (uint32_t)q * vb_step);
+                else sn_lds_dma16(rsrc_a, la + (q - 8) * 4096, va0 + (uint32_t)(q - 8) * va_step + ka);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -230,6 +241,9 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
     using IN = std::integral_constant<int, -1>;
+    using I5 = std::integral_constant<int, 5>;
+    using I6 = std::integral_constant<int, 6>;
+    using I11 = std::integral_constant<int, 11>;
 
     // K steps are processed in pairs (the B halves swap roles every step); an odd
     // number of steps gets one phantom step whose loads are all out of range (zeros).
@@ -270,7 +284,7 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
                 const uint32_t la = lds_base + (uint32_t)(PAR * STAGE), lb = la + BM * BK;
 #pragma unroll
                 for (int t = 0; t < 16; ++t) {                  // (A, B0) | read B1 of this step
-                    const int i = t >> 2, j = t & 3;
+                    const int i = t >> 2, j = (i & 1) ? 3 - (t & 3) : (t & 3);
                     acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[0][j], af[PAR][i], acc[i][j], FB, FA, 0, 0, 0, 0);
                     if (t % 2 == 0 && t < 8) read_b(s_cur, 1, t / 2);
                     __builtin_amdgcn_sched_barrier(0);
@@ -280,7 +294,7 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int t = 0; t < 16; ++t) {                  // (A, B1) | read A, B0 of step k+1, refill (12 loads)
-                    const int i = t >> 2, j = t & 3;
+                    const int i = t >> 2, j = (i & 1) ? 3 - (t & 3) : (t & 3);
                     acc[i][4 + j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[1][j], af[PAR][i], acc[i][4 + j], FB, FA, 0, 0, 0, 0);
                     if (t % 2 == 0 && t < 8) read_ah(s_nxt, PN{}, t / 2);
                     if (t % 2 == 1 && t < 8) read_b(s_nxt, 0, t / 2);
@@ -311,24 +325,24 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
                 const uint32_t ke = (k2 + cb_e * 16 < K) ? (uint32_t)k2 : OOB;
                 const uint32_t ko = (k2 + cb_o * 16 < K) ? (uint32_t)k2 : OOB;
                 const uint32_t la = lds_base + (uint32_t)(par * STAGE), lb = la + BM * BK;
+                // The refill of this step's buffer (sixteen loads) is spread over phases 2-4, so that no phase asks
+                // more of the LDS than it has: B part first (read out after phase 1), then the A part (after phase 2).
                 if (par == 0) {
                     // even step: B order 0,1,1,0.  Holds A0, B0 of this step.
-                    phase(I0{}, I0{}, I0{}, I1{}, IN{}, s_cur, la, lb, ka, ke, ko);   // (A0,B0) | read B1 of this step
-                    phase(I0{}, I1{}, I1{}, I1{}, IN{}, s_cur, la, lb, ka, ke, ko);   // (A0,B1) | read A1 of this step
-                    sn_wait_all_vmem();                // my part of step k+1 has landed
-                    __syncthreads();                   // ... and everyone's; this step's buffer is read out
-                    __builtin_amdgcn_sched_barrier(0);
-                    phase(I1{}, I1{}, I1{}, I0{}, I0{}, s_nxt, la, lb, ka, ke, ko);   // (A1,B1) | read A0 of step k+1, refill A
-                    phase(I1{}, I0{}, I0{}, I1{}, I1{}, s_nxt, la, lb, ka, ke, ko);   // (A1,B0) | read B1 of step k+1, refill B
+                    phase(I0{}, I0{}, I0{}, I1{}, I0{}, I0{}, s_cur, la, lb, ka, ke, ko);    // (A0,B0) | read B1 of this step
+                    sn_barrier_lds();                  // this step's B part is read out by everyone
+                    phase(I0{}, I1{}, I1{}, I1{}, I0{}, I5{}, s_cur, la, lb, ka, ke, ko);    // (A0,B1) | read A1 of this step, refill B 0-4
+                    sn_wait_vmem_but5_barrier();       // step k+1 has landed for everyone; this step's A part is read out
+                    phase(I1{}, I1{}, I1{}, I0{}, I5{}, I6{}, s_nxt, la, lb, ka, ke, ko);    // (A1,B1) | read A0 of step k+1, refill B 5-7, A 0-2
+                    phase(I1{}, I0{}, I0{}, I1{}, I11{}, I5{}, s_nxt, la, lb, ka, ke, ko);   // (A1,B0) | read B1 of step k+1, refill A 3-7
                 } else {
                     // odd step: B order 1,0,0,1.  Holds A0, B1 of this step.
-                    phase(I0{}, I1{}, I0{}, I0{}, IN{}, s_cur, la, lb, ka, ke, ko);   // (A0,B1) | read B0 of this step
-                    phase(I0{}, I0{}, I1{}, I1{}, IN{}, s_cur, la, lb, ka, ke, ko);   // (A0,B0) | read A1 of this step
-                    sn_wait_all_vmem();
-                    __syncthreads();
-                    __builtin_amdgcn_sched_barrier(0);
-                    phase(I1{}, I0{}, I1{}, I0{}, I0{}, s_nxt, la, lb, ka, ke, ko);   // (A1,B0) | read A0 of step k+1, refill A
-                    phase(I1{}, I1{}, I0{}, I0{}, I1{}, s_nxt, la, lb, ka, ke, ko);   // (A1,B1) | read B0 of step k+1, refill B
+                    phase(I0{}, I1{}, I0{}, I0{}, I0{}, I0{}, s_cur, la, lb, ka, ke, ko);    // (A0,B1) | read B0 of this step
+                    sn_barrier_lds();
+                    phase(I0{}, I0{}, I1{}, I1{}, I0{}, I5{}, s_cur, la, lb, ka, ke, ko);    // (A0,B0) | read A1 of this step, refill B 0-4
+                    sn_wait_vmem_but5_barrier();
+                    phase(I1{}, I0{}, I1{}, I0{}, I5{}, I6{}, s_nxt, la, lb, ka, ke, ko);    // (A1,B0) | read A0 of step k+1, refill B 5-7, A 0-2
+                    phase(I1{}, I1{}, I0{}, I0{}, I11{}, I5{}, s_nxt, la, lb, ka, ke, ko);   // (A1,B1) | read B0 of step k+1, refill A 3-7
                 }
             }
         }

@@ -244,8 +244,8 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
         uint32_t raw[4] = {0, 0, 0, 0};
 #pragma unroll
         for (int t = 0; t < 16; ++t) {
-            const int i = t >> 2, j = t & 3;
-            acc[AH * 4 + i][BH * 4 + j] = mfma_sel(t, bf[BH][j], af[AH][i], acc[AH * 4 + i][BH * 4 + j], sb[BH], sa[AH]);
+            const int i = t >> 2, j = (i & 1) ? 3 - (t & 3) : (t & 3);   // boustrophedon: one operand stays between neighbours
+            acc[AH * 4 + i][BH * 4 + j] = mfma_sel(4 * i + j, bf[BH][j], af[AH][i], acc[AH * 4 + i][BH * 4 + j], sb[BH], sa[AH]);
             if constexpr (RDA == 1) { if (t % 2 == 0 && t < 8) read_a(rs, RH, t / 2); }
             if constexpr (RDA == 0) { if (t % 2 == 0 && t < 8) read_b(rs, RH, t / 2); }
             if constexpr (DMA == 0) { if (t % 2 == 1) msn_lds_dma16(rsrc_a, la + (t / 2) * 4096, va0 + (uint32_t)(t / 2) * va_step + ka); }
