@@ -72,6 +72,16 @@ __device__ __forceinline__ void bts_lds_dma16(v4i_t rsrc, uint32_t lds_addr, uin
                  : "memory", "m0");
 }
 __device__ __forceinline__ void bts_wait_all_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// workgroup barrier behind the wave's own LDS reads (no wait for loads in flight)
+__device__ __forceinline__ void bts_barrier_lds() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+// wait until at most the five youngest loads are in flight (loads complete in issue order), own LDS reads done, barrier
+__device__ __forceinline__ void bts_wait_vmem_but5_barrier() {
+    asm volatile("s_waitcnt vmcnt(5) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
 
 // HALF: a workgroup computes half a tile, the rows (i) of ONE A half of every wave's quadrant against the
 // whole width, as in the FP8 kernel: the launcher runs the tiles of a last round that would fill at most half
@@ -187,25 +197,30 @@ __global__ __launch_bounds__(bts::NT) void gemm_bf16_at_b_snake_kernel(
     // one phase: 32 MFMA slots (A half AH x B half BH: the 16 tile pairs with the first 32 contraction
     // elements, then the same 16 with the second 32, so that an accumulator is reused only after 16
     // instructions); in its slots the reads of one fragment half (RDA: 1 = A half RH, 0 = B half RH)
-    // from stage `rs`, and eight LDS-DMA loads (DMA: 0 = A part, 1 = B part, -1 = none)
-    auto phase = [&](auto ah_t, auto bh_t, auto rda_t, auto rh_t, auto dma_t, const uint8_t* rs, uint32_t la, uint32_t lb,
+    // from stage `rs`, and CNT of the step's sixteen LDS-DMA refill loads, from number L0 on
+    // (0-7: the B part, 8-15: the A part)
+    auto phase = [&](auto ah_t, auto bh_t, auto rda_t, auto rh_t, auto l0_t, auto cnt_t, const uint8_t* rs, uint32_t la, uint32_t lb,
                      uint32_t sa_off, uint32_t sb_off) {
         constexpr int AH = decltype(ah_t)::value, BH = decltype(bh_t)::value, RDA = decltype(rda_t)::value,
-                      RH = decltype(rh_t)::value, DMA = decltype(dma_t)::value;
+                      RH = decltype(rh_t)::value, L0 = decltype(l0_t)::value, CNT = decltype(cnt_t)::value;
 #pragma unroll
         for (int t = 0; t < 32; ++t) {
-            const int sub = t >> 4, i = (t & 15) >> 2, j = t & 3;
+            const int sub = t >> 4, i = (t & 15) >> 2, j = (i & 1) ? 3 - (t & 3) : (t & 3);   // boustrophedon inside a pass
             mfma(acc[AH * 4 + i][BH * 4 + j], bf[BH][j][sub], af[AH][i][sub]);
             if constexpr (RDA == 1) { if (t % 4 == 0 && t < 16) read_a(rs, RH, t / 4); }
             if constexpr (RDA == 0) { if (t % 4 == 0 && t < 16) read_b(rs, RH, t / 4); }
-            if constexpr (DMA == 0) { if (t % 4 == 2) dma_a(la, t / 4, sa_off); }
-            if constexpr (DMA == 1) { if (t % 4 == 2) dma_b(lb, t / 4, sb_off); }
+            if (t % 4 == 2 && t / 4 < CNT) {
+                const int q = L0 + t / 4;
+                if (q < 8) dma_b(lb, q, sb_off); else dma_a(la, q - 8, sa_off);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
-    using IN = std::integral_constant<int, -1>;
+    using I5 = std::integral_constant<int, 5>;
+    using I6 = std::integral_constant<int, 6>;
+    using I11 = std::integral_constant<int, 11>;
 
     // K steps in pairs (the B halves swap roles every step); an odd count gets one phantom
     // step whose loads are all past the end (zeros)
@@ -265,22 +280,23 @@ __global__ __launch_bounds__(bts::NT) void gemm_bf16_at_b_snake_kernel(
                 const uint8_t* s_nxt = smem + (par ^ 1) * STAGE;
                 const uint32_t sa_off = (uint32_t)(k + 2) * a_step, sb_off = (uint32_t)(k + 2) * b_step;   // refill with step k + 2
                 const uint32_t la = lds_base + (uint32_t)(par * STAGE), lb = la + PART;
+                // the sixteen refill loads of this step's buffer are spread over phases 2-4 (the LDS is the
+                // kernel's limit: no phase should carry more of them than another): the B part is read out
+                // after phase 1, the A part after phase 2
                 if (par == 0) {
-                    phase(I0{}, I0{}, I0{}, I1{}, IN{}, s_cur, la, lb, sa_off, sb_off);   // (A0,B0) | read B1 of this step
-                    phase(I0{}, I1{}, I1{}, I1{}, IN{}, s_cur, la, lb, sa_off, sb_off);   // (A0,B1) | read A1 of this step
-                    bts_wait_all_vmem();
-                    __syncthreads();
-                    __builtin_amdgcn_sched_barrier(0);
-                    phase(I1{}, I1{}, I1{}, I0{}, I0{}, s_nxt, la, lb, sa_off, sb_off);   // (A1,B1) | read A0 of step k+1, refill A
-                    phase(I1{}, I0{}, I0{}, I1{}, I1{}, s_nxt, la, lb, sa_off, sb_off);   // (A1,B0) | read B1 of step k+1, refill B
+                    phase(I0{}, I0{}, I0{}, I1{}, I0{}, I0{}, s_cur, la, lb, sa_off, sb_off);    // (A0,B0) | read B1 of this step
+                    bts_barrier_lds();
+                    phase(I0{}, I1{}, I1{}, I1{}, I0{}, I5{}, s_cur, la, lb, sa_off, sb_off);    // (A0,B1) | read A1 of this step, refill B 0-4
+                    bts_wait_vmem_but5_barrier();      // step k+1 has landed for everyone; this step's A part is read out
+                    phase(I1{}, I1{}, I1{}, I0{}, I5{}, I6{}, s_nxt, la, lb, sa_off, sb_off);    // (A1,B1) | read A0 of step k+1, refill B 5-7, A 0-2
+                    phase(I1{}, I0{}, I0{}, I1{}, I11{}, I5{}, s_nxt, la, lb, sa_off, sb_off);   // (A1,B0) | read B1 of step k+1, refill A 3-7
                 } else {
-                    phase(I0{}, I1{}, I0{}, I0{}, IN{}, s_cur, la, lb, sa_off, sb_off);   // (A0,B1) | read B0 of this step
-                    phase(I0{}, I0{}, I1{}, I1{}, IN{}, s_cur, la, lb, sa_off, sb_off);   // (A0,B0) | read A1 of this step
-                    bts_wait_all_vmem();
-                    __syncthreads();
-                    __builtin_amdgcn_sched_barrier(0);
-                    phase(I1{}, I0{}, I1{}, I0{}, I0{}, s_nxt, la, lb, sa_off, sb_off);   // (A1,B0) | read A0 of step k+1, refill A
-                    phase(I1{}, I1{}, I0{}, I0{}, I1{}, s_nxt, la, lb, sa_off, sb_off);   // (A1,B1) | read B0 of step k+1, refill B
+                    phase(I0{}, I1{}, I0{}, I0{}, I0{}, I0{}, s_cur, la, lb, sa_off, sb_off);    // (A0,B1) | read B0 of this step
+                    bts_barrier_lds();
+                    phase(I0{}, I0{}, I1{}, I1{}, I0{}, I5{}, s_cur, la, lb, sa_off, sb_off);    // (A0,B0) | read A1 of this step, refill B 0-4
+                    bts_wait_vmem_but5_barrier();
+                    phase(I1{}, I0{}, I1{}, I0{}, I5{}, I6{}, s_nxt, la, lb, sa_off, sb_off);    // (A1,B0) | read A0 of step k+1, refill B 5-7, A 0-2
+                    phase(I1{}, I1{}, I0{}, I0{}, I11{}, I5{}, s_nxt, la, lb, sa_off, sb_off);   // (A1,B1) | read B0 of step k+1, refill A 3-7
                 }
             }
         }
