@@ -61,6 +61,16 @@ __device__ __forceinline__ void msn_lds_dma4(v4i_x rsrc, uint32_t lds_addr, uint
                  : "memory", "m0");
 }
 __device__ __forceinline__ void msn_wait_all_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// workgroup barrier behind the wave's own LDS reads (no wait for loads in flight)
+__device__ __forceinline__ void msn_barrier_lds() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+// wait until at most the five youngest loads are in flight (loads complete in issue order), own LDS reads done, barrier
+__device__ __forceinline__ void msn_wait_vmem_but5_barrier() {
+    asm volatile("s_waitcnt vmcnt(5) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
 
 // SC16 (K a multiple of 512): the scale bytes are fetched 16 per row at a time (four K steps, two buffers
 // behind the stages) instead of 4 per row and K step.  A scale load touches one cache line per lane
@@ -236,11 +246,13 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
 
     // one phase: 16 MFMAs of A half AH x B half BH; in its slots, optionally the
     // reads of one fragment half (RD_A: 1 = A half RH, 0 = B half RH, -1 = none)
-    // from stage `rs`, and eight LDS-DMA loads (DMA: 0 = A part, 1 = B part, -1 = none).
-    auto phase = [&](auto ah_t, auto bh_t, auto rda_t, auto rh_t, auto dma_t, const uint8_t* rs, uint32_t la, uint32_t lb,
+    // from stage `rs`, CNT of the step's sixteen LDS-DMA refill loads from number L0 on (0-7: the B part,
+    // 8-15: the A part), and the refill of one operand's scales (SCD: 0 = A, 1 = B, -1 = none).
+    auto phase = [&](auto ah_t, auto bh_t, auto rda_t, auto rh_t, auto l0_t, auto cnt_t, auto scd_t, const uint8_t* rs, uint32_t la, uint32_t lb,
                      uint32_t ka, uint32_t ke, uint32_t ko, uint32_t lsc, uint32_t ks, const uint8_t* rsc, bool sc_issue) {
         constexpr int AH = decltype(ah_t)::value, BH = decltype(bh_t)::value, RDA = decltype(rda_t)::value,
-                      RH = decltype(rh_t)::value, DMA = decltype(dma_t)::value;
+                      RH = decltype(rh_t)::value, L0 = decltype(l0_t)::value, CNT = decltype(cnt_t)::value,
+                      DMA = decltype(scd_t)::value;
         uint32_t raw[4] = {0, 0, 0, 0};
 #pragma unroll
         for (int t = 0; t < 16; ++t) {
@@ -248,10 +260,10 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
             acc[AH * 4 + i][BH * 4 + j] = mfma_sel(4 * i + j, bf[BH][j], af[AH][i], acc[AH * 4 + i][BH * 4 + j], sb[BH], sa[AH]);
             if constexpr (RDA == 1) { if (t % 2 == 0 && t < 8) read_a(rs, RH, t / 2); }
             if constexpr (RDA == 0) { if (t % 2 == 0 && t < 8) read_b(rs, RH, t / 2); }
-            if constexpr (DMA == 0) { if (t % 2 == 1) msn_lds_dma16(rsrc_a, la + (t / 2) * 4096, va0 + (uint32_t)(t / 2) * va_step + ka); }
-            if constexpr (DMA == 1) {
-                if (t % 2 == 1)
-                    msn_lds_dma16(rsrc_b, lb + (t / 2) * 4096, (((t / 2) & 1) ? vb0_o + ko : vb0_e + ke) + (uint32_t)(t / 2) * vb_step);
+            if (t % 2 == 1 && t / 2 < CNT) {
+                const int q = L0 + t / 2;
+                if (q < 8) msn_lds_dma16(rsrc_b, lb + q * 4096, ((q & 1) ? vb0_o + ko : vb0_e + ke) + (uint32_t)q * vb_step);
+                else msn_lds_dma16(rsrc_a, la + (q - 8) * 4096, va0 + (uint32_t)(q - 8) * va_step + ka);
             }
             // scales of the half that was read in slots 0..6, packed (the half is not in use in this phase)
             if constexpr (RDA == 1) { if (t == 9) scales_a_read(rsc, RH, raw); if (t == 14) sa[RH] = scales_pack(raw); }
@@ -271,6 +283,9 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
     using IN = std::integral_constant<int, -1>;
+    using I5 = std::integral_constant<int, 5>;
+    using I6 = std::integral_constant<int, 6>;
+    using I11 = std::integral_constant<int, 11>;
 
     // K steps are processed in pairs (the B halves swap roles every step); an odd
     // number of steps gets one phantom step whose loads are all out of range (zeros).
@@ -307,24 +322,25 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
                 const uint32_t ks = SC16 ? (uint32_t)(q1 * 16) : (k2 < K ? (uint32_t)(k2 >> 5) : OOB);
                 const uint8_t* c_cur = SC16 ? smem + 2 * STAGE + ((k >> 2) & 1) * SCBUF + (k & 3) * 4 : s_cur;
                 const uint8_t* c_nxt = SC16 ? smem + 2 * STAGE + (((k + 1) >> 2) & 1) * SCBUF + ((k + 1) & 3) * 4 : s_nxt;
+                // The sixteen data loads of the refill are spread over phases 2-4 (B part first: it is read out after
+                // phase 1; the A part after phase 2); the scale loads stay behind the wait in the middle of the step, so
+                // that the five youngest loads at that wait are always phase 2's.
                 if (par == 0) {
                     // even step: B order 0,1,1,0.  Holds A0, B0 of this step.
-                    phase(I0{}, I0{}, I0{}, I1{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks, c_cur, sc_issue);   // (A0,B0) | read B1 of this step
-                    phase(I0{}, I1{}, I1{}, I1{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks, c_cur, sc_issue);   // (A0,B1) | read A1 of this step
-                    msn_wait_all_vmem();                // my part of step k+1 has landed
-                    __syncthreads();                   // ... and everyone's; this step's buffer is read out
-                    __builtin_amdgcn_sched_barrier(0);
-                    phase(I1{}, I1{}, I1{}, I0{}, I0{}, s_nxt, la, lb, ka, ke, ko, lsc, ks, c_nxt, sc_issue);   // (A1,B1) | read A0 of step k+1, refill A
-                    phase(I1{}, I0{}, I0{}, I1{}, I1{}, s_nxt, la, lb, ka, ke, ko, lsc, ks, c_nxt, sc_issue);   // (A1,B0) | read B1 of step k+1, refill B
+                    phase(I0{}, I0{}, I0{}, I1{}, I0{}, I0{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks, c_cur, sc_issue);    // (A0,B0) | read B1 of this step
+                    msn_barrier_lds();                 // this step's B part is read out by everyone
+                    phase(I0{}, I1{}, I1{}, I1{}, I0{}, I5{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks, c_cur, sc_issue);    // (A0,B1) | read A1 of this step, refill B 0-4
+                    msn_wait_vmem_but5_barrier();      // step k+1 has landed for everyone; this step's A part and scales are read out
+                    phase(I1{}, I1{}, I1{}, I0{}, I5{}, I6{}, I0{}, s_nxt, la, lb, ka, ke, ko, lsc, ks, c_nxt, sc_issue);    // (A1,B1) | read A0 of step k+1, refill B 5-7, A 0-2, A scales
+                    phase(I1{}, I0{}, I0{}, I1{}, I11{}, I5{}, I1{}, s_nxt, la, lb, ka, ke, ko, lsc, ks, c_nxt, sc_issue);   // (A1,B0) | read B1 of step k+1, refill A 3-7, B scales
                 } else {
                     // odd step: B order 1,0,0,1.  Holds A0, B1 of this step.
-                    phase(I0{}, I1{}, I0{}, I0{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks, c_cur, sc_issue);   // (A0,B1) | read B0 of this step
-                    phase(I0{}, I0{}, I1{}, I1{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks, c_cur, sc_issue);   // (A0,B0) | read A1 of this step
-                    msn_wait_all_vmem();
-                    __syncthreads();
-                    __builtin_amdgcn_sched_barrier(0);
-                    phase(I1{}, I0{}, I1{}, I0{}, I0{}, s_nxt, la, lb, ka, ke, ko, lsc, ks, c_nxt, sc_issue);   // (A1,B0) | read A0 of step k+1, refill A
-                    phase(I1{}, I1{}, I0{}, I0{}, I1{}, s_nxt, la, lb, ka, ke, ko, lsc, ks, c_nxt, sc_issue);   // (A1,B1) | read B0 of step k+1, refill B
+                    phase(I0{}, I1{}, I0{}, I0{}, I0{}, I0{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks, c_cur, sc_issue);    // (A0,B1) | read B0 of this step
+                    msn_barrier_lds();
+                    phase(I0{}, I0{}, I1{}, I1{}, I0{}, I5{}, IN{}, s_cur, la, lb, ka, ke, ko, lsc, ks, c_cur, sc_issue);    // (A0,B0) | read A1 of this step, refill B 0-4
+                    msn_wait_vmem_but5_barrier();
+                    phase(I1{}, I0{}, I1{}, I0{}, I5{}, I6{}, I0{}, s_nxt, la, lb, ka, ke, ko, lsc, ks, c_nxt, sc_issue);    // (A1,B0) | read A0 of step k+1, refill B 5-7, A 0-2, A scales
+                    phase(I1{}, I1{}, I0{}, I0{}, I11{}, I5{}, I1{}, s_nxt, la, lb, ka, ke, ko, lsc, ks, c_nxt, sc_issue);   // (A1,B1) | read B0 of step k+1, refill A 3-7, B scales
                 }
             }
         }
