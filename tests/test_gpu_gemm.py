@@ -137,6 +137,28 @@ def test_many_tiles_per_workgroup_exact(big_variant, M, N, K):
     assert (got32[rows] == want.out32).all()
 
 
+@pytest.mark.parametrize("M,N,K", [(4096, 4096, 4096), (4096, 4352, 4208), (2048, 2304, 14336)])
+def test_long_contraction_exact_every_element(M, N, K):
+    """Many K steps per tile (32, 33 - an odd count, the last one partial - and 112), every CU busy:
+    the refill of an LDS stage overlaps the reads of the other one for the whole contraction, so a
+    load that lands too early or too late shows as a wrong sum somewhere.  Small integers: every
+    partial sum is exact in binary32, every output element is checked, and three launches in a row
+    must agree bit for bit."""
+    rng = np.random.default_rng(M + N + K)
+    ai = rng.integers(-2, 3, size=(M, K)).astype(np.float32)
+    bi = rng.integers(-2, 3, size=(N, K)).astype(np.float32)
+    a = orc.encode_array(ai * 0.5, orc.E5M2)
+    b = orc.encode_array(bi * 4.0, orc.E4M3FN)
+    sa = (2.0 ** rng.integers(-3, 4, size=M)).astype(np.float32)
+    sb = (2.0 ** rng.integers(-3, 4, size=N)).astype(np.float32)
+    exact = ((ai @ bi.T) * 2.0 / sa[:, None] / sb[None, :]).astype(np.float32)   # |sums| <= 8 K < 2^24: exact
+    for _ in range(3):
+        got32 = host_f32(_run(a, orc.E5M2, sa, fp8.FP8_ROW, b, orc.E4M3FN, sb, fp8.FP8_ROW, fp8.FP8_OUT_FP32))
+        assert (got32 == exact).all()
+        got16 = host_bf16_bits(_run(a, orc.E5M2, sa, fp8.FP8_ROW, b, orc.E4M3FN, sb, fp8.FP8_ROW))
+        assert (got16 == orc.f32_to_bf16(exact)).all()
+
+
 @pytest.mark.parametrize("M,N,K", [(2304, 2560, 640), (2300, 2500, 400), (4608, 4608, 384), (8192, 4352, 256), (16384, 4096, 128)])
 def test_half_tiles_of_a_partly_filled_last_round(M, N, K):
     """When the last round of 256 x 256 tiles would fill at most half of the CUs, those tiles run as half tiles

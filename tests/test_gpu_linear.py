@@ -423,6 +423,25 @@ def test_grad_weight_hp_exact_on_small_integers(bf16_variant, M, K, N):
     assert (got == want16).all(), (M, K, N, np.argwhere(got != want16)[:4])
 
 
+@pytest.mark.parametrize("M,K,N", [(4096, 4096, 4096), (4128, 4352, 4096), (14336, 2304, 2048)])
+def test_grad_weight_hp_long_contraction_exact_every_element(M, K, N):
+    """Many contraction steps per tile with every CU busy (a whole number of steps, an odd count with a
+    partial last one, and a long one): integer inputs, every sum exact in binary32, every element of dW
+    checked, three launches bit for bit the same."""
+    rng = np.random.default_rng(M + K + N)
+    gi = rng.integers(-4, 5, size=(M, N)).astype(np.float32)
+    xi = rng.integers(-4, 5, size=(M, K)).astype(np.float32)
+    dy, x = si.f32_to_bf16_bits(gi), si.f32_to_bf16_bits(xi)
+    exact16 = orc.f32_to_bf16((gi.T @ xi).astype(np.float32))       # |sums| <= 16 M < 2^24: exact
+    rows = si.stratified_rows(N, 8)
+    _, want16 = orc.linear_bwd_dw_hp(dy, x, rows)
+    assert (want16 == exact16[rows]).all()
+    d_dy, d_x = dev_bf16(dy), dev_bf16(x)
+    for _ in range(3):
+        got = host_bf16_bits(fp8.fp8_grad_weight_hp(d_dy, d_x))
+        assert (got == exact16).all()
+
+
 @pytest.mark.parametrize("M,K,N", GW_SHAPES)
 def test_grad_weight_hp_random_inputs(bf16_variant, M, K, N):
     wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)

@@ -89,6 +89,32 @@ def test_mx_gemm_exact_on_small_integers(mx_variant, M, N, K):
         assert (got16 == want.out16).all()
 
 
+@pytest.mark.parametrize("M,N,K", [(4096, 4096, 4096), (4096, 4352, 4224), (2048, 2304, 14336)])
+def test_mx_gemm_long_contraction_exact_every_element(M, N, K):
+    """32, 33 and 112 K steps per tile with every CU busy: the refills of data and scale buffers overlap
+    the reads for the whole contraction.  Integer codes, block scales of 1/2, 1 or 2: every partial sum
+    fits the significand in any order, so the dequantized product in binary32 is exact; every element
+    is checked and three launches must agree bit for bit."""
+    rng = np.random.default_rng(M + N + K)
+    ai = rng.integers(-3, 4, size=(M, K)).astype(np.float32)
+    bi = rng.integers(-3, 4, size=(N, K)).astype(np.float32)
+    a, b = orc.encode_array(ai, orc.E5M2), orc.encode_array(bi, orc.E4M3FN)
+    ea = rng.integers(126, 129, size=(M, K // 32)).astype(np.uint8)
+    eb = rng.integers(126, 129, size=(N, K // 32)).astype(np.uint8)
+    ad = ai * np.repeat(np.exp2(ea.astype(np.float32) - 127.0), 32, axis=1)
+    bd = bi * np.repeat(np.exp2(eb.astype(np.float32) - 127.0), 32, axis=1)
+    exact = (ad @ bd.T).astype(np.float32)        # |sums| < 2^18 in units of 1/4: exact
+    # the oracle proper on a sample of rows
+    rows = si.stratified_rows(M, 8)
+    want = orc.mx_mm(a, orc.E5M2, ea, b, orc.E4M3FN, eb, rows)
+    assert (want.out32 == exact[rows]).all()
+    for _ in range(3):
+        got32 = host_f32(fp8.fp8_mx_scaled_mm(dev_u8(a), orc.E5M2, _dev_e(ea), dev_u8(b), orc.E4M3FN, _dev_e(eb), fp8.FP8_OUT_FP32))
+        assert (got32 == exact).all()
+        got16 = host_bf16_bits(fp8.fp8_mx_scaled_mm(dev_u8(a), orc.E5M2, _dev_e(ea), dev_u8(b), orc.E4M3FN, _dev_e(eb)))
+        assert (got16 == orc.f32_to_bf16(exact)).all()
+
+
 @pytest.mark.parametrize("M,N,K", SHAPES)
 def test_mx_gemm_random_codes(mx_variant, M, N, K):
     rng = np.random.default_rng(M + 3 * N + K)
