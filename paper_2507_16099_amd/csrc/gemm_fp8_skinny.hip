@@ -422,9 +422,14 @@ static hipError_t launch_sk(const uint8_t* a, int64_t lda, const float* sa, int 
                             const float* sb, int row_b, int M, int N, int K, void* out, int64_t ld_out, int out_f32,
                             hipStream_t st) {
     const int mt = (M + 15) / 16;                 // 1..4
-    // columns per wavefront: 16, 32 or 64.  Wider groups reuse every fragment of A for
-    // two or four MFMAs, narrower ones give more wavefronts; measured crossovers
-    const int nw = N >= 12288 ? 4 : (N >= 6144 ? 2 : 1);
+    // columns per wavefront: 16 or 32 (64 through the override).  Wider groups reuse every fragment of A
+    // for two or four MFMAs but shorten the ring of K steps in flight, narrower ones give more wavefronts;
+    // measured: 32 wins or ties from N = 6144 on, 64 never beats 32 (28672 x 8192: 5 % slower)
+    int nw = N >= 6144 ? 2 : 1;
+    if (const char* env_nw = std::getenv("FP8MI355_SKINNY_NW")) {     // 1, 2 or 4: tuning override
+        const int v = std::atoi(env_nw);
+        if (v == 1 || v == 2 || v == 4) nw = v;
+    }
     const int64_t groups = ((int64_t)N + 16 * nw - 1) / (16 * nw);
     // split K over the wavefronts of a workgroup until about 2048 wavefronts stream B
     int ks = 1;

@@ -193,6 +193,33 @@ SKINNY = [(1, 16, 16), (1, 4096, 4096), (5, 100, 400), (16, 1000, 2048), (17, 24
           (64, 14336, 4096), (48, 2048, 8208), (8, 300, 144), (32, 8208, 272), (20, 12304, 144), (32, 14336, 4096)]
 
 
+@pytest.mark.parametrize("nw", ["1", "2", "4"])
+@pytest.mark.parametrize("M,N,K", [(8, 4096, 4096), (32, 14336, 4096), (20, 12304, 144), (64, 6160, 2064)])
+def test_few_rows_columns_per_wavefront(few_rows_form, nw, M, N, K):
+    """The few-row kernel with 16, 32 and 64 output columns per wavefront (the dispatch picks 16 or 32 by N;
+    FP8MI355_SKINNY_NW forces one): the three settings add the same products in the same order, so they
+    agree bit for bit, and the exact small-integer result is the check."""
+    rng = np.random.default_rng(M + N + K)
+    ai = rng.integers(-2, 3, size=(M, K)).astype(np.float32)
+    bi = rng.integers(-2, 3, size=(N, K)).astype(np.float32)
+    a, b = orc.encode_array(ai * 0.5, orc.E4M3FN), orc.encode_array(bi * 4.0, orc.E4M3FN)
+    sa = (2.0 ** rng.integers(-3, 4, size=M)).astype(np.float32)
+    sb = (2.0 ** rng.integers(-3, 4, size=N)).astype(np.float32)
+    exact = ((ai @ bi.T) * 2.0 / sa[:, None] / sb[None, :]).astype(np.float32)
+    old = os.environ.get("FP8MI355_SKINNY_NW")
+    os.environ["FP8MI355_SKINNY_NW"] = nw
+    try:
+        got32 = host_f32(_run(a, orc.E4M3FN, sa, fp8.FP8_ROW, b, orc.E4M3FN, sb, fp8.FP8_ROW, fp8.FP8_OUT_FP32))
+        got16 = host_bf16_bits(_run(a, orc.E4M3FN, sa, fp8.FP8_ROW, b, orc.E4M3FN, sb, fp8.FP8_ROW))
+    finally:
+        if old is None:
+            os.environ.pop("FP8MI355_SKINNY_NW", None)
+        else:
+            os.environ["FP8MI355_SKINNY_NW"] = old
+    assert (got32 == exact).all()
+    assert (got16 == orc.f32_to_bf16(exact)).all()
+
+
 @pytest.mark.parametrize("M,N,K", SKINNY)
 def test_few_rows_exact_on_small_integers(few_rows_form, M, N, K):
     """M <= 64 takes the kernel that streams B once (the decode shape of
