@@ -703,9 +703,12 @@ int fp8_mx_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_
     if (workspace_bytes < p.total) return fail(FP8_ERR_WORKSPACE, "%s: workspace %zu < %zu bytes", fn, workspace_bytes, p.total);
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* ws = static_cast<uint8_t*>(workspace);
-    FP8_TRY(fp8k::launch_mx_quant(x, M, K, K, fmt_x, ws + p.xq, K, ws + p.xe, K / 32, st));
-    FP8_TRY(fp8k::launch_mx_quant(w, N, K, K, fmt_w, ws + p.wq, K, ws + p.we, K / 32, st));
-    FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.xq, K, fmt_x, ws + p.xe, K / 32, ws + p.wq, K, fmt_w, ws + p.we, K / 32, M, N, K, y,
+    // scales between the quantizers and the GEMM: in slabs of sixteen blocks (negative leading dimension) where the GEMM takes them
+    const bool slab = fp8k::gemm_mxfp8_takes_slab_scales(K, K, M, N, K);
+    const int64_t ld_xe = slab ? -M : K / 32, ld_we = slab ? -N : K / 32;
+    FP8_TRY(fp8k::launch_mx_quant(x, M, K, K, fmt_x, ws + p.xq, K, ws + p.xe, ld_xe, st));
+    FP8_TRY(fp8k::launch_mx_quant(w, N, K, K, fmt_w, ws + p.wq, K, ws + p.we, ld_we, st));
+    FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.xq, K, fmt_x, ws + p.xe, ld_xe, ws + p.wq, K, fmt_w, ws + p.we, ld_we, M, N, K, y,
                                     N, 0, st));
     return FP8_OK;
 }
@@ -747,9 +750,12 @@ int fp8_block_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* ws = static_cast<uint8_t*>(workspace);
     // X in tiles of 1 x 128 along K, W in blocks of 128 x 128; the block-scaled GEMM applies the power-of-two scales
-    FP8_TRY(fp8k::launch_block_quant(x, M, K, K, 1, fmt_x, ws + p.xq, K, ws + p.xe, K / 32, st));
-    FP8_TRY(fp8k::launch_block_quant(w, N, K, K, 128, fmt_w, ws + p.wq, K, ws + p.we, K / 32, st));
-    FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.xq, K, fmt_x, ws + p.xe, K / 32, ws + p.wq, K, fmt_w, ws + p.we, K / 32, M, N, K, y,
+    // scales between the quantizers and the GEMM: in slabs of sixteen blocks (negative leading dimension) where the GEMM takes them
+    const bool slab = fp8k::gemm_mxfp8_takes_slab_scales(K, K, M, N, K);
+    const int64_t ld_xe = slab ? -M : K / 32, ld_we = slab ? -N : K / 32;
+    FP8_TRY(fp8k::launch_block_quant(x, M, K, K, 1, fmt_x, ws + p.xq, K, ws + p.xe, ld_xe, st));
+    FP8_TRY(fp8k::launch_block_quant(w, N, K, K, 128, fmt_w, ws + p.wq, K, ws + p.we, ld_we, st));
+    FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.xq, K, fmt_x, ws + p.xe, ld_xe, ws + p.wq, K, fmt_w, ws + p.we, ld_we, M, N, K, y,
                                     N, 0, st));
     return FP8_OK;
 }
@@ -814,21 +820,26 @@ int fp8_mx_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, i
     if (workspace_bytes < p.total) return fail(FP8_ERR_WORKSPACE, "%s: workspace %zu < %zu bytes", fn, workspace_bytes, p.total);
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* ws = static_cast<uint8_t*>(workspace);
+    // scales in slabs of sixteen blocks (negative leading dimension) where the product that reads them takes them
+    const bool slab_dx = dx && fp8k::gemm_mxfp8_takes_slab_scales(N, N, M, K, N);
+    const bool slab_dw = dw && fp8k::gemm_mxfp8_takes_slab_scales(M, M, N, K, M);
+    const int64_t ld_dye = slab_dx ? -M : N / 32, ld_wte = slab_dx ? -K : N / 32;
+    const int64_t ld_dyte = slab_dw ? -N : M / 32, ld_xte = slab_dw ? -K : M / 32;
     // all quantizations first, then the products back to back
     if (dx && dw) {   // the gradient in both orientations from one read
-        FP8_TRY(fp8k::launch_mx_quant_t(dy, M, N, N, fmt_dy, ws + p.dytq, M, ws + p.dyte, M / 32, ws + p.dyq, N, ws + p.dye, N / 32, st));
+        FP8_TRY(fp8k::launch_mx_quant_t(dy, M, N, N, fmt_dy, ws + p.dytq, M, ws + p.dyte, ld_dyte, ws + p.dyq, N, ws + p.dye, ld_dye, st));
     } else if (dx) {
-        FP8_TRY(fp8k::launch_mx_quant(dy, M, N, N, fmt_dy, ws + p.dyq, N, ws + p.dye, N / 32, st));
+        FP8_TRY(fp8k::launch_mx_quant(dy, M, N, N, fmt_dy, ws + p.dyq, N, ws + p.dye, ld_dye, st));
     } else {
-        FP8_TRY(fp8k::launch_mx_quant_t(dy, M, N, N, fmt_dy, ws + p.dytq, M, ws + p.dyte, M / 32, nullptr, 0, nullptr, 0, st));
+        FP8_TRY(fp8k::launch_mx_quant_t(dy, M, N, N, fmt_dy, ws + p.dytq, M, ws + p.dyte, ld_dyte, nullptr, 0, nullptr, 0, st));
     }
-    if (dx) FP8_TRY(fp8k::launch_mx_quant_t(w, N, K, K, fmt_w, ws + p.wtq, N, ws + p.wte, N / 32, nullptr, 0, nullptr, 0, st));
-    if (dw) FP8_TRY(fp8k::launch_mx_quant_t(x, M, K, K, fmt_x, ws + p.xtq, M, ws + p.xte, M / 32, nullptr, 0, nullptr, 0, st));
+    if (dx) FP8_TRY(fp8k::launch_mx_quant_t(w, N, K, K, fmt_w, ws + p.wtq, N, ws + p.wte, ld_wte, nullptr, 0, nullptr, 0, st));
+    if (dw) FP8_TRY(fp8k::launch_mx_quant_t(x, M, K, K, fmt_x, ws + p.xtq, M, ws + p.xte, ld_xte, nullptr, 0, nullptr, 0, st));
     if (dx)
-        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dyq, N, fmt_dy, ws + p.dye, N / 32, ws + p.wtq, N, fmt_w, ws + p.wte, N / 32,
+        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dyq, N, fmt_dy, ws + p.dye, ld_dye, ws + p.wtq, N, fmt_w, ws + p.wte, ld_wte,
                                         M, K, N, dx, K, 0, st));
     if (dw)
-        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dytq, M, fmt_dy, ws + p.dyte, M / 32, ws + p.xtq, M, fmt_x, ws + p.xte, M / 32,
+        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dytq, M, fmt_dy, ws + p.dyte, ld_dyte, ws + p.xtq, M, fmt_x, ws + p.xte, ld_xte,
                                         N, K, M, dw, K, 0, st));
     return FP8_OK;
 }
@@ -896,21 +907,26 @@ int fp8_block_linear_bwd(const void* dy, const void* x, const void* w, int64_t M
     if (workspace_bytes < p.total) return fail(FP8_ERR_WORKSPACE, "%s: workspace %zu < %zu bytes", fn, workspace_bytes, p.total);
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* ws = static_cast<uint8_t*>(workspace);
+    // scales in slabs of sixteen blocks (negative leading dimension) where the product that reads them takes them
+    const bool slab_dx = dx && fp8k::gemm_mxfp8_takes_slab_scales(N, N, M, K, N);
+    const bool slab_dw = dw && fp8k::gemm_mxfp8_takes_slab_scales(M, M, N, K, M);
+    const int64_t ld_dye = slab_dx ? -M : N / 32, ld_wte = slab_dx ? -K : N / 32;
+    const int64_t ld_dyte = slab_dw ? -N : M / 32, ld_xte = slab_dw ? -K : M / 32;
     // dX = dY W: dY in tiles along N, W^T [K, N] in its 128 x 128 blocks; dW = dY^T X: dY^T and X^T in tiles along M
     if (dx && dw) {   // the gradient in both orientations from one read
-        FP8_TRY(fp8k::launch_block_quant_t(dy, M, N, N, 1, fmt_dy, ws + p.dytq, M, ws + p.dyte, M / 32, st, ws + p.dyq, N, ws + p.dye, N / 32));
+        FP8_TRY(fp8k::launch_block_quant_t(dy, M, N, N, 1, fmt_dy, ws + p.dytq, M, ws + p.dyte, ld_dyte, st, ws + p.dyq, N, ws + p.dye, ld_dye));
     } else if (dx) {
-        FP8_TRY(fp8k::launch_block_quant(dy, M, N, N, 1, fmt_dy, ws + p.dyq, N, ws + p.dye, N / 32, st));
+        FP8_TRY(fp8k::launch_block_quant(dy, M, N, N, 1, fmt_dy, ws + p.dyq, N, ws + p.dye, ld_dye, st));
     } else {
-        FP8_TRY(fp8k::launch_block_quant_t(dy, M, N, N, 1, fmt_dy, ws + p.dytq, M, ws + p.dyte, M / 32, st));
+        FP8_TRY(fp8k::launch_block_quant_t(dy, M, N, N, 1, fmt_dy, ws + p.dytq, M, ws + p.dyte, ld_dyte, st));
     }
-    if (dx) FP8_TRY(fp8k::launch_block_quant_t(w, N, K, K, 128, fmt_w, ws + p.wtq, N, ws + p.wte, N / 32, st));
-    if (dw) FP8_TRY(fp8k::launch_block_quant_t(x, M, K, K, 1, fmt_x, ws + p.xtq, M, ws + p.xte, M / 32, st));
+    if (dx) FP8_TRY(fp8k::launch_block_quant_t(w, N, K, K, 128, fmt_w, ws + p.wtq, N, ws + p.wte, ld_wte, st));
+    if (dw) FP8_TRY(fp8k::launch_block_quant_t(x, M, K, K, 1, fmt_x, ws + p.xtq, M, ws + p.xte, ld_xte, st));
     if (dx)
-        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dyq, N, fmt_dy, ws + p.dye, N / 32, ws + p.wtq, N, fmt_w, ws + p.wte, N / 32,
+        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dyq, N, fmt_dy, ws + p.dye, ld_dye, ws + p.wtq, N, fmt_w, ws + p.wte, ld_wte,
                                         M, K, N, dx, K, 0, st));
     if (dw)
-        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dytq, M, fmt_dy, ws + p.dyte, M / 32, ws + p.xtq, M, fmt_x, ws + p.xte, M / 32,
+        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dytq, M, fmt_dy, ws + p.dyte, ld_dyte, ws + p.xtq, M, fmt_x, ws + p.xte, ld_xte,
                                         N, K, M, dw, K, 0, st));
     return FP8_OK;
 }

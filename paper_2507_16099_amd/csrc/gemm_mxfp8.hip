@@ -244,19 +244,34 @@ static hipError_t launch_mx_t(const uint8_t* a, int64_t lda, const uint8_t* ea, 
 
 // K must be a multiple of 128 and ld_ea, ld_eb multiples of 4 (a K step reads one aligned
 // dword of scales per row); checked by the caller
+// large problems: the LDS-DMA kernel (FP8MI355_MX_VARIANT=0 forces this file's kernel, 1 the other)
+static bool mx_takes_snake(int64_t lda, int64_t ldb, int64_t M, int64_t N, int64_t K) {
+    const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
+    const char* e = std::getenv("FP8MI355_MX_VARIANT");
+    const bool big = e ? std::atoi(e) == 1 : tiles256 > 64;
+    return big && K > 0 && gemm_fp8_pipelined_supported(lda, ldb);
+}
+
+// True when launch_gemm_mxfp8 on this problem reads its scales in slabs of sixteen blocks (a negative leading
+// dimension, see there): the LDS-DMA kernel with whole 16-byte scale pieces.  FP8MI355_MX_SLAB=0 switches it off.
+bool gemm_mxfp8_takes_slab_scales(int64_t lda, int64_t ldb, int64_t M, int64_t N, int64_t K) {
+    const char* e = std::getenv("FP8MI355_MX_SLAB");
+    if (e && std::atoi(e) == 0) return false;
+    return mx_takes_snake(lda, ldb, M, N, K) && K % 512 == 0 && M * (K / 32) < (1ll << 31) && N * (K / 32) < (1ll << 31);
+}
+
+// ld_ea / ld_eb >= 0: scale rows of that many bytes.  < 0: slabs of sixteen blocks, [K / 512][-ld rows][16 bytes]
+// (only where gemm_mxfp8_takes_slab_scales says so, and for both operands alike).
 hipError_t launch_gemm_mxfp8(const uint8_t* a, int64_t lda, int fmt_a, const uint8_t* ea, int64_t ld_ea,
                              const uint8_t* b, int64_t ldb, int fmt_b, const uint8_t* eb, int64_t ld_eb, int64_t M,
                              int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32, hipStream_t st) {
     if (M == 0 || N == 0) return hipSuccess;
-    // large problems: the LDS-DMA kernel (FP8MI355_MX_VARIANT=0 forces this file's kernel, 1 the other)
-    {
-        const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
-        const char* e = std::getenv("FP8MI355_MX_VARIANT");
-        const bool big = e ? std::atoi(e) == 1 : tiles256 > 64;
-        if (big && K > 0 && gemm_fp8_pipelined_supported(lda, ldb) && ld_ea < (1 << 23) && ld_eb < (1 << 23))
-            return launch_gemm_mxfp8_snake(a, lda, fmt_a, ea, ld_ea, b, ldb, fmt_b, eb, ld_eb, M, N, K, out, ld_out, out_f32,
-                                           st);
+    if (ld_ea < 0 || ld_eb < 0) {
+        if (!(ld_ea < 0 && ld_eb < 0) || -ld_ea < M || -ld_eb < N || !gemm_mxfp8_takes_slab_scales(lda, ldb, M, N, K))
+            return hipErrorInvalidValue;
     }
+    if (mx_takes_snake(lda, ldb, M, N, K) && ld_ea < (1 << 23) && ld_eb < (1 << 23))
+        return launch_gemm_mxfp8_snake(a, lda, fmt_a, ea, ld_ea, b, ldb, fmt_b, eb, ld_eb, M, N, K, out, ld_out, out_f32, st);
     const int m = (int)M, n = (int)N, k = (int)K;
 #define FP8K_MX(FA_, FB_)                                                                                  \
     if (fmt_a == FA_ && fmt_b == FB_)                                                                      \

@@ -107,12 +107,21 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
     const v4i_x rsrc_a = {(int)(uint32_t)pa, (int)(uint32_t)(pa >> 32), (int)((int64_t)(rows_a - 1) * lda + K), 0x00020000};
     const v4i_x rsrc_b = {(int)(uint32_t)pb, (int)(uint32_t)(pb >> 32), (int)((int64_t)(rows_b - 1) * ldb + K), 0x00020000};
 
-    // scale panels: rows m0.. of EA, n0.. of EB, K / 32 bytes per row; wave w fetches rows 64 w + lane
-    const uint64_t pea = reinterpret_cast<uint64_t>(EA + (int64_t)m0 * ld_ea);
-    const uint64_t peb = reinterpret_cast<uint64_t>(EB + (int64_t)n0 * ld_eb);
-    const v4i_x rsrc_ea = {(int)(uint32_t)pea, (int)(uint32_t)(pea >> 32), (int)((int64_t)(rows_a - 1) * ld_ea + K / 32), 0x00020000};
-    const v4i_x rsrc_eb = {(int)(uint32_t)peb, (int)(uint32_t)(peb >> 32), (int)((int64_t)(rows_b - 1) * ld_eb + K / 32), 0x00020000};
-    const uint32_t vea0 = (uint32_t)((wave * 64 + lane) * (int)ld_ea), veb0 = (uint32_t)((wave * 64 + lane) * (int)ld_eb);
+    // scale panels: rows m0.. of EA, n0.. of EB, K / 32 bytes per row; wave w fetches rows 64 w + lane.
+    // A negative leading dimension (SC16 only) means slabs of sixteen blocks, [K / 512][-ld rows][16 bytes]: the
+    // 256 pieces a tile needs for four K steps are 4 KB in a row (8 cache lines per wave load instead of 64).
+    // Rows past the operand's end then read the next slab's first rows instead of zeros: their products only
+    // reach output rows / columns that are never stored.  The descriptor ends with the buffer.
+    const bool slab_a = ld_ea < 0, slab_b = ld_eb < 0;
+    const int64_t gsa = slab_a ? -ld_ea * 16 : 16, gsb = slab_b ? -ld_eb * 16 : 16;     // bytes from one group of four K steps to the next
+    const uint64_t pea = reinterpret_cast<uint64_t>(EA + (int64_t)m0 * (slab_a ? 16 : ld_ea));
+    const uint64_t peb = reinterpret_cast<uint64_t>(EB + (int64_t)n0 * (slab_b ? 16 : ld_eb));
+    const int64_t nrec_a = slab_a ? (int64_t)(K / 512) * gsa - (int64_t)m0 * 16 : (int64_t)(rows_a - 1) * ld_ea + K / 32;
+    const int64_t nrec_b = slab_b ? (int64_t)(K / 512) * gsb - (int64_t)n0 * 16 : (int64_t)(rows_b - 1) * ld_eb + K / 32;
+    const v4i_x rsrc_ea = {(int)(uint32_t)pea, (int)(uint32_t)(pea >> 32), (int)nrec_a, 0x00020000};
+    const v4i_x rsrc_eb = {(int)(uint32_t)peb, (int)(uint32_t)(peb >> 32), (int)nrec_b, 0x00020000};
+    const uint32_t vea0 = (uint32_t)((wave * 64 + lane) * (slab_a ? 16 : (int)ld_ea)), veb0 = (uint32_t)((wave * 64 + lane) * (slab_b ? 16 : (int)ld_eb));
+    const uint32_t gsa32 = (uint32_t)gsa, gsb32 = (uint32_t)gsb;
     const uint32_t lds_sc = (uint32_t)(size_t)smem + (uint32_t)TILE + (uint32_t)wave * 256u;   // + BM * 4 for B
     const uint32_t lds_sc16 = (uint32_t)(size_t)smem + (uint32_t)(2 * STAGE) + (uint32_t)wave * 1024u;   // + SCBUF per buffer, + BM * 16 for B
 
@@ -270,9 +279,9 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
             if constexpr (RDA == 0) { if (t == 9) scales_b_read(rsc, RH, raw); if (t == 14) sb[RH] = scales_pack(raw); }
             // the refill of the scales rides in a slot that has neither a read nor a data load
             if constexpr (SC16) {
-                // (lsc, ks: scale buffer and byte offset of the next group of four steps)
-                if constexpr (DMA == 0) { if (t == 8 && sc_issue) msn_lds_dma16(rsrc_ea, lsc, vea0 + ks); }
-                if constexpr (DMA == 1) { if (t == 8 && sc_issue) msn_lds_dma16(rsrc_eb, lsc + BM * 16, veb0 + ks); }
+                // (lsc, ks: scale buffer and number of the next group of four steps)
+                if constexpr (DMA == 0) { if (t == 8 && sc_issue) msn_lds_dma16(rsrc_ea, lsc, vea0 + ks * gsa32); }
+                if constexpr (DMA == 1) { if (t == 8 && sc_issue) msn_lds_dma16(rsrc_eb, lsc + BM * 16, veb0 + ks * gsb32); }
             } else {
                 if constexpr (DMA == 0) { if (t == 8) msn_lds_dma4(rsrc_ea, lsc, vea0 + ks); }
                 if constexpr (DMA == 1) { if (t == 8) msn_lds_dma4(rsrc_eb, lsc + BM * 4, veb0 + ks); }
@@ -319,7 +328,7 @@ __global__ __launch_bounds__(msn::NT) void gemm_mxfp8_snake_kernel(
                 const int q1 = (k >> 2) + 1;
                 const bool sc_issue = SC16 && (k & 3) == 1 && q1 * 512 < K;
                 const uint32_t lsc = SC16 ? lds_sc16 + (uint32_t)((q1 & 1) * SCBUF) : lds_sc + (uint32_t)(par * STAGE);
-                const uint32_t ks = SC16 ? (uint32_t)(q1 * 16) : (k2 < K ? (uint32_t)(k2 >> 5) : OOB);
+                const uint32_t ks = SC16 ? (uint32_t)q1 : (k2 < K ? (uint32_t)(k2 >> 5) : OOB);   // SC16: the group's number
                 const uint8_t* c_cur = SC16 ? smem + 2 * STAGE + ((k >> 2) & 1) * SCBUF + (k & 3) * 4 : s_cur;
                 const uint8_t* c_nxt = SC16 ? smem + 2 * STAGE + (((k + 1) >> 2) & 1) * SCBUF + ((k + 1) & 3) * 4 : s_nxt;
                 // The sixteen data loads of the refill are spread over phases 2-4 (B part first: it is read out after

@@ -116,6 +116,7 @@ hipError_t launch_mx_quant(const void* x, int64_t rows, int64_t cols, int64_t ld
 hipError_t launch_mx_quant_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, uint8_t* qt, int64_t ld_t,
                              uint8_t* et, int64_t ld_e, uint8_t* q_row, int64_t ld_row, uint8_t* e_row, int64_t ld_er,
                              hipStream_t st);
+bool gemm_mxfp8_takes_slab_scales(int64_t lda, int64_t ldb, int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemm_mxfp8(const uint8_t* a, int64_t lda, int fmt_a, const uint8_t* ea, int64_t ld_ea,
                              const uint8_t* b, int64_t ldb, int fmt_b, const uint8_t* eb, int64_t ld_eb, int64_t M,
                              int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32, hipStream_t st);

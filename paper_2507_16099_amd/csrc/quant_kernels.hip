@@ -963,6 +963,15 @@ hipError_t launch_sigmoid_bwd(const void* dy, const void* y, int64_t n, void* dz
 // maximum)) - emax of the element format (8 for E4M3, 15 for E5M2), stored as
 // the E8M0 byte exponent + 127 (clamped to [0, 254]; an all-zero block gets 0);
 // elements = x * 2^-exponent (exact), saturating round-to-nearest-even cast.
+// Offset of the scale byte of block kb of row r.  ld_e >= 0: rows of ld_e bytes (the layout of the public
+// entry points).  ld_e < 0: slabs of sixteen blocks, [kb / 16][row][16 bytes] with -ld_e rows per slab: the
+// scales that one 256-row tile of the block-scaled GEMM needs for four K steps are then 4 KB in a row (the
+// linear entry points use it between their quantizers and the GEMM).  Four consecutive blocks from a multiple
+// of four stay consecutive in both layouts.
+__device__ __forceinline__ int64_t e8_off(int64_t r, int64_t kb, int64_t ld_e) {
+    return ld_e >= 0 ? r * ld_e + kb : ((kb >> 4) * -ld_e + r) * 16 + (kb & 15);
+}
+
 // Four lanes own a block (one 128-bit load each); the maximum is taken on the
 // bfloat16 magnitude bits, whose exponent field gives floor(log2) directly.
 template <int FMT, bool DENSE>
@@ -983,10 +992,11 @@ __global__ __launch_bounds__(256) void mx_quant_kernel(const uint16_t* __restric
         // DENSE: all three matrices have no row padding, so the flat vector index addresses them directly
         // (no 64-bit division per thread)
         if constexpr (DENSE) {
-            xo[u] = v * 8; qo[u] = v * 8; eo[u] = v >> 2;
+            xo[u] = v * 8; qo[u] = v * 8;
+            eo[u] = ld_e >= 0 ? v >> 2 : (live ? e8_off(v / vpr, (v % vpr) >> 2, ld_e) : 0);
         } else {
             const int64_t r = live ? v / vpr : 0, cv = live ? v % vpr : 0;
-            xo[u] = r * ld + cv * 8; qo[u] = r * ld_q + cv * 8; eo[u] = r * ld_e + (cv >> 2);
+            xo[u] = r * ld + cv * 8; qo[u] = r * ld_q + cv * 8; eo[u] = e8_off(r, cv >> 2, ld_e);
         }
         d[u] = live ? load_stream(x + xo[u]) : make_uint4(0, 0, 0, 0);
     }
@@ -1018,7 +1028,7 @@ hipError_t launch_mx_quant(const void* x, int64_t rows, int64_t cols, int64_t ld
                            uint8_t* e8m0, int64_t ld_e, hipStream_t st) {
     if (rows == 0 || cols == 0) return hipSuccess;
     const int64_t nvec = rows * (cols / 8);
-    const bool dense = ld == cols && ld_q == cols && ld_e == cols / 32;
+    const bool dense = ld == cols && ld_q == cols && (ld_e == cols / 32 || ld_e < 0);
     const int64_t per_block = dense ? 1024 : 256;       // the dense kernel takes 4 vectors per thread
     const int64_t blocks = (nvec + per_block - 1) / per_block;
     if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
@@ -1091,7 +1101,7 @@ __global__ __launch_bounds__(256) void block_quant_1x128_kernel(const uint16_t* 
         if (v0 + u * 256 < nvec) {
             store_stream(q + r[u] * ld_q + cv[u] * 8, cast8<FMT>(d[u], s));
             if ((threadIdx.x & 15) == 0)     // ld_e % 4 == 0 and (cv / 4) % 4 == 0: an aligned dword
-                *reinterpret_cast<uint32_t*>(e8m0 + r[u] * ld_e + (cv[u] >> 2)) = byte * 0x01010101u;
+                *reinterpret_cast<uint32_t*>(e8m0 + e8_off(r[u], cv[u] >> 2, ld_e)) = byte * 0x01010101u;
         }
     }
 }
@@ -1128,7 +1138,7 @@ __global__ __launch_bounds__(256) void block_quant_128x128_kernel(const uint16_t
         if (r < rows) store_stream(q + r * ld_q + c, cast8<FMT>(v[j], s));
     }
     if (threadIdx.x < 128 && r0 + threadIdx.x < rows) {
-        *reinterpret_cast<uint32_t*>(e8m0 + (r0 + threadIdx.x) * ld_e + (c0 >> 5)) = byte * 0x01010101u;
+        *reinterpret_cast<uint32_t*>(e8m0 + e8_off(r0 + threadIdx.x, c0 >> 5, ld_e)) = byte * 0x01010101u;
     }
 }
 
@@ -1289,7 +1299,7 @@ __global__ __launch_bounds__(256) void mx_quant_t_kernel(const uint16_t* __restr
         store_stream(qt + oc * ld_t + orow, tile16[cc * PARTS + (p ^ ((cc >> 3) & 7))]);
     }
     if (threadIdx.x < 128 && c0 + threadIdx.x < cols) {
-        uint8_t* dst = et + (c0 + threadIdx.x) * ld_e + r0 / 32;
+        uint8_t* dst = et + e8_off(c0 + threadIdx.x, r0 / 32, ld_e);
         const uint32_t four = reinterpret_cast<const uint32_t*>(ebytes)[threadIdx.x];
         if (r0 + TR <= rows) {
             *reinterpret_cast<uint32_t*>(dst) = four;   // ld_e % 4 == 0 and r0 / 32 % 4 == 0
@@ -1301,7 +1311,7 @@ __global__ __launch_bounds__(256) void mx_quant_t_kernel(const uint16_t* __restr
         // the tile's 128 x 4 row-direction scale bytes, one dword per row (threads 128..255)
         const int rr = (int)threadIdx.x - 128;
         if (rr >= 0 && r0 + rr < rows) {
-            uint8_t* dst = e_row + (r0 + rr) * ld_er + c0 / 32;
+            uint8_t* dst = e_row + e8_off(r0 + rr, c0 / 32, ld_er);
             const uint32_t four = reinterpret_cast<const uint32_t*>(rbytes)[rr];
             if (c0 + 128 <= cols) {
                 *reinterpret_cast<uint32_t*>(dst) = four;   // ld_er % 4 == 0 and c0 / 32 % 4 == 0
@@ -1366,7 +1376,7 @@ __global__ __launch_bounds__(256) void block_quant_t_kernel(const uint16_t* __re
             const float sr = pow2_block_scale<FMT>(mr, byte);
             const int64_t r = r0 + ty * 8 + j;
             store_stream(q_row + r * ld_row + c, cast8<FMT>(v[j], sr));                   // cols % 128 == 0: inside
-            if (tx == 0) *reinterpret_cast<uint32_t*>(e_row + r * ld_er + (c0 >> 5)) = byte * 0x01010101u;
+            if (tx == 0) *reinterpret_cast<uint32_t*>(e_row + e8_off(r, c0 >> 5, ld_er)) = byte * 0x01010101u;
         }
     }
     float factor[8];
@@ -1438,7 +1448,7 @@ __global__ __launch_bounds__(256) void block_quant_t_kernel(const uint16_t* __re
         store_stream(qt + oc * ld_t + r0 + p * 16, tile16[cc * PARTS + (p ^ ((cc >> 3) & 7))]);
     }
     if (threadIdx.x < 128 && c0 + threadIdx.x < cols)                 // ld_e % 4 == 0 and (r0 / 32) % 4 == 0
-        *reinterpret_cast<uint32_t*>(et + (c0 + threadIdx.x) * ld_e + r0 / 32) = (uint32_t)ebytes[threadIdx.x] * 0x01010101u;
+        *reinterpret_cast<uint32_t*>(et + e8_off(c0 + threadIdx.x, r0 / 32, ld_e)) = (uint32_t)ebytes[threadIdx.x] * 0x01010101u;
 }
 
 // block_rows: blocks of x^T, 1 (tiles of 1 x 128 of x^T) or 128 (128 x 128); rows % 128 == 0, cols % 8 == 0.

@@ -270,3 +270,49 @@ def test_mx_full_size_llama_ffn_backward_sampled_rows():
     for got, want in ((host_bf16_bits(dx[torch.from_numpy(rx).cuda()]), wx), (host_bf16_bits(dw[torch.from_numpy(rw).cuda()]), ww)):
         assert orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want.out16)) <= TOL
         assert float((got == want.out16).mean()) > 0.97
+
+
+def _with_env(values, fn):
+    import os
+    old = {k: os.environ.get(k) for k in values}
+    os.environ.update(values)
+    try:
+        return fn()
+    finally:
+        for k, v in old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+
+
+@pytest.mark.parametrize("M,K,N", [(640, 1024, 896), (512, 640, 1024), (1536, 512, 1024), (1024, 1024, 640)])
+def test_scale_slabs_between_quantizers_and_gemm(M, K, N):
+    """Inside the MX and blockwise linear entry points the E8M0 scales travel in slabs of sixteen blocks
+    ([blocks / 16][rows][16 bytes]) whenever the product that reads them runs on the LDS-DMA kernel with a
+    contraction that is a multiple of 512.  Forced here on small ragged shapes (row counts that end inside
+    a 256-row tile, products with and without a suitable contraction): outputs must equal the plain layout's
+    bit for bit, and the oracle's within tolerance."""
+    wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)
+    x, w, dy = wl.x(), wl.w(), wl.dy()
+    dx_, dw_, dy_ = dev_bf16(x), dev_bf16(w), dev_bf16(dy)
+
+    def run_all():
+        outs = [fp8.fp8_mx_linear_fwd(dx_, dw_)]
+        outs += list(fp8.fp8_mx_linear_bwd(dy_, dx_, dw_))
+        if M % 128 == 0 and N % 128 == 0 and K % 128 == 0:
+            outs.append(fp8.fp8_block_linear_fwd(dx_, dw_))
+            outs += list(fp8.fp8_block_linear_bwd(dy_, dx_, dw_))
+        return [host_bf16_bits(o) for o in outs]
+
+    slab = _with_env({"FP8MI355_MX_VARIANT": "1", "FP8MI355_MX_SLAB": "1"}, run_all)
+    plain = _with_env({"FP8MI355_MX_VARIANT": "1", "FP8MI355_MX_SLAB": "0"}, run_all)
+    assert len(slab) == len(plain)
+    for a, b in zip(slab, plain):
+        assert (a == b).all()
+    wy = orc.mx_linear_fwd(x, w)
+    wx, ww = orc.mx_linear_bwd(dy, x, w)
+    for got, want in zip(slab[:3], (wy, wx, ww)):
+        assert orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want.out16)) <= TOL
+        assert float((got == want.out16).mean()) > 0.95
+
