@@ -240,7 +240,6 @@ __global__ __launch_bounds__(sn::NT) void gemm_fp8_snake_kernel(
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
-    using IN = std::integral_constant<int, -1>;
     using I5 = std::integral_constant<int, 5>;
     using I6 = std::integral_constant<int, 6>;
     using I11 = std::integral_constant<int, 11>;
