@@ -251,6 +251,26 @@ int fp8_linear_fwd_prequantized(const void* x, int64_t M, int64_t K, int fmt_x, 
                                 void* stream);
 
 /*
+ * fp8_linear_fwd_prequantized for callers that cannot allocate device memory or
+ * hand over a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, checks, kernels and results
+ * as fp8_linear_fwd_prequantized, minus the workspace: the activation codes and
+ * scales go into a buffer of FP8_STATIC_SCRATCH_BYTES bytes that lives inside the
+ * library's device image (one copy per GPU, held until the process ends).  The
+ * call allocates and frees nothing.  Problems whose
+ * fp8_linear_prequantized_workspace_bytes(M, K) exceeds FP8_STATIC_SCRATCH_BYTES
+ * are rejected with FP8_ERR_WORKSPACE before anything is launched (8 MiB: e.g.
+ * 256 tokens x 28672 features, or 2048 x 4096).  All calls on one GPU share the
+ * buffer, which keeps the previous call's contents (nothing in it has to start at
+ * zero): calls that overlap in time on the same GPU, on different streams or from
+ * different threads, race on it and must be serialised by the caller.
+ */
+#define FP8_STATIC_SCRATCH_BYTES (8u << 20)
+int fp8_linear_fwd_prequantized_static(const void* x, int64_t M, int64_t K, int fmt_x, int gran_x, int flags,
+                                       const uint8_t* wq, int64_t ldw, int fmt_w, const float* scale_w, int gran_w,
+                                       int64_t N, void* y, int64_t ld_y, void* stream);
+
+/*
  * Layer normalisation with the float8 cast fused into its epilogue: the block
  * in front of the linear layer in the paper's float8 microbenchmark (appendix
  * "Float8 Training Microbenchmarks": LayerNorm + Linear + Sigmoid), where the

@@ -4,9 +4,16 @@
 #include "../../include/fp8mi355.h"
 #include "launchers.hpp"
 
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+
+// Scratch of fp8_linear_fwd_prequantized_static, the entry point for callers that cannot allocate: every GPU the
+// library runs on holds its own copy of this array until the process ends.  In host code the name is only a handle
+// for hipGetSymbolAddress; kernels and copies get the per-device address that call returns.
+static __device__ __align__(256) unsigned char scratch[FP8_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -531,11 +538,12 @@ size_t fp8_linear_prequantized_workspace_bytes(int64_t M, int64_t K) {
     return align_up((size_t)M * (size_t)K, 256) + align_up(sizeof(float) * (size_t)(M > 0 ? M : 1), 256) + 256;
 }
 
-int fp8_linear_fwd_prequantized(const void* x, int64_t M, int64_t K, int fmt_x, int gran_x, int flags, const uint8_t* wq,
-                                int64_t ldw, int fmt_w, const float* scale_w, int gran_w, int64_t N, void* y,
-                                int64_t ld_y, void* workspace, size_t workspace_bytes, void* stream) {
-    g_err[0] = 0;
-    const char* fn = "fp8_linear_fwd_prequantized";
+namespace {
+// validation and composition shared by fp8_linear_fwd_prequantized and its variant without a workspace argument
+int linear_fwd_prequantized_impl(const char* fn, const void* x, int64_t M, int64_t K, int fmt_x, int gran_x, int flags,
+                                 const uint8_t* wq, int64_t ldw, int fmt_w, const float* scale_w, int gran_w, int64_t N,
+                                 void* y, int64_t ld_y, void* (*workspace_of)(size_t need, void* ctx, int* rc), void* ctx,
+                                 void* stream) {
     if (!fmt_ok(fmt_x) || !fmt_ok(fmt_w)) return fail(FP8_ERR_ENUM, "%s: unknown fp8 format", fn);
     if ((gran_x != FP8_TENSOR && gran_x != FP8_ROW) || (gran_w != FP8_TENSOR && gran_w != FP8_ROW))
         return fail(FP8_ERR_ENUM, "%s: granularity must be FP8_TENSOR or FP8_ROW", fn);
@@ -546,19 +554,79 @@ int fp8_linear_fwd_prequantized(const void* x, int64_t M, int64_t K, int fmt_x, 
     if (ldw < K || ld_y < N) return fail(FP8_ERR_SHAPE, "%s: leading dimension too small", fn);
     if (int rc = check_bf16(fn, x, M, K, K)) return rc;
     if (M == 0 || N == 0) return FP8_OK;
-    if (!y || !workspace || !scale_w || (K > 0 && !wq)) return fail(FP8_ERR_NULL, "%s: NULL pointer", fn);
-    if (!aligned(y, 16) || !aligned(wq, 16) || !aligned(workspace, 256) || !aligned(scale_w, 4))
-        return fail(FP8_ERR_ALIGN, "%s: y, wq (16) / workspace (256) / scale_w (4) misaligned", fn);
+    if (!y || !scale_w || (K > 0 && !wq)) return fail(FP8_ERR_NULL, "%s: NULL pointer", fn);
+    if (!aligned(y, 16) || !aligned(wq, 16) || !aligned(scale_w, 4))
+        return fail(FP8_ERR_ALIGN, "%s: y, wq (16) / scale_w (4) misaligned", fn);
     if (ldw % 16 != 0 || ld_y % 8 != 0) return fail(FP8_ERR_ALIGN, "%s: ldw %% 16 and ld_y %% 8 must be 0", fn);
     const size_t need = fp8_linear_prequantized_workspace_bytes(M, K);
-    if (workspace_bytes < need) return fail(FP8_ERR_WORKSPACE, "%s: workspace %zu < %zu bytes", fn, workspace_bytes, need);
+    int rc = FP8_OK;
+    void* workspace = workspace_of(need, ctx, &rc);
+    if (rc != FP8_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* xq = static_cast<uint8_t*>(workspace);
     float* sx = reinterpret_cast<float*>(xq + align_up((size_t)M * (size_t)K, 256));
-    if (int rc = quantize_impl(x, M, K, K, gran_x, fmt_x, flags, xq, K, nullptr, 0, sx, st)) return rc;
+    if (int rq = quantize_impl(x, M, K, K, gran_x, fmt_x, flags, xq, K, nullptr, 0, sx, st)) return rq;
     FP8_TRY(fp8k::launch_gemm_fp8(xq, K, fmt_x, sx, gran_x == FP8_ROW, wq, ldw, fmt_w, scale_w, gran_w == FP8_ROW, M, N, K, y,
                                   ld_y, 0, st));
     return FP8_OK;
+}
+
+struct CallerWorkspace { void* p; size_t bytes; };
+void* caller_workspace(size_t need, void* ctx, int* rc) {
+    const CallerWorkspace* w = static_cast<const CallerWorkspace*>(ctx);
+    if (!w->p) { *rc = fail(FP8_ERR_NULL, "fp8_linear_fwd_prequantized: workspace is NULL"); return nullptr; }
+    if (!aligned(w->p, 256)) { *rc = fail(FP8_ERR_ALIGN, "fp8_linear_fwd_prequantized: workspace not 256-byte aligned"); return nullptr; }
+    if (w->bytes < need) { *rc = fail(FP8_ERR_WORKSPACE, "fp8_linear_fwd_prequantized: workspace %zu < %zu bytes", w->bytes, need); return nullptr; }
+    return w->p;
+}
+}  // namespace
+
+int fp8_linear_fwd_prequantized(const void* x, int64_t M, int64_t K, int fmt_x, int gran_x, int flags, const uint8_t* wq,
+                                int64_t ldw, int fmt_w, const float* scale_w, int gran_w, int64_t N, void* y,
+                                int64_t ld_y, void* workspace, size_t workspace_bytes, void* stream) {
+    g_err[0] = 0;
+    CallerWorkspace w{workspace, workspace_bytes};
+    return linear_fwd_prequantized_impl("fp8_linear_fwd_prequantized", x, M, K, fmt_x, gran_x, flags, wq, ldw, fmt_w, scale_w,
+                                        gran_w, N, y, ld_y, caller_workspace, &w, stream);
+}
+
+namespace {
+// per device: the address of that device's copy of `scratch` (resolved once, with the device current)
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mu;
+
+void* static_workspace(size_t need, void*, int* rc) {
+    const char* fn = "fp8_linear_fwd_prequantized_static";
+    if (need > (size_t)FP8_STATIC_SCRATCH_BYTES) {
+        *rc = fail(FP8_ERR_WORKSPACE, "%s: M x K needs %zu bytes of scratch, the static buffer holds %zu", fn, need,
+                   (size_t)FP8_STATIC_SCRATCH_BYTES);
+        return nullptr;
+    }
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { *rc = hip_fail(e, "hipGetDevice"); return nullptr; }
+    if (dev < 0 || dev >= kMaxDevices) { *rc = fail(FP8_ERR_HIP, "%s: device index %d out of range", fn, dev); return nullptr; }
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lock(g_scratch_mu);
+        p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+        if (!p) {
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p) { *rc = hip_fail(e, "hipGetSymbolAddress(scratch)"); return nullptr; }
+            g_scratch_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    return p;
+}
+}  // namespace
+
+int fp8_linear_fwd_prequantized_static(const void* x, int64_t M, int64_t K, int fmt_x, int gran_x, int flags,
+                                       const uint8_t* wq, int64_t ldw, int fmt_w, const float* scale_w, int gran_w,
+                                       int64_t N, void* y, int64_t ld_y, void* stream) {
+    g_err[0] = 0;
+    return linear_fwd_prequantized_impl("fp8_linear_fwd_prequantized_static", x, M, K, fmt_x, gran_x, flags, wq, ldw, fmt_w,
+                                        scale_w, gran_w, N, y, ld_y, static_workspace, nullptr, stream);
 }
 
 int fp8_layernorm_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, const void* gamma, const void* beta,

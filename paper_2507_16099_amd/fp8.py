@@ -85,6 +85,8 @@ def load_library() -> C.CDLL:
     L.fp8_linear_fwd_prequantized.restype = ci
     L.fp8_linear_fwd_prequantized.argtypes = [vp, i64, i64, ci, ci, ci, vp, i64, ci, vp, ci, i64, vp, i64, vp,
                                               C.c_size_t, vp]
+    L.fp8_linear_fwd_prequantized_static.restype = ci
+    L.fp8_linear_fwd_prequantized_static.argtypes = [vp, i64, i64, ci, ci, ci, vp, i64, ci, vp, ci, i64, vp, i64, vp]
     L.fp8_linear_bwd_sigmoid_workspace_bytes.restype = C.c_size_t
     L.fp8_linear_bwd_sigmoid_workspace_bytes.argtypes = [i64, i64, i64, vp]
     L.fp8_linear_bwd_sigmoid.restype = ci
@@ -354,6 +356,23 @@ def fp8_linear_fwd_prequantized(x: torch.Tensor, wq: torch.Tensor, fmt_w: int, s
     _check(load_library().fp8_linear_fwd_prequantized(_ptr(x), M, K, fmt_x, gran_x, flags, _ptr(wq), ldw, fmt_w,
                                                       _ptr(scale_w), gran_w, N, _ptr(y), ld_y, _ptr(workspace),
                                                       workspace.numel(), _stream()))
+    return y
+
+
+FP8_STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def fp8_linear_fwd_prequantized_static(x: torch.Tensor, wq: torch.Tensor, fmt_w: int, scale_w: torch.Tensor, gran_w: int,
+                                       y: torch.Tensor, fmt_x: int = FP8_E4M3FN, gran_x: int = FP8_ROW,
+                                       flags: int = 0) -> torch.Tensor:
+    """fp8_linear_fwd_prequantized without a workspace: the library's static device buffer holds the activation
+    codes.  The caller passes y; nothing is allocated here or in the library."""
+    M, K, ldx = _mat(x, 2)
+    N, Kw, ldw = _mat(wq, 1)
+    assert K == Kw and ldx == K, (x.shape, wq.shape)
+    _, _, ld_y = _mat(y, 2)
+    _check(load_library().fp8_linear_fwd_prequantized_static(_ptr(x), M, K, fmt_x, gran_x, flags, _ptr(wq), ldw, fmt_w,
+                                                             _ptr(scale_w), gran_w, N, _ptr(y), ld_y, _stream()))
     return y
 
 

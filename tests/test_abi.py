@@ -93,6 +93,10 @@ def test_argument_errors_of_the_later_entry_points():
     assert L.fp8_linear_fwd_prequantized(p, 16, 64, 0, 1, 0, p, 64, 0, p, 2, 32, p, 32, p, 1 << 20, None) == -3
     assert L.fp8_linear_fwd_prequantized(p, 16, 64, 0, 1, 0, p, 64, 0, p, 1, 32, p, 32, p, 16, None) == -5
     assert L.fp8_linear_prequantized_workspace_bytes(16, 64) >= 16 * 64 + 16 * 4
+    # the variant with the static scratch buffer: same checks, and sizes beyond the buffer are refused on the host
+    assert L.fp8_linear_fwd_prequantized_static(p, 16, 64, 0, 1, 0, p, 64, 0, p, 2, 32, p, 32, None) == -3
+    assert L.fp8_linear_fwd_prequantized_static(p, 4096, 4096, 0, 1, 0, p, 4096, 0, p, 1, 64, p, 64, None) == -5
+    assert "static buffer" in fp8.fp8_last_error()
     # MX: block size, scale leading dimension, contraction length of the GEMM
     assert L.fp8_mx_quantize(p, 4, 48, 48, 0, p, 48, p, 4, None) == -2
     assert L.fp8_mx_quantize(p, 4, 64, 64, 0, p, 64, p, 2, None) == -2           # ld_e % 4
