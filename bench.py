@@ -378,6 +378,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-legs", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=2048)
+    ap.add_argument("--cpu-full", action="store_true",
+                    help="time the CPU oracle on the WHOLE workload instead of a token sample (minutes of CPU time)")
     ap.add_argument("--sweep", action="store_true",
                     help="fp8 vs bf16 linear fwd+bwd over a grid of (M, K, N); prints a JSON table and exits")
     ap.add_argument("--decode", action="store_true",
@@ -758,7 +760,7 @@ def main() -> int:
     # ------------------------------------------------ CPU oracle baseline
     if not args.no_cpu_baseline:
         from oracle import fp8_oracle as orc
-        ms_rows = min(M, args.cpu_sample_rows)
+        ms_rows = M if args.cpu_full else min(M, args.cpu_sample_rows)
         sub = si.scaled_down(wl, ms_rows, K, N)
         hx, hw, hdy = sub.x(), sub.w(), sub.dy()
         orec = orc.Recipe(gran=orc.ROW if rowwise else orc.TENSOR, pow2=wl.pow2)
@@ -770,10 +772,21 @@ def main() -> int:
             orc.linear_bwd_dw(hdy, hx, orec)
         c1 = time.perf_counter()
         cflop = n_gemm * 2.0 * ms_rows * N * K
+        # the cast path by itself: the oracle's rowwise (or tensorwise) quantization of the FULL weight tensor
+        # (the largest tensor that is the same in the sample and in the whole workload), 3 bytes per element
+        q0 = time.perf_counter()
+        orc.quantize(hw, orc.ROW if rowwise else orc.TENSOR, orc.E4M3FN)
+        q1 = time.perf_counter()
+        full_s = (c1 - c0) * M / ms_rows
+        sample = (f"the whole workload ({M} tokens): quantize + {n_gemm} GEMMs, {c1 - c0:.1f} s of CPU time" if ms_rows == M else
+                  f"same workload with M reduced to {ms_rows} tokens (full K, N): quantize + {n_gemm} GEMMs, "
+                  f"{c1 - c0:.1f} s of CPU time; the whole step extrapolates to {full_s:.0f} s, beyond the 10-30 s of CPU "
+                  f"work that a default run allows (bench.py --cpu-full times it in full)")
         result["cpu_baseline"] = {"value": round(cflop / (c1 - c0) / 1e12, 6), "unit": "TFLOP/s",
-                                  "cores": orc.num_threads(), "kind": "oracle",
-                                  "sample": f"same workload with M reduced to {ms_rows} tokens (full K, N): "
-                                            f"quantize + {n_gemm} GEMMs, {c1 - c0:.1f} s of CPU time"}
+                                  "cores": orc.num_threads(), "kind": "oracle", "sample": sample,
+                                  "cast": {"value": round(3.0 * N * K / (q1 - q0) / 1e9, 3), "unit": "GB/s",
+                                           "sample": f"amax + scale + cast of the full weight tensor [{N}, {K}] "
+                                                     f"(3 bytes per element), {q1 - q0:.2f} s"}}
     print(json.dumps(result))
     return 0
 

@@ -90,7 +90,7 @@ int fp8_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran,
              float* amax_out, void* stream);
 
 /*
- * scale (Appendix A: "a single scaling factor for each tensor" / per row).
+ * scale (Appendix A: one factor for the whole tensor, or one per row / column).
  *   scale_out[i] = fp32( FMAX(format) / max(amax[i], 1e-12) ), the quotient
  *   correctly rounded; with FP8_POW2_SCALE it is then rounded down to 2^k.
  *   amax and scale_out have n entries and may alias.
@@ -113,7 +113,9 @@ int fp8_cast(const void* x, int64_t rows, int64_t cols, int64_t ld, const float*
  * and the scales to scale_out ([1] | [rows] | [cols]).
  *   ROW without transpose is a single pass over HBM (the row stays in
  *   registers between the reduction and the cast); TENSOR and COL read the
- *   input twice.  flags: FP8_POW2_SCALE, FP8_TRANSPOSE_OUT.
+ *   input twice.  flags: FP8_POW2_SCALE, FP8_TRANSPOSE_OUT.  q_out may serve as
+ *   scratch before it receives its codes; bytes outside the [rows, cols] (or
+ *   transposed [cols, rows]) window of a padded output are never written.
  */
 int fp8_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran, int format,
                  int flags, uint8_t* q_out, int64_t ld_out, float* scale_out, void* stream);
@@ -128,7 +130,9 @@ int fp8_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran
  * in the pass that writes the rowwise codes.
  *   q_row [rows, cols] (ld_row), scale_row [rows]; q_col_t [cols, rows]
  *   (ld_col_t), scale_col [cols].  The four outputs must not overlap; q_col_t
- *   is also used as scratch before it receives its codes.
+ *   is also used as scratch before it receives its codes (only bytes that the
+ *   codes overwrite afterwards: the padding between the rows of an output with
+ *   ld_col_t > rows is never written).
  *   flags: FP8_POW2_SCALE only.
  */
 int fp8_quantize_row_col(const void* x, int64_t rows, int64_t cols, int64_t ld, int format, int flags,
@@ -136,7 +140,8 @@ int fp8_quantize_row_col(const void* x, int64_t rows, int64_t cols, int64_t ld, 
                          uint8_t* q_col_t, int64_t ld_col_t, float* scale_col, void* stream);
 
 /*
- * scaled GEMM on FP8 matrix cores (Section 2.1: "specialized GEMM kernels").
+ * scaled GEMM on FP8 matrix cores (Section 2.1: the FP8 products run in GEMM
+ * kernels made for the low-precision matrix units).
  *   out[m, n] = ( sum_k dec(a[m, k]) * dec(b[n, k]) ) / (sa * sb)
  *   a [M, K] and b [N, K] are fp8 codes with the contraction axis contiguous
  *   (leading dimensions lda, ldb); fmt_a / fmt_b select E4M3FN or E5M2 per
@@ -293,7 +298,7 @@ int fp8_layernorm_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld
 
 /*
  * MX (microscaling) FP8, the finer scaling granularity that the paper lists
- * among its prototype features ("MX formats: ... mxfp8 for training"); format
+ * among its prototype features (Appendix E, "Prototype Features": MX formats, mxfp8 for training); format
  * and conversion follow the OCP Microscaling Formats (MX) specification v1.0:
  * every block of 32 consecutive elements along the contraction axis has one
  * power-of-two scale, stored as an E8M0 byte (value 2^(byte - 127)).
@@ -347,8 +352,8 @@ int fp8_mx_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, i
                       void* stream);
 
 /*
- * Blockwise FP8 ("Blockwise FP8: FP8 blockwise quantization introduced by
- * DeepSeek" on the paper's list of prototype features; the recipe is that of the
+ * Blockwise FP8 (Appendix E, the paper's list of prototype features, names the
+ * blockwise FP8 quantization that DeepSeek introduced; the recipe is that of the
  * DeepSeek-V3 technical report, Section 3.3.2): activations are scaled per tile of
  * 1 x 128 elements along the contraction axis, weights per block of 128 x 128.
  * Here the scale of a block is s = fp32(FMAX / max(amax, 1e-12)) rounded DOWN to a

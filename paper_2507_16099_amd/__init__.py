@@ -5,7 +5,7 @@ streams."""
 from .fp8 import (  # noqa: F401
     FP8_E4M3FN, FP8_E5M2, FP8_TENSOR, FP8_ROW, FP8_COL,
     FP8_POW2_SCALE, FP8_TRANSPOSE_OUT, FP8_OUT_FP32, FP8_GRAD_WEIGHT_HP, FP8_SAVE_FOR_BWD, FP8_EPILOGUE_SIGMOID,
-    Fp8Error, Recipe, library_path, load_library,
+    Fp8Error, Recipe, library_path, load_library, set_knob,
     fp8_amax, fp8_scale, fp8_cast, fp8_quantize, fp8_quantize_row_col, fp8_scaled_mm,
     fp8_linear_workspace_bytes, fp8_linear_fwd, fp8_linear_bwd,
     fp8_linear_prequantized_workspace_bytes, fp8_linear_fwd_prequantized, fp8_grad_weight_hp,

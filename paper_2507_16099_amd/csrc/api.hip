@@ -59,6 +59,13 @@ int64_t n_groups(int gran, int64_t rows, int64_t cols) {
     return gran == FP8_TENSOR ? 1 : (gran == FP8_ROW ? rows : cols);
 }
 
+// bytes at the start of an fp8 output [out_rows, out_cols] (leading dimension ld_out) that may hold scratch data
+// before the cast writes its codes: every byte of a dense matrix, else only the first row (the bytes between the
+// rows of a padded output belong to the caller and are never written)
+size_t output_scratch_bytes(int64_t out_rows, int64_t out_cols, int64_t ld_out) {
+    return ld_out == out_cols ? (size_t)out_rows * (size_t)out_cols : (size_t)out_cols;
+}
+
 // amax -> scale -> cast of one operand; amax_tmp has n_groups floats
 int quantize_impl(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran, int format, int flags,
                   uint8_t* q, int64_t ld_out, uint8_t* q_plain, int64_t ld_plain, float* scale_out,
@@ -78,12 +85,13 @@ int quantize_impl(const void* x, int64_t rows, int64_t cols, int64_t ld, int gra
     }
     // scale_out doubles as the amax buffer: fp8_scale may run in place.  For a
     // per-column quantization with transposed output, the output buffer itself
-    // (cols x ld_out bytes, overwritten by the cast afterwards) serves as the
-    // scratch matrix of the two-level column amax.
+    // (overwritten by the cast afterwards) serves as the scratch matrix of the
+    // two-level column amax - only the bytes that the cast will rewrite: all of a
+    // dense output, the first row of one whose rows are padded (ld_out > rows).
     hipError_t ea = hipErrorNotSupported;
     if (gran == FP8_COL && transpose && q_plain == nullptr && rows > 0 && cols > 0)
         ea = fp8k::launch_col_scales_two_level(x, rows, cols, ld, format, pow2, scale_out, q,
-                                               (size_t)(cols - 1) * (size_t)ld_out + (size_t)rows, st);
+                                               output_scratch_bytes(cols, rows, ld_out), st);
     if (ea == hipErrorNotSupported) {
         ea = fp8k::launch_amax(x, rows, cols, ld, gran, scale_out, st);
         if (ea != hipSuccess) return hip_fail(ea, "amax");
@@ -105,7 +113,7 @@ int quantize_row_col_impl(const void* x, int64_t rows, int64_t cols, int64_t ld,
     hipError_t e = hipErrorNotSupported;
     if (rows > 0 && cols > 0)
         e = fp8k::launch_quant_row_colmax(x, rows, cols, ld, format, pow2, q_row, ld_row, scale_row, scale_col, q_col_t,
-                                          (size_t)(cols - 1) * (size_t)ld_col_t + (size_t)rows, st);
+                                          output_scratch_bytes(cols, rows, ld_col_t), st);
     if (e == hipSuccess) {
         FP8_TRY(fp8k::launch_cast(x, rows, cols, ld, scale_col, FP8_COL, format, 1, q_col_t, ld_col_t, nullptr, 0, st));
         return FP8_OK;
@@ -292,7 +300,7 @@ int fp8_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a
     }
     if (flags & FP8_EPILOGUE_SIGMOID) {
         // the fused activation lives in the LDS-DMA kernel's epilogue, which handles every shape
-        if (!fp8k::gemm_fp8_pipelined_supported(lda, ldb))
+        if (!fp8k::gemm_fp8_snake_fits(lda, ldb))
             return fail(FP8_ERR_SHAPE, "fp8_scaled_mm: the sigmoid epilogue needs lda, ldb below 2^23");
         FP8_TRY(fp8k::launch_gemm_fp8_snake(a, lda, fmt_a, scale_a, gran_a == FP8_ROW, b, ldb, fmt_b, scale_b, gran_b == FP8_ROW,
                                             M, N, K, out, ld_out, 0, static_cast<hipStream_t>(stream), 1));

@@ -25,8 +25,8 @@
 // kernels (a 16-row fragment is a permutation of 16 consecutive physical rows).
 #include "fp8_device.hpp"
 #include "launchers.hpp"
+#include "tuning.hpp"
 
-#include <cstdlib>
 
 namespace fp8k {
 
@@ -198,19 +198,14 @@ hipError_t launch_gemm_bf16_at_b(const void* a, int64_t lda, const void* b, int6
     {
         // more than 64 tiles: the LDS-DMA kernel (FP8MI355_BF16_VARIANT=0 / 1 forces one of the two)
         const int64_t tiles = ((I + BI - 1) / BI) * ((J + BJ - 1) / BJ);
-        const char* e = std::getenv("FP8MI355_BF16_VARIANT");
-        const bool want = e ? std::atoi(e) != 0 : tiles > 64;
+        const int forced = knob(KNOB_BF16_VARIANT);
+        const bool want = forced >= 0 ? forced != 0 : tiles > 64;
         if (want && gemm_bf16_at_b_snake_fits(lda, ldb, I, J, C))
             return launch_gemm_bf16_at_b_snake(a, lda, b, ldb, I, J, C, out, ld_out, st);
     }
-    static bool attr_done = false;          // idempotent, a race is harmless
     constexpr int lds = 2 * STAGE;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_at_b_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static DynamicLdsOnce attr;
+    if (hipError_t e = attr.ensure(reinterpret_cast<const void*>(gemm_bf16_at_b_kernel), lds); e != hipSuccess) return e;
     const int tiles_i = (int)((I + BI - 1) / BI), tiles_j = (int)((J + BJ - 1) / BJ);
     const int64_t ntiles = (int64_t)tiles_i * tiles_j;
     const int64_t grid = (ntiles + NUM_XCD - 1) / NUM_XCD * NUM_XCD;

@@ -30,8 +30,8 @@
 // slot ^ (key << 1)).
 #include "fp8_device.hpp"
 #include "launchers.hpp"
+#include "tuning.hpp"
 
-#include <cstdlib>
 #include <type_traits>
 
 namespace fp8k {
@@ -353,14 +353,9 @@ static hipError_t bts_launch_part(const uint16_t* a, int64_t lda, const uint16_t
                                   uint16_t* out, int64_t ld_out, int tiles_i, int tiles_j, int tile_first, int64_t units,
                                   hipStream_t st) {
     using namespace bts;
-    static bool attr_done = false;          // idempotent, a race is harmless
     constexpr int lds = 2 * STAGE;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_at_b_snake_kernel<HALF>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static DynamicLdsOnce attr;
+    if (hipError_t e = attr.ensure(reinterpret_cast<const void*>(gemm_bf16_at_b_snake_kernel<HALF>), lds); e != hipSuccess) return e;
     const int64_t grid = (units + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
     if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
     gemm_bf16_at_b_snake_kernel<HALF><<<dim3((unsigned)grid), dim3(NT), lds, st>>>(a, lda, b, ldb, I, J, C, out, ld_out, tiles_i,
@@ -380,15 +375,9 @@ hipError_t launch_gemm_bf16_at_b_snake(const void* a, int64_t lda, const void* b
     const uint16_t* bp = static_cast<const uint16_t*>(b);
     uint16_t* op = static_cast<uint16_t*>(out);
     // a last round that would fill at most half of the CUs runs as half tiles (FP8MI355_SNAKE_HALF=0: whole tiles)
-    static int cus = -1;                    // a race only repeats the query
-    if (cus < 0) {
-        int dev = 0, n = 0;
-        cus = (hipGetDevice(&dev) == hipSuccess &&
-               hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess) ? n : 0;
-    }
-    const char* e = std::getenv("FP8MI355_SNAKE_HALF");
+    const int cus = compute_units();
     const int64_t rest = cus > 0 ? ntiles % cus : 0;
-    if (!(e && e[0] == '0') && cus >= 16 && cus % NUM_XCD == 0 && rest > 0 && 2 * rest <= cus) {
+    if (knob(KNOB_SNAKE_HALF) != 0 && cus >= 16 && cus % NUM_XCD == 0 && rest > 0 && 2 * rest <= cus) {
         const int64_t full = ntiles - rest;
         if (full > 0) {
             hipError_t err = bts_launch_part<false>(ap, lda, bp, ldb, (int)I, (int)J, (int)C, op, ld_out, tiles_i, tiles_j, 0, full, st);

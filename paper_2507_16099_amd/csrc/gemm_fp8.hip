@@ -1,8 +1,8 @@
 // Scaled FP8 GEMM for gfx950 on the CDNA4 matrix cores
 // (v_mfma_f32_16x16x128_f8f6f4): out[M,N] = (A[M,K] . B[N,K]^T) / (sa * sb).
 //
-// The paper (Section 2.1) only says that the FP8 products run on "specialized
-// GEMM kernels"; this is this library's own kernel.
+// The paper (Section 2.1) leaves the FP8 products to the hardware vendor's GEMM
+// kernels; this is this library's own kernel for problems of few tiles, and the dispatch.
 //
 // Layout of the work
 //   - Both operands have the contraction axis contiguous.  A workgroup owns a
@@ -30,8 +30,7 @@
 //     in that XCD's L2.
 #include "fp8_device.hpp"
 #include "launchers.hpp"
-
-#include <cstdlib>
+#include "tuning.hpp"
 
 namespace fp8k {
 
@@ -261,13 +260,8 @@ static hipError_t launch_variant(const uint8_t* a, int64_t lda, const float* sa,
                                  int64_t ld_out, hipStream_t st) {
     auto kern = gemm_fp8_tn_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, OUT_F32, PD>;
     constexpr int lds = 2 * (BM + BN) * BK;
-    static bool attr_done = false;  // one attribute per instantiation; idempotent, so a race is harmless
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static DynamicLdsOnce attr;     // one per instantiation
+    if (hipError_t e = attr.ensure(reinterpret_cast<const void*>(kern), lds); e != hipSuccess) return e;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int64_t ntiles = (int64_t)tiles_m * tiles_n;
     const int64_t grid = (ntiles + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
@@ -285,10 +279,6 @@ static hipError_t launch_fmt(int variant, const uint8_t* a, int64_t lda, const f
         return launch_variant<64, 64, 4, 1, FA, FB, OUT_F32, 4>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
     if (variant == 7)
         return launch_variant<128, 128, 2, 2, FA, FB, OUT_F32, 3>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
-    if (variant == 2)
-        return launch_variant<256, 256, 2, 2, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
-    if (variant == 1 || (variant >= 3 && variant <= 5))
-        return launch_variant<256, 256, 2, 4, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
     return launch_variant<128, 128, 2, 2, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
 }
 
@@ -298,17 +288,13 @@ static hipError_t launch_fmt(int variant, const uint8_t* a, int64_t lda, const f
 // gemm_fp8_snake.hip) as soon as its 256 x 256 tiles keep more than a quarter
 // of the CUs busy (measured: equal to the 128 x 128 tile of this file at 64
 // tiles, 10-80 % faster from 96 tiles on), and 128 x 128 or 64 x 64 tiles (more
-// workgroups) below that.  FP8MI355_GEMM_VARIANT=0..7 overrides (tuning and
-// test aid): 0 = 128x128 / 4 waves, 1 = 256x256 / 8 waves, 2 = 256x256 / 4
-// waves (all register-staged), 3 = pipelined 32x32x64
-// (gemm_fp8_pipelined.hip), 4 = snake, 5 = few-row kernel (only where M <= 64),
-// 6 = 64x64 / 4 waves with loads 4 steps ahead, 7 = 128x128 / 4 waves with loads
-// 3 steps ahead (both register-staged through buffer loads).
+// workgroups) below that.  The switch GEMM_VARIANT overrides (tuning and
+// test aid): 0 = 128x128 / 4 waves (register-staged; also the fallback where the
+// 32-bit offsets of the others do not reach), 4 = snake, 5 = few-row kernel (only
+// where M <= 64), 6 = 64x64 / 4 waves with loads 4 steps ahead, 7 = 128x128 / 4
+// waves with loads 3 steps ahead (both register-staged through buffer loads).
 static int pick_variant(int64_t M, int64_t N) {
-    if (const char* e = std::getenv("FP8MI355_GEMM_VARIANT")) {
-        const int v = std::atoi(e);
-        if (v >= 0 && v <= 7) return v;
-    }
+    if (const int v = knob(KNOB_GEMM_VARIANT); v == 0 || (v >= 4 && v <= 7)) return v;
     if (M <= 32) return 5;
     const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
     if (tiles256 > 64) return 4;
@@ -331,12 +317,10 @@ hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float
     if (v == 5 && M <= 64 && K > 0)
         return launch_gemm_fp8_skinny(a, lda, fmt_a, scale_a, row_a, b, ldb, fmt_b, scale_b, row_b, M, N, K, out, ld_out,
                                       out_f32, st);
-    if (v == 4 && gemm_fp8_pipelined_supported(lda, ldb))
+    if (v == 4 && gemm_fp8_snake_fits(lda, ldb))   // else: the 128 x 128 register-staged kernel below
         return launch_gemm_fp8_snake(a, lda, fmt_a, scale_a, row_a, b, ldb, fmt_b, scale_b, row_b, M, N, K, out, ld_out,
                                      out_f32, st);
-    if (v == 3 && gemm_fp8_pipelined_supported(lda, ldb))   // else: fall through to the 256 x 256 register-staged kernel
-        return launch_gemm_fp8_pipelined(a, lda, fmt_a, scale_a, row_a, b, ldb, fmt_b, scale_b, row_b, M, N, K, out,
-                                         ld_out, out_f32, st);
+    if (v == 4 || v == 5) v = 0;
     const int m = (int)M, n = (int)N, k = (int)K;
 #define FP8K_GEMM(FA_, FB_)                                                                                     \
     if (fmt_a == FA_ && fmt_b == FB_)                                                                           \

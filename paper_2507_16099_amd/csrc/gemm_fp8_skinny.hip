@@ -24,8 +24,8 @@
 // wavefronts to keep the memory system busy.
 #include "fp8_device.hpp"
 #include "launchers.hpp"
+#include "tuning.hpp"
 
-#include <cstdlib>
 
 namespace fp8k {
 
@@ -407,12 +407,8 @@ static hipError_t launch_sk_dma(const uint8_t* a, int64_t lda, const float* sa, 
     constexpr int R = SLOT <= 4096 ? 5 : (SLOT <= 6144 ? 3 : 2);     // about 20 KB of ring per wavefront: two workgroups per CU
     constexpr int lds = 4 * R * SLOT;
     auto kern = gemm_fp8_skinny_dma_kernel<FA, FB, MT, KS, NW, R>;
-    static bool attr_done = false;          // idempotent, a race is harmless
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static DynamicLdsOnce attr;
+    if (hipError_t e = attr.ensure(reinterpret_cast<const void*>(kern), lds); e != hipSuccess) return e;
     kern<<<dim3((unsigned)grid), dim3(256), lds, st>>>(a, lda, b, ldb, sa, row_a, sb, row_b, M, N, K, out, ld_out, out_f32);
     return hipGetLastError();
 }
@@ -426,10 +422,7 @@ static hipError_t launch_sk(const uint8_t* a, int64_t lda, const float* sa, int 
     // for two or four MFMAs but shorten the ring of K steps in flight, narrower ones give more wavefronts;
     // measured: 32 wins or ties from N = 6144 on, 64 never beats 32 (28672 x 8192: 5 % slower)
     int nw = N >= 6144 ? 2 : 1;
-    if (const char* env_nw = std::getenv("FP8MI355_SKINNY_NW")) {     // 1, 2 or 4: tuning override
-        const int v = std::atoi(env_nw);
-        if (v == 1 || v == 2 || v == 4) nw = v;
-    }
+    if (const int v = knob(KNOB_SKINNY_NW); v == 1 || v == 2 || v == 4) nw = v;     // tuning override
     const int64_t groups = ((int64_t)N + 16 * nw - 1) / (16 * nw);
     // split K over the wavefronts of a workgroup until about 2048 wavefronts stream B
     int ks = 1;
@@ -437,9 +430,8 @@ static hipError_t launch_sk(const uint8_t* a, int64_t lda, const float* sa, int 
     const int64_t grid = (groups + (4 / ks) - 1) / (4 / ks);
     if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
     // LDS-DMA form for up to 32 rows when the 32-bit buffer offsets suffice (FP8MI355_SKINNY_DMA=0 / 1 overrides)
-    const char* e = std::getenv("FP8MI355_SKINNY_DMA");
     const bool fits = lda < (1 << 23) && ldb < (1 << 23) && mt <= 2;
-    if (fits && (e ? std::atoi(e) != 0 : true)) {
+    if (fits && knob(KNOB_SKINNY_DMA) != 0) {
 #define FP8K_SKD(MT_, KS_, NW_)                                                                               \
     if (mt == MT_ && ks == KS_ && nw == NW_)                                                                  \
         return launch_sk_dma<FA, FB, MT_, KS_, NW_>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, out_f32, grid, st)

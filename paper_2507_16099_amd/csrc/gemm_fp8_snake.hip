@@ -18,7 +18,7 @@
 // buffer, which is then refilled with step k+2 during phases 3 and 4 (one
 // LDS-DMA load every second MFMA slot).
 //
-// Data movement (see also gemm_fp8_pipelined.hip, which shares the approach)
+// Data movement
 //   - global -> LDS by buffer_load_dwordx4 ... lds, 8 rows x 128 bytes per wave
 //     instruction, XOR swizzle applied on the global side, rows past M / N and
 //     chunks past K zero-filled by the buffer descriptor's bounds check;
@@ -40,8 +40,8 @@
 //     group of rows overlap the arithmetic of the next.
 #include "fp8_device.hpp"
 #include "launchers.hpp"
+#include "tuning.hpp"
 
-#include <cstdlib>
 #include <type_traits>
 
 namespace fp8k {
@@ -451,29 +451,13 @@ static hipError_t launch_sn_part(const uint8_t* a, int64_t lda, const float* sa,
     using namespace sn;
     auto kern = gemm_fp8_snake_kernel<FA, FB, OUT_F32, ACT, HALF>;
     constexpr int lds = 2 * STAGE + 2048;   // two stages + the reciprocal-scale tables of the epilogue
-    static bool attr_done = false;          // idempotent, a race is harmless
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static DynamicLdsOnce attr;
+    if (hipError_t e = attr.ensure(reinterpret_cast<const void*>(kern), lds); e != hipSuccess) return e;
     const int64_t grid = (units + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
     if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
     kern<<<dim3((unsigned)grid), dim3(NT), lds, st>>>(a, lda, b, ldb, sa, row_a, sb, row_b, M, N, K, out, ld_out,
                                                       tiles_m, tiles_n, tile_first, (int)units);
     return hipGetLastError();
-}
-
-// number of compute units of the current device (0 if the query fails)
-static int sn_compute_units() {
-    static int cus = -1;                    // a race only repeats the query
-    if (cus < 0) {
-        int dev = 0, n = 0;
-        cus = (hipGetDevice(&dev) == hipSuccess &&
-               hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess) ? n : 0;
-    }
-    return cus;
 }
 
 template <int FA, int FB, bool OUT_F32, bool ACT = false>
@@ -486,11 +470,10 @@ static hipError_t launch_sn(const uint8_t* a, int64_t lda, const float* sa, int 
     if (ntiles > 0x3FFFFFFF) return hipErrorInvalidValue;
     if constexpr (!OUT_F32) {
         // A last round that would fill at most half of the CUs runs as half tiles instead: twice the
-        // workgroups, half the duration each (FP8MI355_SNAKE_HALF=0 keeps whole tiles; tuning and test aid).
-        const char* e = std::getenv("FP8MI355_SNAKE_HALF");
-        const int cus = sn_compute_units();
+        // workgroups, half the duration each (the switch SNAKE_HALF = 0 keeps whole tiles; tuning and test aid).
+        const int cus = compute_units();
         const int64_t rest = cus > 0 ? ntiles % cus : 0;
-        if (!(e && e[0] == '0') && cus >= 16 && cus % NUM_XCD == 0 && rest > 0 && 2 * rest <= cus) {
+        if (knob(KNOB_SNAKE_HALF) != 0 && cus >= 16 && cus % NUM_XCD == 0 && rest > 0 && 2 * rest <= cus) {
             const int64_t full = ntiles - rest;
             if (full > 0) {
                 hipError_t err = launch_sn_part<FA, FB, OUT_F32, ACT, false>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out,
@@ -504,6 +487,8 @@ static hipError_t launch_sn(const uint8_t* a, int64_t lda, const float* sa, int 
     return launch_sn_part<FA, FB, OUT_F32, ACT, false>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, tiles_m, tiles_n,
                                                        0, ntiles, st);
 }
+
+bool gemm_fp8_snake_fits(int64_t lda, int64_t ldb) { return lda < (1 << 23) && ldb < (1 << 23); }
 
 hipError_t launch_gemm_fp8_snake(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
                                  const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int row_b,

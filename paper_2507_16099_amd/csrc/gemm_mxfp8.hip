@@ -24,8 +24,8 @@
 // fragment) so that a lane ends up with 16 consecutive output columns.
 #include "fp8_device.hpp"
 #include "launchers.hpp"
+#include "tuning.hpp"
 
-#include <cstdlib>
 
 namespace fp8k {
 
@@ -226,13 +226,8 @@ static hipError_t launch_mx_t(const uint8_t* a, int64_t lda, const uint8_t* ea, 
     using namespace mx;
     auto kern = gemm_mxfp8_kernel<FA, FB, OUT_F32>;
     constexpr int lds = 2 * STAGE;
-    static bool attr_done = false;          // idempotent, a race is harmless
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static DynamicLdsOnce attr;
+    if (hipError_t e = attr.ensure(reinterpret_cast<const void*>(kern), lds); e != hipSuccess) return e;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int64_t ntiles = (int64_t)tiles_m * tiles_n;
     const int64_t grid = (ntiles + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
@@ -244,31 +239,37 @@ static hipError_t launch_mx_t(const uint8_t* a, int64_t lda, const uint8_t* ea, 
 
 // K must be a multiple of 128 and ld_ea, ld_eb multiples of 4 (a K step reads one aligned
 // dword of scales per row); checked by the caller
-// large problems: the LDS-DMA kernel (FP8MI355_MX_VARIANT=0 forces this file's kernel, 1 the other)
+// large problems: the LDS-DMA kernel (the switch MX_VARIANT = 0 forces this file's kernel, 1 the other)
+static bool mx_snake_possible(int64_t lda, int64_t ldb, int64_t K) { return K > 0 && gemm_fp8_snake_fits(lda, ldb); }
 static bool mx_takes_snake(int64_t lda, int64_t ldb, int64_t M, int64_t N, int64_t K) {
     const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
-    const char* e = std::getenv("FP8MI355_MX_VARIANT");
-    const bool big = e ? std::atoi(e) == 1 : tiles256 > 64;
-    return big && K > 0 && gemm_fp8_pipelined_supported(lda, ldb);
+    const int forced = knob(KNOB_MX_VARIANT);
+    const bool big = forced >= 0 ? forced == 1 : tiles256 > 64;
+    return big && mx_snake_possible(lda, ldb, K);
+}
+// shapes whose scales can lie in slabs of sixteen blocks (whole 16-byte scale pieces, 32-bit offsets reach)
+static bool mx_slab_possible(int64_t lda, int64_t ldb, int64_t M, int64_t N, int64_t K) {
+    return mx_snake_possible(lda, ldb, K) && K % 512 == 0 && M * (K / 32) < (1ll << 31) && N * (K / 32) < (1ll << 31);
 }
 
-// True when launch_gemm_mxfp8 on this problem reads its scales in slabs of sixteen blocks (a negative leading
-// dimension, see there): the LDS-DMA kernel with whole 16-byte scale pieces.  FP8MI355_MX_SLAB=0 switches it off.
+// True when the MX / blockwise linear calls should hand their scales to launch_gemm_mxfp8 in slabs of sixteen
+// blocks (a negative leading dimension, see there).  The caller decides ONCE per call with this function and
+// passes the decision down through the sign of the leading dimensions; the switch MX_SLAB = 0 turns it off.
 bool gemm_mxfp8_takes_slab_scales(int64_t lda, int64_t ldb, int64_t M, int64_t N, int64_t K) {
-    const char* e = std::getenv("FP8MI355_MX_SLAB");
-    if (e && std::atoi(e) == 0) return false;
-    return mx_takes_snake(lda, ldb, M, N, K) && K % 512 == 0 && M * (K / 32) < (1ll << 31) && N * (K / 32) < (1ll << 31);
+    if (knob(KNOB_MX_SLAB) == 0) return false;
+    return mx_takes_snake(lda, ldb, M, N, K) && mx_slab_possible(lda, ldb, M, N, K);
 }
 
 // ld_ea / ld_eb >= 0: scale rows of that many bytes.  < 0: slabs of sixteen blocks, [K / 512][-ld rows][16 bytes]
-// (only where gemm_mxfp8_takes_slab_scales says so, and for both operands alike).
+// (for both operands alike; only the LDS-DMA kernel reads that layout, so it is taken whatever the switches say).
 hipError_t launch_gemm_mxfp8(const uint8_t* a, int64_t lda, int fmt_a, const uint8_t* ea, int64_t ld_ea,
                              const uint8_t* b, int64_t ldb, int fmt_b, const uint8_t* eb, int64_t ld_eb, int64_t M,
                              int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32, hipStream_t st) {
     if (M == 0 || N == 0) return hipSuccess;
     if (ld_ea < 0 || ld_eb < 0) {
-        if (!(ld_ea < 0 && ld_eb < 0) || -ld_ea < M || -ld_eb < N || !gemm_mxfp8_takes_slab_scales(lda, ldb, M, N, K))
+        if (!(ld_ea < 0 && ld_eb < 0) || -ld_ea < M || -ld_eb < N || !mx_slab_possible(lda, ldb, M, N, K))
             return hipErrorInvalidValue;
+        return launch_gemm_mxfp8_snake(a, lda, fmt_a, ea, ld_ea, b, ldb, fmt_b, eb, ld_eb, M, N, K, out, ld_out, out_f32, st);
     }
     if (mx_takes_snake(lda, ldb, M, N, K) && ld_ea < (1 << 23) && ld_eb < (1 << 23))
         return launch_gemm_mxfp8_snake(a, lda, fmt_a, ea, ld_ea, b, ldb, fmt_b, eb, ld_eb, M, N, K, out, ld_out, out_f32, st);

@@ -12,6 +12,7 @@
 // one-byte LDS read of its scale.  The epilogue has no scaling left to do.
 #include "fp8_device.hpp"
 #include "launchers.hpp"
+#include "tuning.hpp"
 
 #include <type_traits>
 
@@ -445,13 +446,8 @@ static hipError_t launch_msn(const uint8_t* a, int64_t lda, const uint8_t* ea, i
     using namespace msn;
     auto kern = gemm_mxfp8_snake_kernel<FA, FB, OUT_F32, SC16>;
     constexpr int lds = 2 * STAGE + (SC16 ? 2 * SCBUF : 0);
-    static bool attr_done = false;          // idempotent, a race is harmless
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static DynamicLdsOnce attr;
+    if (hipError_t e = attr.ensure(reinterpret_cast<const void*>(kern), lds); e != hipSuccess) return e;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int64_t ntiles = (int64_t)tiles_m * tiles_n;
     const int64_t grid = (ntiles + NUM_XCD - 1) / NUM_XCD * NUM_XCD;

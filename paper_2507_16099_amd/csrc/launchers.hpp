@@ -57,14 +57,9 @@ hipError_t launch_quant_row_colmax(const void* x, int64_t rows, int64_t cols, in
                                    uint8_t* q, int64_t ld_out, float* scale_out, float* scale_cols, void* scratch,
                                    size_t scratch_bytes, hipStream_t st);
 
-// 256 x 256 software-pipelined kernel (direct-to-LDS loads); same contract.
-bool gemm_fp8_pipelined_supported(int64_t lda, int64_t ldb);
-hipError_t launch_gemm_fp8_pipelined(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
-                                     const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int row_b,
-                                     int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
-                                     hipStream_t st);
-
-// 256 x 256 kernel on 16x16x128 MFMAs with the four-phase "snake" schedule; same contract.
+// 256 x 256 kernel on 16x16x128 MFMAs with LDS-DMA loads and the four-phase "snake" schedule; same contract.
+// _fits: its 32-bit buffer offsets reach (leading dimensions below 2^23)
+bool gemm_fp8_snake_fits(int64_t lda, int64_t ldb);
 // act != 0 (bfloat16 output only): the logistic function applied to the fp32 result before rounding
 hipError_t launch_gemm_fp8_snake(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
                                  const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int row_b,

@@ -14,8 +14,10 @@
 // computed in binary64 and h is rounded ONCE to bfloat16 (through a binary32
 // value, see f64_to_bf16_bits): whatever the summation order, the bfloat16 result is the
 // correctly rounded one except when the binary64 value lies within ~1e-16 of a
-// rounding boundary.  The binary64 work (about ten operations per element) stays
-// below the time the row's bytes take from HBM.
+// rounding boundary (the bit-parity with a reference that sums in another order is
+// therefore statistical, not by construction).  The binary64 work makes the kernel
+// ALU-bound: about 38 instructions per element, measured at 0.45 of the HBM rate
+// that its 5 bytes per element would allow.
 #include "fp8_device.hpp"
 #include "launchers.hpp"
 

@@ -6,6 +6,7 @@
 // per tensor, per row, or per column.
 #include "fp8_device.hpp"
 #include "launchers.hpp"
+#include "tuning.hpp"
 
 namespace fp8k {
 
@@ -851,8 +852,8 @@ hipError_t launch_quant_row_colmax(const void* x, int64_t rows, int64_t cols, in
     int64_t G = 0;
 #define FP8K_QRC(FMT, NV)                                                                                     \
     do {                                                                                                      \
-        static int resident = -1;   /* per kernel; a race only repeats the query */                           \
-        if (resident < 0) resident = resident_blocks(quant_row_colmax_kernel<FMT, NV>);                        \
+        static CachedInt resident_c;   /* per kernel */                                                       \
+        const int resident = resident_c.get([] { return resident_blocks(quant_row_colmax_kernel<FMT, NV>); }); \
         G = resident < 1024 ? resident : 1024;                                                                \
         { /* at least 8 rows per block, but not fewer than 256 blocks while each still has 2 rows */          \
             int64_t cap = rows / 8;                                                                           \
@@ -893,12 +894,13 @@ hipError_t launch_quant_row_col_sigmoid_bwd(const void* dy, const void* y, int64
     const uint16_t* yp = static_cast<const uint16_t*>(y);
     const int64_t ld_part = cols;
     uint16_t* part = reinterpret_cast<uint16_t*>(q_col_t);          // overwritten by the transposed codes afterwards
-    const size_t scratch_bytes = (size_t)(cols - 1) * (size_t)ld_col_t + (size_t)rows;
+    // only bytes that the transposed cast rewrites: all of a dense output, else its first row
+    const size_t scratch_bytes = ld_col_t == rows ? (size_t)cols * (size_t)rows : (size_t)rows;
     int64_t G = 0;
 #define FP8K_QRCA(FMT, NV)                                                                                    \
     do {                                                                                                      \
-        static int resident = -1;                                                                             \
-        if (resident < 0) resident = resident_blocks(quant_row_colmax_kernel<FMT, NV, true>);                  \
+        static CachedInt resident_c;                                                                          \
+        const int resident = resident_c.get([] { return resident_blocks(quant_row_colmax_kernel<FMT, NV, true>); }); \
         G = resident < 1024 ? resident : 1024;                                                                \
         { /* at least 8 rows per block, but not fewer than 256 blocks while each still has 2 rows */          \
             int64_t cap = rows / 8;                                                                           \

@@ -127,8 +127,18 @@ def load_library() -> C.CDLL:
     L.fp8_grad_weight_hp.argtypes = [vp, vp, i64, i64, i64, vp, vp]
     L.fp8_linear_bwd.restype = ci
     L.fp8_linear_bwd.argtypes = [vp, vp, vp, i64, i64, i64, C.POINTER(_CRecipe), vp, vp, vp, C.c_size_t, vp]
+    L.fp8_internal_set_knob.restype = ci
+    L.fp8_internal_set_knob.argtypes = [C.c_char_p, ci]
     _lib = L
     return L
+
+
+def set_knob(name: str, value: int | None) -> None:
+    """Force one of the library's tuning / test switches (GEMM_VARIANT, SNAKE_HALF, SKINNY_NW, SKINNY_DMA,
+    MX_VARIANT, MX_SLAB, BF16_VARIANT, GEMM_STREAM) for the rest of the process; None restores the default.  The
+    library reads FP8MI355_<NAME> from the environment once, on first use; afterwards only this call changes a switch."""
+    if load_library().fp8_internal_set_knob(name.encode(), -1 if value is None else int(value)) != 0:
+        raise ValueError(f"unknown switch {name!r}")
 
 
 def fp8_last_error() -> str:

@@ -184,6 +184,24 @@ def scaled_down(w: Workload, M: int, K: int, N: int, name: str | None = None) ->
                     w.x_dist, w.w_dist, w.dy_dist, w.backward, w.seed)
 
 
+def tile_band_rows(M: int, count: int = 256, tile: int = 256, seed: int = 0) -> np.ndarray:
+    """Row indices for sampled GEMM parity at full size: the first and the last row of EVERY band of `tile`
+    rows (every row of output tiles, and both wavefront rows inside each, is looked at), plus seeded random rows
+    up to at least `count` in all; sorted, unique."""
+    fixed = set()
+    for first in range(0, M, tile):
+        fixed.add(first)
+        fixed.add(min(first + tile, M) - 1)
+    rng = _stream(seed, 98)
+    pool = rng.permutation(M)
+    rows = set(fixed)
+    for r in pool:
+        if len(rows) >= min(M, count):
+            break
+        rows.add(int(r))
+    return np.asarray(sorted(rows), dtype=np.int64)
+
+
 def stratified_rows(M: int, count: int, tile: int = 256, seed: int = 0) -> np.ndarray:
     """Row indices for sampled GEMM parity: first/last rows of the first and
     last tiles plus seeded random rows, sorted, unique."""

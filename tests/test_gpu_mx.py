@@ -9,7 +9,7 @@ import torch
 
 import synthetic_inputs as si
 from oracle import fp8_oracle as orc
-from tests.gpu_util import dev_bf16, dev_u8, host_bf16_bits, host_f32, host_u8
+from tests.gpu_util import dev_bf16, dev_u8, host_bf16_bits, host_f32, host_u8, knobs
 
 pytestmark = pytest.mark.gpu
 
@@ -59,14 +59,8 @@ SHAPES = [(16, 16, 128), (33, 17, 256), (200, 300, 384), (256, 512, 512), (257, 
 @pytest.fixture(params=["0", "1"], ids=["staged", "snake"])
 def mx_variant(request):
     """Both MX GEMM kernels on every shape (the dispatch would pick by problem size)."""
-    import os
-    old = os.environ.get("FP8MI355_MX_VARIANT")
-    os.environ["FP8MI355_MX_VARIANT"] = request.param
-    yield request.param
-    if old is None:
-        os.environ.pop("FP8MI355_MX_VARIANT", None)
-    else:
-        os.environ["FP8MI355_MX_VARIANT"] = old
+    with knobs(MX_VARIANT=int(request.param)):
+        yield request.param
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
@@ -163,7 +157,7 @@ def test_mx_full_size_llama_ffn_forward_sampled_rows():
     assert (host_u8(xq) == oxq).all() and (host_u8(xe) == oxe).all()
     assert (host_u8(wq) == owq).all() and (host_u8(we) == owe).all()
     y = fp8.fp8_mx_scaled_mm(xq, 0, xe, wq, 0, we)
-    rows = si.stratified_rows(wl.M, 32)
+    rows = si.tile_band_rows(wl.M, 128)     # first and last row of every band of 256 rows
     want = orc.mx_mm(oxq, orc.E4M3FN, oxe, owq, orc.E4M3FN, owe, rows)
     got = host_bf16_bits(y[torch.from_numpy(rows).cuda()])
     assert orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want.out16)) <= TOL
@@ -265,25 +259,11 @@ def test_mx_full_size_llama_ffn_backward_sampled_rows():
     assert (host_u8(q_col_t) == oq).all() and (host_u8(e_col_t) == oe).all()
     del q_row, e_row, q_col_t, e_col_t, oq, oe
     dx, dw = fp8.fp8_mx_linear_bwd(dyd, dxd, dwd)
-    rx, rw = si.stratified_rows(wl.M, 16), si.stratified_rows(wl.N, 16)
+    rx, rw = si.tile_band_rows(wl.M, 128), si.tile_band_rows(wl.N, 112)   # first and last row of every band of 256
     wx, ww = orc.mx_linear_bwd(dy, x, w, rows_dx=rx, rows_dw=rw)
     for got, want in ((host_bf16_bits(dx[torch.from_numpy(rx).cuda()]), wx), (host_bf16_bits(dw[torch.from_numpy(rw).cuda()]), ww)):
         assert orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want.out16)) <= TOL
         assert float((got == want.out16).mean()) > 0.97
-
-
-def _with_env(values, fn):
-    import os
-    old = {k: os.environ.get(k) for k in values}
-    os.environ.update(values)
-    try:
-        return fn()
-    finally:
-        for k, v in old.items():
-            if v is None:
-                os.environ.pop(k, None)
-            else:
-                os.environ[k] = v
 
 
 @pytest.mark.parametrize("M,K,N", [(640, 1024, 896), (512, 640, 1024), (1536, 512, 1024), (1024, 1024, 640)])
@@ -305,8 +285,10 @@ def test_scale_slabs_between_quantizers_and_gemm(M, K, N):
             outs += list(fp8.fp8_block_linear_bwd(dy_, dx_, dw_))
         return [host_bf16_bits(o) for o in outs]
 
-    slab = _with_env({"FP8MI355_MX_VARIANT": "1", "FP8MI355_MX_SLAB": "1"}, run_all)
-    plain = _with_env({"FP8MI355_MX_VARIANT": "1", "FP8MI355_MX_SLAB": "0"}, run_all)
+    with knobs(MX_VARIANT=1, MX_SLAB=1):
+        slab = run_all()
+    with knobs(MX_VARIANT=1, MX_SLAB=0):
+        plain = run_all()
     assert len(slab) == len(plain)
     for a, b in zip(slab, plain):
         assert (a == b).all()

@@ -235,3 +235,29 @@ def test_quantize_full_size_llama_ffn_gradient_both_axes():
     wc, wsc = orc.quantize(bits, orc.COL, orc.E5M2, orc.TRANSPOSE_OUT)
     assert (_bits(host_f32(sc)) == _bits(wsc)).all()
     assert (host_u8(qc) == wc).all()
+
+
+@pytest.mark.parametrize("rows,cols,pad", [(4096, 1024, 16), (4096, 1024, 0), (3000, 2048, 48), (520, 512, 16)])
+def test_transposed_outputs_leave_the_padding_between_rows_alone(rows, cols, pad):
+    """A transposed output [cols, rows] handed in as a view of a wider buffer (ld_out = rows + pad): the per-column
+    quantization may park its partial column maxima in the output before the cast, but only in bytes that the
+    cast rewrites - the bytes between the rows belong to the caller and must keep their sentinel.  Both entry
+    points that use the output as scratch; codes and scales still equal the oracle's."""
+    x = si.normal_bf16((rows, cols), 1.0, seed=21, stream=rows + pad)
+    xd = dev_bf16(x)
+    wq, ws = orc.quantize(x, orc.COL, orc.E5M2, orc.TRANSPOSE_OUT)
+    ld = (rows + 15) // 16 * 16 + pad
+    # fp8_quantize(COL | TRANSPOSE_OUT)
+    full = torch.full((cols, ld), 0xAB, dtype=torch.uint8, device="cuda")
+    q, s = fp8.fp8_quantize(xd, fp8.FP8_COL, fp8.FP8_E5M2, fp8.FP8_TRANSPOSE_OUT, out=full[:, :rows])
+    torch.cuda.synchronize()
+    assert (_bits(host_f32(s)) == _bits(ws)).all() and (host_u8(q) == wq).all()
+    assert bool((full[:, rows:] == 0xAB).all()), "padding of the transposed output was overwritten"
+    # fp8_quantize_row_col: q_col_t is the padded one
+    full = torch.full((cols, ld), 0xCD, dtype=torch.uint8, device="cuda")
+    q_row, s_row, q_col_t, s_col = fp8.fp8_quantize_row_col(xd, fp8.FP8_E5M2, 0, q_col_t=full[:, :rows])
+    torch.cuda.synchronize()
+    rq, rs = orc.quantize(x, orc.ROW, orc.E5M2)
+    assert (host_u8(q_row) == rq).all() and (_bits(host_f32(s_row)) == _bits(rs)).all()
+    assert (host_u8(q_col_t) == wq).all() and (_bits(host_f32(s_col)) == _bits(ws)).all()
+    assert bool((full[:, rows:] == 0xCD).all()), "padding of q_col_t was overwritten"

@@ -196,6 +196,31 @@ def test_cast_static_scale_saturates_and_counts():
     assert (st.n_sat, st.n_zero) == (2, 1)
 
 
+def test_cast_stats_counts_subnormal_codes_hand_worked():
+    """n_subnormal = nonzero codes whose exponent field is 0, counted on rows worked by hand with scale 1.
+    e4m3: subnormals are m * 2^-9, m = 1..7, the smallest normal is 2^-6.  e5m2: m * 2^-16, m = 1..3, smallest
+    normal 2^-14.  Ties go to the even code; half the smallest subnormal goes to zero (counted in n_zero, not here)."""
+    one = np.array([1.0], np.float32)
+    xf = np.array([[1.0, 2.0 ** -7, 3 * 2.0 ** -9, 2.0 ** -6, 2.0 ** -10, -(2.0 ** -9), 0.0, 7.5 * 2.0 ** -9,
+                    1.5 * 2.0 ** -9]], np.float32)
+    x = si.f32_to_bf16_bits(xf)
+    assert (si.bf16_bits_to_f32(x) == xf).all()           # every value is a bfloat16 number
+    q = orc.cast(x, one, orc.TENSOR, orc.E4M3FN)
+    assert list(q[0]) == [0x38, 0x04, 0x03, 0x08, 0x00, 0x81, 0x00, 0x08, 0x02]
+    st = orc.cast_stats(x, one, orc.TENSOR, orc.E4M3FN)
+    assert (st.n_sat, st.n_zero, st.n_subnormal) == (0, 1, 4)
+    xf = np.array([[2.0 ** -15, 2.0 ** -14, 3 * 2.0 ** -16, 2.0 ** -17, 1.0, -(2.0 ** -16)]], np.float32)
+    x = si.f32_to_bf16_bits(xf)
+    q = orc.cast(x, one, orc.TENSOR, orc.E5M2)
+    assert list(q[0]) == [0x02, 0x04, 0x03, 0x00, 0x3C, 0x81]
+    st = orc.cast_stats(x, one, orc.TENSOR, orc.E5M2)
+    assert (st.n_sat, st.n_zero, st.n_subnormal) == (0, 1, 3)
+    # a scale moves values across the boundary: x * 2^-3 turns 2^-6 .. 2^-4 into subnormals
+    xf = np.array([[2.0 ** -6, 2.0 ** -5, 2.0 ** -4, 2.0 ** -3]], np.float32)
+    st = orc.cast_stats(si.f32_to_bf16_bits(xf), np.array([0.125], np.float32), orc.TENSOR, orc.E4M3FN)
+    assert st.n_subnormal == 3 and st.n_zero == 0
+
+
 # --------------------------------------------------------------- scaled mm
 
 def _rand_codes(shape, fmt, rng):

@@ -9,7 +9,7 @@ import torch
 
 import paper_2507_16099_amd as fp8
 import synthetic_inputs as si
-from gpu_util import dev_bf16, host_bf16_bits
+from tests.gpu_util import dev_bf16, host_bf16_bits
 
 pytestmark = pytest.mark.gpu
 
