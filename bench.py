@@ -748,7 +748,7 @@ def main() -> int:
                              "speedup": round(bf_ms / fp8_ms, 3),
                              "bf16_TFLOP/s": round(flop_step / (bf_ms * 1e-3) / 1e12, 1),
                              "comparator": "torch.matmul bf16 (vendor BLAS), benchmark only"}
-        result["roofline"] = {"kernel": "forward scaled GEMM (gemm_fp8_snake_kernel<e4m3,e4m3,bf16>)", "bound": "mfma",
+        result["roofline"] = {"kernel": "forward scaled GEMM (gemm_fp8_stream_kernel<e4m3,e4m3>)", "bound": "mfma",
                               "achieved": round(fwd_tf, 1), "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
                               "frac": round(fwd_tf / FP8_PEAK_TFLOPS, 4), "traffic": _profiled_traffic(wl.name),
                               "flop_per_launch": 2.0 * M * N * K, "avg_launch_ms": round(fwd_ms, 4),

@@ -468,6 +468,16 @@ static hipError_t launch_sn(const uint8_t* a, int64_t lda, const float* sa, int 
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int64_t ntiles = (int64_t)tiles_m * tiles_n;
     if (ntiles > 0x3FFFFFFF) return hipErrorInvalidValue;
+    // whole tiles go to the persistent form of this kernel when there is more than one round of them (it overlaps a
+    // tile's epilogue with the next tile's products: nothing to overlap with one tile per CU)
+    auto whole_tiles = [&](int64_t count) -> hipError_t {
+        const int sw = knob(KNOB_GEMM_STREAM);
+        const bool want = sw != 0 && (sw >= 2 || count > compute_units());
+        if (want && gemm_fp8_stream_fits(lda, ldb, ld_out, N, K, OUT_F32, ACT))
+            return launch_gemm_fp8_stream(a, lda, FA, sa, row_a, b, ldb, FB, sb, row_b, M, N, K, out, ld_out, count, st);
+        return launch_sn_part<FA, FB, OUT_F32, ACT, false>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, tiles_m, tiles_n,
+                                                          0, count, st);
+    };
     if constexpr (!OUT_F32) {
         // A last round that would fill at most half of the CUs runs as half tiles instead: twice the
         // workgroups, half the duration each (the switch SNAKE_HALF = 0 keeps whole tiles; tuning and test aid).
@@ -476,16 +486,14 @@ static hipError_t launch_sn(const uint8_t* a, int64_t lda, const float* sa, int 
         if (knob(KNOB_SNAKE_HALF) != 0 && cus >= 16 && cus % NUM_XCD == 0 && rest > 0 && 2 * rest <= cus) {
             const int64_t full = ntiles - rest;
             if (full > 0) {
-                hipError_t err = launch_sn_part<FA, FB, OUT_F32, ACT, false>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out,
-                                                                            ld_out, tiles_m, tiles_n, 0, full, st);
+                hipError_t err = whole_tiles(full);
                 if (err != hipSuccess) return err;
             }
             return launch_sn_part<FA, FB, OUT_F32, ACT, true>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, tiles_m,
                                                               tiles_n, (int)full, 2 * rest, st);
         }
     }
-    return launch_sn_part<FA, FB, OUT_F32, ACT, false>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, tiles_m, tiles_n,
-                                                       0, ntiles, st);
+    return whole_tiles(ntiles);
 }
 
 bool gemm_fp8_snake_fits(int64_t lda, int64_t ldb) { return lda < (1 << 23) && ldb < (1 << 23); }

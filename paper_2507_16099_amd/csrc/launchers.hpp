@@ -66,6 +66,14 @@ hipError_t launch_gemm_fp8_snake(const uint8_t* a, int64_t lda, int fmt_a, const
                                  int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
                                  hipStream_t st, int act = 0);
 
+// persistent form of the same kernel (gemm_fp8_stream.hip): one workgroup per CU walks many tiles, the epilogue of a
+// tile is drained inside the K steps of the next.  bfloat16 output, whole tiles [0, units) of the snake kernel's tile
+// order; _fits: shapes it takes (N % 8 == 0, more than two K steps, 32-bit offsets reach)
+bool gemm_fp8_stream_fits(int64_t lda, int64_t ldb, int64_t ld_out, int64_t N, int64_t K, int out_f32, int act);
+hipError_t launch_gemm_fp8_stream(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
+                                  const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int row_b,
+                                  int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int64_t units, hipStream_t st);
+
 // few rows of A (M <= 64, the decode shape of inference): B is streamed once
 // from HBM by wavefronts that load their MFMA operands straight from global
 // memory; same contract otherwise.

@@ -126,6 +126,59 @@ def test_many_tiles_per_workgroup_exact(big_variant, M, N, K):
     assert (got32[rows] == want.out32).all()
 
 
+STREAM_SHAPES = [(256, 256, 384), (1024, 768, 512), (1300, 1000, 640), (2304, 2560, 640), (700, 520, 1152),
+                 (4608, 4608, 384), (300, 5000, 2176), (16, 8, 400)]
+
+
+@pytest.mark.parametrize("workgroups", [2, 8, 16, 64], ids=["default_grid", "8_workgroups", "16_workgroups", "64_workgroups"])
+@pytest.mark.parametrize("M,N,K", STREAM_SHAPES)
+def test_persistent_kernel_exact_and_equal_to_the_tile_per_workgroup_kernel(workgroups, M, N, K):
+    """The persistent form of the LDS-DMA kernel (a workgroup walks several tiles; the epilogue of a tile is drained
+    inside the K steps of the next one; stores regrouped by lane swaps, through a bounds-checked buffer), forced on
+    small problems with few workgroups so that every workgroup crosses tile boundaries: exact on small integers,
+    ragged edges in M and N, an odd number of K steps (a phantom step), the minimum of four steps, a single tile.
+    On random codes it adds the same products in the same order as the one-tile-per-workgroup kernel, so the two
+    agree bit for bit; three launches in a row agree as well."""
+    rng = np.random.default_rng(M + N + K)
+    ai = rng.integers(-2, 3, size=(M, K))
+    bi = rng.integers(-2, 3, size=(N, K))
+    sa = (2.0 ** rng.integers(-3, 4, size=M)).astype(np.float32)
+    sb = (2.0 ** rng.integers(-3, 4, size=N)).astype(np.float32)
+    exact = orc.f32_to_bf16(((ai @ bi.T) * 2.0 / sa[:, None] / sb[None, :]).astype(np.float32))
+    for fa, fb in ((orc.E4M3FN, orc.E4M3FN), (orc.E5M2, orc.E4M3FN)):
+        a = orc.encode_array((ai * 0.5).astype(np.float32), fa)
+        b = orc.encode_array((bi * 4.0).astype(np.float32), fb)
+        with knobs(GEMM_VARIANT=4, GEMM_STREAM=workgroups):
+            print(f"persistent kernel, exact case M={M} N={N} K={K} fmt=({fa},{fb}) workgroups={workgroups}", flush=True)
+            got = host_bf16_bits(_run(a, fa, sa, fp8.FP8_ROW, b, fb, sb, fp8.FP8_ROW))
+        assert (got == exact).all(), (M, N, K, fa, fb, np.argwhere(got != exact)[:6])
+    # random codes, non-power-of-two scales, tensorwise on one side, padded leading dimensions and an output view
+    a, b = _rand_codes((M, K), orc.E5M2, rng), _rand_codes((N, K), orc.E4M3FN, rng)
+    sa = rng.uniform(0.5, 300, M).astype(np.float32)
+    sb = rng.uniform(0.5, 300, 1).astype(np.float32)
+    ad, bd = dev_u8(a, (K + 15) // 16 * 16 + 32), dev_u8(b, (K + 15) // 16 * 16 + 16)
+    sad, sbd = dev_f32(sa), dev_f32(sb)
+    outs = []
+    for stream in (0, workgroups, workgroups, workgroups):
+        buf = torch.full((M, (N + 7) // 8 * 8 + 24), 0x7FC0, dtype=torch.int16, device="cuda").view(torch.bfloat16)   # NaN sentinel
+        with knobs(GEMM_VARIANT=4, GEMM_STREAM=stream):
+            fp8.fp8_scaled_mm(ad, orc.E5M2, sad, fp8.FP8_ROW, bd, orc.E4M3FN, sbd, fp8.FP8_TENSOR, 0, out=buf[:, :N])
+        torch.cuda.synchronize()
+        full = host_bf16_bits(buf)
+        assert (full[:, N:] == 0x7FC0).all(), "columns beyond N were written"
+        outs.append(full[:, :N])
+    for o in outs[1:]:
+        assert (o == outs[0]).all(), (M, N, K, np.argwhere(o != outs[0])[:6])
+    rows = si.stratified_rows(M, 12)
+    want = orc.scaled_mm(a, orc.E5M2, sa, orc.ROW, b, orc.E4M3FN, sb, orc.TENSOR, rows)
+    # uniformly random codes span the whole dynamic range: few huge products dominate every sum, and bfloat16 outputs
+    # that sit near a rounding boundary flip with the order of the additions.  Element by element: within one
+    # bfloat16 step (or, where the sum cancels, within 2^-13 of the sum of the products' magnitudes)
+    mag = orc.scaled_mm(a & 0x7F, orc.E5M2, sa, orc.ROW, b & 0x7F, orc.E4M3FN, sb, orc.TENSOR, rows).out32
+    assert_elementwise(outs[1][rows], want.out16, want.out32, min_within1=0.999, mag32=mag)
+    assert orc.rel_frobenius(si.bf16_bits_to_f32(outs[1][rows]), si.bf16_bits_to_f32(want.out16)) <= 2 * TOL
+
+
 @pytest.mark.parametrize("M,N,K", [(4096, 4096, 4096), (4096, 4352, 4208), (2048, 2304, 14336)])
 def test_long_contraction_exact_every_element(M, N, K):
     """Many K steps per tile (32, 33 - an odd count, the last one partial - and 112), every CU busy:
