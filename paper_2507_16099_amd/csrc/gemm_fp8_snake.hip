@@ -470,14 +470,30 @@ static hipError_t launch_sn(const uint8_t* a, int64_t lda, const float* sa, int 
     if (ntiles > 0x3FFFFFFF) return hipErrorInvalidValue;
     // whole tiles go to the persistent form of this kernel when there is more than one round of them (it overlaps a
     // tile's epilogue with the next tile's products: nothing to overlap with one tile per CU)
+    const int sw = knob(KNOB_GEMM_STREAM);
+    const bool stream_ok = sw != 0 && gemm_fp8_stream_fits(lda, ldb, ld_out, N, K, OUT_F32, ACT);
     auto whole_tiles = [&](int64_t count) -> hipError_t {
-        const int sw = knob(KNOB_GEMM_STREAM);
-        const bool want = sw != 0 && (sw >= 2 || count > compute_units());
-        if (want && gemm_fp8_stream_fits(lda, ldb, ld_out, N, K, OUT_F32, ACT))
-            return launch_gemm_fp8_stream(a, lda, FA, sa, row_a, b, ldb, FB, sb, row_b, M, N, K, out, ld_out, count, st);
+        if (stream_ok && (sw >= 2 || count > compute_units()))
+            return launch_gemm_fp8_stream(a, lda, FA, sa, row_a, b, ldb, FB, sb, row_b, M, N, K, out, ld_out, count, 256, st);
         return launch_sn_part<FA, FB, OUT_F32, ACT, false>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, tiles_m, tiles_n,
                                                           0, count, st);
     };
+    if (stream_ok && (sw >= 2 || ntiles > compute_units())) {
+        // a lower tile (224 or 192 rows) when its tile count fills whole rounds of workgroups better than 256-row
+        // tiles with their partly filled last round do: then the persistent kernel takes every tile
+        const int tm = gemm_fp8_stream_tile_m(M, N);
+        if (tm != 256) {
+            const int64_t cus = compute_units() > 0 ? compute_units() : 256;
+            const int64_t rest = ntiles % cus;
+            // cost of the 256-row plan in rows per CU: whole rounds, plus a last round of half tiles (measured at
+            // 0.85 of a whole round) or of whole tiles
+            const double cost256 = 256.0 * ((double)(ntiles / cus) + (rest == 0 ? 0.0 : (2 * rest <= cus ? 0.85 : 1.0)));
+            const int64_t tiles_tm = ((int64_t)M + tm - 1) / tm * tiles_n;
+            const double cost_tm = (double)tm * (double)((tiles_tm + cus - 1) / cus);
+            if (cost_tm < 0.97 * cost256 || knob(KNOB_GEMM_TILE_M) == tm)
+                return launch_gemm_fp8_stream(a, lda, FA, sa, row_a, b, ldb, FB, sb, row_b, M, N, K, out, ld_out, tiles_tm, tm, st);
+        }
+    }
     if constexpr (!OUT_F32) {
         // A last round that would fill at most half of the CUs runs as half tiles instead: twice the
         // workgroups, half the duration each (the switch SNAKE_HALF = 0 keeps whole tiles; tuning and test aid).

@@ -23,6 +23,12 @@
 // the number of operations issued after that step's last load: the five refill loads of phase 2 and, around a tile
 // boundary, the stores issued since (counted exactly; their positions in the slot sequence are fixed).
 //
+// Tile height.  The A half of a wave is two groups of fragments, A0 (four fragments, 64 rows) and A1 (AF1 = four,
+// three or two fragments): tiles of 256, 224 or 192 rows x 256 columns.  A lower tile does (4 + AF1) / 8 of the work
+// of a full one in as much less time, so the launcher picks the height whose tile count fills whole rounds of
+// workgroups best (the weight gradient of the benchmark, 14336 x 4096: 896 tiles of 256 rows are 3.5 rounds on 256
+// CUs, 1024 tiles of 224 rows are exactly 4 rounds of 7/8 the length).
+//
 // Restrictions (the launcher falls back to the non-persistent kernel otherwise): bfloat16 output, N a multiple
 // of 8, at least four K steps, leading dimensions below 2^23.
 #include "fp8_device.hpp"
@@ -90,14 +96,26 @@ struct StTile {
 
 enum { ST_FIRST = 0, ST_FIRST_DRAIN = 1, ST_MIDDLE = 2, ST_LAST = 3 };
 
-// One accumulator-drain job: A fragment U of quadrant (A half AH, B half BH).  NONE: no job.
+// One accumulator-drain job: A fragment U of quadrant (A half AH, B half BH).  none(AF1): the fragment does not
+// exist in a tile whose A1 group has AF1 fragments.
 template <int AH_, int BH_, int U_>
-struct StJob { static constexpr int AH = AH_, BH = BH_, U = U_; static constexpr bool NONE = false; };
-struct StNoJob { static constexpr int AH = 0, BH = 0, U = 0; static constexpr bool NONE = true; };
+struct StJob {
+    static constexpr int AH = AH_, BH = BH_, U = U_;
+    static constexpr bool none(int af1) { return AH == 1 && U >= af1; }
+};
+struct StNoJob {
+    static constexpr int AH = 0, BH = 0, U = 0;
+    static constexpr bool none(int) { return true; }
+};
 // Up to three jobs ride on the sixteen issue slots of a phase: job n takes slots 5n .. 5n+5 (its scale loads in
 // slot 5n, four packing slots, swaps + its two stores in slot 5n+5, which it shares with the next job's loads).
 template <class J0_, class J1_, class J2_>
-struct StJobs { using J0 = J0_; using J1 = J1_; using J2 = J2_; };
+struct StJobs {
+    using J0 = J0_; using J1 = J1_; using J2 = J2_;
+    // stores issued by the phase (two per job), and those of its slots 10 and 15 alone
+    static constexpr int stores(int af1) { return 2 * ((J0::none(af1) ? 0 : 1) + (J1::none(af1) ? 0 : 1) + (J2::none(af1) ? 0 : 1)); }
+    static constexpr int late_stores(int af1) { return 2 * ((J1::none(af1) ? 0 : 1) + (J2::none(af1) ? 0 : 1)); }
+};
 using StNoJobs = StJobs<StNoJob, StNoJob, StNoJob>;
 // The schedule around a tile boundary (L = last step of a tile, odd; F = first step of the next, even).  A quadrant
 // is final after the phase that last adds to it and must be gone before the phase of F that restarts it:
@@ -109,18 +127,22 @@ using StJobsL4 = StJobs<StJob<0, 0, 2>, StJob<0, 0, 3>, StJob<1, 0, 0>>;
 using StJobsF1 = StJobs<StJob<1, 1, 0>, StJob<1, 1, 1>, StJob<1, 0, 1>>;
 using StJobsF2 = StJobs<StJob<1, 1, 2>, StJob<1, 1, 3>, StJob<1, 0, 2>>;
 using StJobsF3 = StJobs<StJob<1, 0, 3>, StNoJob, StNoJob>;
-// Vector-memory operations issued after the last refill load of a step's phase 4 (slot 9) and before the wait in
-// the middle of the next step, beyond the five refill loads of that step's phase 2:
-//   wait of L: the six stores of L.P2;
-//   wait of F (behind a drained tile): the four stores of L.P4's slots 10 and 15, six of F.P1, six of F.P2.
-constexpr int ST_EXTRA_L = 6, ST_EXTRA_F = 4 + 6 + 6;
+// Vector-memory operations issued after the last refill load of a step's phase 4 (slot 9 at the latest) and before
+// the wait in the middle of the next step, beyond the five refill loads of that step's phase 2:
+//   wait of L: the stores of L.P2;
+//   wait of F (behind a drained tile): the stores of L.P4's slots 10 and 15, those of F.P1 and of F.P2.
+constexpr int st_extra_l(int af1) { return StJobsL2::stores(af1); }
+constexpr int st_extra_f(int af1) { return StJobsL4::late_stores(af1) + StJobsF1::stores(af1) + StJobsF2::stores(af1); }
 
-template <int FA, int FB>
+template <int FA, int FB, int AF1>
 __global__ __launch_bounds__(st::NT) void gemm_fp8_stream_kernel(
     const uint8_t* __restrict__ A, int64_t lda, const uint8_t* __restrict__ B, int64_t ldb,
     const float* __restrict__ scale_a, int row_a, const float* __restrict__ scale_b, int row_b, int M, int N,
     int K, uint16_t* __restrict__ out, int64_t ld_out, int tiles_m, int tiles_n, int units) {
     using namespace st;
+    static_assert(AF1 >= 2 && AF1 <= 4, "the A1 group has two to four fragments");
+    constexpr int TM = 32 * (4 + AF1);     // tile height: 256, 224 or 192 rows (the LDS layout keeps room for 256)
+    constexpr int NLA = TM / 32;           // LDS-DMA loads of the A part per wave and K step
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- this workgroup's tiles.  Workgroup ids are dealt round-robin to the 8 XCDs; each XCD owns a contiguous
@@ -136,7 +158,7 @@ __global__ __launch_bounds__(st::NT) void gemm_fp8_stream_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm0 = (wave >> 1) * WM, wn0 = (wave & 1) * WN;
+    const int wm0 = (wave >> 1) * (TM / 2), wn0 = (wave & 1) * WN;
 
     auto tile_of = [&](int j) {
         StTile t;
@@ -148,9 +170,9 @@ __global__ __launch_bounds__(st::NT) void gemm_fp8_stream_kernel(
         const int gsize = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
         const int tm = first_m + (logical % in_group) % gsize;
         const int tn = (logical % in_group) / gsize;
-        t.m0 = tm * BM;
+        t.m0 = tm * TM;
         t.n0 = tn * BN;
-        const int rows_a = M - t.m0 < BM ? M - t.m0 : BM, rows_b = N - t.n0 < BN ? N - t.n0 : BN;
+        const int rows_a = M - t.m0 < TM ? M - t.m0 : TM, rows_b = N - t.n0 < BN ? N - t.n0 : BN;
         const uint64_t pa = reinterpret_cast<uint64_t>(A + (int64_t)t.m0 * lda);
         const uint64_t pb = reinterpret_cast<uint64_t>(B + (int64_t)t.n0 * ldb);
         t.rsrc_a = v4i_t2{(int)(uint32_t)pa, (int)(uint32_t)(pa >> 32), (int)((int64_t)(rows_a - 1) * lda + K), 0x00020000};
@@ -159,7 +181,8 @@ __global__ __launch_bounds__(st::NT) void gemm_fp8_stream_kernel(
     };
 
     // ---- global -> LDS (as in the non-persistent kernel): wave w fills row groups w, w+4, ... (8 rows each) of both
-    //      tiles; lane l fills (row l/8, chunk slot l%8) with logical chunk slot ^ key(row)
+    //      tiles; lane l fills (row l/8, chunk slot l%8) with logical chunk slot ^ key(row).  The A part has TM rows:
+    //      NLA loads per wave (rows past TM are never read: the wave halves start at TM / 2).
     const int lrow = lane >> 3;
     const int ca = (lane & 7) ^ ((4 * (wave & 1) + (lrow >> 1)) & 7);
     const int cb_e = (lane & 7) ^ (((lrow >> 1) & 1) | (((wave >> 1) & 3) << 1));
@@ -184,7 +207,7 @@ __global__ __launch_bounds__(st::NT) void gemm_fp8_stream_kernel(
         const KOff ko = koff(k0, t.valid);
         const uint32_t la = lds_base + (uint32_t)(stage * STAGE), lb = la + BM * BK;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) st_lds_dma16(t.rsrc_a, la + i * 4096, va0 + (uint32_t)i * va_step + ko.a);
+        for (int i = 0; i < NLA; ++i) st_lds_dma16(t.rsrc_a, la + i * 4096, va0 + (uint32_t)i * va_step + ko.a);
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             st_lds_dma16(t.rsrc_b, lb + i * 4096, ((i & 1) ? vb0_o + ko.o : vb0_e + ko.e) + (uint32_t)i * vb_step);
@@ -234,7 +257,7 @@ __global__ __launch_bounds__(st::NT) void gemm_fp8_stream_kernel(
     auto job_step = [&](auto job_t, auto step_t, const Drain& d) {
         using J = decltype(job_t);
         constexpr int S = decltype(step_t)::value;
-        if constexpr (!J::NONE) {
+        if constexpr (!J::none(AF1)) {
             constexpr int AH = J::AH, BH = J::BH, U = J::U;
             auto fetch_b = [&](int T) {
                 const float4 t4 = *reinterpret_cast<const float4*>(d.tab + 256 + wn0 + 64 * BH + 16 * g + 4 * T);
@@ -297,23 +320,25 @@ __global__ __launch_bounds__(st::NT) void gemm_fp8_stream_kernel(
                       RH = decltype(rh_t)::value, L0 = decltype(l0_t)::value, CNT = decltype(cnt_t)::value,
                       ZERO = decltype(zero_t)::value;
         using JS = decltype(jobs_t);
-        constexpr bool DRAINS = !JS::J0::NONE;
+        constexpr bool DRAINS = JS::stores(AF1) > 0;
         [&]<int... TS>(std::integer_sequence<int, TS...>) {
             ([&] {
                 constexpr int t = TS;
                 constexpr int i = t >> 2, j = (i & 1) ? 3 - (t & 3) : (t & 3);   // boustrophedon: one operand stays between neighbours
-                if constexpr (ZERO)
-                    acc[AH * 4 + i][BH * 4 + j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                        bf[BH][j], af[AH][i], v4f_t2{0.f, 0.f, 0.f, 0.f}, FB, FA, 0, 0, 0, 0);
-                else
-                    acc[AH * 4 + i][BH * 4 + j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                        bf[BH][j], af[AH][i], acc[AH * 4 + i][BH * 4 + j], FB, FA, 0, 0, 0, 0);
-                if constexpr (RDA == 1 && t % 2 == 0 && t < 8) read_a(rs, RH, t / 2);
+                if constexpr (AH == 0 || i < AF1) {        // (a lower tile has no fragment i of the A1 group: the slot stays empty)
+                    if constexpr (ZERO)
+                        acc[AH * 4 + i][BH * 4 + j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                            bf[BH][j], af[AH][i], v4f_t2{0.f, 0.f, 0.f, 0.f}, FB, FA, 0, 0, 0, 0);
+                    else
+                        acc[AH * 4 + i][BH * 4 + j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                            bf[BH][j], af[AH][i], acc[AH * 4 + i][BH * 4 + j], FB, FA, 0, 0, 0, 0);
+                }
+                if constexpr (RDA == 1 && t % 2 == 0 && t < 8 && (RH == 0 || t / 2 < AF1)) read_a(rs, RH, t / 2);
                 if constexpr (RDA == 0 && t % 2 == 0 && t < 8) read_b(rs, RH, t / 2);
                 if constexpr (t % 2 == 1 && t / 2 < CNT) {
                     constexpr int q = L0 + t / 2;
                     if constexpr (q < 8) st_lds_dma16(lt.rsrc_b, lb + q * 4096, ((q & 1) ? vb0_o + ko.o : vb0_e + ko.e) + (uint32_t)q * vb_step);
-                    else st_lds_dma16(lt.rsrc_a, la + (q - 8) * 4096, va0 + (uint32_t)(q - 8) * va_step + ko.a);
+                    else if constexpr (q - 8 < NLA) st_lds_dma16(lt.rsrc_a, la + (q - 8) * 4096, va0 + (uint32_t)(q - 8) * va_step + ko.a);
                 }
                 if constexpr (DRAINS) {
                     __builtin_amdgcn_sched_barrier(0);     // the slot's refill load is issued before its stores (the wait counts rely on it)
@@ -351,7 +376,7 @@ __global__ __launch_bounds__(st::NT) void gemm_fp8_stream_kernel(
 
     auto drain_of = [&](int m0, int n0, int j) {
         Drain d;
-        const int rows = M - m0 < BM ? M - m0 : BM;
+        const int rows = M - m0 < TM ? M - m0 : TM;
         d.n_left = N - n0;
         const int cols = d.n_left < BN ? d.n_left : BN;
         d.rsrc = __builtin_amdgcn_make_buffer_rsrc(out + (int64_t)m0 * ld_out + n0, 0, (int)(((int64_t)(rows - 1) * ld_out + cols) * 2), 0x00020000);
@@ -378,7 +403,7 @@ __global__ __launch_bounds__(st::NT) void gemm_fp8_stream_kernel(
             phase(I0{}, I0{}, I0{}, I1{}, I0{}, I0{}, Z{}, std::conditional_t<FD, StJobsF1, NJ>{}, s_cur, la, lb, lt, ko, dprev);   // (A0,B0) | read B1 of this step
             st_barrier_lds();                  // this step's B part is read out by everyone
             phase(I0{}, I1{}, I1{}, I1{}, I0{}, I5{}, Z{}, std::conditional_t<FD, StJobsF2, NJ>{}, s_cur, la, lb, lt, ko, dprev);   // (A0,B1) | read A1 of this step, refill B 0-4
-            st_wait_vmem_but_barrier<5 + (FD ? ST_EXTRA_F : 0)>();   // step k+1 has landed for everyone; this step's A part is read out
+            st_wait_vmem_but_barrier<5 + (FD ? st_extra_f(AF1) : 0)>();   // step k+1 has landed for everyone; this step's A part is read out
             if constexpr (FIRST) scale_loads(cur);   // older than the refill loads below: complete at the next such wait
             phase(I1{}, I1{}, I1{}, I0{}, I5{}, I6{}, Z{}, std::conditional_t<FD, StJobsF3, NJ>{}, s_nxt, la, lb, lt, ko, dprev);   // (A1,B1) | read A0 of step k+1, refill B 5-7, A 0-2
             phase(I1{}, I0{}, I0{}, I1{}, I11{}, I5{}, Z{}, NJ{}, s_nxt, la, lb, lt, ko, dprev);                                    // (A1,B0) | read B1 of step k+1, refill A 3-7
@@ -392,7 +417,7 @@ __global__ __launch_bounds__(st::NT) void gemm_fp8_stream_kernel(
             phase(I0{}, I1{}, I0{}, I0{}, I0{}, I0{}, I0{}, NJ{}, s_cur, la, lb, lt, ko, dcur);                                     // (A0,B1) | read B0 of this step
             st_barrier_lds();
             phase(I0{}, I0{}, I1{}, I1{}, I0{}, I5{}, I0{}, std::conditional_t<LD, StJobsL2, NJ>{}, s_cur, la, lb, lt, ko, dcur);   // (A0,B0) | read A1 of this step, refill B 0-4
-            st_wait_vmem_but_barrier<5 + (LD ? ST_EXTRA_L : 0)>();
+            st_wait_vmem_but_barrier<5 + (LD ? st_extra_l(AF1) : 0)>();
             if constexpr (FIRST) scale_table(tab_cur);
             phase(I1{}, I0{}, I1{}, I0{}, I5{}, I6{}, I0{}, std::conditional_t<LD, StJobsL3, NJ>{}, s_nxt, la, lb, lt, ko, dcur);   // (A1,B0) | read A0 of step k+1, refill B 5-7, A 0-2
             phase(I1{}, I1{}, I0{}, I0{}, I11{}, I5{}, I0{}, std::conditional_t<LD, StJobsL4, NJ>{}, s_nxt, la, lb, lt, ko, dcur);  // (A1,B1) | read B0 of step k+1, refill A 3-7
@@ -445,12 +470,12 @@ __global__ __launch_bounds__(st::NT) void gemm_fp8_stream_kernel(
     }
 }
 
-template <int FA, int FB>
+template <int FA, int FB, int AF1>
 static hipError_t launch_stream_t(const uint8_t* a, int64_t lda, const float* sa, int row_a, const uint8_t* b, int64_t ldb,
                                   const float* sb, int row_b, int M, int N, int K, void* out, int64_t ld_out, int tiles_m,
                                   int tiles_n, int64_t units, hipStream_t st) {
     using namespace st;
-    auto kern = gemm_fp8_stream_kernel<FA, FB>;
+    auto kern = gemm_fp8_stream_kernel<FA, FB, AF1>;
     static DynamicLdsOnce attr;
     if (hipError_t e = attr.ensure(reinterpret_cast<const void*>(kern), LDS_BYTES); e != hipSuccess) return e;
     // one workgroup per CU (they do not fit twice), a multiple of the XCD count; the switch GEMM_STREAM >= 8 sets
@@ -466,26 +491,50 @@ static hipError_t launch_stream_t(const uint8_t* a, int64_t lda, const float* sa
     return hipGetLastError();
 }
 
-// whole tiles [0, units) of the tile order of the non-persistent kernel
 bool gemm_fp8_stream_fits(int64_t lda, int64_t ldb, int64_t ld_out, int64_t N, int64_t K, int out_f32, int act) {
     return !out_f32 && !act && N % 8 == 0 && K > 2 * st::BK && lda < (1 << 23) && ldb < (1 << 23) && ld_out < (1 << 22);
 }
 
+// Tile height (256, 224 or 192 rows) for an [M, N] output when the persistent kernel takes every tile: the one
+// with the least rounds x height on this device's CUs; 256 when it is no worse (a lower tile moves more operand
+// bytes per product).  The switch GEMM_TILE_M forces one.
+int gemm_fp8_stream_tile_m(int64_t M, int64_t N) {
+    const int forced = knob(KNOB_GEMM_TILE_M);
+    if (forced == 256 || forced == 224 || forced == 192) return forced;
+    const int64_t cus = compute_units() > 0 ? compute_units() : 256;
+    const int64_t tiles_n = (N + st::BN - 1) / st::BN;
+    int best = 256;
+    int64_t best_cost = 0;
+    for (int tm : {256, 224, 192}) {
+        const int64_t tiles = (M + tm - 1) / tm * tiles_n;
+        const int64_t cost = (tiles + cus - 1) / cus * tm;
+        if (tm == 256 || cost < best_cost) { best = tm; best_cost = cost; }
+    }
+    return best;
+}
+
+// tiles [0, units) of the tile order of the non-persistent kernel (tile_m == 256), or every tile of the problem cut
+// into tiles of tile_m rows (units == the tile count)
 hipError_t launch_gemm_fp8_stream(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
                                   const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int row_b,
-                                  int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int64_t units, hipStream_t st) {
+                                  int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int64_t units, int tile_m,
+                                  hipStream_t st) {
     using namespace st;
     if (units <= 0) return hipSuccess;
-    const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
+    if (tile_m != 256 && tile_m != 224 && tile_m != 192) return hipErrorInvalidValue;
+    const int tiles_m = (int)((M + tile_m - 1) / tile_m), tiles_n = (int)((N + BN - 1) / BN);
     if (units > (int64_t)tiles_m * tiles_n || units > 0x3FFFFFFF) return hipErrorInvalidValue;
     const int m = (int)M, n = (int)N, k = (int)K;
 #define FP8K_STREAM(FA_, FB_)                                                                                   \
-    if (fmt_a == FA_ && fmt_b == FB_)                                                                           \
-        return launch_stream_t<FA_, FB_>(a, lda, scale_a, row_a, b, ldb, scale_b, row_b, m, n, k, out, ld_out, tiles_m, tiles_n, units, st)
-    FP8K_STREAM(FMT_E4M3FN, FMT_E4M3FN);
-    FP8K_STREAM(FMT_E5M2, FMT_E4M3FN);
-    FP8K_STREAM(FMT_E4M3FN, FMT_E5M2);
-    FP8K_STREAM(FMT_E5M2, FMT_E5M2);
+    if (fmt_a == FA_ && fmt_b == FB_) {                                                                         \
+        if (tile_m == 256) return launch_stream_t<FA_, FB_, 4>(a, lda, scale_a, row_a, b, ldb, scale_b, row_b, m, n, k, out, ld_out, tiles_m, tiles_n, units, st); \
+        if (tile_m == 224) return launch_stream_t<FA_, FB_, 3>(a, lda, scale_a, row_a, b, ldb, scale_b, row_b, m, n, k, out, ld_out, tiles_m, tiles_n, units, st); \
+        return launch_stream_t<FA_, FB_, 2>(a, lda, scale_a, row_a, b, ldb, scale_b, row_b, m, n, k, out, ld_out, tiles_m, tiles_n, units, st); \
+    }
+    FP8K_STREAM(FMT_E4M3FN, FMT_E4M3FN)
+    FP8K_STREAM(FMT_E5M2, FMT_E4M3FN)
+    FP8K_STREAM(FMT_E4M3FN, FMT_E5M2)
+    FP8K_STREAM(FMT_E5M2, FMT_E5M2)
 #undef FP8K_STREAM
     return hipErrorInvalidValue;
 }

@@ -70,9 +70,13 @@ hipError_t launch_gemm_fp8_snake(const uint8_t* a, int64_t lda, int fmt_a, const
 // tile is drained inside the K steps of the next.  bfloat16 output, whole tiles [0, units) of the snake kernel's tile
 // order; _fits: shapes it takes (N % 8 == 0, more than two K steps, 32-bit offsets reach)
 bool gemm_fp8_stream_fits(int64_t lda, int64_t ldb, int64_t ld_out, int64_t N, int64_t K, int out_f32, int act);
+// tile_m: 256 (tiles [0, units) of the snake kernel's tile order) or 224 / 192 (then units must be the whole tile count
+// of the problem cut into tiles of that height); gemm_fp8_stream_tile_m picks the height for an [M, N] output
+int gemm_fp8_stream_tile_m(int64_t M, int64_t N);
 hipError_t launch_gemm_fp8_stream(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a, int row_a,
                                   const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int row_b,
-                                  int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int64_t units, hipStream_t st);
+                                  int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int64_t units, int tile_m,
+                                  hipStream_t st);
 
 // few rows of A (M <= 64, the decode shape of inference): B is streamed once
 // from HBM by wavefronts that load their MFMA operands straight from global

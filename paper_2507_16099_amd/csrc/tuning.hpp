@@ -20,6 +20,7 @@ enum Knob {
     KNOB_MX_SLAB,           // 0 = plain scale rows inside the MX / blockwise linear calls
     KNOB_BF16_VARIANT,      // bfloat16 dW: 0 = register-staged kernel, 1 = LDS-DMA kernel
     KNOB_GEMM_STREAM,       // persistent LDS-DMA kernel: 0 = never, 2 = wherever it fits, >= 8 = wherever it fits, with that many workgroups
+    KNOB_GEMM_TILE_M,       // persistent kernel: 256, 224 or 192 forces the tile height
     KNOB_COUNT
 };
 

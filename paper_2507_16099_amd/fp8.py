@@ -135,7 +135,7 @@ def load_library() -> C.CDLL:
 
 def set_knob(name: str, value: int | None) -> None:
     """Force one of the library's tuning / test switches (GEMM_VARIANT, SNAKE_HALF, SKINNY_NW, SKINNY_DMA,
-    MX_VARIANT, MX_SLAB, BF16_VARIANT, GEMM_STREAM) for the rest of the process; None restores the default.  The
+    MX_VARIANT, MX_SLAB, BF16_VARIANT, GEMM_STREAM, GEMM_TILE_M) for the rest of the process; None restores the default.  The
     library reads FP8MI355_<NAME> from the environment once, on first use; afterwards only this call changes a switch."""
     if load_library().fp8_internal_set_knob(name.encode(), -1 if value is None else int(value)) != 0:
         raise ValueError(f"unknown switch {name!r}")

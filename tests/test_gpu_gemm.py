@@ -130,15 +130,18 @@ STREAM_SHAPES = [(256, 256, 384), (1024, 768, 512), (1300, 1000, 640), (2304, 25
                  (4608, 4608, 384), (300, 5000, 2176), (16, 8, 400)]
 
 
-@pytest.mark.parametrize("workgroups", [2, 8, 16, 64], ids=["default_grid", "8_workgroups", "16_workgroups", "64_workgroups"])
+@pytest.mark.parametrize("workgroups,tile_m", [(2, 256), (8, 256), (16, 256), (64, 256), (8, 224), (64, 224), (8, 192), (2, 192)],
+                         ids=["default_grid", "8_workgroups", "16_workgroups", "64_workgroups", "8_workgroups_224_rows",
+                              "64_workgroups_224_rows", "8_workgroups_192_rows", "default_grid_192_rows"])
 @pytest.mark.parametrize("M,N,K", STREAM_SHAPES)
-def test_persistent_kernel_exact_and_equal_to_the_tile_per_workgroup_kernel(workgroups, M, N, K):
+def test_persistent_kernel_exact_and_equal_to_the_tile_per_workgroup_kernel(workgroups, tile_m, M, N, K):
     """The persistent form of the LDS-DMA kernel (a workgroup walks several tiles; the epilogue of a tile is drained
     inside the K steps of the next one; stores regrouped by lane swaps, through a bounds-checked buffer), forced on
     small problems with few workgroups so that every workgroup crosses tile boundaries: exact on small integers,
     ragged edges in M and N, an odd number of K steps (a phantom step), the minimum of four steps, a single tile.
     On random codes it adds the same products in the same order as the one-tile-per-workgroup kernel, so the two
-    agree bit for bit; three launches in a row agree as well."""
+    agree bit for bit; three launches in a row agree as well.  Tiles of 256, 224 and 192 rows (the lower ones are
+    what the dispatch takes when their count fills whole rounds of workgroups better)."""
     rng = np.random.default_rng(M + N + K)
     ai = rng.integers(-2, 3, size=(M, K))
     bi = rng.integers(-2, 3, size=(N, K))
@@ -148,8 +151,8 @@ def test_persistent_kernel_exact_and_equal_to_the_tile_per_workgroup_kernel(work
     for fa, fb in ((orc.E4M3FN, orc.E4M3FN), (orc.E5M2, orc.E4M3FN)):
         a = orc.encode_array((ai * 0.5).astype(np.float32), fa)
         b = orc.encode_array((bi * 4.0).astype(np.float32), fb)
-        with knobs(GEMM_VARIANT=4, GEMM_STREAM=workgroups):
-            print(f"persistent kernel, exact case M={M} N={N} K={K} fmt=({fa},{fb}) workgroups={workgroups}", flush=True)
+        with knobs(GEMM_VARIANT=4, GEMM_STREAM=workgroups, GEMM_TILE_M=tile_m):
+            print(f"persistent kernel, exact case M={M} N={N} K={K} fmt=({fa},{fb}) workgroups={workgroups} tile_m={tile_m}", flush=True)
             got = host_bf16_bits(_run(a, fa, sa, fp8.FP8_ROW, b, fb, sb, fp8.FP8_ROW))
         assert (got == exact).all(), (M, N, K, fa, fb, np.argwhere(got != exact)[:6])
     # random codes, non-power-of-two scales, tensorwise on one side, padded leading dimensions and an output view
@@ -161,7 +164,7 @@ def test_persistent_kernel_exact_and_equal_to_the_tile_per_workgroup_kernel(work
     outs = []
     for stream in (0, workgroups, workgroups, workgroups):
         buf = torch.full((M, (N + 7) // 8 * 8 + 24), 0x7FC0, dtype=torch.int16, device="cuda").view(torch.bfloat16)   # NaN sentinel
-        with knobs(GEMM_VARIANT=4, GEMM_STREAM=stream):
+        with knobs(GEMM_VARIANT=4, GEMM_STREAM=stream, GEMM_TILE_M=tile_m):
             fp8.fp8_scaled_mm(ad, orc.E5M2, sad, fp8.FP8_ROW, bd, orc.E4M3FN, sbd, fp8.FP8_TENSOR, 0, out=buf[:, :N])
         torch.cuda.synchronize()
         full = host_bf16_bits(buf)
