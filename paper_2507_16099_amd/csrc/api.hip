@@ -127,11 +127,12 @@ int quantize_row_col_impl(const void* x, int64_t rows, int64_t cols, int64_t ld,
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // part: per-block maxima of the tensorwise amax pass (one tensor at a time: the casts consume them in stream order)
+// fold_*: side storage for first-level column maxima of small tensors (rowwise recipe; may be empty)
 struct FwdPlan {
-    size_t xq, wq, sx, sw, part, total;
+    size_t xq, wq, sx, sw, part, fold_x, fold_w, total;
 };
 struct BwdPlan {
-    size_t gq, gqt, wt, xt, sg, sgt, swt, sxt, part, total;
+    size_t gq, gqt, wt, xt, sg, sgt, swt, sxt, part, fold_g, fold_w, fold_x, total;
 };
 
 FwdPlan plan_fwd(int64_t M, int64_t K, int64_t N, int gran) {
@@ -143,6 +144,8 @@ FwdPlan plan_fwd(int64_t M, int64_t K, int64_t N, int gran) {
     p.sx = take(sizeof(float) * (gran == FP8_ROW ? (size_t)M : 1));
     p.sw = take(sizeof(float) * (gran == FP8_ROW ? (size_t)N : 1));
     p.part = take(sizeof(float) * fp8k::TENSOR_PARTIALS);
+    p.fold_x = take(gran == FP8_ROW ? (size_t)fp8k::quant_fold_bytes(M, K) : 0);
+    p.fold_w = take(gran == FP8_ROW ? (size_t)fp8k::quant_fold_bytes(N, K) : 0);
     p.total = o;
     return p;
 }
@@ -161,8 +164,28 @@ BwdPlan plan_bwd(int64_t M, int64_t K, int64_t N, int gran) {
     p.swt = take(sizeof(float) * (row ? (size_t)K : 1));
     p.sxt = take(sizeof(float) * (row ? (size_t)K : 1));
     p.part = take(sizeof(float) * fp8k::TENSOR_PARTIALS);
+    p.fold_g = take(row ? (size_t)fp8k::quant_fold_bytes(M, N) : 0);
+    p.fold_w = take(row ? (size_t)fp8k::quant_fold_bytes(N, K) : 0);
+    p.fold_x = take(row ? (size_t)fp8k::quant_fold_bytes(M, K) : 0);
     p.total = o;
     return p;
+}
+
+// The two products of a backward step from quantized operands: dX[M, K] = dY W (contraction over N) and
+// dW[N, K] = dY^T X (contraction over M).  sg / sgt: scales of dY for the first / second product (the same
+// pointer for tensorwise scaling).  Small products share one launch.
+int grad_gemms(const fp8_recipe* r, int row, const uint8_t* gq, const float* sg, const uint8_t* wt, const float* swt,
+               const uint8_t* gqt, const float* sgt, const uint8_t* xt, const float* sxt, int64_t M, int64_t K, int64_t N,
+               void* dx, void* dw, hipStream_t st) {
+    if (dx && dw && r->fmt_w == r->fmt_x) {
+        const fp8k::GemmOperands g1{gq, N, sg, wt, N, swt, M, K, N, dx, K}, g2{gqt, M, sgt, xt, M, sxt, N, K, M, dw, K};
+        const hipError_t e = fp8k::launch_gemm_fp8_pair(g1, g2, r->fmt_dy, r->fmt_w, row, row, st);
+        if (e == hipSuccess) return FP8_OK;
+        if (e != hipErrorNotSupported) return hip_fail(e, "gemm_fp8_pair");
+    }
+    if (dx) FP8_TRY(fp8k::launch_gemm_fp8(gq, N, r->fmt_dy, sg, row, wt, N, r->fmt_w, swt, row, M, K, N, dx, K, 0, st));
+    if (dw) FP8_TRY(fp8k::launch_gemm_fp8(gqt, M, r->fmt_dy, sgt, row, xt, M, r->fmt_x, sxt, row, N, K, M, dw, K, 0, st));
+    return FP8_OK;
 }
 
 int check_recipe(const char* fn, const fp8_recipe* r) {
@@ -357,12 +380,23 @@ int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N
             return FP8_OK;
         }
         float *sx = reinterpret_cast<float*>(wsf + p.sx), *sw = reinterpret_cast<float*>(wsf + p.sw);
-        if (recipe->flags & FP8_GRAD_WEIGHT_HP) {   // dW will come from the bfloat16 X: no fp8 copy of X to keep
-            if (int rc = quantize_impl(x, M, K, K, FP8_ROW, recipe->fmt_x, fl, wsf + p.xq, K, nullptr, 0, sx, st)) return rc;
-        } else {
-            if (int rc = quantize_row_col_impl(x, M, K, K, recipe->fmt_x, fl, wsf + p.xq, K, sx, wsb + b.xt, M, sxt, st)) return rc;
+        bool done = false;
+        if (!(recipe->flags & FP8_GRAD_WEIGHT_HP) && recipe->fmt_x == recipe->fmt_w) {
+            // X and W the same way: twin launches, three (small tensors: two) instead of six
+            const fp8k::RowColOperand ox{x, M, K, wsf + p.xq, K, sx, wsb + b.xt, M, sxt, wsf + p.fold_x};
+            const fp8k::RowColOperand ow{w, N, K, wsf + p.wq, K, sw, wsb + b.wt, N, swt, wsf + p.fold_w};
+            const hipError_t e = fp8k::launch_quant_row_col_pair(ox, &ow, K, recipe->fmt_x, fl, st);
+            if (e == hipSuccess) done = true;
+            else if (e != hipErrorNotSupported) return hip_fail(e, "quant_row_col_pair");
         }
-        if (int rc = quantize_row_col_impl(w, N, K, K, recipe->fmt_w, fl, wsf + p.wq, K, sw, wsb + b.wt, N, swt, st)) return rc;
+        if (!done) {
+            if (recipe->flags & FP8_GRAD_WEIGHT_HP) {   // dW will come from the bfloat16 X: no fp8 copy of X to keep
+                if (int rc = quantize_impl(x, M, K, K, FP8_ROW, recipe->fmt_x, fl, wsf + p.xq, K, nullptr, 0, sx, st)) return rc;
+            } else {
+                if (int rc = quantize_row_col_impl(x, M, K, K, recipe->fmt_x, fl, wsf + p.xq, K, sx, wsb + b.xt, M, sxt, st)) return rc;
+            }
+            if (int rc = quantize_row_col_impl(w, N, K, K, recipe->fmt_w, fl, wsf + p.wq, K, sw, wsb + b.wt, N, swt, st)) return rc;
+        }
         FP8_TRY(fp8k::launch_gemm_fp8(wsf + p.xq, K, recipe->fmt_x, sx, 1, wsf + p.wq, K, recipe->fmt_w, sw, 1, M, N, K, y, N, 0, st));
         return FP8_OK;
     }
@@ -373,8 +407,16 @@ int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N
     float *sx = reinterpret_cast<float*>(ws + p.sx), *sw = reinterpret_cast<float*>(ws + p.sw);
     const int g = recipe->gran, fl = recipe->flags & FP8_POW2_SCALE;
     float* part = reinterpret_cast<float*>(ws + p.part);
-    if (int rc = quantize_impl(x, M, K, K, g, recipe->fmt_x, fl, xq, K, nullptr, 0, sx, st, part)) return rc;
-    if (int rc = quantize_impl(w, N, K, K, g, recipe->fmt_w, fl, wq, K, nullptr, 0, sw, st, part)) return rc;
+    bool pair_done = false;
+    if (g == FP8_ROW && recipe->fmt_x == recipe->fmt_w && K > 0) {   // X and W in one launch
+        const hipError_t e = fp8k::launch_quant_row_pair(x, M, K, xq, K, sx, w, N, K, wq, K, sw, K, recipe->fmt_x, fl, st);
+        if (e == hipSuccess) pair_done = true;
+        else if (e != hipErrorNotSupported) return hip_fail(e, "quant_row_pair");
+    }
+    if (!pair_done) {
+        if (int rc = quantize_impl(x, M, K, K, g, recipe->fmt_x, fl, xq, K, nullptr, 0, sx, st, part)) return rc;
+        if (int rc = quantize_impl(w, N, K, K, g, recipe->fmt_w, fl, wq, K, nullptr, 0, sw, st, part)) return rc;
+    }
     FP8_TRY(fp8k::launch_gemm_fp8(xq, K, recipe->fmt_x, sx, g == FP8_ROW, wq, K, recipe->fmt_w, sw, g == FP8_ROW, M, N, K,
                                   y, N, 0, st));
     return FP8_OK;
@@ -424,24 +466,33 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
         } else {
             if (int rc = quantize_impl(dy, M, N, N, FP8_TENSOR, recipe->fmt_dy, fl, gq, N, nullptr, 0, sg, st, part)) return rc;
         }
-        if (dx) {
-            if (!saved)
-                if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st, part)) return rc;
-            FP8_TRY(fp8k::launch_gemm_fp8(gq, N, recipe->fmt_dy, sg, 0, wt, N, recipe->fmt_w, swt, 0, M, K, N, dx, K, 0, st));
-        }
-        if (dw) {
-            if (!saved)
-                if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st, part)) return rc;
-            FP8_TRY(fp8k::launch_gemm_fp8(gqt, M, recipe->fmt_dy, sg, 0, xt, M, recipe->fmt_x, sxt, 0, N, K, M, dw, K, 0, st));
-        }
-        return FP8_OK;
+        if (dx && !saved)
+            if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st, part)) return rc;
+        if (dw && !saved)
+            if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st, part)) return rc;
+        return grad_gemms(recipe, 0, gq, sg, wt, swt, gqt, sg, xt, sxt, M, K, N, dx, dw, st);
     }
     // rowwise: every operand re-quantized along the contraction axis of its GEMM
     // (dX = dY W contracts over N, dW = dY^T X over M).  All quantizations first,
     // then the GEMMs back to back.
     const bool both = dx && dw;
+    if (both && !saved && recipe->fmt_w == recipe->fmt_x) {
+        // all three tensors in five launches: dY's rowwise pass (which also gathers its column maxima), the column
+        // maxima of W and X together, one launch for every column scale, two for the transposing casts
+        const fp8k::RowColOperand og{dy, M, N, gq, N, sg, gqt, M, sgt, ws + p.fold_g};
+        const fp8k::ColOperand ow{w, N, K, wt, N, swt, ws + p.fold_w}, ox{x, M, K, xt, M, sxt, ws + p.fold_x};
+        const hipError_t e = fp8k::launch_quant_bwd_rowwise(og, N, recipe->fmt_dy, ow, ox, K, recipe->fmt_w, fl, st);
+        if (e == hipSuccess) return grad_gemms(recipe, 1, gq, sg, wt, swt, gqt, sgt, xt, sxt, M, K, N, dx, dw, st);
+        if (e != hipErrorNotSupported) return hip_fail(e, "quant_bwd_rowwise");
+    }
     if (both) {   // dY along N (rows) and along M (columns, transposed) from two reads instead of three
-        if (int rc = quantize_row_col_impl(dy, M, N, N, recipe->fmt_dy, fl, gq, N, sg, gqt, M, sgt, st)) return rc;
+        const fp8k::RowColOperand og{dy, M, N, gq, N, sg, gqt, M, sgt, ws + p.fold_g};
+        const hipError_t e = fp8k::launch_quant_row_col_pair(og, nullptr, N, recipe->fmt_dy, fl, st);
+        if (e == hipErrorNotSupported) {
+            if (int rc = quantize_row_col_impl(dy, M, N, N, recipe->fmt_dy, fl, gq, N, sg, gqt, M, sgt, st)) return rc;
+        } else if (e != hipSuccess) {
+            return hip_fail(e, "quant_row_col");
+        }
     } else if (dx) {
         if (int rc = quantize_impl(dy, M, N, N, FP8_ROW, recipe->fmt_dy, fl, gq, N, nullptr, 0, sg, st)) return rc;
     } else {
@@ -451,11 +502,7 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
         if (int rc = quantize_impl(w, N, K, K, FP8_COL, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st)) return rc;
     if (dw && !saved)
         if (int rc = quantize_impl(x, M, K, K, FP8_COL, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st)) return rc;
-    if (dx)
-        FP8_TRY(fp8k::launch_gemm_fp8(gq, N, recipe->fmt_dy, sg, 1, wt, N, recipe->fmt_w, swt, 1, M, K, N, dx, K, 0, st));
-    if (dw)
-        FP8_TRY(fp8k::launch_gemm_fp8(gqt, M, recipe->fmt_dy, sgt, 1, xt, M, recipe->fmt_x, sxt, 1, N, K, M, dw, K, 0, st));
-    return FP8_OK;
+    return grad_gemms(recipe, 1, gq, sg, wt, swt, gqt, sgt, xt, sxt, M, K, N, dx, dw, st);
 }
 
 namespace {
@@ -515,11 +562,7 @@ int fp8_linear_bwd_sigmoid(const void* dy, const void* y, const void* x, const v
         if (int rc = quantize_impl(w, N, K, K, FP8_COL, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st)) return rc;
     if (dw && !saved)
         if (int rc = quantize_impl(x, M, K, K, FP8_COL, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st)) return rc;
-    if (dx)
-        FP8_TRY(fp8k::launch_gemm_fp8(gq, N, recipe->fmt_dy, sg, 1, wt, N, recipe->fmt_w, swt, 1, M, K, N, dx, K, 0, st));
-    if (dw)
-        FP8_TRY(fp8k::launch_gemm_fp8(gqt, M, recipe->fmt_dy, sgt, 1, xt, M, recipe->fmt_x, sxt, 1, N, K, M, dw, K, 0, st));
-    return FP8_OK;
+    return grad_gemms(recipe, 1, gq, sg, wt, swt, gqt, sgt, xt, sxt, M, K, N, dx, dw, st);
 }
 
 int fp8_grad_weight_hp(const void* dy, const void* x, int64_t M, int64_t K, int64_t N, void* dw, void* stream) {

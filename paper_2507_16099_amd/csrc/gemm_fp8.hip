@@ -55,11 +55,29 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 // PD: how many K steps ahead of the matrix cores the global loads run (register sets in flight).  A
 // workgroup that is alone on its CU has nothing else to hide the load latency with (about 1 us per step
 // at PD = 1, whatever the tile); the small tiles, used when there are few of them, take PD = 4.
+// One product as the kernel sees it.  A launch can carry two of them (same formats, same kinds of scale): workgroups
+// from `split` on, a multiple of 8, work on the second, so that the two small products of a backward step share
+// one launch and run side by side.
+struct TnProblem {
+    const uint8_t* A; int64_t lda; const uint8_t* B; int64_t ldb;
+    const float* scale_a; const float* scale_b; int M, N, K; void* out; int64_t ld_out; int tiles_m, tiles_n;
+};
+constexpr int ONE_PROBLEM = 0x7FFFFFFF;
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, bool OUT_F32, int PD = 1>
-__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_tn_kernel(
-    const uint8_t* __restrict__ A, int64_t lda, const uint8_t* __restrict__ B, int64_t ldb,
-    const float* __restrict__ scale_a, int row_a, const float* __restrict__ scale_b, int row_b, int M, int N,
-    int K, void* __restrict__ out, int64_t ld_out, int tiles_m, int tiles_n) {
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_tn_kernel(TnProblem p1, int row_a, int row_b, int split,
+                                                                            TnProblem p2) {
+    const bool second = (int)blockIdx.x >= split;
+    const TnProblem& p = second ? p2 : p1;
+    const uint8_t* __restrict__ A = p.A;
+    const uint8_t* __restrict__ B = p.B;
+    const float* __restrict__ scale_a = p.scale_a;
+    const float* __restrict__ scale_b = p.scale_b;
+    void* __restrict__ out = p.out;
+    const int64_t lda = p.lda, ldb = p.ldb, ld_out = p.ld_out;
+    const int M = p.M, N = p.N, K = p.K, tiles_m = p.tiles_m, tiles_n = p.tiles_n;
+    const int bid = second ? (int)blockIdx.x - split : (int)blockIdx.x;
+    const int nblocks = second ? (int)gridDim.x - split : (split == ONE_PROBLEM ? (int)gridDim.x : split);
     constexpr int NT = WAVES_M * WAVES_N * 64;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int FM = WM / 16;       // A fragments (16 rows each) per wave
@@ -74,8 +92,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_tn_kernel(
 
     // ---- workgroup -> tile
     const int ntiles = tiles_m * tiles_n;
-    const int per_xcd = gridDim.x / NUM_XCD;
-    const int logical = (blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
+    const int per_xcd = nblocks / NUM_XCD;
+    const int logical = (bid % NUM_XCD) * per_xcd + bid / NUM_XCD;
     if (logical >= ntiles) return;
     const int in_group = GROUP_M * tiles_n;
     const int first_m = (logical / in_group) * GROUP_M;
@@ -254,54 +272,63 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_tn_kernel(
     }
 }
 
+// g2 == nullptr: one product
 template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, bool OUT_F32, int PD = 1>
-static hipError_t launch_variant(const uint8_t* a, int64_t lda, const float* sa, int row_a, const uint8_t* b,
-                                 int64_t ldb, const float* sb, int row_b, int M, int N, int K, void* out,
-                                 int64_t ld_out, hipStream_t st) {
+static hipError_t launch_variant(const GemmOperands& g1, const GemmOperands* g2, int row_a, int row_b, hipStream_t st) {
     auto kern = gemm_fp8_tn_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, OUT_F32, PD>;
     constexpr int lds = 2 * (BM + BN) * BK;
     static DynamicLdsOnce attr;     // one per instantiation
     if (hipError_t e = attr.ensure(reinterpret_cast<const void*>(kern), lds); e != hipSuccess) return e;
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const int64_t ntiles = (int64_t)tiles_m * tiles_n;
-    const int64_t grid = (ntiles + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
-    if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
-    kern<<<dim3((unsigned)grid), dim3(WAVES_M * WAVES_N * 64), lds, st>>>(a, lda, b, ldb, sa, row_a, sb, row_b, M, N,
-                                                                          K, out, ld_out, tiles_m, tiles_n);
+    int64_t blocks[2] = {0, 0};
+    auto problem = [&](const GemmOperands& g, int64_t* nb) {
+        const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
+        *nb = ((int64_t)tiles_m * tiles_n + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
+        return TnProblem{g.a, g.lda, g.b, g.ldb, g.scale_a, g.scale_b, (int)g.M, (int)g.N, (int)g.K, g.out, g.ld_out, tiles_m, tiles_n};
+    };
+    const TnProblem p1 = problem(g1, &blocks[0]);
+    const TnProblem p2 = g2 ? problem(*g2, &blocks[1]) : p1;
+    if (blocks[0] + blocks[1] > 0x7FFFFFF0) return hipErrorInvalidValue;
+    kern<<<dim3((unsigned)(blocks[0] + blocks[1])), dim3(WAVES_M * WAVES_N * 64), lds, st>>>(
+        p1, row_a, row_b, g2 ? (int)blocks[0] : ONE_PROBLEM, p2);
     return hipGetLastError();
 }
 
 template <int FA, int FB, bool OUT_F32>
-static hipError_t launch_fmt(int variant, const uint8_t* a, int64_t lda, const float* sa, int row_a,
-                             const uint8_t* b, int64_t ldb, const float* sb, int row_b, int M, int N, int K,
-                             void* out, int64_t ld_out, hipStream_t st) {
-    if (variant == 6)
-        return launch_variant<64, 64, 4, 1, FA, FB, OUT_F32, 4>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
-    if (variant == 7)
-        return launch_variant<128, 128, 2, 2, FA, FB, OUT_F32, 3>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
-    return launch_variant<128, 128, 2, 2, FA, FB, OUT_F32>(a, lda, sa, row_a, b, ldb, sb, row_b, M, N, K, out, ld_out, st);
+static hipError_t launch_fmt(int variant, const GemmOperands& g1, const GemmOperands* g2, int row_a, int row_b, hipStream_t st) {
+    if (variant == 6) return launch_variant<64, 64, 4, 1, FA, FB, OUT_F32, 4>(g1, g2, row_a, row_b, st);
+    if (variant == 7) return launch_variant<128, 128, 2, 2, FA, FB, OUT_F32, 3>(g1, g2, row_a, row_b, st);
+    return launch_variant<128, 128, 2, 2, FA, FB, OUT_F32>(g1, g2, row_a, row_b, st);
 }
 
 // Kernel choice: the few-row kernel of gemm_fp8_skinny.hip (variant 5) for
 // M <= 32 (measured 2-7x faster there; from 33 to 64 rows its loads of A
-// through the L1 cache cost as much as the tiled kernels' padding); otherwise the 16x16x128 "snake" kernel (variant 4,
-// gemm_fp8_snake.hip) as soon as its 256 x 256 tiles keep more than a quarter
-// of the CUs busy (measured: equal to the 128 x 128 tile of this file at 64
-// tiles, 10-80 % faster from 96 tiles on), and 128 x 128 or 64 x 64 tiles (more
-// workgroups) below that.  The switch GEMM_VARIANT overrides (tuning and
-// test aid): 0 = 128x128 / 4 waves (register-staged; also the fallback where the
-// 32-bit offsets of the others do not reach), 4 = snake, 5 = few-row kernel (only
-// where M <= 64), 6 = 64x64 / 4 waves with loads 4 steps ahead, 7 = 128x128 / 4
-// waves with loads 3 steps ahead (both register-staged through buffer loads).
+// through the L1 cache cost as much as the tiled kernels' padding); otherwise by the number of 128 x 128 tiles of
+// the output: up to 128 of them 64 x 64 tiles, up to 256 of them 128 x 128 tiles, beyond that the 256 x 256 kernels
+// of gemm_fp8_snake.hip / gemm_fp8_stream.hip (variant 4).
+// Measured per product, ten in a HIP graph, K = 1024 / 4096 / 16384 (us):
+//      64 tiles (1024 x 1024):   64x64  8.1 / 15.3 /   -     128x128 13.5 / 29.5 /   -     256x256 10.5 / 24.5 /   -
+//     128 tiles (1024 x 2048):         10.1 / 22.0 /   -             13.9 / 30.7 /   -             10.8 / 31.3 /   -
+//     192 tiles (1536 x 2048):         13.2 / 27.3 /  86             14.2 / 30.8 /  95             10.8 / 31.3 / 103
+//     256 tiles (2048 x 2048):         16.2 / 35.1 / 114             14.6 / 31.4 /  95             10.8 / 31.4 / 104
+//     384 tiles (2048 x 3072):         22.3 / 48.4 / 163             26.8 / 58.6 / 186             10.8 / 31.8 / 105
+//     512 tiles (2048 x 4096):         29.1 / 62.1 / 215             27.8 / 59.6 / 188             12.0 / 34.1 / 112
+// With few tiles the K loop of a lone workgroup per CU is bound by the latency of its loads, about 1 us per step
+// whatever the tile, so more and smaller tiles finish sooner; once every CU has a workgroup the time of the small
+// tiles grows with the work, while sixty-four 256 x 256 tiles still take what one takes.  At 129-256 tiles the
+// 128 x 128 tiles are kept although the table favours the large ones for short contractions: inside whole
+// forward + backward steps they came out ahead (3-6 us per step at 1024 x 1024 x 4096 and 4096 x 1024 x 1024), and
+// the two products of a backward step can then share one launch (launch_gemm_fp8_pair), which in steps of
+// 4096 x 1024 x 4096 and five other shapes of that class saved 22-65 us (13-15 %).
+// Switches (tuning and test aid): GEMM_BIG_FROM moves the tile count from which the 256 x 256 kernels are used;
+// GEMM_VARIANT forces a kernel: 0 = 128x128 / 4 waves (register-staged; also the fallback where the 32-bit
+// offsets of the others do not reach), 4 = 256 x 256, 5 = few-row kernel (only where M <= 64), 6 = 64x64 / 4 waves
+// with loads 4 steps ahead, 7 = 128x128 / 4 waves with loads 3 steps ahead (both register-staged through buffer loads).
 static int pick_variant(int64_t M, int64_t N) {
     if (const int v = knob(KNOB_GEMM_VARIANT); v == 0 || (v >= 4 && v <= 7)) return v;
     if (M <= 32) return 5;
-    const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
-    if (tiles256 > 64) return 4;
-    // few tiles: the K loop of a lone workgroup per CU is bound by the latency of its loads (about 1 us per
-    // step whatever the tile), so more, smaller tiles finish sooner (64 x 64: 1.3-1.9x faster up to 128 tiles
-    // of 128 x 128, equal at 256)
     const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128);
+    const int big = knob(KNOB_GEMM_BIG_FROM);
+    if (tiles128 >= (big > 0 ? big : 257)) return 4;
     return tiles128 <= 128 ? 6 : 7;   // (launch_gemm_fp8 falls back to 0 where their 32-bit offsets do not reach)
 }
 
@@ -321,11 +348,35 @@ hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float
         return launch_gemm_fp8_snake(a, lda, fmt_a, scale_a, row_a, b, ldb, fmt_b, scale_b, row_b, M, N, K, out, ld_out,
                                      out_f32, st);
     if (v == 4 || v == 5) v = 0;
-    const int m = (int)M, n = (int)N, k = (int)K;
-#define FP8K_GEMM(FA_, FB_)                                                                                     \
-    if (fmt_a == FA_ && fmt_b == FB_)                                                                           \
-        return out_f32 ? launch_fmt<FA_, FB_, true>(v, a, lda, scale_a, row_a, b, ldb, scale_b, row_b, m, n, k, out, ld_out, st) \
-                       : launch_fmt<FA_, FB_, false>(v, a, lda, scale_a, row_a, b, ldb, scale_b, row_b, m, n, k, out, ld_out, st)
+    const GemmOperands g{a, lda, scale_a, b, ldb, scale_b, M, N, K, out, ld_out};
+#define FP8K_GEMM(FA_, FB_)                                                                    \
+    if (fmt_a == FA_ && fmt_b == FB_)                                                          \
+        return out_f32 ? launch_fmt<FA_, FB_, true>(v, g, nullptr, row_a, row_b, st)          \
+                       : launch_fmt<FA_, FB_, false>(v, g, nullptr, row_a, row_b, st)
+    FP8K_GEMM(FMT_E4M3FN, FMT_E4M3FN);
+    FP8K_GEMM(FMT_E5M2, FMT_E4M3FN);
+    FP8K_GEMM(FMT_E4M3FN, FMT_E5M2);
+    FP8K_GEMM(FMT_E5M2, FMT_E5M2);
+#undef FP8K_GEMM
+    return hipErrorInvalidValue;
+}
+
+// Two products of the same formats and kinds of scale (bfloat16 results) in ONE launch, for the pair dX, dW of a
+// backward step whose products are too small to fill the chip one at a time.  hipErrorNotSupported (nothing
+// launched) where either is large enough for the 256 x 256 kernels, has few rows, or the two would take different
+// tiles: the caller then launches them one after the other.
+hipError_t launch_gemm_fp8_pair(const GemmOperands& g1, const GemmOperands& g2, int fmt_a, int fmt_b, int row_a, int row_b,
+                                hipStream_t st) {
+    if (g1.M == 0 || g1.N == 0 || g2.M == 0 || g2.N == 0) return hipErrorNotSupported;
+    const int v1 = pick_variant(g1.M, g1.N), v2 = pick_variant(g2.M, g2.N);
+    if ((v1 != 6 && v1 != 7) || v1 != v2) return hipErrorNotSupported;
+    auto reach = [](const GemmOperands& g) {
+        return (g.M + 128) * g.lda + g.K < (int64_t)1 << 31 && (g.N + 128) * g.ldb + g.K < (int64_t)1 << 31;
+    };
+    if (!reach(g1) || !reach(g2)) return hipErrorNotSupported;
+    const int v = v1;   // (a product with few tiles and a long contraction, sharing a launch on the larger tile of the other, took 2-3x longer)
+#define FP8K_GEMM(FA_, FB_) \
+    if (fmt_a == FA_ && fmt_b == FB_) return launch_fmt<FA_, FB_, false>(v, g1, &g2, row_a, row_b, st)
     FP8K_GEMM(FMT_E4M3FN, FMT_E4M3FN);
     FP8K_GEMM(FMT_E5M2, FMT_E4M3FN);
     FP8K_GEMM(FMT_E4M3FN, FMT_E5M2);

@@ -49,6 +49,15 @@ hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float
                            const uint8_t* b, int64_t ldb, int fmt_b, const float* scale_b, int row_b,
                            int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
                            hipStream_t st);
+// one scaled product out[M, N] = A[M, K] . B[N, K]^T / (scale_a * scale_b), operands as for launch_gemm_fp8
+struct GemmOperands {
+    const uint8_t* a; int64_t lda; const float* scale_a;
+    const uint8_t* b; int64_t ldb; const float* scale_b;
+    int64_t M, N, K; void* out; int64_t ld_out;
+};
+// two small products (bfloat16 results) in one launch; hipErrorNotSupported, with nothing launched, where that does not pay
+hipError_t launch_gemm_fp8_pair(const GemmOperands& g1, const GemmOperands& g2, int fmt_a, int fmt_b, int row_a, int row_b,
+                                hipStream_t st);
 
 // Rowwise quantization (codes q, scales scale_out) and the per-column scales
 // scale_cols[c] = scale(max_r |x[r, c]|) from a single read of x; scratch holds
@@ -56,6 +65,37 @@ hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float
 hipError_t launch_quant_row_colmax(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, int flags,
                                    uint8_t* q, int64_t ld_out, float* scale_out, float* scale_cols, void* scratch,
                                    size_t scratch_bytes, hipStream_t st);
+
+// Paired launches: the quantizations of a linear layer come in twos and threes of the same kind; these issue them as
+// twin launches (one grid, two problems) with one second-level launch for all column scales.  Results are those of the
+// single-tensor functions.  hipErrorNotSupported (nothing launched): a tensor does not suit - quantize one by one.
+// fold (optional): quant_fold_bytes(rows, cols) bytes of side storage, 256-byte aligned, for the first-level column
+// maxima.  With it the transposing cast derives the column scales itself (one launch less); without it, or where
+// quant_fold_bytes is 0, the maxima are parked in the transposed output and a second-level launch reduces them.
+constexpr int64_t FOLD_ROWS = 256;
+int64_t quant_fold_bytes(int64_t rows, int64_t cols);
+struct RowColOperand {      // a tensor [rows, cols] quantized per row (q_row, scale_row) and per column, transposed (q_col_t [cols, rows], scale_col)
+    const void* x; int64_t rows, ld;
+    uint8_t* q_row; int64_t ld_row; float* scale_row;
+    uint8_t* q_col_t; int64_t ld_col_t; float* scale_col;
+    void* fold = nullptr;
+};
+struct ColOperand {         // a tensor [rows, cols] quantized per column, transposed
+    const void* x; int64_t rows, ld;
+    uint8_t* q_col_t; int64_t ld_col_t; float* scale_col;
+    void* fold = nullptr;
+};
+// two tensors of the same width and format, rowwise: one launch
+hipError_t launch_quant_row_pair(const void* x1, int64_t rows1, int64_t ld1, uint8_t* q1, int64_t ld_q1, float* s1, const void* x2,
+                                 int64_t rows2, int64_t ld2, uint8_t* q2, int64_t ld_q2, float* s2, int64_t cols, int fmt,
+                                 int flags, hipStream_t st);
+// one tensor (b == nullptr) or two of the same width and format along both axes: three launches, two with folding
+hipError_t launch_quant_row_col_pair(const RowColOperand& a, const RowColOperand* b, int64_t cols, int fmt, int flags, hipStream_t st);
+// two tensors of the same width and format per column, transposed: three launches (instead of six)
+hipError_t launch_quant_col_t_pair(const ColOperand& a, const ColOperand& b, int64_t cols, int fmt, int flags, hipStream_t st);
+// the backward of the rowwise recipe: the gradient g along both axes, W and X per column: five launches (instead of nine), four with folding
+hipError_t launch_quant_bwd_rowwise(const RowColOperand& g, int64_t cols_g, int fmt_g, const ColOperand& w, const ColOperand& x,
+                                    int64_t cols_wx, int fmt_wx, int flags, hipStream_t st);
 
 // 256 x 256 kernel on 16x16x128 MFMAs with LDS-DMA loads and the four-phase "snake" schedule; same contract.
 // _fits: its 32-bit buffer offsets reach (leading dimensions below 2^23)

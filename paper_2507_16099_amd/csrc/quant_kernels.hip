@@ -10,6 +10,13 @@
 
 namespace fp8k {
 
+// Twin launches.  Several kernels below take a second problem of the same kind after their ordinary arguments
+// (x2, rows2, ...): blocks [0, split) work on the first, blocks [split, gridDim.x) on the second.  A linear layer
+// quantizes two or three tensors the same way back to back (X and W; dY, W and X); for small layers the ~5 us that
+// every dependent launch costs on the stream is what the step costs, so the launchers pair them up.
+constexpr int NO_TWIN = 0x7FFFFFFF;
+
+
 // ---------------------------------------------------------------- fill
 __global__ void fill_u32_kernel(uint32_t* p, int64_t n, uint32_t v) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -198,14 +205,19 @@ __global__ __launch_bounds__(AMAX_COLS_WAVES * 64) void amax_cols_kernel(const u
 template <int NV>
 __global__ __launch_bounds__(256) void colmax_partial_kernel(const uint16_t* __restrict__ x, int64_t rows,
                                                               int64_t cols, int64_t ld,
-                                                              uint16_t* __restrict__ part, int64_t ld_part) {
+                                                              uint16_t* __restrict__ part, int64_t ld_part,
+                                                              int split = NO_TWIN, const uint16_t* __restrict__ x2 = nullptr,
+                                                              int64_t rows2 = 0, int64_t ld2 = 0,
+                                                              uint16_t* __restrict__ part2 = nullptr) {
+    int bid = blockIdx.x, nb = split == NO_TWIN ? (int)gridDim.x : split;
+    if (bid >= split) { bid -= split; nb = (int)gridDim.x - split; x = x2; rows = rows2; ld = ld2; part = part2; }
     const int64_t nvec = cols >> 3;
     const int ntail = (int)(cols & 7);
     uint4 acc[NV];
 #pragma unroll
     for (int j = 0; j < NV; ++j) acc[j] = make_uint4(0, 0, 0, 0);
     uint32_t tail = 0;
-    for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
+    for (int64_t r = bid; r < rows; r += nb) {
         const uint16_t* row = x + r * ld;
         const uint4* rv = reinterpret_cast<const uint4*>(row);
         uint4 v[NV];
@@ -223,7 +235,7 @@ __global__ __launch_bounds__(256) void colmax_partial_kernel(const uint16_t* __r
             acc[j].w = pk_absmax(acc[j].w, v[j].w);
         }
     }
-    uint16_t* prow = part + (int64_t)blockIdx.x * ld_part;
+    uint16_t* prow = part + (int64_t)bid * ld_part;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
         const int64_t vi = threadIdx.x + (int64_t)j * 256;
@@ -243,10 +255,19 @@ __global__ __launch_bounds__(256) void colmax_partial_kernel(const uint16_t* __r
 template <int CL>
 __global__ __launch_bounds__(1024) void colmax_final_scale_kernel(const uint16_t* __restrict__ part, int G,
                                                                    int64_t cols, int64_t ld_part, int fmt, int flags,
-                                                                   float* __restrict__ scale_out) {
+                                                                   float* __restrict__ scale_out,
+                                                                   int split = NO_TWIN, const uint16_t* __restrict__ part2 = nullptr,
+                                                                   int G2 = 0, int64_t cols2 = 0, int64_t ld_part2 = 0, int fmt2 = 0,
+                                                                   float* __restrict__ scale_out2 = nullptr,
+                                                                   int split3 = NO_TWIN, const uint16_t* __restrict__ part3 = nullptr,
+                                                                   int G3 = 0, int64_t cols3 = 0, int64_t ld_part3 = 0, int fmt3 = 0,
+                                                                   float* __restrict__ scale_out3 = nullptr) {
     constexpr int RG = 1024 / CL;   // row groups
     const int tid = threadIdx.x, cl = tid % CL, rg = tid / CL;
-    const int64_t c = (int64_t)blockIdx.x * (CL * 8) + cl * 8;
+    int bid = blockIdx.x;
+    if (bid >= split3) { bid -= split3; part = part3; G = G3; cols = cols3; ld_part = ld_part3; fmt = fmt3; scale_out = scale_out3; }
+    else if (bid >= split) { bid -= split; part = part2; G = G2; cols = cols2; ld_part = ld_part2; fmt = fmt2; scale_out = scale_out2; }
+    const int64_t c = (int64_t)bid * (CL * 8) + cl * 8;
     uint4 acc = make_uint4(0, 0, 0, 0);
     if (c < cols) {
         const uint16_t* p = part + c;
@@ -458,7 +479,8 @@ __device__ __forceinline__ void transpose4x4_bytes(uint32_t a, uint32_t b, uint3
 // 2 * ((row / 8) & 7) so that a wavefront's column pieces spread over banks.
 // ACT: the tensor to cast is x * y * (1 - y) (gradient through a stored sigmoid output y of the same shape and
 // leading dimension, cols a multiple of 8), formed on the fly.
-template <int FMT, int GRAN, int TR, bool ACT = false>
+// FOLD (per-column scales only): the scales may come from first-level column maxima, see below.
+template <int FMT, int GRAN, int TR, bool ACT = false, bool FOLD = false>
 __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __restrict__ x, int64_t rows,
                                                               int64_t cols, int64_t ld,
                                                               const float* __restrict__ scale,
@@ -466,7 +488,18 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
                                                               uint8_t* __restrict__ q_plain, int64_t ld_plain,
                                                               int nx, int ny, const uint16_t* __restrict__ yact = nullptr,
                                                               int n_part = 0, int sflags = 0,
-                                                              float* __restrict__ scale_out = nullptr) {
+                                                              float* __restrict__ scale_out = nullptr,
+                                                              int split = NO_TWIN, const uint16_t* __restrict__ x2 = nullptr,
+                                                              int64_t rows2 = 0, int64_t ld2 = 0,
+                                                              const float* __restrict__ scale2 = nullptr,
+                                                              uint8_t* __restrict__ qt2 = nullptr, int64_t ld_t2 = 0, int nx2 = 0,
+                                                              int64_t ld_part = 0, int n_part2 = 0,
+                                                              float* __restrict__ scale_out2 = nullptr) {
+    int bid = blockIdx.x;
+    if (bid >= split) {
+        bid -= split; x = x2; rows = rows2; ld = ld2; scale = scale2; qt = qt2; ld_t = ld_t2; nx = nx2;
+        n_part = n_part2; scale_out = scale_out2;
+    }
     constexpr int SLOTS = TR / 8;   // 8-byte slots per output row
     constexpr int PARTS = TR / 16;  // 16-byte parts per output row
     __shared__ __attribute__((aligned(16))) uint2 tile[128 * SLOTS];
@@ -476,7 +509,7 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
     // 2 KB runs of the output rows, instead of isolated 256-byte / 128-byte pieces
     constexpr int PX = 16, PY = 16;
     const int pxc = (nx + PX - 1) / PX;
-    const int patch = blockIdx.x / (PX * PY), within = blockIdx.x % (PX * PY);
+    const int patch = bid / (PX * PY), within = bid % (PX * PY);
     const int bx = (patch % pxc) * PX + within % PX, by = (patch / pxc) * PY + within / PX;
     if (bx >= nx || by >= ny) return;
     const int64_t r0 = (int64_t)bx * TR, c0 = (int64_t)by * 128;
@@ -488,8 +521,10 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
         if (n_part == 0) s_t = scale[0];
     }
     if constexpr (GRAN == GRAN_COL) {
+        if (!FOLD || n_part == 0) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) s_col[e] = (c + e < cols) ? scale[c + e] : 0.0f;
+            for (int e = 0; e < 8; ++e) s_col[e] = (c + e < cols) ? scale[c + e] : 0.0f;
+        }
     }
 
 #pragma unroll
@@ -500,7 +535,13 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
         for (int j = 0; j < 8; ++j) {
             const int64_t r = r0 + rh * 128 + ty * 8 + j;
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (r < rows) {
+            if constexpr (FOLD) {
+                // (cols is a multiple of 8 here.)  Unconditional loads from clamped addresses: all eight, and the
+                // maxima after them, are in flight together whatever the compiler makes of the tile's edges
+                const bool in = r < rows && c < cols;
+                v = load_stream(x + (r < rows ? r : rows - 1) * ld + (c < cols ? c : 0));
+                if (!in) v = make_uint4(0, 0, 0, 0);
+            } else if (r < rows) {
                 const uint16_t* src = x + r * ld + c;
                 if (c + 8 <= cols) {
                     v = load_stream(src);
@@ -517,7 +558,50 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
             // n_part > 0: scale points at the per-block maxima of the amax pass instead of at the scale; the
             // scale is derived here, behind the tile's loads, so that its latency hides under them
             if (rh == 0 && n_part > 0)
-                s_t = tensor_scale_from_partials<FMT>(scale, n_part, sflags, threadIdx.x, blockIdx.x == 0, scale_out);
+                s_t = tensor_scale_from_partials<FMT>(scale, n_part, sflags, threadIdx.x, blockIdx.x == 0, scale_out);   // (never a twin launch)
+        }
+        if constexpr (GRAN == GRAN_COL) {
+            // n_part > 0: scale points at n_part rows (leading dimension ld_part) of first-level column maxima,
+            // bfloat16 magnitudes; the block folds those of its 128 columns behind the tile's loads and the
+            // blocks of the first row of tiles publish the scales.  Same maxima and scales as
+            // colmax_final_scale_kernel, without its launch.
+            if (FOLD && rh == 0 && n_part > 0) {
+                __shared__ uint4 colred[16][16];
+                const uint16_t* part = reinterpret_cast<const uint16_t*>(scale);
+                uint4 acc = make_uint4(0, 0, 0, 0);
+                for (int g0 = 0; g0 < n_part; g0 += 256) {   // (one trip: the launchers keep n_part <= 256)
+                    uint4 pv[16];                            // sixteen rows of maxima per thread, all requested at once
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {   // (a row read twice does not change a maximum)
+                        const int g = g0 + ty + 16 * i;
+                        pv[i] = *reinterpret_cast<const uint4*>(part + (int64_t)(g < n_part ? g : n_part - 1) * ld_part + (c < cols ? c : 0));
+                    }
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        acc.x = pk_absmax(acc.x, pv[i].x);
+                        acc.y = pk_absmax(acc.y, pv[i].y);
+                        acc.z = pk_absmax(acc.z, pv[i].z);
+                        acc.w = pk_absmax(acc.w, pv[i].w);
+                    }
+                }
+                colred[ty][tx] = acc;
+                __syncthreads();
+#pragma unroll
+                for (int w = 0; w < 16; ++w) {
+                    const uint4 o = colred[w][tx];
+                    acc.x = pk_absmax(acc.x, o.x);
+                    acc.y = pk_absmax(acc.y, o.y);
+                    acc.z = pk_absmax(acc.z, o.z);
+                    acc.w = pk_absmax(acc.w, o.w);
+                }
+                const uint32_t wds[4] = {acc.x, acc.y, acc.z, acc.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t mag = (wds[e >> 1] >> ((e & 1) * 16)) & 0x7FFFu;
+                    s_col[e] = (c + e < cols) ? scale_from_amax(mag_to_float(mag), FMT, sflags) : 0.0f;
+                    if (bx == 0 && ty == 0 && c + e < cols) scale_out[c + e] = s_col[e];
+                }
+            }
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -645,10 +729,15 @@ hipError_t launch_cast(const void* x, int64_t rows, int64_t cols, int64_t ld, co
 template <int FMT, int TX, int NV>
 __global__ __launch_bounds__(256) void quant_row_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
                                                          int64_t ld, int flags, uint8_t* __restrict__ q,
-                                                         int64_t ld_out, float* __restrict__ scale_out) {
+                                                         int64_t ld_out, float* __restrict__ scale_out,
+                                                         int split = NO_TWIN, const uint16_t* __restrict__ x2 = nullptr,
+                                                         int64_t rows2 = 0, int64_t ld2 = 0, uint8_t* __restrict__ q2 = nullptr,
+                                                         int64_t ld_out2 = 0, float* __restrict__ scale_out2 = nullptr) {
     constexpr int TY = 256 / TX;
     const int tx = threadIdx.x % TX, ty = threadIdx.x / TX;
-    const int64_t r = (int64_t)blockIdx.x * TY + ty;
+    int bid = blockIdx.x;
+    if (bid >= split) { bid -= split; x = x2; rows = rows2; ld = ld2; q = q2; ld_out = ld_out2; scale_out = scale_out2; }
+    const int64_t r = (int64_t)bid * TY + ty;
     const bool live = r < rows;
     const int64_t nvec = cols >> 3;
     const int ntail = (int)(cols & 7);
@@ -736,11 +825,13 @@ hipError_t launch_quant_row(const void* x, int64_t rows, int64_t cols, int64_t l
 // maxima of its own 8 * NV columns.  The block's column maxima go to row b of
 // a [G, cols] matrix of bfloat16 magnitudes, which amax_cols_kernel reduces;
 // the per-column cast then reads the tensor a second (and last) time.
-// With up to four vectors per thread the next row is requested before the
-// current one is reduced; wider rows rely on the other resident blocks to keep
-// loads in flight (a second row in registers would halve the occupancy).  The
-// per-row wave maxima alternate between two LDS slots, so one barrier per row
-// is enough.
+// With up to four vectors per thread the next rows are requested before the
+// current ones are reduced; wider rows rely on the other resident blocks to keep
+// loads in flight (a second row in registers would halve the occupancy).  Rows
+// of up to 2048 (4096) elements travel four (two) at a time: a block of a small
+// tensor has only a handful of rows, and each trip to memory that it has to
+// wait for costs about a microsecond.  The wave maxima alternate between two
+// LDS slots, so one barrier per trip is enough.
 // ACT: the tensor to quantize is dz = x * y * (1 - y), formed on the fly from the gradient x and the stored
 // sigmoid output y (same shape and leading dimension): the backward through Sigmoid + Linear never
 // materialises dz.
@@ -750,73 +841,100 @@ __global__ __launch_bounds__(256) void quant_row_colmax_kernel(const uint16_t* _
                                                                 uint8_t* __restrict__ q, int64_t ld_out,
                                                                 float* __restrict__ scale_out,
                                                                 uint16_t* __restrict__ part, int64_t ld_part,
-                                                                const uint16_t* __restrict__ yact = nullptr) {
+                                                                const uint16_t* __restrict__ yact = nullptr,
+                                                                int split = NO_TWIN, const uint16_t* __restrict__ x2 = nullptr,
+                                                                int64_t rows2 = 0, int64_t ld2 = 0, uint8_t* __restrict__ q2 = nullptr,
+                                                                int64_t ld_out2 = 0, float* __restrict__ scale_out2 = nullptr,
+                                                                uint16_t* __restrict__ part2 = nullptr) {
     constexpr bool PREFETCH = NV <= 4;
+    constexpr int R = NV == 1 ? 4 : NV == 2 ? 2 : 1;   // rows in flight together (narrow rows: one round trip to memory serves R rows)
+    int bid = blockIdx.x, nb = split == NO_TWIN ? (int)gridDim.x : split;
+    if (bid >= split) {
+        bid -= split; nb = (int)gridDim.x - split;
+        x = x2; rows = rows2; ld = ld2; q = q2; ld_out = ld_out2; scale_out = scale_out2; part = part2;
+    }
     const int64_t nvec = cols >> 3;     // cols is a multiple of 8 (checked by the launcher)
     const int tid = threadIdx.x;
-    __shared__ uint32_t red[2][4];
-    uint4 cmax[NV], v[NV];
+    __shared__ uint32_t red[2][R][4];
+    uint4 cmax[NV], v[R][NV];
 #pragma unroll
     for (int j = 0; j < NV; ++j) cmax[j] = make_uint4(0, 0, 0, 0);
-    auto load_row = [&](int64_t r, uint4 (&dst)[NV]) {
-        const uint4* rv = reinterpret_cast<const uint4*>(x + r * ld);
+    // rows r0, r0 + nb, ..., r0 + (R - 1) nb; zeros for rows beyond the end
+    auto load_rows = [&](int64_t r0, uint4 (&dst)[R][NV]) {
 #pragma unroll
-        for (int j = 0; j < NV; ++j) {
-            const int64_t vi = tid + (int64_t)j * 256;
-            dst[j] = vi < nvec ? rv[vi] : make_uint4(0, 0, 0, 0);
-        }
-        if constexpr (ACT) {
-            const uint4* yv = reinterpret_cast<const uint4*>(yact + r * ld);
+        for (int k = 0; k < R; ++k) {
+            const int64_t r = r0 + (int64_t)k * nb;
+            const bool in = r < rows;
+            const uint4* rv = reinterpret_cast<const uint4*>(x + (in ? r : 0) * ld);
 #pragma unroll
             for (int j = 0; j < NV; ++j) {
                 const int64_t vi = tid + (int64_t)j * 256;
-                if (vi < nvec) dst[j] = sigmoid_bwd8(dst[j], yv[vi]);
+                dst[k][j] = (in && vi < nvec) ? rv[vi] : make_uint4(0, 0, 0, 0);
+            }
+            if constexpr (ACT) {
+                const uint4* yv = reinterpret_cast<const uint4*>(yact + (in ? r : 0) * ld);
+#pragma unroll
+                for (int j = 0; j < NV; ++j) {
+                    const int64_t vi = tid + (int64_t)j * 256;
+                    if (in && vi < nvec) dst[k][j] = sigmoid_bwd8(dst[k][j], yv[vi]);
+                }
             }
         }
     };
-    int64_t r = blockIdx.x;
-    if (PREFETCH && r < rows) load_row(r, v);
+    const int64_t stride = (int64_t)R * nb;
+    int64_t r = bid;
+    if (PREFETCH && r < rows) load_rows(r, v);
     int slot = 0;
-    for (; r < rows; r += gridDim.x) {
-        const int64_t rn = r + gridDim.x;
-        uint4 nv[PREFETCH ? NV : 1];
+    for (; r < rows; r += stride) {
+        const int64_t rn = r + stride;
+        uint4 nv[PREFETCH ? R : 1][PREFETCH ? NV : 1];
         if constexpr (PREFETCH) {
-            if (rn < rows) load_row(rn, nv);
+            if (rn < rows) load_rows(rn, nv);
         } else {
-            load_row(r, v);
+            load_rows(r, v);
         }
-        uint32_t acc = 0;
 #pragma unroll
-        for (int j = 0; j < NV; ++j) {
-            cmax[j].x = pk_absmax(cmax[j].x, v[j].x);
-            cmax[j].y = pk_absmax(cmax[j].y, v[j].y);
-            cmax[j].z = pk_absmax(cmax[j].z, v[j].z);
-            cmax[j].w = pk_absmax(cmax[j].w, v[j].w);
-            acc = pk_absmax4(acc, v[j]);
+        for (int k = 0; k < R; ++k) {
+            uint32_t acc = 0;
+#pragma unroll
+            for (int j = 0; j < NV; ++j) {
+                cmax[j].x = pk_absmax(cmax[j].x, v[k][j].x);
+                cmax[j].y = pk_absmax(cmax[j].y, v[k][j].y);
+                cmax[j].z = pk_absmax(cmax[j].z, v[k][j].z);
+                cmax[j].w = pk_absmax(cmax[j].w, v[k][j].w);
+                acc = pk_absmax4(acc, v[k][j]);
+            }
+            const uint32_t m = wave_max_u32<64>(pk_fold(acc));
+            if ((tid & 63) == 0) red[slot][k][tid >> 6] = m;
         }
-        uint32_t m = wave_max_u32<64>(pk_fold(acc));
-        if ((tid & 63) == 0) red[slot][tid >> 6] = m;
         __syncthreads();
-        m = red[slot][0];
 #pragma unroll
-        for (int i = 1; i < 4; ++i) m = red[slot][i] > m ? red[slot][i] : m;
-        slot ^= 1;
-        const float s = scale_from_amax(mag_to_float(m), FMT, flags);
-        if (tid == 0) scale_out[r] = s;
-        uint8_t* dst = q + r * ld_out;
+        for (int k = 0; k < R; ++k) {
+            const int64_t rk = r + (int64_t)k * nb;
+            if (rk >= rows) break;
+            uint32_t m = red[slot][k][0];
 #pragma unroll
-        for (int j = 0; j < NV; ++j) {
-            const int64_t vi = tid + (int64_t)j * 256;
-            if (vi < nvec) store_stream(reinterpret_cast<uint2*>(dst) + vi, cast8<FMT>(v[j], s));
+            for (int i = 1; i < 4; ++i) m = red[slot][k][i] > m ? red[slot][k][i] : m;
+            const float s = scale_from_amax(mag_to_float(m), FMT, flags);
+            if (tid == 0) scale_out[rk] = s;
+            uint8_t* dst = q + rk * ld_out;
+#pragma unroll
+            for (int j = 0; j < NV; ++j) {
+                const int64_t vi = tid + (int64_t)j * 256;
+                if (vi < nvec) store_stream(reinterpret_cast<uint2*>(dst) + vi, cast8<FMT>(v[k][j], s));
+            }
         }
+        slot ^= 1;
         if constexpr (PREFETCH) {
             if (rn < rows) {
 #pragma unroll
-                for (int j = 0; j < NV; ++j) v[j] = nv[j];
+                for (int k = 0; k < R; ++k)
+#pragma unroll
+                    for (int j = 0; j < NV; ++j) v[k][j] = nv[k][j];
             }
         }
     }
-    uint16_t* prow = part + (int64_t)blockIdx.x * ld_part;
+    uint16_t* prow = part + (int64_t)bid * ld_part;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
         const int64_t vi = tid + (int64_t)j * 256;
@@ -880,6 +998,245 @@ hipError_t launch_quant_row_colmax(const void* x, int64_t rows, int64_t cols, in
     return launch_colmax_final_scale(part, G, cols, ld_part, fmt, flags, scale_cols, st);
 }
 
+
+// ------------------------------------------------------------------ paired launches
+// The quantizations of a linear layer come in twos and threes of the same kind.  The functions below issue them as
+// twin launches (see NO_TWIN above) and share one second-level launch for all column scales.  They return
+// hipErrorNotSupported when a tensor does not suit the kernels involved: the caller then quantizes one by one.
+
+// Side storage for first-level column maxima: with it they stay out of the transposed output, so the transposing cast
+// can fold them itself and the second-level launch falls away.  Worth it for small tensors only: every block of the
+// cast reads all the maxima of its 128 columns, and the first level must make do with FOLD_ROWS blocks (measured:
+// 3-8 us less per forward + backward step with tensors of 1024 rows, 3-5 us more with 4096).  0 for the others.
+int64_t quant_fold_bytes(int64_t rows, int64_t cols) {
+    if (rows < 256 || rows > 2048 || cols < 8 || cols % 8 != 0 || rows * cols > ((int64_t)4 << 20)) return 0;
+    return FOLD_ROWS * ((cols + 7) / 8 * 8) * 2;
+}
+
+namespace {
+
+int64_t output_scratch(int64_t out_rows, int64_t out_cols, int64_t ld_out) {   // bytes of a transposed output that may hold partial maxima
+    return ld_out == out_cols ? out_rows * out_cols : out_cols;
+}
+
+// where the first-level maxima of a tensor go: the caller's side storage, if any (the cast then folds them), else the
+// transposed output itself, which the cast overwrites afterwards
+struct Partials { uint16_t* at; int64_t room; bool folded; };
+Partials partials_of(void* fold, int64_t rows, int64_t cols, uint8_t* q_col_t, int64_t ld_col_t) {
+    const int64_t fb = fold ? quant_fold_bytes(rows, cols) : 0;
+    if (fb) return Partials{static_cast<uint16_t*>(fold), fb, true};
+    return Partials{reinterpret_cast<uint16_t*>(q_col_t), output_scratch(cols, rows, ld_col_t), false};
+}
+
+// blocks of quant_row_colmax_kernel for a tensor, given how many the device keeps resident for it (0: not suited)
+int64_t row_colmax_blocks(int64_t rows, int64_t cols, int64_t scratch_bytes, int64_t resident) {
+    int64_t G = resident < 1024 ? resident : 1024;
+    int64_t cap = rows / 8;                       // at least 8 rows per block, but not fewer than 256 blocks while each still has 2 rows
+    if (cap < 256) cap = rows / 2 < 256 ? rows / 2 : 256;
+    if (G > cap) G = cap;
+    if (G * cols * 2 > scratch_bytes) G = scratch_bytes / (cols * 2);
+    return G < 128 ? 0 : G;
+}
+
+// blocks of colmax_partial_kernel for a tensor (0: not suited)
+int64_t colmax_partial_blocks(int64_t rows, int64_t cols, int64_t scratch_bytes) {
+    const int64_t ld_part = (cols + 7) / 8 * 8;
+    int64_t G = 1024;
+    while (G > 64 && (G * ld_part * 2 > scratch_bytes || rows < 4 * G)) G /= 2;
+    if (rows < 4 * G || cols / 8 > 256 * 16 || G * ld_part * 2 > scratch_bytes) return 0;
+    return G;
+}
+
+struct FinalSeg { const uint16_t* part; int64_t G, cols, ld_part; int fmt; float* scale_out; };
+// second level of up to three column-scale problems in one launch (none: no launch)
+hipError_t launch_colmax_final_scale_multi(const FinalSeg* seg, int n, int flags, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    int64_t nb[3] = {0, 0, 0};
+    for (int i = 0; i < n; ++i) nb[i] = (seg[i].cols + 63) / 64;
+    const FinalSeg z{nullptr, 0, 0, 0, 0, nullptr};
+    const FinalSeg &a = seg[0], &b = n > 1 ? seg[1] : z, &c = n > 2 ? seg[2] : z;
+    const int64_t total = nb[0] + nb[1] + nb[2];
+    if (total > 0x7FFFFFFF) return hipErrorInvalidValue;
+    colmax_final_scale_kernel<8><<<dim3((unsigned)total), dim3(1024), 0, st>>>(
+        a.part, (int)a.G, a.cols, a.ld_part, a.fmt, flags, a.scale_out,
+        n > 1 ? (int)nb[0] : NO_TWIN, b.part, (int)b.G, b.cols, b.ld_part, b.fmt, b.scale_out,
+        n > 2 ? (int)(nb[0] + nb[1]) : NO_TWIN, c.part, (int)c.G, c.cols, c.ld_part, c.fmt, c.scale_out);
+    return hipGetLastError();
+}
+
+// Transposing per-column cast of one tensor (b == nullptr) or two of the same width in one launch.  An operand with
+// folded partials (pa / pb .folded, Ga / Gb rows of leading dimension ld_part) derives and publishes its scales itself;
+// the others read scale_col.
+template <int FMT>
+hipError_t cast_t_col(const ColOperand& a, const Partials& pa, int64_t Ga, const ColOperand* b, const Partials& pb, int64_t Gb,
+                      int64_t cols, int64_t ld_part, int flags, hipStream_t st) {
+    const int64_t gx = (cols + 127) / 128;
+    const int64_t gya = (a.rows + 127) / 128, gyb = b ? (b->rows + 127) / 128 : 0;
+    const int64_t ta = ((gya + 15) / 16) * ((gx + 15) / 16) * 256, tb = ((gyb + 15) / 16) * ((gx + 15) / 16) * 256;
+    if (ta + tb > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const float* sa = pa.folded ? reinterpret_cast<const float*>(pa.at) : a.scale_col;
+    const float* sb = !b ? nullptr : pb.folded ? reinterpret_cast<const float*>(pb.at) : b->scale_col;
+    auto kern = pa.folded || (b && pb.folded) ? cast_transpose_kernel<FMT, GRAN_COL, 128, false, true>
+                                              : cast_transpose_kernel<FMT, GRAN_COL, 128, false, false>;
+    kern<<<dim3((unsigned)(ta + tb)), dim3(256), 0, st>>>(
+        static_cast<const uint16_t*>(a.x), a.rows, cols, a.ld, sa, a.q_col_t, a.ld_col_t, nullptr, 0, (int)gya, (int)gx,
+        nullptr, pa.folded ? (int)Ga : 0, flags & 1, a.scale_col,
+        b ? (int)ta : NO_TWIN, b ? static_cast<const uint16_t*>(b->x) : nullptr, b ? b->rows : 0, b ? b->ld : 0, sb,
+        b ? b->q_col_t : nullptr, b ? b->ld_col_t : 0, (int)gyb, ld_part, b && pb.folded ? (int)Gb : 0, b ? b->scale_col : nullptr);
+    return hipGetLastError();
+}
+hipError_t cast_t_col(int fmt, const ColOperand& a, const Partials& pa, int64_t Ga, const ColOperand* b, const Partials& pb,
+                      int64_t Gb, int64_t cols, int64_t ld_part, int flags, hipStream_t st) {
+    return fmt == FMT_E4M3FN ? cast_t_col<FMT_E4M3FN>(a, pa, Ga, b, pb, Gb, cols, ld_part, flags, st)
+                             : cast_t_col<FMT_E5M2>(a, pa, Ga, b, pb, Gb, cols, ld_part, flags, st);
+}
+
+// first level of the column maxima of two tensors of the same width in one launch; Ga, Gb: blocks (rows of partials) of each
+hipError_t colmax_partial_pair(const ColOperand& a, uint16_t* pa, int64_t Ga, const ColOperand& b, uint16_t* pb, int64_t Gb,
+                               int64_t cols, hipStream_t st) {
+    const int64_t nvec = cols / 8, ld_part = (cols + 7) / 8 * 8;
+    const uint16_t *xa = static_cast<const uint16_t*>(a.x), *xb = static_cast<const uint16_t*>(b.x);
+#define FP8K_CPP(NV) colmax_partial_kernel<NV><<<dim3((unsigned)(Ga + Gb)), dim3(256), 0, st>>>(xa, a.rows, cols, a.ld, pa, ld_part, (int)Ga, xb, b.rows, b.ld, pb)
+    if (nvec <= 256) FP8K_CPP(1);
+    else if (nvec <= 512) FP8K_CPP(2);
+    else if (nvec <= 1024) FP8K_CPP(4);
+    else if (nvec <= 2048) FP8K_CPP(8);
+    else FP8K_CPP(16);
+#undef FP8K_CPP
+    return hipGetLastError();
+}
+
+// rowwise codes + first-level column maxima of one tensor (b == nullptr) or two of the same width and format in one
+// launch, the maxima going to pa / pb.  Ga / Gb receive the numbers of blocks = rows of partials; 0 blocks: not suited
+// (nothing launched).
+template <int FMT, int NV>
+hipError_t row_colmax_first_level(const RowColOperand& a, const Partials& pa, const RowColOperand* b, const Partials& pb,
+                                  int64_t cols, int flags, int64_t* Ga, int64_t* Gb, hipStream_t st) {
+    static CachedInt resident_c;
+    const int64_t resident = resident_c.get([] { return resident_blocks(quant_row_colmax_kernel<FMT, NV>); });
+    // two tensors share the resident blocks in proportion to their rows
+    const int64_t ra = b ? resident * a.rows / (a.rows + b->rows) : resident;
+    *Ga = row_colmax_blocks(a.rows, cols, pa.room, ra);
+    *Gb = b ? row_colmax_blocks(b->rows, cols, pb.room, resident - ra) : 0;
+    if (*Ga == 0 || (b && *Gb == 0)) return hipErrorNotSupported;
+    if (b)
+        quant_row_colmax_kernel<FMT, NV><<<dim3((unsigned)(*Ga + *Gb)), dim3(256), 0, st>>>(
+            static_cast<const uint16_t*>(a.x), a.rows, cols, a.ld, flags, a.q_row, a.ld_row, a.scale_row, pa.at, cols, nullptr,
+            (int)*Ga, static_cast<const uint16_t*>(b->x), b->rows, b->ld, b->q_row, b->ld_row, b->scale_row, pb.at);
+    else
+        quant_row_colmax_kernel<FMT, NV><<<dim3((unsigned)*Ga), dim3(256), 0, st>>>(
+            static_cast<const uint16_t*>(a.x), a.rows, cols, a.ld, flags, a.q_row, a.ld_row, a.scale_row, pa.at, cols);
+    return hipGetLastError();
+}
+
+hipError_t row_colmax_first_level(const RowColOperand& a, const Partials& pa, const RowColOperand* b, const Partials& pb,
+                                  int64_t cols, int fmt, int flags, int64_t* Ga, int64_t* Gb, hipStream_t st) {
+    const int64_t nvec = cols / 8;
+    if (cols % 8 != 0 || nvec > 256 * 16 || nvec < 64) return hipErrorNotSupported;
+#define FP8K_RCF(FMT)                                                                                     \
+    if (nvec <= 256) return row_colmax_first_level<FMT, 1>(a, pa, b, pb, cols, flags, Ga, Gb, st);        \
+    if (nvec <= 512) return row_colmax_first_level<FMT, 2>(a, pa, b, pb, cols, flags, Ga, Gb, st);        \
+    if (nvec <= 1024) return row_colmax_first_level<FMT, 4>(a, pa, b, pb, cols, flags, Ga, Gb, st);       \
+    if (nvec <= 2048) return row_colmax_first_level<FMT, 8>(a, pa, b, pb, cols, flags, Ga, Gb, st);       \
+    return row_colmax_first_level<FMT, 16>(a, pa, b, pb, cols, flags, Ga, Gb, st)
+    if (fmt == FMT_E4M3FN) { FP8K_RCF(FMT_E4M3FN); }
+    FP8K_RCF(FMT_E5M2);
+#undef FP8K_RCF
+}
+
+ColOperand col_part(const RowColOperand& o) { return ColOperand{o.x, o.rows, o.ld, o.q_col_t, o.ld_col_t, o.scale_col, o.fold}; }
+Partials partials_of(const RowColOperand& o, int64_t cols) { return partials_of(o.fold, o.rows, cols, o.q_col_t, o.ld_col_t); }
+Partials partials_of(const ColOperand& o, int64_t cols) { return partials_of(o.fold, o.rows, cols, o.q_col_t, o.ld_col_t); }
+
+}  // namespace
+
+hipError_t launch_quant_row_pair(const void* x1, int64_t rows1, int64_t ld1, uint8_t* q1, int64_t ld_q1, float* s1, const void* x2,
+                                 int64_t rows2, int64_t ld2, uint8_t* q2, int64_t ld_q2, float* s2, int64_t cols, int fmt,
+                                 int flags, hipStream_t st) {
+    if (rows1 == 0 || rows2 == 0) return hipErrorNotSupported;
+    const int64_t nvec = cols / 8;
+    const uint16_t *a = static_cast<const uint16_t*>(x1), *b = static_cast<const uint16_t*>(x2);
+#define FP8K_QRP(FMT, TX, NV)                                                                                     \
+    do {                                                                                                          \
+        const int64_t ba = (rows1 + (256 / TX) - 1) / (256 / TX), bb = (rows2 + (256 / TX) - 1) / (256 / TX);     \
+        if (ba + bb > 0x7FFFFFFF) return hipErrorInvalidValue;                                                    \
+        quant_row_kernel<FMT, TX, NV><<<dim3((unsigned)(ba + bb)), dim3(256), 0, st>>>(a, rows1, cols, ld1, flags, q1, ld_q1, s1, \
+                                                                                       (int)ba, b, rows2, ld2, q2, ld_q2, s2); \
+    } while (0)
+#define FP8K_QRP_F(FMT)                          \
+    if (nvec <= 16) FP8K_QRP(FMT, 16, 1);        \
+    else if (nvec <= 64) FP8K_QRP(FMT, 64, 1);   \
+    else if (nvec <= 256) FP8K_QRP(FMT, 256, 1); \
+    else if (nvec <= 512) FP8K_QRP(FMT, 256, 2); \
+    else if (nvec <= 1024) FP8K_QRP(FMT, 256, 4);\
+    else if (nvec <= 2048) FP8K_QRP(FMT, 256, 8);\
+    else if (nvec <= 4096) FP8K_QRP(FMT, 256, 16);\
+    else return hipErrorNotSupported
+    if (fmt == FMT_E4M3FN) { FP8K_QRP_F(FMT_E4M3FN); }
+    else { FP8K_QRP_F(FMT_E5M2); }
+#undef FP8K_QRP_F
+#undef FP8K_QRP
+    return hipGetLastError();
+}
+
+hipError_t launch_quant_row_col_pair(const RowColOperand& a, const RowColOperand* b, int64_t cols, int fmt, int flags,
+                                     hipStream_t st) {
+    if (a.rows == 0 || (b && b->rows == 0) || cols == 0) return hipErrorNotSupported;
+    const Partials pa = partials_of(a, cols), pb = b ? partials_of(*b, cols) : Partials{nullptr, 0, false};
+    int64_t Ga = 0, Gb = 0;
+    hipError_t e = row_colmax_first_level(a, pa, b, pb, cols, fmt, flags, &Ga, &Gb, st);
+    if (e != hipSuccess) return e;
+    FinalSeg seg[2];
+    int n = 0;
+    if (!pa.folded) seg[n++] = FinalSeg{pa.at, Ga, cols, cols, fmt, a.scale_col};
+    if (b && !pb.folded) seg[n++] = FinalSeg{pb.at, Gb, cols, cols, fmt, b->scale_col};
+    e = launch_colmax_final_scale_multi(seg, n, flags, st);
+    if (e != hipSuccess) return e;
+    const ColOperand ca = col_part(a), cb = b ? col_part(*b) : ColOperand{};
+    return cast_t_col(fmt, ca, pa, Ga, b ? &cb : nullptr, pb, Gb, cols, cols, flags, st);
+}
+
+hipError_t launch_quant_col_t_pair(const ColOperand& a, const ColOperand& b, int64_t cols, int fmt, int flags, hipStream_t st) {
+    if (a.rows == 0 || b.rows == 0 || cols == 0) return hipErrorNotSupported;
+    const Partials pa = partials_of(a, cols), pb = partials_of(b, cols);
+    const int64_t Ga = colmax_partial_blocks(a.rows, cols, pa.room), Gb = colmax_partial_blocks(b.rows, cols, pb.room);
+    if (Ga == 0 || Gb == 0) return hipErrorNotSupported;
+    hipError_t e = colmax_partial_pair(a, pa.at, Ga, b, pb.at, Gb, cols, st);
+    if (e != hipSuccess) return e;
+    const int64_t ld_part = (cols + 7) / 8 * 8;
+    FinalSeg seg[2];
+    int n = 0;
+    if (!pa.folded) seg[n++] = FinalSeg{pa.at, Ga, cols, ld_part, fmt, a.scale_col};
+    if (!pb.folded) seg[n++] = FinalSeg{pb.at, Gb, cols, ld_part, fmt, b.scale_col};
+    e = launch_colmax_final_scale_multi(seg, n, flags, st);
+    if (e != hipSuccess) return e;
+    return cast_t_col(fmt, a, pa, Ga, &b, pb, Gb, cols, ld_part, flags, st);
+}
+
+hipError_t launch_quant_bwd_rowwise(const RowColOperand& g, int64_t cols_g, int fmt_g, const ColOperand& w, const ColOperand& x,
+                                    int64_t cols_wx, int fmt_wx, int flags, hipStream_t st) {
+    if (g.rows == 0 || w.rows == 0 || x.rows == 0 || cols_g == 0 || cols_wx == 0) return hipErrorNotSupported;
+    // everything is checked before the first launch, so that "not suited" leaves nothing half done
+    const Partials pg = partials_of(g, cols_g), pw = partials_of(w, cols_wx), px = partials_of(x, cols_wx);
+    const int64_t Gw = colmax_partial_blocks(w.rows, cols_wx, pw.room), Gx = colmax_partial_blocks(x.rows, cols_wx, px.room);
+    if (Gw == 0 || Gx == 0) return hipErrorNotSupported;
+    int64_t Gg = 0, unused = 0;
+    hipError_t e = row_colmax_first_level(g, pg, nullptr, Partials{nullptr, 0, false}, cols_g, fmt_g, flags, &Gg, &unused, st);   // (launches only if suited)
+    if (e != hipSuccess) return e;
+    e = colmax_partial_pair(w, pw.at, Gw, x, px.at, Gx, cols_wx, st);
+    if (e != hipSuccess) return e;
+    const int64_t ld_part = (cols_wx + 7) / 8 * 8;
+    FinalSeg seg[3];
+    int n = 0;
+    if (!pg.folded) seg[n++] = FinalSeg{pg.at, Gg, cols_g, cols_g, fmt_g, g.scale_col};
+    if (!pw.folded) seg[n++] = FinalSeg{pw.at, Gw, cols_wx, ld_part, fmt_wx, w.scale_col};
+    if (!px.folded) seg[n++] = FinalSeg{px.at, Gx, cols_wx, ld_part, fmt_wx, x.scale_col};
+    e = launch_colmax_final_scale_multi(seg, n, flags, st);
+    if (e != hipSuccess) return e;
+    e = cast_t_col(fmt_g, col_part(g), pg, Gg, nullptr, Partials{nullptr, 0, false}, 0, cols_g, cols_g, flags, st);
+    if (e != hipSuccess) return e;
+    return cast_t_col(fmt_wx, w, pw, Gw, &x, px, Gx, cols_wx, ld_part, flags, st);
+}
 
 // The gradient through Sigmoid + Linear, quantized along both axes without materialising
 // dz = dy * y * (1 - y): rowwise codes + scales and per-column scales from one read of (dy, y), then

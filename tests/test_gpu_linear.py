@@ -264,7 +264,10 @@ def test_full_size_outlier_stress_rowwise_vs_tensorwise():
 
 # ------------------------------------------------ fp8 copies of X and W saved by the forward
 
-@pytest.mark.parametrize("M,K,N", [(64, 64, 64), (208, 176, 272), (512, 1024, 768), (1024, 384, 640), (2048, 1024, 256)])
+# (the last three: small tensors whose column scales are derived inside the transposing cast, next to a large one
+# whose scales are not; a width that is not a multiple of 128; two products small enough to share a launch)
+@pytest.mark.parametrize("M,K,N", [(64, 64, 64), (208, 176, 272), (512, 1024, 768), (1024, 384, 640), (2048, 1024, 256),
+                                   (8192, 1024, 512), (1024, 1024, 1024), (2048, 1008, 528)])
 @pytest.mark.parametrize("recipe", ["tensorwise", "tensorwise_pow2", "rowwise", "rowwise_pow2", "rowwise_gw_hp"])
 def test_backward_reuses_the_forward_copies(M, K, N, recipe):
     """FP8_SAVE_FOR_BWD: the copies of X and W that the backward needs are made by
