@@ -94,7 +94,7 @@ def _sweep(torch, fp8, dev, iters: int) -> dict:
     normalisation / activation around it)."""
     rows = []
     sizes = (1024, 2048, 4096, 8192, 16384)
-    for M in (1024, 4096, 16384):
+    for M in (1024, 2048, 4096, 16384):
         for K in sizes:
             for N in sizes:
                 x = torch.randn((M, K), device=dev).to(torch.bfloat16)
@@ -126,6 +126,18 @@ def _sweep(torch, fp8, dev, iters: int) -> dict:
                     gms = _graph_time_ms(fp8_step, iters, torch)
                     entry[f"fp8_{tag}_graph_ms"] = round(gms, 4)
                     entry[f"speedup_{tag}_graph"] = round(entry["bf16_graph_ms"] / gms, 3)
+                # rowwise with the weight gradient from the unquantized tensors on the bf16 matrix cores
+                # (Appendix A, rowwise_gw_hp): where does it beat plain rowwise on this chip?
+                r = fp8.Recipe(gran=fp8.FP8_ROW, flags=fp8.FP8_SAVE_FOR_BWD | fp8.FP8_GRAD_WEIGHT_HP)
+                wh = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, r, True), dtype=torch.uint8, device=dev)
+
+                def gw_hp_step():
+                    fp8.fp8_linear_fwd(x, w, r, y=y, workspace=wh)
+                    fp8.fp8_linear_bwd(dy, x, (N, K), r, dx=dx, dw=dw, workspace=wh)
+                ms = _event_time_ms(gw_hp_step, iters, 2, torch)
+                entry["fp8_rowwise_gw_hp_ms"] = round(ms, 4)
+                entry["speedup_rowwise_gw_hp"] = round(entry["bf16_ms"] / ms, 3)
+                entry["gw_hp_vs_rowwise"] = round(entry["fp8_rowwise_ms"] / ms, 3)   # > 1: the bf16 weight gradient is the faster choice
                 rows.append(entry)
                 del x, w, dy, y, dx, dw
     return {"sweep": "fp8 linear fwd+bwd (quantization included) vs bf16 torch.matmul x3, one MI355X; *_graph_ms: the same step "

@@ -126,7 +126,8 @@ int quantize_row_col_impl(const void* x, int64_t rows, int64_t cols, int64_t ld,
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// part: per-block maxima of the tensorwise amax pass (one tensor at a time: the casts consume them in stream order)
+// part: per-block maxima of the tensorwise amax pass, room for two tensors (a pair shares its launches; otherwise one
+// tensor at a time: the casts consume them in stream order)
 // fold_*: side storage for first-level column maxima of small tensors (rowwise recipe; may be empty)
 struct FwdPlan {
     size_t xq, wq, sx, sw, part, fold_x, fold_w, total;
@@ -143,7 +144,7 @@ FwdPlan plan_fwd(int64_t M, int64_t K, int64_t N, int gran) {
     p.wq = take((size_t)N * K);
     p.sx = take(sizeof(float) * (gran == FP8_ROW ? (size_t)M : 1));
     p.sw = take(sizeof(float) * (gran == FP8_ROW ? (size_t)N : 1));
-    p.part = take(sizeof(float) * fp8k::TENSOR_PARTIALS);
+    p.part = take(2 * sizeof(float) * fp8k::TENSOR_PARTIALS);
     p.fold_x = take(gran == FP8_ROW ? (size_t)fp8k::quant_fold_bytes(M, K) : 0);
     p.fold_w = take(gran == FP8_ROW ? (size_t)fp8k::quant_fold_bytes(N, K) : 0);
     p.total = o;
@@ -163,7 +164,7 @@ BwdPlan plan_bwd(int64_t M, int64_t K, int64_t N, int gran) {
     p.sgt = take(sizeof(float) * (row ? (size_t)N : 1));
     p.swt = take(sizeof(float) * (row ? (size_t)K : 1));
     p.sxt = take(sizeof(float) * (row ? (size_t)K : 1));
-    p.part = take(sizeof(float) * fp8k::TENSOR_PARTIALS);
+    p.part = take(2 * sizeof(float) * fp8k::TENSOR_PARTIALS);
     p.fold_g = take(row ? (size_t)fp8k::quant_fold_bytes(M, N) : 0);
     p.fold_w = take(row ? (size_t)fp8k::quant_fold_bytes(N, K) : 0);
     p.fold_x = take(row ? (size_t)fp8k::quant_fold_bytes(M, K) : 0);
@@ -374,8 +375,19 @@ int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N
         const int fl = recipe->flags & FP8_POW2_SCALE;
         float *sxt = reinterpret_cast<float*>(wsb + b.sxt), *swt = reinterpret_cast<float*>(wsb + b.swt);
         if (recipe->gran == FP8_TENSOR) {
-            if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | FP8_TRANSPOSE_OUT, wsb + b.xt, M, wsf + p.xq, K, sxt, st, reinterpret_cast<float*>(wsf + p.part))) return rc;
-            if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | FP8_TRANSPOSE_OUT, wsb + b.wt, N, wsf + p.wq, K, swt, st, reinterpret_cast<float*>(wsf + p.part))) return rc;
+            float* part = reinterpret_cast<float*>(wsf + p.part);
+            bool pair_done = false;
+            if (recipe->fmt_x == recipe->fmt_w && K > 0) {   // both tensors in two launches
+                const fp8k::TensorOperand ox{x, M, wsb + b.xt, M, wsf + p.xq, K, sxt, part};
+                const fp8k::TensorOperand ow{w, N, wsb + b.wt, N, wsf + p.wq, K, swt, part + fp8k::TENSOR_PARTIALS};
+                const hipError_t e = fp8k::launch_quant_tensor_pair(ox, ow, K, recipe->fmt_x, fl, 1, st);
+                if (e == hipSuccess) pair_done = true;
+                else if (e != hipErrorNotSupported) return hip_fail(e, "quant_tensor_pair");
+            }
+            if (!pair_done) {
+                if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | FP8_TRANSPOSE_OUT, wsb + b.xt, M, wsf + p.xq, K, sxt, st, part)) return rc;
+                if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | FP8_TRANSPOSE_OUT, wsb + b.wt, N, wsf + p.wq, K, swt, st, part)) return rc;
+            }
             FP8_TRY(fp8k::launch_gemm_fp8(wsf + p.xq, K, recipe->fmt_x, sxt, 0, wsf + p.wq, K, recipe->fmt_w, swt, 0, M, N, K, y, N, 0, st));
             return FP8_OK;
         }
@@ -412,6 +424,12 @@ int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N
         const hipError_t e = fp8k::launch_quant_row_pair(x, M, K, xq, K, sx, w, N, K, wq, K, sw, K, recipe->fmt_x, fl, st);
         if (e == hipSuccess) pair_done = true;
         else if (e != hipErrorNotSupported) return hip_fail(e, "quant_row_pair");
+    }
+    if (g == FP8_TENSOR && recipe->fmt_x == recipe->fmt_w && K > 0) {
+        const fp8k::TensorOperand ox{x, M, xq, K, nullptr, 0, sx, part}, ow{w, N, wq, K, nullptr, 0, sw, part + fp8k::TENSOR_PARTIALS};
+        const hipError_t e = fp8k::launch_quant_tensor_pair(ox, ow, K, recipe->fmt_x, fl, 0, st);
+        if (e == hipSuccess) pair_done = true;
+        else if (e != hipErrorNotSupported) return hip_fail(e, "quant_tensor_pair");
     }
     if (!pair_done) {
         if (int rc = quantize_impl(x, M, K, K, g, recipe->fmt_x, fl, xq, K, nullptr, 0, sx, st, part)) return rc;
@@ -466,9 +484,16 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
         } else {
             if (int rc = quantize_impl(dy, M, N, N, FP8_TENSOR, recipe->fmt_dy, fl, gq, N, nullptr, 0, sg, st, part)) return rc;
         }
-        if (dx && !saved)
+        bool pair_done = false;
+        if (dx && dw && !saved && recipe->fmt_w == recipe->fmt_x) {   // W and X in two launches
+            const fp8k::TensorOperand ow{w, N, wt, N, nullptr, 0, swt, part}, ox{x, M, xt, M, nullptr, 0, sxt, part + fp8k::TENSOR_PARTIALS};
+            const hipError_t e = fp8k::launch_quant_tensor_pair(ow, ox, K, recipe->fmt_w, fl, 1, st);
+            if (e == hipSuccess) pair_done = true;
+            else if (e != hipErrorNotSupported) return hip_fail(e, "quant_tensor_pair");
+        }
+        if (dx && !saved && !pair_done)
             if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st, part)) return rc;
-        if (dw && !saved)
+        if (dw && !saved && !pair_done)
             if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st, part)) return rc;
         return grad_gemms(recipe, 0, gq, sg, wt, swt, gqt, sg, xt, sxt, M, K, N, dx, dw, st);
     }

@@ -66,6 +66,16 @@ hipError_t launch_quant_row_colmax(const void* x, int64_t rows, int64_t cols, in
                                    uint8_t* q, int64_t ld_out, float* scale_out, float* scale_cols, void* scratch,
                                    size_t scratch_bytes, hipStream_t st);
 
+// a dense tensor [rows, cols] for tensorwise quantization: codes q (transposed [cols, rows] if asked for, then
+// optionally also untransposed in q_plain), its scale, and room for TENSOR_PARTIALS floats of per-block maxima
+struct TensorOperand {
+    const void* x; int64_t rows;
+    uint8_t* q; int64_t ld_out; uint8_t* q_plain; int64_t ld_plain; float* scale_out; float* part;
+};
+// two dense tensors of the same width and format, tensorwise: two launches (instead of four)
+hipError_t launch_quant_tensor_pair(const TensorOperand& a, const TensorOperand& b, int64_t cols, int fmt, int flags,
+                                    int transpose, hipStream_t st);
+
 // Paired launches: the quantizations of a linear layer come in twos and threes of the same kind; these issue them as
 // twin launches (one grid, two problems) with one second-level launch for all column scales.  Results are those of the
 // single-tensor functions.  hipErrorNotSupported (nothing launched): a tensor does not suit - quantize one by one.

@@ -81,9 +81,13 @@ __global__ __launch_bounds__(256) void amax_rows_kernel(const uint16_t* __restri
 // loads back to back (all in flight together), then reduces.  One integer
 // atomic max per block (out zeroed beforehand); PART: the block's maximum goes to
 // out[blockIdx.x] instead (nothing to zero, the reader combines the gridDim.x values).
+// A launch with gridDim.z == 2 serves two tensors: the blocks with blockIdx.z == 1 work on (x2, n2, out2).
 template <bool PART>
 __global__ __launch_bounds__(256) void amax_flat_kernel(const uint16_t* __restrict__ x, int64_t n,
-                                                         float* __restrict__ out) {
+                                                         float* __restrict__ out,
+                                                         const uint16_t* __restrict__ x2 = nullptr, int64_t n2 = 0,
+                                                         float* __restrict__ out2 = nullptr) {
+    if (blockIdx.z) { x = x2; n = n2; out = out2; }
     const uint4* xv = reinterpret_cast<const uint4*>(x);
     const int64_t nvec = n >> 3;
     uint32_t acc = 0;
@@ -413,7 +417,13 @@ template <int FMT, int GRAN>
 __global__ __launch_bounds__(256) void cast_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
                                                     int64_t ld, const float* __restrict__ scale,
                                                     uint8_t* __restrict__ q, int64_t ld_out, int n_part = 0,
-                                                    int sflags = 0, float* __restrict__ scale_out = nullptr) {
+                                                    int sflags = 0, float* __restrict__ scale_out = nullptr,
+                                                    const uint16_t* __restrict__ x2 = nullptr, int64_t rows2 = 0,
+                                                    const float* __restrict__ scale2 = nullptr,
+                                                    uint8_t* __restrict__ q2 = nullptr,
+                                                    float* __restrict__ scale_out2 = nullptr) {
+    // gridDim.z == 2: a second tensor of the same width and leading dimensions in the blocks with blockIdx.z == 1
+    if (blockIdx.z) { x = x2; rows = rows2; scale = scale2; q = q2; scale_out = scale_out2; }
     const int64_t c = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 16;
     float s_t = 0.0f;
     if constexpr (GRAN == GRAN_TENSOR) {
@@ -494,11 +504,12 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
                                                               const float* __restrict__ scale2 = nullptr,
                                                               uint8_t* __restrict__ qt2 = nullptr, int64_t ld_t2 = 0, int nx2 = 0,
                                                               int64_t ld_part = 0, int n_part2 = 0,
-                                                              float* __restrict__ scale_out2 = nullptr) {
+                                                              float* __restrict__ scale_out2 = nullptr,
+                                                              uint8_t* __restrict__ q_plain2 = nullptr, int64_t ld_plain2 = 0) {
     int bid = blockIdx.x;
     if (bid >= split) {
         bid -= split; x = x2; rows = rows2; ld = ld2; scale = scale2; qt = qt2; ld_t = ld_t2; nx = nx2;
-        n_part = n_part2; scale_out = scale_out2;
+        n_part = n_part2; scale_out = scale_out2; q_plain = q_plain2; ld_plain = ld_plain2;
     }
     constexpr int SLOTS = TR / 8;   // 8-byte slots per output row
     constexpr int PARTS = TR / 16;  // 16-byte parts per output row
@@ -558,7 +569,7 @@ __global__ __launch_bounds__(256) void cast_transpose_kernel(const uint16_t* __r
             // n_part > 0: scale points at the per-block maxima of the amax pass instead of at the scale; the
             // scale is derived here, behind the tile's loads, so that its latency hides under them
             if (rh == 0 && n_part > 0)
-                s_t = tensor_scale_from_partials<FMT>(scale, n_part, sflags, threadIdx.x, blockIdx.x == 0, scale_out);   // (never a twin launch)
+                s_t = tensor_scale_from_partials<FMT>(scale, n_part, sflags, threadIdx.x, bid == 0, scale_out);
         }
         if constexpr (GRAN == GRAN_COL) {
             // n_part > 0: scale points at n_part rows (leading dimension ld_part) of first-level column maxima,
@@ -703,6 +714,51 @@ hipError_t launch_quant_tensor(const void* x, int64_t rows, int64_t cols, int fm
                                                       (int)blocks, sfl, scale_out);
     return launch_cast_t<FMT_E5M2, GRAN_TENSOR>(xp, rows, cols, cols, part, transpose, q, ld_out, q_plain, ld_plain, st,
                                                 (int)blocks, sfl, scale_out);
+}
+
+// The same for two dense tensors of the same width and format in two launches (one for both sets of maxima, one for
+// both casts): X and W of a tensorwise forward, W and X of a stateless backward.
+template <int FMT>
+static hipError_t quant_tensor_pair(const TensorOperand& a, const TensorOperand& b, int64_t cols, int flags, int transpose,
+                                    hipStream_t st) {
+    const uint16_t *xa = static_cast<const uint16_t*>(a.x), *xb = static_cast<const uint16_t*>(b.x);
+    auto blocks_of = [&](int64_t rows) {
+        int64_t nb = (rows * cols / 8 + 256 * 8 - 1) / (256 * 8);
+        return nb < 1 ? (int64_t)1 : nb > TENSOR_PARTIALS ? (int64_t)TENSOR_PARTIALS : nb;
+    };
+    const int64_t ba = blocks_of(a.rows), bb = blocks_of(b.rows), blocks = ba > bb ? ba : bb;   // (spare blocks of the smaller tensor store a zero)
+    amax_flat_kernel<true><<<dim3((unsigned)blocks, 1, 2), dim3(256), 0, st>>>(xa, a.rows * cols, a.part, xb, b.rows * cols, b.part);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int sfl = flags & 1;
+    if (transpose) {
+        const int64_t gx = (cols + 127) / 128, gya = (a.rows + 127) / 128, gyb = (b.rows + 127) / 128;
+        const int64_t ta = ((gya + 15) / 16) * ((gx + 15) / 16) * 256, tb = ((gyb + 15) / 16) * ((gx + 15) / 16) * 256;
+        if (ta + tb > 0x7FFFFFFF) return hipErrorInvalidValue;
+        cast_transpose_kernel<FMT, GRAN_TENSOR, 128><<<dim3((unsigned)(ta + tb)), dim3(256), 0, st>>>(
+            xa, a.rows, cols, cols, a.part, a.q, a.ld_out, a.q_plain, a.ld_plain, (int)gya, (int)gx, nullptr, (int)blocks, sfl,
+            a.scale_out, (int)ta, xb, b.rows, cols, b.part, b.q, b.ld_out, (int)gyb, 0, (int)blocks, b.scale_out, b.q_plain,
+            b.ld_plain);
+        return hipGetLastError();
+    }
+    if (a.ld_out != b.ld_out) return hipErrorInvalidValue;
+    const int64_t items = (cols + 15) / 16;
+    int tx = 1;
+    while (tx < items && tx < 256) tx *= 2;
+    const int ty = 256 / tx;
+    const int64_t rmax = a.rows > b.rows ? a.rows : b.rows;
+    int64_t gy = (rmax + ty - 1) / ty;
+    if (gy > 65535) gy = 65535;
+    cast_kernel<FMT, GRAN_TENSOR><<<dim3((unsigned)((items + tx - 1) / tx), (unsigned)gy, 2), dim3(tx, ty), 0, st>>>(
+        xa, a.rows, cols, cols, a.part, a.q, a.ld_out, (int)blocks, sfl, a.scale_out, xb, b.rows, b.part, b.q, b.scale_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_quant_tensor_pair(const TensorOperand& a, const TensorOperand& b, int64_t cols, int fmt, int flags,
+                                    int transpose, hipStream_t st) {
+    if (a.rows == 0 || b.rows == 0 || cols == 0) return hipErrorNotSupported;
+    return fmt == FMT_E4M3FN ? quant_tensor_pair<FMT_E4M3FN>(a, b, cols, flags, transpose, st)
+                             : quant_tensor_pair<FMT_E5M2>(a, b, cols, flags, transpose, st);
 }
 
 hipError_t launch_cast(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int gran,
@@ -1082,7 +1138,8 @@ hipError_t cast_t_col(const ColOperand& a, const Partials& pa, int64_t Ga, const
         static_cast<const uint16_t*>(a.x), a.rows, cols, a.ld, sa, a.q_col_t, a.ld_col_t, nullptr, 0, (int)gya, (int)gx,
         nullptr, pa.folded ? (int)Ga : 0, flags & 1, a.scale_col,
         b ? (int)ta : NO_TWIN, b ? static_cast<const uint16_t*>(b->x) : nullptr, b ? b->rows : 0, b ? b->ld : 0, sb,
-        b ? b->q_col_t : nullptr, b ? b->ld_col_t : 0, (int)gyb, ld_part, b && pb.folded ? (int)Gb : 0, b ? b->scale_col : nullptr);
+        b ? b->q_col_t : nullptr, b ? b->ld_col_t : 0, (int)gyb, ld_part, b && pb.folded ? (int)Gb : 0, b ? b->scale_col : nullptr,
+        nullptr, 0);
     return hipGetLastError();
 }
 hipError_t cast_t_col(int fmt, const ColOperand& a, const Partials& pa, int64_t Ga, const ColOperand* b, const Partials& pb,

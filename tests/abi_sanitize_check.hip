@@ -37,6 +37,7 @@ hipError_t launch_gemm_bf16_at_b_snake(const void*, int64_t, const void*, int64_
 hipError_t launch_quant_row_col_sigmoid_bwd(const void*, const void*, int64_t, int64_t, int64_t, int, int, uint8_t*, int64_t, float*, uint8_t*, int64_t, float*, hipStream_t) STUB
 // the paired launches decline every other call, so that both the paired path and the one-by-one path behind it run
 #define STUB_ALTERNATING { return (++g_launches & 1) ? hipSuccess : hipErrorNotSupported; }
+hipError_t launch_quant_tensor_pair(const TensorOperand&, const TensorOperand&, int64_t, int, int, int, hipStream_t) STUB_ALTERNATING
 hipError_t launch_quant_row_pair(const void*, int64_t, int64_t, uint8_t*, int64_t, float*, const void*, int64_t, int64_t, uint8_t*, int64_t, float*, int64_t, int, int, hipStream_t) STUB_ALTERNATING
 hipError_t launch_quant_row_col_pair(const RowColOperand&, const RowColOperand*, int64_t, int, int, hipStream_t) STUB_ALTERNATING
 int64_t quant_fold_bytes(int64_t rows, int64_t cols) { return rows >= 256 && rows <= 2048 && cols >= 8 && cols % 8 == 0 && rows * cols <= ((int64_t)4 << 20) ? FOLD_ROWS * ((cols + 7) / 8 * 8) * 2 : 0; }
