@@ -686,7 +686,18 @@ def main() -> int:
             wm, we = fp8.fp8_mx_quantize(w, E4)
             ms = _event_time_ms(lambda: fp8.fp8_mx_scaled_mm(xm, E4, xe, wm, E4, we, 0, out=y), it, wu, torch)
             tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
-            kernels["mx_gemm_fwd"] = {"ms": round(ms, 4), "TFLOP/s": round(tf, 1), "frac_of_fp8_peak": round(tf / FP8_PEAK_TFLOPS, 4)}
+            kernels["mx_gemm_fwd"] = {"ms": round(ms, 4), "TFLOP/s": round(tf, 1), "frac_of_fp8_peak": round(tf / FP8_PEAK_TFLOPS, 4),
+                                      "note": "scales in plain rows [rows, K/32]"}
+            if K % 512 == 0:
+                # the same product with the scale bytes in slabs of sixteen blocks (negative ld_e at the public entry points)
+                xm2, xe2 = fp8.fp8_mx_quantize(x, E4, slabs=True)
+                wm2, we2 = fp8.fp8_mx_quantize(w, E4, slabs=True)
+                ms = _event_time_ms(lambda: fp8.fp8_mx_scaled_mm(xm2, E4, xe2, wm2, E4, we2, 0, out=y), it, wu, torch)
+                tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+                kernels["mx_gemm_fwd_scale_slabs"] = {"ms": round(ms, 4), "TFLOP/s": round(tf, 1),
+                                                      "frac_of_fp8_peak": round(tf / FP8_PEAK_TFLOPS, 4),
+                                                      "note": "scales in slabs [K/512, rows, 16]"}
+                del xm2, xe2, wm2, we2
             wsm = torch.empty(fp8.fp8_mx_linear_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
             ms = _event_time_ms(lambda: fp8.fp8_mx_linear_fwd(x, w, y=y, workspace=wsm), max(3, args.steps // 2), 2, torch)
             result["mx_linear_fwd"] = {"ms": round(ms, 4), "TFLOP/s": round(2.0 * M * N * K / (ms * 1e-3) / 1e12, 1),

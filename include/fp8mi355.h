@@ -332,7 +332,22 @@ int fp8_layernorm_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld
  *   along M for dW.  M % 128 == 0, N % 128 == 0, K % 8 == 0; dy [M, N], x [M, K],
  *   w [N, K] dense bfloat16; workspace of fp8_mx_linear_bwd_workspace_bytes bytes,
  *   256-byte aligned.
+ *
+ * Layout of an array of E8M0 scale bytes (every ld_e* argument of the MX and blockwise
+ * entry points): R scale rows of B = (contracted length) / 32 bytes.
+ *   ld_e >= 0: plain rows, byte of block b of row r at e[r * ld_e + b]
+ *     (ld_e >= B, a multiple of 4; e 4-byte aligned).
+ *   ld_e <  0: slabs of sixteen blocks, e[((b / 16) * S + r) * 16 + b % 16] with
+ *     S = -ld_e >= R rows per slab (B % 16 == 0, i.e. the contracted length a multiple of
+ *     512; S * B < 2^31; e 16-byte aligned, S * B bytes).  FP8_E8M0_SLABS(S) spells the
+ *     argument.  The 256 x 256 product kernel fetches the scales of four K steps of a row as
+ *     one 16-byte piece; in slabs the pieces of consecutive rows are consecutive in
+ *     memory (8 cache lines per wavefront load instead of 64).  fp8_mx_scaled_mm takes
+ *     slabs for both operands or for neither (lda, ldb < 2^23 with slabs); rows
+ *     between R and S are never read for output that is stored.  Same codes, same
+ *     scale bytes, same products as with plain rows.
  */
+#define FP8_E8M0_SLABS(rows_per_slab) (-(int64_t)(rows_per_slab))
 int fp8_mx_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int format,
                     uint8_t* q_out, int64_t ld_q, uint8_t* e8m0_out, int64_t ld_e, void* stream);
 int fp8_mx_quantize_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int format,

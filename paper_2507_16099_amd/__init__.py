@@ -10,7 +10,7 @@ from .fp8 import (  # noqa: F401
     fp8_linear_workspace_bytes, fp8_linear_fwd, fp8_linear_bwd,
     fp8_linear_prequantized_workspace_bytes, fp8_linear_fwd_prequantized, fp8_grad_weight_hp,
     FP8_STATIC_SCRATCH_BYTES, fp8_linear_fwd_prequantized_static,
-    fp8_layernorm_quantize, fp8_block_quantize, fp8_block_linear_workspace_bytes, fp8_block_linear_fwd, fp8_block_quantize_t, fp8_block_quantize_row_col, fp8_block_linear_bwd_workspace_bytes, fp8_block_linear_bwd, fp8_linear_bwd_sigmoid_workspace_bytes, fp8_linear_bwd_sigmoid, fp8_mx_quantize, fp8_mx_quantize_t, fp8_mx_quantize_row_col, fp8_mx_scaled_mm, fp8_mx_linear_workspace_bytes, fp8_mx_linear_fwd,
+    fp8_layernorm_quantize, fp8_block_quantize, fp8_block_linear_workspace_bytes, fp8_block_linear_fwd, fp8_block_quantize_t, fp8_block_quantize_row_col, fp8_block_linear_bwd_workspace_bytes, fp8_block_linear_bwd, fp8_linear_bwd_sigmoid_workspace_bytes, fp8_linear_bwd_sigmoid, fp8_mx_quantize, e8m0_plain_rows, fp8_mx_quantize_t, fp8_mx_quantize_row_col, fp8_mx_scaled_mm, fp8_mx_linear_workspace_bytes, fp8_mx_linear_fwd,
     fp8_mx_linear_bwd_workspace_bytes, fp8_mx_linear_bwd,
     fp8_last_error, fp8_version,
 )

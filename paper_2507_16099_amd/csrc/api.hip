@@ -730,6 +730,30 @@ int fp8_layernorm_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld
     return FP8_OK;
 }
 
+namespace {
+// An array of E8M0 scale bytes, one per block of 32: `rows` scale rows of `blocks` bytes.  ld_e >= 0: plain rows of
+// ld_e bytes (a multiple of 4, 4-byte aligned).  ld_e < 0: slabs of sixteen blocks, [blocks / 16][-ld_e][16 bytes]
+// (blocks a multiple of 16, -ld_e >= rows, 16-byte aligned): the layout that the 256 x 256 product kernel reads as
+// whole 16-byte pieces.
+int check_e8m0(const char* fn, const void* e, int64_t rows, int64_t blocks, int64_t ld_e) {
+    if (ld_e < 0) {
+        if (blocks % 16 != 0)
+            return fail(FP8_ERR_SHAPE, "%s: scale slabs (negative ld_e) need a multiple of 512 elements along the blocks, got %lld blocks", fn, (long long)blocks);
+        if (-ld_e < rows) return fail(FP8_ERR_SHAPE, "%s: scale slabs of %lld rows for %lld rows of scales", fn, (long long)-ld_e, (long long)rows);
+        if (-ld_e > kMaxDim || -ld_e * blocks >= ((int64_t)1 << 31))
+            return fail(FP8_ERR_SHAPE, "%s: scale slabs of %lld rows x %lld blocks exceed 2^31 bytes", fn, (long long)-ld_e, (long long)blocks);
+        if (rows > 0 && blocks > 0 && !e) return fail(FP8_ERR_NULL, "%s: scale array is NULL", fn);
+        if (!aligned(e, 16)) return fail(FP8_ERR_ALIGN, "%s: scale slabs not 16-byte aligned", fn);
+        return FP8_OK;
+    }
+    if (ld_e < blocks || ld_e % 4 != 0)
+        return fail(FP8_ERR_SHAPE, "%s: ld_e=%lld must be >= %lld (one byte per block of 32) and a multiple of 4", fn, (long long)ld_e, (long long)blocks);
+    if (rows > 0 && blocks > 0 && !e) return fail(FP8_ERR_NULL, "%s: scale array is NULL", fn);
+    if (!aligned(e, 4)) return fail(FP8_ERR_ALIGN, "%s: scale array not 4-byte aligned", fn);
+    return FP8_OK;
+}
+}  // namespace
+
 int fp8_mx_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int format, uint8_t* q_out, int64_t ld_q,
                     uint8_t* e8m0_out, int64_t ld_e, void* stream) {
     g_err[0] = 0;
@@ -738,9 +762,7 @@ int fp8_mx_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, int f
     if (int rc = check_bf16(fn, x, rows, cols, ld)) return rc;
     if (cols % 32 != 0) return fail(FP8_ERR_SHAPE, "%s: cols=%lld must be a multiple of the block size 32", fn, (long long)cols);
     if (int rc = check_q_out(fn, q_out, rows, cols, ld_q, 0)) return rc;
-    if (ld_e < cols / 32 || ld_e % 4 != 0) return fail(FP8_ERR_SHAPE, "%s: ld_e=%lld must be >= cols/32 and a multiple of 4", fn, (long long)ld_e);
-    if (rows > 0 && cols > 0 && !e8m0_out) return fail(FP8_ERR_NULL, "%s: e8m0_out is NULL", fn);
-    if (!aligned(e8m0_out, 4)) return fail(FP8_ERR_ALIGN, "%s: e8m0_out not 4-byte aligned", fn);
+    if (int rc = check_e8m0(fn, e8m0_out, rows, cols / 32, ld_e)) return rc;
     FP8_TRY(fp8k::launch_mx_quant(x, rows, cols, ld, format, q_out, ld_q, e8m0_out, ld_e, static_cast<hipStream_t>(stream)));
     return FP8_OK;
 }
@@ -753,9 +775,7 @@ int fp8_mx_quantize_t(const void* x, int64_t rows, int64_t cols, int64_t ld, int
     if (int rc = check_bf16(fn, x, rows, cols, ld)) return rc;
     if (rows % 32 != 0) return fail(FP8_ERR_SHAPE, "%s: rows=%lld must be a multiple of the block size 32", fn, (long long)rows);
     if (int rc = check_q_out(fn, qt_out, cols, rows, ld_q, 0)) return rc;
-    if (ld_e < rows / 32 || ld_e % 4 != 0) return fail(FP8_ERR_SHAPE, "%s: ld_e=%lld must be >= rows/32 and a multiple of 4", fn, (long long)ld_e);
-    if (rows > 0 && cols > 0 && !e8m0_t_out) return fail(FP8_ERR_NULL, "%s: e8m0_t_out is NULL", fn);
-    if (!aligned(e8m0_t_out, 4)) return fail(FP8_ERR_ALIGN, "%s: e8m0_t_out not 4-byte aligned", fn);
+    if (int rc = check_e8m0(fn, e8m0_t_out, cols, rows / 32, ld_e)) return rc;
     FP8_TRY(fp8k::launch_mx_quant_t(x, rows, cols, ld, format, qt_out, ld_q, e8m0_t_out, ld_e, nullptr, 0, nullptr, 0,
                                     static_cast<hipStream_t>(stream)));
     return FP8_OK;
@@ -772,10 +792,8 @@ int fp8_mx_quantize_row_col(const void* x, int64_t rows, int64_t cols, int64_t l
         return fail(FP8_ERR_SHAPE, "%s: rows=%lld and cols=%lld must be multiples of the block size 32", fn, (long long)rows, (long long)cols);
     if (int rc = check_q_out("fp8_mx_quantize_row_col(q_row)", q_row, rows, cols, ld_row, 0)) return rc;
     if (int rc = check_q_out("fp8_mx_quantize_row_col(q_col_t)", q_col_t, cols, rows, ld_col_t, 0)) return rc;
-    if (ld_er < cols / 32 || ld_er % 4 != 0 || ld_ec < rows / 32 || ld_ec % 4 != 0)
-        return fail(FP8_ERR_SHAPE, "%s: ld_er=%lld, ld_ec=%lld must cover the blocks and be multiples of 4", fn, (long long)ld_er, (long long)ld_ec);
-    if (rows > 0 && cols > 0 && (!e_row || !e_col_t)) return fail(FP8_ERR_NULL, "%s: scale output is NULL", fn);
-    if (!aligned(e_row, 4) || !aligned(e_col_t, 4)) return fail(FP8_ERR_ALIGN, "%s: scale outputs not 4-byte aligned", fn);
+    if (int rc = check_e8m0("fp8_mx_quantize_row_col(e_row)", e_row, rows, cols / 32, ld_er)) return rc;
+    if (int rc = check_e8m0("fp8_mx_quantize_row_col(e_col_t)", e_col_t, cols, rows / 32, ld_ec)) return rc;
     FP8_TRY(fp8k::launch_mx_quant_t(x, rows, cols, ld, format, q_col_t, ld_col_t, e_col_t, ld_ec, q_row, ld_row, e_row, ld_er,
                                     static_cast<hipStream_t>(stream)));
     return FP8_OK;
@@ -791,13 +809,18 @@ int fp8_mx_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const uint8_t* ea
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxDim)
         return fail(FP8_ERR_SHAPE, "%s: M=%lld N=%lld K=%lld out of range", fn, (long long)M, (long long)N, (long long)K);
     if (K % 128 != 0) return fail(FP8_ERR_SHAPE, "%s: K=%lld must be a multiple of 128", fn, (long long)K);
-    if (lda < K || ldb < K || ld_out < N || ld_ea < K / 32 || ld_eb < K / 32) return fail(FP8_ERR_SHAPE, "%s: leading dimension too small", fn);
+    if (lda < K || ldb < K || ld_out < N) return fail(FP8_ERR_SHAPE, "%s: leading dimension too small", fn);
+    if ((ld_ea < 0) != (ld_eb < 0)) return fail(FP8_ERR_SHAPE, "%s: scale slabs (negative ld_ea, ld_eb) for both operands or for neither", fn);
+    if (ld_ea < 0 && !fp8k::gemm_fp8_snake_fits(lda, ldb))
+        return fail(FP8_ERR_SHAPE, "%s: scale slabs need lda, ldb below 2^23", fn);
     if (M > 0 && N > 0) {
-        if (!out || (K > 0 && (!a || !b || !ea || !eb))) return fail(FP8_ERR_NULL, "%s: NULL pointer", fn);
-        if (!aligned(a, 16) || !aligned(b, 16) || !aligned(out, 16) || !aligned(ea, 4) || !aligned(eb, 4))
-            return fail(FP8_ERR_ALIGN, "%s: a, b, out (16) / ea, eb (4) misaligned", fn);
-        if (lda % 16 != 0 || ldb % 16 != 0 || ld_ea % 4 != 0 || ld_eb % 4 != 0)
-            return fail(FP8_ERR_ALIGN, "%s: lda, ldb must be multiples of 16, ld_ea, ld_eb of 4", fn);
+        if (int rc = check_e8m0("fp8_mx_scaled_mm(ea)", ea, K > 0 ? M : 0, K / 32, ld_ea)) return rc;
+        if (int rc = check_e8m0("fp8_mx_scaled_mm(eb)", eb, K > 0 ? N : 0, K / 32, ld_eb)) return rc;
+        if (!out || (K > 0 && (!a || !b))) return fail(FP8_ERR_NULL, "%s: NULL pointer", fn);
+        if (!aligned(a, 16) || !aligned(b, 16) || !aligned(out, 16))
+            return fail(FP8_ERR_ALIGN, "%s: a, b, out not 16-byte aligned", fn);
+        if (lda % 16 != 0 || ldb % 16 != 0)
+            return fail(FP8_ERR_ALIGN, "%s: lda, ldb must be multiples of 16", fn);
         const int64_t out_align = (flags & FP8_OUT_FP32) ? 4 : 8;
         if (ld_out % out_align != 0) return fail(FP8_ERR_ALIGN, "%s: ld_out=%lld must be a multiple of %lld", fn, (long long)ld_out, (long long)out_align);
     }
@@ -867,9 +890,7 @@ int fp8_block_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld, in
     if (cols % 128 != 0) return fail(FP8_ERR_SHAPE, "%s: cols=%lld must be a multiple of the block width 128", fn, (long long)cols);
     if (block_rows == 128 && rows > (int64_t)65535 * 128) return fail(FP8_ERR_SHAPE, "%s: rows=%lld too large", fn, (long long)rows);
     if (int rc = check_q_out(fn, q_out, rows, cols, ld_q, 0)) return rc;
-    if (ld_e < cols / 32 || ld_e % 4 != 0) return fail(FP8_ERR_SHAPE, "%s: ld_e=%lld must be >= cols/32 and a multiple of 4", fn, (long long)ld_e);
-    if (rows > 0 && cols > 0 && !e8m0_out) return fail(FP8_ERR_NULL, "%s: e8m0_out is NULL", fn);
-    if (!aligned(e8m0_out, 4)) return fail(FP8_ERR_ALIGN, "%s: e8m0_out not 4-byte aligned", fn);
+    if (int rc = check_e8m0(fn, e8m0_out, rows, cols / 32, ld_e)) return rc;
     FP8_TRY(fp8k::launch_block_quant(x, rows, cols, ld, block_rows, format, q_out, ld_q, e8m0_out, ld_e, static_cast<hipStream_t>(stream)));
     return FP8_OK;
 }
@@ -998,9 +1019,7 @@ int fp8_block_quantize_t(const void* x, int64_t rows, int64_t cols, int64_t ld, 
     if (rows % 128 != 0) return fail(FP8_ERR_SHAPE, "%s: rows=%lld must be a multiple of the block length 128", fn, (long long)rows);
     if (cols % 8 != 0) return fail(FP8_ERR_SHAPE, "%s: cols=%lld must be a multiple of 8", fn, (long long)cols);
     if (int rc = check_q_out(fn, qt_out, cols, rows, ld_q, 0)) return rc;
-    if (ld_e < rows / 32 || ld_e % 4 != 0) return fail(FP8_ERR_SHAPE, "%s: ld_e=%lld must be >= rows/32 and a multiple of 4", fn, (long long)ld_e);
-    if (rows > 0 && cols > 0 && !e8m0_t_out) return fail(FP8_ERR_NULL, "%s: e8m0_t_out is NULL", fn);
-    if (!aligned(e8m0_t_out, 4)) return fail(FP8_ERR_ALIGN, "%s: e8m0_t_out not 4-byte aligned", fn);
+    if (int rc = check_e8m0(fn, e8m0_t_out, cols, rows / 32, ld_e)) return rc;
     FP8_TRY(fp8k::launch_block_quant_t(x, rows, cols, ld, block_rows, format, qt_out, ld_q, e8m0_t_out, ld_e,
                                        static_cast<hipStream_t>(stream)));
     return FP8_OK;
@@ -1017,10 +1036,8 @@ int fp8_block_quantize_row_col(const void* x, int64_t rows, int64_t cols, int64_
         return fail(FP8_ERR_SHAPE, "%s: rows=%lld and cols=%lld must be multiples of the tile length 128", fn, (long long)rows, (long long)cols);
     if (int rc = check_q_out(fn, q_row, rows, cols, ld_row, 0)) return rc;
     if (int rc = check_q_out(fn, q_col_t, cols, rows, ld_col_t, 0)) return rc;
-    if (ld_er < cols / 32 || ld_er % 4 != 0 || ld_ec < rows / 32 || ld_ec % 4 != 0)
-        return fail(FP8_ERR_SHAPE, "%s: ld_er=%lld / ld_ec=%lld must cover cols/32 / rows/32 and be multiples of 4", fn, (long long)ld_er, (long long)ld_ec);
-    if (rows > 0 && cols > 0 && (!e_row || !e_col_t)) return fail(FP8_ERR_NULL, "%s: a scale output is NULL", fn);
-    if (!aligned(e_row, 4) || !aligned(e_col_t, 4)) return fail(FP8_ERR_ALIGN, "%s: scale outputs not 4-byte aligned", fn);
+    if (int rc = check_e8m0("fp8_block_quantize_row_col(e_row)", e_row, rows, cols / 32, ld_er)) return rc;
+    if (int rc = check_e8m0("fp8_block_quantize_row_col(e_col_t)", e_col_t, cols, rows / 32, ld_ec)) return rc;
     FP8_TRY(fp8k::launch_block_quant_t(x, rows, cols, ld, 1, format, q_col_t, ld_col_t, e_col_t, ld_ec, static_cast<hipStream_t>(stream),
                                        q_row, ld_row, e_row, ld_er));
     return FP8_OK;

@@ -420,32 +420,57 @@ def fp8_layernorm_quantize(x: torch.Tensor, gamma: torch.Tensor, beta: torch.Ten
     return h, q, s, mean, rstd
 
 
-def fp8_mx_quantize(x: torch.Tensor, fmt: int, q: torch.Tensor | None = None, e8m0: torch.Tensor | None = None):
-    """MX blocks of 32 along the last axis: codes [rows, cols] and E8M0 bytes [rows, cols / 32]."""
+def _alloc_e8m0(rows: int, nb: int, slabs: bool, device) -> torch.Tensor:
+    """Room for the E8M0 bytes of `rows` scale rows of `nb` blocks: plain rows [rows, nb] (row pitch a multiple
+    of 4), or, with slabs, [nb / 16, rows, 16] (see the layout note in fp8mi355.h)."""
+    if slabs:
+        if nb % 16 != 0:
+            raise ValueError("scale slabs need a multiple of 16 blocks (512 elements) per row")
+        return torch.empty((nb // 16, rows, 16), dtype=torch.uint8, device=device)
+    return torch.empty((rows, (nb + 3) // 4 * 4), dtype=torch.uint8, device=device)[:, :nb]
+
+
+def _e8m0_ld(e: torch.Tensor) -> int:
+    """The ld_e argument for a scale tensor: its row pitch, or minus the rows per slab for a 3-D slab tensor."""
+    if e.dim() == 3:
+        assert e.dtype == torch.uint8 and e.shape[2] == 16 and e.is_contiguous(), "slab tensor must be [nb/16, rows, 16] uint8, contiguous"
+        return -int(e.shape[1])
+    return _mat(e, 1)[2]
+
+
+def e8m0_plain_rows(e: torch.Tensor) -> torch.Tensor:
+    """A scale tensor as plain rows [rows, nb], whatever its layout (a copy for slabs)."""
+    if e.dim() == 3:
+        return e.permute(1, 0, 2).reshape(e.shape[1], e.shape[0] * 16)
+    return e
+
+
+def fp8_mx_quantize(x: torch.Tensor, fmt: int, q: torch.Tensor | None = None, e8m0: torch.Tensor | None = None,
+                    slabs: bool = False):
+    """MX blocks of 32 along the last axis: codes [rows, cols] and E8M0 bytes [rows, cols / 32]
+    (slabs: [cols / 512, rows, 16])."""
     rows, cols, ld = _mat(x, 2)
     if q is None:
         q = _alloc_q(rows, cols, 0, x.device)
     if e8m0 is None:
-        nb = cols // 32
-        e8m0 = torch.empty((rows, (nb + 3) // 4 * 4), dtype=torch.uint8, device=x.device)[:, :nb]
+        e8m0 = _alloc_e8m0(rows, cols // 32, slabs, x.device)
     _, _, ld_q = _mat(q, 1)
-    _, _, ld_e = _mat(e8m0, 1)
+    ld_e = _e8m0_ld(e8m0)
     _check(load_library().fp8_mx_quantize(_ptr(x), rows, cols, ld, fmt, _ptr(q), ld_q, _ptr(e8m0), ld_e, _stream()))
     return q, e8m0
 
 
 def fp8_block_quantize(x: torch.Tensor, block_rows: int, fmt: int, q: torch.Tensor | None = None,
-                       e8m0: torch.Tensor | None = None):
+                       e8m0: torch.Tensor | None = None, slabs: bool = False):
     """Blockwise FP8: tiles of 1 x 128 (block_rows = 1) or blocks of 128 x 128 (block_rows = 128) with power-of-two
     scales; codes [rows, cols] and E8M0 bytes [rows, cols / 32] in the layout of the MX scales."""
     rows, cols, ld = _mat(x, 2)
     if q is None:
         q = _alloc_q(rows, cols, 0, x.device)
     if e8m0 is None:
-        nb = cols // 32
-        e8m0 = torch.empty((rows, (nb + 3) // 4 * 4), dtype=torch.uint8, device=x.device)[:, :nb]
+        e8m0 = _alloc_e8m0(rows, cols // 32, slabs, x.device)
     _, _, ld_q = _mat(q, 1)
-    _, _, ld_e = _mat(e8m0, 1)
+    ld_e = _e8m0_ld(e8m0)
     _check(load_library().fp8_block_quantize(_ptr(x), rows, cols, ld, block_rows, fmt, _ptr(q), ld_q, _ptr(e8m0), ld_e,
                                              _stream()))
     return q, e8m0
@@ -474,17 +499,16 @@ def fp8_block_linear_fwd(x: torch.Tensor, w: torch.Tensor, fmt_x: int = FP8_E4M3
 
 
 def fp8_block_quantize_t(x: torch.Tensor, block_rows: int, fmt: int, qt: torch.Tensor | None = None,
-                         e8m0_t: torch.Tensor | None = None):
+                         e8m0_t: torch.Tensor | None = None, slabs: bool = False):
     """Blockwise FP8 of the transposed matrix, written transposed: codes [cols, rows], E8M0 bytes [cols, rows / 32]
     (block_rows = 1: tiles of 128 rows x 1 column of x; 128: blocks of 128 x 128)."""
     rows, cols, ld = _mat(x, 2)
     if qt is None:
         qt = _alloc_q(cols, rows, 0, x.device)
     if e8m0_t is None:
-        nb = rows // 32
-        e8m0_t = torch.empty((cols, (nb + 3) // 4 * 4), dtype=torch.uint8, device=x.device)[:, :nb]
+        e8m0_t = _alloc_e8m0(cols, rows // 32, slabs, x.device)
     _, _, ld_q = _mat(qt, 1)
-    _, _, ld_e = _mat(e8m0_t, 1)
+    ld_e = _e8m0_ld(e8m0_t)
     _check(load_library().fp8_block_quantize_t(_ptr(x), rows, cols, ld, block_rows, fmt, _ptr(qt), ld_q, _ptr(e8m0_t), ld_e,
                                                _stream()))
     return qt, e8m0_t
@@ -518,51 +542,47 @@ def fp8_block_linear_bwd(dy: torch.Tensor, x: torch.Tensor, w: torch.Tensor, fmt
     return dx, dw
 
 
-def fp8_mx_quantize_t(x: torch.Tensor, fmt: int, qt: torch.Tensor | None = None, e8m0_t: torch.Tensor | None = None):
+def fp8_mx_quantize_t(x: torch.Tensor, fmt: int, qt: torch.Tensor | None = None, e8m0_t: torch.Tensor | None = None,
+                      slabs: bool = False):
     """MX blocks of 32 down the columns, transposed output: codes [cols, rows], E8M0 bytes [cols, rows / 32]."""
     rows, cols, ld = _mat(x, 2)
     if qt is None:
         qt = _alloc_q(cols, rows, 0, x.device)
     if e8m0_t is None:
-        nb = rows // 32
-        e8m0_t = torch.empty((cols, (nb + 3) // 4 * 4), dtype=torch.uint8, device=x.device)[:, :nb]
+        e8m0_t = _alloc_e8m0(cols, rows // 32, slabs, x.device)
     _, _, ld_q = _mat(qt, 1)
-    _, _, ld_e = _mat(e8m0_t, 1)
+    ld_e = _e8m0_ld(e8m0_t)
     _check(load_library().fp8_mx_quantize_t(_ptr(x), rows, cols, ld, fmt, _ptr(qt), ld_q, _ptr(e8m0_t), ld_e, _stream()))
     return qt, e8m0_t
 
 
-def fp8_mx_quantize_row_col(x: torch.Tensor, fmt: int, out=None):
+def fp8_mx_quantize_row_col(x: torch.Tensor, fmt: int, out=None, slabs: bool = False):
     """Both MX orientations from one read: (q_row [rows, cols], e_row [rows, cols/32], q_col_t [cols, rows],
     e_col_t [cols, rows/32]); out: the same four tensors to write into."""
     rows, cols, ld = _mat(x, 2)
     if out is None:
         nb_r, nb_c = cols // 32, rows // 32
-        out = (_alloc_q(rows, cols, 0, x.device),
-               torch.empty((rows, (nb_r + 3) // 4 * 4), dtype=torch.uint8, device=x.device)[:, :nb_r],
-               _alloc_q(cols, rows, 0, x.device),
-               torch.empty((cols, (nb_c + 3) // 4 * 4), dtype=torch.uint8, device=x.device)[:, :nb_c])
+        out = (_alloc_q(rows, cols, 0, x.device), _alloc_e8m0(rows, nb_r, slabs, x.device),
+               _alloc_q(cols, rows, 0, x.device), _alloc_e8m0(cols, nb_c, slabs, x.device))
     q_row, e_row, q_col_t, e_col_t = out
     _check(load_library().fp8_mx_quantize_row_col(_ptr(x), rows, cols, ld, fmt, _ptr(q_row), _mat(q_row, 1)[2], _ptr(e_row),
-                                                  _mat(e_row, 1)[2], _ptr(q_col_t), _mat(q_col_t, 1)[2], _ptr(e_col_t),
-                                                  _mat(e_col_t, 1)[2], _stream()))
+                                                  _e8m0_ld(e_row), _ptr(q_col_t), _mat(q_col_t, 1)[2], _ptr(e_col_t),
+                                                  _e8m0_ld(e_col_t), _stream()))
     return q_row, e_row, q_col_t, e_col_t
 
 
-def fp8_block_quantize_row_col(x: torch.Tensor, fmt: int, out=None):
+def fp8_block_quantize_row_col(x: torch.Tensor, fmt: int, out=None, slabs: bool = False):
     """Blockwise tiles of 1 x 128 along the rows and, transposed, of 128 x 1 down the columns from one read:
     (q_row [rows, cols], e_row [rows, cols/32], q_col_t [cols, rows], e_col_t [cols, rows/32])."""
     rows, cols, ld = _mat(x, 2)
     if out is None:
         nb_r, nb_c = cols // 32, rows // 32
-        out = (_alloc_q(rows, cols, 0, x.device),
-               torch.empty((rows, (nb_r + 3) // 4 * 4), dtype=torch.uint8, device=x.device)[:, :nb_r],
-               _alloc_q(cols, rows, 0, x.device),
-               torch.empty((cols, (nb_c + 3) // 4 * 4), dtype=torch.uint8, device=x.device)[:, :nb_c])
+        out = (_alloc_q(rows, cols, 0, x.device), _alloc_e8m0(rows, nb_r, slabs, x.device),
+               _alloc_q(cols, rows, 0, x.device), _alloc_e8m0(cols, nb_c, slabs, x.device))
     q_row, e_row, q_col_t, e_col_t = out
     _check(load_library().fp8_block_quantize_row_col(_ptr(x), rows, cols, ld, fmt, _ptr(q_row), _mat(q_row, 1)[2], _ptr(e_row),
-                                                     _mat(e_row, 1)[2], _ptr(q_col_t), _mat(q_col_t, 1)[2], _ptr(e_col_t),
-                                                     _mat(e_col_t, 1)[2], _stream()))
+                                                     _e8m0_ld(e_row), _ptr(q_col_t), _mat(q_col_t, 1)[2], _ptr(e_col_t),
+                                                     _e8m0_ld(e_col_t), _stream()))
     return q_row, e_row, q_col_t, e_col_t
 
 
@@ -571,8 +591,7 @@ def fp8_mx_scaled_mm(a: torch.Tensor, fmt_a: int, ea: torch.Tensor, b: torch.Ten
     M, K, lda = _mat(a, 1)
     N, Kb, ldb = _mat(b, 1)
     assert K == Kb, (a.shape, b.shape)
-    _, _, ld_ea = _mat(ea, 1)
-    _, _, ld_eb = _mat(eb, 1)
+    ld_ea, ld_eb = _e8m0_ld(ea), _e8m0_ld(eb)      # (3-D slab tensors give negative values)
     if out is None:
         dt = torch.float32 if flags & FP8_OUT_FP32 else torch.bfloat16
         pad = 4 if flags & FP8_OUT_FP32 else 8

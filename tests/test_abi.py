@@ -104,6 +104,16 @@ def test_argument_errors_of_the_later_entry_points():
     assert L.fp8_mx_quantize_t(p, 64, 64, 64, 7, p, 64, p, 4, None) == -3
     assert L.fp8_mx_scaled_mm(p, 64, 0, p, 4, p, 64, 0, p, 4, 16, 16, 64, p, 16, 0, None) == -2   # K % 128
     assert L.fp8_mx_scaled_mm(p, 128, 0, p, 4, p, 128, 0, p, 4, 16, 16, 128, p, 16, 8, None) == -3  # unknown flag
+    # scale slabs (negative ld_e): whole slabs of sixteen blocks, enough rows per slab, both operands of a product alike
+    assert L.fp8_mx_quantize(p, 4, 256, 256, 0, p, 256, p, -4, None) == -2        # 8 blocks per row: not a multiple of 16
+    assert "512" in fp8.fp8_last_error()
+    assert L.fp8_mx_quantize(p, 4, 512, 512, 0, p, 512, p, -3, None) == -2        # 3 rows per slab for 4 rows
+    assert L.fp8_mx_quantize(p + 4, 4, 512, 512, 0, p, 512, p + 4, -4, None) == -4    # slabs 16-byte aligned
+    assert L.fp8_mx_quantize_t(p, 512, 8, 8, 0, p, 512, p, -7, None) == -2        # 8 scale rows
+    assert L.fp8_mx_scaled_mm(p, 512, 0, p, -16, p, 512, 0, p, 16, 16, 16, 512, p, 16, 0, None) == -2   # slabs and plain rows mixed
+    assert "both" in fp8.fp8_last_error()
+    assert L.fp8_mx_scaled_mm(p, 512, 0, p, -8, p, 512, 0, p, -16, 16, 16, 512, p, 16, 0, None) == -2   # 8 rows per slab for M = 16
+    assert L.fp8_mx_scaled_mm(p, 256, 0, p, -16, p, 256, 0, p, -16, 16, 16, 256, p, 16, 0, None) == -2  # K % 512
     assert L.fp8_mx_linear_workspace_bytes(16, 96, 16) == 0
     assert L.fp8_mx_linear_bwd_workspace_bytes(100, 64, 128) == 0                # M % 128
     assert L.fp8_mx_linear_bwd_workspace_bytes(128, 64, 256) >= 2 * 128 * 256 + 64 * 256 + 64 * 128

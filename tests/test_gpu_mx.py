@@ -298,3 +298,106 @@ def test_scale_slabs_between_quantizers_and_gemm(M, K, N):
         assert orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want.out16)) <= TOL
         assert float((got == want.out16).mean()) > 0.95
 
+
+
+# ------------------------------------------------ scale slabs at the public entry points
+
+@pytest.mark.parametrize("rows,cols", [(32, 512), (96, 1024), (288, 1536), (640, 512), (512, 544), (1024, 512)])
+@pytest.mark.parametrize("fmt", FMTS)
+def test_public_quantizers_write_scale_slabs(rows, cols, fmt):
+    """A negative ld_e selects slabs of sixteen blocks, [blocks / 16][rows per slab][16 bytes].  Every quantizer that
+    writes E8M0 bytes must produce, in slabs, the bytes (and codes) that it produces in plain rows and that the
+    oracle computes; slabs with more rows than the tensor (spare rows at the end of each slab) stay untouched there."""
+    x = si.student_t_outlier_bf16((rows, cols), 3.0, 0.01, 100.0, seed=14, stream=rows + cols)
+    xd = dev_bf16(x)
+    wq, we = orc.mx_quantize(x, fmt)
+    wqt, wet = orc.mx_quantize(np.ascontiguousarray(x.T), fmt)
+    if rows % 512 == 0:                      # blocks down the columns: rows / 32 of them per scale row
+        qt, et = fp8.fp8_mx_quantize_t(xd, fmt, slabs=True)
+        assert tuple(et.shape) == (rows // 512, cols, 16)
+        assert (host_u8(qt) == wqt).all() and (host_u8(fp8.e8m0_plain_rows(et)) == wet).all()
+    if cols % 512 != 0:
+        with pytest.raises(fp8.Fp8Error):    # blocks along the rows do not fill whole slabs
+            fp8.fp8_mx_quantize(xd, fmt, e8m0=torch.empty((cols // 512 + 1, rows, 16), dtype=torch.uint8, device="cuda"))
+        return
+    q, e = fp8.fp8_mx_quantize(xd, fmt, slabs=True)
+    assert e.dim() == 3 and tuple(e.shape) == (cols // 512, rows, 16)
+    assert (host_u8(q) == wq).all() and (host_u8(fp8.e8m0_plain_rows(e)) == we).all()
+    # spare rows in every slab: a sentinel there survives
+    spare = torch.full((cols // 512, rows + 5, 16), 0xA5, dtype=torch.uint8, device="cuda")
+    q2, e2 = fp8.fp8_mx_quantize(xd, fmt, e8m0=spare)
+    assert (host_u8(q2) == wq).all()
+    assert (host_u8(fp8.e8m0_plain_rows(e2))[:rows] == we).all() and (host_u8(spare)[:, rows:, :] == 0xA5).all()
+
+
+@pytest.mark.parametrize("rows,cols", [(512, 512), (1024, 640)])
+def test_public_row_col_and_block_quantizers_write_scale_slabs(rows, cols):
+    """The two-orientation quantizers and the blockwise ones in slabs against their own plain-row output."""
+    x = si.student_t_outlier_bf16((rows, cols), 3.0, 0.01, 100.0, seed=15, stream=rows)
+    xd = dev_bf16(x)
+    fmt = orc.E4M3FN
+    for fn in (fp8.fp8_mx_quantize_row_col, fp8.fp8_block_quantize_row_col):
+        if fn is fp8.fp8_block_quantize_row_col and (rows % 128 or cols % 128):
+            continue
+        plain = fn(xd, fmt)
+        # slabs only where the blocks of a row fill whole slabs: the row direction needs cols % 512, the column direction rows % 512
+        out = (torch.empty_like(plain[0]),
+               torch.empty((cols // 512, rows, 16), dtype=torch.uint8, device="cuda") if cols % 512 == 0 else torch.empty_like(plain[1]),
+               torch.empty_like(plain[2]),
+               torch.empty((rows // 512, cols, 16), dtype=torch.uint8, device="cuda") if rows % 512 == 0 else torch.empty_like(plain[3]))
+        got = fn(xd, fmt, out=out)
+        for a, b in zip(got, plain):
+            assert (host_u8(fp8.e8m0_plain_rows(a)) == host_u8(fp8.e8m0_plain_rows(b))).all()
+    for br in (1, 128):
+        if cols % 512 == 0 and rows % 128 == 0:
+            pq, pe = fp8.fp8_block_quantize(xd, br, fmt)
+            sq, se = fp8.fp8_block_quantize(xd, br, fmt, slabs=True)
+            assert (host_u8(sq) == host_u8(pq)).all() and (host_u8(fp8.e8m0_plain_rows(se)) == host_u8(pe)).all()
+        if rows % 512 == 0:
+            pq, pe = fp8.fp8_block_quantize_t(xd, br, fmt)
+            sq, se = fp8.fp8_block_quantize_t(xd, br, fmt, slabs=True)
+            assert (host_u8(sq) == host_u8(pq)).all() and (host_u8(fp8.e8m0_plain_rows(se)) == host_u8(pe)).all()
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 512, 512), (200, 300, 1024), (640, 896, 1536), (33, 17, 512)])
+def test_public_mx_product_takes_scale_slabs(M, N, K):
+    """fp8_mx_scaled_mm with both scale arrays in slabs: the result of the plain-row call on the same kernel bit for
+    bit, and the oracle's product within tolerance (exact on these small-integer operands)."""
+    rng = np.random.default_rng(M + N + K)
+    a = orc.encode_array(rng.integers(-3, 4, (M, K)).astype(np.float32), orc.E4M3FN)
+    b = orc.encode_array(rng.integers(-3, 4, (N, K)).astype(np.float32), orc.E4M3FN)
+    # (block scales within a factor of 4 and at most 48 blocks: every partial sum fits the significand in any order)
+    ea = rng.integers(126, 129, (M, K // 32)).astype(np.uint8)
+    eb = rng.integers(126, 129, (N, K // 32)).astype(np.uint8)
+    ad, bd = dev_u8(a), dev_u8(b)
+
+    def slabs(e, spare):
+        rows, nb = e.shape
+        t = torch.full((nb // 16, rows + spare, 16), 0x7F, dtype=torch.uint8, device="cuda")
+        t[:, :rows, :] = torch.from_numpy(np.ascontiguousarray(e.reshape(rows, nb // 16, 16).transpose(1, 0, 2))).cuda()
+        return t
+    want = orc.mx_mm(a, orc.E4M3FN, ea, b, orc.E4M3FN, eb)
+    got_slab = fp8.fp8_mx_scaled_mm(ad, fp8.FP8_E4M3FN, slabs(ea, 3), bd, fp8.FP8_E4M3FN, slabs(eb, 0), fp8.FP8_OUT_FP32)
+    with knobs(MX_VARIANT=1):
+        got_plain = fp8.fp8_mx_scaled_mm(ad, fp8.FP8_E4M3FN, _dev_e(ea), bd, fp8.FP8_E4M3FN, _dev_e(eb), fp8.FP8_OUT_FP32)
+    assert torch.equal(got_slab, got_plain)
+    assert (host_f32(got_slab) == want.out32).all()
+    # one operand in slabs, the other in plain rows: refused
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_mx_scaled_mm(ad, fp8.FP8_E4M3FN, slabs(ea, 0), bd, fp8.FP8_E4M3FN, _dev_e(eb))
+
+
+def test_public_scale_slabs_full_size_forward():
+    """The benchmark's forward product with its scales in slabs, from the public quantizer to the public product:
+    bit-identical to the plain-row route on the same kernel."""
+    wl = si.WORKLOADS[si.BENCH_WORKLOAD]
+    xd, wd = dev_bf16(wl.x()), dev_bf16(wl.w())
+    xq, xe = fp8.fp8_mx_quantize(xd, fp8.FP8_E4M3FN)
+    wq, we = fp8.fp8_mx_quantize(wd, fp8.FP8_E4M3FN)
+    xq2, xe2 = fp8.fp8_mx_quantize(xd, fp8.FP8_E4M3FN, slabs=True)
+    wq2, we2 = fp8.fp8_mx_quantize(wd, fp8.FP8_E4M3FN, slabs=True)
+    assert torch.equal(xq, xq2) and torch.equal(wq, wq2)
+    assert torch.equal(fp8.e8m0_plain_rows(xe2), xe) and torch.equal(fp8.e8m0_plain_rows(we2), we)
+    y_plain = fp8.fp8_mx_scaled_mm(xq, fp8.FP8_E4M3FN, xe, wq, fp8.FP8_E4M3FN, we)
+    y_slab = fp8.fp8_mx_scaled_mm(xq2, fp8.FP8_E4M3FN, xe2, wq2, fp8.FP8_E4M3FN, we2)
+    assert torch.equal(y_plain.view(torch.int16), y_slab.view(torch.int16))
