@@ -367,7 +367,7 @@ hipError_t launch_gemm_fp8(const uint8_t* a, int64_t lda, int fmt_a, const float
 // tiles: the caller then launches them one after the other.
 hipError_t launch_gemm_fp8_pair(const GemmOperands& g1, const GemmOperands& g2, int fmt_a, int fmt_b, int row_a, int row_b,
                                 hipStream_t st) {
-    if (g1.M == 0 || g1.N == 0 || g2.M == 0 || g2.N == 0) return hipErrorNotSupported;
+    if (g1.M == 0 || g1.N == 0 || g2.M == 0 || g2.N == 0 || knob(KNOB_PAIRS) == 0) return hipErrorNotSupported;
     const int v1 = pick_variant(g1.M, g1.N), v2 = pick_variant(g2.M, g2.N);
     if ((v1 != 6 && v1 != 7) || v1 != v2) return hipErrorNotSupported;
     auto reach = [](const GemmOperands& g) {

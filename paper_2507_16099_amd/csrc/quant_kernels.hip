@@ -756,6 +756,7 @@ static hipError_t quant_tensor_pair(const TensorOperand& a, const TensorOperand&
 
 hipError_t launch_quant_tensor_pair(const TensorOperand& a, const TensorOperand& b, int64_t cols, int fmt, int flags,
                                     int transpose, hipStream_t st) {
+    if (knob(KNOB_PAIRS) == 0) return hipErrorNotSupported;
     if (a.rows == 0 || b.rows == 0 || cols == 0) return hipErrorNotSupported;
     return fmt == FMT_E4M3FN ? quant_tensor_pair<FMT_E4M3FN>(a, b, cols, flags, transpose, st)
                              : quant_tensor_pair<FMT_E5M2>(a, b, cols, flags, transpose, st);
@@ -1210,6 +1211,7 @@ Partials partials_of(const ColOperand& o, int64_t cols) { return partials_of(o.f
 hipError_t launch_quant_row_pair(const void* x1, int64_t rows1, int64_t ld1, uint8_t* q1, int64_t ld_q1, float* s1, const void* x2,
                                  int64_t rows2, int64_t ld2, uint8_t* q2, int64_t ld_q2, float* s2, int64_t cols, int fmt,
                                  int flags, hipStream_t st) {
+    if (knob(KNOB_PAIRS) == 0) return hipErrorNotSupported;
     if (rows1 == 0 || rows2 == 0) return hipErrorNotSupported;
     const int64_t nvec = cols / 8;
     const uint16_t *a = static_cast<const uint16_t*>(x1), *b = static_cast<const uint16_t*>(x2);
@@ -1238,6 +1240,7 @@ hipError_t launch_quant_row_pair(const void* x1, int64_t rows1, int64_t ld1, uin
 
 hipError_t launch_quant_row_col_pair(const RowColOperand& a, const RowColOperand* b, int64_t cols, int fmt, int flags,
                                      hipStream_t st) {
+    if (b && knob(KNOB_PAIRS) == 0) return hipErrorNotSupported;
     if (a.rows == 0 || (b && b->rows == 0) || cols == 0) return hipErrorNotSupported;
     const Partials pa = partials_of(a, cols), pb = b ? partials_of(*b, cols) : Partials{nullptr, 0, false};
     int64_t Ga = 0, Gb = 0;
@@ -1254,6 +1257,7 @@ hipError_t launch_quant_row_col_pair(const RowColOperand& a, const RowColOperand
 }
 
 hipError_t launch_quant_col_t_pair(const ColOperand& a, const ColOperand& b, int64_t cols, int fmt, int flags, hipStream_t st) {
+    if (knob(KNOB_PAIRS) == 0) return hipErrorNotSupported;
     if (a.rows == 0 || b.rows == 0 || cols == 0) return hipErrorNotSupported;
     const Partials pa = partials_of(a, cols), pb = partials_of(b, cols);
     const int64_t Ga = colmax_partial_blocks(a.rows, cols, pa.room), Gb = colmax_partial_blocks(b.rows, cols, pb.room);
@@ -1272,6 +1276,7 @@ hipError_t launch_quant_col_t_pair(const ColOperand& a, const ColOperand& b, int
 
 hipError_t launch_quant_bwd_rowwise(const RowColOperand& g, int64_t cols_g, int fmt_g, const ColOperand& w, const ColOperand& x,
                                     int64_t cols_wx, int fmt_wx, int flags, hipStream_t st) {
+    if (knob(KNOB_PAIRS) == 0) return hipErrorNotSupported;
     if (g.rows == 0 || w.rows == 0 || x.rows == 0 || cols_g == 0 || cols_wx == 0) return hipErrorNotSupported;
     // everything is checked before the first launch, so that "not suited" leaves nothing half done
     const Partials pg = partials_of(g, cols_g), pw = partials_of(w, cols_wx), px = partials_of(x, cols_wx);

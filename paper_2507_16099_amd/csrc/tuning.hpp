@@ -22,6 +22,7 @@ enum Knob {
     KNOB_GEMM_STREAM,       // persistent LDS-DMA kernel: 0 = never, 2 = wherever it fits, >= 8 = wherever it fits, with that many workgroups
     KNOB_GEMM_TILE_M,       // persistent kernel: 256, 224 or 192 forces the tile height
     KNOB_GEMM_BIG_FROM,     // number of 128 x 128 tiles from which a product goes to the 256 x 256 kernels
+    KNOB_PAIRS,             // 0 = no shared launches: every tensor of a linear step quantized, every product launched, by itself
     KNOB_COUNT
 };
 

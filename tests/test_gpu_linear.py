@@ -537,3 +537,37 @@ def test_full_size_grad_weight_hp_sampled_rows():
     err = orc.rel_frobenius(si.bf16_bits_to_f32(got), si.bf16_bits_to_f32(want16))
     assert err <= TOL, err
     assert float((got == want16).mean()) > 0.98
+
+
+# ------------------------------------------------ shared launches
+
+@pytest.mark.parametrize("M,K,N", [(256, 512, 512), (1024, 1024, 1024), (2048, 1008, 528), (4096, 1024, 512), (1536, 2048, 4096)])
+@pytest.mark.parametrize("recipe", ["tensorwise", "rowwise", "rowwise_pow2"])
+def test_shared_launches_change_no_bit(M, K, N, recipe):
+    """Inside the linear entry points the quantizations of two tensors of the same kind, and the two small products of a
+    backward step, share launches; small tensors have their column scales derived inside the transposing cast.  With the
+    switch PAIRS = 0 every tensor is quantized and every product launched by itself, through the kernels that the
+    single-tensor entry points use (compared with the oracle elsewhere): outputs must agree bit for bit, with and
+    without the forward's saved copies."""
+    base = "c3_llama3_8b_qkv_tensorwise" if recipe.startswith("tensorwise") else "c2_llama3_8b_ffn_rowwise"
+    wl = si.scaled_down(si.WORKLOADS[base], M, K, N)
+    xd, wd, dyd = dev_bf16(wl.x()), dev_bf16(wl.w()), dev_bf16(wl.dy())
+    gran = fp8.FP8_TENSOR if recipe.startswith("tensorwise") else fp8.FP8_ROW
+    fl = fp8.FP8_POW2_SCALE if recipe.endswith("pow2") else 0
+
+    def run():
+        outs = []
+        plain = fp8.Recipe(gran=gran, flags=fl)
+        outs.append(fp8.fp8_linear_fwd(xd, wd, plain))
+        outs += list(fp8.fp8_linear_bwd(dyd, xd, wd, plain))
+        saved = fp8.Recipe(gran=gran, flags=fl | fp8.FP8_SAVE_FOR_BWD)
+        ws = torch.empty(fp8.fp8_linear_workspace_bytes(M, K, N, saved, True), dtype=torch.uint8, device="cuda")
+        outs.append(fp8.fp8_linear_fwd(xd, wd, saved, workspace=ws))
+        outs += list(fp8.fp8_linear_bwd(dyd, (M, K), (N, K), saved, workspace=ws))
+        return [o.view(torch.int16).clone() for o in outs]
+
+    shared = run()
+    with knobs(PAIRS=0):
+        single = run()
+    for a_, b_ in zip(shared, single):
+        assert torch.equal(a_, b_)
