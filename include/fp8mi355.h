@@ -205,6 +205,10 @@ int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N
  * per-column operands are written transposed so that every GEMM contracts
  * over a contiguous axis.  Tensorwise: one scale per tensor, only the layouts
  * change.  dx and dw are bfloat16, dense; either may be NULL to skip it.
+ * K and N multiples of 16; M (tokens) arbitrary: the transposed operands of dW,
+ * whose contraction axis is M, get rows padded to 16 bytes with zero codes
+ * inside the workspace (token counts on the 16-byte grid take the faster
+ * quantization kernels).
  */
 int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int64_t K, int64_t N,
                    const fp8_recipe* recipe, void* dx, void* dw, void* workspace,
@@ -216,7 +220,7 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
  * output, dy [M, N] the gradient arriving at it.  The gradient of the linear layer's
  * output,  dz = dy * y * (1 - y)  (binary32, one operation at a time, rounded to
  * bfloat16), takes the place of dY in fp8_linear_bwd; with the rowwise recipe and
- * M >= 1024, N a multiple of 8 in [512, 32768] it is formed inside the two
+ * M >= 1024 a multiple of 16, N a multiple of 8 in [512, 32768] it is formed inside the two
  * quantization passes and never stored, otherwise it is written once into the
  * workspace.  Everything else as fp8_linear_bwd (including FP8_SAVE_FOR_BWD, where
  * the shared workspace must then have fp8_linear_bwd_sigmoid_workspace_bytes bytes).

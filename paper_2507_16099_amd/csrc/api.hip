@@ -125,6 +125,10 @@ int quantize_row_col_impl(const void* x, int64_t rows, int64_t cols, int64_t ld,
 }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+// Leading dimension of the operands whose contraction axis is the token axis M (dY^T [N, M] and X^T [K, M] of the
+// weight gradient): rows of 16-byte multiples for the products' loads.  The pad columns hold zero codes (the buffers
+// are cleared before the transposing casts write the valid part), so the product may contract over the padded length.
+int64_t pad16(int64_t v) { return (v + 15) / 16 * 16; }
 
 // part: per-block maxima of the tensorwise amax pass, room for two tensors (a pair shares its launches; otherwise one
 // tensor at a time: the casts consume them in stream order)
@@ -157,9 +161,9 @@ BwdPlan plan_bwd(int64_t M, int64_t K, int64_t N, int gran) {
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     const bool row = gran == FP8_ROW;
     p.gq = take((size_t)M * N);   // dY codes, [M, N]
-    p.gqt = take((size_t)M * N);  // dY codes, [N, M]
+    p.gqt = take((size_t)pad16(M) * N);  // dY codes, [N, M] (rows padded to multiples of 16 bytes)
     p.wt = take((size_t)K * N);   // W codes,  [K, N]
-    p.xt = take((size_t)K * M);   // X codes,  [K, M]
+    p.xt = take((size_t)K * pad16(M));   // X codes,  [K, M] (rows padded likewise)
     p.sg = take(sizeof(float) * (row ? (size_t)M : 1));
     p.sgt = take(sizeof(float) * (row ? (size_t)N : 1));
     p.swt = take(sizeof(float) * (row ? (size_t)K : 1));
@@ -174,18 +178,19 @@ BwdPlan plan_bwd(int64_t M, int64_t K, int64_t N, int gran) {
 
 // The two products of a backward step from quantized operands: dX[M, K] = dY W (contraction over N) and
 // dW[N, K] = dY^T X (contraction over M).  sg / sgt: scales of dY for the first / second product (the same
-// pointer for tensorwise scaling).  Small products share one launch.
+// pointer for tensorwise scaling).  Small products share one launch.  Mp: padded token count, the leading dimension
+// of gqt and xt and the contraction length of the second product.
 int grad_gemms(const fp8_recipe* r, int row, const uint8_t* gq, const float* sg, const uint8_t* wt, const float* swt,
-               const uint8_t* gqt, const float* sgt, const uint8_t* xt, const float* sxt, int64_t M, int64_t K, int64_t N,
-               void* dx, void* dw, hipStream_t st) {
+               const uint8_t* gqt, const float* sgt, const uint8_t* xt, const float* sxt, int64_t M, int64_t Mp, int64_t K,
+               int64_t N, void* dx, void* dw, hipStream_t st) {
     if (dx && dw && r->fmt_w == r->fmt_x) {
-        const fp8k::GemmOperands g1{gq, N, sg, wt, N, swt, M, K, N, dx, K}, g2{gqt, M, sgt, xt, M, sxt, N, K, M, dw, K};
+        const fp8k::GemmOperands g1{gq, N, sg, wt, N, swt, M, K, N, dx, K}, g2{gqt, Mp, sgt, xt, Mp, sxt, N, K, Mp, dw, K};
         const hipError_t e = fp8k::launch_gemm_fp8_pair(g1, g2, r->fmt_dy, r->fmt_w, row, row, st);
         if (e == hipSuccess) return FP8_OK;
         if (e != hipErrorNotSupported) return hip_fail(e, "gemm_fp8_pair");
     }
     if (dx) FP8_TRY(fp8k::launch_gemm_fp8(gq, N, r->fmt_dy, sg, row, wt, N, r->fmt_w, swt, row, M, K, N, dx, K, 0, st));
-    if (dw) FP8_TRY(fp8k::launch_gemm_fp8(gqt, M, r->fmt_dy, sgt, row, xt, M, r->fmt_x, sxt, row, N, K, M, dw, K, 0, st));
+    if (dw) FP8_TRY(fp8k::launch_gemm_fp8(gqt, Mp, r->fmt_dy, sgt, row, xt, Mp, r->fmt_x, sxt, row, N, K, Mp, dw, K, 0, st));
     return FP8_OK;
 }
 
@@ -205,9 +210,10 @@ int check_linear_dims(const char* fn, int64_t M, int64_t K, int64_t N, bool bwd)
         return fail(FP8_ERR_SHAPE, "%s: M=%lld K=%lld N=%lld out of range", fn, (long long)M, (long long)K, (long long)N);
     if (K % 16 != 0) return fail(FP8_ERR_SHAPE, "%s: K=%lld must be a multiple of 16", fn, (long long)K);
     if (N % 8 != 0) return fail(FP8_ERR_SHAPE, "%s: N=%lld must be a multiple of 8 (dense bfloat16 rows)", fn, (long long)N);
-    if (bwd && (M % 16 != 0 || N % 16 != 0))
-        return fail(FP8_ERR_SHAPE, "%s: backward contracts over M and N: M=%lld, N=%lld must be multiples of 16", fn,
-                    (long long)M, (long long)N);
+    if (bwd && N % 16 != 0)
+        return fail(FP8_ERR_SHAPE, "%s: the backward contracts over N: N=%lld must be a multiple of 16", fn, (long long)N);
+    if (bwd && M > kMaxDim - 15)
+        return fail(FP8_ERR_SHAPE, "%s: M=%lld, padded to a multiple of 16, is out of range", fn, (long long)M);
     return FP8_OK;
 }
 
@@ -374,18 +380,20 @@ int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N
         uint8_t* wsf = wsb + b.total;
         const int fl = recipe->flags & FP8_POW2_SCALE;
         float *sxt = reinterpret_cast<float*>(wsb + b.sxt), *swt = reinterpret_cast<float*>(wsb + b.swt);
+        const int64_t Mp = pad16(M);
+        if (Mp != M) FP8_TRY(fp8k::launch_fill_u32(reinterpret_cast<uint32_t*>(wsb + b.xt), K * Mp / 4, 0u, st));   // zero codes in the pad columns of X^T
         if (recipe->gran == FP8_TENSOR) {
             float* part = reinterpret_cast<float*>(wsf + p.part);
             bool pair_done = false;
             if (recipe->fmt_x == recipe->fmt_w && K > 0) {   // both tensors in two launches
-                const fp8k::TensorOperand ox{x, M, wsb + b.xt, M, wsf + p.xq, K, sxt, part};
+                const fp8k::TensorOperand ox{x, M, wsb + b.xt, Mp, wsf + p.xq, K, sxt, part};
                 const fp8k::TensorOperand ow{w, N, wsb + b.wt, N, wsf + p.wq, K, swt, part + fp8k::TENSOR_PARTIALS};
                 const hipError_t e = fp8k::launch_quant_tensor_pair(ox, ow, K, recipe->fmt_x, fl, 1, st);
                 if (e == hipSuccess) pair_done = true;
                 else if (e != hipErrorNotSupported) return hip_fail(e, "quant_tensor_pair");
             }
             if (!pair_done) {
-                if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | FP8_TRANSPOSE_OUT, wsb + b.xt, M, wsf + p.xq, K, sxt, st, part)) return rc;
+                if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | FP8_TRANSPOSE_OUT, wsb + b.xt, Mp, wsf + p.xq, K, sxt, st, part)) return rc;
                 if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | FP8_TRANSPOSE_OUT, wsb + b.wt, N, wsf + p.wq, K, swt, st, part)) return rc;
             }
             FP8_TRY(fp8k::launch_gemm_fp8(wsf + p.xq, K, recipe->fmt_x, sxt, 0, wsf + p.wq, K, recipe->fmt_w, swt, 0, M, N, K, y, N, 0, st));
@@ -395,7 +403,7 @@ int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N
         bool done = false;
         if (!(recipe->flags & FP8_GRAD_WEIGHT_HP) && recipe->fmt_x == recipe->fmt_w) {
             // X and W the same way: twin launches, three (small tensors: two) instead of six
-            const fp8k::RowColOperand ox{x, M, K, wsf + p.xq, K, sx, wsb + b.xt, M, sxt, wsf + p.fold_x};
+            const fp8k::RowColOperand ox{x, M, K, wsf + p.xq, K, sx, wsb + b.xt, Mp, sxt, wsf + p.fold_x};
             const fp8k::RowColOperand ow{w, N, K, wsf + p.wq, K, sw, wsb + b.wt, N, swt, wsf + p.fold_w};
             const hipError_t e = fp8k::launch_quant_row_col_pair(ox, &ow, K, recipe->fmt_x, fl, st);
             if (e == hipSuccess) done = true;
@@ -405,7 +413,7 @@ int fp8_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int64_t N
             if (recipe->flags & FP8_GRAD_WEIGHT_HP) {   // dW will come from the bfloat16 X: no fp8 copy of X to keep
                 if (int rc = quantize_impl(x, M, K, K, FP8_ROW, recipe->fmt_x, fl, wsf + p.xq, K, nullptr, 0, sx, st)) return rc;
             } else {
-                if (int rc = quantize_row_col_impl(x, M, K, K, recipe->fmt_x, fl, wsf + p.xq, K, sx, wsb + b.xt, M, sxt, st)) return rc;
+                if (int rc = quantize_row_col_impl(x, M, K, K, recipe->fmt_x, fl, wsf + p.xq, K, sx, wsb + b.xt, Mp, sxt, st)) return rc;
             }
             if (int rc = quantize_row_col_impl(w, N, K, K, recipe->fmt_w, fl, wsf + p.wq, K, sw, wsb + b.wt, N, swt, st)) return rc;
         }
@@ -474,19 +482,24 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
         dw = nullptr;
         if (!dx) return FP8_OK;
     }
+    const int64_t Mp = pad16(M);
+    if (dw && Mp != M) {   // zero codes in the pad columns of dY^T and (unless the forward left it) X^T
+        FP8_TRY(fp8k::launch_fill_u32(reinterpret_cast<uint32_t*>(gqt), N * Mp / 4, 0u, st));
+        if (!saved) FP8_TRY(fp8k::launch_fill_u32(reinterpret_cast<uint32_t*>(xt), K * Mp / 4, 0u, st));
+    }
 
     if (recipe->gran == FP8_TENSOR) {
         // one scale per tensor; dY is converted once into both layouts
         float* part = reinterpret_cast<float*>(ws + p.part);
         uint8_t* plain = dx ? gq : nullptr;
         if (dw) {
-            if (int rc = quantize_impl(dy, M, N, N, FP8_TENSOR, recipe->fmt_dy, fl | T, gqt, M, plain, N, sg, st, part)) return rc;
+            if (int rc = quantize_impl(dy, M, N, N, FP8_TENSOR, recipe->fmt_dy, fl | T, gqt, Mp, plain, N, sg, st, part)) return rc;
         } else {
             if (int rc = quantize_impl(dy, M, N, N, FP8_TENSOR, recipe->fmt_dy, fl, gq, N, nullptr, 0, sg, st, part)) return rc;
         }
         bool pair_done = false;
         if (dx && dw && !saved && recipe->fmt_w == recipe->fmt_x) {   // W and X in two launches
-            const fp8k::TensorOperand ow{w, N, wt, N, nullptr, 0, swt, part}, ox{x, M, xt, M, nullptr, 0, sxt, part + fp8k::TENSOR_PARTIALS};
+            const fp8k::TensorOperand ow{w, N, wt, N, nullptr, 0, swt, part}, ox{x, M, xt, Mp, nullptr, 0, sxt, part + fp8k::TENSOR_PARTIALS};
             const hipError_t e = fp8k::launch_quant_tensor_pair(ow, ox, K, recipe->fmt_w, fl, 1, st);
             if (e == hipSuccess) pair_done = true;
             else if (e != hipErrorNotSupported) return hip_fail(e, "quant_tensor_pair");
@@ -494,8 +507,8 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
         if (dx && !saved && !pair_done)
             if (int rc = quantize_impl(w, N, K, K, FP8_TENSOR, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st, part)) return rc;
         if (dw && !saved && !pair_done)
-            if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st, part)) return rc;
-        return grad_gemms(recipe, 0, gq, sg, wt, swt, gqt, sg, xt, sxt, M, K, N, dx, dw, st);
+            if (int rc = quantize_impl(x, M, K, K, FP8_TENSOR, recipe->fmt_x, fl | T, xt, Mp, nullptr, 0, sxt, st, part)) return rc;
+        return grad_gemms(recipe, 0, gq, sg, wt, swt, gqt, sg, xt, sxt, M, Mp, K, N, dx, dw, st);
     }
     // rowwise: every operand re-quantized along the contraction axis of its GEMM
     // (dX = dY W contracts over N, dW = dY^T X over M).  All quantizations first,
@@ -504,36 +517,37 @@ int fp8_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int6
     if (both && !saved && recipe->fmt_w == recipe->fmt_x) {
         // all three tensors in five launches: dY's rowwise pass (which also gathers its column maxima), the column
         // maxima of W and X together, one launch for every column scale, two for the transposing casts
-        const fp8k::RowColOperand og{dy, M, N, gq, N, sg, gqt, M, sgt, ws + p.fold_g};
-        const fp8k::ColOperand ow{w, N, K, wt, N, swt, ws + p.fold_w}, ox{x, M, K, xt, M, sxt, ws + p.fold_x};
+        const fp8k::RowColOperand og{dy, M, N, gq, N, sg, gqt, Mp, sgt, ws + p.fold_g};
+        const fp8k::ColOperand ow{w, N, K, wt, N, swt, ws + p.fold_w}, ox{x, M, K, xt, Mp, sxt, ws + p.fold_x};
         const hipError_t e = fp8k::launch_quant_bwd_rowwise(og, N, recipe->fmt_dy, ow, ox, K, recipe->fmt_w, fl, st);
-        if (e == hipSuccess) return grad_gemms(recipe, 1, gq, sg, wt, swt, gqt, sgt, xt, sxt, M, K, N, dx, dw, st);
+        if (e == hipSuccess) return grad_gemms(recipe, 1, gq, sg, wt, swt, gqt, sgt, xt, sxt, M, Mp, K, N, dx, dw, st);
         if (e != hipErrorNotSupported) return hip_fail(e, "quant_bwd_rowwise");
     }
     if (both) {   // dY along N (rows) and along M (columns, transposed) from two reads instead of three
-        const fp8k::RowColOperand og{dy, M, N, gq, N, sg, gqt, M, sgt, ws + p.fold_g};
+        const fp8k::RowColOperand og{dy, M, N, gq, N, sg, gqt, Mp, sgt, ws + p.fold_g};
         const hipError_t e = fp8k::launch_quant_row_col_pair(og, nullptr, N, recipe->fmt_dy, fl, st);
         if (e == hipErrorNotSupported) {
-            if (int rc = quantize_row_col_impl(dy, M, N, N, recipe->fmt_dy, fl, gq, N, sg, gqt, M, sgt, st)) return rc;
+            if (int rc = quantize_row_col_impl(dy, M, N, N, recipe->fmt_dy, fl, gq, N, sg, gqt, Mp, sgt, st)) return rc;
         } else if (e != hipSuccess) {
             return hip_fail(e, "quant_row_col");
         }
     } else if (dx) {
         if (int rc = quantize_impl(dy, M, N, N, FP8_ROW, recipe->fmt_dy, fl, gq, N, nullptr, 0, sg, st)) return rc;
     } else {
-        if (int rc = quantize_impl(dy, M, N, N, FP8_COL, recipe->fmt_dy, fl | T, gqt, M, nullptr, 0, sgt, st)) return rc;
+        if (int rc = quantize_impl(dy, M, N, N, FP8_COL, recipe->fmt_dy, fl | T, gqt, Mp, nullptr, 0, sgt, st)) return rc;
     }
     if (dx && !saved)
         if (int rc = quantize_impl(w, N, K, K, FP8_COL, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st)) return rc;
     if (dw && !saved)
-        if (int rc = quantize_impl(x, M, K, K, FP8_COL, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st)) return rc;
-    return grad_gemms(recipe, 1, gq, sg, wt, swt, gqt, sgt, xt, sxt, M, K, N, dx, dw, st);
+        if (int rc = quantize_impl(x, M, K, K, FP8_COL, recipe->fmt_x, fl | T, xt, Mp, nullptr, 0, sxt, st)) return rc;
+    return grad_gemms(recipe, 1, gq, sg, wt, swt, gqt, sgt, xt, sxt, M, Mp, K, N, dx, dw, st);
 }
 
 namespace {
 // shapes and recipes for which the gradient through the sigmoid is quantized without being materialised
 bool sigmoid_bwd_fused(int64_t M, int64_t N, const fp8_recipe* r) {
-    return r->gran == FP8_ROW && !(r->flags & FP8_GRAD_WEIGHT_HP) && N % 8 == 0 && N / 8 >= 64 && N / 8 <= 4096 && M >= 1024;
+    return r->gran == FP8_ROW && !(r->flags & FP8_GRAD_WEIGHT_HP) && N % 8 == 0 && N / 8 >= 64 && N / 8 <= 4096 && M >= 1024 &&
+           M % 16 == 0;   // (a token count off the 16-byte grid takes the padded buffers of fp8_linear_bwd)
 }
 }  // namespace
 
@@ -587,7 +601,7 @@ int fp8_linear_bwd_sigmoid(const void* dy, const void* y, const void* x, const v
         if (int rc = quantize_impl(w, N, K, K, FP8_COL, recipe->fmt_w, fl | T, wt, N, nullptr, 0, swt, st)) return rc;
     if (dw && !saved)
         if (int rc = quantize_impl(x, M, K, K, FP8_COL, recipe->fmt_x, fl | T, xt, M, nullptr, 0, sxt, st)) return rc;
-    return grad_gemms(recipe, 1, gq, sg, wt, swt, gqt, sgt, xt, sxt, M, K, N, dx, dw, st);
+    return grad_gemms(recipe, 1, gq, sg, wt, swt, gqt, sgt, xt, sxt, M, M, K, N, dx, dw, st);
 }
 
 int fp8_grad_weight_hp(const void* dy, const void* x, int64_t M, int64_t K, int64_t N, void* dw, void* stream) {

@@ -158,7 +158,7 @@ def test_workspace_too_small_and_bad_shapes_are_rejected():
     with pytest.raises(fp8.Fp8Error):
         fp8.fp8_linear_workspace_bytes(32, 60, 48, r, False)      # K not a multiple of 16
     with pytest.raises(fp8.Fp8Error):
-        fp8.fp8_linear_workspace_bytes(40, 64, 48, r, True)       # M not a multiple of 16 in backward
+        fp8.fp8_linear_workspace_bytes(32, 64, 40, r, True)       # N not a multiple of 16 in backward
 
 
 def test_full_size_llama_ffn_fwd_bwd_sampled():
@@ -571,3 +571,37 @@ def test_shared_launches_change_no_bit(M, K, N, recipe):
         single = run()
     for a_, b_ in zip(shared, single):
         assert torch.equal(a_, b_)
+
+
+@pytest.mark.parametrize("M,K,N", [(40, 64, 48), (200, 256, 272), (1000, 1024, 512), (2056, 512, 1024), (4100, 1024, 768)])
+@pytest.mark.parametrize("recipe", ["tensorwise", "rowwise", "rowwise_pow2", "rowwise_gw_hp"])
+def test_backward_with_a_token_count_off_the_16_byte_grid(M, K, N, recipe):
+    """The weight gradient contracts over the tokens; its transposed operands get rows padded to 16 bytes with zero
+    codes inside the workspace, so any M is accepted.  Stateless and with the forward's saved copies: same bits, and the
+    oracle's results."""
+    base = "c3_llama3_8b_qkv_tensorwise" if recipe.startswith("tensorwise") else "c2_llama3_8b_ffn_rowwise"
+    wl = si.scaled_down(si.WORKLOADS[base], M, K, N)
+    x, w, dy = wl.x(), wl.w(), wl.dy()
+    xd, wd, dyd = dev_bf16(x), dev_bf16(w), dev_bf16(dy)
+    pow2, hp = recipe.endswith("pow2"), recipe.endswith("gw_hp")
+    gran = fp8.FP8_TENSOR if recipe.startswith("tensorwise") else fp8.FP8_ROW
+    fl = (fp8.FP8_POW2_SCALE if pow2 else 0) | (fp8.FP8_GRAD_WEIGHT_HP if hp else 0)
+    plain = fp8.Recipe(gran=gran, flags=fl)
+    saved = fp8.Recipe(gran=gran, flags=fl | fp8.FP8_SAVE_FOR_BWD)
+    y0 = fp8.fp8_linear_fwd(xd, wd, plain)
+    dx0, dw0 = fp8.fp8_linear_bwd(dyd, xd, wd, plain)
+    ws = torch.full((fp8.fp8_linear_workspace_bytes(M, K, N, saved, True),), 0x7E, dtype=torch.uint8, device="cuda")   # (garbage the pads must not keep)
+    y1 = fp8.fp8_linear_fwd(xd, wd, saved, workspace=ws)
+    dx1, dw1 = fp8.fp8_linear_bwd(dyd, xd if hp else (M, K), (N, K), saved, workspace=ws)
+    for a_, b_ in ((y0, y1), (dx0, dx1), (dw0, dw1)):
+        assert torch.equal(a_.view(torch.int16), b_.view(torch.int16))
+    o = orc.Recipe(gran=orc.TENSOR if gran == fp8.FP8_TENSOR else orc.ROW, pow2=pow2)
+    _cmp(y1, orc.linear_fwd(x, w, o)[0])
+    _cmp(dx1, orc.linear_bwd_dx(dy, w, o)[0])
+    if hp:
+        _, want16 = orc.linear_bwd_dw_hp(dy, x)
+        assert orc.rel_frobenius(si.bf16_bits_to_f32(host_bf16_bits(dw1)), si.bf16_bits_to_f32(want16)) <= TOL
+    else:
+        _cmp(dw1, orc.linear_bwd_dw(dy, x, o)[0])
+    none, only_dw = fp8.fp8_linear_bwd(dyd, xd, wd, plain, need_dx=False)
+    assert none is None and torch.equal(only_dw.view(torch.int16), dw0.view(torch.int16))
