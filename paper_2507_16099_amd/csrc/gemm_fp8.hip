@@ -210,12 +210,27 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_tn_kernel(TnPr
     // conditions.
     const int ksteps = (K + BK - 1) / BK;
     const int kpad = (ksteps + PD - 1) / PD * PD;
+    // the scales of this tile's rows and columns are requested now, so that their latency lies under the K loop
+    // (problems of few tiles are bound by such fixed costs: a trip to memory is about as long as two K steps)
+    float sa_raw[FM], sb_raw[NG][16];
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        const int m = m0 + wm0 + 16 * i + (lane & 15);
+        sa_raw[i] = row_a ? (m < M ? scale_a[m] : 1.0f) : scale_a[0];
+    }
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int n = n0 + wn0 + 64 * g + 16 * (lane >> 4) + e;
+            sb_raw[g][e] = row_b ? (n < N ? scale_b[n] : 1.0f) : scale_b[0];
+        }
     if (ksteps > 0) {
-        gload(0, ra[0], rb[0]);
+        // all PD register sets are requested before the first one is awaited (loads return in issue order)
+#pragma unroll
+        for (int s_ = 0; s_ < PD; ++s_) gload(s_ * BK, ra[s_], rb[s_]);
         lstore(0, ra[0], rb[0]);
         __syncthreads();
-#pragma unroll
-        for (int s_ = 1; s_ < PD; ++s_) gload(s_ * BK, ra[s_], rb[s_]);
         for (int kb = 0; kb < kpad; kb += PD) {
 #pragma unroll
             for (int u = 0; u < PD; ++u) {
@@ -229,19 +244,17 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_fp8_tn_kernel(TnPr
     }
 
     // ---- epilogue: (acc * 1/sa) * 1/sb, round, store 16 consecutive n per lane
-    const float inv_a_t = row_a ? 0.f : 1.0f / scale_a[0];
-    const float inv_b_t = row_b ? 0.f : 1.0f / scale_b[0];
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
         const int nb = n0 + wn0 + 64 * g + 16 * (lane >> 4);
         float inv_b[16];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) inv_b[e] = row_b ? ((nb + e < N) ? 1.0f / scale_b[nb + e] : 0.f) : inv_b_t;
+        for (int e = 0; e < 16; ++e) inv_b[e] = (nb + e < N) ? 1.0f / sb_raw[g][e] : 0.f;
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
             const int m = m0 + wm0 + 16 * i + (lane & 15);
             if (m >= M || nb >= N) continue;
-            const float inv_a = row_a ? 1.0f / scale_a[m] : inv_a_t;
+            const float inv_a = 1.0f / sa_raw[i];
             float v[16];
 #pragma unroll
             for (int t = 0; t < 4; ++t)
@@ -296,7 +309,7 @@ static hipError_t launch_variant(const GemmOperands& g1, const GemmOperands* g2,
 template <int FA, int FB, bool OUT_F32>
 static hipError_t launch_fmt(int variant, const GemmOperands& g1, const GemmOperands* g2, int row_a, int row_b, hipStream_t st) {
     if (variant == 6) return launch_variant<64, 64, 4, 1, FA, FB, OUT_F32, 4>(g1, g2, row_a, row_b, st);
-    if (variant == 7) return launch_variant<128, 128, 2, 2, FA, FB, OUT_F32, 3>(g1, g2, row_a, row_b, st);
+    if (variant == 7) return launch_variant<128, 128, 2, 2, FA, FB, OUT_F32, 4>(g1, g2, row_a, row_b, st);
     return launch_variant<128, 128, 2, 2, FA, FB, OUT_F32>(g1, g2, row_a, row_b, st);
 }
 
@@ -322,7 +335,8 @@ static hipError_t launch_fmt(int variant, const GemmOperands& g1, const GemmOper
 // Switches (tuning and test aid): GEMM_BIG_FROM moves the tile count from which the 256 x 256 kernels are used;
 // GEMM_VARIANT forces a kernel: 0 = 128x128 / 4 waves (register-staged; also the fallback where the 32-bit
 // offsets of the others do not reach), 4 = 256 x 256, 5 = few-row kernel (only where M <= 64), 6 = 64x64 / 4 waves
-// with loads 4 steps ahead, 7 = 128x128 / 4 waves with loads 3 steps ahead (both register-staged through buffer loads).
+// with loads 4 steps ahead, 7 = 128x128 / 4 waves likewise (both register-staged through buffer loads; eight steps ahead
+// measured 5-35 % slower on the small tile, three steps ahead 4-6 % slower on the large one).
 static int pick_variant(int64_t M, int64_t N) {
     if (const int v = knob(KNOB_GEMM_VARIANT); v == 0 || (v >= 4 && v <= 7)) return v;
     if (M <= 32) return 5;
