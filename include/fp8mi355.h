@@ -333,9 +333,11 @@ int fp8_layernorm_quantize(const void* x, int64_t rows, int64_t cols, int64_t ld
  *   dot product over blocks of the contracted index, so each operand is
  *   re-quantized from its bfloat16 original with the blocks along that product's
  *   contraction axis: dY along N and W^T along N for dX, dY^T along M and X^T
- *   along M for dW.  M % 128 == 0, N % 128 == 0, K % 8 == 0; dy [M, N], x [M, K],
- *   w [N, K] dense bfloat16; workspace of fp8_mx_linear_bwd_workspace_bytes bytes,
- *   256-byte aligned.
+ *   along M for dW.  M % 32 == 0, N % 32 == 0 (whole blocks along both contraction
+ *   axes), K % 8 == 0; dy [M, N], x [M, K], w [N, K] dense bfloat16; workspace of
+ *   fp8_mx_linear_bwd_workspace_bytes bytes, 256-byte aligned.  (The products step
+ *   through 128 contracted elements at a time: inside the workspace the contraction
+ *   axes are padded to multiples of 128 with zero codes.)
  *
  * Layout of an array of E8M0 scale bytes (every ld_e* argument of the MX and blockwise
  * entry points): R scale rows of B = (contracted length) / 32 bytes.

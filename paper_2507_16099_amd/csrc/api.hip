@@ -942,27 +942,33 @@ int fp8_block_linear_fwd(const void* x, const void* w, int64_t M, int64_t K, int
 namespace {
 // workspace of the MX backward: the four re-quantized operands and their block scales
 struct MxBwdPlan { size_t dyq, dye, wtq, wte, dytq, dyte, xtq, xte, total; };
+// The products contract over 128 bytes per step: the operands' contraction axes (N for dX, M for dW) are padded to
+// multiples of 128 inside the workspace, with zero codes and zero scale bytes in the pad (cleared before the
+// quantizers write the valid part), so the products may run over the padded lengths.
+int64_t pad128(int64_t v) { return (v + 127) / 128 * 128; }
 MxBwdPlan plan_mx_bwd(int64_t M, int64_t K, int64_t N) {
     MxBwdPlan p{};
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
-    p.dyq = take((size_t)M * N);
-    p.dye = take((size_t)M * (N / 32));
-    p.wtq = take((size_t)K * N);
-    p.wte = take((size_t)K * (N / 32));
-    p.dytq = take((size_t)N * M);
-    p.dyte = take((size_t)N * (M / 32));
-    p.xtq = take((size_t)K * M);
-    p.xte = take((size_t)K * (M / 32));
+    const size_t Mp = (size_t)pad128(M), Np = (size_t)pad128(N);
+    p.dyq = take((size_t)M * Np);
+    p.dye = take((size_t)M * (Np / 32));
+    p.wtq = take((size_t)K * Np);
+    p.wte = take((size_t)K * (Np / 32));
+    p.dytq = take((size_t)N * Mp);
+    p.dyte = take((size_t)N * (Mp / 32));
+    p.xtq = take((size_t)K * Mp);
+    p.xte = take((size_t)K * (Mp / 32));
     p.total = o;
     return p;
 }
-int check_mx_bwd_dims(const char* fn, int64_t M, int64_t K, int64_t N) {
-    if (M < 0 || K < 0 || N < 0 || M > kMaxDim || K > kMaxDim || N > kMaxDim)
+// granule: what M and N must be multiples of - the block of 32 for MX, the tile of 128 for the blockwise recipe
+int check_mx_bwd_dims(const char* fn, int64_t M, int64_t K, int64_t N, int granule) {
+    if (M < 0 || K < 0 || N < 0 || M > kMaxDim - 127 || K > kMaxDim || N > kMaxDim - 127)
         return fail(FP8_ERR_SHAPE, "%s: M=%lld K=%lld N=%lld out of range", fn, (long long)M, (long long)K, (long long)N);
-    if (M % 128 != 0 || N % 128 != 0)
-        return fail(FP8_ERR_SHAPE, "%s: the backward contracts over M and N: M=%lld, N=%lld must be multiples of 128", fn,
-                    (long long)M, (long long)N);
+    if (M % granule != 0 || N % granule != 0)
+        return fail(FP8_ERR_SHAPE, "%s: the backward contracts over M and N: M=%lld, N=%lld must be multiples of %d", fn,
+                    (long long)M, (long long)N, granule);
     if (K % 8 != 0) return fail(FP8_ERR_SHAPE, "%s: K=%lld must be a multiple of 8 (dense bfloat16 rows)", fn, (long long)K);
     return FP8_OK;
 }
@@ -970,7 +976,7 @@ int check_mx_bwd_dims(const char* fn, int64_t M, int64_t K, int64_t N) {
 
 size_t fp8_mx_linear_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     g_err[0] = 0;
-    if (check_mx_bwd_dims("fp8_mx_linear_bwd_workspace_bytes", M, K, N)) return 0;
+    if (check_mx_bwd_dims("fp8_mx_linear_bwd_workspace_bytes", M, K, N, 32)) return 0;
     const size_t t = plan_mx_bwd(M, K, N).total;
     return t ? t : 256;
 }
@@ -980,7 +986,7 @@ int fp8_mx_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, i
     g_err[0] = 0;
     const char* fn = "fp8_mx_linear_bwd";
     if (!fmt_ok(fmt_dy) || !fmt_ok(fmt_x) || !fmt_ok(fmt_w)) return fail(FP8_ERR_ENUM, "%s: unknown fp8 format", fn);
-    if (int rc = check_mx_bwd_dims(fn, M, K, N)) return rc;
+    if (int rc = check_mx_bwd_dims(fn, M, K, N, 32)) return rc;
     if (int rc = check_bf16("fp8_mx_linear_bwd(dy)", dy, M, N, N)) return rc;
     if (dx) if (int rc = check_bf16("fp8_mx_linear_bwd(w)", w, N, K, K)) return rc;
     if (dw) if (int rc = check_bf16("fp8_mx_linear_bwd(x)", x, M, K, K)) return rc;
@@ -999,27 +1005,29 @@ int fp8_mx_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, i
     if (workspace_bytes < p.total) return fail(FP8_ERR_WORKSPACE, "%s: workspace %zu < %zu bytes", fn, workspace_bytes, p.total);
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* ws = static_cast<uint8_t*>(workspace);
+    const int64_t Mp = pad128(M), Np = pad128(N);   // contraction lengths of dW / dX, padded with zeros
+    if (Mp != M || Np != N) FP8_TRY(fp8k::launch_fill_u32(reinterpret_cast<uint32_t*>(ws), (int64_t)(p.total / 4), 0u, st));
     // scales in slabs of sixteen blocks (negative leading dimension) where the product that reads them takes them
-    const bool slab_dx = dx && fp8k::gemm_mxfp8_takes_slab_scales(N, N, M, K, N);
-    const bool slab_dw = dw && fp8k::gemm_mxfp8_takes_slab_scales(M, M, N, K, M);
-    const int64_t ld_dye = slab_dx ? -M : N / 32, ld_wte = slab_dx ? -K : N / 32;
-    const int64_t ld_dyte = slab_dw ? -N : M / 32, ld_xte = slab_dw ? -K : M / 32;
+    const bool slab_dx = dx && fp8k::gemm_mxfp8_takes_slab_scales(Np, Np, M, K, Np);
+    const bool slab_dw = dw && fp8k::gemm_mxfp8_takes_slab_scales(Mp, Mp, N, K, Mp);
+    const int64_t ld_dye = slab_dx ? -M : Np / 32, ld_wte = slab_dx ? -K : Np / 32;
+    const int64_t ld_dyte = slab_dw ? -N : Mp / 32, ld_xte = slab_dw ? -K : Mp / 32;
     // all quantizations first, then the products back to back
     if (dx && dw) {   // the gradient in both orientations from one read
-        FP8_TRY(fp8k::launch_mx_quant_t(dy, M, N, N, fmt_dy, ws + p.dytq, M, ws + p.dyte, ld_dyte, ws + p.dyq, N, ws + p.dye, ld_dye, st));
+        FP8_TRY(fp8k::launch_mx_quant_t(dy, M, N, N, fmt_dy, ws + p.dytq, Mp, ws + p.dyte, ld_dyte, ws + p.dyq, Np, ws + p.dye, ld_dye, st));
     } else if (dx) {
-        FP8_TRY(fp8k::launch_mx_quant(dy, M, N, N, fmt_dy, ws + p.dyq, N, ws + p.dye, ld_dye, st));
+        FP8_TRY(fp8k::launch_mx_quant(dy, M, N, N, fmt_dy, ws + p.dyq, Np, ws + p.dye, ld_dye, st));
     } else {
-        FP8_TRY(fp8k::launch_mx_quant_t(dy, M, N, N, fmt_dy, ws + p.dytq, M, ws + p.dyte, ld_dyte, nullptr, 0, nullptr, 0, st));
+        FP8_TRY(fp8k::launch_mx_quant_t(dy, M, N, N, fmt_dy, ws + p.dytq, Mp, ws + p.dyte, ld_dyte, nullptr, 0, nullptr, 0, st));
     }
-    if (dx) FP8_TRY(fp8k::launch_mx_quant_t(w, N, K, K, fmt_w, ws + p.wtq, N, ws + p.wte, ld_wte, nullptr, 0, nullptr, 0, st));
-    if (dw) FP8_TRY(fp8k::launch_mx_quant_t(x, M, K, K, fmt_x, ws + p.xtq, M, ws + p.xte, ld_xte, nullptr, 0, nullptr, 0, st));
+    if (dx) FP8_TRY(fp8k::launch_mx_quant_t(w, N, K, K, fmt_w, ws + p.wtq, Np, ws + p.wte, ld_wte, nullptr, 0, nullptr, 0, st));
+    if (dw) FP8_TRY(fp8k::launch_mx_quant_t(x, M, K, K, fmt_x, ws + p.xtq, Mp, ws + p.xte, ld_xte, nullptr, 0, nullptr, 0, st));
     if (dx)
-        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dyq, N, fmt_dy, ws + p.dye, ld_dye, ws + p.wtq, N, fmt_w, ws + p.wte, ld_wte,
-                                        M, K, N, dx, K, 0, st));
+        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dyq, Np, fmt_dy, ws + p.dye, ld_dye, ws + p.wtq, Np, fmt_w, ws + p.wte, ld_wte,
+                                        M, K, Np, dx, K, 0, st));
     if (dw)
-        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dytq, M, fmt_dy, ws + p.dyte, ld_dyte, ws + p.xtq, M, fmt_x, ws + p.xte, ld_xte,
-                                        N, K, M, dw, K, 0, st));
+        FP8_TRY(fp8k::launch_gemm_mxfp8(ws + p.dytq, Mp, fmt_dy, ws + p.dyte, ld_dyte, ws + p.xtq, Mp, fmt_x, ws + p.xte, ld_xte,
+                                        N, K, Mp, dw, K, 0, st));
     return FP8_OK;
 }
 
@@ -1057,14 +1065,19 @@ int fp8_block_quantize_row_col(const void* x, int64_t rows, int64_t cols, int64_
     return FP8_OK;
 }
 
-size_t fp8_block_linear_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N) { return fp8_mx_linear_bwd_workspace_bytes(M, K, N); }
+size_t fp8_block_linear_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+    g_err[0] = 0;
+    if (check_mx_bwd_dims("fp8_block_linear_bwd_workspace_bytes", M, K, N, 128)) return 0;
+    const size_t t = plan_mx_bwd(M, K, N).total;
+    return t ? t : 256;
+}
 
 int fp8_block_linear_bwd(const void* dy, const void* x, const void* w, int64_t M, int64_t K, int64_t N, int fmt_dy,
                          int fmt_x, int fmt_w, void* dx, void* dw, void* workspace, size_t workspace_bytes, void* stream) {
     g_err[0] = 0;
     const char* fn = "fp8_block_linear_bwd";
     if (!fmt_ok(fmt_dy) || !fmt_ok(fmt_x) || !fmt_ok(fmt_w)) return fail(FP8_ERR_ENUM, "%s: unknown fp8 format", fn);
-    if (int rc = check_mx_bwd_dims(fn, M, K, N)) return rc;
+    if (int rc = check_mx_bwd_dims(fn, M, K, N, 128)) return rc;
     if (int rc = check_bf16("fp8_block_linear_bwd(dy)", dy, M, N, N)) return rc;
     if (dx) if (int rc = check_bf16("fp8_block_linear_bwd(w)", w, N, K, K)) return rc;
     if (dw) if (int rc = check_bf16("fp8_block_linear_bwd(x)", x, M, K, K)) return rc;

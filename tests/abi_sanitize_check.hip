@@ -71,7 +71,7 @@ int main() {
     float* f = static_cast<float*>(p);
     const int64_t shapes[][3] = {{0, 0, 0}, {16, 16, 16}, {48, 64, 80}, {4096, 4096, 11008}, {16384, 4096, 14336},
                                  {8192, 28672, 8192}, {2147483647, 16, 8}, {1 << 20, 1 << 16, 1 << 12}, {1000, 64, 48},
-                                 {2147483647 - 15, 16, 16}, {2147483647 - 20, 16, 16}, {3, 16, 16}};
+                                 {2147483647 - 15, 16, 16}, {2147483647 - 20, 16, 16}, {3, 16, 16}, {96, 128, 160}, {1056, 384, 672}};
     for (const auto& s : shapes) {
         const int64_t M = s[0], K = s[1], N = s[2];
         for (int gran = FP8_TENSOR; gran <= FP8_ROW; ++gran)
@@ -96,9 +96,13 @@ int main() {
                 EXPECT(fp8_mx_linear_fwd(p, p, M, K, N, 0, 0, p, p, wm, nullptr), FP8_OK);
                 EXPECT(fp8_block_linear_fwd(p, p, M, K, N, 0, 0, p, p, wm, nullptr), FP8_OK);
             }
+            if (M % 32 == 0 && N % 32 == 0) {
+                const size_t wmx = fp8_mx_linear_bwd_workspace_bytes(M, K, N);
+                EXPECT(fp8_mx_linear_bwd(p, p, p, M, K, N, 1, 0, 0, p, p, p, wmx, nullptr), FP8_OK);
+                if (wmx > 256) EXPECT(fp8_mx_linear_bwd(p, p, p, M, K, N, 1, 0, 0, p, p, p, wmx - 1, nullptr), M && N && K ? FP8_ERR_WORKSPACE : FP8_OK);
+            }
             if (M % 128 == 0 && N % 128 == 0) {
-                const size_t wmb = fp8_mx_linear_bwd_workspace_bytes(M, K, N);
-                EXPECT(fp8_mx_linear_bwd(p, p, p, M, K, N, 1, 0, 0, p, p, p, wmb, nullptr), FP8_OK);
+                const size_t wmb = fp8_block_linear_bwd_workspace_bytes(M, K, N);
                 EXPECT(fp8_block_linear_bwd(p, p, p, M, K, N, 1, 0, 0, p, p, p, wmb, nullptr), FP8_OK);
             }
         }

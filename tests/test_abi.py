@@ -115,7 +115,9 @@ def test_argument_errors_of_the_later_entry_points():
     assert L.fp8_mx_scaled_mm(p, 512, 0, p, -8, p, 512, 0, p, -16, 16, 16, 512, p, 16, 0, None) == -2   # 8 rows per slab for M = 16
     assert L.fp8_mx_scaled_mm(p, 256, 0, p, -16, p, 256, 0, p, -16, 16, 16, 256, p, 16, 0, None) == -2  # K % 512
     assert L.fp8_mx_linear_workspace_bytes(16, 96, 16) == 0
-    assert L.fp8_mx_linear_bwd_workspace_bytes(100, 64, 128) == 0                # M % 128
+    assert L.fp8_mx_linear_bwd_workspace_bytes(100, 64, 128) == 0                # M % 32
+    assert L.fp8_mx_linear_bwd_workspace_bytes(96, 64, 160) >= 96 * 256 + 64 * 256 + 160 * 128 + 64 * 128   # padded to 128
+    assert L.fp8_block_linear_bwd_workspace_bytes(96, 64, 128) == 0              # blockwise tiles: M % 128
     assert L.fp8_mx_linear_bwd_workspace_bytes(128, 64, 256) >= 2 * 128 * 256 + 64 * 256 + 64 * 128
     assert L.fp8_mx_linear_bwd(p, p, p, 128, 64, 128, 0, 0, 9, p, p, p, 1 << 20, None) == -3
     assert L.fp8_mx_linear_bwd(p, p, p, 128, 64, 128, 0, 0, 0, p, p, p, 16, None) == -5

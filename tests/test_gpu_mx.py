@@ -208,7 +208,10 @@ def test_mx_quantize_row_col_shapes(rows, cols, ld, fmt):
     assert (host_u8(e_col_t) == wet).all() and (host_u8(q_col_t) == wqt).all()
 
 
-@pytest.mark.parametrize("M,K,N", [(128, 64, 128), (256, 8, 128), (384, 272, 512), (1024, 384, 640), (128, 1152, 256)])
+# (the last four: token and feature counts that are whole blocks of 32 but not whole K steps of 128 - the contraction
+# axes are padded inside the workspace)
+@pytest.mark.parametrize("M,K,N", [(128, 64, 128), (256, 8, 128), (384, 272, 512), (1024, 384, 640), (128, 1152, 256),
+                                   (96, 64, 160), (416, 272, 288), (1056, 384, 672), (32, 8, 32)])
 def test_mx_linear_backward(M, K, N):
     wl = si.scaled_down(si.WORKLOADS["c2_llama3_8b_ffn_rowwise"], M, K, N)
     x, w, dy = wl.x(), wl.w(), wl.dy()
@@ -234,7 +237,7 @@ def test_mx_linear_backward_exact_on_integers_and_single_outputs():
     none, only_dw = fp8.fp8_mx_linear_bwd(dev_bf16(dy), dev_bf16(x), dev_bf16(w), need_dx=False)
     assert none is None and torch.equal(only_dw, dw)
     with pytest.raises(fp8.Fp8Error):
-        fp8.fp8_mx_linear_bwd_workspace_bytes(100, 64, 128)          # M not a multiple of 128
+        fp8.fp8_mx_linear_bwd_workspace_bytes(100, 64, 128)          # M not a multiple of 32
     xb = torch.zeros((48, 64), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(fp8.Fp8Error):
         fp8.fp8_mx_quantize_t(xb, fp8.FP8_E4M3FN)                   # rows not a multiple of 32
