@@ -729,6 +729,14 @@ def main() -> int:
                 mq_both = lambda inp, *o: fp8.fp8_mx_quantize_row_col(inp, E4) if o[0] is None else fp8.fp8_mx_quantize_row_col(inp, E4, out=o)
                 cast_leg("mx_quant_dy_row_and_col_t", dy, mq_both, M * N, 4)
                 cast_leg("mx_quant_x_t", x, mqt, M * K, 3)
+                if M % 512 == 0:
+                    # the same with the scale bytes in slabs (the layout the linear entry points use between their
+                    # quantizers and products): the dwords of neighbouring output rows are 16 bytes apart instead of a scale row apart
+                    mqt_s = lambda inp, q, e: fp8.fp8_mx_quantize_t(inp, E4, slabs=True) if q is None else fp8.fp8_mx_quantize_t(inp, E4, q, e)
+                    cast_leg("mx_quant_dy_t_scale_slabs", dy, mqt_s, M * N, 3)
+                    cast_leg("mx_quant_x_t_scale_slabs", x, mqt_s, M * K, 3)
+                    bqt_s = lambda inp, q, e: fp8.fp8_block_quantize_t(inp, 1, E4, slabs=True) if q is None else fp8.fp8_block_quantize_t(inp, 1, E4, q, e)
+                    cast_leg("block_quant_dy_t_128x1_scale_slabs", dy, bqt_s, M * N, 3)
                 torch.cuda.empty_cache()
                 wsb = torch.empty(fp8.fp8_mx_linear_bwd_workspace_bytes(M, K, N), dtype=torch.uint8, device=dev)
 

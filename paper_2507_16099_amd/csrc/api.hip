@@ -223,7 +223,7 @@ extern "C" {
 
 const char* fp8_last_error(void) { return g_err; }
 
-const char* fp8_version(void) { return "fp8mi355 0.1 (gfx950)"; }
+const char* fp8_version(void) { return "fp8mi355 0.2 (gfx950)"; }
 
 int fp8_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int gran, float* amax_out, void* stream) {
     g_err[0] = 0;
