@@ -80,6 +80,30 @@ __device__ __forceinline__ void st_barrier_lds() {
     __builtin_amdgcn_sched_barrier(0);
 }
 // everything but the N youngest vector-memory operations has completed (they complete in issue order), own LDS reads done, barrier
+// The matrix instruction as assembly with the accumulator tied to the destination (FA / FB: 0 = e4m3, 1 = e5m2; the B
+// fragment is the first operand).  Through the builtin the compiler keeps the accumulation in place inside the K loop,
+// but around the tile boundary - where the drain reads the accumulators a phase or two after their last update - it
+// sent the last updates to other registers and copied them out right behind the instruction (a matrix-core latency
+// of stall each, and 64 copies back per tile: 158 instructions more in the last two K steps).  With the accumulator
+// fixed in its register the reads happen where the drain is scheduled (+0.5 %).  The compiler inserts no wait states
+// for assembly: the drain schedule keeps at least two matrix instructions between an accumulator's last update and
+// its first read, and between its last read and the next tile's first write.
+template <int FA, int FB>
+__device__ __forceinline__ void st_mfma(v4f_t2& c, const v8i_t2& b, const v8i_t2& a) {
+    if constexpr (FB == 0 && FA == 0) asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(c) : "v"(b), "v"(a));
+    else if constexpr (FB == 1 && FA == 0) asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 cbsz:1" : "+a"(c) : "v"(b), "v"(a));
+    else if constexpr (FB == 0 && FA == 1) asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 blgp:1" : "+a"(c) : "v"(b), "v"(a));
+    else asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 cbsz:1 blgp:1" : "+a"(c) : "v"(b), "v"(a));
+}
+// the same starting from C = 0 (the first K step of a tile: nothing is cleared beforehand)
+template <int FA, int FB>
+__device__ __forceinline__ void st_mfma_zero(v4f_t2& c, const v8i_t2& b, const v8i_t2& a) {
+    if constexpr (FB == 0 && FA == 0) asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, 0" : "=a"(c) : "v"(b), "v"(a));
+    else if constexpr (FB == 1 && FA == 0) asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, 0 cbsz:1" : "=a"(c) : "v"(b), "v"(a));
+    else if constexpr (FB == 0 && FA == 1) asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, 0 blgp:1" : "=a"(c) : "v"(b), "v"(a));
+    else asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, 0 cbsz:1 blgp:1" : "=a"(c) : "v"(b), "v"(a));
+}
+
 template <int N>
 __device__ __forceinline__ void st_wait_vmem_but_barrier() {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
@@ -250,7 +274,7 @@ __global__ __launch_bounds__(st::NT) void gemm_fp8_stream_kernel(
     };
     const uint32_t lane_out = (uint32_t)(((wm0 + r16) * (int)ld_out + wn0 + 8 * g) * 2);   // byte offset of this lane's first piece in a tile
     const int lane_col = wn0 + 8 * g;
-    float inv_b[2][4], inv_a = 0.f;     // column scales: the four of the B fragment being packed, and the next four
+    float inv_b[4][4], inv_a = 0.f;     // the job's sixteen column scales and its row scale
     uint32_t pk[8];
     // step S of a job: 0 = fetch its row scale and first column scales; 1..4 = read four accumulators (one B fragment),
     // scale, round, pack, and fetch the next fragment's column scales; 5 = regroup and store
@@ -259,19 +283,19 @@ __global__ __launch_bounds__(st::NT) void gemm_fp8_stream_kernel(
         constexpr int S = decltype(step_t)::value;
         if constexpr (!J::none(AF1)) {
             constexpr int AH = J::AH, BH = J::BH, U = J::U;
-            auto fetch_b = [&](int T) {
-                const float4 t4 = *reinterpret_cast<const float4*>(d.tab + 256 + wn0 + 64 * BH + 16 * g + 4 * T);
-                inv_b[T & 1][0] = t4.x; inv_b[T & 1][1] = t4.y; inv_b[T & 1][2] = t4.z; inv_b[T & 1][3] = t4.w;
-            };
             if constexpr (S == 0) {
+                // all of the job's scales in one go (one wait for LDS per job instead of five; measured neutral)
                 inv_a = d.tab[wm0 + 16 * (AH * 4 + U) + r16];
-                fetch_b(0);
+#pragma unroll
+                for (int T = 0; T < 4; ++T) {
+                    const float4 t4 = *reinterpret_cast<const float4*>(d.tab + 256 + wn0 + 64 * BH + 16 * g + 4 * T);
+                    inv_b[T][0] = t4.x; inv_b[T][1] = t4.y; inv_b[T][2] = t4.z; inv_b[T][3] = t4.w;
+                }
             } else if constexpr (S <= 4) {
                 constexpr int T = S - 1;                                   // B fragment of the half
-                if constexpr (T < 3) fetch_b(T + 1);
                 const v4f_t2 v = acc[AH * 4 + U][BH * 4 + T];
-                pk[2 * T] = st_pack_bf16((v[0] * inv_a) * inv_b[T & 1][0], (v[1] * inv_a) * inv_b[T & 1][1]);
-                pk[2 * T + 1] = st_pack_bf16((v[2] * inv_a) * inv_b[T & 1][2], (v[3] * inv_a) * inv_b[T & 1][3]);
+                pk[2 * T] = st_pack_bf16((v[0] * inv_a) * inv_b[T][0], (v[1] * inv_a) * inv_b[T][1]);
+                pk[2 * T + 1] = st_pack_bf16((v[2] * inv_a) * inv_b[T][2], (v[3] * inv_a) * inv_b[T][3]);
             } else {
                 // lanes g = 0..3 of a row hold the 16-byte pieces (2g, 2g+1) of its 128 bytes; after the two swaps
                 // lane g holds pieces g (lo) and 4 + g (hi): each store writes 64 contiguous bytes per row
@@ -326,12 +350,8 @@ __global__ __launch_bounds__(st::NT) void gemm_fp8_stream_kernel(
                 constexpr int t = TS;
                 constexpr int i = t >> 2, j = (i & 1) ? 3 - (t & 3) : (t & 3);   // boustrophedon: one operand stays between neighbours
                 if constexpr (AH == 0 || i < AF1) {        // (a lower tile has no fragment i of the A1 group: the slot stays empty)
-                    if constexpr (ZERO)
-                        acc[AH * 4 + i][BH * 4 + j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                            bf[BH][j], af[AH][i], v4f_t2{0.f, 0.f, 0.f, 0.f}, FB, FA, 0, 0, 0, 0);
-                    else
-                        acc[AH * 4 + i][BH * 4 + j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                            bf[BH][j], af[AH][i], acc[AH * 4 + i][BH * 4 + j], FB, FA, 0, 0, 0, 0);
+                    if constexpr (ZERO) st_mfma_zero<FA, FB>(acc[AH * 4 + i][BH * 4 + j], bf[BH][j], af[AH][i]);
+                    else st_mfma<FA, FB>(acc[AH * 4 + i][BH * 4 + j], bf[BH][j], af[AH][i]);
                 }
                 if constexpr (RDA == 1 && t % 2 == 0 && t < 8 && (RH == 0 || t / 2 < AF1)) read_a(rs, RH, t / 2);
                 if constexpr (RDA == 0 && t % 2 == 0 && t < 8) read_b(rs, RH, t / 2);
