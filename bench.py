@@ -142,7 +142,7 @@ def _sweep(torch, fp8, dev, iters: int) -> dict:
                 del x, w, dy, y, dx, dw
     return {"sweep": "fp8 linear fwd+bwd (quantization included) vs bf16 torch.matmul x3, one MI355X; *_graph_ms: the same step "
                      "replayed from a HIP graph (no per-call host cost)",
-            "iters": iters, "rows": rows}
+            "graph_one_thread_kernel_us": round(floor_us, 2), "iters": iters, "rows": rows}
 
 
 def _block(torch, fp8, dev, iters: int) -> dict:
@@ -217,7 +217,7 @@ def _block(torch, fp8, dev, iters: int) -> dict:
         del x, w, dy, y, dh, dw, wf, wb, lnq, wq
         torch.cuda.empty_cache()
     return {"block": "LayerNorm + Linear + Sigmoid forward and backward, float8 rowwise vs bfloat16, one MI355X",
-            "iters": iters, "rows": rows}
+            "graph_one_thread_kernel_us": round(floor_us, 2), "iters": iters, "rows": rows}
 
 
 def _configs(torch, fp8, dev, iters: int) -> dict:
@@ -263,7 +263,7 @@ def _configs(torch, fp8, dev, iters: int) -> dict:
         del x, w, dy, y, dx, dw, ws
         torch.cuda.empty_cache()
     return {"configs": "fp8 linear step (dynamic quantization included) vs bf16 torch.matmul on every synthetic workload, one MI355X",
-            "iters": iters, "rows": rows}
+            "graph_one_thread_kernel_us": round(floor_us, 2), "iters": iters, "rows": rows}
 
 
 def _data_probe(torch, fp8, dev, iters: int) -> dict:
@@ -342,6 +342,9 @@ def _decode(torch, fp8, dev, iters: int) -> dict:
     shapes = (("llama3_8b_qkv", 6144, 4096), ("llama3_8b_o", 4096, 4096), ("llama3_8b_ffn_up", 14336, 4096),
               ("llama3_8b_ffn_down", 4096, 14336), ("llama3_70b_ffn_up", 28672, 8192), ("llama3_70b_ffn_down", 8192, 28672))
     E4, ROW = fp8.FP8_E4M3FN, fp8.FP8_ROW
+    # what one launch costs when it follows another in a graph: a one-thread kernel (fp8_scale of one amax), 64 in a row
+    one_amax, one_scale = torch.ones(1, device=dev), torch.empty(1, device=dev)
+    floor_us = _graph_time_ms(lambda: [fp8.fp8_scale(one_amax, E4, 0, out=one_scale) for _ in range(64)], 20, torch) / 64 * 1e3
     for name, N, K in shapes:
         ncopy = max(2, -(-1_600_000_000 // (N * K)))
         ws = [(torch.randn((N, K), device=dev) * 0.02).to(torch.bfloat16) for _ in range(ncopy)]
@@ -388,7 +391,7 @@ def _decode(torch, fp8, dev, iters: int) -> dict:
                       "both cycle through > 1.6 GB of fp8 weight copies (and their bf16 originals)",
             "roofline": {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "algorithmic_bytes_per_launch": "N*K weight bytes"},
-            "iters": iters, "rows": rows}
+            "graph_one_thread_kernel_us": round(floor_us, 2), "iters": iters, "rows": rows}
 
 
 def main() -> int:

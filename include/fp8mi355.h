@@ -168,7 +168,7 @@ int fp8_scaled_mm(const uint8_t* a, int64_t lda, int fmt_a, const float* scale_a
  * FP8_SAVE_FOR_BWD: the fp8 copies of X and W that the backward needs do not
  * depend on the gradient, so the forward can make them from the same read as
  * its own and leave them in the workspace; the backward then quantizes dY alone.
- * Tensorwise (Appendix A: a single scaling factor for each tensor): the same
+ * Tensorwise (Appendix A: one scale for the whole tensor): the same
  * codes, only transposed - one conversion into both layouts, 3 quantizations
  * per step instead of 5.  Rowwise: the per-column, transposed codes of X and W
  * next to the rowwise ones, two reads of each tensor per step instead of
