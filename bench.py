@@ -142,7 +142,7 @@ def _sweep(torch, fp8, dev, iters: int) -> dict:
                 del x, w, dy, y, dx, dw
     return {"sweep": "fp8 linear fwd+bwd (quantization included) vs bf16 torch.matmul x3, one MI355X; *_graph_ms: the same step "
                      "replayed from a HIP graph (no per-call host cost)",
-            "graph_one_thread_kernel_us": round(floor_us, 2), "iters": iters, "rows": rows}
+            "iters": iters, "rows": rows}
 
 
 def _block(torch, fp8, dev, iters: int) -> dict:
@@ -217,7 +217,7 @@ def _block(torch, fp8, dev, iters: int) -> dict:
         del x, w, dy, y, dh, dw, wf, wb, lnq, wq
         torch.cuda.empty_cache()
     return {"block": "LayerNorm + Linear + Sigmoid forward and backward, float8 rowwise vs bfloat16, one MI355X",
-            "graph_one_thread_kernel_us": round(floor_us, 2), "iters": iters, "rows": rows}
+            "iters": iters, "rows": rows}
 
 
 def _configs(torch, fp8, dev, iters: int) -> dict:
@@ -263,7 +263,7 @@ def _configs(torch, fp8, dev, iters: int) -> dict:
         del x, w, dy, y, dx, dw, ws
         torch.cuda.empty_cache()
     return {"configs": "fp8 linear step (dynamic quantization included) vs bf16 torch.matmul on every synthetic workload, one MI355X",
-            "graph_one_thread_kernel_us": round(floor_us, 2), "iters": iters, "rows": rows}
+            "iters": iters, "rows": rows}
 
 
 def _data_probe(torch, fp8, dev, iters: int) -> dict:
