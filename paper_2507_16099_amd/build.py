@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfp8mi355.so")
-SOURCES = ["quant_kernels.hip", "tuning.hip", "gemm_fp8.hip", "gemm_fp8_snake.hip", "gemm_fp8_stream.hip", "gemm_fp8_skinny.hip", "gemm_bf16_at_b.hip", "gemm_bf16_at_b_snake.hip", "layernorm_quant.hip", "gemm_mxfp8.hip", "gemm_mxfp8_snake.hip", "api.hip"]
+SOURCES = ["quant_kernels.hip", "tuning.hip", "gemm_fp8.hip", "gemm_fp8_snake.hip", "gemm_fp8_stream.hip", "gemm_fp8_skinny.hip", "gemm_fp8_skinny_fused.hip", "gemm_bf16_at_b.hip", "gemm_bf16_at_b_snake.hip", "layernorm_quant.hip", "gemm_mxfp8.hip", "gemm_mxfp8_snake.hip", "api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are disabled on purpose (the compiler would
 # otherwise form v_pk_*_f32 from plain float code)

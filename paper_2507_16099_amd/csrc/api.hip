@@ -655,6 +655,11 @@ int linear_fwd_prequantized_impl(const char* fn, const void* x, int64_t M, int64
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* xq = static_cast<uint8_t*>(workspace);
     float* sx = reinterpret_cast<float*>(xq + align_up((size_t)M * (size_t)K, 256));
+    // a few tokens: scales and codes of x are formed inside the product's launch (the workspace stays unused)
+    const hipError_t fused = fp8k::launch_linear_skinny_fused(x, K, fmt_x, gran_x == FP8_ROW, flags & FP8_POW2_SCALE, wq, ldw, fmt_w,
+                                                              scale_w, gran_w == FP8_ROW, M, N, K, y, ld_y, st);
+    if (fused == hipSuccess) return FP8_OK;
+    if (fused != hipErrorNotSupported) return hip_fail(fused, "launch_linear_skinny_fused");
     if (int rq = quantize_impl(x, M, K, K, gran_x, fmt_x, flags, xq, K, nullptr, 0, sx, st)) return rq;
     FP8_TRY(fp8k::launch_gemm_fp8(xq, K, fmt_x, sx, gran_x == FP8_ROW, wq, ldw, fmt_w, scale_w, gran_w == FP8_ROW, M, N, K, y,
                                   ld_y, 0, st));

@@ -136,6 +136,13 @@ hipError_t launch_gemm_fp8_skinny(const uint8_t* a, int64_t lda, int fmt_a, cons
                                   int64_t M, int64_t N, int64_t K, void* out, int64_t ld_out, int out_f32,
                                   hipStream_t st);
 
+// y[M, N] = fp8(x * s_x)[M, K] . b[N, K]^T / (s_x * scale_b) for up to 16 rows of bfloat16 x, in one launch: the amax of
+// x (per row if row_x, else of the whole tensor), its scale (flags: FLAG_POW2) and the cast happen inside the
+// few-row product.  hipErrorNotSupported (nothing launched) where that form does not apply.
+hipError_t launch_linear_skinny_fused(const void* x, int64_t ldx, int fmt_x, int row_x, int flags, const uint8_t* b,
+                                      int64_t ldb, int fmt_b, const float* scale_b, int row_b, int64_t M, int64_t N,
+                                      int64_t K, void* out, int64_t ld_out, hipStream_t st);
+
 // bfloat16 GEMM with the contraction on the rows of both operands:
 // out[I, J] = a[C, I]^T b[C, J], fp32 accumulate, bfloat16 out (the weight gradient
 // dW = dY^T X kept in high precision).  I, J and the leading dimensions are

@@ -10,7 +10,7 @@ namespace fp8k {
 namespace {
 const char* const kNames[KNOB_COUNT] = {"GEMM_VARIANT", "SNAKE_HALF", "SKINNY_NW", "SKINNY_DMA",
                                         "MX_VARIANT",   "MX_SLAB",    "BF16_VARIANT", "GEMM_STREAM", "GEMM_TILE_M",
-                                        "GEMM_BIG_FROM", "PAIRS"};
+                                        "GEMM_BIG_FROM", "PAIRS", "DECODE_FUSED"};
 std::atomic<int> g_value[KNOB_COUNT];
 std::once_flag g_once;
 

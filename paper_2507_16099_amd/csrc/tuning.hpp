@@ -23,6 +23,7 @@ enum Knob {
     KNOB_GEMM_TILE_M,       // persistent kernel: 256, 224 or 192 forces the tile height
     KNOB_GEMM_BIG_FROM,     // number of 128 x 128 tiles from which a product goes to the 256 x 256 kernels
     KNOB_PAIRS,             // 0 = no shared launches: every tensor of a linear step quantized, every product launched, by itself
+    KNOB_DECODE_FUSED,      // few tokens against a quantized weight: 0 = activation quantization always a launch of its own, 2 = inside the product wherever that kernel applies
     KNOB_COUNT
 };
 

@@ -41,6 +41,7 @@ hipError_t launch_quant_tensor_pair(const TensorOperand&, const TensorOperand&, 
 hipError_t launch_quant_row_pair(const void*, int64_t, int64_t, uint8_t*, int64_t, float*, const void*, int64_t, int64_t, uint8_t*, int64_t, float*, int64_t, int, int, hipStream_t) STUB_ALTERNATING
 hipError_t launch_quant_row_col_pair(const RowColOperand&, const RowColOperand*, int64_t, int, int, hipStream_t) STUB_ALTERNATING
 int64_t quant_fold_bytes(int64_t rows, int64_t cols) { return rows >= 256 && rows <= 2048 && cols >= 8 && cols % 8 == 0 && rows * cols <= ((int64_t)4 << 20) ? FOLD_ROWS * ((cols + 7) / 8 * 8) * 2 : 0; }
+hipError_t launch_linear_skinny_fused(const void*, int64_t, int, int, int, const uint8_t*, int64_t, int, const float*, int, int64_t, int64_t, int64_t, void*, int64_t, hipStream_t) STUB_ALTERNATING
 hipError_t launch_quant_col_t_pair(const ColOperand&, const ColOperand&, int64_t, int, int, hipStream_t) STUB_ALTERNATING
 hipError_t launch_quant_bwd_rowwise(const RowColOperand&, int64_t, int, const ColOperand&, const ColOperand&, int64_t, int, int, hipStream_t) STUB_ALTERNATING
 hipError_t launch_gemm_fp8_pair(const GemmOperands&, const GemmOperands&, int, int, int, int, hipStream_t) STUB_ALTERNATING

@@ -411,6 +411,42 @@ def test_prequantized_forward_rejects_bad_arguments():
     assert y.shape == (0, 32)
 
 
+@pytest.mark.parametrize("K,N", [(512, 40), (1024, 1000), (2048, 264), (4096, 6152), (14336, 1040)])
+@pytest.mark.parametrize("gran_x", [fp8.FP8_ROW, fp8.FP8_TENSOR])
+def test_one_launch_form_for_few_tokens_changes_no_bit(K, N, gran_x):
+    """Up to 8 tokens: the scales and codes of the activations can be formed inside the product's launch (by
+    default for one token; the switch DECODE_FUSED=2 forces that form wherever it applies).  The result must
+    equal, bit for bit, that of the two-launch form (DECODE_FUSED=0), for either kind of activation scale,
+    power-of-two scales, both widths of a wavefront's column group, an e5m2 activation format (which falls
+    back to two launches), and rows that are all zero."""
+    rng = np.random.default_rng(K + N)
+    w = si.normal_bf16((N, K), 0.02, 7, 1)
+    wq, sw = fp8.fp8_quantize(dev_bf16(w), fp8.FP8_ROW, fp8.FP8_E4M3FN)
+    for M in (1, 2, 3, 5, 8):
+        xf = si.bf16_bits_to_f32(si.normal_bf16((M, K), 1.0, 7, M)) * (0.3 + 1.7 * np.arange(M, dtype=np.float32)[:, None])
+        xf[np.arange(M), rng.integers(0, K, M)] *= 9.0          # every row its own scale, set by an outlier somewhere
+        xb = si.f32_to_bf16_bits(xf.astype(np.float32))
+        if M >= 5:
+            xb[3, :] = 0                     # a row of zeros: scale of the clamped amax, codes 0
+        xd = dev_bf16(xb)
+        for fmt_x, flags, nw in ((fp8.FP8_E4M3FN, 0, None), (fp8.FP8_E4M3FN, fp8.FP8_POW2_SCALE, 1),
+                                 (fp8.FP8_E5M2, 0, 2)):
+            with knobs(DECODE_FUSED=0, SKINNY_NW=nw):
+                want = fp8.fp8_linear_fwd_prequantized(xd, wq, fp8.FP8_E4M3FN, sw, fp8.FP8_ROW, fmt_x, gran_x, flags)
+            with knobs(DECODE_FUSED=2, SKINNY_NW=nw):
+                got = fp8.fp8_linear_fwd_prequantized(xd, wq, fp8.FP8_E4M3FN, sw, fp8.FP8_ROW, fmt_x, gran_x, flags)
+            assert torch.equal(got.view(torch.int16), want.view(torch.int16)), (M, K, N, fmt_x, flags, nw)
+    # and the default choice for one token (the one-launch form) against the oracle
+    M = 1
+    xb = si.normal_bf16((M, K), 1.0, 7, 99)
+    y = fp8.fp8_linear_fwd_prequantized(dev_bf16(xb), wq, fp8.FP8_E4M3FN, sw, fp8.FP8_ROW, fp8.FP8_E4M3FN, gran_x)
+    ogran = orc.ROW if gran_x == fp8.FP8_ROW else orc.TENSOR
+    xq_o, sx_o = orc.quantize(xb, ogran, orc.E4M3FN)
+    wq_o, sw_o = orc.quantize(w, orc.ROW, orc.E4M3FN)
+    want = orc.scaled_mm(xq_o, orc.E4M3FN, sx_o, ogran, wq_o, orc.E4M3FN, sw_o, orc.ROW)
+    _cmp(y, want, min_identical=0.95)
+
+
 def test_full_size_decode_step_llama_ffn_weight():
     """Decode batch of 16 tokens against the full Llama-3-8B FFN up-projection
     weight [14336, 4096], rowwise scales: the whole output against the oracle."""
