@@ -256,8 +256,8 @@ def test_full_size_outlier_stress_rowwise_vs_tensorwise():
     assert report["c5_outlier_rowwise"]["fp8_vs_unquantized_product_rel_frobenius"] < \
         report["c5_outlier_tensorwise"]["fp8_vs_unquantized_product_rel_frobenius"]
     print("OUTLIER_REPORT " + json.dumps(report), flush=True)
-    out_dir = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(out_dir):          # kept record of the run (summarised under profiles/)
+    out_dir = os.environ.get("FP8MI355_REPORT_DIR")      # a kept record of the run, where the caller asks for one
+    if out_dir and os.path.isdir(out_dir):
         with open(os.path.join(out_dir, "c5_outlier_report.json"), "w") as f:
             json.dump(report, f, indent=1)
 
