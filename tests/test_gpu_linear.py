@@ -436,6 +436,20 @@ def test_one_launch_form_for_few_tokens_changes_no_bit(K, N, gran_x):
             with knobs(DECODE_FUSED=2, SKINNY_NW=nw):
                 got = fp8.fp8_linear_fwd_prequantized(xd, wq, fp8.FP8_E4M3FN, sw, fp8.FP8_ROW, fmt_x, gran_x, flags)
             assert torch.equal(got.view(torch.int16), want.view(torch.int16)), (M, K, N, fmt_x, flags, nw)
+    # a weight with padded rows, and activations with an infinity and a NaN (their rows come out as NaN either way)
+    wide = torch.full((N, K + 64), 0x7E, dtype=torch.uint8, device="cuda")
+    wide[:, :K] = wq
+    xf = si.bf16_bits_to_f32(si.normal_bf16((4, K), 1.0, 7, 50))
+    xf[1, 5] = np.inf
+    xf[2, K - 1] = np.nan
+    xd = dev_bf16(si.f32_to_bf16_bits(xf))
+    with knobs(DECODE_FUSED=0):
+        want = fp8.fp8_linear_fwd_prequantized(xd, wide[:, :K], fp8.FP8_E4M3FN, sw, fp8.FP8_ROW, fp8.FP8_E4M3FN, gran_x)
+    with knobs(DECODE_FUSED=2):
+        got = fp8.fp8_linear_fwd_prequantized(xd, wide[:, :K], fp8.FP8_E4M3FN, sw, fp8.FP8_ROW, fp8.FP8_E4M3FN, gran_x)
+    assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+    if gran_x == fp8.FP8_ROW:
+        assert torch.isfinite(got[0].float()).all() and torch.isfinite(got[3].float()).all()
     # and the default choice for one token (the one-launch form) against the oracle
     M = 1
     xb = si.normal_bf16((M, K), 1.0, 7, 99)
