@@ -349,7 +349,7 @@ def _decode(torch, fp8, dev, iters: int) -> dict:
         ncopy = max(2, -(-1_600_000_000 // (N * K)))
         ws = [(torch.randn((N, K), device=dev) * 0.02).to(torch.bfloat16) for _ in range(ncopy)]
         q = [fp8.fp8_quantize(w, ROW, E4) for w in ws]
-        for M in (1, 8, 16, 32):
+        for M in (1, 4, 8, 16, 32):
             x = torch.randn((M, K), device=dev).to(torch.bfloat16)
             y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
             wsp = torch.empty(fp8.fp8_linear_prequantized_workspace_bytes(M, K), dtype=torch.uint8, device=dev)

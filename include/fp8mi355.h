@@ -252,9 +252,9 @@ int fp8_grad_weight_hp(const void* dy, const void* x, int64_t M, int64_t K, int6
  * workspace: fp8_linear_prequantized_workspace_bytes(M, K) bytes, 256-byte
  * aligned (activation codes and scales).  With few rows (M <= 32, decoding) the
  * GEMM streams wq once and is bound by that HBM read.  For a single token (and
- * where M * K <= 8192, K a multiple of 512, fmt_x e4m3) the activation scales
- * and codes are formed inside that GEMM's launch: one launch instead of two,
- * the same bits, and the workspace is not written.
+ * up to four with M * K <= 16384; K a multiple of 512 and at most 32768, fmt_x
+ * e4m3) the activation scales and codes are formed inside that GEMM's launch:
+ * one launch instead of two, the same bits, and the workspace is not written.
  */
 size_t fp8_linear_prequantized_workspace_bytes(int64_t M, int64_t K);
 int fp8_linear_fwd_prequantized(const void* x, int64_t M, int64_t K, int fmt_x, int gran_x, int flags,

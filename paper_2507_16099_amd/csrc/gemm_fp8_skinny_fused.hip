@@ -1,26 +1,24 @@
-// Linear layer for up to 8 tokens against a weight quantized once, in ONE launch:
+// Linear layer for a few tokens against a weight quantized once, in ONE launch:
 //     y[M, N] = (q(X)[M, K] . Wq[N, K]^T) / (s_x * s_w),   q(X) = fp8(X * s_x),  s_x = FMAX / amax(X)
 // (Section 3 of the paper: dynamic activation quantization in front of a
 // pre-quantized weight, at decode batch sizes).  The two-launch form quantizes X
 // in a kernel of its own; at these sizes that launch costs as much as streaming
-// a third of the weight.  Here every workgroup derives the scales of X itself
-// and converts the bfloat16 activations to fp8 on their way into the matrix cores.
+// a third of the weight.  Here every workgroup quantizes X itself, into LDS.
 //
 // The product is the LDS-DMA few-row kernel of gemm_fp8_skinny.hip: a wavefront owns NW column
 // tiles of 16 weight rows and a part of K; the weight streams through a private ring of LDS slots,
-// R steps of 128 bytes ahead.  What differs:
-//  * the amax of X: all wavefronts of the workgroup read X once (M * K bfloat16, from L2 after the
-//    first workgroups), 512 elements per wavefront and load, and fold the maxima into one LDS word per row;
-//    the loads are issued behind the first ring fill, so they travel while the weight's first bytes do;
-//  * the A operand: per K step the wavefront loads the M x 128 activations of the step densely (lane l the
-//    elements 2 l and 2 l + 1 of every row: MB dwords, R steps ahead like the ring), converts them when the
-//    step is due (multiply by s_x, clamp, round to nearest even: the arithmetic of the row quantizer, so
-//    the codes are the ones it would have written), parks the codes in a 16 x 128 byte LDS tile of its own
-//    and reads its MFMA operand from there.  Converting in the operand's own layout would have every lane
-//    convert 32 elements of some row, present or not: as many conversions as the weight has bytes.
-// Register loads and LDS-DMA loads complete in the order of issue; a step issues first its ring loads, then its
-// A loads, so "step s is there" is one wait on the number of younger loads.  The A loads are assembly for that
-// reason: the compiler's own bookkeeping of loads in flight knows nothing of the LDS-DMA loads between them.
+// R steps of 128 bytes ahead, no barriers in the main loop.  What differs:
+//  * a workgroup is eight wavefronts (one per CU: X is read and converted once per CU) where that still gives
+//    most CUs a workgroup, else four (two per CU);
+//  * before the main loop the workgroup reads all of X (at most 32768 elements: 8 loads of 16 bytes per
+//    lane, requested ahead of the first ring fill and waited for by count, so they arrive while the
+//    weight's first bytes are still on their way), reduces the row maxima (lane maxima folded within rows
+//    of 16 lanes by DPP rotations, then through scalar registers, then one LDS word per row), derives the
+//    scales with the row quantizer's arithmetic, converts the registers it still holds and leaves the
+//    codes in LDS, one padded row per token;
+//  * in the main loop the A operand is two 16-byte LDS reads from those codes (lanes of rows past M read
+//    zeros); nothing of X is fetched again.
+// Same codes, scales and order of sums as the two-launch form: the results are bit-identical.
 #include "fp8_device.hpp"
 #include "launchers.hpp"
 #include "tuning.hpp"
@@ -32,7 +30,6 @@ typedef int v4i_q __attribute__((ext_vector_type(4)));
 typedef float v4f_q __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2_q __attribute__((ext_vector_type(2)));
 typedef float f32x2_q __attribute__((ext_vector_type(2)));
-typedef uint16_t __attribute__((may_alias)) u16_any;      // the codes of X are written as halfwords and read back as 16-byte operands
 
 __device__ __forceinline__ uint32_t skf_pack_bf16(float a, float b) {
     f32x2_q v = {a, b};
@@ -50,36 +47,67 @@ __device__ __forceinline__ void skf_lds_dma16(v4i_q rsrc, uint32_t lds_addr, uin
                  : "s"(lds_addr), "v"(voffset), "s"(rsrc)
                  : "memory", "m0");
 }
-// one dword per lane from a raw buffer into a register; the data is there after skf_wait
-__device__ __forceinline__ void skf_load4(int& dst, v4i_q rsrc, uint32_t voffset) {
-    asm volatile("buffer_load_dword %0, %1, %2, 0 offen" : "=v"(dst) : "v"(voffset), "s"(rsrc) : "memory");
+// 16 bytes per lane from a raw buffer into registers; the data is there after skf_wait_x.  Assembly, like
+// the wait: the compiler's own count of loads in flight knows nothing of the LDS-DMA loads issued behind these.
+__device__ __forceinline__ void skf_load16(v4i_q& dst, v4i_q rsrc, uint32_t voffset) {
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(dst) : "v"(voffset), "s"(rsrc) : "memory");
 }
 // wait until at most N_ loads are in flight; the registers are operands so that no use of them moves above the wait
-template <int N_, int MB>
-__device__ __forceinline__ void skf_wait(int (&a)[MB]) {
-    if constexpr (MB == 1) asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a[0]) : "n"(N_) : "memory");
-    if constexpr (MB == 2) asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a[0]), "+v"(a[1]) : "n"(N_) : "memory");
-    if constexpr (MB == 4)
-        asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]) : "n"(N_) : "memory");
-    if constexpr (MB == 8)
+template <int N_, int U>
+__device__ __forceinline__ void skf_wait_x(v4i_q (&x)[U]) {
+    static_assert(U == 8 || U == 16, "8 or 16 register sets");
+    if constexpr (U == 8) {
         asm volatile("s_waitcnt vmcnt(%8)"
-                     : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+                     : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
                      : "n"(N_)
                      : "memory");
+    } else {
+        asm volatile("s_waitcnt vmcnt(%16)"
+                     : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]),
+                       "+v"(x[8]), "+v"(x[9]), "+v"(x[10]), "+v"(x[11]), "+v"(x[12]), "+v"(x[13]), "+v"(x[14]), "+v"(x[15])
+                     : "n"(N_)
+                     : "memory");
+    }
 }
-__device__ __forceinline__ void skf_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+template <int N_>
+__device__ __forceinline__ void skf_wait_vmem() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_) : "memory"); }
 
-// MB: rows of X the kernel is built for (M <= MB; 1, 2, 4 or 8)
-template <int FX, int FB, int KS, int NW, int MB, int R>
-__global__ __launch_bounds__(256) void gemm_fp8_skinny_fused_kernel(
+// maximum over the wavefront, the same value in every lane: rotations within rows of 16 lanes (DPP), then
+// the four rows through scalar registers
+__device__ __forceinline__ uint32_t skf_wave_max(uint32_t v) {
+    uint32_t o;
+    o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x121, 0xF, 0xF, false);   // row_ror:1
+    v = o > v ? o : v;
+    o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x122, 0xF, 0xF, false);   // row_ror:2
+    v = o > v ? o : v;
+    o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x124, 0xF, 0xF, false);   // row_ror:4
+    v = o > v ? o : v;
+    o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xF, 0xF, false);   // row_ror:8
+    v = o > v ? o : v;
+    const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)v, 0), b = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+    const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)v, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+    const uint32_t ab = a > b ? a : b, cd = c > d ? c : d;
+    return ab > cd ? ab : cd;
+}
+
+namespace skf {
+constexpr int MAX_X = 32768;       // elements of X a workgroup holds in registers: 8 loads of 8 per lane
+constexpr int ROW_PAD = 64;        // bytes between the rows of codes in LDS beyond K: consecutive rows start 16 banks apart
+}  // namespace skf
+
+template <int FX, int FB, int KS, int NW, int WAVES, int R>
+__global__ __launch_bounds__(64 * WAVES) void gemm_fp8_skinny_fused_kernel(
     const uint16_t* __restrict__ X, int64_t ldx, int row_x, int flags, const uint8_t* __restrict__ B, int64_t ldb,
     const float* __restrict__ scale_b, int row_b, int M, int N, int K, uint16_t* __restrict__ out, int64_t ld_out) {
-    constexpr int NTW = 4 / KS;
+    using namespace skf;
+    constexpr int NTW = WAVES / KS;
     constexpr int SLOT = NW * 2048;              // weight bytes of one K step of this wavefront
-    constexpr int LB = 2 * NW, LA = MB;          // loads per step: LDS-DMA (weight), registers (activations)
-    static_assert((R - 1) * (LB + LA) <= 63, "vmcnt range");
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];     // 4 rings of R slots, then 4 tiles of 16 x 128 codes of X
+    constexpr int LB = 2 * NW;                   // LDS-DMA loads per step
+    static_assert((R - 1) * LB <= 63 && R * LB <= 63, "vmcnt range");
+    // dynamic LDS: WAVES rings of R slots; then the codes of X, row r at r * (K + ROW_PAD); then 128 bytes of zeros
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     __shared__ uint32_t amax_bits[8];
+    __shared__ float scale_x[8];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = lane & 15, g = lane >> 4;
@@ -89,13 +117,12 @@ __global__ __launch_bounds__(256) void gemm_fp8_skinny_fused_kernel(
     const int per = (ksteps + KS - 1) / KS;
     const int s_begin = kp * per;
     const int s_end = s_begin + per < ksteps ? s_begin + per : ksteps;
+    uint8_t* codes = smem + WAVES * R * SLOT;
+    const int row_bytes = K + ROW_PAD;
+    uint8_t* zeros = codes + M * row_bytes;
 
     if (tid < 8) amax_bits[tid] = 0;
-    // this wavefront's tile of codes: rows M..15 stay zero for good
-    uint8_t* codes = smem + 4 * R * SLOT + wave * 2048;
-    *reinterpret_cast<uint4*>(codes + lane * 32) = make_uint4(0, 0, 0, 0);
-    *reinterpret_cast<uint4*>(codes + lane * 32 + 16) = make_uint4(0, 0, 0, 0);
-    __syncthreads();
+    if (tid < 8) *reinterpret_cast<uint4*>(zeros + tid * 16) = make_uint4(0, 0, 0, 0);
 
     float sc_b[NW][4];
 #pragma unroll
@@ -114,7 +141,21 @@ __global__ __launch_bounds__(256) void gemm_fp8_skinny_fused_kernel(
     const v4i_q rsrc_x = {(int)(uint32_t)px, (int)(uint32_t)(px >> 32), (int)(((int64_t)(M - 1) * ldx + K) * 2), 0x00020000};
     constexpr uint32_t OOB = 0x80000000u;
 
-    // weight: load j of a 16-row tile fetches rows 8 j + lane / 8; lane's chunk slot lane % 8 receives chunk slot ^ key(row)
+    // ---- X: wavefront w takes the pieces w, w + 8, ... of 512 elements (piece q = 512 elements from column
+    //      512 (q % cpr) of row q / cpr); a piece past the end is not fetched (zeros)
+    constexpr int U = 64 / WAVES;                // pieces per wavefront: 8 or 16 loads of 16 bytes per lane
+    const int cpr = K / 512, pieces = M * cpr;
+    v4i_q xv[U];
+    int prow[U], pcol[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int q = wave + WAVES * u;
+        prow[u] = q / cpr;
+        pcol[u] = q - prow[u] * cpr;
+        skf_load16(xv[u], rsrc_x, q < pieces ? (uint32_t)((prow[u] * (int)ldx + pcol[u] * 512 + lane * 8) * 2) : OOB);
+    }
+
+    // ---- weight: load j of a 16-row tile fetches rows 8 j + lane / 8; lane's chunk slot lane % 8 receives chunk slot ^ key(row)
     const int lrow = lane >> 3;
     const int c0 = (lane & 7) ^ ((lrow >> 1) & 7);
     const int c1 = (lane & 7) ^ ((4 + (lrow >> 1)) & 7);
@@ -129,60 +170,40 @@ __global__ __launch_bounds__(256) void gemm_fp8_skinny_fused_kernel(
             skf_lds_dma16(rsrc_b, dst + w * 2048 + 1024, vb1 + (uint32_t)(16 * w * (int)ldb) + k0);
         }
     };
-    // activations: lane l takes elements 2 l, 2 l + 1 of the step of every row (rows past M and steps past
-    // the end point outside the buffer: no access, zeros - but the same number of loads every time)
-    auto load_a = [&](int (&dst)[MB], int s) {
 #pragma unroll
-        for (int r = 0; r < MB; ++r)
-            skf_load4(dst[r], rsrc_x, (r < M && s < ksteps) ? (uint32_t)((r * (int)ldx + s * 128 + 2 * lane) * 2) : OOB);
-    };
+    for (int r = 0; r < R; ++r) issue_b(r, s_begin + r);
 
-    int araw[R][MB];
+    // ---- amax per row, scales, codes into LDS
+    __syncthreads();                              // amax_bits and zeros are set
+    skf_wait_x<R * LB, U>(xv);                       // X is there; the first ring fill may still be under way
+    auto as_u4 = [](const v4i_q& a) { return make_uint4((uint32_t)a[0], (uint32_t)a[1], (uint32_t)a[2], (uint32_t)a[3]); };
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        issue_b(r, s_begin + r);
-        load_a(araw[r], s_begin + r);
-    }
-
-    // ---- amax of every row of X: wavefront w takes pieces w, w + 4, ... of 512 elements
-    {
-        const int cpr = K / 512, pieces = M * cpr;
-        constexpr int U = 16;
-        for (int q0 = wave; q0 < pieces; q0 += 4 * U) {
-            uint4 v[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {       // all requested before the first is used (a piece past the end repeats the last one)
-                const int q = q0 + 4 * u < pieces ? q0 + 4 * u : pieces - 1;
-                v[u] = *reinterpret_cast<const uint4*>(X + (int64_t)(q / cpr) * ldx + (q % cpr) * 512 + lane * 8);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int q = q0 + 4 * u;
-                if (q < pieces) {
-                    const uint32_t m = wave_max_u32<64>(pk_fold(pk_absmax4(0u, v[u])));
-                    if (lane == 0) atomicMax(&amax_bits[q / cpr], m);
-                }
-            }
+    for (int u = 0; u < U; ++u) {
+        if (wave + WAVES * u < pieces) {
+            const uint32_t m = skf_wave_max(pk_fold(pk_absmax4(0u, as_u4(xv[u]))));
+            if (lane == 0) atomicMax(&amax_bits[prow[u]], m);
         }
     }
     __syncthreads();
-    float sx[MB];
-    if (row_x) {
-#pragma unroll
-        for (int r = 0; r < MB; ++r) sx[r] = scale_from_amax(mag_to_float(amax_bits[r < M ? r : M - 1]), FX, flags);
-    } else {
-        uint32_t mag = 0;
-        for (int m = 0; m < M; ++m) mag = amax_bits[m] > mag ? amax_bits[m] : mag;
-        const float s1 = scale_from_amax(mag_to_float(mag), FX, flags);
-#pragma unroll
-        for (int r = 0; r < MB; ++r) sx[r] = s1;
+    if (tid < M) {
+        uint32_t mag = amax_bits[tid];
+        if (!row_x)
+            for (int m = 0; m < M; ++m) mag = amax_bits[m] > mag ? amax_bits[m] : mag;
+        scale_x[tid] = scale_from_amax(mag_to_float(mag), FX, flags);
     }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (wave + WAVES * u < pieces)
+            *reinterpret_cast<uint2*>(codes + prow[u] * row_bytes + pcol[u] * 512 + lane * 8) = cast8<FX>(as_u4(xv[u]), scale_x[prow[u]]);
+    }
+    __syncthreads();
 
     v4f_q acc[NW];
 #pragma unroll
     for (int w = 0; w < NW; ++w) acc[w] = v4f_q{0.f, 0.f, 0.f, 0.f};
 
-    // weight fragment: chunks g and g + 4 of row i of a tile
+    // weight fragment: chunks g and g + 4 of row i of a tile; A fragment: the same chunks of row i of the codes
     const int key = (i >> 1) & 7;
     const int f_lo = i * 128 + ((g ^ key) << 4), f_hi = i * 128 + (((g + 4) ^ key) << 4);
     auto frag = [&](const uint8_t* tile) {
@@ -190,36 +211,26 @@ __global__ __launch_bounds__(256) void gemm_fp8_skinny_fused_kernel(
         const uint4 hi = *reinterpret_cast<const uint4*>(tile + f_hi);
         return v8i_q{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
     };
-    // the same chunks of row i of the codes of X (plain layout)
-    const uint8_t* a_lo = codes + i * 128 + 16 * g;
+    const uint8_t* a_row = i < M ? codes + i * row_bytes + 16 * g : zeros + 16 * g;
+    const int a_step = i < M ? 128 : 0;
 
-    for (int s0 = s_begin; s0 < s_end; s0 += R) {
+    int slot = 0;
+    for (int s = s_begin; s < s_end; ++s) {
+        skf_wait_vmem<(R - 1) * LB>();            // all but the R - 1 younger slots have landed
+        const uint8_t* base = smem + wave * (R * SLOT) + slot * SLOT;
+        v8i_q bf[NW];
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int s = s0 + r;
-            if (s < s_end) {
-                skf_wait<(R - 1) * (LB + LA), MB>(araw[r]);   // step s has landed
+        for (int w = 0; w < NW; ++w) bf[w] = frag(base + w * 2048);
+        const uint8_t* ap = a_row + s * a_step;
+        const uint4 lo = *reinterpret_cast<const uint4*>(ap), hi = *reinterpret_cast<const uint4*>(ap + 64);
+        const v8i_q af = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
 #pragma unroll
-                for (int m = 0; m < MB; ++m) {
-                    const uint32_t w2 = (uint32_t)araw[r][m];
-                    *reinterpret_cast<u16_any*>(codes + m * 128 + 2 * lane) =
-                        (uint16_t)cvt2<FX>(bf16_lo(w2) * sx[m], bf16_hi(w2) * sx[m]);
-                }
-                const uint8_t* base = smem + wave * (R * SLOT) + r * SLOT;
-                v8i_q bf[NW];
-#pragma unroll
-                for (int w = 0; w < NW; ++w) bf[w] = frag(base + w * 2048);
-                const uint4 lo = *reinterpret_cast<const uint4*>(a_lo), hi = *reinterpret_cast<const uint4*>(a_lo + 64);
-                const v8i_q af = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-#pragma unroll
-                for (int w = 0; w < NW; ++w)
-                    acc[w] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[w], af, acc[w], FB, FX, 0, 0, 0, 0);
-                issue_b(r, s + R);
-                load_a(araw[r], s + R);
-            }
-        }
+        for (int w = 0; w < NW; ++w)
+            acc[w] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[w], af, acc[w], FB, FX, 0, 0, 0, 0);
+        issue_b(slot, s + R);
+        slot = slot + 1 == R ? 0 : slot + 1;
     }
-    skf_wait_all();           // trailing loads must land before the registers die and the LDS is reused or handed back
+    skf_wait_vmem<0>();       // trailing (out-of-range) refills must land before the LDS is reused or handed back
 
     // ---- sum the K parts of a column group through LDS (the rings are free now)
     if constexpr (KS > 1) {
@@ -240,10 +251,7 @@ __global__ __launch_bounds__(256) void gemm_fp8_skinny_fused_kernel(
 
     // ---- epilogue: lane holds y[i][n0 + 16 w + 4 g + r], r = 0..3
     if (i >= M) return;
-    float sxi = sx[0];
-#pragma unroll
-    for (int r = 1; r < MB; ++r) sxi = i == r ? sx[r] : sxi;
-    const float inv_a = 1.0f / sxi;
+    const float inv_a = 1.0f / scale_x[i];
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
         const int nb = n0 + 16 * w + 4 * g;
@@ -262,33 +270,37 @@ __global__ __launch_bounds__(256) void gemm_fp8_skinny_fused_kernel(
     }
 }
 
-template <int FX, int FB, int KS, int NW, int MB>
+template <int FX, int FB, int KS, int NW, int WAVES>
 static hipError_t launch_skf(const uint16_t* x, int64_t ldx, int row_x, int flags, const uint8_t* b, int64_t ldb,
                              const float* sb, int row_b, int M, int N, int K, uint16_t* out, int64_t ld_out, int64_t grid,
                              hipStream_t st) {
-    constexpr int R = NW == 1 ? 6 : 4;      // 56 KB or 72 KB of LDS with the tiles of codes: two workgroups per CU
-    constexpr int lds = 4 * R * NW * 2048 + 4 * 2048;
-    auto kern = gemm_fp8_skinny_fused_kernel<FX, FB, KS, NW, MB, R>;
+    using namespace skf;
+    // eight wavefronts: 96 KB of rings, one workgroup per CU with the codes of X (33 KB at most); four: 40 or 48 KB
+    constexpr int R = WAVES == 8 ? (NW == 1 ? 6 : 3) : (NW == 1 ? 5 : 3);
+    const int lds = WAVES * R * NW * 2048 + M * (K + ROW_PAD) + 128;
+    auto kern = gemm_fp8_skinny_fused_kernel<FX, FB, KS, NW, WAVES, R>;
     static DynamicLdsOnce attr;
-    if (hipError_t e = attr.ensure(reinterpret_cast<const void*>(kern), lds); e != hipSuccess) return e;
-    kern<<<dim3((unsigned)grid), dim3(256), lds, st>>>(x, ldx, row_x, flags, b, ldb, sb, row_b, M, N, K, out, ld_out);
+    if (hipError_t e = attr.ensure(reinterpret_cast<const void*>(kern), WAVES * R * NW * 2048 + MAX_X + 8 * ROW_PAD + 128); e != hipSuccess) return e;
+    kern<<<dim3((unsigned)grid), dim3(64 * WAVES), lds, st>>>(x, ldx, row_x, flags, b, ldb, sb, row_b, M, N, K, out, ld_out);
     return hipGetLastError();
 }
 
-// hipErrorNotSupported (nothing launched) where the one-launch form does not apply (more than 8 tokens,
-// activations to e5m2, K not a multiple of 512, operands beyond the reach of 32-bit buffer offsets) or does not
-// pay.  Every workgroup reads all of X for the amax and every wavefront its K part of X for the product, and all
-// of them want the same lines at the same time: each further token costs 1-2 us on the Llama-3-8B projections
-// (more on larger weights), where the launch that is saved costs 2-3 us.  Measured against the two-launch form,
-// calls replayed from a graph: one token 6-17 % faster on the 8B shapes (1-6 % on the 70B ones), two tokens
-// 2-11 % faster at K = 4096 and 6-10 % slower beyond, four tokens slower nearly everywhere.  Default
-// therefore: one token, or M * K <= 8192.  The switch DECODE_FUSED: 0 = never, 2 = wherever the kernel applies.
+// hipErrorNotSupported (nothing launched) where the one-launch form does not apply (more than 8 tokens or more
+// than 32768 activations - what a workgroup holds in registers between the amax and the conversion -, activations
+// to e5m2, K not a multiple of 512, operands beyond the reach of 32-bit buffer offsets) or does not pay: every
+// workgroup reads and converts all of X before its first product, 16 to 128 elements per lane, and that time
+// grows with M while the launch it saves (2-3 us) does not.  Measured against the two-launch form on the
+// Llama-3 projections, calls replayed from a graph: one token 13-21 % faster on the 8B shapes (2-4 % on the
+// 70B ones), two tokens 4-16 %, four tokens 0-9 %, eight tokens 3 % faster on the 14336 x 4096 weight and
+// 12-13 % slower on the 4096 x 4096 and 6144 x 4096 ones.  Default therefore: one token, or up to four with
+// M * K <= 16384.  The switch DECODE_FUSED: 0 = never, 2 = wherever the kernel applies.
 hipError_t launch_linear_skinny_fused(const void* x, int64_t ldx, int fmt_x, int row_x, int flags, const uint8_t* b,
                                       int64_t ldb, int fmt_b, const float* scale_b, int row_b, int64_t M, int64_t N,
                                       int64_t K, void* out, int64_t ld_out, hipStream_t st) {
+    using namespace skf;
     const int mode = knob(KNOB_DECODE_FUSED);
-    if (mode == 0 || M < 1 || M > 8 || N < 1 || K < 512 || K % 512 != 0) return hipErrorNotSupported;
-    if (mode != 2 && M != 1 && M * K > 8192) return hipErrorNotSupported;
+    if (mode == 0 || M < 1 || M > 8 || N < 1 || K < 512 || K % 512 != 0 || M * K > MAX_X) return hipErrorNotSupported;
+    if (mode != 2 && M != 1 && (M > 4 || M * K > 16384)) return hipErrorNotSupported;
     if (fmt_x != FMT_E4M3FN) return hipErrorNotSupported;
     if (ldb >= (1 << 23) || ((M - 1) * ldx + K) * 2 >= (int64_t)1 << 31 || (int64_t)16 * 4 * ldb + K >= (int64_t)1 << 31)
         return hipErrorNotSupported;
@@ -297,23 +309,25 @@ hipError_t launch_linear_skinny_fused(const void* x, int64_t ldx, int fmt_x, int
     const int64_t groups = (N + 16 * nw - 1) / (16 * nw);
     int ks = 1;
     while (ks < 4 && groups * ks < 2048 && K / (ks * 2) >= 512) ks *= 2;
-    const int64_t grid = (groups + (4 / ks) - 1) / (4 / ks);
+    // eight wavefronts per workgroup unless that leaves a quarter of the CUs without one
+    const int cus = compute_units() > 0 ? compute_units() : 256;
+    const int waves = (groups * ks + 7) / 8 * 4 >= (int64_t)cus * 3 ? 8 : 4;
+    const int ntw = waves / ks;
+    const int64_t grid = (groups + ntw - 1) / ntw;
     if (grid > 0x7FFFFFFF) return hipErrorNotSupported;
     const uint16_t* xp = static_cast<const uint16_t*>(x);
     uint16_t* op = static_cast<uint16_t*>(out);
     const int m = (int)M, n = (int)N, k = (int)K;
-    const int mb = m == 1 ? 1 : (m == 2 ? 2 : (m <= 4 ? 4 : 8));
-#define FP8K_SKF(FB_, KS_, NW_, MB_)                                  \
-    if (fmt_b == FB_ && ks == KS_ && nw == NW_ && mb == MB_)          \
-        return launch_skf<FMT_E4M3FN, FB_, KS_, NW_, MB_>(xp, ldx, row_x, flags, b, ldb, scale_b, row_b, m, n, k, op, ld_out, grid, st)
-#define FP8K_SKF4(FB_, KS_, NW_) \
-    FP8K_SKF(FB_, KS_, NW_, 1); FP8K_SKF(FB_, KS_, NW_, 2); FP8K_SKF(FB_, KS_, NW_, 4); FP8K_SKF(FB_, KS_, NW_, 8)
-#define FP8K_SKF6(FB_) \
-    FP8K_SKF4(FB_, 1, 1); FP8K_SKF4(FB_, 2, 1); FP8K_SKF4(FB_, 4, 1); FP8K_SKF4(FB_, 1, 2); FP8K_SKF4(FB_, 2, 2); FP8K_SKF4(FB_, 4, 2)
-    FP8K_SKF6(FMT_E4M3FN);
-    FP8K_SKF6(FMT_E5M2);
+#define FP8K_SKF(FB_, KS_, NW_, W_)                                  \
+    if (fmt_b == FB_ && ks == KS_ && nw == NW_ && waves == W_)       \
+        return launch_skf<FMT_E4M3FN, FB_, KS_, NW_, W_>(xp, ldx, row_x, flags, b, ldb, scale_b, row_b, m, n, k, op, ld_out, grid, st)
+#define FP8K_SKF6(FB_, W_) \
+    FP8K_SKF(FB_, 1, 1, W_); FP8K_SKF(FB_, 2, 1, W_); FP8K_SKF(FB_, 4, 1, W_); FP8K_SKF(FB_, 1, 2, W_); FP8K_SKF(FB_, 2, 2, W_); FP8K_SKF(FB_, 4, 2, W_)
+    FP8K_SKF6(FMT_E4M3FN, 8);
+    FP8K_SKF6(FMT_E4M3FN, 4);
+    FP8K_SKF6(FMT_E5M2, 8);
+    FP8K_SKF6(FMT_E5M2, 4);
 #undef FP8K_SKF6
-#undef FP8K_SKF4
 #undef FP8K_SKF
     return hipErrorNotSupported;
 }
