@@ -69,15 +69,37 @@ __device__ __forceinline__ uint32_t pk_fold(uint32_t acc) {
 }
 __device__ __forceinline__ float mag_to_float(uint32_t mag15) { return __uint_as_float(mag15 << 16); }
 
-// maximum over the lanes of a (sub)wavefront of WIDTH lanes (power of two <= 64)
+// maximum over the lanes of a (sub)wavefront of WIDTH lanes (power of two <= 64), the same value in all of them.
+// Groups of 16 lanes fold by DPP rotations within their row (register-to-register: four dependent VALU
+// operations instead of four round trips through the LDS crossbar); a whole wavefront then combines its
+// four rows through scalar registers.
 template <int WIDTH>
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
-#pragma unroll
-    for (int off = WIDTH / 2; off > 0; off >>= 1) {
-        const uint32_t o = (uint32_t)__shfl_xor((int)v, off, 64);
+    if constexpr (WIDTH == 16 || WIDTH == 64) {
+        uint32_t o;
+        o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x121, 0xF, 0xF, false);   // row_ror:1
         v = o > v ? o : v;
+        o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x122, 0xF, 0xF, false);   // row_ror:2
+        v = o > v ? o : v;
+        o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x124, 0xF, 0xF, false);   // row_ror:4
+        v = o > v ? o : v;
+        o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xF, 0xF, false);   // row_ror:8
+        v = o > v ? o : v;
+        if constexpr (WIDTH == 64) {
+            const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)v, 0), b = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+            const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)v, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+            const uint32_t ab = a > b ? a : b, cd = c > d ? c : d;
+            v = ab > cd ? ab : cd;
+        }
+        return v;
+    } else {
+#pragma unroll
+        for (int off = WIDTH / 2; off > 0; off >>= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)v, off, 64);
+            v = o > v ? o : v;
+        }
+        return v;
     }
-    return v;
 }
 
 // scale from amax: binary64 quotient rounded once to binary32

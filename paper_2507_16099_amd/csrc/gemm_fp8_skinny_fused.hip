@@ -72,24 +72,6 @@ __device__ __forceinline__ void skf_wait_x(v4i_q (&x)[U]) {
 template <int N_>
 __device__ __forceinline__ void skf_wait_vmem() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_) : "memory"); }
 
-// maximum over the wavefront, the same value in every lane: rotations within rows of 16 lanes (DPP), then
-// the four rows through scalar registers
-__device__ __forceinline__ uint32_t skf_wave_max(uint32_t v) {
-    uint32_t o;
-    o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x121, 0xF, 0xF, false);   // row_ror:1
-    v = o > v ? o : v;
-    o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x122, 0xF, 0xF, false);   // row_ror:2
-    v = o > v ? o : v;
-    o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x124, 0xF, 0xF, false);   // row_ror:4
-    v = o > v ? o : v;
-    o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xF, 0xF, false);   // row_ror:8
-    v = o > v ? o : v;
-    const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)v, 0), b = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
-    const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)v, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
-    const uint32_t ab = a > b ? a : b, cd = c > d ? c : d;
-    return ab > cd ? ab : cd;
-}
-
 namespace skf {
 constexpr int MAX_X = 32768;       // elements of X a workgroup holds in registers: 8 loads of 8 per lane
 constexpr int ROW_PAD = 64;        // bytes between the rows of codes in LDS beyond K: consecutive rows start 16 banks apart
@@ -180,7 +162,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_fp8_skinny_fused_kernel(
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if (wave + WAVES * u < pieces) {
-            const uint32_t m = skf_wave_max(pk_fold(pk_absmax4(0u, as_u4(xv[u]))));
+            const uint32_t m = wave_max_u32<64>(pk_fold(pk_absmax4(0u, as_u4(xv[u]))));
             if (lane == 0) atomicMax(&amax_bits[prow[u]], m);
         }
     }
