@@ -103,3 +103,43 @@ def test_step_replays_from_a_hip_graph(recipe):
         torch.cuda.synchronize()
         for got, want, name in zip((y, dx, dw), eager[i], ("y", "dx", "dw")):
             assert torch.equal(got.view(torch.int16), want), (recipe, i, name)
+
+
+@pytest.mark.parametrize("M", [1, 4, 12])
+def test_decode_linear_replays_from_a_hip_graph(M):
+    """The decode linear with a weight quantized once - one launch for a few tokens, two launches beyond -
+    recorded once and replayed with new activations in the same buffer."""
+    K, N = 2048, 1000
+    w = dev_bf16(si.normal_bf16((N, K), 0.02, 11, 0))
+    wq, sw = fp8.fp8_quantize(w, fp8.FP8_ROW, fp8.FP8_E4M3FN)
+    inputs = [dev_bf16(si.f32_to_bf16_bits(si.bf16_bits_to_f32(si.normal_bf16((M, K), 1.0, 11, 1 + s)) * np.float32(0.5 + 3 * s)))
+              for s in range(3)]
+    x = torch.empty_like(inputs[0])
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(fp8.fp8_linear_prequantized_workspace_bytes(M, K), dtype=torch.uint8, device="cuda")
+
+    def step():
+        fp8.fp8_linear_fwd_prequantized(x, wq, fp8.FP8_E4M3FN, sw, fp8.FP8_ROW, fp8.FP8_E4M3FN, fp8.FP8_ROW, 0, y=y, workspace=ws)
+
+    eager = []
+    for i in range(3):
+        x.copy_(inputs[i])
+        step()
+        torch.cuda.synchronize()
+        eager.append(_bits(y))
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    x.copy_(inputs[0])
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for i in (1, 2, 0, 2):
+        x.copy_(inputs[i])
+        y.zero_()
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), eager[i]), (M, i)
