@@ -10,8 +10,8 @@
 // R steps of 128 bytes ahead, no barriers in the main loop.  What differs:
 //  * a workgroup is eight wavefronts (one per CU: X is read and converted once per CU) where that still gives
 //    most CUs a workgroup, else four (two per CU);
-//  * before the main loop the workgroup reads all of X (at most 32768 elements: 8 loads of 16 bytes per
-//    lane, requested ahead of the first ring fill and waited for by count, so they arrive while the
+//  * before the main loop the workgroup reads all of X (at most 32768 elements: 8 or 16 loads of 16 bytes
+//    per lane, requested ahead of the first ring fill and waited for by count, so they arrive while the
 //    weight's first bytes are still on their way), reduces the row maxima (lane maxima folded within rows
 //    of 16 lanes by DPP rotations, then through scalar registers, then one LDS word per row), derives the
 //    scales with the row quantizer's arithmetic, converts the registers it still holds and leaves the
@@ -73,7 +73,7 @@ template <int N_>
 __device__ __forceinline__ void skf_wait_vmem() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_) : "memory"); }
 
 namespace skf {
-constexpr int MAX_X = 32768;       // elements of X a workgroup holds in registers: 8 loads of 8 per lane
+constexpr int MAX_X = 32768;       // elements of X a workgroup holds in registers: 8 (16) loads of 8 per lane of its 512 (256) threads
 constexpr int ROW_PAD = 64;        // bytes between the rows of codes in LDS beyond K: consecutive rows start 16 banks apart
 }  // namespace skf
 
