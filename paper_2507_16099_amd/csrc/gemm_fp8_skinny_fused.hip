@@ -8,8 +8,8 @@
 // The product is the LDS-DMA few-row kernel of gemm_fp8_skinny.hip: a wavefront owns NW column
 // tiles of 16 weight rows and a part of K; the weight streams through a private ring of LDS slots,
 // R steps of 128 bytes ahead, no barriers in the main loop.  What differs:
-//  * a workgroup is eight wavefronts (one per CU: X is read and converted once per CU) where that still gives
-//    most CUs a workgroup, else four (two per CU);
+//  * a workgroup is eight wavefronts (one per CU: X is read and converted once per CU) where that makes one
+//    round of workgroups over most CUs, else four (two per CU);
 //  * before the main loop the workgroup reads all of X (at most 32768 elements: 8 or 16 loads of 16 bytes
 //    per lane, requested ahead of the first ring fill and waited for by count, so they arrive while the
 //    weight's first bytes are still on their way), reduces the row maxima (lane maxima folded within rows
@@ -291,9 +291,12 @@ hipError_t launch_linear_skinny_fused(const void* x, int64_t ldx, int fmt_x, int
     const int64_t groups = (N + 16 * nw - 1) / (16 * nw);
     int ks = 1;
     while (ks < 4 && groups * ks < 2048 && K / (ks * 2) >= 512) ks *= 2;
-    // eight wavefronts per workgroup unless that leaves a quarter of the CUs without one
+    // eight wavefronts per workgroup where that makes one round of workgroups over at least three quarters of the CUs;
+    // fewer would leave CUs idle, and with more than one round a CU streams nothing while its only workgroup
+    // quantizes X and waits for its first ring fill (two workgroups of four wavefronts cover for each other)
     const int cus = compute_units() > 0 ? compute_units() : 256;
-    const int waves = (groups * ks + 7) / 8 * 4 >= (int64_t)cus * 3 ? 8 : 4;
+    const int64_t grid8 = (groups * ks + 7) / 8;
+    const int waves = grid8 * 4 >= (int64_t)cus * 3 && grid8 <= cus ? 8 : 4;
     const int ntw = waves / ks;
     const int64_t grid = (groups + ntw - 1) / ntw;
     if (grid > 0x7FFFFFFF) return hipErrorNotSupported;
