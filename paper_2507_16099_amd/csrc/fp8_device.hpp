@@ -69,6 +69,25 @@ __device__ __forceinline__ uint32_t pk_fold(uint32_t acc) {
 }
 __device__ __forceinline__ float mag_to_float(uint32_t mag15) { return __uint_as_float(mag15 << 16); }
 
+// pk_absmax of a register with the same register of the lane OFF away (lane ^ OFF), without a trip through the
+// LDS crossbar: neighbours within a quad by DPP quad permutation, 8 away by a DPP rotation of the row of 16,
+// 16 and 32 away by the row swaps (v_permlane16_swap / v_permlane32_swap of a register with itself leave, in
+// every lane, the lane's own value in one result and its partner's in the other).
+template <int OFF>
+__device__ __forceinline__ uint32_t pk_absmax_xor(uint32_t v) {
+    static_assert(OFF == 1 || OFF == 2 || OFF == 8 || OFF == 16 || OFF == 32, "no register-to-register form for this distance");
+    if constexpr (OFF == 1) return pk_absmax(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false));        // quad_perm:[1,0,3,2]
+    else if constexpr (OFF == 2) return pk_absmax(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false));   // quad_perm:[2,3,0,1]
+    else if constexpr (OFF == 8) return pk_absmax(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xF, 0xF, false));  // row_ror:8
+    else if constexpr (OFF == 16) {
+        const auto s = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+        return pk_absmax(s[0] & 0x7FFF7FFFu, s[1]);
+    } else {
+        const auto s = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+        return pk_absmax(s[0] & 0x7FFF7FFFu, s[1]);
+    }
+}
+
 // maximum over the lanes of a (sub)wavefront of WIDTH lanes (power of two <= 64), the same value in all of them.
 // Groups of 16 lanes fold by DPP rotations within their row (register-to-register: four dependent VALU
 // operations instead of four round trips through the LDS crossbar); a whole wavefront then combines its

@@ -284,13 +284,12 @@ __global__ __launch_bounds__(1024) void colmax_final_scale_kernel(const uint16_t
             acc.w = pk_absmax(acc.w, v.w);
         }
     }
-#pragma unroll
-    for (int off = CL; off <= 32; off <<= 1) {
-        acc.x = pk_absmax(acc.x, (uint32_t)__shfl_xor((int)acc.x, off, 64));
-        acc.y = pk_absmax(acc.y, (uint32_t)__shfl_xor((int)acc.y, off, 64));
-        acc.z = pk_absmax(acc.z, (uint32_t)__shfl_xor((int)acc.z, off, 64));
-        acc.w = pk_absmax(acc.w, (uint32_t)__shfl_xor((int)acc.w, off, 64));
+    static_assert(CL == 8 || CL == 16, "row pieces of 8 or 16 lanes");
+    if constexpr (CL == 8) {
+        acc.x = pk_absmax_xor<8>(acc.x); acc.y = pk_absmax_xor<8>(acc.y); acc.z = pk_absmax_xor<8>(acc.z); acc.w = pk_absmax_xor<8>(acc.w);
     }
+    acc.x = pk_absmax_xor<16>(acc.x); acc.y = pk_absmax_xor<16>(acc.y); acc.z = pk_absmax_xor<16>(acc.z); acc.w = pk_absmax_xor<16>(acc.w);
+    acc.x = pk_absmax_xor<32>(acc.x); acc.y = pk_absmax_xor<32>(acc.y); acc.z = pk_absmax_xor<32>(acc.z); acc.w = pk_absmax_xor<32>(acc.w);
     __shared__ uint4 sm[16][CL];
     if ((tid & 63) < CL) sm[tid >> 6][cl] = acc;
     __syncthreads();
@@ -1424,10 +1423,7 @@ __global__ __launch_bounds__(256) void mx_quant_kernel(const uint16_t* __restric
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         uint32_t m = pk_fold(pk_absmax4(0u, d[u]));
-        uint32_t o = (uint32_t)__shfl_xor((int)m, 1, 64);
-        m = o > m ? o : m;
-        o = (uint32_t)__shfl_xor((int)m, 2, 64);
-        m = o > m ? o : m;                                   // block maximum, 15 magnitude bits of bfloat16
+        m = pk_absmax_xor<2>(pk_absmax_xor<1>(m));           // block maximum (four lanes), 15 magnitude bits of bfloat16
         int byte = 0;
         if (m != 0) {
             const int ef = (int)(m >> 7);
@@ -1511,12 +1507,7 @@ __global__ __launch_bounds__(256) void block_quant_1x128_kernel(const uint16_t* 
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        uint32_t m = pk_fold(pk_absmax4(0u, d[u]));
-#pragma unroll
-        for (int off = 1; off <= 8; off <<= 1) {
-            const uint32_t o = (uint32_t)__shfl_xor((int)m, off, 64);
-            m = o > m ? o : m;
-        }
+        uint32_t m = wave_max_u32<16>(pk_fold(pk_absmax4(0u, d[u])));     // the tile's sixteen lanes
         uint32_t byte;
         const float s = pow2_block_scale<FMT>(m, byte);
         if (v0 + u * 256 < nvec) {
@@ -1638,10 +1629,7 @@ __global__ __launch_bounds__(256) void mx_quant_t_kernel(const uint16_t* __restr
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             uint32_t mr = pk_fold(pk_absmax4(0u, v[j]));
-            uint32_t o = (uint32_t)__shfl_xor((int)mr, 1, 64);
-            mr = o > mr ? o : mr;
-            o = (uint32_t)__shfl_xor((int)mr, 2, 64);
-            mr = o > mr ? o : mr;
+            mr = pk_absmax_xor<2>(pk_absmax_xor<1>(mr));
             int byte = 0;
             if (mr != 0) {
                 const int ef = (int)(mr >> 7);
@@ -1666,9 +1654,7 @@ __global__ __launch_bounds__(256) void mx_quant_t_kernel(const uint16_t* __restr
         m[3] = pk_absmax(m[3], v[j].w);
     }
 #pragma unroll
-    for (int off = 16; off <= 32; off <<= 1)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) m[i] = pk_absmax(m[i], (uint32_t)__shfl_xor((int)m[i], off, 64));
+    for (int i = 0; i < 4; ++i) m[i] = pk_absmax_xor<32>(pk_absmax_xor<16>(m[i]));
     float factor[8];
     uint32_t bytes_lo = 0, bytes_hi = 0;
 #pragma unroll
@@ -1787,12 +1773,7 @@ __global__ __launch_bounds__(256) void block_quant_t_kernel(const uint16_t* __re
     if constexpr (ROWS_TOO) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            uint32_t mr = pk_fold(pk_absmax4(0u, v[j]));
-#pragma unroll
-            for (int off = 1; off <= 8; off <<= 1) {
-                const uint32_t o = (uint32_t)__shfl_xor((int)mr, off, 64);
-                mr = o > mr ? o : mr;
-            }
+            uint32_t mr = wave_max_u32<16>(pk_fold(pk_absmax4(0u, v[j])));
             uint32_t byte;
             const float sr = pow2_block_scale<FMT>(mr, byte);
             const int64_t r = r0 + ty * 8 + j;
@@ -1816,9 +1797,7 @@ __global__ __launch_bounds__(256) void block_quant_t_kernel(const uint16_t* __re
         if (threadIdx.x < 128) ebytes[threadIdx.x] = (uint8_t)byte;
     } else {
 #pragma unroll
-        for (int off = 16; off <= 32; off <<= 1)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) m[i] = pk_absmax(m[i], (uint32_t)__shfl_xor((int)m[i], off, 64));
+        for (int i = 0; i < 4; ++i) m[i] = pk_absmax_xor<32>(pk_absmax_xor<16>(m[i]));
         if ((threadIdx.x & 63) < 16) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) red[wave][tx][i] = m[i];
